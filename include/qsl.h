@@ -1,0 +1,149 @@
+/* qsl.h -- C ABI of the MI355X-native compression hot path of Qsparse-local-SGD
+ * (Basu, Data, Karakus, Diggavi, arXiv:1906.02367).
+ *
+ * The library computes, for R simulated workers held as a batch on ONE GPU, the two worker
+ * lines and the master line of a synchronisation step of Algorithm 1:
+ *
+ *     g^(r)  <-  Q Comp_k( m^(r) + Delta^(r) )          (compress, "send")
+ *     m^(r)  <-  m^(r) + Delta^(r) - g^(r)              (error memory update)
+ *     x      <-  x - (1/R) sum_r g^(r)                   (aggregate at the master)
+ *
+ * with Comp_k in {Top_k, Rand_k} (Section 2.2), Q in {QSGD with s levels (Definition 1,
+ * example 1), Sign scaled by ||Comp_k(x)||_1 / k (Definition 2, Lemma 3 with m = 1)}, the
+ * quantiser acting on the k kept values as a length-k vector (proof of Lemma 1), and the whole
+ * operator optionally applied block by block (Corollary 1).
+ *
+ * Conventions
+ *   - Every `device` pointer is GPU memory owned by the caller; [R, d] arrays are row-major,
+ *     contiguous, row stride d; message arrays are [R, qsl_msg_capacity_bytes()] bytes.
+ *     Device pointers must be 4-byte aligned (messages and 64-bit outputs 8-byte aligned).
+ *   - `host` pointers are ordinary CPU memory, read (or written) before the call returns.
+ *   - All GPU work is enqueued on the context's HIP stream and is asynchronous; nothing on the
+ *     hot path allocates, frees or synchronises.  The context owns only scratch memory.
+ *   - Argument errors are reported synchronously and have no side effect.  Errors that depend
+ *     on the data (a NaN/Inf in m + Delta) set a status word on the device, returned by
+ *     qsl_device_status().
+ *   - A context is not thread-safe; calls on one context must not overlap.
+ *
+ * Wire format of one message (little endian; fields are packed least-significant bit first;
+ * "w_idx" = bits needed to write d - 1, at least 1; "w_lev" = bits needed to write s - 1):
+ *     u32  nnz                         number of transmitted coordinates
+ *     f32  scale[num_segments]         ||v_S||_2 (QSGD) or ||v_S||_1 / k (Sign), per segment
+ *     u32  nnz_l[num_segments]         only for QSGD with num_segments > 1
+ *     nnz x w_idx bits                 coordinate indices, ascending     (starts on a 32-bit boundary)
+ *     nnz x w_val bits                 QSGD: (level - 1) in w_lev bits, then the sign bit;
+ *                                      Sign: the sign bit (1 = negative)  (starts on a 32-bit boundary)
+ *     zero padding up to the capacity (a multiple of 8 bytes)
+ * A QSGD coordinate whose level is 0 is not transmitted (Section 5.1.2 notes that the quantiser
+ * "further induces sparsity").  The paper fixes no encoding; this one is the library's choice.
+ */
+#ifndef QSL_H
+#define QSL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct qsl_ctx qsl_ctx;
+
+typedef enum {
+  QSL_OK = 0,
+  QSL_ERR_INVALID_ARG = 1,
+  QSL_ERR_BUFFER_TOO_SMALL = 2,
+  QSL_ERR_NONFINITE_INPUT = 3,
+  QSL_ERR_DEVICE = 4,
+  QSL_ERR_UNSUPPORTED = 5
+} qsl_status;
+
+enum { QSL_TOPK = 0, QSL_RANDK = 1 };    /* sparsifier, Section 2.2 */
+enum { QSL_QSGD = 0, QSL_SIGN_L1 = 1 };  /* quantiser, Definitions 1 and 2 */
+
+/* Parameters of the operator Q Comp_k, in the paper's notation. */
+typedef struct {
+  uint64_t d;                 /* coordinates per worker, 1 <= d < 2^32                                  */
+  uint32_t num_segments;      /* 1: one operator on the whole vector; 1 < L <= 16384: piecewise (Cor. 1)  */
+  const uint64_t *seg_offset; /* host, num_segments + 1 entries, seg_offset[0] = 0, last = d, increasing */
+  const uint32_t *seg_k;      /* host, k per segment, 1 <= k_l <= size of the segment                   */
+  uint32_t s;                 /* QSGD levels, 1 <= s <= 32768 (ignored by the sign quantiser)           */
+  uint32_t sparsifier;        /* QSL_TOPK or QSL_RANDK                                                  */
+  uint32_t quantizer;         /* QSL_QSGD or QSL_SIGN_L1                                                */
+  uint64_t seed;              /* seed of the counter-based randomness (Rand_k choice, QSGD rounding)    */
+  uint32_t max_workers;       /* largest R passed to one call; scratch is sized for it                  */
+  uint32_t flags;             /* 0, or QSL_FLAG_* below                                                 */
+} qsl_config;
+
+enum {
+  QSL_FLAG_NO_FAST_PATH = 1   /* always use the general multi-pass selection (testing, comparison)     */
+};
+
+/* Create a context for one operator on the current HIP device.  `hip_stream` is a hipStream_t
+ * (NULL = the default stream).  Allocates all scratch memory.  */
+qsl_status qsl_create(qsl_ctx **out, const qsl_config *cfg, void *hip_stream);
+qsl_status qsl_destroy(qsl_ctx *ctx);
+qsl_status qsl_set_stream(qsl_ctx *ctx, void *hip_stream);
+
+/* Size in bytes of one worker's message buffer (an upper bound over all inputs; multiple of 8). */
+size_t qsl_msg_capacity_bytes(const qsl_ctx *ctx);
+
+/* Algorithm 1, worker lines of a synchronisation step, for workers worker0 .. worker0 + R - 1 at
+ * sync round `round` (< 2^62): forms v = m + delta, selects, quantises, packs the messages and
+ * writes the new error memory.
+ *   m, delta  device, const float [R, d]
+ *   m_out     device, float [R, d]; receives m + delta - g; may be the same pointer as m; required
+ *   msg       device, uint8 [R, capacity]; every byte is written (zero padded)
+ *   msg_bits  device, uint64 [R] or NULL; payload bits of each message (padding excluded)
+ *   sel_idx   device, uint32 [R, K] or NULL, K = sum_l k_l; the selected coordinates, ascending
+ *   sel_level device, uint16 [R, K] or NULL; QSGD level 0..s of each selected coordinate
+ *             (0 = not transmitted); 1 for every entry under the sign quantiser
+ * The random word of coordinate i is Philox4x32-10 with counter (i / 4, worker, round mod 2^32,
+ * (round >> 32) | stream << 30), key (seed mod 2^32, seed >> 32), output word i mod 4; stream 0
+ * ranks coordinates for Rand_k, stream 1 drives the QSGD rounding.  */
+qsl_status qsl_compress(qsl_ctx *ctx, const float *m, const float *delta, float *m_out, uint32_t worker0,
+                        uint32_t R, uint64_t round, uint8_t *msg, uint64_t *msg_bits, uint32_t *sel_idx,
+                        uint16_t *sel_level);
+
+/* Algorithm 1, second worker line on its own: m <- (m + delta) - decode(msg), in place, for R
+ * workers.  Gives bit-for-bit the memory that qsl_compress writes to m_out.
+ *   m device float [R, d] (updated), delta device const float [R, d], msg device const [R, capacity] */
+qsl_status qsl_error_update(qsl_ctx *ctx, float *m, const float *delta, const uint8_t *msg, uint32_t R);
+
+/* Algorithm 1, master line (and Algorithm 2's, where only a subset reports and the scale stays
+ * 1/R):  out[j] = (accumulate ? out[j] : 0) + scale * sum_{r in list, in list order} decode(msg_r)[j],
+ * the inner sum accumulated in fp32 in list order, without atomics.
+ *   msg          device const uint8 [*, capacity]
+ *   worker_list  host, R row numbers into msg, or NULL for rows 0 .. R-1;  R <= 64
+ *   out          device float [d]                                                     */
+qsl_status qsl_aggregate(qsl_ctx *ctx, const uint8_t *msg, const uint32_t *worker_list, uint32_t R, float scale,
+                         int accumulate, float *out);
+
+/* Payload bits of each of R messages (the communication-budget axis of the paper's plots), read
+ * from the message headers.  Synchronises the stream.  bits_host: host uint64 [R].  */
+qsl_status qsl_bits_sent(qsl_ctx *ctx, const uint8_t *msg, uint32_t R, uint64_t *bits_host);
+
+/* Synchronise the stream and return QSL_ERR_NONFINITE_INPUT if any compress call since the last
+ * query met a NaN or Inf in m + delta (its outputs are then unspecified), QSL_ERR_DEVICE on a HIP
+ * error or if a kernel met a malformed message (an index >= d; the entry is skipped), else QSL_OK.
+ * Clears the word.  */
+qsl_status qsl_device_status(qsl_ctx *ctx);
+
+/* Per-unit diagnostics of the last compress call (unit = worker-major (worker, segment)); synchronises.
+ * out_host receives, per unit, 8 uint32: {path, candidates, threshold key, n_greater, n_equal_taken,
+ * guess key, reserved, reserved}; path: 0 = single-pass fast path, 1 = general path by
+ * configuration, 2 = general path after a failed guess.  */
+qsl_status qsl_debug_units(qsl_ctx *ctx, uint32_t *out_host, uint32_t max_units, uint32_t *n_units);
+
+/* Kernel timing for the benchmark: when enabled, compress calls bracket the streaming kernel with
+ * HIP events on the context's stream.  qsl_timing_read synchronises, returns the summed duration
+ * in milliseconds and the number of bracketed launches since it was enabled, and resets both.  */
+qsl_status qsl_timing_enable(qsl_ctx *ctx, int enabled);
+qsl_status qsl_timing_read(qsl_ctx *ctx, double *total_ms, uint32_t *launches);
+
+const char *qsl_status_string(qsl_status st);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QSL_H */

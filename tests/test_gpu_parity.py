@@ -1,0 +1,220 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs -- indices, level codes, packed bytes, bit counts and the error memory bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from oracle import oracle as O  # noqa: E402
+from paper_1906_02367_amd import workloads as W  # noqa: E402
+
+f32 = np.float32
+
+
+@pytest.fixture(scope="module")
+def P():
+    import parity_util
+    return parity_util
+
+
+def custom(d, seg_offset, seg_k, s, sparsifier, quantizer, R, name="custom", cfg=2, seed=12345):
+    return W.Workload(cfg, name, R, d, np.asarray(seg_offset, dtype=np.uint64), np.asarray(seg_k, dtype=np.uint32), s,
+                      sparsifier, quantizer, 1, seed)
+
+
+# ---------------------------------------------------------------------------------------------
+# small shapes: the general (multi-pass) path; several tiles and a ragged tail
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_configs_reduced_size(P, cfg):
+    d = {1: 65_536, 2: 70_001, 3: 70_001, 4: 150_000, 5: 99_991}[cfg]
+    wl = W.config(cfg, d=d, R=2 if cfg != 1 else None, rounds=4)
+    print(f"\n[{wl.name}] d={wl.d} K={wl.K} L={wl.L}", flush=True)
+    P.run_parity(wl, 4 if cfg != 1 else 10)
+
+
+@pytest.mark.parametrize("sparsifier", [W.TOPK, W.RANDK])
+@pytest.mark.parametrize("quantizer,s", [(W.QSGD, 15), (W.QSGD, 1), (W.QSGD, 32768), (W.SIGN_L1, 1)])
+def test_operator_grid_small(P, sparsifier, quantizer, s):
+    wl = custom(40_003, [0, 40_003], [777], s, sparsifier, quantizer, R=3)
+    P.run_parity(wl, 2, worker0=5)
+
+
+def test_not_in_place(P):
+    wl = W.config(2, d=50_000, R=2)
+    P.run_parity(wl, 3, in_place=False)
+
+
+# ---------------------------------------------------------------------------------------------
+# the single-pass fast path (guess + candidate pool) at sizes that enable it
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg,d", [(2, 1_000_003), (3, 600_011), (5, 4_000_037)])
+def test_fast_path_mid_size(P, cfg, d):
+    wl = W.config(cfg, d=d, R=3, rounds=3)
+    print(f"\n[{wl.name}] d={wl.d} K={wl.K}", flush=True)
+    P.run_parity(wl, 3, expect_path=0)
+
+
+def test_fast_and_general_paths_agree_layerwise(P):
+    # segments from 64 coordinates to ~1.9 M: a mix of fast and general units in one call
+    wl = W.config(4, d=20_000_000, R=2)
+    run, op, m_host, paths = P.run_parity(wl, 2)
+    assert (paths[0] == 0).any() and (paths[0] == 1).any()
+
+
+def test_failed_guess_falls_back(P):
+    # large values exactly where the sample looks -> the guess is far too high -> too few candidates
+    d, k, R = 1_000_003, 1000, 2
+    wl = custom(d, [0, d], [k], 16, W.TOPK, W.QSGD, R)
+    rng = np.random.default_rng(3)
+    delta = rng.standard_normal((R, d)).astype(f32)
+    n_s = 42.25 * 3.0 / (4.0 * (k / d))                    # the library's sampling plan at alpha = 3
+    n_runs = int(np.ceil(n_s / 64.0))
+    starts = (np.arange(n_runs, dtype=np.int64) * d) // n_runs
+    pos = (starts[:, None] + np.arange(64)[None, :]).ravel()
+    delta[:, pos] *= 1000.0
+    run, op, m_host, paths = P.run_parity(wl, 1, deltas=[delta])
+    assert np.all(paths[0] == 2), paths
+    # ... and the opposite failure: tiny values where the sample looks -> far too many candidates
+    delta = rng.standard_normal((R, d)).astype(f32)
+    delta[:, pos] *= 1e-6
+    run, op, m_host, paths = P.run_parity(wl, 1, deltas=[delta])
+    print("paths after a low guess:", paths)
+
+
+# ---------------------------------------------------------------------------------------------
+# degenerate inputs
+# ---------------------------------------------------------------------------------------------
+def _adversarial(d, rng):
+    yield "all_equal", np.full(d, 1.5, dtype=f32)
+    yield "all_zero", np.zeros(d, dtype=f32)
+    yield "signed_zeros", np.where(np.arange(d) % 2 == 0, 0.0, -0.0).astype(f32)
+    one = np.full(d, 1e-3, dtype=f32); one[d // 3] = -1e6
+    yield "one_dominant", one
+    yield "denormals", (rng.integers(-200, 200, d) * 1e-45).astype(f32)
+    yield "few_values", rng.integers(-2, 3, d).astype(f32)
+    yield "wide_range", (rng.standard_normal(d) * np.exp(8 * rng.standard_normal(d))).astype(f32)
+
+
+@pytest.mark.parametrize("quantizer,s", [(W.QSGD, 16), (W.SIGN_L1, 1)])
+@pytest.mark.parametrize("k", [1, 37, 20_011])
+def test_degenerate_inputs(P, quantizer, s, k):
+    d = 20_011
+    rng = np.random.default_rng(17)
+    wl = custom(d, [0, d], [k], s, W.TOPK, quantizer, R=1)
+    for name, v in _adversarial(d, rng):
+        P.run_parity(wl, 1, deltas=[v[None, :].copy()])
+
+
+def test_degenerate_inputs_on_fast_sizes(P):
+    d, k = 600_000, 500
+    rng = np.random.default_rng(19)
+    wl = custom(d, [0, d], [k], 4, W.TOPK, W.QSGD, R=1)
+    for name, v in _adversarial(d, rng):
+        print(name, flush=True)
+        P.run_parity(wl, 1, deltas=[v[None, :].copy()])
+
+
+def test_tiny_segments_and_unaligned_offsets(P):
+    off = [0, 64, 65, 130, 1_031, 5_000, 5_003, 40_000, 70_001]
+    k = [1, 1, 65, 9, 100, 3, 35, 30_001]
+    for sp, qz, s in [(W.TOPK, W.SIGN_L1, 1), (W.TOPK, W.QSGD, 4), (W.RANDK, W.QSGD, 2)]:
+        wl = custom(70_001, off, k, s, sp, qz, R=3)
+        P.run_parity(wl, 2)
+
+
+def test_d_equals_one_and_k_equals_d(P):
+    wl = custom(1, [0, 1], [1], 16, W.TOPK, W.QSGD, R=2)
+    P.run_parity(wl, 2)
+    wl = custom(5_000, [0, 5_000], [5_000], 16, W.TOPK, W.QSGD, R=1)      # QSGD on the whole vector
+    P.run_parity(wl, 2)
+
+
+# ---------------------------------------------------------------------------------------------
+# the other entry points
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg", [1, 2, 4])
+def test_aggregate_error_update_bits(P, cfg):
+    from paper_1906_02367_amd import binding as B
+    wl = W.config(cfg, d=80_000, R=4)
+    run, op, m_host, _ = P.run_parity(wl, 2)
+    q = run.q
+    msgs_host = run.msg.cpu().numpy()
+    # payload bits
+    assert q.bits_sent(run.msg) == [op.bits_sent(msgs_host[r]) for r in range(wl.R)]
+    # master line: all workers, then a subset accumulated onto x with scale -1/R
+    out = torch.full((wl.d,), 7.0, dtype=torch.float32, device=q.device)
+    q.aggregate(run.msg, out, 1.0 / wl.R)
+    torch.cuda.synchronize()
+    want = op.aggregate(msgs_host, 1.0 / wl.R)
+    dense_abs = np.zeros(wl.d)
+    for r in range(wl.R):
+        i, v = op.decode(msgs_host[r])
+        dense_abs[i] += np.abs(v.astype(np.float64))
+    assert np.all(np.abs(out.cpu().numpy().astype(np.float64) - want) <= 1e-6 * dense_abs / wl.R + 1e-38)
+    x0 = np.random.default_rng(5).standard_normal(wl.d).astype(f32)
+    out = torch.from_numpy(x0).to(q.device)
+    q.aggregate(run.msg, out, -1.0 / wl.R, worker_list=[1, 3], accumulate=True)
+    torch.cuda.synchronize()
+    want = op.aggregate(msgs_host, -1.0 / wl.R, worker_list=[1, 3], out=x0)
+    assert np.all(np.abs(out.cpu().numpy().astype(np.float64) - want) <= 1e-6 * (dense_abs / wl.R + np.abs(want)) + 1e-38)
+    # stand-alone error update reproduces the fused one bit for bit
+    rng = np.random.default_rng(9)
+    m0 = rng.standard_normal((wl.R, wl.d)).astype(f32)
+    d0 = W.delta_all(wl, 7)
+    m_dev, d_dev = torch.from_numpy(m0).to(q.device), torch.from_numpy(d0).to(q.device)
+    m_fused = torch.empty_like(m_dev)
+    q.compress(m_dev, d_dev, m_fused, 0, 7, run.msg)
+    q.error_update(m_dev, d_dev, run.msg)
+    torch.cuda.synchronize()
+    assert torch.equal(m_dev.view(torch.int32), m_fused.view(torch.int32))
+    assert q.device_status() == B.OK
+
+
+def test_nonfinite_input_is_reported(P):
+    from paper_1906_02367_amd import binding as B
+    wl = W.config(2, d=100_000, R=2)
+    q = B.from_workload(wl)
+    m = torch.zeros(2, wl.d, device=q.device)
+    delta = torch.randn(2, wl.d, device=q.device)
+    delta[1, 77_777] = float("inf")
+    q.compress(m, delta, m, 0, 0, q.new_msg(2))
+    assert q.device_status() == B.ERR_NONFINITE_INPUT
+    assert q.device_status() == B.OK                     # the word is cleared by the query
+
+
+def test_argument_errors_are_synchronous(P):
+    from paper_1906_02367_amd import binding as B
+    wl = W.config(2, d=10_000, R=2)
+    q = B.from_workload(wl)
+    m = torch.zeros(2, wl.d, device=q.device)
+    with pytest.raises(B.QslError):
+        q.compress(m, m, m, 0, 1 << 62, q.new_msg(2))                   # round out of range
+    big = torch.zeros(3, wl.d, device=q.device)
+    with pytest.raises(B.QslError):
+        q.compress(big, big, big, 0, 0, q.new_msg(3))                   # R > max_workers
+    with pytest.raises(B.QslError):
+        B.Qsl(100, [0, 100], [101], 16, B.TOPK, B.QSGD, 1, 1)          # k > d
+    with pytest.raises(B.QslError):
+        q.aggregate(q.new_msg(2), torch.zeros(wl.d, device=q.device), 1.0, worker_list=[0, 0])
+
+
+def test_results_do_not_depend_on_launch_history(P):
+    # same inputs three times, with unrelated calls in between: identical bytes (no stale scratch)
+    wl = W.config(2, d=1_000_003, R=2)
+    from paper_1906_02367_amd import binding as B
+    q = B.from_workload(wl)
+    d0 = torch.from_numpy(W.delta_all(wl, 0)).to(q.device)
+    d1 = torch.from_numpy(W.delta_all(wl, 1)).to(q.device)
+    outs = []
+    for rep in range(3):
+        m = torch.zeros(2, wl.d, device=q.device)
+        msg = q.new_msg(2)
+        q.compress(m, d0, m, 0, 0, msg)
+        outs.append((m.clone(), msg.clone()))
+        junk = torch.zeros(2, wl.d, device=q.device)
+        q.compress(junk, d1 * (rep + 1), junk, 0, 5, q.new_msg(2))
+    torch.cuda.synchronize()
+    for m, msg in outs[1:]:
+        assert torch.equal(m.view(torch.int32), outs[0][0].view(torch.int32)) and torch.equal(msg, outs[0][1])
