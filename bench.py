@@ -1,0 +1,138 @@
+#!/usr/bin/env python3
+"""Benchmark of the compression hot path on one MI355X.
+
+A "step" is one synchronisation round of the whole hot path over one batch of synthetic input:
+qsl_compress for the R workers (form m + Delta, Top_k select, QSGD quantise, bit-pack, error-memory
+update, payload bit counts) followed by qsl_aggregate of the R messages into the dense update.
+Inputs (a fresh Delta[R, d] per step, the carried error memory) are resident in HBM before the timed
+region starts.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
+ALGO_BYTES_PER_COORD = 12       # read m, read Delta, write m': what the method itself must move
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (2 = headline)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-rounds", type=int, default=2)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the R workers are a batch on one device); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1906_02367_amd import binding as B
+    from paper_1906_02367_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    wl = W.config(args.config)
+    q = B.from_workload(wl, device=dev)
+    R, d = wl.R, wl.d
+    total = args.steps + args.warmup
+
+    # inputs resident in HBM: one fresh Delta per step, generated on the device from a fixed seed
+    gen = W.TorchDeltas(wl, dev)
+    n_buf = total if total * R * d * 4 <= 120e9 else max(2, int(120e9 // (R * d * 4)))
+    deltas = [gen(t) for t in range(n_buf)]
+    m = torch.zeros(R, d, dtype=torch.float32, device=dev)
+    msg = q.new_msg(R)
+    msg_bits = torch.zeros(R, dtype=torch.int64, device=dev)
+    out = torch.zeros(d, dtype=torch.float32, device=dev)
+    torch.cuda.synchronize()
+
+    def step(t):
+        q.compress(m, deltas[t % n_buf], m, 0, t, msg, msg_bits)
+        q.aggregate(msg, out, 1.0 / R)
+
+    for t in range(args.warmup):
+        step(t)
+    torch.cuda.synchronize()
+    q.timing_enable(True)
+    t0 = time.perf_counter()
+    for t in range(args.warmup, total):
+        step(t)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    stream_ms, launches = q.timing_read()
+    q.timing_enable(False)
+    assert q.device_status() == B.OK
+    elapsed = t1 - t0
+    coords_per_s = R * d * args.steps / elapsed
+    units = q.debug_units()
+    bits = msg_bits.cpu().numpy()
+
+    avg_stream_s = stream_ms / 1e3 / max(1, launches)
+    achieved = ALGO_BYTES_PER_COORD * R * d / avg_stream_s / 1e9 if launches else None
+    roofline = {"bound": "hbm", "kernel": "k_stream", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": None,
+                "avg_launch_us": avg_stream_s * 1e6, "launches": launches,
+                "algorithmic_bytes_per_launch": ALGO_BYTES_PER_COORD * R * d}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from concurrent.futures import ThreadPoolExecutor
+        from oracle import oracle as O
+        op = O.OracleOp(wl.d, wl.seg_offset, wl.seg_k, wl.s, wl.sparsifier, wl.quantizer, wl.seed)
+        try:
+            cores = len(os.sched_getaffinity(0))
+        except AttributeError:
+            cores = os.cpu_count() or 1
+        threads = max(1, min(R, cores, int(os.environ.get("OMP_NUM_THREADS", cores))))
+        m_host = np.zeros((R, d), dtype=np.float32)
+        cpu_t, cpu_coords = 0.0, 0
+        for t in range(args.cpu_rounds):
+            d_host = deltas[t % n_buf].cpu().numpy()
+            c0 = time.perf_counter()
+            with ThreadPoolExecutor(max_workers=threads) as ex:
+                res = list(ex.map(lambda r: op.compress(m_host[r], d_host[r], r, t), range(R)))
+            msgs = np.stack([x["msg"] for x in res])
+            op.aggregate(msgs, 1.0 / R)
+            cpu_t += time.perf_counter() - c0
+            cpu_coords += R * d
+            m_host = np.stack([x["m_out"] for x in res])
+        cpu = {"value": cpu_coords / cpu_t, "unit": "coords/s", "cores": threads, "kind": "oracle",
+               "sample": f"{args.cpu_rounds} full sync rounds of the same workload (R={R}, d={d}), one oracle "
+                         f"thread per worker, compress + aggregate"}
+
+    line = {
+        "metric": "compressed coords/sec, Top-k+QSGD+err-update+aggregate" if args.config == 2 else
+                  f"compressed coords/sec, {wl.name}",
+        "value": coords_per_s, "unit": "coords/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "R": R, "d": d, "k": int(wl.K), "s": wl.s, "segments": wl.L,
+                   "sparsifier": ["top_k", "rand_k"][wl.sparsifier], "quantizer": ["qsgd", "sign_l1"][wl.quantizer],
+                   "fresh_delta_buffers": n_buf,
+                   "paths": {"fast": int((units[:, 0] == 0).sum()), "general": int((units[:, 0] == 1).sum()),
+                             "fallback": int((units[:, 0] == 2).sum())},
+                   "max_candidates": int(units[:, 1].max()), "mean_msg_bits": float(bits.mean())},
+        "algorithmic_GBps_whole_step": ALGO_BYTES_PER_COORD * coords_per_s / 1e9,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
