@@ -58,12 +58,12 @@ def main():
     m = torch.zeros(R, d, dtype=torch.float32, device=dev)
     msg = q.new_msg(R)
     msg_bits = torch.zeros(R, dtype=torch.int64, device=dev)
-    out = torch.zeros(d, dtype=torch.float32, device=dev)
+    x = torch.zeros(d, dtype=torch.float32, device=dev)       # the master's parameter vector
     torch.cuda.synchronize()
 
     def step(t):
         q.compress(m, deltas[t % n_buf], m, 0, t, msg, msg_bits)
-        q.aggregate(msg, out, 1.0 / R)
+        q.aggregate(msg, x, -1.0 / R, accumulate=True)     # x <- x - (1/R) sum_r g^(r)
 
     for t in range(args.warmup):
         step(t)

@@ -1,24 +1,31 @@
 // qsl.hip -- kernels and C ABI of the compression hot path of Qsparse-local-SGD for gfx950.
 //
 // One synchronisation step of Algorithm 1 (arXiv:1906.02367) for a batch of R workers:
-//   k_stream        v = m + Delta (worker line 1), written over the error memory, in ONE pass over
-//                   HBM; coordinates whose rank key reaches a per-unit guess threshold are appended,
-//                   in coordinate order, to a small candidate pool
-//   k_sample*       the guess: a quantile of a strided sample of |m + Delta| (Top_k); for Rand_k the
-//                   keys are uniform random words, so the guess is analytic
-//   k_pool_hist,    exact radix selection of the k-th largest key (Section 2.2: Top_k / Rand_k)
-//   k_v_hist,       among the candidates -- or, when a guess fails or a unit is too small/dense for
-//   k_hist_scan     guessing, over the whole vector (the general path, always exact)
-//   k_tile_count/scan/write   ordered compaction of the selected coordinates, ties to the lower index
-//   k_norm*         exact ||v_S||_2^2 or ||v_S||_1 (proof of Lemma 1; Lemma 3 with m = 1)
-//   k_quantize      QSGD levels (Definition 1, example 1) or signs (Definition 2); error update
-//                   m <- v - g on the transmitted coordinates (Algorithm 1, worker line 2)
-//   k_surv_*, k_pack    the packed message
-//   k_aggregate     master line of Algorithm 1, atomic-free
+//   k_sample     the guess (Top_k only): a quantile of a strided sample of |m + Delta|; for Rand_k
+//                the rank keys are uniform random words, so the guess is analytic
+//   k_stream     v = m + Delta (worker line 1), written over the error memory in ONE pass over HBM;
+//                coordinates whose rank key reaches the unit's guess are appended, in coordinate
+//                order, to a small candidate pool (one atomic per wave, no LDS, no block barrier)
+//   k_select<l>  exact radix selection of the k-th largest key (Section 2.2: Top_k / Rand_k), 12+12+8
+//                bits, over the candidates -- or over the whole vector when the guess failed or the
+//                unit is too small/dense for guessing (the general path; always exact)
+//   k_tile_count / k_tile_write    ordered compaction of the selected coordinates, ties to the lower index
+//   k_norm       exact ||v_S||_2^2 or ||v_S||_1 (proof of Lemma 1; Lemma 3 with m = 1) -> fp32 scale
+//   k_quantize   QSGD levels (Definition 1, example 1) or signs (Definition 2); error update
+//                m <- v - g on the transmitted coordinates (Algorithm 1, worker line 2)
+//   k_surv_compact, k_pack    the packed message
+//   k_aggregate  master line of Algorithm 1, atomic-free
 //
 // A "unit" is one (worker, segment) pair: the operator is applied independently to each unit
 // (Corollary 1).  Rank key: Top_k: magnitude bits of v shifted left by one; Rand_k: the
 // coordinate's random word of stream 0.  Larger key first, ties to the lower coordinate.
+//
+// No kernel waits for another block and none uses a device-wide fence (on this GPU the L2 is per
+// XCD, so a device-scope release costs a cache write-back): a value that needs all blocks of a
+// unit -- the radix digit, a prefix of block counts, the fp32 scale -- is recomputed by every block
+// of the NEXT kernel from the small per-block results the previous one left in memory.  Counters
+// that many waves add to (candidate pool, histograms) are split so that few atomics share an
+// address: same-address atomics serialise at ~0.1 us each.
 //
 // Arithmetic contract: every fp32 operation that decides an output is a single IEEE operation
 // (compile with -ffp-contract=off, no fast-math); norms are the exact sum rounded once to double.
@@ -39,56 +46,73 @@ using namespace qsl;
 
 namespace {
 
-constexpr uint32_t CHUNK = 1024;           // coordinates one wave handles at a time: 4 x (64 lanes x 4)
-constexpr uint32_t CHUNKS_PER_TILE = 16;   // a tile is the work of one 256-thread block
-constexpr uint32_t TILE = CHUNK * CHUNKS_PER_TILE;
+constexpr uint32_t CHUNK = 1024;           // coordinates a wave handles at a time: 4 x (64 lanes x 4)
+constexpr uint32_t WT_CHUNKS = 4;          // a wave-tile: the contiguous chunks one wave streams
+constexpr uint32_t WTILE = CHUNK * WT_CHUNKS;
+constexpr uint32_t GROUP = 64;             // wave-tiles per block of the ordered-compaction kernels
 constexpr uint32_t BLOCK = 256;
 constexpr uint32_t HBINS = 4096;           // radix digits: 12 + 12 + 8 bits of the 32-bit rank key
 constexpr uint32_t ACC_SLOTS = 20;         // 32-bit digits of the exact accumulator
-constexpr uint32_t NORM_TILE = 4096;
-constexpr uint32_t QBLOCK = 256;           // block of the quantise / compact kernels
-constexpr uint32_t SAMPLE_BLOCKS = 32;
-constexpr uint32_t POOL_HIST_BLOCKS = 16;
+constexpr uint32_t NORM_TILE = 2048;
+constexpr uint32_t SAMPLE_BLOCKS = 16;     // blocks (of 1024 threads) per unit of the sampling kernel
+constexpr uint32_t SELECT_BLOCKS = 16;     // blocks per unit of the selection kernels
+constexpr uint32_t NSUB = 64;              // sub-pools per unit: wave-tile t appends to sub-pool t mod 64
+constexpr uint32_t MAX_QB_INLINE = 4096;   // above this many quantise blocks a separate prefix kernel runs
 
 enum : uint32_t { PATH_FAST = 0, PATH_GENERAL = 1, PATH_FALLBACK = 2 };
 
 struct SegInfo {
   uint64_t start, size;
-  uint64_t pool_off;    // first pool entry of this segment inside one worker's pool
-  uint32_t k, koff;     // koff: first slot in the [K] selected arrays
-  uint32_t tile_base, ntiles;
-  uint32_t mode;        // PATH_FAST or PATH_GENERAL, decided on the host from (size, k)
-  uint32_t pool_cap;
-  uint32_t n_runs;      // sample: runs of 64 consecutive coordinates
-  uint32_t r_s;         // sample rank that defines the guess
-  uint32_t T_static;    // Rand_k: analytic guess
+  uint64_t pool_off;     // first pool entry of this segment inside one worker's pool
+  uint32_t k, koff;      // koff: first slot in the [K] selected arrays
+  uint32_t wt_base, nwt; // wave-tiles: index of the first one in per-worker arrays, how many
+  uint32_t grp_base, ngrp;
+  uint32_t mode;         // PATH_FAST or PATH_GENERAL, decided on the host from (size, k)
+  uint32_t pool_cap;     // NSUB * sub_cap
+  uint32_t sub_cap;      // entries per sub-pool
+  uint32_t n_runs;       // sample: runs of 64 consecutive coordinates
+  uint32_t r_s;          // sample rank that defines the guess
+  uint32_t T_static;     // Rand_k: analytic guess
+  uint32_t nsel;         // blocks of this unit in the selection kernels
+  uint32_t nnorm;        // norm tiles
+};
+
+struct WtInfo { uint32_t seg, first_chunk, nchunks, pad; };        // one wave-tile
+struct GrpInfo { uint32_t seg, first_wt, nwt, pad; };               // one group of wave-tiles (inside a unit)
+struct SelInfo { uint32_t seg, j, pad0, pad1; };                    // one block of a selection kernel
+struct NormTile { uint32_t seg, first, count, pad; };
+
+// Every field is written by exactly one kernel of a call and read only by later kernels.
+struct UnitState {
+  uint32_t path;        // static: PATH_FAST or PATH_GENERAL
+  uint32_t T;           // guess key (k_sample_scan; static for Rand_k and for the general path)
+  uint32_t cand;        // candidates collected (k_select<0>)
+  uint32_t fell_back;   // 1: the guess failed, the unit runs the general path (k_select<0>)
+  uint32_t prefix, k_rem;   // radix selection state (k_select<1>, k_select<2>)
+  uint32_t tau, need, n_gt; // threshold key, how many equal to it are kept, how many above (k_tile_count)
+  uint32_t nnz;         // transmitted coordinates (zeroed by k_select<0>, counted by k_quantize)
+  uint32_t scale_bits;  // fp32 scale (k_quantize)
   uint32_t pad;
 };
 
-struct TileInfo { uint32_t seg, first_chunk, nchunks, pad; };
-struct NormTile { uint32_t seg, first, count, pad; };
-
-struct UnitState {
-  uint32_t path, T, cand, overflow;
-  uint32_t prefix, k_rem, tau, need;
-  uint32_t n_gt, nnz, scale_bits, pad;
-};
-
 struct DevCtx {
-  const SegInfo* segs; const TileInfo* tiles; const NormTile* ntiles; const uint32_t* fast_segs;
+  const SegInfo* segs; const WtInfo* wts; const GrpInfo* grps; const SelInfo* sels; const NormTile* ntiles;
+  const uint32_t* fast_segs;
   UnitState* units;
   uint2* pool; uint64_t pool_stride;
-  uint2* tile_rec;      // [R][NT]: (offset in the unit's pool, count) of the tile's candidates
-  uint2* tile_cnt;      // [R][NT]: (#key > tau, #key == tau), then their exclusive prefix inside the unit
-  uint32_t* hist;       // [U][HBINS]
-  uint64_t* norm_acc;   // [U][ACC_SLOTS]
+  uint2* wt_rec;        // [R][NWT]: (offset in the unit's pool, count) of the wave-tile's candidates
+  uint2* wt_cnt;        // [R][NWT]: (#key > tau, #key == tau) of the wave-tile
+  uint2* grp_cnt;       // [R][NGRP]: the same per group, then its exclusive prefix inside the unit
+  uint32_t* hist;       // [U][3][HBINS], one histogram per radix digit; all zero between calls
+  uint32_t* sub_cnt;    // [U][NSUB] entries appended to each sub-pool; all zero between calls
+  uint64_t* norm_acc;   // [U][ACC_SLOTS]; all zero between calls
   uint32_t* sel_idx; uint32_t* sel_val; uint32_t* sel_code;   // [R][K]; code = level | neg << 31
-  uint32_t* blk_cnt;    // [R][QB] survivors per quantise block, then exclusive prefix
-  uint32_t* nnz_total;  // [R]
+  uint32_t* blk_cnt;    // [R][QB] survivors per quantise block
+  uint32_t* blk_pre;    // [R][QB + 1] their exclusive prefix and total (only when QB > MAX_QB_INLINE)
   uint32_t* surv_idx; uint32_t* surv_code;                    // [R][K]
-  uint32_t* status; uint32_t* any_fallback;
+  uint32_t* status;
   uint64_t d, seed;
-  uint32_t L, K, NT, NNT, QB, nfast, s, w_idx, w_lev, w_val, sparsifier, quantizer, has_general, cap_words;
+  uint32_t L, K, NWT, NGRP, NSEL, NNT, QB, nfast, s, w_idx, w_lev, w_val, sparsifier, quantizer, cap_words;
 };
 
 __device__ __forceinline__ uint32_t key_of_value(uint32_t vbits) { return (vbits & 0x7FFFFFFFu) << 1; }
@@ -98,204 +122,230 @@ __device__ __forceinline__ uint32_t entry_key(uint2 e, const RandKey& rk) {
   return SPARS == QSL_TOPK ? key_of_value(e.y) : rand_word(rk, e.x);
 }
 
+// rank key of a coordinate in the general path: from v (already written to m_out) or its random word
+template <int SPARS>
+__device__ __forceinline__ uint32_t coord_key(const float* vp, uint64_t e, uint64_t start, const RandKey& rk) {
+  return SPARS == QSL_TOPK ? key_of_value(__float_as_uint(vp[e])) : rand_word(rk, static_cast<uint32_t>(start + e));
+}
+
 // Find, scanning a 4096-bin histogram from its top, the bin in which the running count reaches
-// `target` (1-based).  1024 threads.  Returns the bin; *above = count in the bins above it.
-// If the histogram holds fewer than `target` entries, returns bin 0 with *above = total - hist[0].
-__device__ uint32_t find_from_top(const uint32_t* hist, uint32_t target, uint32_t* above, uint64_t* scratch,
-                                  uint32_t* result) {
-  const uint32_t t = threadIdx.x;                 // thread t owns bins 4095-4t .. 4092-4t (top first)
-  uint32_t h[4]; uint32_t sum = 0;
+// `target` (1-based).  256 threads, thread t owns the 16 bins below 4096 - 16 t.  Returns the bin;
+// *above = count in the bins above it.  If the histogram holds fewer than `target` entries,
+// returns bin 0 with *above = total - hist[0].  If `clear`, zeroes the histogram afterwards.
+__device__ uint32_t find_from_top(uint32_t* hist, uint32_t target, uint32_t* above, uint64_t* scratch,
+                                  uint32_t* result, bool clear) {
+  const uint32_t t = threadIdx.x;
+  uint32_t h[16]; uint32_t sum = 0;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) { h[j] = hist[HBINS - 1 - (4 * t + j)]; sum += h[j]; }
+  for (int j = 0; j < 16; ++j) { h[j] = hist[HBINS - 1 - (16 * t + j)]; sum += h[j]; }
   uint64_t total;
   const uint64_t before = block_exclusive_scan64(sum, scratch, &total);
-  if (t == 0) { result[0] = 0; result[1] = static_cast<uint32_t>(total) - hist[0]; }
+  if (t == BLOCK - 1) { result[0] = 0; result[1] = static_cast<uint32_t>(total) - h[15]; }
   __syncthreads();
   if (before < target && before + sum >= target) {
     uint32_t cum = static_cast<uint32_t>(before);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (cum + h[j] >= target) { result[0] = HBINS - 1 - (4 * t + j); result[1] = cum; break; }
+    for (int j = 0; j < 16; ++j) {
+      if (cum + h[j] >= target) { result[0] = HBINS - 1 - (16 * t + j); result[1] = cum; break; }
       cum += h[j];
     }
+  }
+  if (clear) {
+#pragma unroll
+    for (int j = 0; j < 16; ++j) if (h[j]) hist[HBINS - 1 - (16 * t + j)] = 0;
   }
   __syncthreads();
   *above = result[1];
   return result[0];
 }
 
-// ------------------------------------------------------------------------------------------------
-// per-call initialisation
-// ------------------------------------------------------------------------------------------------
-__global__ void k_init(DevCtx c, uint32_t R) {
-  const uint64_t gid = static_cast<uint64_t>(blockIdx.x) * blockDim.x + threadIdx.x;
-  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * blockDim.x;
-  const uint32_t U = R * c.L;
-  for (uint64_t i = gid; i < U; i += stride) {
-    const SegInfo& sg = c.segs[i % c.L];
-    UnitState u;
-    u.path = sg.mode; u.T = sg.mode == PATH_FAST ? sg.T_static : 0xFFFFFFFFu; u.cand = 0; u.overflow = 0;
-    u.prefix = 0; u.k_rem = sg.k; u.tau = 0; u.need = 0; u.n_gt = 0; u.nnz = 0; u.scale_bits = 0; u.pad = 0;
-    c.units[i] = u;
+__device__ __forceinline__ void flush_hist(const uint32_t* lh, uint32_t* gh) {
+  for (uint32_t i = threadIdx.x; i < HBINS; i += blockDim.x) {
+    const uint32_t v = lh[i];
+    if (v) atomicAdd(&gh[i], v);
   }
-  for (uint64_t i = gid; i < static_cast<uint64_t>(U) * HBINS; i += stride) c.hist[i] = 0;
-  for (uint64_t i = gid; i < static_cast<uint64_t>(U) * ACC_SLOTS; i += stride) c.norm_acc[i] = 0;
-  if (gid == 0) *c.any_fallback = 0;
+}
+
+__device__ __forceinline__ uint32_t eff_path(const UnitState& us) {
+  return us.path == PATH_FAST && us.fell_back ? static_cast<uint32_t>(PATH_FALLBACK) : us.path;
+}
+
+// ------------------------------------------------------------------------------------------------
+// one-time initialisation of the static part of the unit states (at qsl_create)
+// ------------------------------------------------------------------------------------------------
+__global__ void k_init(DevCtx c, uint32_t U) {
+  const uint32_t u = blockIdx.x * blockDim.x + threadIdx.x;
+  if (u >= U) return;
+  const SegInfo& sg = c.segs[u % c.L];
+  UnitState s;
+  s.path = sg.mode; s.T = sg.mode == PATH_FAST ? sg.T_static : 0xFFFFFFFFu; s.cand = 0; s.fell_back = 0;
+  s.prefix = 0; s.k_rem = sg.k; s.tau = 0; s.need = 0; s.n_gt = 0; s.nnz = 0; s.scale_bits = 0; s.pad = 0;
+  c.units[u] = s;
 }
 
 // ------------------------------------------------------------------------------------------------
 // the guess for Top_k: histogram of the rank keys of a strided sample of v = m + Delta
+// (runs of 64 consecutive coordinates, evenly spaced), then the key at a fixed rank of the sample
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(BLOCK) void k_sample(DevCtx c, const float* m, const float* delta) {
+__global__ __launch_bounds__(1024) void k_sample(DevCtx c, const float* m, const float* delta) {
   __shared__ uint32_t lh[HBINS];
   const uint32_t seg = c.fast_segs[blockIdx.y], w = blockIdx.z;
   const SegInfo sg = c.segs[seg];
-  for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK) lh[i] = 0;
+  for (uint32_t i = threadIdx.x; i < HBINS; i += 1024) lh[i] = 0;
   __syncthreads();
   const uint64_t row = static_cast<uint64_t>(w) * c.d + sg.start;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  for (uint32_t run = blockIdx.x * 4 + wave; run < sg.n_runs; run += SAMPLE_BLOCKS * 4) {
-    // run start: floor(run * size / n_runs); size < 2^32 and run < 2^32, so the product fits 64 bits
-    const uint64_t pos = static_cast<uint64_t>(run) * sg.size / sg.n_runs + lane;
-    if (pos < sg.size) {
-      const float v = m[row + pos] + delta[row + pos];
-      atomicAdd(&lh[key_of_value(__float_as_uint(v)) >> 20], 1u);
+  const uint32_t nwaves = SAMPLE_BLOCKS * 16;
+  for (uint32_t run0 = blockIdx.x * 16 + wave; run0 < sg.n_runs; run0 += 4 * nwaves) {
+    float a[4], b[4]; bool ok[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const uint32_t run = run0 + r * nwaves;
+      // run start: floor(run * size / n_runs); size < 2^32 and run < 2^32, so the product fits 64 bits
+      const uint64_t pos = static_cast<uint64_t>(run) * sg.size / sg.n_runs + lane;
+      ok[r] = run < sg.n_runs && pos < sg.size;
+      a[r] = ok[r] ? m[row + pos] : 0.f;
+      b[r] = ok[r] ? delta[row + pos] : 0.f;
     }
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      if (ok[r]) atomicAdd(&lh[key_of_value(__float_as_uint(a[r] + b[r])) >> 20], 1u);
   }
   __syncthreads();
-  uint32_t* gh = c.hist + (static_cast<uint64_t>(w) * c.L + seg) * HBINS;
-  for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK)
-    if (lh[i]) atomicAdd(&gh[i], lh[i]);
+  flush_hist(lh, c.hist + (static_cast<uint64_t>(w) * c.L + seg) * 3 * HBINS);
 }
 
-__global__ __launch_bounds__(1024) void k_sample_scan(DevCtx c) {
+__global__ __launch_bounds__(BLOCK) void k_sample_scan(DevCtx c) {
   __shared__ uint64_t scratch[17];
   __shared__ uint32_t result[2];
   const uint32_t seg = c.fast_segs[blockIdx.x], w = blockIdx.y;
-  const SegInfo& sg = c.segs[seg];
   const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
-  uint32_t* gh = c.hist + u * HBINS;
   uint32_t above;
-  const uint32_t bin = find_from_top(gh, sg.r_s, &above, scratch, result);
-  if (threadIdx.x == 0) c.units[u].T = bin << 20;      // lower edge of the bin
-  for (uint32_t i = threadIdx.x; i < HBINS; i += 1024) gh[i] = 0;
+  const uint32_t bin = find_from_top(c.hist + u * 3 * HBINS, c.segs[seg].r_s, &above, scratch, result, true);
+  if (threadIdx.x == 0) c.units[u].T = bin << 20;      // the guess: lower edge of the bin
 }
 
 // ------------------------------------------------------------------------------------------------
-// the streaming pass
+// the streaming pass.  Every wave owns one wave-tile (4 contiguous chunks of 1024 coordinates).
 // ------------------------------------------------------------------------------------------------
-template <int SPARS>
-__global__ __launch_bounds__(BLOCK) void k_stream(DevCtx c, const float* m,
-                                                  const float* delta, float* m_out, uint32_t worker0,
-                                                  uint64_t round) {
-  __shared__ uint32_t s_cnt[CHUNKS_PER_TILE];
-  __shared__ uint32_t s_base[CHUNKS_PER_TILE + 1];
-  const TileInfo ti = c.tiles[blockIdx.x];
+struct StreamSeg { uint64_t start, size, pool_off; uint32_t sub_cap, wt_base; };
+
+template <int SPARS, bool SINGLE>
+__global__ __launch_bounds__(BLOCK) void k_stream(DevCtx c, StreamSeg one, const float* m, const float* delta,
+                                                  float* m_out, uint32_t worker0, uint64_t round) {
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t wt = blockIdx.x * 4 + wave;
+  if (wt >= c.NWT) return;
   const uint32_t w = blockIdx.y;
-  const SegInfo sg = c.segs[ti.seg];
-  UnitState* us = &c.units[static_cast<uint64_t>(w) * c.L + ti.seg];
-  const bool collect = us->path == PATH_FAST;
-  const uint32_t T = us->T;
+  StreamSeg sg = one;
+  uint32_t seg = 0, first_chunk = wt * WT_CHUNKS, nchunks;
+  if (!SINGLE) {
+    const WtInfo wi = c.wts[wt];
+    const SegInfo& s = c.segs[wi.seg];
+    seg = wi.seg; first_chunk = wi.first_chunk; nchunks = wi.nchunks; sg.wt_base = s.wt_base;
+    sg.start = s.start; sg.size = s.size; sg.pool_off = s.pool_off; sg.sub_cap = s.sub_cap;
+  } else {
+    const uint64_t left = (sg.size + CHUNK - 1) / CHUNK - first_chunk;
+    nchunks = left < WT_CHUNKS ? static_cast<uint32_t>(left) : WT_CHUNKS;
+  }
+  const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
+  const uint32_t T = c.units[u].T;
+  const uint32_t path = c.units[u].path;
   const uint64_t row = static_cast<uint64_t>(w) * c.d + sg.start;
   const float* mp = m + row;
   const float* dp = delta + row;
   float* op = m_out + row;
-  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
-  uint32_t pmask[4] = {0, 0, 0, 0};
+  uint32_t pmask[WT_CHUNKS] = {0, 0, 0, 0};
   bool nonfinite = false;
 
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    const uint32_t lc = q * 4 + wave;
+  for (uint32_t q = 0; q < WT_CHUNKS; ++q) {
+    if (q >= nchunks) break;
+    const uint64_t cb = static_cast<uint64_t>(first_chunk + q) * CHUNK;   // segment-local
     uint32_t pm = 0;
-    if (lc < ti.nchunks) {
-      const uint64_t cb = static_cast<uint64_t>(ti.first_chunk + lc) * CHUNK;   // segment-local
-      const uint64_t left = sg.size - cb;
-      if (left >= CHUNK) {
-        f4u a[4], b[4];
+    if (sg.size - cb >= CHUNK) {
+      f4u a[4], b[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const uint64_t e = cb + t * 256 + lane * 4;
-          a[t] = *reinterpret_cast<const f4u*>(mp + e);
-          b[t] = *reinterpret_cast<const f4u*>(dp + e);
+      for (int t = 0; t < 4; ++t) {
+        const uint64_t e = cb + t * 256 + lane * 4;
+        a[t] = *reinterpret_cast<const f4u*>(mp + e);
+        b[t] = *reinterpret_cast<const f4u*>(dp + e);
+      }
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const uint64_t e = cb + t * 256 + lane * 4;
+        const f4u v = a[t] + b[t];
+        *reinterpret_cast<f4u*>(op + e) = v;
+        Words4 rw;
+        if (SPARS == QSL_RANDK) rw = rand_words4(rk, static_cast<uint32_t>(sg.start + e));
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t bits = __float_as_uint(v[j]);
+          nonfinite |= (bits & 0x7FFFFFFFu) >= 0x7F800000u;
+          const uint32_t key = SPARS == QSL_TOPK ? key_of_value(bits) : rw.w[j];
+          pm |= (key >= T ? 1u : 0u) << (t * 4 + j);
         }
+      }
+    } else {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const uint64_t e = cb + t * 256 + lane * 4;
-          const f4u v = a[t] + b[t];
-          *reinterpret_cast<f4u*>(op + e) = v;
-          Words4 rw;
-          if (SPARS == QSL_RANDK) rw = rand_words4(rk, static_cast<uint32_t>(sg.start + e));
+      for (int t = 0; t < 4; ++t) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const uint32_t bits = __float_as_uint(v[j]);
+        for (int j = 0; j < 4; ++j) {
+          const uint64_t e = cb + t * 256 + lane * 4 + j;
+          if (e < sg.size) {
+            const float v = mp[e] + dp[e];
+            op[e] = v;
+            const uint32_t bits = __float_as_uint(v);
             nonfinite |= (bits & 0x7FFFFFFFu) >= 0x7F800000u;
-            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(bits) : rw.w[j];
+            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(bits)
+                                                   : rand_word(rk, static_cast<uint32_t>(sg.start + e));
             pm |= (key >= T ? 1u : 0u) << (t * 4 + j);
           }
         }
-      } else {
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            const uint64_t e = cb + t * 256 + lane * 4 + j;
-            if (e < sg.size) {
-              const float v = mp[e] + dp[e];
-              op[e] = v;
-              const uint32_t bits = __float_as_uint(v);
-              nonfinite |= (bits & 0x7FFFFFFFu) >= 0x7F800000u;
-              const uint32_t key = SPARS == QSL_TOPK ? key_of_value(bits)
-                                                     : rand_word(rk, static_cast<uint32_t>(sg.start + e));
-              pm |= (key >= T ? 1u : 0u) << (t * 4 + j);
-            }
-          }
-        }
       }
-      if (!collect) pm = 0;
     }
     pmask[q] = pm;
-    const uint32_t cnt = wave_sum(__popc(pm));
-    if (lane == 0) s_cnt[lc] = cnt;
   }
   if (__ballot(nonfinite) != 0 && lane == 0) atomicOr(c.status, 1u);
-  if (!collect) return;                           // uniform over the block
+  if (path != PATH_FAST) return;                  // uniform over the wave
 
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t run = 0;
-    for (uint32_t i = 0; i < CHUNKS_PER_TILE; ++i) { s_base[i] = run; run += s_cnt[i]; }
-    uint32_t off = 0;
-    if (run) {
-      off = atomicAdd(&us->cand, run);
-      if (off > sg.pool_cap || run > sg.pool_cap - off) { us->overflow = 1; off = 0xFFFFFFFFu; }
+  // reserve room in one of the unit's sub-pools for this wave-tile's candidates and write them in
+  // coordinate order.  A sub-pool that runs full keeps counting (the count then exceeds its
+  // capacity, which k_select<0> reads as "guess failed") but takes no more entries.
+  const uint32_t mine = __popc(pmask[0]) + __popc(pmask[1]) + __popc(pmask[2]) + __popc(pmask[3]);
+  const uint32_t total = wave_sum(mine);
+  const uint32_t sp = (SINGLE ? wt : wt - sg.wt_base) & (NSUB - 1);
+  uint32_t off = 0;
+  if (total) {
+    if (lane == 0) {
+      off = atomicAdd(&c.sub_cnt[u * NSUB + sp], total);
+      if (off > sg.sub_cap || total > sg.sub_cap - off) off = 0xFFFFFFFFu;
     }
-    s_base[CHUNKS_PER_TILE] = off;
-    c.tile_rec[static_cast<uint64_t>(w) * c.NT + blockIdx.x] = make_uint2(off == 0xFFFFFFFFu ? 0u : off,
-                                                                          off == 0xFFFFFFFFu ? 0u : run);
+    off = __shfl(off, 0, WAVE);
   }
-  __syncthreads();
-  const uint32_t off = s_base[CHUNKS_PER_TILE];
-  if (off == 0xFFFFFFFFu) return;
+  const bool ok = off != 0xFFFFFFFFu;
+  off += sp * sg.sub_cap;                         // offset inside the unit's pool
+  if (lane == 0)
+    c.wt_rec[static_cast<uint64_t>(w) * c.NWT + wt] = make_uint2(ok ? off : 0u, ok ? total : 0u);
+  if (!ok || total == 0) return;
   uint2* pool = c.pool + static_cast<uint64_t>(w) * c.pool_stride + sg.pool_off + off;
+  uint32_t base = 0;
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
+  for (uint32_t q = 0; q < WT_CHUNKS; ++q) {
     const uint32_t pm = pmask[q];
     if (__ballot(pm != 0) == 0) continue;         // wave-uniform
-    const uint32_t lc = q * 4 + wave;
-    const uint64_t cb = static_cast<uint64_t>(ti.first_chunk + lc) * CHUNK;
-    uint32_t base = s_base[lc];
+    const uint64_t cb = static_cast<uint64_t>(first_chunk + q) * CHUNK;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const uint32_t nib = (pm >> (t * 4)) & 0xFu;
       if (__ballot(nib != 0) == 0) continue;      // wave-uniform
-      uint32_t before = 0, total = 0;
+      uint32_t before = 0, tot = 0;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const uint64_t bal = __ballot((nib >> j) & 1u);
         before += popc_below(bal);
-        total += __popcll(bal);
+        tot += __popcll(bal);
       }
       uint32_t pos = base + before;
 #pragma unroll
@@ -305,24 +355,14 @@ __global__ __launch_bounds__(BLOCK) void k_stream(DevCtx c, const float* m,
           pool[pos++] = make_uint2(static_cast<uint32_t>(sg.start + e), __float_as_uint(op[e]));
         }
       }
-      base += total;
+      base += tot;
     }
   }
 }
 
 // ------------------------------------------------------------------------------------------------
-// validation of the guess; radix selection
+// radix selection, one kernel per digit; the last block of each unit fixes the digit
 // ------------------------------------------------------------------------------------------------
-__global__ void k_validate(DevCtx c, uint32_t U) {
-  const uint32_t u = blockIdx.x * blockDim.x + threadIdx.x;
-  if (u >= U) return;
-  UnitState* us = &c.units[u];
-  if (us->path == PATH_FAST && (us->overflow || us->cand < c.segs[u % c.L].k)) {
-    us->path = PATH_FALLBACK;
-    atomicOr(c.any_fallback, 1u);
-  }
-}
-
 template <int LEVEL>
 __device__ __forceinline__ bool level_bin(uint32_t key, uint32_t prefix, uint32_t* bin) {
   if (LEVEL == 0) { *bin = key >> 20; return true; }
@@ -330,225 +370,193 @@ __device__ __forceinline__ bool level_bin(uint32_t key, uint32_t prefix, uint32_
   *bin = key & 0xFFu; return (key >> 8) == (prefix >> 8);
 }
 
+// Digit LEVEL of the k-th largest key.  The blocks of a unit build the digit's histogram (LDS, then
+// a few global atomics per bin); which bin the previous digit fell in is recomputed by every block
+// from the previous kernel's histogram.
 template <int LEVEL, int SPARS>
-__global__ __launch_bounds__(BLOCK) void k_pool_hist(DevCtx c, uint32_t worker0, uint64_t round) {
+__global__ __launch_bounds__(BLOCK) void k_select(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
   __shared__ uint32_t lh[HBINS];
-  const uint32_t seg = c.fast_segs[blockIdx.y], w = blockIdx.z;
-  const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
-  const UnitState us = c.units[u];
-  if (us.path != PATH_FAST) return;
-  const SegInfo& sg = c.segs[seg];
-  for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK) lh[i] = 0;
-  __syncthreads();
-  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
-  const uint2* pool = c.pool + static_cast<uint64_t>(w) * c.pool_stride + sg.pool_off;
-  for (uint32_t e = blockIdx.x * BLOCK + threadIdx.x; e < us.cand; e += POOL_HIST_BLOCKS * BLOCK) {
-    uint32_t bin;
-    if (level_bin<LEVEL>(entry_key<SPARS>(pool[e], rk), us.prefix, &bin)) atomicAdd(&lh[bin], 1u);
-  }
-  __syncthreads();
-  uint32_t* gh = c.hist + u * HBINS;
-  for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK)
-    if (lh[i]) atomicAdd(&gh[i], lh[i]);
-}
-
-// rank key of a coordinate in the general path: from v (already written to m_out) or its random word
-template <int SPARS>
-__device__ __forceinline__ uint32_t coord_key(const float* vp, uint64_t e, uint64_t start, const RandKey& rk) {
-  return SPARS == QSL_TOPK ? key_of_value(__float_as_uint(vp[e])) : rand_word(rk, static_cast<uint32_t>(start + e));
-}
-
-template <int LEVEL, int SPARS>
-__global__ __launch_bounds__(BLOCK) void k_v_hist(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
-  __shared__ uint32_t lh[HBINS];
-  if (!c.has_general && !*c.any_fallback) return;
-  const uint32_t w = blockIdx.y;
-  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
-  for (uint32_t t = blockIdx.x; t < c.NT; t += gridDim.x) {
-    const TileInfo ti = c.tiles[t];
-    const uint64_t u = static_cast<uint64_t>(w) * c.L + ti.seg;
-    const UnitState us = c.units[u];
-    if (us.path == PATH_FAST) continue;
-    const SegInfo& sg = c.segs[ti.seg];
-    for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK) lh[i] = 0;
-    __syncthreads();
-    const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
-    const uint64_t lo = static_cast<uint64_t>(ti.first_chunk) * CHUNK;
-    const uint64_t hi = std::min<uint64_t>(sg.size, lo + static_cast<uint64_t>(ti.nchunks) * CHUNK);
-    for (uint64_t e = lo + threadIdx.x; e < hi; e += BLOCK) {
-      uint32_t bin;
-      if (level_bin<LEVEL>(coord_key<SPARS>(vp, e, sg.start, rk), us.prefix, &bin)) atomicAdd(&lh[bin], 1u);
-    }
-    __syncthreads();
-    uint32_t* gh = c.hist + u * HBINS;
-    for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK)
-      if (lh[i]) atomicAdd(&gh[i], lh[i]);
-    __syncthreads();
-  }
-}
-
-template <int LEVEL>
-__global__ __launch_bounds__(1024) void k_hist_scan(DevCtx c) {
   __shared__ uint64_t scratch[17];
-  __shared__ uint32_t result[2];
-  const uint64_t u = static_cast<uint64_t>(blockIdx.y) * c.L + blockIdx.x;
-  UnitState* us = &c.units[u];
-  uint32_t* gh = c.hist + u * HBINS;
-  uint32_t above;
-  const uint32_t k_rem = us->k_rem;
-  const uint32_t bin = find_from_top(gh, k_rem, &above, scratch, result);
+  __shared__ uint32_t result[2], s_sub[NSUB];
+  const SelInfo si = c.sels[blockIdx.x];
+  const uint32_t w = blockIdx.y;
+  const SegInfo sg = c.segs[si.seg];
+  const uint64_t u = static_cast<uint64_t>(w) * c.L + si.seg;
+  UnitState* usp = &c.units[u];
+  const UnitState us = *usp;
+  uint32_t* hist = c.hist + u * 3 * HBINS;
+  for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK) lh[i] = 0;
+  if (threadIdx.x < NSUB) s_sub[threadIdx.x] = us.path == PATH_FAST ? c.sub_cnt[u * NSUB + threadIdx.x] : 0u;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    const uint32_t shift = LEVEL == 0 ? 20 : LEVEL == 1 ? 8 : 0;
-    const uint32_t prefix = us->prefix | (bin << shift);
-    us->prefix = prefix;
-    us->k_rem = k_rem - above;
-    if (LEVEL == 2) {
-      us->tau = prefix;
-      us->need = k_rem - above;                       // how many coordinates with key == tau are kept
-      us->n_gt = c.segs[blockIdx.x].k - (k_rem - above);
+  uint32_t path, prefix = 0, k_rem = sg.k;
+  if (LEVEL == 0) {
+    // a guess that produced too few candidates, or overflowed a sub-pool, is discarded here
+    path = us.path;
+    if (path == PATH_FAST) {
+      uint32_t cand = 0; bool over = false;
+      for (uint32_t i = 0; i < NSUB; ++i) { cand += s_sub[i]; over |= s_sub[i] > sg.sub_cap; }
+      if (over || cand < sg.k) path = PATH_FALLBACK;
+      if (threadIdx.x == 0 && si.j == 0) { usp->cand = cand; usp->fell_back = path == PATH_FALLBACK; }
+    } else if (threadIdx.x == 0 && si.j == 0) { usp->cand = 0; usp->fell_back = 0; }
+    if (threadIdx.x == 0 && si.j == 0) usp->nnz = 0;
+  } else {
+    path = eff_path(us);
+    uint32_t above;
+    if (LEVEL == 1) {
+      const uint32_t bin = find_from_top(hist, sg.k, &above, scratch, result, false);
+      prefix = bin << 20; k_rem = sg.k - above;
+    } else {
+      const uint32_t bin = find_from_top(hist + HBINS, us.k_rem, &above, scratch, result, false);
+      prefix = us.prefix | (bin << 8); k_rem = us.k_rem - above;
+    }
+    if (threadIdx.x == 0 && si.j == 0) { usp->prefix = prefix; usp->k_rem = k_rem; }
+  }
+  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
+  if (path == PATH_FAST) {
+    const uint2* pool = c.pool + static_cast<uint64_t>(w) * c.pool_stride + sg.pool_off;
+    for (uint32_t sp = si.j; sp < NSUB; sp += sg.nsel) {
+      const uint2* sub = pool + static_cast<uint64_t>(sp) * sg.sub_cap;
+      const uint32_t n = s_sub[sp];
+      for (uint32_t e = threadIdx.x; e < n; e += BLOCK) {
+        uint32_t bin;
+        if (level_bin<LEVEL>(entry_key<SPARS>(sub[e], rk), prefix, &bin)) atomicAdd(&lh[bin], 1u);
+      }
+    }
+  } else {
+    const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
+    for (uint64_t t = si.j; t < sg.nwt; t += sg.nsel) {
+      const uint64_t lo = t * WTILE, hi = lo + WTILE < sg.size ? lo + WTILE : sg.size;
+      for (uint64_t e = lo + threadIdx.x; e < hi; e += BLOCK) {
+        uint32_t bin;
+        if (level_bin<LEVEL>(coord_key<SPARS>(vp, e, sg.start, rk), prefix, &bin)) atomicAdd(&lh[bin], 1u);
+      }
     }
   }
-  for (uint32_t i = threadIdx.x; i < HBINS; i += 1024) gh[i] = 0;
+  __syncthreads();
+  flush_hist(lh, hist + LEVEL * HBINS);
 }
 
 // ------------------------------------------------------------------------------------------------
-// ordered compaction of the selected coordinates
+// ordered compaction of the selected coordinates.  A block handles a group of up to 64 wave-tiles
+// of one unit; a wave handles one wave-tile at a time.
 // ------------------------------------------------------------------------------------------------
 template <int SPARS>
 __global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
   __shared__ uint32_t s_gt[4], s_eq[4];
-  const TileInfo ti = c.tiles[blockIdx.x];
+  __shared__ uint64_t scratch[17];
+  __shared__ uint32_t result[2];
+  const GrpInfo gi = c.grps[blockIdx.x];
   const uint32_t w = blockIdx.y;
-  const uint64_t u = static_cast<uint64_t>(w) * c.L + ti.seg;
-  const UnitState us = c.units[u];
-  const SegInfo& sg = c.segs[ti.seg];
+  const SegInfo sg = c.segs[gi.seg];
+  const uint64_t u = static_cast<uint64_t>(w) * c.L + gi.seg;
+  UnitState us = c.units[u];
+  us.path = eff_path(us);
+  {  // the last digit, from the histogram k_select<2> left: the threshold key and the tie budget
+    uint32_t above;
+    const uint32_t bin = find_from_top(c.hist + (u * 3 + 2) * HBINS, us.k_rem, &above, scratch, result, false);
+    us.tau = us.prefix | bin; us.need = us.k_rem - above;
+    if (threadIdx.x == 0 && gi.first_wt == 0) {
+      c.units[u].tau = us.tau; c.units[u].need = us.need; c.units[u].n_gt = sg.k - us.need;
+    }
+  }
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  uint2* out = &c.tile_cnt[static_cast<uint64_t>(w) * c.NT + blockIdx.x];
-  uint32_t gt = 0, eq = 0;
-  if (us.path == PATH_FAST) {
-    if (wave != 0) return;
-    const uint2 rec = c.tile_rec[static_cast<uint64_t>(w) * c.NT + blockIdx.x];
-    const uint2* pool = c.pool + static_cast<uint64_t>(w) * c.pool_stride + sg.pool_off + rec.x;
-    for (uint32_t e = lane; e < rec.y; e += WAVE) {
-      const uint32_t key = entry_key<SPARS>(pool[e], rk);
-      gt += key > us.tau; eq += key == us.tau;
+  const uint64_t wbase = static_cast<uint64_t>(w) * c.NWT + sg.wt_base;
+  const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
+  const uint2* pool = c.pool + static_cast<uint64_t>(w) * c.pool_stride + sg.pool_off;
+  uint32_t tot_gt = 0, tot_eq = 0;
+  for (uint32_t i = wave; i < gi.nwt; i += 4) {
+    const uint32_t t = gi.first_wt + i;
+    uint32_t gt = 0, eq = 0;
+    if (us.path == PATH_FAST) {
+      const uint2 rec = c.wt_rec[wbase + t];
+      for (uint32_t e = lane; e < rec.y; e += WAVE) {
+        const uint32_t key = entry_key<SPARS>(pool[rec.x + e], rk);
+        gt += key > us.tau; eq += key == us.tau;
+      }
+    } else {
+      const uint64_t lo = static_cast<uint64_t>(t) * WTILE, hi = lo + WTILE < sg.size ? lo + WTILE : sg.size;
+      for (uint64_t e = lo + lane; e < hi; e += WAVE) {
+        const uint32_t key = coord_key<SPARS>(vp, e, sg.start, rk);
+        gt += key > us.tau; eq += key == us.tau;
+      }
     }
     gt = wave_sum(gt); eq = wave_sum(eq);
-    if (lane == 0) *out = make_uint2(gt, eq);
-    return;
+    if (lane == 0) c.wt_cnt[wbase + t] = make_uint2(gt, eq);
+    tot_gt += gt; tot_eq += eq;
   }
-  const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
-  const uint64_t lo = static_cast<uint64_t>(ti.first_chunk) * CHUNK;
-  const uint64_t hi = std::min<uint64_t>(sg.size, lo + static_cast<uint64_t>(ti.nchunks) * CHUNK);
-  for (uint64_t e = lo + threadIdx.x; e < hi; e += BLOCK) {
-    const uint32_t key = coord_key<SPARS>(vp, e, sg.start, rk);
-    gt += key > us.tau; eq += key == us.tau;
-  }
-  gt = wave_sum(gt); eq = wave_sum(eq);
-  if (lane == 0) { s_gt[wave] = gt; s_eq[wave] = eq; }
+  if (lane == 0) { s_gt[wave] = tot_gt; s_eq[wave] = tot_eq; }
   __syncthreads();
-  if (threadIdx.x == 0) *out = make_uint2(s_gt[0] + s_gt[1] + s_gt[2] + s_gt[3], s_eq[0] + s_eq[1] + s_eq[2] + s_eq[3]);
-}
-
-// exclusive prefix of the (greater, equal) tile counts inside each unit; one block per unit
-__global__ __launch_bounds__(1024) void k_tile_scan(DevCtx c) {
-  __shared__ uint64_t scratch[17];
-  const SegInfo& sg = c.segs[blockIdx.x];
-  uint2* cnt = c.tile_cnt + static_cast<uint64_t>(blockIdx.y) * c.NT + sg.tile_base;
-  uint64_t carry = 0;
-  for (uint32_t base = 0; base < sg.ntiles; base += 1024) {
-    const uint32_t i = base + threadIdx.x;
-    uint64_t x = 0;
-    if (i < sg.ntiles) { const uint2 p = cnt[i]; x = (static_cast<uint64_t>(p.y) << 32) | p.x; }
-    uint64_t total;
-    const uint64_t ex = block_exclusive_scan64(x, scratch, &total) + carry;
-    if (i < sg.ntiles) cnt[i] = make_uint2(static_cast<uint32_t>(ex), static_cast<uint32_t>(ex >> 32));
-    carry += total;
-  }
+  uint2* gc = c.grp_cnt + static_cast<uint64_t>(w) * c.NGRP + sg.grp_base;
+  if (threadIdx.x == 0)
+    gc[gi.first_wt / GROUP] = make_uint2(s_gt[0] + s_gt[1] + s_gt[2] + s_gt[3], s_eq[0] + s_eq[1] + s_eq[2] + s_eq[3]);
 }
 
 template <int SPARS>
 __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
-  __shared__ uint32_t s_gt[CHUNKS_PER_TILE + 1], s_eq[CHUNKS_PER_TILE + 1];
-  const TileInfo ti = c.tiles[blockIdx.x];
+  __shared__ uint32_t s_gt[GROUP], s_eq[GROUP];
+  __shared__ uint64_t s_part[4];
+  const GrpInfo gi = c.grps[blockIdx.x];
   const uint32_t w = blockIdx.y;
-  const uint64_t u = static_cast<uint64_t>(w) * c.L + ti.seg;
-  const UnitState us = c.units[u];
-  const SegInfo& sg = c.segs[ti.seg];
+  const SegInfo sg = c.segs[gi.seg];
+  const uint64_t u = static_cast<uint64_t>(w) * c.L + gi.seg;
+  UnitState us = c.units[u];
+  us.path = eff_path(us);
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const uint2 base = c.tile_cnt[static_cast<uint64_t>(w) * c.NT + blockIdx.x];
+  const uint64_t wbase = static_cast<uint64_t>(w) * c.NWT + sg.wt_base;
+  // how many selected coordinates precede this group: the sum of the earlier groups' counts
+  {
+    const uint2* gc = c.grp_cnt + static_cast<uint64_t>(w) * c.NGRP + sg.grp_base;
+    const uint32_t g = gi.first_wt / GROUP;
+    uint64_t x = 0;
+    for (uint32_t i = threadIdx.x; i < g; i += BLOCK) { const uint2 p = gc[i]; x += (static_cast<uint64_t>(p.y) << 32) | p.x; }
+    x = wave_sum64(x);
+    if (lane == 0) s_part[wave] = x;
+  }
+  __syncthreads();
+  // exclusive prefix of this group's wave-tile counts, on top of the group's own prefix
+  if (threadIdx.x < GROUP) {
+    uint2 p = make_uint2(0, 0);
+    if (threadIdx.x < gi.nwt) p = c.wt_cnt[wbase + gi.first_wt + threadIdx.x];
+    const uint64_t x = (static_cast<uint64_t>(p.y) << 32) | p.x;
+    const uint64_t ex = wave_inclusive_scan64(x) - x + s_part[0] + s_part[1] + s_part[2] + s_part[3];
+    s_gt[threadIdx.x] = static_cast<uint32_t>(ex); s_eq[threadIdx.x] = static_cast<uint32_t>(ex >> 32);
+  }
+  __syncthreads();
   uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
   uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
-  if (us.path == PATH_FAST) {
-    if (wave != 0) return;
-    const uint2 rec = c.tile_rec[static_cast<uint64_t>(w) * c.NT + blockIdx.x];
-    const uint2* pool = c.pool + static_cast<uint64_t>(w) * c.pool_stride + sg.pool_off + rec.x;
-    uint32_t gt_before = base.x, eq_before = base.y;
-    for (uint32_t e0 = 0; e0 < rec.y; e0 += WAVE) {
-      const uint32_t e = e0 + lane;
-      uint2 ent = make_uint2(0, 0);
-      bool is_gt = false, is_eq = false;
-      if (e < rec.y) {
-        ent = pool[e];
-        const uint32_t key = entry_key<SPARS>(ent, rk);
-        is_gt = key > us.tau; is_eq = key == us.tau;
-      }
-      const uint64_t bg = __ballot(is_gt), be = __ballot(is_eq);
-      const uint32_t my_gt = gt_before + popc_below(bg), my_eq = eq_before + popc_below(be);
-      if (is_gt || (is_eq && my_eq < us.need)) {
-        const uint32_t pos = my_gt + min(my_eq, us.need);
-        oi[pos] = ent.x; ov[pos] = ent.y;
-      }
-      gt_before += __popcll(bg); eq_before += __popcll(be);
-    }
-    return;
-  }
-  // general path: per-chunk counts first, so that every wave knows where its chunks start
   const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
-  for (uint32_t lc = wave; lc < CHUNKS_PER_TILE; lc += 4) {
-    uint32_t gt = 0, eq = 0;
-    if (lc < ti.nchunks) {
-      const uint64_t cb = static_cast<uint64_t>(ti.first_chunk + lc) * CHUNK;
-      for (uint32_t j = lane; j < CHUNK; j += WAVE) {
-        const uint64_t e = cb + j;
-        if (e < sg.size) {
-          const uint32_t key = coord_key<SPARS>(vp, e, sg.start, rk);
-          gt += key > us.tau; eq += key == us.tau;
-        }
-      }
+  const uint2* pool = c.pool + static_cast<uint64_t>(w) * c.pool_stride + sg.pool_off;
+  for (uint32_t i = wave; i < gi.nwt; i += 4) {
+    const uint32_t t = gi.first_wt + i;
+    uint32_t gt_before = s_gt[i], eq_before = s_eq[i];
+    uint32_t n_items; uint64_t lo = 0; uint2 rec = make_uint2(0, 0);
+    if (us.path == PATH_FAST) { rec = c.wt_rec[wbase + t]; n_items = rec.y; }
+    else {
+      lo = static_cast<uint64_t>(t) * WTILE;
+      n_items = static_cast<uint32_t>((lo + WTILE < sg.size ? lo + WTILE : sg.size) - lo);
     }
-    gt = wave_sum(gt); eq = wave_sum(eq);
-    if (lane == 0) { s_gt[lc] = gt; s_eq[lc] = eq; }
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t rg = base.x, re = base.y;
-    for (uint32_t i = 0; i < CHUNKS_PER_TILE; ++i) {
-      const uint32_t g = s_gt[i], q = s_eq[i];
-      s_gt[i] = rg; s_eq[i] = re; rg += g; re += q;
-    }
-  }
-  __syncthreads();
-  for (uint32_t lc = wave; lc < ti.nchunks; lc += 4) {
-    const uint64_t cb = static_cast<uint64_t>(ti.first_chunk + lc) * CHUNK;
-    uint32_t gt_before = s_gt[lc], eq_before = s_eq[lc];
-    for (uint32_t j0 = 0; j0 < CHUNK; j0 += WAVE) {
-      const uint64_t e = cb + j0 + lane;
+    for (uint32_t j0 = 0; j0 < n_items; j0 += WAVE) {
+      const uint32_t j = j0 + lane;
       bool is_gt = false, is_eq = false;
-      uint32_t bits = 0;
-      if (e < sg.size) {
-        bits = __float_as_uint(vp[e]);
-        const uint32_t key = SPARS == QSL_TOPK ? key_of_value(bits) : rand_word(rk, static_cast<uint32_t>(sg.start + e));
+      uint32_t idx = 0, bits = 0;
+      if (j < n_items) {
+        uint32_t key;
+        if (us.path == PATH_FAST) {
+          const uint2 ent = pool[rec.x + j];
+          idx = ent.x; bits = ent.y; key = entry_key<SPARS>(ent, rk);
+        } else {
+          idx = static_cast<uint32_t>(sg.start + lo + j); bits = __float_as_uint(vp[lo + j]);
+          key = SPARS == QSL_TOPK ? key_of_value(bits) : rand_word(rk, idx);
+        }
         is_gt = key > us.tau; is_eq = key == us.tau;
       }
       const uint64_t bg = __ballot(is_gt), be = __ballot(is_eq);
       const uint32_t my_gt = gt_before + popc_below(bg), my_eq = eq_before + popc_below(be);
       if (is_gt || (is_eq && my_eq < us.need)) {
         const uint32_t pos = my_gt + min(my_eq, us.need);
-        oi[pos] = static_cast<uint32_t>(sg.start + e); ov[pos] = bits;
+        oi[pos] = idx; ov[pos] = bits;
       }
       gt_before += __popcll(bg); eq_before += __popcll(be);
     }
@@ -557,13 +565,49 @@ __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, const float* v, 
 
 // ------------------------------------------------------------------------------------------------
 // exact norms: every |v| (or v^2) is an integer multiple of 2^-149 (2^-298); its 32-bit digits are
-// added into 64-bit counters, integer addition commutes, so any schedule gives the same sum
+// added into 64-bit counters, integer addition commutes, so any schedule gives the same sum.  The
+// digits become one correctly rounded double and then the fp32 scale (in k_quantize).
 // ------------------------------------------------------------------------------------------------
+__device__ float finalize_scale(const uint64_t* acc, bool squares, uint32_t k) {
+  uint32_t dig[ACC_SLOTS + 2];
+  uint64_t carry = 0;
+  for (uint32_t i = 0; i < ACC_SLOTS; ++i) { const uint64_t t = acc[i] + carry; dig[i] = static_cast<uint32_t>(t); carry = t >> 32; }
+  dig[ACC_SLOTS] = static_cast<uint32_t>(carry);
+  dig[ACC_SLOTS + 1] = 0;
+  int tw = -1;
+  for (int i = ACC_SLOTS; i >= 0; --i) if (dig[i]) { tw = i; break; }
+  double S = 0.0;
+  if (tw >= 0) {
+    const int top = tw * 32 + 31 - __clz(dig[tw]);
+    const int low = top - 52;                       // position of the last kept bit
+    uint64_t mant; int e2;
+    if (low <= 0) {
+      mant = (static_cast<uint64_t>(dig[1]) << 32) | dig[0]; e2 = 0;      // the whole value, exact
+    } else {
+      const int wq = low >> 5, r = low & 31;        // wq + 1 <= tw <= ACC_SLOTS
+      const uint64_t lo64 = (static_cast<uint64_t>(dig[wq + 1]) << 32) | dig[wq];
+      const uint64_t hi32 = wq + 2 <= static_cast<int>(ACC_SLOTS) ? dig[wq + 2] : 0u;
+      uint64_t win = lo64 >> r;
+      if (r) win |= hi32 << (64 - r);
+      mant = win & ((1ull << 53) - 1);
+      const int g = low - 1;
+      const uint32_t guard = (dig[g >> 5] >> (g & 31)) & 1u;
+      bool sticky = (dig[g >> 5] & ((1u << (g & 31)) - 1u)) != 0;
+      for (int i = 0; i < (g >> 5); ++i) sticky |= dig[i] != 0;
+      if (guard && (sticky || (mant & 1u))) mant += 1;
+      e2 = low;
+    }
+    S = ldexp(static_cast<double>(mant), e2 + (squares ? -298 : -149));
+  }
+  return squares ? static_cast<float>(sqrt(S)) : static_cast<float>(S / static_cast<double>(k));
+}
+
 __global__ __launch_bounds__(BLOCK) void k_norm(DevCtx c) {
   __shared__ uint64_t acc[BLOCK * (ACC_SLOTS + 1)];
   const NormTile nt = c.ntiles[blockIdx.x];
   const uint32_t w = blockIdx.y;
-  const SegInfo& sg = c.segs[nt.seg];
+  const SegInfo sg = c.segs[nt.seg];
+  const bool squares = c.quantizer == QSL_QSGD;
   uint64_t* mine = acc + threadIdx.x * (ACC_SLOTS + 1);
 #pragma unroll
   for (uint32_t i = 0; i < ACC_SLOTS; ++i) mine[i] = 0;
@@ -574,7 +618,7 @@ __global__ __launch_bounds__(BLOCK) void k_norm(DevCtx c) {
     const uint32_t M = ex ? (frac | 0x800000u) : frac;       // |v| = M * 2^(max(ex,1) - 150)
     const uint32_t e1 = ex ? ex : 1u;
     if (M == 0) continue;
-    if (c.quantizer == QSL_QSGD) {
+    if (squares) {
       const uint64_t sq = static_cast<uint64_t>(M) * M;       // < 2^48;  v^2 = sq * 2^(2 e1 - 300)
       const uint32_t p = 2u * e1 - 2u;                        // bit position above 2^-298
       const uint32_t q = p >> 5, r = p & 31u;
@@ -589,43 +633,16 @@ __global__ __launch_bounds__(BLOCK) void k_norm(DevCtx c) {
     }
   }
   __syncthreads();
-  if (threadIdx.x < ACC_SLOTS) {
-    uint64_t sum = 0;
-    for (uint32_t t = 0; t < BLOCK; ++t) sum += acc[t * (ACC_SLOTS + 1) + threadIdx.x];
-    if (sum) atomicAdd(reinterpret_cast<unsigned long long*>(c.norm_acc + (static_cast<uint64_t>(w) * c.L + nt.seg) * ACC_SLOTS + threadIdx.x),
-                       static_cast<unsigned long long>(sum));
+  const uint64_t u = static_cast<uint64_t>(w) * c.L + nt.seg;
+  uint64_t* ga = c.norm_acc + u * ACC_SLOTS;
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  for (uint32_t s = wave; s < ACC_SLOTS; s += 4) {
+    uint64_t x = 0;
+#pragma unroll
+    for (uint32_t r = 0; r < BLOCK; r += WAVE) x += acc[(r + lane) * (ACC_SLOTS + 1) + s];
+    x = wave_sum64(x);
+    if (lane == 0 && x) atomicAdd(reinterpret_cast<unsigned long long*>(ga + s), static_cast<unsigned long long>(x));
   }
-}
-
-// digits -> one correctly rounded double -> the fp32 scale of the unit
-__global__ void k_norm_finalize(DevCtx c, uint32_t U) {
-  const uint32_t u = blockIdx.x * blockDim.x + threadIdx.x;
-  if (u >= U) return;
-  const uint64_t* a = c.norm_acc + static_cast<uint64_t>(u) * ACC_SLOTS;
-  uint32_t dig[ACC_SLOTS + 1];
-  uint64_t carry = 0;
-  for (uint32_t i = 0; i < ACC_SLOTS; ++i) { const uint64_t t = a[i] + carry; dig[i] = static_cast<uint32_t>(t); carry = t >> 32; }
-  dig[ACC_SLOTS] = static_cast<uint32_t>(carry);
-  int top = -1;
-  for (int i = ACC_SLOTS; i >= 0; --i) if (dig[i]) { top = i * 32 + 31 - __clz(dig[i]); break; }
-  double S = 0.0;
-  if (top >= 0) {
-    const int low = top - 52;                 // last kept bit
-    uint64_t mant = 0;
-    for (int b = top; b >= (low > 0 ? low : 0); --b) mant = (mant << 1) | ((dig[b >> 5] >> (b & 31)) & 1u);
-    int e2 = low > 0 ? low : 0;
-    if (low > 0) {
-      const uint32_t guard = (dig[(low - 1) >> 5] >> ((low - 1) & 31)) & 1u;
-      bool sticky = false;
-      for (int b = 0; b < low - 1; ++b) sticky |= (dig[b >> 5] >> (b & 31)) & 1u;
-      if (guard && (sticky || (mant & 1u))) mant += 1;
-    }
-    S = ldexp(static_cast<double>(mant), e2 + (c.quantizer == QSL_QSGD ? -298 : -149));
-  }
-  float scale;
-  if (c.quantizer == QSL_QSGD) scale = static_cast<float>(sqrt(S));
-  else scale = static_cast<float>(S / static_cast<double>(c.segs[u % c.L].k));
-  c.units[u].scale_bits = __float_as_uint(scale);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -648,18 +665,31 @@ __device__ __forceinline__ float qsgd_value(float N, uint32_t level, uint32_t s,
   return neg ? -mag : mag;
 }
 
-__global__ __launch_bounds__(QBLOCK) void k_quantize(DevCtx c, float* m_out, uint32_t worker0, uint64_t round,
-                                                     uint32_t* dbg_idx, uint16_t* dbg_level) {
-  __shared__ uint32_t s_w[QBLOCK / 64];
+__global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint32_t worker0, uint64_t round,
+                                                    uint32_t* dbg_idx, uint16_t* dbg_level) {
+  __shared__ uint32_t s_w[BLOCK / 64];
+  __shared__ float s_scale[BLOCK];
   const uint32_t w = blockIdx.y;
-  const uint32_t j = blockIdx.x * QBLOCK + threadIdx.x;
+  const uint32_t j = blockIdx.x * BLOCK + threadIdx.x;
+  // the scales of the units this block's slots belong to (at most one unit per slot)
+  const uint32_t j_first = blockIdx.x * BLOCK, j_last = min(j_first + BLOCK, c.K) - 1;
+  const uint32_t seg_first = c.L == 1 ? 0u : seg_of_slot(c, j_first);
+  const uint32_t seg_last = c.L == 1 ? 0u : seg_of_slot(c, j_last);
+  if (threadIdx.x <= seg_last - seg_first) {
+    const uint32_t seg = seg_first + threadIdx.x;
+    const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
+    const float sc = finalize_scale(c.norm_acc + u * ACC_SLOTS, c.quantizer == QSL_QSGD, c.segs[seg].k);
+    s_scale[threadIdx.x] = sc;
+    if (c.segs[seg].koff >= j_first) c.units[u].scale_bits = __float_as_uint(sc);   // the block holding the unit's first slot
+  }
+  __syncthreads();
   uint32_t sent = 0;
   if (j < c.K) {
     const uint32_t seg = c.L == 1 ? 0u : seg_of_slot(c, j);
     const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
     const uint64_t slot = static_cast<uint64_t>(w) * c.K + j;
     const uint32_t idx = c.sel_idx[slot], bits = c.sel_val[slot];
-    const float scale = __uint_as_float(c.units[u].scale_bits);
+    const float scale = s_scale[seg - seg_first];
     const float v = __uint_as_float(bits);
     const bool neg = v < 0.0f;
     uint32_t level;
@@ -694,32 +724,46 @@ __global__ __launch_bounds__(QBLOCK) void k_quantize(DevCtx c, float* m_out, uin
   const uint32_t wc = __popcll(__ballot(sent));
   if (lane_id() == 0) s_w[threadIdx.x >> 6] = wc;
   __syncthreads();
-  if (threadIdx.x == 0) {
-    uint32_t t = 0;
-    for (uint32_t i = 0; i < QBLOCK / 64; ++i) t += s_w[i];
-    c.blk_cnt[static_cast<uint64_t>(w) * c.QB + blockIdx.x] = t;
-  }
+  uint32_t* cnt = c.blk_cnt + static_cast<uint64_t>(w) * c.QB;
+  if (threadIdx.x == 0) cnt[blockIdx.x] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
 }
 
+// sum of cnt[0 .. n), by the whole block
+__device__ __forceinline__ uint32_t block_sum_u32(const uint32_t* cnt, uint32_t n, uint32_t* s_part) {
+  uint32_t x = 0;
+  for (uint32_t i = threadIdx.x; i < n; i += BLOCK) x += cnt[i];
+  x = wave_sum(x);
+  __syncthreads();
+  if (lane_id() == 0) s_part[threadIdx.x >> 6] = x;
+  __syncthreads();
+  return s_part[0] + s_part[1] + s_part[2] + s_part[3];
+}
+
+// only for very large K: exclusive prefix (and total) of the per-block survivor counts, one block per worker
 __global__ __launch_bounds__(1024) void k_surv_scan(DevCtx c) {
   __shared__ uint64_t scratch[17];
-  uint32_t* cnt = c.blk_cnt + static_cast<uint64_t>(blockIdx.x) * c.QB;
+  const uint32_t* cnt = c.blk_cnt + static_cast<uint64_t>(blockIdx.x) * c.QB;
+  uint32_t* pre = c.blk_pre + static_cast<uint64_t>(blockIdx.x) * (c.QB + 1);
   uint64_t carry = 0;
   for (uint32_t base = 0; base < c.QB; base += 1024) {
     const uint32_t i = base + threadIdx.x;
     const uint64_t x = i < c.QB ? cnt[i] : 0;
     uint64_t total;
     const uint64_t ex = block_exclusive_scan64(x, scratch, &total) + carry;
-    if (i < c.QB) cnt[i] = static_cast<uint32_t>(ex);
+    if (i < c.QB) pre[i] = static_cast<uint32_t>(ex);
     carry += total;
   }
-  if (threadIdx.x == 0) c.nnz_total[blockIdx.x] = static_cast<uint32_t>(carry);
+  if (threadIdx.x == 0) pre[c.QB] = static_cast<uint32_t>(carry);
 }
 
-__global__ __launch_bounds__(QBLOCK) void k_surv_compact(DevCtx c) {
-  __shared__ uint32_t s_w[QBLOCK / 64];
+__global__ __launch_bounds__(BLOCK) void k_surv_compact(DevCtx c) {
+  __shared__ uint32_t s_w[BLOCK / 64], s_part[4];
   const uint32_t w = blockIdx.y;
-  const uint32_t j = blockIdx.x * QBLOCK + threadIdx.x;
+  const uint32_t j = blockIdx.x * BLOCK + threadIdx.x;
+  // survivors before this block: the sum of the earlier blocks' counts
+  const uint32_t before = c.QB > MAX_QB_INLINE
+                              ? c.blk_pre[static_cast<uint64_t>(w) * (c.QB + 1) + blockIdx.x]
+                              : block_sum_u32(c.blk_cnt + static_cast<uint64_t>(w) * c.QB, blockIdx.x, s_part);
   uint32_t code = 0;
   const uint64_t slot = static_cast<uint64_t>(w) * c.K + j;
   if (j < c.K) code = c.sel_code[slot];
@@ -727,7 +771,7 @@ __global__ __launch_bounds__(QBLOCK) void k_surv_compact(DevCtx c) {
   const uint64_t bal = __ballot(sent);
   if (lane_id() == 0) s_w[threadIdx.x >> 6] = __popcll(bal);
   __syncthreads();
-  uint32_t pos = c.blk_cnt[static_cast<uint64_t>(w) * c.QB + blockIdx.x] + popc_below(bal);
+  uint32_t pos = before + popc_below(bal);
   for (uint32_t i = 0; i < (threadIdx.x >> 6); ++i) pos += s_w[i];
   if (sent) {
     const uint32_t level = code & 0x7FFFFFFFu, neg = code >> 31;
@@ -750,10 +794,22 @@ __device__ __forceinline__ uint32_t gather_word(const uint32_t* arr, uint64_t n,
 }
 
 __global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t* msg_bits) {
+  __shared__ uint32_t s_part[4];
   const uint32_t w = blockIdx.y;
+  // this is the last kernel of a call: it also returns the shared scratch of this worker to all-zero
+  {
+    const uint64_t tid = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x, nth = static_cast<uint64_t>(gridDim.x) * BLOCK;
+    uint32_t* h = c.hist + static_cast<uint64_t>(w) * c.L * 3 * HBINS;
+    for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * 3 * HBINS; i += nth) h[i] = 0;
+    uint32_t* sc = c.sub_cnt + static_cast<uint64_t>(w) * c.L * NSUB;
+    for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * NSUB; i += nth) sc[i] = 0;
+    uint64_t* na = c.norm_acc + static_cast<uint64_t>(w) * c.L * ACC_SLOTS;
+    for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * ACC_SLOTS; i += nth) na[i] = 0;
+  }
+  const uint64_t nnz = c.QB > MAX_QB_INLINE ? c.blk_pre[static_cast<uint64_t>(w) * (c.QB + 1) + c.QB]
+                                            : block_sum_u32(c.blk_cnt + static_cast<uint64_t>(w) * c.QB, c.QB, s_part);
   const uint64_t q = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x;
   if (q >= c.cap_words) return;
-  const uint64_t nnz = c.nnz_total[w];
   const bool counts = c.quantizer == QSL_QSGD && c.L > 1;
   const uint64_t hdr = 1 + static_cast<uint64_t>(c.L) + (counts ? c.L : 0);
   const uint64_t idx_words = (nnz * c.w_idx + 31) / 32, code_words = (nnz * c.w_val + 31) / 32;
@@ -842,27 +898,47 @@ __global__ __launch_bounds__(BLOCK) void k_fill_zero(float* out, uint64_t n) {
 }
 
 struct RowList { uint32_t row[64]; };
+constexpr uint32_t AGG_ENTRIES = 32;     // message entries per block; 8 threads look one entry up in parallel
 
-// Thread (q, j) owns entry j of the q-th listed message.  It writes out[idx] only if no earlier
-// listed message holds idx; it then adds the later messages' values in list order: no atomics,
-// one writer per coordinate, a fixed summation order.
+// Entry j of the q-th listed message is served by 8 threads, which look its coordinate up in the
+// other listed messages (binary search on the packed, ascending indices).  The coordinate is
+// written by the earliest listed message that holds it -- one writer per coordinate, no atomics --
+// and the values are added in list order, so the result does not depend on the schedule.
 __global__ __launch_bounds__(BLOCK) void k_aggregate(DevCtx c, const uint8_t* msg, RowList rows, uint32_t R,
                                                      float scale, int accumulate, float* out) {
+  __shared__ float s_val[AGG_ENTRIES][65];
+  __shared__ unsigned long long s_has[AGG_ENTRIES];
   const uint32_t q = blockIdx.y;
+  const uint32_t e = threadIdx.x >> 3, sub = threadIdx.x & 7u;
   const MsgView mine = view_msg(c, msg, rows.row[q]);
-  const uint32_t j = blockIdx.x * BLOCK + threadIdx.x;
-  if (j >= mine.nnz) return;
-  const uint32_t idx = msg_index(c, mine, j);
-  if (idx >= c.d) { atomicOr(c.status, 4u); return; }   // malformed message
-  for (uint32_t p = 0; p < q; ++p) {
-    const MsgView other = view_msg(c, msg, rows.row[p]);
-    if (msg_find(c, other, idx) >= 0) return;
+  const uint32_t j = blockIdx.x * AGG_ENTRIES + e;
+  if (sub == 0) s_has[e] = 0;
+  __syncthreads();
+  uint32_t idx = 0xFFFFFFFFu;
+  if (j < mine.nnz) {
+    idx = msg_index(c, mine, j);
+    if (idx >= c.d) { if (sub == 0) atomicOr(c.status, 4u); idx = 0xFFFFFFFFu; }   // malformed message
   }
-  float acc = msg_value(c, mine, j, idx);
-  for (uint32_t p = q + 1; p < R; ++p) {
-    const MsgView other = view_msg(c, msg, rows.row[p]);
-    const int64_t pos = msg_find(c, other, idx);
-    if (pos >= 0) acc = acc + msg_value(c, other, static_cast<uint32_t>(pos), idx);
+  if (idx != 0xFFFFFFFFu) {
+    unsigned long long has = 0;
+    for (uint32_t p = sub; p < R; p += 8) {
+      if (p == q) { s_val[e][p] = msg_value(c, mine, j, idx); has |= 1ull << p; continue; }
+      const MsgView other = view_msg(c, msg, rows.row[p]);
+      const int64_t pos = msg_find(c, other, idx);
+      if (pos >= 0) { s_val[e][p] = msg_value(c, other, static_cast<uint32_t>(pos), idx); has |= 1ull << p; }
+    }
+    if (has) atomicOr(&s_has[e], has);
+  }
+  __syncthreads();
+  if (sub != 0 || idx == 0xFFFFFFFFu) return;
+  const unsigned long long has = s_has[e];
+  if (has & ((1ull << q) - 1ull)) return;               // an earlier listed message owns this coordinate
+  float acc = 0.0f;
+  bool first = true;
+  for (uint32_t p = q; p < R; ++p) {
+    if (!((has >> p) & 1ull)) continue;
+    acc = first ? s_val[e][p] : acc + s_val[e][p];
+    first = false;
   }
   const float term = scale * acc;
   out[idx] = accumulate ? out[idx] + term : term;
@@ -887,17 +963,17 @@ struct qsl_ctx {
   std::vector<SegInfo> segs;
   hipStream_t stream;
   DevCtx dc;
+  StreamSeg one;
   void* slab;                 // one allocation holding every scratch array
   uint32_t Rmax;
   uint32_t last_R;
+  uint32_t n_sampled;         // units per worker that k_sample initialises
   size_t capacity;
   uint32_t* h_status;         // pinned
   uint32_t* d_nnz_tmp;
   int timing;
   std::vector<hipEvent_t> ev;
   size_t ev_used;
-  double ev_ms;
-  uint32_t ev_launches;
 };
 
 #define QSL_HIP(call)                              \
@@ -947,7 +1023,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->stream = static_cast<hipStream_t>(hip_stream);
   ctx->Rmax = cfg->max_workers;
   ctx->last_R = 0;
-  ctx->timing = 0; ctx->ev_used = 0; ctx->ev_ms = 0; ctx->ev_launches = 0;
+  ctx->timing = 0; ctx->ev_used = 0;
   ctx->slab = nullptr; ctx->h_status = nullptr;
 
   const uint32_t K = static_cast<uint32_t>(K64);
@@ -963,25 +1039,40 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   // per-segment plan: single-pass guessing ("fast") where the unit is large and sparse enough
   std::vector<SegInfo>& segs = ctx->segs;
   segs.resize(L);
-  std::vector<TileInfo> tiles;
+  std::vector<WtInfo> wts;
+  std::vector<GrpInfo> grps;
+  std::vector<SelInfo> sels;
   std::vector<NormTile> ntiles;
   std::vector<uint32_t> fast;
   uint64_t pool_entries = 0;
   uint32_t koff = 0;
-  bool has_general = false;
+  uint64_t nwt64 = 0;
+  ctx->n_sampled = 0;
   for (uint32_t l = 0; l < L; ++l) {
     SegInfo& sg = segs[l];
     memset(&sg, 0, sizeof sg);
     sg.start = ctx->off[l]; sg.size = ctx->off[l + 1] - ctx->off[l];
     sg.k = ctx->k[l]; sg.koff = koff; koff += sg.k;
-    sg.tile_base = static_cast<uint32_t>(tiles.size());
     const uint64_t nchunks = (sg.size + CHUNK - 1) / CHUNK;
-    sg.ntiles = static_cast<uint32_t>((nchunks + CHUNKS_PER_TILE - 1) / CHUNKS_PER_TILE);
-    for (uint32_t t = 0; t < sg.ntiles; ++t) {
-      TileInfo ti; ti.seg = l; ti.first_chunk = t * CHUNKS_PER_TILE;
-      ti.nchunks = static_cast<uint32_t>(std::min<uint64_t>(CHUNKS_PER_TILE, nchunks - ti.first_chunk)); ti.pad = 0;
-      tiles.push_back(ti);
+    sg.wt_base = static_cast<uint32_t>(nwt64);
+    sg.nwt = static_cast<uint32_t>((nchunks + WT_CHUNKS - 1) / WT_CHUNKS);
+    nwt64 += sg.nwt;
+    if (L > 1) {
+      for (uint32_t t = 0; t < sg.nwt; ++t) {
+        WtInfo wi; wi.seg = l; wi.first_chunk = t * WT_CHUNKS;
+        wi.nchunks = static_cast<uint32_t>(std::min<uint64_t>(WT_CHUNKS, nchunks - wi.first_chunk)); wi.pad = 0;
+        wts.push_back(wi);
+      }
     }
+    sg.grp_base = static_cast<uint32_t>(grps.size());
+    sg.ngrp = (sg.nwt + GROUP - 1) / GROUP;
+    for (uint32_t g = 0; g < sg.ngrp; ++g) {
+      GrpInfo gi; gi.seg = l; gi.first_wt = g * GROUP; gi.nwt = std::min(GROUP, sg.nwt - gi.first_wt); gi.pad = 0;
+      grps.push_back(gi);
+    }
+    sg.nsel = std::min(SELECT_BLOCKS, sg.nwt);
+    for (uint32_t j = 0; j < sg.nsel; ++j) { SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0; sels.push_back(si); }
+    sg.nnorm = (sg.k + NORM_TILE - 1) / NORM_TILE;
     for (uint32_t f = 0; f < sg.k; f += NORM_TILE) {
       NormTile nt; nt.seg = l; nt.first = f; nt.count = std::min(NORM_TILE, sg.k - f); nt.pad = 0;
       ntiles.push_back(nt);
@@ -999,8 +1090,9 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
           if (n_s > n / 16) continue;
           sg.n_runs = static_cast<uint32_t>(std::ceil(n_s / 64.0));
           sg.r_s = static_cast<uint32_t>(std::ceil(alpha * (sg.n_runs * 64.0) * p));
-          sg.pool_cap = static_cast<uint32_t>(std::min<double>(n, 4.0 * alpha * sg.k + 8192.0));
+          sg.sub_cap = static_cast<uint32_t>(std::ceil((4.0 * alpha * sg.k + 8192.0) / NSUB));
           sg.mode = PATH_FAST;
+          ++ctx->n_sampled;
           break;
         }
       } else if (cfg->sparsifier == QSL_RANDK && static_cast<uint64_t>(sg.k) * 16 <= sg.size) {
@@ -1008,70 +1100,94 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
         const double q = p + 7.0 * std::sqrt(p * (1 - p) / n);
         if (q < 0.25) {
           sg.T_static = static_cast<uint32_t>(std::floor(4294967296.0 * (1.0 - q)));
-          sg.pool_cap = static_cast<uint32_t>(std::min<double>(n, q * n + 8.0 * std::sqrt(q * n) + 1024.0));
+          // a sub-pool sees 1/64 of the wave-tiles: its own count has mean qn/64 and sigma sqrt(qn/64)
+          sg.sub_cap = static_cast<uint32_t>(std::ceil(q * n / NSUB + 8.0 * std::sqrt(q * n / NSUB) + 64.0));
           sg.mode = PATH_FAST;
         }
       }
     }
-    if (sg.mode == PATH_FAST) { fast.push_back(l); sg.pool_off = pool_entries; pool_entries += sg.pool_cap; }
-    else has_general = true;
+    if (sg.mode == PATH_FAST) {
+      sg.pool_cap = sg.sub_cap * NSUB;
+      fast.push_back(l); sg.pool_off = pool_entries; pool_entries += sg.pool_cap;
+    }
   }
-  const uint32_t NT = static_cast<uint32_t>(tiles.size()), NNT = static_cast<uint32_t>(ntiles.size());
-  const uint32_t QB = (K + QBLOCK - 1) / QBLOCK;
+  const uint32_t NWT = static_cast<uint32_t>(nwt64);
+  const uint32_t NGRP = static_cast<uint32_t>(grps.size()), NSEL = static_cast<uint32_t>(sels.size());
+  const uint32_t NNT = static_cast<uint32_t>(ntiles.size());
+  const uint32_t QB = (K + BLOCK - 1) / BLOCK;
   const uint64_t R = ctx->Rmax, U = R * L;
 
-  // one slab, carved
+  // one slab, carved; the part that must be zero between kernels comes first
   uint64_t bytes = 0;
   auto carve = [&](uint64_t n) { const uint64_t o = bytes; bytes = align_up(bytes + n, 256); return o; };
-  const uint64_t o_segs = carve(sizeof(SegInfo) * L), o_tiles = carve(sizeof(TileInfo) * NT);
-  const uint64_t o_nt = carve(sizeof(NormTile) * std::max(1u, NNT)), o_fast = carve(4ull * std::max<size_t>(1, fast.size()));
+  const uint64_t o_hist = carve(4ull * 3 * HBINS * U), o_sub = carve(4ull * NSUB * U);
+  const uint64_t o_acc = carve(8ull * ACC_SLOTS * U), o_status = carve(8);
+  const uint64_t zero_bytes = bytes;
+  const uint64_t o_segs = carve(sizeof(SegInfo) * L), o_wts = carve(sizeof(WtInfo) * std::max<size_t>(1, wts.size()));
+  const uint64_t o_grps = carve(sizeof(GrpInfo) * NGRP), o_sels = carve(sizeof(SelInfo) * NSEL);
+  const uint64_t o_nt = carve(sizeof(NormTile) * NNT), o_fast = carve(4ull * std::max<size_t>(1, fast.size()));
   const uint64_t o_units = carve(sizeof(UnitState) * U);
   const uint64_t o_pool = carve(8ull * std::max<uint64_t>(1, pool_entries) * R);
-  const uint64_t o_rec = carve(8ull * NT * R), o_cnt = carve(8ull * NT * R);
-  const uint64_t o_hist = carve(4ull * HBINS * U), o_acc = carve(8ull * ACC_SLOTS * U);
+  const uint64_t o_rec = carve(8ull * NWT * R), o_cnt = carve(8ull * NWT * R), o_gcnt = carve(8ull * NGRP * R);
   const uint64_t o_si = carve(4ull * K * R), o_sv = carve(4ull * K * R), o_sc = carve(4ull * K * R);
-  const uint64_t o_blk = carve(4ull * QB * R), o_nnz = carve(4ull * R);
+  const uint64_t o_blk = carve(4ull * QB * R), o_pre = carve(4ull * (QB + 1) * R);
   const uint64_t o_vi = carve(4ull * K * R), o_vc = carve(4ull * K * R);
-  const uint64_t o_status = carve(8), o_tmp = carve(4ull * 1024);
+  const uint64_t o_tmp = carve(4ull * 1024);
   if (hipMalloc(&ctx->slab, bytes) != hipSuccess) { delete ctx; return QSL_ERR_DEVICE; }
   char* base = static_cast<char*>(ctx->slab);
-  bool ok = hipMemset(base + o_status, 0, 8) == hipSuccess;
-  ok = ok && hipMemcpy(base + o_segs, segs.data(), sizeof(SegInfo) * L, hipMemcpyHostToDevice) == hipSuccess;
-  ok = ok && hipMemcpy(base + o_tiles, tiles.data(), sizeof(TileInfo) * NT, hipMemcpyHostToDevice) == hipSuccess;
-  if (NNT) ok = ok && hipMemcpy(base + o_nt, ntiles.data(), sizeof(NormTile) * NNT, hipMemcpyHostToDevice) == hipSuccess;
-  if (!fast.empty()) ok = ok && hipMemcpy(base + o_fast, fast.data(), 4 * fast.size(), hipMemcpyHostToDevice) == hipSuccess;
+  bool ok = hipMemset(base, 0, zero_bytes) == hipSuccess;
+  auto upload = [&](uint64_t o, const void* src, size_t n) {
+    if (n) ok = ok && hipMemcpy(base + o, src, n, hipMemcpyHostToDevice) == hipSuccess;
+  };
+  upload(o_segs, segs.data(), sizeof(SegInfo) * L);
+  upload(o_wts, wts.data(), sizeof(WtInfo) * wts.size());
+  upload(o_grps, grps.data(), sizeof(GrpInfo) * NGRP);
+  upload(o_sels, sels.data(), sizeof(SelInfo) * NSEL);
+  upload(o_nt, ntiles.data(), sizeof(NormTile) * NNT);
+  upload(o_fast, fast.data(), 4 * fast.size());
   ok = ok && hipHostMalloc(reinterpret_cast<void**>(&ctx->h_status), 64, hipHostMallocDefault) == hipSuccess;
-  if (!ok) { hipFree(ctx->slab); delete ctx; return QSL_ERR_DEVICE; }
+  ok = ok && hipDeviceSynchronize() == hipSuccess;
+  if (!ok) { (void)hipFree(ctx->slab); delete ctx; return QSL_ERR_DEVICE; }
 
   DevCtx& c = ctx->dc;
   c.segs = reinterpret_cast<const SegInfo*>(base + o_segs);
-  c.tiles = reinterpret_cast<const TileInfo*>(base + o_tiles);
+  c.wts = reinterpret_cast<const WtInfo*>(base + o_wts);
+  c.grps = reinterpret_cast<const GrpInfo*>(base + o_grps);
+  c.sels = reinterpret_cast<const SelInfo*>(base + o_sels);
   c.ntiles = reinterpret_cast<const NormTile*>(base + o_nt);
   c.fast_segs = reinterpret_cast<const uint32_t*>(base + o_fast);
   c.units = reinterpret_cast<UnitState*>(base + o_units);
   c.pool = reinterpret_cast<uint2*>(base + o_pool); c.pool_stride = std::max<uint64_t>(1, pool_entries);
-  c.tile_rec = reinterpret_cast<uint2*>(base + o_rec); c.tile_cnt = reinterpret_cast<uint2*>(base + o_cnt);
-  c.hist = reinterpret_cast<uint32_t*>(base + o_hist); c.norm_acc = reinterpret_cast<uint64_t*>(base + o_acc);
+  c.wt_rec = reinterpret_cast<uint2*>(base + o_rec); c.wt_cnt = reinterpret_cast<uint2*>(base + o_cnt);
+  c.grp_cnt = reinterpret_cast<uint2*>(base + o_gcnt);
+  c.hist = reinterpret_cast<uint32_t*>(base + o_hist); c.sub_cnt = reinterpret_cast<uint32_t*>(base + o_sub);
+  c.norm_acc = reinterpret_cast<uint64_t*>(base + o_acc);
   c.sel_idx = reinterpret_cast<uint32_t*>(base + o_si); c.sel_val = reinterpret_cast<uint32_t*>(base + o_sv);
   c.sel_code = reinterpret_cast<uint32_t*>(base + o_sc);
-  c.blk_cnt = reinterpret_cast<uint32_t*>(base + o_blk); c.nnz_total = reinterpret_cast<uint32_t*>(base + o_nnz);
+  c.blk_cnt = reinterpret_cast<uint32_t*>(base + o_blk); c.blk_pre = reinterpret_cast<uint32_t*>(base + o_pre);
   c.surv_idx = reinterpret_cast<uint32_t*>(base + o_vi); c.surv_code = reinterpret_cast<uint32_t*>(base + o_vc);
-  c.status = reinterpret_cast<uint32_t*>(base + o_status); c.any_fallback = c.status + 1;
+  c.status = reinterpret_cast<uint32_t*>(base + o_status);
   ctx->d_nnz_tmp = reinterpret_cast<uint32_t*>(base + o_tmp);
-  c.d = d; c.seed = cfg->seed; c.L = L; c.K = K; c.NT = NT; c.NNT = NNT; c.QB = QB;
+  c.d = d; c.seed = cfg->seed; c.L = L; c.K = K; c.NWT = NWT; c.NGRP = NGRP; c.NSEL = NSEL; c.NNT = NNT; c.QB = QB;
   c.nfast = static_cast<uint32_t>(fast.size()); c.s = s; c.w_idx = w_idx; c.w_lev = w_lev; c.w_val = w_val;
-  c.sparsifier = cfg->sparsifier; c.quantizer = cfg->quantizer; c.has_general = has_general ? 1 : 0;
+  c.sparsifier = cfg->sparsifier; c.quantizer = cfg->quantizer;
   c.cap_words = static_cast<uint32_t>(ctx->capacity / 4);
+  ctx->one.start = 0; ctx->one.size = segs[0].size; ctx->one.pool_off = 0; ctx->one.sub_cap = segs[0].sub_cap;
+  ctx->one.wt_base = 0;
+  k_init<<<dim3(static_cast<uint32_t>((U + 255) / 256)), 256, 0, ctx->stream>>>(c, static_cast<uint32_t>(U));
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) {
+    (void)hipFree(ctx->slab); (void)hipHostFree(ctx->h_status); delete ctx; return QSL_ERR_DEVICE;
+  }
   *out = ctx;
   return QSL_OK;
 }
 
 extern "C" qsl_status qsl_destroy(qsl_ctx* ctx) {
   if (!ctx) return QSL_ERR_INVALID_ARG;
-  hipStreamSynchronize(ctx->stream);
-  for (hipEvent_t e : ctx->ev) hipEventDestroy(e);
-  if (ctx->slab) hipFree(ctx->slab);
-  if (ctx->h_status) hipHostFree(ctx->h_status);
+  (void)hipStreamSynchronize(ctx->stream);
+  for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+  if (ctx->slab) (void)hipFree(ctx->slab);
+  if (ctx->h_status) (void)hipHostFree(ctx->h_status);
   delete ctx;
   return QSL_OK;
 }
@@ -1090,11 +1206,9 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
                                   uint16_t* sel_level) {
   const DevCtx& c = ctx->dc;
   hipStream_t st = ctx->stream;
-  const uint32_t U = R * c.L;
-  k_init<<<dim3(static_cast<uint32_t>(std::min<uint64_t>(1024, (static_cast<uint64_t>(U) * HBINS + 255) / 256))), 256, 0, st>>>(c, R);
-  if (SPARS == QSL_TOPK && c.nfast) {
-    k_sample<<<dim3(SAMPLE_BLOCKS, c.nfast, R), BLOCK, 0, st>>>(c, m, delta);
-    k_sample_scan<<<dim3(c.nfast, R), 1024, 0, st>>>(c);
+  if (SPARS == QSL_TOPK && ctx->n_sampled > 0) {
+    k_sample<<<dim3(SAMPLE_BLOCKS, c.nfast, R), 1024, 0, st>>>(c, m, delta);
+    k_sample_scan<<<dim3(c.nfast, R), BLOCK, 0, st>>>(c);
   }
   const bool timed = ctx->timing != 0;
   if (timed) {
@@ -1103,33 +1217,20 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
     }
     QSL_HIP(hipEventRecord(ctx->ev[ctx->ev_used], st));
   }
-  k_stream<SPARS><<<dim3(c.NT, R), BLOCK, 0, st>>>(c, m, delta, m_out, worker0, round);
+  const dim3 sgrid((c.NWT + 3) / 4, R);
+  if (c.L == 1) k_stream<SPARS, true><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, m_out, worker0, round);
+  else k_stream<SPARS, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, m_out, worker0, round);
   if (timed) { QSL_HIP(hipEventRecord(ctx->ev[ctx->ev_used + 1], st)); ctx->ev_used += 2; }
 
-  const dim3 ugrid(c.L, R);
-  const dim3 vgrid(std::min<uint32_t>(c.NT, 1024), R);
-  if (c.nfast) {
-    k_validate<<<dim3((U + 255) / 256), 256, 0, st>>>(c, U);
-    k_pool_hist<0, SPARS><<<dim3(POOL_HIST_BLOCKS, c.nfast, R), BLOCK, 0, st>>>(c, worker0, round);
-  }
-  k_v_hist<0, SPARS><<<vgrid, BLOCK, 0, st>>>(c, m_out, worker0, round);
-  k_hist_scan<0><<<ugrid, 1024, 0, st>>>(c);
-  if (c.nfast) k_pool_hist<1, SPARS><<<dim3(POOL_HIST_BLOCKS, c.nfast, R), BLOCK, 0, st>>>(c, worker0, round);
-  k_v_hist<1, SPARS><<<vgrid, BLOCK, 0, st>>>(c, m_out, worker0, round);
-  k_hist_scan<1><<<ugrid, 1024, 0, st>>>(c);
-  if (c.nfast) k_pool_hist<2, SPARS><<<dim3(POOL_HIST_BLOCKS, c.nfast, R), BLOCK, 0, st>>>(c, worker0, round);
-  k_v_hist<2, SPARS><<<vgrid, BLOCK, 0, st>>>(c, m_out, worker0, round);
-  k_hist_scan<2><<<ugrid, 1024, 0, st>>>(c);
-
-  k_tile_count<SPARS><<<dim3(c.NT, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
-  k_tile_scan<<<ugrid, 1024, 0, st>>>(c);
-  k_tile_write<SPARS><<<dim3(c.NT, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
-
+  k_select<0, SPARS><<<dim3(c.NSEL, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
+  k_select<1, SPARS><<<dim3(c.NSEL, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
+  k_select<2, SPARS><<<dim3(c.NSEL, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
+  k_tile_count<SPARS><<<dim3(c.NGRP, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
+  k_tile_write<SPARS><<<dim3(c.NGRP, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
   k_norm<<<dim3(c.NNT, R), BLOCK, 0, st>>>(c);
-  k_norm_finalize<<<dim3((U + 63) / 64), 64, 0, st>>>(c, U);
-  k_quantize<<<dim3(c.QB, R), QBLOCK, 0, st>>>(c, m_out, worker0, round, sel_idx, sel_level);
-  k_surv_scan<<<dim3(R), 1024, 0, st>>>(c);
-  k_surv_compact<<<dim3(c.QB, R), QBLOCK, 0, st>>>(c);
+  k_quantize<<<dim3(c.QB, R), BLOCK, 0, st>>>(c, m_out, worker0, round, sel_idx, sel_level);
+  if (c.QB > MAX_QB_INLINE) k_surv_scan<<<dim3(R), 1024, 0, st>>>(c);
+  k_surv_compact<<<dim3(c.QB, R), BLOCK, 0, st>>>(c);
   k_pack<<<dim3((c.cap_words + BLOCK - 1) / BLOCK, R), BLOCK, 0, st>>>(c, msg, msg_bits);
   QSL_HIP(hipGetLastError());
   return QSL_OK;
@@ -1177,7 +1278,8 @@ extern "C" qsl_status qsl_aggregate(qsl_ctx* ctx, const uint8_t* msg, const uint
     const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((c.d + BLOCK * 4 - 1) / (BLOCK * 4), 1u << 16));
     k_fill_zero<<<dim3(blocks), BLOCK, 0, ctx->stream>>>(out, c.d);
   }
-  k_aggregate<<<dim3((c.K + BLOCK - 1) / BLOCK, R), BLOCK, 0, ctx->stream>>>(c, msg, rows, R, scale, accumulate, out);
+  k_aggregate<<<dim3((c.K + AGG_ENTRIES - 1) / AGG_ENTRIES, R), BLOCK, 0, ctx->stream>>>(c, msg, rows, R, scale,
+                                                                                        accumulate, out);
   QSL_HIP(hipGetLastError());
   return QSL_OK;
 }
@@ -1214,7 +1316,8 @@ extern "C" qsl_status qsl_debug_units(qsl_ctx* ctx, uint32_t* out_host, uint32_t
   QSL_HIP(hipStreamSynchronize(ctx->stream));
   for (uint32_t u = 0; u < U; ++u) {
     uint32_t* o = out_host + 8ull * u;
-    o[0] = us[u].path; o[1] = us[u].cand; o[2] = us[u].tau; o[3] = us[u].n_gt; o[4] = us[u].need; o[5] = us[u].T;
+    o[0] = us[u].path == PATH_FAST && us[u].fell_back ? static_cast<uint32_t>(PATH_FALLBACK) : us[u].path;
+    o[1] = us[u].cand; o[2] = us[u].tau; o[3] = us[u].n_gt; o[4] = us[u].need; o[5] = us[u].T;
     o[6] = us[u].scale_bits; o[7] = us[u].nnz;
   }
   *n_units = U;
@@ -1223,7 +1326,7 @@ extern "C" qsl_status qsl_debug_units(qsl_ctx* ctx, uint32_t* out_host, uint32_t
 
 extern "C" qsl_status qsl_timing_enable(qsl_ctx* ctx, int enabled) {
   if (!ctx) return QSL_ERR_INVALID_ARG;
-  ctx->timing = enabled; ctx->ev_used = 0; ctx->ev_ms = 0; ctx->ev_launches = 0;
+  ctx->timing = enabled; ctx->ev_used = 0;
   return QSL_OK;
 }
 
