@@ -4,13 +4,14 @@
 //   k_sample     the guess (Top_k only): a quantile of a strided sample of |m + Delta|; for Rand_k
 //                the rank keys are uniform random words, so the guess is analytic
 //   k_stream     v = m + Delta (worker line 1), written over the error memory in ONE pass over HBM;
-//                coordinates whose rank key reaches the unit's guess are appended, in coordinate
-//                order, to a small candidate pool (one atomic per wave, no LDS, no block barrier)
+//                each wave streams one chunk of 1024 coordinates and leaves the coordinates whose
+//                rank key reaches the unit's guess in the chunk's own slot line (written as one
+//                full 128-byte line: no read-modify-write in HBM, no atomic to wait for)
 //   k_select<l>  exact radix selection of the k-th largest key (Section 2.2: Top_k / Rand_k), 12+12+8
 //                bits, over the candidates -- or over the whole vector when the guess failed or the
 //                unit is too small/dense for guessing (the general path; always exact)
 //   k_tile_count / k_tile_write    ordered compaction of the selected coordinates, ties to the lower index
-//   k_norm       exact ||v_S||_2^2 or ||v_S||_1 (proof of Lemma 1; Lemma 3 with m = 1) -> fp32 scale
+//   k_norm       exact ||v_S||_2^2 or ||v_S||_1 (proof of Lemma 1; Lemma 3 with m = 1)
 //   k_quantize   QSGD levels (Definition 1, example 1) or signs (Definition 2); error update
 //                m <- v - g on the transmitted coordinates (Algorithm 1, worker line 2)
 //   k_surv_compact, k_pack    the packed message
@@ -24,8 +25,7 @@
 // XCD, so a device-scope release costs a cache write-back): a value that needs all blocks of a
 // unit -- the radix digit, a prefix of block counts, the fp32 scale -- is recomputed by every block
 // of the NEXT kernel from the small per-block results the previous one left in memory.  Counters
-// that many waves add to (candidate pool, histograms) are split so that few atomics share an
-// address: same-address atomics serialise at ~0.1 us each.
+// that many waves add to sit in cache lines of their own: atomics that share a line serialise.
 //
 // Arithmetic contract: every fp32 operation that decides an output is a single IEEE operation
 // (compile with -ffp-contract=off, no fast-math); norms are the exact sum rounded once to double.
@@ -46,30 +46,34 @@ using namespace qsl;
 
 namespace {
 
-constexpr uint32_t CHUNK = 1024;           // coordinates a wave handles at a time: 4 x (64 lanes x 4)
-constexpr uint32_t WT_CHUNKS = 4;          // a wave-tile: the contiguous chunks one wave streams
-constexpr uint32_t WTILE = CHUNK * WT_CHUNKS;
-constexpr uint32_t GROUP = 64;             // wave-tiles per block of the ordered-compaction kernels
+constexpr uint32_t CHUNK = 1024;           // coordinates one wave streams: 4 x (64 lanes x 4)
+constexpr uint32_t GROUP = 256;            // chunks per block of the ordered-compaction kernels
 constexpr uint32_t BLOCK = 256;
 constexpr uint32_t HBINS = 4096;           // radix digits: 12 + 12 + 8 bits of the 32-bit rank key
 constexpr uint32_t ACC_SLOTS = 20;         // 32-bit digits of the exact accumulator
 constexpr uint32_t NORM_TILE = 2048;
 constexpr uint32_t SAMPLE_BLOCKS = 16;     // blocks (of 1024 threads) per unit of the sampling kernel
-constexpr uint32_t SELECT_BLOCKS = 16;     // blocks per unit of the selection kernels
-constexpr uint32_t NSUB = 64;              // sub-pools per unit: wave-tile t appends to sub-pool t mod 64
+constexpr uint32_t SELECT_BLOCKS = 16;     // blocks (of 1024 threads) per unit of the selection kernels
+constexpr uint32_t BIG = 1024;             // threads of the sampling and selection kernels
 constexpr uint32_t MAX_QB_INLINE = 4096;   // above this many quantise blocks a separate prefix kernel runs
+constexpr uint32_t NSUB = 64;              // candidate counters per unit: chunk t adds to counter t mod 64
+constexpr uint32_t PAD = 64;               // words between two counters: atomics that share a cache line serialise
+constexpr uint32_t CTR_OVF = NSUB;         // counter NSUB: cursor of the unit's overflow pool
+constexpr uint32_t CTR_FAIL = NSUB + 1;    // counter NSUB + 1: set when the overflow pool ran out
+constexpr uint32_t CTR_LINES = NSUB + 2;
 
 enum : uint32_t { PATH_FAST = 0, PATH_GENERAL = 1, PATH_FALLBACK = 2 };
 
 struct SegInfo {
   uint64_t start, size;
-  uint64_t pool_off;     // first pool entry of this segment inside one worker's pool
+  uint64_t slot_off;     // first slot element (uint2) of this segment inside one worker's slot area
+  uint64_t ovf_off;      // first entry of this segment inside one worker's overflow pool
   uint32_t k, koff;      // koff: first slot in the [K] selected arrays
-  uint32_t wt_base, nwt; // wave-tiles: index of the first one in per-worker arrays, how many
+  uint32_t wt_base, nwt; // chunks: index of the first one in per-worker arrays, how many
   uint32_t grp_base, ngrp;
   uint32_t mode;         // PATH_FAST or PATH_GENERAL, decided on the host from (size, k)
-  uint32_t pool_cap;     // NSUB * sub_cap
-  uint32_t sub_cap;      // entries per sub-pool
+  uint32_t lpc;          // slot size: lpc * 16 bytes per chunk (8: one 128-byte line, 16: two lines)
+  uint32_t ovf_cap;      // entries of the overflow pool
   uint32_t n_runs;       // sample: runs of 64 consecutive coordinates
   uint32_t r_s;          // sample rank that defines the guess
   uint32_t T_static;     // Rand_k: analytic guess
@@ -77,8 +81,8 @@ struct SegInfo {
   uint32_t nnorm;        // norm tiles
 };
 
-struct WtInfo { uint32_t seg, first_chunk, nchunks, pad; };        // one wave-tile
-struct GrpInfo { uint32_t seg, first_wt, nwt, pad; };               // one group of wave-tiles (inside a unit)
+struct WtInfo { uint32_t seg, chunk, pad0, pad1; };                 // one chunk (multi-segment contexts only)
+struct GrpInfo { uint32_t seg, first_wt, nwt, pad; };               // one group of chunks (inside a unit)
 struct SelInfo { uint32_t seg, j, pad0, pad1; };                    // one block of a selection kernel
 struct NormTile { uint32_t seg, first, count, pad; };
 
@@ -99,12 +103,12 @@ struct DevCtx {
   const SegInfo* segs; const WtInfo* wts; const GrpInfo* grps; const SelInfo* sels; const NormTile* ntiles;
   const uint32_t* fast_segs;
   UnitState* units;
-  uint2* pool; uint64_t pool_stride;
-  uint2* wt_rec;        // [R][NWT]: (offset in the unit's pool, count) of the wave-tile's candidates
-  uint2* wt_cnt;        // [R][NWT]: (#key > tau, #key == tau) of the wave-tile
-  uint2* grp_cnt;       // [R][NGRP]: the same per group, then its exclusive prefix inside the unit
+  uint2* slots; uint64_t slot_stride;   // per worker: one slot (lpc * 2 elements) per chunk of every fast segment
+  uint2* ovf; uint64_t ovf_stride;      // per worker: overflow pools, for chunks with more candidates than a slot holds
+  uint2* wt_cnt;        // [R][NWT]: (#key > tau, #key == tau) of the chunk
+  uint2* grp_cnt;       // [R][NGRP]: the same per group of chunks
   uint32_t* hist;       // [U][3][HBINS], one histogram per radix digit; all zero between calls
-  uint32_t* sub_cnt;    // [U][NSUB] entries appended to each sub-pool; all zero between calls
+  uint32_t* ctr;        // [U][CTR_LINES][PAD]; word 0 of each line is a counter; all zero between calls
   uint64_t* norm_acc;   // [U][ACC_SLOTS]; all zero between calls
   uint32_t* sel_idx; uint32_t* sel_val; uint32_t* sel_code;   // [R][K]; code = level | neg << 31
   uint32_t* blk_cnt;    // [R][QB] survivors per quantise block
@@ -118,8 +122,8 @@ struct DevCtx {
 __device__ __forceinline__ uint32_t key_of_value(uint32_t vbits) { return (vbits & 0x7FFFFFFFu) << 1; }
 
 template <int SPARS>
-__device__ __forceinline__ uint32_t entry_key(uint2 e, const RandKey& rk) {
-  return SPARS == QSL_TOPK ? key_of_value(e.y) : rand_word(rk, e.x);
+__device__ __forceinline__ uint32_t entry_key(uint32_t idx, uint32_t bits, const RandKey& rk) {
+  return SPARS == QSL_TOPK ? key_of_value(bits) : rand_word(rk, idx);
 }
 
 // rank key of a coordinate in the general path: from v (already written to m_out) or its random word
@@ -128,31 +132,38 @@ __device__ __forceinline__ uint32_t coord_key(const float* vp, uint64_t e, uint6
   return SPARS == QSL_TOPK ? key_of_value(__float_as_uint(vp[e])) : rand_word(rk, static_cast<uint32_t>(start + e));
 }
 
+__device__ __forceinline__ uint32_t eff_path(const UnitState& us) {
+  return us.path == PATH_FAST && us.fell_back ? static_cast<uint32_t>(PATH_FALLBACK) : us.path;
+}
+
 // Find, scanning a 4096-bin histogram from its top, the bin in which the running count reaches
-// `target` (1-based).  256 threads, thread t owns the 16 bins below 4096 - 16 t.  Returns the bin;
-// *above = count in the bins above it.  If the histogram holds fewer than `target` entries,
-// returns bin 0 with *above = total - hist[0].  If `clear`, zeroes the histogram afterwards.
+// `target` (1-based).  NT threads (the whole block), thread t owns the 4096/NT bins below
+// 4096 - t * 4096/NT.  Returns the bin; *above = count in the bins above it.  If the histogram
+// holds fewer than `target` entries, returns bin 0 with *above = total - hist[0].  If `clear`,
+// zeroes the histogram afterwards.
+template <uint32_t NT>
 __device__ uint32_t find_from_top(uint32_t* hist, uint32_t target, uint32_t* above, uint64_t* scratch,
                                   uint32_t* result, bool clear) {
+  constexpr uint32_t PER = HBINS / NT;
   const uint32_t t = threadIdx.x;
-  uint32_t h[16]; uint32_t sum = 0;
+  uint32_t h[PER]; uint32_t sum = 0;
 #pragma unroll
-  for (int j = 0; j < 16; ++j) { h[j] = hist[HBINS - 1 - (16 * t + j)]; sum += h[j]; }
+  for (uint32_t j = 0; j < PER; ++j) { h[j] = hist[HBINS - 1 - (PER * t + j)]; sum += h[j]; }
   uint64_t total;
   const uint64_t before = block_exclusive_scan64(sum, scratch, &total);
-  if (t == BLOCK - 1) { result[0] = 0; result[1] = static_cast<uint32_t>(total) - h[15]; }
+  if (t == NT - 1) { result[0] = 0; result[1] = static_cast<uint32_t>(total) - h[PER - 1]; }
   __syncthreads();
   if (before < target && before + sum >= target) {
     uint32_t cum = static_cast<uint32_t>(before);
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-      if (cum + h[j] >= target) { result[0] = HBINS - 1 - (16 * t + j); result[1] = cum; break; }
+    for (uint32_t j = 0; j < PER; ++j) {
+      if (cum + h[j] >= target) { result[0] = HBINS - 1 - (PER * t + j); result[1] = cum; break; }
       cum += h[j];
     }
   }
   if (clear) {
 #pragma unroll
-    for (int j = 0; j < 16; ++j) if (h[j]) hist[HBINS - 1 - (16 * t + j)] = 0;
+    for (uint32_t j = 0; j < PER; ++j) if (h[j]) hist[HBINS - 1 - (PER * t + j)] = 0;
   }
   __syncthreads();
   *above = result[1];
@@ -164,10 +175,6 @@ __device__ __forceinline__ void flush_hist(const uint32_t* lh, uint32_t* gh) {
     const uint32_t v = lh[i];
     if (v) atomicAdd(&gh[i], v);
   }
-}
-
-__device__ __forceinline__ uint32_t eff_path(const UnitState& us) {
-  return us.path == PATH_FAST && us.fell_back ? static_cast<uint32_t>(PATH_FALLBACK) : us.path;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -187,22 +194,22 @@ __global__ void k_init(DevCtx c, uint32_t U) {
 // the guess for Top_k: histogram of the rank keys of a strided sample of v = m + Delta
 // (runs of 64 consecutive coordinates, evenly spaced), then the key at a fixed rank of the sample
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void k_sample(DevCtx c, const float* m, const float* delta) {
+__global__ __launch_bounds__(BIG) void k_sample(DevCtx c, const float* m, const float* delta) {
   __shared__ uint32_t lh[HBINS];
   const uint32_t seg = c.fast_segs[blockIdx.y], w = blockIdx.z;
   const SegInfo sg = c.segs[seg];
-  for (uint32_t i = threadIdx.x; i < HBINS; i += 1024) lh[i] = 0;
+  for (uint32_t i = threadIdx.x; i < HBINS; i += BIG) lh[i] = 0;
   __syncthreads();
   const uint64_t row = static_cast<uint64_t>(w) * c.d + sg.start;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const uint32_t nwaves = SAMPLE_BLOCKS * 16;
-  for (uint32_t run0 = blockIdx.x * 16 + wave; run0 < sg.n_runs; run0 += 4 * nwaves) {
+  const uint32_t nwaves = SAMPLE_BLOCKS * (BIG / 64);
+  const uint64_t stride = sg.size / sg.n_runs;           // >= 64: the runs do not overlap
+  for (uint32_t run0 = blockIdx.x * (BIG / 64) + wave; run0 < sg.n_runs; run0 += 4 * nwaves) {
     float a[4], b[4]; bool ok[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const uint32_t run = run0 + r * nwaves;
-      // run start: floor(run * size / n_runs); size < 2^32 and run < 2^32, so the product fits 64 bits
-      const uint64_t pos = static_cast<uint64_t>(run) * sg.size / sg.n_runs + lane;
+      const uint64_t pos = static_cast<uint64_t>(run) * stride + lane;
       ok[r] = run < sg.n_runs && pos < sg.size;
       a[r] = ok[r] ? m[row + pos] : 0.f;
       b[r] = ok[r] ? delta[row + pos] : 0.f;
@@ -215,38 +222,45 @@ __global__ __launch_bounds__(1024) void k_sample(DevCtx c, const float* m, const
   flush_hist(lh, c.hist + (static_cast<uint64_t>(w) * c.L + seg) * 3 * HBINS);
 }
 
-__global__ __launch_bounds__(BLOCK) void k_sample_scan(DevCtx c) {
+__global__ __launch_bounds__(BIG) void k_sample_scan(DevCtx c) {
   __shared__ uint64_t scratch[17];
   __shared__ uint32_t result[2];
   const uint32_t seg = c.fast_segs[blockIdx.x], w = blockIdx.y;
   const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
   uint32_t above;
-  const uint32_t bin = find_from_top(c.hist + u * 3 * HBINS, c.segs[seg].r_s, &above, scratch, result, true);
+  const uint32_t bin = find_from_top<BIG>(c.hist + u * 3 * HBINS, c.segs[seg].r_s, &above, scratch, result, true);
   if (threadIdx.x == 0) c.units[u].T = bin << 20;      // the guess: lower edge of the bin
 }
 
 // ------------------------------------------------------------------------------------------------
-// the streaming pass.  Every wave owns one wave-tile (4 contiguous chunks of 1024 coordinates).
+// the streaming pass.  One wave per chunk of 1024 coordinates: 8 + 4 dwordx4 accesses with
+// streaming (non-temporal) cache hints, then the chunk's candidates go to the chunk's slot.
+//
+// Slot of a chunk: lpc * 2 elements of 8 bytes.  Element 0 is the header (count, overflow offset);
+// elements 1 .. count hold (coordinate, value bits) in coordinate order.  A chunk with more
+// candidates than its slot holds puts all of them into the unit's overflow pool instead (one
+// returning atomic; rare unless the large values cluster) and records where.
 // ------------------------------------------------------------------------------------------------
-struct StreamSeg { uint64_t start, size, pool_off; uint32_t sub_cap, wt_base; };
+struct StreamSeg { uint64_t start, size, slot_off, ovf_off; uint32_t lpc, ovf_cap; };
+
+typedef uint32_t u2v __attribute__((ext_vector_type(2)));
 
 template <int SPARS, bool SINGLE>
 __global__ __launch_bounds__(BLOCK) void k_stream(DevCtx c, StreamSeg one, const float* m, const float* delta,
                                                   float* m_out, uint32_t worker0, uint64_t round) {
+  __shared__ uint2 s_stage[BLOCK / 64][32];
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   const uint32_t wt = blockIdx.x * 4 + wave;
   if (wt >= c.NWT) return;
   const uint32_t w = blockIdx.y;
   StreamSeg sg = one;
-  uint32_t seg = 0, first_chunk = wt * WT_CHUNKS, nchunks;
+  uint32_t seg = 0, chunk = wt;
   if (!SINGLE) {
     const WtInfo wi = c.wts[wt];
     const SegInfo& s = c.segs[wi.seg];
-    seg = wi.seg; first_chunk = wi.first_chunk; nchunks = wi.nchunks; sg.wt_base = s.wt_base;
-    sg.start = s.start; sg.size = s.size; sg.pool_off = s.pool_off; sg.sub_cap = s.sub_cap;
-  } else {
-    const uint64_t left = (sg.size + CHUNK - 1) / CHUNK - first_chunk;
-    nchunks = left < WT_CHUNKS ? static_cast<uint32_t>(left) : WT_CHUNKS;
+    seg = wi.seg; chunk = wi.chunk;
+    sg.start = s.start; sg.size = s.size; sg.slot_off = s.slot_off; sg.ovf_off = s.ovf_off;
+    sg.lpc = s.lpc; sg.ovf_cap = s.ovf_cap;
   }
   const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
   const uint32_t T = c.units[u].T;
@@ -255,113 +269,148 @@ __global__ __launch_bounds__(BLOCK) void k_stream(DevCtx c, StreamSeg one, const
   const float* mp = m + row;
   const float* dp = delta + row;
   float* op = m_out + row;
-  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
-  uint32_t pmask[WT_CHUNKS] = {0, 0, 0, 0};
-  bool nonfinite = false;
-
+  const uint64_t cb = static_cast<uint64_t>(chunk) * CHUNK;           // segment-local
+  f4u v[4];
+  if (sg.size - cb >= CHUNK) {
+    f4u a[4], b[4];
 #pragma unroll
-  for (uint32_t q = 0; q < WT_CHUNKS; ++q) {
-    if (q >= nchunks) break;
-    const uint64_t cb = static_cast<uint64_t>(first_chunk + q) * CHUNK;   // segment-local
-    uint32_t pm = 0;
-    if (sg.size - cb >= CHUNK) {
-      f4u a[4], b[4];
+    for (int t = 0; t < 4; ++t) {
+      const uint64_t e = cb + t * 256 + lane * 4;
+      a[t] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(mp + e));
+      b[t] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(dp + e));
+    }
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const uint64_t e = cb + t * 256 + lane * 4;
-        a[t] = *reinterpret_cast<const f4u*>(mp + e);
-        b[t] = *reinterpret_cast<const f4u*>(dp + e);
-      }
+    for (int t = 0; t < 4; ++t) {
+      v[t] = a[t] + b[t];
+      __builtin_nontemporal_store(v[t], reinterpret_cast<f4u*>(op + cb + t * 256 + lane * 4));
+    }
+  } else {
 #pragma unroll
-      for (int t = 0; t < 4; ++t) {
-        const uint64_t e = cb + t * 256 + lane * 4;
-        const f4u v = a[t] + b[t];
-        *reinterpret_cast<f4u*>(op + e) = v;
-        Words4 rw;
-        if (SPARS == QSL_RANDK) rw = rand_words4(rk, static_cast<uint32_t>(sg.start + e));
+    for (int t = 0; t < 4; ++t) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const uint32_t bits = __float_as_uint(v[j]);
-          nonfinite |= (bits & 0x7FFFFFFFu) >= 0x7F800000u;
-          const uint32_t key = SPARS == QSL_TOPK ? key_of_value(bits) : rw.w[j];
-          pm |= (key >= T ? 1u : 0u) << (t * 4 + j);
-        }
-      }
-    } else {
-#pragma unroll
-      for (int t = 0; t < 4; ++t) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const uint64_t e = cb + t * 256 + lane * 4 + j;
-          if (e < sg.size) {
-            const float v = mp[e] + dp[e];
-            op[e] = v;
-            const uint32_t bits = __float_as_uint(v);
-            nonfinite |= (bits & 0x7FFFFFFFu) >= 0x7F800000u;
-            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(bits)
-                                                   : rand_word(rk, static_cast<uint32_t>(sg.start + e));
-            pm |= (key >= T ? 1u : 0u) << (t * 4 + j);
-          }
-        }
+      for (int j = 0; j < 4; ++j) {
+        const uint64_t e = cb + t * 256 + lane * 4 + j;
+        float x = 0.0f;                                               // past the end: never a candidate
+        if (e < sg.size) { x = mp[e] + dp[e]; op[e] = x; }
+        v[t][j] = x;
       }
     }
-    pmask[q] = pm;
+  }
+  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
+  uint32_t pm = 0;                                                    // bit t*4+j: coordinate (t, j) is a candidate
+  bool nonfinite = false;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    Words4 rw;
+    if (SPARS == QSL_RANDK) rw = rand_words4(rk, static_cast<uint32_t>(sg.start + cb + t * 256 + lane * 4));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t bits = __float_as_uint(v[t][j]);
+      nonfinite |= (bits & 0x7FFFFFFFu) >= 0x7F800000u;
+      const uint32_t key = SPARS == QSL_TOPK ? key_of_value(bits) : rw.w[j];
+      const bool inside = cb + t * 256 + lane * 4 + j < sg.size;
+      pm |= (inside && key >= T ? 1u : 0u) << (t * 4 + j);
+    }
   }
   if (__ballot(nonfinite) != 0 && lane == 0) atomicOr(c.status, 1u);
   if (path != PATH_FAST) return;                  // uniform over the wave
 
-  // reserve room in one of the unit's sub-pools for this wave-tile's candidates and write them in
-  // coordinate order.  A sub-pool that runs full keeps counting (the count then exceeds its
-  // capacity, which k_select<0> reads as "guess failed") but takes no more entries.
-  const uint32_t mine = __popc(pmask[0]) + __popc(pmask[1]) + __popc(pmask[2]) + __popc(pmask[3]);
-  const uint32_t total = wave_sum(mine);
-  const uint32_t sp = (SINGLE ? wt : wt - sg.wt_base) & (NSUB - 1);
-  uint32_t off = 0;
-  if (total) {
-    if (lane == 0) {
-      off = atomicAdd(&c.sub_cnt[u * NSUB + sp], total);
-      if (off > sg.sub_cap || total > sg.sub_cap - off) off = 0xFFFFFFFFu;
-    }
-    off = __shfl(off, 0, WAVE);
-  }
-  const bool ok = off != 0xFFFFFFFFu;
-  off += sp * sg.sub_cap;                         // offset inside the unit's pool
-  if (lane == 0)
-    c.wt_rec[static_cast<uint64_t>(w) * c.NWT + wt] = make_uint2(ok ? off : 0u, ok ? total : 0u);
-  if (!ok || total == 0) return;
-  uint2* pool = c.pool + static_cast<uint64_t>(w) * c.pool_stride + sg.pool_off + off;
-  uint32_t base = 0;
-#pragma unroll
-  for (uint32_t q = 0; q < WT_CHUNKS; ++q) {
-    const uint32_t pm = pmask[q];
-    if (__ballot(pm != 0) == 0) continue;         // wave-uniform
-    const uint64_t cb = static_cast<uint64_t>(first_chunk + q) * CHUNK;
+  const uint32_t cap = sg.lpc * 2 - 1;
+  uint2* stage = s_stage[wave];
+  uint32_t total = 0, ovf_at = 0;
+  if (__ballot(pm != 0) != 0) {
+    uint32_t before[4], tot[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
+      before[t] = 0; tot[t] = 0;
       const uint32_t nib = (pm >> (t * 4)) & 0xFu;
       if (__ballot(nib != 0) == 0) continue;      // wave-uniform
-      uint32_t before = 0, tot = 0;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const uint64_t bal = __ballot((nib >> j) & 1u);
-        before += popc_below(bal);
-        tot += __popcll(bal);
+        before[t] += popc_below(bal);
+        tot[t] += __popcll(bal);
       }
-      uint32_t pos = base + before;
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        if ((nib >> j) & 1u) {
-          const uint64_t e = cb + t * 256 + lane * 4 + j;
-          pool[pos++] = make_uint2(static_cast<uint32_t>(sg.start + e), __float_as_uint(op[e]));
-        }
-      }
-      base += tot;
     }
+    total = tot[0] + tot[1] + tot[2] + tot[3];
+    uint32_t* ctr = c.ctr + u * (CTR_LINES * PAD);
+    uint2* dst = stage + 1;                       // where entry 0 goes
+    bool write = true;
+    if (total > cap) {                            // wave-uniform: the slot cannot hold this chunk
+      if (lane == 0) {
+        ovf_at = atomicAdd(&ctr[CTR_OVF * PAD], total);
+        if (ovf_at > sg.ovf_cap || total > sg.ovf_cap - ovf_at) { atomicOr(&ctr[CTR_FAIL * PAD], 1u); ovf_at = 0xFFFFFFFFu; }
+      }
+      ovf_at = __shfl(ovf_at, 0, WAVE);
+      write = ovf_at != 0xFFFFFFFFu;
+      dst = c.ovf + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off + ovf_at;
+    }
+    if (lane == 0) atomicAdd(&ctr[(chunk & (NSUB - 1)) * PAD], total);          // nobody waits for this one
+    if (write) {
+      uint32_t base = 0;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const uint32_t nib = (pm >> (t * 4)) & 0xFu;
+        uint32_t pos = base + before[t];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          if ((nib >> j) & 1u)
+            dst[pos++] = make_uint2(static_cast<uint32_t>(sg.start + cb + t * 256 + lane * 4 + j), __float_as_uint(v[t][j]));
+        }
+        base += tot[t];
+      }
+    }
+  }
+  if (lane == 0) stage[0] = make_uint2(total, ovf_at);
+  // the staging line is private to the wave, whose lanes run in lockstep: order the LDS traffic only
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  if (lane < sg.lpc * 2) {
+    const uint2 e = stage[lane];
+    const u2v ev = {e.x, e.y};
+    uint2* slot = c.slots + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off + static_cast<uint64_t>(chunk) * (sg.lpc * 2);
+    __builtin_nontemporal_store(ev, reinterpret_cast<u2v*>(slot + lane));
   }
 }
 
 // ------------------------------------------------------------------------------------------------
-// radix selection, one kernel per digit; the last block of each unit fixes the digit
+// walking the candidates of a fast unit.  A wave reads 64 x 16 bytes of the slot area at a time,
+// i.e. 64 / lpc whole slots; lane l holds elements 2 (l mod lpc) and 2 (l mod lpc) + 1 of its slot.
+// ------------------------------------------------------------------------------------------------
+struct SlotRow {
+  uint32_t chunk;        // chunk this lane's slot belongs to
+  uint32_t count;        // candidates of that chunk (0 if the chunk does not exist)
+  uint32_t ovf_at;       // where they are in the overflow pool, if count > cap
+  bool lead;             // this lane holds the slot's header
+  bool inl;              // the candidates are in the slot itself
+  bool has0, has1;       // this lane's first / second element is a candidate
+  uint32_t idx0, bits0, idx1, bits1;
+};
+
+__device__ __forceinline__ SlotRow read_slot_row(const uint2* slots, uint32_t lpc, uint32_t nwt, uint64_t row) {
+  SlotRow r;
+  const uint32_t lane = lane_id();
+  const uint32_t sub = lane & (lpc - 1);
+  const uint64_t chunk64 = (row * 64 + lane) / lpc;
+  r.chunk = static_cast<uint32_t>(chunk64);
+  uint4 q = make_uint4(0, 0, 0, 0);
+  if (chunk64 < nwt) q = reinterpret_cast<const uint4*>(slots)[row * 64 + lane];
+  const uint32_t leader = lane & ~(lpc - 1);
+  r.count = __shfl(q.x, leader, WAVE);
+  r.ovf_at = __shfl(q.y, leader, WAVE);
+  r.lead = sub == 0;
+  const uint32_t cap = lpc * 2 - 1;
+  r.inl = r.count <= cap;
+  const uint32_t e0 = sub * 2;                    // element numbers of this lane; element e holds candidate e - 1
+  r.has0 = r.inl && e0 >= 1 && e0 <= r.count;
+  r.has1 = r.inl && e0 + 1 <= r.count;
+  r.idx0 = q.x; r.bits0 = q.y; r.idx1 = q.z; r.bits1 = q.w;
+  return r;
+}
+
+// ------------------------------------------------------------------------------------------------
+// radix selection, one kernel per digit
 // ------------------------------------------------------------------------------------------------
 template <int LEVEL>
 __device__ __forceinline__ bool level_bin(uint32_t key, uint32_t prefix, uint32_t* bin) {
@@ -374,10 +423,10 @@ __device__ __forceinline__ bool level_bin(uint32_t key, uint32_t prefix, uint32_
 // a few global atomics per bin); which bin the previous digit fell in is recomputed by every block
 // from the previous kernel's histogram.
 template <int LEVEL, int SPARS>
-__global__ __launch_bounds__(BLOCK) void k_select(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
+__global__ __launch_bounds__(BIG) void k_select(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
   __shared__ uint32_t lh[HBINS];
   __shared__ uint64_t scratch[17];
-  __shared__ uint32_t result[2], s_sub[NSUB];
+  __shared__ uint32_t result[2], s_ctr[CTR_LINES];
   const SelInfo si = c.sels[blockIdx.x];
   const uint32_t w = blockIdx.y;
   const SegInfo sg = c.segs[si.seg];
@@ -385,17 +434,18 @@ __global__ __launch_bounds__(BLOCK) void k_select(DevCtx c, const float* v, uint
   UnitState* usp = &c.units[u];
   const UnitState us = *usp;
   uint32_t* hist = c.hist + u * 3 * HBINS;
-  for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK) lh[i] = 0;
-  if (threadIdx.x < NSUB) s_sub[threadIdx.x] = us.path == PATH_FAST ? c.sub_cnt[u * NSUB + threadIdx.x] : 0u;
+  for (uint32_t i = threadIdx.x; i < HBINS; i += BIG) lh[i] = 0;
+  if (LEVEL == 0 && threadIdx.x < CTR_LINES)
+    s_ctr[threadIdx.x] = us.path == PATH_FAST ? c.ctr[(u * CTR_LINES + threadIdx.x) * PAD] : 0u;
   __syncthreads();
   uint32_t path, prefix = 0, k_rem = sg.k;
   if (LEVEL == 0) {
-    // a guess that produced too few candidates, or overflowed a sub-pool, is discarded here
+    // a guess that produced too few candidates, or ran out of overflow room, is discarded here
     path = us.path;
     if (path == PATH_FAST) {
-      uint32_t cand = 0; bool over = false;
-      for (uint32_t i = 0; i < NSUB; ++i) { cand += s_sub[i]; over |= s_sub[i] > sg.sub_cap; }
-      if (over || cand < sg.k) path = PATH_FALLBACK;
+      uint32_t cand = 0;
+      for (uint32_t i = 0; i < NSUB; ++i) cand += s_ctr[i];
+      if (s_ctr[CTR_FAIL] || cand < sg.k) path = PATH_FALLBACK;
       if (threadIdx.x == 0 && si.j == 0) { usp->cand = cand; usp->fell_back = path == PATH_FALLBACK; }
     } else if (threadIdx.x == 0 && si.j == 0) { usp->cand = 0; usp->fell_back = 0; }
     if (threadIdx.x == 0 && si.j == 0) usp->nnz = 0;
@@ -403,33 +453,44 @@ __global__ __launch_bounds__(BLOCK) void k_select(DevCtx c, const float* v, uint
     path = eff_path(us);
     uint32_t above;
     if (LEVEL == 1) {
-      const uint32_t bin = find_from_top(hist, sg.k, &above, scratch, result, false);
+      const uint32_t bin = find_from_top<BIG>(hist, sg.k, &above, scratch, result, false);
       prefix = bin << 20; k_rem = sg.k - above;
     } else {
-      const uint32_t bin = find_from_top(hist + HBINS, us.k_rem, &above, scratch, result, false);
+      const uint32_t bin = find_from_top<BIG>(hist + HBINS, us.k_rem, &above, scratch, result, false);
       prefix = us.prefix | (bin << 8); k_rem = us.k_rem - above;
     }
     if (threadIdx.x == 0 && si.j == 0) { usp->prefix = prefix; usp->k_rem = k_rem; }
   }
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   if (path == PATH_FAST) {
-    const uint2* pool = c.pool + static_cast<uint64_t>(w) * c.pool_stride + sg.pool_off;
-    for (uint32_t sp = si.j; sp < NSUB; sp += sg.nsel) {
-      const uint2* sub = pool + static_cast<uint64_t>(sp) * sg.sub_cap;
-      const uint32_t n = s_sub[sp];
-      for (uint32_t e = threadIdx.x; e < n; e += BLOCK) {
+    const uint2* slots = c.slots + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off;
+    const uint2* ovf = c.ovf + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off;
+    const uint64_t nrows = (static_cast<uint64_t>(sg.nwt) * sg.lpc + 63) / 64;
+    const uint32_t nwaves = sg.nsel * (BIG / 64);
+    for (uint64_t row0 = si.j * (BIG / 64) + (threadIdx.x >> 6); row0 < nrows; row0 += 4 * nwaves) {
+      SlotRow rr[4];                               // four independent accesses in flight; rows past the end read as empty
+#pragma unroll
+      for (int b = 0; b < 4; ++b) rr[b] = read_slot_row(slots, sg.lpc, sg.nwt, row0 + b * nwaves);
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const SlotRow& r = rr[b];
         uint32_t bin;
-        if (level_bin<LEVEL>(entry_key<SPARS>(sub[e], rk), prefix, &bin)) atomicAdd(&lh[bin], 1u);
+        if (r.has0 && level_bin<LEVEL>(entry_key<SPARS>(r.idx0, r.bits0, rk), prefix, &bin)) atomicAdd(&lh[bin], 1u);
+        if (r.has1 && level_bin<LEVEL>(entry_key<SPARS>(r.idx1, r.bits1, rk), prefix, &bin)) atomicAdd(&lh[bin], 1u);
+        if (r.lead && !r.inl) {
+          for (uint32_t e = 0; e < r.count; ++e) {
+            const uint2 ent = ovf[r.ovf_at + e];
+            if (level_bin<LEVEL>(entry_key<SPARS>(ent.x, ent.y, rk), prefix, &bin)) atomicAdd(&lh[bin], 1u);
+          }
+        }
       }
     }
   } else {
     const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
     for (uint64_t t = si.j; t < sg.nwt; t += sg.nsel) {
-      const uint64_t lo = t * WTILE, hi = lo + WTILE < sg.size ? lo + WTILE : sg.size;
-      for (uint64_t e = lo + threadIdx.x; e < hi; e += BLOCK) {
-        uint32_t bin;
-        if (level_bin<LEVEL>(coord_key<SPARS>(vp, e, sg.start, rk), prefix, &bin)) atomicAdd(&lh[bin], 1u);
-      }
+      const uint64_t e = t * CHUNK + threadIdx.x;
+      uint32_t bin;
+      if (e < sg.size && level_bin<LEVEL>(coord_key<SPARS>(vp, e, sg.start, rk), prefix, &bin)) atomicAdd(&lh[bin], 1u);
     }
   }
   __syncthreads();
@@ -437,8 +498,9 @@ __global__ __launch_bounds__(BLOCK) void k_select(DevCtx c, const float* v, uint
 }
 
 // ------------------------------------------------------------------------------------------------
-// ordered compaction of the selected coordinates.  A block handles a group of up to 64 wave-tiles
-// of one unit; a wave handles one wave-tile at a time.
+// ordered compaction of the selected coordinates.  A block handles a group of up to 256 chunks of
+// one unit.  Fast units: the waves read slot rows (several chunks per access).  General path: a
+// wave reads one chunk of v at a time.
 // ------------------------------------------------------------------------------------------------
 template <int SPARS>
 __global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
@@ -453,7 +515,7 @@ __global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, const float* v, 
   us.path = eff_path(us);
   {  // the last digit, from the histogram k_select<2> left: the threshold key and the tie budget
     uint32_t above;
-    const uint32_t bin = find_from_top(c.hist + (u * 3 + 2) * HBINS, us.k_rem, &above, scratch, result, false);
+    const uint32_t bin = find_from_top<BLOCK>(c.hist + (u * 3 + 2) * HBINS, us.k_rem, &above, scratch, result, false);
     us.tau = us.prefix | bin; us.need = us.k_rem - above;
     if (threadIdx.x == 0 && gi.first_wt == 0) {
       c.units[u].tau = us.tau; c.units[u].need = us.need; c.units[u].n_gt = sg.k - us.need;
@@ -461,40 +523,58 @@ __global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, const float* v, 
   }
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const uint64_t wbase = static_cast<uint64_t>(w) * c.NWT + sg.wt_base;
-  const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
-  const uint2* pool = c.pool + static_cast<uint64_t>(w) * c.pool_stride + sg.pool_off;
-  uint32_t tot_gt = 0, tot_eq = 0;
-  for (uint32_t i = wave; i < gi.nwt; i += 4) {
-    const uint32_t t = gi.first_wt + i;
-    uint32_t gt = 0, eq = 0;
-    if (us.path == PATH_FAST) {
-      const uint2 rec = c.wt_rec[wbase + t];
-      for (uint32_t e = lane; e < rec.y; e += WAVE) {
-        const uint32_t key = entry_key<SPARS>(pool[rec.x + e], rk);
-        gt += key > us.tau; eq += key == us.tau;
+  uint2* cnt = c.wt_cnt + static_cast<uint64_t>(w) * c.NWT + sg.wt_base;
+  uint32_t tot_gt = 0, tot_eq = 0;                 // per lane; summed over the wave at the end
+  if (us.path == PATH_FAST) {
+    const uint2* slots = c.slots + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off;
+    const uint2* ovf = c.ovf + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off;
+    const uint64_t row0 = static_cast<uint64_t>(gi.first_wt) * sg.lpc / 64;       // first_wt is a multiple of 256
+    const uint32_t nrows = (gi.nwt * sg.lpc + 63) / 64;
+    const uint64_t gmask = (sg.lpc == 16 ? 0xFFFFull : 0xFFull) << (lane & ~(sg.lpc - 1));
+    for (uint32_t i = wave; i < nrows; i += 4) {
+      const SlotRow r = read_slot_row(slots, sg.lpc, sg.nwt, row0 + i);
+      const uint32_t k0 = entry_key<SPARS>(r.idx0, r.bits0, rk), k1 = entry_key<SPARS>(r.idx1, r.bits1, rk);
+      const bool g0 = r.has0 && k0 > us.tau, g1 = r.has1 && k1 > us.tau;
+      const bool q0 = r.has0 && k0 == us.tau, q1 = r.has1 && k1 == us.tau;
+      const uint64_t bg0 = __ballot(g0), bg1 = __ballot(g1), bq0 = __ballot(q0), bq1 = __ballot(q1);
+      uint32_t gt = __popcll(bg0 & gmask) + __popcll(bg1 & gmask);
+      uint32_t eq = __popcll(bq0 & gmask) + __popcll(bq1 & gmask);
+      if (r.lead && !r.inl) {
+        gt = 0; eq = 0;
+        for (uint32_t e = 0; e < r.count; ++e) {
+          const uint2 ent = ovf[r.ovf_at + e];
+          const uint32_t key = entry_key<SPARS>(ent.x, ent.y, rk);
+          gt += key > us.tau; eq += key == us.tau;
+        }
       }
-    } else {
-      const uint64_t lo = static_cast<uint64_t>(t) * WTILE, hi = lo + WTILE < sg.size ? lo + WTILE : sg.size;
+      if (r.lead && r.chunk < sg.nwt) { cnt[r.chunk] = make_uint2(gt, eq); tot_gt += gt; tot_eq += eq; }
+    }
+  } else {
+    const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
+    for (uint32_t i = wave; i < gi.nwt; i += 4) {
+      const uint32_t t = gi.first_wt + i;
+      uint32_t gt = 0, eq = 0;
+      const uint64_t lo = static_cast<uint64_t>(t) * CHUNK, hi = lo + CHUNK < sg.size ? lo + CHUNK : sg.size;
       for (uint64_t e = lo + lane; e < hi; e += WAVE) {
         const uint32_t key = coord_key<SPARS>(vp, e, sg.start, rk);
         gt += key > us.tau; eq += key == us.tau;
       }
+      gt = wave_sum(gt); eq = wave_sum(eq);
+      if (lane == 0) { cnt[t] = make_uint2(gt, eq); tot_gt += gt; tot_eq += eq; }
     }
-    gt = wave_sum(gt); eq = wave_sum(eq);
-    if (lane == 0) c.wt_cnt[wbase + t] = make_uint2(gt, eq);
-    tot_gt += gt; tot_eq += eq;
   }
+  tot_gt = wave_sum(tot_gt); tot_eq = wave_sum(tot_eq);
   if (lane == 0) { s_gt[wave] = tot_gt; s_eq[wave] = tot_eq; }
   __syncthreads();
-  uint2* gc = c.grp_cnt + static_cast<uint64_t>(w) * c.NGRP + sg.grp_base;
   if (threadIdx.x == 0)
-    gc[gi.first_wt / GROUP] = make_uint2(s_gt[0] + s_gt[1] + s_gt[2] + s_gt[3], s_eq[0] + s_eq[1] + s_eq[2] + s_eq[3]);
+    c.grp_cnt[static_cast<uint64_t>(w) * c.NGRP + sg.grp_base + gi.first_wt / GROUP] =
+        make_uint2(s_gt[0] + s_gt[1] + s_gt[2] + s_gt[3], s_eq[0] + s_eq[1] + s_eq[2] + s_eq[3]);
 }
 
 template <int SPARS>
 __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
   __shared__ uint32_t s_gt[GROUP], s_eq[GROUP];
+  __shared__ uint64_t scratch[17];
   __shared__ uint64_t s_part[4];
   const GrpInfo gi = c.grps[blockIdx.x];
   const uint32_t w = blockIdx.y;
@@ -504,7 +584,7 @@ __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, const float* v, 
   us.path = eff_path(us);
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const uint64_t wbase = static_cast<uint64_t>(w) * c.NWT + sg.wt_base;
+  const uint2* cnt = c.wt_cnt + static_cast<uint64_t>(w) * c.NWT + sg.wt_base;
   // how many selected coordinates precede this group: the sum of the earlier groups' counts
   {
     const uint2* gc = c.grp_cnt + static_cast<uint64_t>(w) * c.NGRP + sg.grp_base;
@@ -515,41 +595,64 @@ __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, const float* v, 
     if (lane == 0) s_part[wave] = x;
   }
   __syncthreads();
-  // exclusive prefix of this group's wave-tile counts, on top of the group's own prefix
-  if (threadIdx.x < GROUP) {
+  {  // exclusive prefix of this group's chunk counts, on top of the group's own prefix
     uint2 p = make_uint2(0, 0);
-    if (threadIdx.x < gi.nwt) p = c.wt_cnt[wbase + gi.first_wt + threadIdx.x];
-    const uint64_t x = (static_cast<uint64_t>(p.y) << 32) | p.x;
-    const uint64_t ex = wave_inclusive_scan64(x) - x + s_part[0] + s_part[1] + s_part[2] + s_part[3];
+    if (threadIdx.x < gi.nwt) p = cnt[gi.first_wt + threadIdx.x];
+    uint64_t total;
+    const uint64_t ex = block_exclusive_scan64((static_cast<uint64_t>(p.y) << 32) | p.x, scratch, &total) +
+                        s_part[0] + s_part[1] + s_part[2] + s_part[3];
     s_gt[threadIdx.x] = static_cast<uint32_t>(ex); s_eq[threadIdx.x] = static_cast<uint32_t>(ex >> 32);
   }
   __syncthreads();
   uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
   uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
-  const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
-  const uint2* pool = c.pool + static_cast<uint64_t>(w) * c.pool_stride + sg.pool_off;
-  for (uint32_t i = wave; i < gi.nwt; i += 4) {
-    const uint32_t t = gi.first_wt + i;
-    uint32_t gt_before = s_gt[i], eq_before = s_eq[i];
-    uint32_t n_items; uint64_t lo = 0; uint2 rec = make_uint2(0, 0);
-    if (us.path == PATH_FAST) { rec = c.wt_rec[wbase + t]; n_items = rec.y; }
-    else {
-      lo = static_cast<uint64_t>(t) * WTILE;
-      n_items = static_cast<uint32_t>((lo + WTILE < sg.size ? lo + WTILE : sg.size) - lo);
+  if (us.path == PATH_FAST) {
+    const uint2* slots = c.slots + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off;
+    const uint2* ovf = c.ovf + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off;
+    const uint64_t row0 = static_cast<uint64_t>(gi.first_wt) * sg.lpc / 64;
+    const uint32_t nrows = (gi.nwt * sg.lpc + 63) / 64;
+    const uint64_t gmask = (sg.lpc == 16 ? 0xFFFFull : 0xFFull) << (lane & ~(sg.lpc - 1));
+    const uint64_t below = gmask & ((1ull << lane) - 1ull);             // lanes of my slot before me
+    for (uint32_t i = wave; i < nrows; i += 4) {
+      const SlotRow r = read_slot_row(slots, sg.lpc, sg.nwt, row0 + i);
+      if (r.chunk >= sg.nwt) continue;             // only the last row of a unit has such lanes; no ballot below needs them
+      const uint32_t k0 = entry_key<SPARS>(r.idx0, r.bits0, rk), k1 = entry_key<SPARS>(r.idx1, r.bits1, rk);
+      const bool g0 = r.has0 && k0 > us.tau, g1 = r.has1 && k1 > us.tau;
+      const bool q0 = r.has0 && k0 == us.tau, q1 = r.has1 && k1 == us.tau;
+      const uint64_t bg0 = __ballot(g0), bg1 = __ballot(g1), bq0 = __ballot(q0), bq1 = __ballot(q1);
+      const uint32_t li = r.chunk - gi.first_wt;
+      const uint32_t gt_base = s_gt[li], eq_base = s_eq[li];
+      // candidates of a slot are ordered: lane by lane, first element before second
+      const uint32_t gt0 = gt_base + __popcll(bg0 & below) + __popcll(bg1 & below);
+      const uint32_t eq0 = eq_base + __popcll(bq0 & below) + __popcll(bq1 & below);
+      if (g0 || (q0 && eq0 < us.need)) { const uint32_t pos = gt0 + min(eq0, us.need); oi[pos] = r.idx0; ov[pos] = r.bits0; }
+      const uint32_t gt1 = gt0 + (g0 ? 1u : 0u), eq1 = eq0 + (q0 ? 1u : 0u);
+      if (g1 || (q1 && eq1 < us.need)) { const uint32_t pos = gt1 + min(eq1, us.need); oi[pos] = r.idx1; ov[pos] = r.bits1; }
+      if (r.lead && !r.inl) {
+        uint32_t gt = gt_base, eq = eq_base;
+        for (uint32_t e = 0; e < r.count; ++e) {
+          const uint2 ent = ovf[r.ovf_at + e];
+          const uint32_t key = entry_key<SPARS>(ent.x, ent.y, rk);
+          const bool g = key > us.tau, q = key == us.tau;
+          if (g || (q && eq < us.need)) { const uint32_t pos = gt + min(eq, us.need); oi[pos] = ent.x; ov[pos] = ent.y; }
+          gt += g; eq += q;
+        }
+      }
     }
+    return;
+  }
+  const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
+  for (uint32_t i = wave; i < gi.nwt; i += 4) {
+    const uint64_t lo = static_cast<uint64_t>(gi.first_wt + i) * CHUNK;
+    const uint32_t n_items = static_cast<uint32_t>((lo + CHUNK < sg.size ? lo + CHUNK : sg.size) - lo);
+    uint32_t gt_before = s_gt[i], eq_before = s_eq[i];
     for (uint32_t j0 = 0; j0 < n_items; j0 += WAVE) {
       const uint32_t j = j0 + lane;
       bool is_gt = false, is_eq = false;
       uint32_t idx = 0, bits = 0;
       if (j < n_items) {
-        uint32_t key;
-        if (us.path == PATH_FAST) {
-          const uint2 ent = pool[rec.x + j];
-          idx = ent.x; bits = ent.y; key = entry_key<SPARS>(ent, rk);
-        } else {
-          idx = static_cast<uint32_t>(sg.start + lo + j); bits = __float_as_uint(vp[lo + j]);
-          key = SPARS == QSL_TOPK ? key_of_value(bits) : rand_word(rk, idx);
-        }
+        idx = static_cast<uint32_t>(sg.start + lo + j); bits = __float_as_uint(vp[lo + j]);
+        const uint32_t key = SPARS == QSL_TOPK ? key_of_value(bits) : rand_word(rk, idx);
         is_gt = key > us.tau; is_eq = key == us.tau;
       }
       const uint64_t bg = __ballot(is_gt), be = __ballot(is_eq);
@@ -801,8 +904,8 @@ __global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t
     const uint64_t tid = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x, nth = static_cast<uint64_t>(gridDim.x) * BLOCK;
     uint32_t* h = c.hist + static_cast<uint64_t>(w) * c.L * 3 * HBINS;
     for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * 3 * HBINS; i += nth) h[i] = 0;
-    uint32_t* sc = c.sub_cnt + static_cast<uint64_t>(w) * c.L * NSUB;
-    for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * NSUB; i += nth) sc[i] = 0;
+    uint32_t* ct = c.ctr + static_cast<uint64_t>(w) * c.L * CTR_LINES * PAD;
+    for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * CTR_LINES; i += nth) ct[i * PAD] = 0;
     uint64_t* na = c.norm_acc + static_cast<uint64_t>(w) * c.L * ACC_SLOTS;
     for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * ACC_SLOTS; i += nth) na[i] = 0;
   }
@@ -1044,7 +1147,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   std::vector<SelInfo> sels;
   std::vector<NormTile> ntiles;
   std::vector<uint32_t> fast;
-  uint64_t pool_entries = 0;
+  uint64_t slot_elems = 0, ovf_entries = 0;
   uint32_t koff = 0;
   uint64_t nwt64 = 0;
   ctx->n_sampled = 0;
@@ -1053,16 +1156,11 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
     memset(&sg, 0, sizeof sg);
     sg.start = ctx->off[l]; sg.size = ctx->off[l + 1] - ctx->off[l];
     sg.k = ctx->k[l]; sg.koff = koff; koff += sg.k;
-    const uint64_t nchunks = (sg.size + CHUNK - 1) / CHUNK;
     sg.wt_base = static_cast<uint32_t>(nwt64);
-    sg.nwt = static_cast<uint32_t>((nchunks + WT_CHUNKS - 1) / WT_CHUNKS);
+    sg.nwt = static_cast<uint32_t>((sg.size + CHUNK - 1) / CHUNK);
     nwt64 += sg.nwt;
     if (L > 1) {
-      for (uint32_t t = 0; t < sg.nwt; ++t) {
-        WtInfo wi; wi.seg = l; wi.first_chunk = t * WT_CHUNKS;
-        wi.nchunks = static_cast<uint32_t>(std::min<uint64_t>(WT_CHUNKS, nchunks - wi.first_chunk)); wi.pad = 0;
-        wts.push_back(wi);
-      }
+      for (uint32_t t = 0; t < sg.nwt; ++t) { WtInfo wi; wi.seg = l; wi.chunk = t; wi.pad0 = wi.pad1 = 0; wts.push_back(wi); }
     }
     sg.grp_base = static_cast<uint32_t>(grps.size());
     sg.ngrp = (sg.nwt + GROUP - 1) / GROUP;
@@ -1090,7 +1188,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
           if (n_s > n / 16) continue;
           sg.n_runs = static_cast<uint32_t>(std::ceil(n_s / 64.0));
           sg.r_s = static_cast<uint32_t>(std::ceil(alpha * (sg.n_runs * 64.0) * p));
-          sg.sub_cap = static_cast<uint32_t>(std::ceil((4.0 * alpha * sg.k + 8192.0) / NSUB));
+          sg.lpc = alpha * p * CHUNK + 5.0 * std::sqrt(alpha * p * CHUNK) + 3.0 <= 15.0 ? 8 : 16;
           sg.mode = PATH_FAST;
           ++ctx->n_sampled;
           break;
@@ -1098,17 +1196,20 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
       } else if (cfg->sparsifier == QSL_RANDK && static_cast<uint64_t>(sg.k) * 16 <= sg.size) {
         // the keys are uniform 32-bit words: keep those above the (1 - q) quantile, q = p + 7 sigma
         const double q = p + 7.0 * std::sqrt(p * (1 - p) / n);
-        if (q < 0.25) {
+        if (q * CHUNK <= 16.0) {                  // at most ~16 candidates per chunk: they fit a two-line slot
           sg.T_static = static_cast<uint32_t>(std::floor(4294967296.0 * (1.0 - q)));
-          // a sub-pool sees 1/64 of the wave-tiles: its own count has mean qn/64 and sigma sqrt(qn/64)
-          sg.sub_cap = static_cast<uint32_t>(std::ceil(q * n / NSUB + 8.0 * std::sqrt(q * n / NSUB) + 64.0));
+          sg.lpc = q * CHUNK + 5.0 * std::sqrt(q * CHUNK) + 3.0 <= 15.0 ? 8 : 16;
           sg.mode = PATH_FAST;
         }
       }
     }
     if (sg.mode == PATH_FAST) {
-      sg.pool_cap = sg.sub_cap * NSUB;
-      fast.push_back(l); sg.pool_off = pool_entries; pool_entries += sg.pool_cap;
+      // the slot of a chunk holds the expected candidates with ~5 sigma to spare; chunks that hold more
+      // (clustered large values) spill to an overflow pool sized for several times all candidates
+      fast.push_back(l);
+      sg.slot_off = slot_elems; slot_elems += static_cast<uint64_t>(sg.nwt) * sg.lpc * 2;
+      sg.ovf_cap = static_cast<uint32_t>(std::min<double>(n, 8.0 * sg.k + 16384.0));
+      sg.ovf_off = ovf_entries; ovf_entries += sg.ovf_cap;
     }
   }
   const uint32_t NWT = static_cast<uint32_t>(nwt64);
@@ -1120,15 +1221,16 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   // one slab, carved; the part that must be zero between kernels comes first
   uint64_t bytes = 0;
   auto carve = [&](uint64_t n) { const uint64_t o = bytes; bytes = align_up(bytes + n, 256); return o; };
-  const uint64_t o_hist = carve(4ull * 3 * HBINS * U), o_sub = carve(4ull * NSUB * U);
+  const uint64_t o_hist = carve(4ull * 3 * HBINS * U), o_ctr = carve(4ull * CTR_LINES * PAD * U);
   const uint64_t o_acc = carve(8ull * ACC_SLOTS * U), o_status = carve(8);
   const uint64_t zero_bytes = bytes;
   const uint64_t o_segs = carve(sizeof(SegInfo) * L), o_wts = carve(sizeof(WtInfo) * std::max<size_t>(1, wts.size()));
   const uint64_t o_grps = carve(sizeof(GrpInfo) * NGRP), o_sels = carve(sizeof(SelInfo) * NSEL);
   const uint64_t o_nt = carve(sizeof(NormTile) * NNT), o_fast = carve(4ull * std::max<size_t>(1, fast.size()));
   const uint64_t o_units = carve(sizeof(UnitState) * U);
-  const uint64_t o_pool = carve(8ull * std::max<uint64_t>(1, pool_entries) * R);
-  const uint64_t o_rec = carve(8ull * NWT * R), o_cnt = carve(8ull * NWT * R), o_gcnt = carve(8ull * NGRP * R);
+  const uint64_t o_slots = carve(8ull * std::max<uint64_t>(2, slot_elems) * R);
+  const uint64_t o_ovf = carve(8ull * std::max<uint64_t>(1, ovf_entries) * R);
+  const uint64_t o_cnt = carve(8ull * NWT * R), o_gcnt = carve(8ull * NGRP * R);
   const uint64_t o_si = carve(4ull * K * R), o_sv = carve(4ull * K * R), o_sc = carve(4ull * K * R);
   const uint64_t o_blk = carve(4ull * QB * R), o_pre = carve(4ull * (QB + 1) * R);
   const uint64_t o_vi = carve(4ull * K * R), o_vc = carve(4ull * K * R);
@@ -1157,10 +1259,11 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.ntiles = reinterpret_cast<const NormTile*>(base + o_nt);
   c.fast_segs = reinterpret_cast<const uint32_t*>(base + o_fast);
   c.units = reinterpret_cast<UnitState*>(base + o_units);
-  c.pool = reinterpret_cast<uint2*>(base + o_pool); c.pool_stride = std::max<uint64_t>(1, pool_entries);
-  c.wt_rec = reinterpret_cast<uint2*>(base + o_rec); c.wt_cnt = reinterpret_cast<uint2*>(base + o_cnt);
+  c.slots = reinterpret_cast<uint2*>(base + o_slots); c.slot_stride = std::max<uint64_t>(2, slot_elems);
+  c.ovf = reinterpret_cast<uint2*>(base + o_ovf); c.ovf_stride = std::max<uint64_t>(1, ovf_entries);
+  c.wt_cnt = reinterpret_cast<uint2*>(base + o_cnt);
   c.grp_cnt = reinterpret_cast<uint2*>(base + o_gcnt);
-  c.hist = reinterpret_cast<uint32_t*>(base + o_hist); c.sub_cnt = reinterpret_cast<uint32_t*>(base + o_sub);
+  c.hist = reinterpret_cast<uint32_t*>(base + o_hist); c.ctr = reinterpret_cast<uint32_t*>(base + o_ctr);
   c.norm_acc = reinterpret_cast<uint64_t*>(base + o_acc);
   c.sel_idx = reinterpret_cast<uint32_t*>(base + o_si); c.sel_val = reinterpret_cast<uint32_t*>(base + o_sv);
   c.sel_code = reinterpret_cast<uint32_t*>(base + o_sc);
@@ -1172,8 +1275,8 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.nfast = static_cast<uint32_t>(fast.size()); c.s = s; c.w_idx = w_idx; c.w_lev = w_lev; c.w_val = w_val;
   c.sparsifier = cfg->sparsifier; c.quantizer = cfg->quantizer;
   c.cap_words = static_cast<uint32_t>(ctx->capacity / 4);
-  ctx->one.start = 0; ctx->one.size = segs[0].size; ctx->one.pool_off = 0; ctx->one.sub_cap = segs[0].sub_cap;
-  ctx->one.wt_base = 0;
+  ctx->one.start = 0; ctx->one.size = segs[0].size; ctx->one.slot_off = 0; ctx->one.ovf_off = 0;
+  ctx->one.lpc = segs[0].lpc ? segs[0].lpc : 8; ctx->one.ovf_cap = segs[0].ovf_cap;
   k_init<<<dim3(static_cast<uint32_t>((U + 255) / 256)), 256, 0, ctx->stream>>>(c, static_cast<uint32_t>(U));
   if (hipStreamSynchronize(ctx->stream) != hipSuccess) {
     (void)hipFree(ctx->slab); (void)hipHostFree(ctx->h_status); delete ctx; return QSL_ERR_DEVICE;
@@ -1207,8 +1310,8 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   const DevCtx& c = ctx->dc;
   hipStream_t st = ctx->stream;
   if (SPARS == QSL_TOPK && ctx->n_sampled > 0) {
-    k_sample<<<dim3(SAMPLE_BLOCKS, c.nfast, R), 1024, 0, st>>>(c, m, delta);
-    k_sample_scan<<<dim3(c.nfast, R), BLOCK, 0, st>>>(c);
+    k_sample<<<dim3(SAMPLE_BLOCKS, c.nfast, R), BIG, 0, st>>>(c, m, delta);
+    k_sample_scan<<<dim3(c.nfast, R), BIG, 0, st>>>(c);
   }
   const bool timed = ctx->timing != 0;
   if (timed) {
@@ -1222,9 +1325,9 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   else k_stream<SPARS, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, m_out, worker0, round);
   if (timed) { QSL_HIP(hipEventRecord(ctx->ev[ctx->ev_used + 1], st)); ctx->ev_used += 2; }
 
-  k_select<0, SPARS><<<dim3(c.NSEL, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
-  k_select<1, SPARS><<<dim3(c.NSEL, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
-  k_select<2, SPARS><<<dim3(c.NSEL, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
+  k_select<0, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
+  k_select<1, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
+  k_select<2, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
   k_tile_count<SPARS><<<dim3(c.NGRP, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
   k_tile_write<SPARS><<<dim3(c.NGRP, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
   k_norm<<<dim3(c.NNT, R), BLOCK, 0, st>>>(c);

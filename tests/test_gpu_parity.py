@@ -71,7 +71,7 @@ def test_failed_guess_falls_back(P):
     delta = rng.standard_normal((R, d)).astype(f32)
     n_s = 42.25 * 3.0 / (4.0 * (k / d))                    # the library's sampling plan at alpha = 3
     n_runs = int(np.ceil(n_s / 64.0))
-    starts = (np.arange(n_runs, dtype=np.int64) * d) // n_runs
+    starts = np.arange(n_runs, dtype=np.int64) * (d // n_runs)          # the library samples runs of 64 at this stride
     pos = (starts[:, None] + np.arange(64)[None, :]).ravel()
     delta[:, pos] *= 1000.0
     run, op, m_host, paths = P.run_parity(wl, 1, deltas=[delta])
@@ -81,6 +81,25 @@ def test_failed_guess_falls_back(P):
     delta[:, pos] *= 1e-6
     run, op, m_host, paths = P.run_parity(wl, 1, deltas=[delta])
     print("paths after a low guess:", paths)
+
+
+def test_clustered_candidates_use_the_overflow_pool(P):
+    # most of the large values sit in a few chunks of 1024 coordinates: their slots cannot hold them,
+    # they spill to the overflow pool, and the unit still runs on the single-pass path
+    d, k, R = 1_000_003, 1000, 2
+    rng = np.random.default_rng(23)
+    for sp, qz, s in [(W.TOPK, W.QSGD, 16), (W.TOPK, W.SIGN_L1, 1)]:
+        wl = custom(d, [0, d], [k], s, sp, qz, R)
+        deltas = []
+        for t in range(2):
+            delta = rng.standard_normal((R, d)).astype(f32)
+            for r in range(R):
+                delta[r, 5_000:5_700] *= 50.0                  # 700 coordinates of one chunk-and-a-bit
+                delta[r, 777_000:777_040] *= 80.0
+                hot = rng.choice(d, 300, replace=False)
+                delta[r, hot] *= 30.0
+            deltas.append(delta)
+        P.run_parity(wl, 2, deltas=deltas, expect_path=0)
 
 
 # ---------------------------------------------------------------------------------------------
