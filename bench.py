@@ -20,6 +20,10 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
 ALGO_BYTES_PER_COORD = 12       # read m, read Delta, write m': what the method itself must move
+# HBM bytes per k_stream launch measured with rocprofv3 (FETCH_SIZE and WRITE_SIZE, each scaled by what the
+# counter reads for a 1 GiB device copy): profiles/k_stream_cfg2_hbm_traffic.txt.  Only for the configuration
+# that was profiled.
+MEASURED_TRAFFIC_BYTES = {2: 2_527_400_000}
 
 
 def main():
@@ -30,6 +34,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (2 = headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rounds", type=int, default=2)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the R workers are a batch on one device); "
@@ -65,6 +71,12 @@ def main():
         q.compress(m, deltas[t % n_buf], m, 0, t, msg, msg_bits)
         q.aggregate(msg, x, -1.0 / R, accumulate=True)     # x <- x - (1/R) sum_r g^(r)
 
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
     for t in range(args.warmup):
         step(t)
     torch.cuda.synchronize()
@@ -85,7 +97,8 @@ def main():
     avg_stream_s = stream_ms / 1e3 / max(1, launches)
     achieved = ALGO_BYTES_PER_COORD * R * d / avg_stream_s / 1e9 if launches else None
     roofline = {"bound": "hbm", "kernel": "k_stream", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": (achieved / HBM_PEAK_GBS) if achieved else None, "traffic": None,
+                "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
                 "avg_launch_us": avg_stream_s * 1e6, "launches": launches,
                 "algorithmic_bytes_per_launch": ALGO_BYTES_PER_COORD * R * d}
 

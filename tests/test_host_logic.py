@@ -1,0 +1,125 @@
+"""CPU-only checks of the host side: the C-ABI library loads and exports what include/qsl.h declares,
+argument errors are caught before any GPU work, the workload generators are deterministic, and
+bench.py refuses more than one GPU."""
+import ctypes as C
+import os
+import re
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+from paper_1906_02367_amd import workloads as W  # noqa: E402
+from paper_1906_02367_amd.build import LIB_PATH  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(LIB_PATH):
+        from paper_1906_02367_amd import build
+        build.build()
+    return C.CDLL(LIB_PATH)
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "qsl.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(qsl_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(lib):
+    names = declared_functions()
+    assert {"qsl_compress", "qsl_error_update", "qsl_aggregate", "qsl_bits_sent", "qsl_create"} <= set(names)
+    for name in names:
+        assert getattr(lib, name) is not None, name
+
+
+def test_binding_lists_the_same_entry_points():
+    src = open(os.path.join(ROOT, "paper_1906_02367_amd", "binding.py")).read()
+    listed = set(re.findall(r'"(qsl_[a-z_]+)"', src))
+    assert set(declared_functions()) <= listed
+
+
+class Config(C.Structure):
+    _fields_ = [("d", C.c_uint64), ("num_segments", C.c_uint32), ("seg_offset", C.POINTER(C.c_uint64)),
+                ("seg_k", C.POINTER(C.c_uint32)), ("s", C.c_uint32), ("sparsifier", C.c_uint32),
+                ("quantizer", C.c_uint32), ("seed", C.c_uint64), ("max_workers", C.c_uint32), ("flags", C.c_uint32)]
+
+
+def make_cfg(d, off, k, s=16, sp=0, qz=0, R=1):
+    off_a = (C.c_uint64 * len(off))(*off)
+    k_a = (C.c_uint32 * len(k))(*k)
+    cfg = Config(d, len(k), off_a, k_a, s, sp, qz, 1, R, 0)
+    cfg._keep = (off_a, k_a)
+    return cfg
+
+
+@pytest.mark.parametrize("kwargs", [
+    dict(d=0, off=[0, 0], k=[1]),                      # empty vector
+    dict(d=100, off=[0, 100], k=[0]),                  # k = 0
+    dict(d=100, off=[0, 100], k=[101]),                # k > d
+    dict(d=100, off=[1, 100], k=[5]),                  # offsets do not start at 0
+    dict(d=100, off=[0, 60, 50, 100], k=[1, 1, 1]),    # offsets not increasing
+    dict(d=100, off=[0, 100], k=[5], s=0),             # no quantisation levels
+    dict(d=100, off=[0, 100], k=[5], s=40000),         # too many levels
+    dict(d=100, off=[0, 100], k=[5], sp=2),            # unknown sparsifier
+    dict(d=100, off=[0, 100], k=[5], qz=7),            # unknown quantiser
+    dict(d=100, off=[0, 100], k=[5], R=0),             # no workers
+    dict(d=1 << 32, off=[0, 1 << 32], k=[5]),          # d out of range
+])
+def test_invalid_configurations_are_rejected_before_any_gpu_work(lib, kwargs):
+    lib.qsl_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(Config), C.c_void_p]
+    lib.qsl_create.restype = C.c_int
+    ctx = C.c_void_p()
+    cfg = make_cfg(**kwargs)
+    assert lib.qsl_create(C.byref(ctx), C.byref(cfg), None) == 1          # QSL_ERR_INVALID_ARG
+    assert not ctx.value
+
+
+def test_null_arguments_and_status_strings(lib):
+    lib.qsl_status_string.argtypes = [C.c_int]
+    lib.qsl_status_string.restype = C.c_char_p
+    assert lib.qsl_status_string(0) == b"ok" and b"non-finite" in lib.qsl_status_string(3)
+    lib.qsl_compress.restype = C.c_int
+    assert lib.qsl_compress(None, None, None, None, 0, 1, 0, None, None, None, None) == 1
+    lib.qsl_msg_capacity_bytes.restype = C.c_size_t
+    lib.qsl_msg_capacity_bytes.argtypes = [C.c_void_p]
+    assert lib.qsl_msg_capacity_bytes(None) == 0
+    lib.qsl_destroy.argtypes = [C.c_void_p]
+    assert lib.qsl_destroy(None) == 1
+
+
+def test_workload_tables():
+    for cfg, (R, d, K) in {1: (2, 65_536, 655), 2: (8, 25_557_032, 25_557), 3: (8, 25_557_032, 255_570),
+                           5: (4, 1 << 28, 26_844)}.items():
+        wl = W.config(cfg)
+        assert (wl.R, wl.d, wl.K, wl.L) == (R, d, K, 1)
+    wl = W.config(4)
+    sizes = np.diff(wl.seg_offset.astype(np.int64))
+    assert wl.L == 160 and sizes.sum() == 25_557_032 and sizes.min() >= 64 and sizes.max() <= 2_400_001 * 1.2
+    assert np.array_equal(wl.seg_k, (sizes + 999) // 1000)
+    a, b = W.config(4), W.config(4)
+    assert np.array_equal(a.seg_offset, b.seg_offset)
+
+
+def test_host_generators_are_deterministic_and_shaped():
+    wl = W.config(2, d=10_000, R=3)
+    a = W.delta_all(wl, 4)
+    b = W.delta_all(wl, 4)
+    assert a.shape == (3, 10_000) and a.dtype == np.float32 and np.array_equal(a, b)
+    assert not np.array_equal(a, W.delta_all(wl, 5))
+    assert not np.array_equal(a[0], a[1])
+    # the component shared by the workers: rows are positively correlated after removing the scale
+    sig = W._sigma(wl)
+    z = a / sig
+    assert np.corrcoef(z[0], z[1])[0, 1] > 0.3
+    wl5 = W.config(5, d=20_000, R=1)
+    t = W.delta(wl5, 0, 0)
+    assert np.isfinite(t).all() and np.abs(t).max() > 20 * np.median(np.abs(t))      # heavy tails
+
+
+def test_bench_refuses_more_than_one_gpu():
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert res.returncode != 0 and "ONE GPU" in res.stderr
