@@ -11,7 +11,7 @@
 //                bits, over the candidates -- or over the whole vector when the guess failed or the
 //                unit is too small/dense for guessing (the general path; always exact)
 //   k_tile_count / k_tile_write    ordered compaction of the selected coordinates, ties to the lower index
-//   k_norm       exact ||v_S||_2^2 or ||v_S||_1 (proof of Lemma 1; Lemma 3 with m = 1)
+//                (k_tile_write also accumulates the exact ||v_S||_2^2 or ||v_S||_1: proof of Lemma 1; Lemma 3, m = 1)
 //   k_quantize   QSGD levels (Definition 1, example 1) or signs (Definition 2); error update
 //                m <- v - g on the transmitted coordinates (Algorithm 1, worker line 2)
 //   k_surv_compact, k_pack    the packed message
@@ -47,13 +47,11 @@ using namespace qsl;
 namespace {
 
 constexpr uint32_t CHUNK = 1024;           // coordinates one wave streams: 4 x (64 lanes x 4)
-constexpr uint32_t GROUP = 256;            // chunks per block of the ordered-compaction kernels
 constexpr uint32_t BLOCK = 256;
 constexpr uint32_t HBINS = 4096;           // radix digits: 12 + 12 + 8 bits of the 32-bit rank key
 constexpr uint32_t ACC_SLOTS = 20;         // 32-bit digits of the exact accumulator
-constexpr uint32_t NORM_TILE = 2048;
-constexpr uint32_t SAMPLE_BLOCKS = 16;     // blocks (of 1024 threads) per unit of the sampling kernel
-constexpr uint32_t SELECT_BLOCKS = 16;     // blocks (of 1024 threads) per unit of the selection kernels
+constexpr uint32_t MAX_SAMPLE_BLOCKS = 128; // blocks (of 1024 threads) per unit of the sampling kernel: 16 .. 128
+constexpr uint32_t MAX_SELECT_BLOCKS = 64; // blocks (of 1024 threads) per unit of the selection kernels: 1 .. 64
 constexpr uint32_t BIG = 1024;             // threads of the sampling and selection kernels
 constexpr uint32_t MAX_QB_INLINE = 4096;   // above this many quantise blocks a separate prefix kernel runs
 constexpr uint32_t NSUB = 64;              // candidate counters per unit: chunk t adds to counter t mod 64
@@ -68,23 +66,26 @@ struct SegInfo {
   uint64_t start, size;
   uint64_t slot_off;     // first slot element (uint2) of this segment inside one worker's slot area
   uint64_t ovf_off;      // first entry of this segment inside one worker's overflow pool
+  uint64_t d0_off;       // first entry of this segment inside one worker's dense candidate lists
   uint32_t k, koff;      // koff: first slot in the [K] selected arrays
-  uint32_t wt_base, nwt; // chunks: index of the first one in per-worker arrays, how many
-  uint32_t grp_base, ngrp;
+  uint32_t nwt;          // chunks of 1024 coordinates
+  uint32_t d0_cap;       // entries of the dense candidate list
+  uint32_t wc_base;      // first per-wave counter of this segment (per worker)
+  uint32_t cb_base, ncb; // compaction blocks: index of the first one (per worker), how many
+  uint32_t nsamp;        // blocks of this unit in the sampling kernel
   uint32_t mode;         // PATH_FAST or PATH_GENERAL, decided on the host from (size, k)
-  uint32_t lpc;          // slot size: lpc * 16 bytes per chunk (8: one 128-byte line, 16: two lines)
+  uint32_t lpc;          // slot size: lpc * 16 bytes per chunk (4: 64 bytes, 8: one 128-byte line, 16: two lines)
   uint32_t ovf_cap;      // entries of the overflow pool
   uint32_t n_runs;       // sample: runs of 64 consecutive coordinates
   uint32_t r_s;          // sample rank that defines the guess
   uint32_t T_static;     // Rand_k: analytic guess
   uint32_t nsel;         // blocks of this unit in the selection kernels
-  uint32_t nnorm;        // norm tiles
+  uint32_t pad;
 };
 
 struct WtInfo { uint32_t seg, chunk, pad0, pad1; };                 // one chunk (multi-segment contexts only)
-struct GrpInfo { uint32_t seg, first_wt, nwt, pad; };               // one group of chunks (inside a unit)
 struct SelInfo { uint32_t seg, j, pad0, pad1; };                    // one block of a selection kernel
-struct NormTile { uint32_t seg, first, count, pad; };
+struct CbInfo { uint32_t seg, b, pad0, pad1; };                     // one compaction block
 
 // Every field is written by exactly one kernel of a call and read only by later kernels.
 struct UnitState {
@@ -100,13 +101,14 @@ struct UnitState {
 };
 
 struct DevCtx {
-  const SegInfo* segs; const WtInfo* wts; const GrpInfo* grps; const SelInfo* sels; const NormTile* ntiles;
+  const SegInfo* segs; const WtInfo* wts; const SelInfo* sels; const CbInfo* cbs;
   const uint32_t* fast_segs;
   UnitState* units;
   uint2* slots; uint64_t slot_stride;   // per worker: one slot (lpc * 2 elements) per chunk of every fast segment
   uint2* ovf; uint64_t ovf_stride;      // per worker: overflow pools, for chunks with more candidates than a slot holds
-  uint2* wt_cnt;        // [R][NWT]: (#key > tau, #key == tau) of the chunk
-  uint2* grp_cnt;       // [R][NGRP]: the same per group of chunks
+  uint2* d0; uint32_t* d0_key; uint64_t d0_stride;   // per worker: dense, coordinate-ordered candidate lists (+ keys, Rand_k)
+  uint32_t* wave_cnt;   // [R][NWC]: candidates met by each wave of k_select<0>
+  uint2* cb_cnt;        // [R][NCB]: (#key > tau, #key == tau) of each compaction block
   uint32_t* hist;       // [U][3][HBINS], one histogram per radix digit; all zero between calls
   uint32_t* ctr;        // [U][CTR_LINES][PAD]; word 0 of each line is a counter; all zero between calls
   uint64_t* norm_acc;   // [U][ACC_SLOTS]; all zero between calls
@@ -116,7 +118,7 @@ struct DevCtx {
   uint32_t* surv_idx; uint32_t* surv_code;                    // [R][K]
   uint32_t* status;
   uint64_t d, seed;
-  uint32_t L, K, NWT, NGRP, NSEL, NNT, QB, nfast, s, w_idx, w_lev, w_val, sparsifier, quantizer, cap_words;
+  uint32_t L, K, NWT, NSEL, NCB, NWC, QB, nfast, s, w_idx, w_lev, w_val, sparsifier, quantizer, cap_words;
 };
 
 __device__ __forceinline__ uint32_t key_of_value(uint32_t vbits) { return (vbits & 0x7FFFFFFFu) << 1; }
@@ -198,11 +200,12 @@ __global__ __launch_bounds__(BIG) void k_sample(DevCtx c, const float* m, const 
   __shared__ uint32_t lh[HBINS];
   const uint32_t seg = c.fast_segs[blockIdx.y], w = blockIdx.z;
   const SegInfo sg = c.segs[seg];
+  if (blockIdx.x >= sg.nsamp) return;
   for (uint32_t i = threadIdx.x; i < HBINS; i += BIG) lh[i] = 0;
   __syncthreads();
   const uint64_t row = static_cast<uint64_t>(w) * c.d + sg.start;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const uint32_t nwaves = SAMPLE_BLOCKS * (BIG / 64);
+  const uint32_t nwaves = sg.nsamp * (BIG / 64);
   const uint64_t stride = sg.size / sg.n_runs;           // >= 64: the runs do not overlap
   for (uint32_t run0 = blockIdx.x * (BIG / 64) + wave; run0 < sg.n_runs; run0 += 4 * nwaves) {
     float a[4], b[4]; bool ok[4];
@@ -379,34 +382,45 @@ __global__ __launch_bounds__(BLOCK) void k_stream(DevCtx c, StreamSeg one, const
 // i.e. 64 / lpc whole slots; lane l holds elements 2 (l mod lpc) and 2 (l mod lpc) + 1 of its slot.
 // ------------------------------------------------------------------------------------------------
 struct SlotRow {
-  uint32_t chunk;        // chunk this lane's slot belongs to
-  uint32_t count;        // candidates of that chunk (0 if the chunk does not exist)
+  uint32_t count;        // candidates of this lane's chunk (0 if the chunk does not exist)
   uint32_t ovf_at;       // where they are in the overflow pool, if count > cap
-  bool lead;             // this lane holds the slot's header
-  bool inl;              // the candidates are in the slot itself
+  uint32_t n;            // candidates this lane is responsible for: 0..2 of its own elements, or all
+                         // `count` entries in the overflow pool if it holds the header of such a chunk
+  bool spill;            // n entries are read from the overflow pool
   bool has0, has1;       // this lane's first / second element is a candidate
   uint32_t idx0, bits0, idx1, bits1;
 };
 
-__device__ __forceinline__ SlotRow read_slot_row(const uint2* slots, uint32_t lpc, uint32_t nwt, uint64_t row) {
+__device__ __forceinline__ SlotRow read_slot_row(const uint2* slots, uint32_t lpc, uint32_t nwt, uint64_t row,
+                                                 uint64_t nrows) {
   SlotRow r;
   const uint32_t lane = lane_id();
   const uint32_t sub = lane & (lpc - 1);
-  const uint64_t chunk64 = (row * 64 + lane) / lpc;
-  r.chunk = static_cast<uint32_t>(chunk64);
   uint4 q = make_uint4(0, 0, 0, 0);
-  if (chunk64 < nwt) q = reinterpret_cast<const uint4*>(slots)[row * 64 + lane];
+  if (row < nrows && (row * 64 + lane) / lpc < nwt) q = reinterpret_cast<const uint4*>(slots)[row * 64 + lane];
   const uint32_t leader = lane & ~(lpc - 1);
   r.count = __shfl(q.x, leader, WAVE);
   r.ovf_at = __shfl(q.y, leader, WAVE);
-  r.lead = sub == 0;
   const uint32_t cap = lpc * 2 - 1;
-  r.inl = r.count <= cap;
+  const bool inl = r.count <= cap;
   const uint32_t e0 = sub * 2;                    // element numbers of this lane; element e holds candidate e - 1
-  r.has0 = r.inl && e0 >= 1 && e0 <= r.count;
-  r.has1 = r.inl && e0 + 1 <= r.count;
+  r.has0 = inl && e0 >= 1 && e0 <= r.count;
+  r.has1 = inl && e0 + 1 <= r.count;
+  r.spill = !inl && sub == 0;
+  r.n = r.spill ? r.count : (r.has0 ? 1u : 0u) + (r.has1 ? 1u : 0u);
   r.idx0 = q.x; r.bits0 = q.y; r.idx1 = q.z; r.bits1 = q.w;
   return r;
+}
+
+__device__ __forceinline__ uint32_t wave_exclusive_scan32(uint32_t x, uint32_t* total) {
+  uint32_t inc = x;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t y = __shfl_up(inc, o, WAVE);
+    if (lane_id() >= static_cast<uint32_t>(o)) inc += y;
+  }
+  *total = __shfl(inc, 63, WAVE);
+  return inc - x;
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -422,6 +436,12 @@ __device__ __forceinline__ bool level_bin(uint32_t key, uint32_t prefix, uint32_
 // Digit LEVEL of the k-th largest key.  The blocks of a unit build the digit's histogram (LDS, then
 // a few global atomics per bin); which bin the previous digit fell in is recomputed by every block
 // from the previous kernel's histogram.
+//   fast unit, digit 0: reads the slot rows (every wave a contiguous range) and leaves the number of
+//                       candidates each wave met;
+//   fast unit, digit 1: reads them again and writes all candidates, in coordinate order, into the
+//                       unit's dense list (the offset of a wave = sum of the earlier waves' counts);
+//   fast unit, digit 2: reads the dense list;
+//   general path:       reads v.
 template <int LEVEL, int SPARS>
 __global__ __launch_bounds__(BIG) void k_select(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
   __shared__ uint32_t lh[HBINS];
@@ -440,12 +460,12 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, const float* v, uint32
   __syncthreads();
   uint32_t path, prefix = 0, k_rem = sg.k;
   if (LEVEL == 0) {
-    // a guess that produced too few candidates, or ran out of overflow room, is discarded here
+    // a guess that produced too few candidates, or more than there is room for, is discarded here
     path = us.path;
     if (path == PATH_FAST) {
       uint32_t cand = 0;
       for (uint32_t i = 0; i < NSUB; ++i) cand += s_ctr[i];
-      if (s_ctr[CTR_FAIL] || cand < sg.k) path = PATH_FALLBACK;
+      if (s_ctr[CTR_FAIL] || cand < sg.k || cand > sg.d0_cap) path = PATH_FALLBACK;
       if (threadIdx.x == 0 && si.j == 0) { usp->cand = cand; usp->fell_back = path == PATH_FALLBACK; }
     } else if (threadIdx.x == 0 && si.j == 0) { usp->cand = 0; usp->fell_back = 0; }
     if (threadIdx.x == 0 && si.j == 0) usp->nnz = 0;
@@ -462,28 +482,65 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, const float* v, uint32
     if (threadIdx.x == 0 && si.j == 0) { usp->prefix = prefix; usp->k_rem = k_rem; }
   }
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
-  if (path == PATH_FAST) {
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  if (path == PATH_FAST && LEVEL < 2) {
     const uint2* slots = c.slots + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off;
     const uint2* ovf = c.ovf + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off;
+    uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    uint32_t* wcnt = c.wave_cnt + static_cast<uint64_t>(w) * c.NWC + sg.wc_base;
     const uint64_t nrows = (static_cast<uint64_t>(sg.nwt) * sg.lpc + 63) / 64;
-    const uint32_t nwaves = sg.nsel * (BIG / 64);
-    for (uint64_t row0 = si.j * (BIG / 64) + (threadIdx.x >> 6); row0 < nrows; row0 += 4 * nwaves) {
+    const uint32_t nwaves = sg.nsel * (BIG / 64), gw = si.j * (BIG / 64) + wave;
+    const uint64_t rpw = (nrows + nwaves - 1) / nwaves;
+    const uint64_t r_lo = gw * rpw, r_hi = r_lo + rpw < nrows ? r_lo + rpw : nrows;
+    uint32_t seen = 0;                              // digit 0: candidates this wave met
+    uint32_t off = 0;                               // digit 1: where this wave's candidates go in the dense list
+    if (LEVEL == 1) {
+      uint32_t x = 0;
+      for (uint32_t g = lane; g < gw; g += WAVE) x += wcnt[g];
+      off = wave_sum(x);
+    }
+    for (uint64_t row0 = r_lo; row0 < r_hi; row0 += 4) {
       SlotRow rr[4];                               // four independent accesses in flight; rows past the end read as empty
 #pragma unroll
-      for (int b = 0; b < 4; ++b) rr[b] = read_slot_row(slots, sg.lpc, sg.nwt, row0 + b * nwaves);
+      for (int b = 0; b < 4; ++b) rr[b] = read_slot_row(slots, sg.lpc, sg.nwt, row0 + b, r_hi);
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
         const SlotRow& r = rr[b];
-        uint32_t bin;
-        if (r.has0 && level_bin<LEVEL>(entry_key<SPARS>(r.idx0, r.bits0, rk), prefix, &bin)) atomicAdd(&lh[bin], 1u);
-        if (r.has1 && level_bin<LEVEL>(entry_key<SPARS>(r.idx1, r.bits1, rk), prefix, &bin)) atomicAdd(&lh[bin], 1u);
-        if (r.lead && !r.inl) {
+        uint32_t pos = 0, tot = 0;
+        if (LEVEL == 0) seen += r.n;
+        else { pos = off + wave_exclusive_scan32(r.n, &tot); off += tot; }
+        if (!r.spill) {
+          uint32_t bin;
+          if (r.has0) {
+            const uint32_t key = entry_key<SPARS>(r.idx0, r.bits0, rk);
+            if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
+            if (LEVEL == 1) { d0[pos] = make_uint2(r.idx0, r.bits0); if (SPARS == QSL_RANDK) d0k[pos] = key; ++pos; }
+          }
+          if (r.has1) {
+            const uint32_t key = entry_key<SPARS>(r.idx1, r.bits1, rk);
+            if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
+            if (LEVEL == 1) { d0[pos] = make_uint2(r.idx1, r.bits1); if (SPARS == QSL_RANDK) d0k[pos] = key; }
+          }
+        } else {
           for (uint32_t e = 0; e < r.count; ++e) {
             const uint2 ent = ovf[r.ovf_at + e];
-            if (level_bin<LEVEL>(entry_key<SPARS>(ent.x, ent.y, rk), prefix, &bin)) atomicAdd(&lh[bin], 1u);
+            const uint32_t key = entry_key<SPARS>(ent.x, ent.y, rk);
+            uint32_t bin;
+            if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
+            if (LEVEL == 1) { d0[pos + e] = ent; if (SPARS == QSL_RANDK) d0k[pos + e] = key; }
           }
         }
       }
+    }
+    if (LEVEL == 0) { seen = wave_sum(seen); if (lane == 0) wcnt[gw] = seen; }
+  } else if (path == PATH_FAST) {
+    const uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    const uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    for (uint32_t e = si.j * BIG + threadIdx.x; e < us.cand; e += sg.nsel * BIG) {
+      const uint32_t key = SPARS == QSL_TOPK ? key_of_value(d0[e].y) : d0k[e];
+      uint32_t bin;
+      if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
     }
   } else {
     const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
@@ -498,179 +555,277 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, const float* v, uint32
 }
 
 // ------------------------------------------------------------------------------------------------
-// ordered compaction of the selected coordinates.  A block handles a group of up to 256 chunks of
-// one unit.  Fast units: the waves read slot rows (several chunks per access).  General path: a
-// wave reads one chunk of v at a time.
+// ordered compaction of the selected coordinates, with the exact norm of what is selected.
+//
+// A "compaction block" covers either a tile of 2048 entries of a fast unit's dense candidate list
+// (each thread 8 consecutive entries), or a group of 16 chunks of v on the general path (each wave
+// 4 chunks, a lane 16 coordinates of a chunk).  k_tile_count leaves the number of selected
+// coordinates of every block; k_tile_write sums the earlier blocks' numbers to know where it writes.
+// A fast unit whose guess failed runs the general path with the blocks it has: each takes a
+// contiguous range of groups.
+//
+// Exact norms: every |v| (or v^2) is an integer multiple of 2^-149 (2^-298); its 32-bit digits are
+// added into 64-bit counters; integer addition commutes, so any schedule gives the same sum.
 // ------------------------------------------------------------------------------------------------
+constexpr uint32_t DTILE = 2048;           // dense-list entries per compaction block
+constexpr uint32_t GGROUP = 16;            // chunks per general-path group
+
+struct Thresh { uint32_t tau, need; };
+
+// one chunk of v in registers: 16 coordinates per lane, as two 16-bit masks (key > tau, key == tau)
 template <int SPARS>
-__global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
-  __shared__ uint32_t s_gt[4], s_eq[4];
-  __shared__ uint64_t scratch[17];
-  __shared__ uint32_t result[2];
-  const GrpInfo gi = c.grps[blockIdx.x];
-  const uint32_t w = blockIdx.y;
-  const SegInfo sg = c.segs[gi.seg];
-  const uint64_t u = static_cast<uint64_t>(w) * c.L + gi.seg;
-  UnitState us = c.units[u];
-  us.path = eff_path(us);
-  {  // the last digit, from the histogram k_select<2> left: the threshold key and the tie budget
-    uint32_t above;
-    const uint32_t bin = find_from_top<BLOCK>(c.hist + (u * 3 + 2) * HBINS, us.k_rem, &above, scratch, result, false);
-    us.tau = us.prefix | bin; us.need = us.k_rem - above;
-    if (threadIdx.x == 0 && gi.first_wt == 0) {
-      c.units[u].tau = us.tau; c.units[u].need = us.need; c.units[u].n_gt = sg.k - us.need;
+__device__ __forceinline__ void load_chunk_masks(const float* vp, uint64_t cb, uint64_t size, uint64_t start,
+                                                 const RandKey& rk, Thresh th, f4u* val, uint32_t* gmask,
+                                                 uint32_t* qmask) {
+  const uint32_t lane = lane_id();
+  uint32_t gm = 0, qm = 0;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const uint64_t e = cb + t * 256 + lane * 4;
+    f4u x = {0.f, 0.f, 0.f, 0.f};
+    if (e + 4 <= size) x = *reinterpret_cast<const f4u*>(vp + e);
+    else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) if (e + j < size) x[j] = vp[e + j];
+    }
+    val[t] = x;
+    Words4 rw;
+    if (SPARS == QSL_RANDK) rw = rand_words4(rk, static_cast<uint32_t>(start + e));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t key = SPARS == QSL_TOPK ? key_of_value(__float_as_uint(x[j])) : rw.w[j];
+      const bool inside = e + j < size;
+      gm |= (inside && key > th.tau ? 1u : 0u) << (t * 4 + j);
+      qm |= (inside && key == th.tau ? 1u : 0u) << (t * 4 + j);
     }
   }
-  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
+  *gmask = gm; *qmask = qm;
+}
+
+// digits of |v| (or v^2) into the thread's private accumulator row
+__device__ __forceinline__ void add_digits(uint64_t* mine, uint32_t bits, bool squares) {
+  const uint32_t ab = bits & 0x7FFFFFFFu;
+  const uint32_t ex = ab >> 23, frac = ab & 0x7FFFFFu;
+  const uint32_t M = ex ? (frac | 0x800000u) : frac;       // |v| = M * 2^(max(ex,1) - 150)
+  const uint32_t e1 = ex ? ex : 1u;
+  if (M == 0) return;
+  if (squares) {
+    const uint64_t sq = static_cast<uint64_t>(M) * M;       // < 2^48;  v^2 = sq * 2^(2 e1 - 300)
+    const uint32_t p = 2u * e1 - 2u;                        // bit position above 2^-298
+    const uint32_t q = p >> 5, r = p & 31u;
+    const uint64_t lo = sq << r;                            // low 64 bits of sq * 2^r  (r <= 30)
+    const uint64_t hi = r ? (sq >> (64 - r)) : 0;
+    mine[q] += lo & 0xFFFFFFFFu; mine[q + 1] += lo >> 32; mine[q + 2] += hi;
+  } else {
+    const uint32_t p = e1 - 1u;                             // bit position above 2^-149
+    const uint32_t q = p >> 5, r = p & 31u;
+    const uint64_t sh = static_cast<uint64_t>(M) << r;      // < 2^55
+    mine[q] += sh & 0xFFFFFFFFu; mine[q + 1] += sh >> 32;
+  }
+}
+
+// the general-path groups [g_lo, g_hi) of one unit, by one 256-thread block.
+// WRITE = false: returns (in *tot_gt, *tot_eq, valid in thread 0) how many coordinates of these groups have key > tau / == tau.
+// WRITE = true: writes the selected ones, in coordinate order, starting at ranks (gt0, eq0).
+template <int SPARS, bool WRITE>
+__device__ void general_groups(const DevCtx& c, const SegInfo& sg, const float* vp, const RandKey& rk, Thresh th,
+                               uint32_t g_lo, uint32_t g_hi, uint32_t gt0, uint32_t eq0, uint32_t* oi, uint32_t* ov,
+                               uint64_t* mine, bool squares, uint32_t* s_cnt /*[2][GGROUP + 1]*/,
+                               uint32_t* tot_gt, uint32_t* tot_eq) {
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  uint2* cnt = c.wt_cnt + static_cast<uint64_t>(w) * c.NWT + sg.wt_base;
-  uint32_t tot_gt = 0, tot_eq = 0;                 // per lane; summed over the wave at the end
-  if (us.path == PATH_FAST) {
-    const uint2* slots = c.slots + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off;
-    const uint2* ovf = c.ovf + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off;
-    const uint64_t row0 = static_cast<uint64_t>(gi.first_wt) * sg.lpc / 64;       // first_wt is a multiple of 256
-    const uint32_t nrows = (gi.nwt * sg.lpc + 63) / 64;
-    const uint64_t gmask = (sg.lpc == 16 ? 0xFFFFull : 0xFFull) << (lane & ~(sg.lpc - 1));
-    for (uint32_t i = wave; i < nrows; i += 4) {
-      const SlotRow r = read_slot_row(slots, sg.lpc, sg.nwt, row0 + i);
-      const uint32_t k0 = entry_key<SPARS>(r.idx0, r.bits0, rk), k1 = entry_key<SPARS>(r.idx1, r.bits1, rk);
-      const bool g0 = r.has0 && k0 > us.tau, g1 = r.has1 && k1 > us.tau;
-      const bool q0 = r.has0 && k0 == us.tau, q1 = r.has1 && k1 == us.tau;
-      const uint64_t bg0 = __ballot(g0), bg1 = __ballot(g1), bq0 = __ballot(q0), bq1 = __ballot(q1);
-      uint32_t gt = __popcll(bg0 & gmask) + __popcll(bg1 & gmask);
-      uint32_t eq = __popcll(bq0 & gmask) + __popcll(bq1 & gmask);
-      if (r.lead && !r.inl) {
-        gt = 0; eq = 0;
-        for (uint32_t e = 0; e < r.count; ++e) {
-          const uint2 ent = ovf[r.ovf_at + e];
-          const uint32_t key = entry_key<SPARS>(ent.x, ent.y, rk);
-          gt += key > us.tau; eq += key == us.tau;
+  uint32_t run_gt = gt0, run_eq = eq0;             // ranks at the start of the current group (all threads agree)
+  for (uint32_t g = g_lo; g < g_hi; ++g) {
+    f4u val[4][4]; uint32_t gm[4], qm[4];
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {
+      const uint32_t lc = wave * 4 + q;            // chunk inside the group: a wave takes 4 consecutive ones
+      const uint64_t chunk = static_cast<uint64_t>(g) * GGROUP + lc;
+      gm[q] = 0; qm[q] = 0;
+      if (chunk < sg.nwt) load_chunk_masks<SPARS>(vp, chunk * CHUNK, sg.size, sg.start, rk, th, val[q], &gm[q], &qm[q]);
+      const uint32_t cg = wave_sum(__popc(gm[q])), cq = wave_sum(__popc(qm[q]));
+      if (lane == 0) { s_cnt[lc] = cg; s_cnt[GGROUP + 1 + lc] = cq; }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {                        // exclusive prefix over the 16 chunks, on top of the running ranks
+      uint32_t a = run_gt, b = run_eq;
+      for (uint32_t i = 0; i < GGROUP; ++i) {
+        const uint32_t x = s_cnt[i], y = s_cnt[GGROUP + 1 + i];
+        s_cnt[i] = a; s_cnt[GGROUP + 1 + i] = b; a += x; b += y;
+      }
+      s_cnt[GGROUP] = a; s_cnt[2 * GGROUP + 1] = b;
+    }
+    __syncthreads();
+    if (WRITE) {
+#pragma unroll
+      for (uint32_t q = 0; q < 4; ++q) {
+        if (__ballot((gm[q] | qm[q]) != 0) == 0) continue;          // wave-uniform
+        const uint32_t lc = wave * 4 + q;
+        const uint64_t cb = (static_cast<uint64_t>(g) * GGROUP + lc) * CHUNK;
+        uint32_t base_gt = s_cnt[lc], base_eq = s_cnt[GGROUP + 1 + lc];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const uint32_t gn = (gm[q] >> (t * 4)) & 0xFu, qn = (qm[q] >> (t * 4)) & 0xFu;
+          if (__ballot((gn | qn) != 0) == 0) continue;              // wave-uniform
+          uint32_t bg = 0, bq = 0, tg = 0, tq = 0;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint64_t b1 = __ballot((gn >> j) & 1u), b2 = __ballot((qn >> j) & 1u);
+            bg += popc_below(b1); tg += __popcll(b1); bq += popc_below(b2); tq += __popcll(b2);
+          }
+          uint32_t my_gt = base_gt + bg, my_eq = base_eq + bq;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const bool is_gt = (gn >> j) & 1u, is_eq = (qn >> j) & 1u;
+            if (is_gt || (is_eq && my_eq < th.need)) {
+              const uint32_t pos = my_gt + min(my_eq, th.need);
+              const uint32_t bits = __float_as_uint(val[q][t][j]);
+              oi[pos] = static_cast<uint32_t>(sg.start + cb + t * 256 + lane * 4 + j); ov[pos] = bits;
+              add_digits(mine, bits, squares);
+            }
+            my_gt += is_gt; my_eq += is_eq;
+          }
+          base_gt += tg; base_eq += tq;
         }
       }
-      if (r.lead && r.chunk < sg.nwt) { cnt[r.chunk] = make_uint2(gt, eq); tot_gt += gt; tot_eq += eq; }
     }
-  } else {
-    const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
-    for (uint32_t i = wave; i < gi.nwt; i += 4) {
-      const uint32_t t = gi.first_wt + i;
-      uint32_t gt = 0, eq = 0;
-      const uint64_t lo = static_cast<uint64_t>(t) * CHUNK, hi = lo + CHUNK < sg.size ? lo + CHUNK : sg.size;
-      for (uint64_t e = lo + lane; e < hi; e += WAVE) {
-        const uint32_t key = coord_key<SPARS>(vp, e, sg.start, rk);
-        gt += key > us.tau; eq += key == us.tau;
-      }
-      gt = wave_sum(gt); eq = wave_sum(eq);
-      if (lane == 0) { cnt[t] = make_uint2(gt, eq); tot_gt += gt; tot_eq += eq; }
-    }
+    run_gt = s_cnt[GGROUP]; run_eq = s_cnt[2 * GGROUP + 1];
+    __syncthreads();                               // s_cnt is reused by the next group
   }
-  tot_gt = wave_sum(tot_gt); tot_eq = wave_sum(tot_eq);
-  if (lane == 0) { s_gt[wave] = tot_gt; s_eq[wave] = tot_eq; }
-  __syncthreads();
-  if (threadIdx.x == 0)
-    c.grp_cnt[static_cast<uint64_t>(w) * c.NGRP + sg.grp_base + gi.first_wt / GROUP] =
-        make_uint2(s_gt[0] + s_gt[1] + s_gt[2] + s_gt[3], s_eq[0] + s_eq[1] + s_eq[2] + s_eq[3]);
+  *tot_gt = run_gt - gt0; *tot_eq = run_eq - eq0;
+}
+
+// the threshold key and the tie budget, from the histogram of the last digit
+__device__ __forceinline__ Thresh last_digit(const DevCtx& c, uint64_t u, const UnitState& us, uint64_t* scratch,
+                                             uint32_t* result) {
+  uint32_t above;
+  const uint32_t bin = find_from_top<BLOCK>(c.hist + (u * 3 + 2) * HBINS, us.k_rem, &above, scratch, result, false);
+  Thresh th; th.tau = us.prefix | bin; th.need = us.k_rem - above;
+  return th;
+}
+
+// range of general-path groups a compaction block of a fallen-back fast unit takes
+__device__ __forceinline__ void fallback_range(const SegInfo& sg, uint32_t b, uint32_t* g_lo, uint32_t* g_hi) {
+  const uint64_t ngg = (static_cast<uint64_t>(sg.nwt) + GGROUP - 1) / GGROUP;
+  *g_lo = static_cast<uint32_t>(ngg * b / sg.ncb); *g_hi = static_cast<uint32_t>(ngg * (b + 1) / sg.ncb);
+}
+
+template <int SPARS>
+__global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
+  __shared__ uint32_t s_cnt[2 * GGROUP + 2], s_red[8], result[2];
+  __shared__ uint64_t scratch[17];
+  const CbInfo cb = c.cbs[blockIdx.x];
+  const uint32_t w = blockIdx.y;
+  const SegInfo sg = c.segs[cb.seg];
+  const uint64_t u = static_cast<uint64_t>(w) * c.L + cb.seg;
+  const UnitState us = c.units[u];
+  const uint32_t path = eff_path(us);
+  const Thresh th = last_digit(c, u, us, scratch, result);
+  if (threadIdx.x == 0 && cb.b == 0) { c.units[u].tau = th.tau; c.units[u].need = th.need; c.units[u].n_gt = sg.k - th.need; }
+  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
+  uint2* out = c.cb_cnt + static_cast<uint64_t>(w) * c.NCB + sg.cb_base + cb.b;
+  if (path == PATH_FAST) {
+    const uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    const uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    uint32_t gt = 0, eq = 0;
+    const uint32_t e0 = cb.b * DTILE + threadIdx.x * 8;
+#pragma unroll
+    for (uint32_t i = 0; i < 8; ++i) {
+      if (e0 + i < us.cand) {
+        const uint32_t key = SPARS == QSL_TOPK ? key_of_value(d0[e0 + i].y) : d0k[e0 + i];
+        gt += key > th.tau; eq += key == th.tau;
+      }
+    }
+    gt = wave_sum(gt); eq = wave_sum(eq);
+    if (lane_id() == 0) { s_red[threadIdx.x >> 6] = gt; s_red[4 + (threadIdx.x >> 6)] = eq; }
+    __syncthreads();
+    if (threadIdx.x == 0) *out = make_uint2(s_red[0] + s_red[1] + s_red[2] + s_red[3], s_red[4] + s_red[5] + s_red[6] + s_red[7]);
+    return;
+  }
+  uint32_t g_lo = cb.b, g_hi = cb.b + 1;
+  if (us.path == PATH_FAST) fallback_range(sg, cb.b, &g_lo, &g_hi);
+  uint32_t tg = 0, tq = 0;
+  general_groups<SPARS, false>(c, sg, v + static_cast<uint64_t>(w) * c.d + sg.start, rk, th, g_lo, g_hi, 0, 0, nullptr,
+                               nullptr, nullptr, false, s_cnt, &tg, &tq);
+  if (threadIdx.x == 0) *out = make_uint2(tg, tq);
 }
 
 template <int SPARS>
 __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
-  __shared__ uint32_t s_gt[GROUP], s_eq[GROUP];
-  __shared__ uint64_t scratch[17];
-  __shared__ uint64_t s_part[4];
-  const GrpInfo gi = c.grps[blockIdx.x];
+  __shared__ uint64_t acc[BLOCK * (ACC_SLOTS + 1)];
+  __shared__ uint32_t s_cnt[2 * GGROUP + 2];
+  __shared__ uint64_t scratch[17], s_part[4];
+  const CbInfo cb = c.cbs[blockIdx.x];
   const uint32_t w = blockIdx.y;
-  const SegInfo sg = c.segs[gi.seg];
-  const uint64_t u = static_cast<uint64_t>(w) * c.L + gi.seg;
-  UnitState us = c.units[u];
-  us.path = eff_path(us);
+  const SegInfo sg = c.segs[cb.seg];
+  const uint64_t u = static_cast<uint64_t>(w) * c.L + cb.seg;
+  const UnitState us = c.units[u];
+  const uint32_t path = eff_path(us);
+  Thresh th; th.tau = us.tau; th.need = us.need;
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const uint2* cnt = c.wt_cnt + static_cast<uint64_t>(w) * c.NWT + sg.wt_base;
-  // how many selected coordinates precede this group: the sum of the earlier groups' counts
+  const bool squares = c.quantizer == QSL_QSGD;
+  uint64_t* mine = acc + threadIdx.x * (ACC_SLOTS + 1);
+#pragma unroll
+  for (uint32_t i = 0; i < ACC_SLOTS; ++i) mine[i] = 0;
+  // how many selected coordinates precede this block: the sum of the unit's earlier blocks' counts
   {
-    const uint2* gc = c.grp_cnt + static_cast<uint64_t>(w) * c.NGRP + sg.grp_base;
-    const uint32_t g = gi.first_wt / GROUP;
+    const uint2* cc = c.cb_cnt + static_cast<uint64_t>(w) * c.NCB + sg.cb_base;
     uint64_t x = 0;
-    for (uint32_t i = threadIdx.x; i < g; i += BLOCK) { const uint2 p = gc[i]; x += (static_cast<uint64_t>(p.y) << 32) | p.x; }
+    for (uint32_t i = threadIdx.x; i < cb.b; i += BLOCK) { const uint2 p = cc[i]; x += (static_cast<uint64_t>(p.y) << 32) | p.x; }
     x = wave_sum64(x);
     if (lane == 0) s_part[wave] = x;
   }
   __syncthreads();
-  {  // exclusive prefix of this group's chunk counts, on top of the group's own prefix
-    uint2 p = make_uint2(0, 0);
-    if (threadIdx.x < gi.nwt) p = cnt[gi.first_wt + threadIdx.x];
-    uint64_t total;
-    const uint64_t ex = block_exclusive_scan64((static_cast<uint64_t>(p.y) << 32) | p.x, scratch, &total) +
-                        s_part[0] + s_part[1] + s_part[2] + s_part[3];
-    s_gt[threadIdx.x] = static_cast<uint32_t>(ex); s_eq[threadIdx.x] = static_cast<uint32_t>(ex >> 32);
-  }
-  __syncthreads();
+  const uint64_t before = s_part[0] + s_part[1] + s_part[2] + s_part[3];
+  const uint32_t gt0 = static_cast<uint32_t>(before), eq0 = static_cast<uint32_t>(before >> 32);
   uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
   uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
-  if (us.path == PATH_FAST) {
-    const uint2* slots = c.slots + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off;
-    const uint2* ovf = c.ovf + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off;
-    const uint64_t row0 = static_cast<uint64_t>(gi.first_wt) * sg.lpc / 64;
-    const uint32_t nrows = (gi.nwt * sg.lpc + 63) / 64;
-    const uint64_t gmask = (sg.lpc == 16 ? 0xFFFFull : 0xFFull) << (lane & ~(sg.lpc - 1));
-    const uint64_t below = gmask & ((1ull << lane) - 1ull);             // lanes of my slot before me
-    for (uint32_t i = wave; i < nrows; i += 4) {
-      const SlotRow r = read_slot_row(slots, sg.lpc, sg.nwt, row0 + i);
-      if (r.chunk >= sg.nwt) continue;             // only the last row of a unit has such lanes; no ballot below needs them
-      const uint32_t k0 = entry_key<SPARS>(r.idx0, r.bits0, rk), k1 = entry_key<SPARS>(r.idx1, r.bits1, rk);
-      const bool g0 = r.has0 && k0 > us.tau, g1 = r.has1 && k1 > us.tau;
-      const bool q0 = r.has0 && k0 == us.tau, q1 = r.has1 && k1 == us.tau;
-      const uint64_t bg0 = __ballot(g0), bg1 = __ballot(g1), bq0 = __ballot(q0), bq1 = __ballot(q1);
-      const uint32_t li = r.chunk - gi.first_wt;
-      const uint32_t gt_base = s_gt[li], eq_base = s_eq[li];
-      // candidates of a slot are ordered: lane by lane, first element before second
-      const uint32_t gt0 = gt_base + __popcll(bg0 & below) + __popcll(bg1 & below);
-      const uint32_t eq0 = eq_base + __popcll(bq0 & below) + __popcll(bq1 & below);
-      if (g0 || (q0 && eq0 < us.need)) { const uint32_t pos = gt0 + min(eq0, us.need); oi[pos] = r.idx0; ov[pos] = r.bits0; }
-      const uint32_t gt1 = gt0 + (g0 ? 1u : 0u), eq1 = eq0 + (q0 ? 1u : 0u);
-      if (g1 || (q1 && eq1 < us.need)) { const uint32_t pos = gt1 + min(eq1, us.need); oi[pos] = r.idx1; ov[pos] = r.bits1; }
-      if (r.lead && !r.inl) {
-        uint32_t gt = gt_base, eq = eq_base;
-        for (uint32_t e = 0; e < r.count; ++e) {
-          const uint2 ent = ovf[r.ovf_at + e];
-          const uint32_t key = entry_key<SPARS>(ent.x, ent.y, rk);
-          const bool g = key > us.tau, q = key == us.tau;
-          if (g || (q && eq < us.need)) { const uint32_t pos = gt + min(eq, us.need); oi[pos] = ent.x; ov[pos] = ent.y; }
-          gt += g; eq += q;
-        }
+  if (path == PATH_FAST) {
+    const uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    const uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    const uint32_t e0 = cb.b * DTILE + threadIdx.x * 8;
+    uint2 ent[8]; uint32_t gm = 0, qm = 0;
+#pragma unroll
+    for (uint32_t i = 0; i < 8; ++i) {
+      ent[i] = make_uint2(0, 0);
+      if (e0 + i < us.cand) {
+        ent[i] = d0[e0 + i];
+        const uint32_t key = SPARS == QSL_TOPK ? key_of_value(ent[i].y) : d0k[e0 + i];
+        gm |= (key > th.tau ? 1u : 0u) << i; qm |= (key == th.tau ? 1u : 0u) << i;
       }
     }
-    return;
+    uint64_t total;
+    const uint64_t ex = block_exclusive_scan64((static_cast<uint64_t>(__popc(qm)) << 32) | __popc(gm), scratch, &total);
+    uint32_t my_gt = gt0 + static_cast<uint32_t>(ex), my_eq = eq0 + static_cast<uint32_t>(ex >> 32);
+#pragma unroll
+    for (uint32_t i = 0; i < 8; ++i) {
+      const bool is_gt = (gm >> i) & 1u, is_eq = (qm >> i) & 1u;
+      if (is_gt || (is_eq && my_eq < th.need)) {
+        const uint32_t pos = my_gt + min(my_eq, th.need);
+        oi[pos] = ent[i].x; ov[pos] = ent[i].y;
+        add_digits(mine, ent[i].y, squares);
+      }
+      my_gt += is_gt; my_eq += is_eq;
+    }
+  } else {
+    uint32_t g_lo = cb.b, g_hi = cb.b + 1;
+    if (us.path == PATH_FAST) fallback_range(sg, cb.b, &g_lo, &g_hi);
+    uint32_t tg, tq;
+    general_groups<SPARS, true>(c, sg, v + static_cast<uint64_t>(w) * c.d + sg.start, rk, th, g_lo, g_hi, gt0, eq0, oi, ov,
+                                mine, squares, s_cnt, &tg, &tq);
   }
-  const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
-  for (uint32_t i = wave; i < gi.nwt; i += 4) {
-    const uint64_t lo = static_cast<uint64_t>(gi.first_wt + i) * CHUNK;
-    const uint32_t n_items = static_cast<uint32_t>((lo + CHUNK < sg.size ? lo + CHUNK : sg.size) - lo);
-    uint32_t gt_before = s_gt[i], eq_before = s_eq[i];
-    for (uint32_t j0 = 0; j0 < n_items; j0 += WAVE) {
-      const uint32_t j = j0 + lane;
-      bool is_gt = false, is_eq = false;
-      uint32_t idx = 0, bits = 0;
-      if (j < n_items) {
-        idx = static_cast<uint32_t>(sg.start + lo + j); bits = __float_as_uint(vp[lo + j]);
-        const uint32_t key = SPARS == QSL_TOPK ? key_of_value(bits) : rand_word(rk, idx);
-        is_gt = key > us.tau; is_eq = key == us.tau;
-      }
-      const uint64_t bg = __ballot(is_gt), be = __ballot(is_eq);
-      const uint32_t my_gt = gt_before + popc_below(bg), my_eq = eq_before + popc_below(be);
-      if (is_gt || (is_eq && my_eq < us.need)) {
-        const uint32_t pos = my_gt + min(my_eq, us.need);
-        oi[pos] = idx; ov[pos] = bits;
-      }
-      gt_before += __popcll(bg); eq_before += __popcll(be);
-    }
+  __syncthreads();
+  uint64_t* ga = c.norm_acc + u * ACC_SLOTS;
+  for (uint32_t s = wave; s < ACC_SLOTS; s += 4) {
+    uint64_t x = 0;
+#pragma unroll
+    for (uint32_t r = 0; r < BLOCK; r += WAVE) x += acc[(r + lane) * (ACC_SLOTS + 1) + s];
+    x = wave_sum64(x);
+    if (lane == 0 && x) atomicAdd(reinterpret_cast<unsigned long long*>(ga + s), static_cast<unsigned long long>(x));
   }
 }
 
-// ------------------------------------------------------------------------------------------------
-// exact norms: every |v| (or v^2) is an integer multiple of 2^-149 (2^-298); its 32-bit digits are
-// added into 64-bit counters, integer addition commutes, so any schedule gives the same sum.  The
-// digits become one correctly rounded double and then the fp32 scale (in k_quantize).
-// ------------------------------------------------------------------------------------------------
+// digits -> one correctly rounded double -> the fp32 scale of the unit
 __device__ float finalize_scale(const uint64_t* acc, bool squares, uint32_t k) {
   uint32_t dig[ACC_SLOTS + 2];
   uint64_t carry = 0;
@@ -703,49 +858,6 @@ __device__ float finalize_scale(const uint64_t* acc, bool squares, uint32_t k) {
     S = ldexp(static_cast<double>(mant), e2 + (squares ? -298 : -149));
   }
   return squares ? static_cast<float>(sqrt(S)) : static_cast<float>(S / static_cast<double>(k));
-}
-
-__global__ __launch_bounds__(BLOCK) void k_norm(DevCtx c) {
-  __shared__ uint64_t acc[BLOCK * (ACC_SLOTS + 1)];
-  const NormTile nt = c.ntiles[blockIdx.x];
-  const uint32_t w = blockIdx.y;
-  const SegInfo sg = c.segs[nt.seg];
-  const bool squares = c.quantizer == QSL_QSGD;
-  uint64_t* mine = acc + threadIdx.x * (ACC_SLOTS + 1);
-#pragma unroll
-  for (uint32_t i = 0; i < ACC_SLOTS; ++i) mine[i] = 0;
-  const uint32_t* val = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff + nt.first;
-  for (uint32_t j = threadIdx.x; j < nt.count; j += BLOCK) {
-    const uint32_t ab = val[j] & 0x7FFFFFFFu;
-    const uint32_t ex = ab >> 23, frac = ab & 0x7FFFFFu;
-    const uint32_t M = ex ? (frac | 0x800000u) : frac;       // |v| = M * 2^(max(ex,1) - 150)
-    const uint32_t e1 = ex ? ex : 1u;
-    if (M == 0) continue;
-    if (squares) {
-      const uint64_t sq = static_cast<uint64_t>(M) * M;       // < 2^48;  v^2 = sq * 2^(2 e1 - 300)
-      const uint32_t p = 2u * e1 - 2u;                        // bit position above 2^-298
-      const uint32_t q = p >> 5, r = p & 31u;
-      const uint64_t lo = sq << r;                            // low 64 bits of sq * 2^r  (r <= 30)
-      const uint64_t hi = r ? (sq >> (64 - r)) : 0;
-      mine[q] += lo & 0xFFFFFFFFu; mine[q + 1] += lo >> 32; mine[q + 2] += hi;
-    } else {
-      const uint32_t p = e1 - 1u;                             // bit position above 2^-149
-      const uint32_t q = p >> 5, r = p & 31u;
-      const uint64_t sh = static_cast<uint64_t>(M) << r;      // < 2^55
-      mine[q] += sh & 0xFFFFFFFFu; mine[q + 1] += sh >> 32;
-    }
-  }
-  __syncthreads();
-  const uint64_t u = static_cast<uint64_t>(w) * c.L + nt.seg;
-  uint64_t* ga = c.norm_acc + u * ACC_SLOTS;
-  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  for (uint32_t s = wave; s < ACC_SLOTS; s += 4) {
-    uint64_t x = 0;
-#pragma unroll
-    for (uint32_t r = 0; r < BLOCK; r += WAVE) x += acc[(r + lane) * (ACC_SLOTS + 1) + s];
-    x = wave_sum64(x);
-    if (lane == 0 && x) atomicAdd(reinterpret_cast<unsigned long long*>(ga + s), static_cast<unsigned long long>(x));
-  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -1070,7 +1182,8 @@ struct qsl_ctx {
   void* slab;                 // one allocation holding every scratch array
   uint32_t Rmax;
   uint32_t last_R;
-  uint32_t n_sampled;         // units per worker that k_sample initialises
+  uint32_t n_sampled;         // segments whose guess comes from k_sample
+  uint32_t max_nsamp;         // most sampling blocks any of them uses
   size_t capacity;
   uint32_t* h_status;         // pinned
   uint32_t* d_nnz_tmp;
@@ -1143,41 +1256,27 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   std::vector<SegInfo>& segs = ctx->segs;
   segs.resize(L);
   std::vector<WtInfo> wts;
-  std::vector<GrpInfo> grps;
   std::vector<SelInfo> sels;
-  std::vector<NormTile> ntiles;
+  std::vector<CbInfo> cbs;
   std::vector<uint32_t> fast;
-  uint64_t slot_elems = 0, ovf_entries = 0;
-  uint32_t koff = 0;
-  uint64_t nwt64 = 0;
+  uint64_t slot_elems = 0, ovf_entries = 0, d0_entries = 0, nwt64 = 0, nwc = 0;
+  uint32_t koff = 0, max_nsamp = 1;
   ctx->n_sampled = 0;
   for (uint32_t l = 0; l < L; ++l) {
     SegInfo& sg = segs[l];
     memset(&sg, 0, sizeof sg);
     sg.start = ctx->off[l]; sg.size = ctx->off[l + 1] - ctx->off[l];
     sg.k = ctx->k[l]; sg.koff = koff; koff += sg.k;
-    sg.wt_base = static_cast<uint32_t>(nwt64);
     sg.nwt = static_cast<uint32_t>((sg.size + CHUNK - 1) / CHUNK);
     nwt64 += sg.nwt;
     if (L > 1) {
       for (uint32_t t = 0; t < sg.nwt; ++t) { WtInfo wi; wi.seg = l; wi.chunk = t; wi.pad0 = wi.pad1 = 0; wts.push_back(wi); }
     }
-    sg.grp_base = static_cast<uint32_t>(grps.size());
-    sg.ngrp = (sg.nwt + GROUP - 1) / GROUP;
-    for (uint32_t g = 0; g < sg.ngrp; ++g) {
-      GrpInfo gi; gi.seg = l; gi.first_wt = g * GROUP; gi.nwt = std::min(GROUP, sg.nwt - gi.first_wt); gi.pad = 0;
-      grps.push_back(gi);
-    }
-    sg.nsel = std::min(SELECT_BLOCKS, sg.nwt);
-    for (uint32_t j = 0; j < sg.nsel; ++j) { SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0; sels.push_back(si); }
-    sg.nnorm = (sg.k + NORM_TILE - 1) / NORM_TILE;
-    for (uint32_t f = 0; f < sg.k; f += NORM_TILE) {
-      NormTile nt; nt.seg = l; nt.first = f; nt.count = std::min(NORM_TILE, sg.k - f); nt.pad = 0;
-      ntiles.push_back(nt);
-    }
     sg.mode = PATH_GENERAL;
     sg.T_static = 0xFFFFFFFFu;
+    sg.lpc = 8;
     const double n = static_cast<double>(sg.size), p = static_cast<double>(sg.k) / n;
+    double cand = 0;                                // expected number of candidates
     if (!(cfg->flags & QSL_FLAG_NO_FAST_PATH) && sg.size >= (1u << 18)) {
       if (cfg->sparsifier == QSL_TOPK && static_cast<uint64_t>(sg.k) * 64 <= sg.size) {
         // candidates ~ alpha k; the sample must hold enough of them for the guess to sit below the
@@ -1188,7 +1287,10 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
           if (n_s > n / 16) continue;
           sg.n_runs = static_cast<uint32_t>(std::ceil(n_s / 64.0));
           sg.r_s = static_cast<uint32_t>(std::ceil(alpha * (sg.n_runs * 64.0) * p));
-          sg.lpc = alpha * p * CHUNK + 5.0 * std::sqrt(alpha * p * CHUNK) + 3.0 <= 15.0 ? 8 : 16;
+          sg.nsamp = std::min(MAX_SAMPLE_BLOCKS, std::max(16u, sg.n_runs / 128));
+          max_nsamp = std::max(max_nsamp, sg.nsamp);
+          cand = alpha * sg.k;
+          sg.d0_cap = static_cast<uint32_t>(std::min<double>(n, 4.0 * cand + 8192.0));
           sg.mode = PATH_FAST;
           ++ctx->n_sampled;
           break;
@@ -1196,41 +1298,59 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
       } else if (cfg->sparsifier == QSL_RANDK && static_cast<uint64_t>(sg.k) * 16 <= sg.size) {
         // the keys are uniform 32-bit words: keep those above the (1 - q) quantile, q = p + 7 sigma
         const double q = p + 7.0 * std::sqrt(p * (1 - p) / n);
-        if (q * CHUNK <= 16.0) {                  // at most ~16 candidates per chunk: they fit a two-line slot
+        if (q * CHUNK <= 14.0) {                  // at most ~14 candidates per chunk: they fit a two-line slot
           sg.T_static = static_cast<uint32_t>(std::floor(4294967296.0 * (1.0 - q)));
-          sg.lpc = q * CHUNK + 5.0 * std::sqrt(q * CHUNK) + 3.0 <= 15.0 ? 8 : 16;
+          cand = q * n;
+          sg.d0_cap = static_cast<uint32_t>(std::min<double>(n, cand + 8.0 * std::sqrt(cand) + 1024.0));
           sg.mode = PATH_FAST;
         }
       }
     }
     if (sg.mode == PATH_FAST) {
-      // the slot of a chunk holds the expected candidates with ~5 sigma to spare; chunks that hold more
-      // (clustered large values) spill to an overflow pool sized for several times all candidates
+      // the slot of a chunk (64, 128 or 256 bytes) holds the expected candidates with ~4 sigma to spare;
+      // chunks that hold more (chance, or clustered large values) spill to an overflow pool that can
+      // take every candidate
+      const double per_chunk = cand / sg.nwt, need = per_chunk + 4.0 * std::sqrt(per_chunk);
+      sg.lpc = need <= 7.0 ? 4 : need <= 15.0 ? 8 : 16;
       fast.push_back(l);
       sg.slot_off = slot_elems; slot_elems += static_cast<uint64_t>(sg.nwt) * sg.lpc * 2;
-      sg.ovf_cap = static_cast<uint32_t>(std::min<double>(n, 8.0 * sg.k + 16384.0));
+      sg.ovf_cap = sg.d0_cap;
       sg.ovf_off = ovf_entries; ovf_entries += sg.ovf_cap;
+      sg.d0_off = d0_entries; d0_entries += sg.d0_cap;
+      const uint64_t nrows = (static_cast<uint64_t>(sg.nwt) * sg.lpc + 63) / 64;
+      sg.nsel = static_cast<uint32_t>(std::min<uint64_t>(MAX_SELECT_BLOCKS, std::max<uint64_t>(16, (nrows + 127) / 128)));
+      sg.ncb = (sg.d0_cap + DTILE - 1) / DTILE;
+    } else {
+      sg.nsel = std::min(MAX_SELECT_BLOCKS, std::max(1u, (sg.nwt + 3) / 4));
+      sg.ncb = (sg.nwt + GGROUP - 1) / GGROUP;
     }
+    for (uint32_t j = 0; j < sg.nsel; ++j) { SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0; sels.push_back(si); }
+    sg.wc_base = static_cast<uint32_t>(nwc); nwc += sg.nsel * (BIG / 64);
+    sg.cb_base = static_cast<uint32_t>(cbs.size());
+    for (uint32_t b = 0; b < sg.ncb; ++b) { CbInfo ci; ci.seg = l; ci.b = b; ci.pad0 = ci.pad1 = 0; cbs.push_back(ci); }
   }
+  ctx->max_nsamp = max_nsamp;
   const uint32_t NWT = static_cast<uint32_t>(nwt64);
-  const uint32_t NGRP = static_cast<uint32_t>(grps.size()), NSEL = static_cast<uint32_t>(sels.size());
-  const uint32_t NNT = static_cast<uint32_t>(ntiles.size());
+  const uint32_t NSEL = static_cast<uint32_t>(sels.size()), NCB = static_cast<uint32_t>(cbs.size());
+  const uint32_t NWC = static_cast<uint32_t>(nwc);
   const uint32_t QB = (K + BLOCK - 1) / BLOCK;
   const uint64_t R = ctx->Rmax, U = R * L;
 
-  // one slab, carved; the part that must be zero between kernels comes first
+  // one slab, carved; the part that must be zero between calls comes first
   uint64_t bytes = 0;
   auto carve = [&](uint64_t n) { const uint64_t o = bytes; bytes = align_up(bytes + n, 256); return o; };
   const uint64_t o_hist = carve(4ull * 3 * HBINS * U), o_ctr = carve(4ull * CTR_LINES * PAD * U);
   const uint64_t o_acc = carve(8ull * ACC_SLOTS * U), o_status = carve(8);
   const uint64_t zero_bytes = bytes;
   const uint64_t o_segs = carve(sizeof(SegInfo) * L), o_wts = carve(sizeof(WtInfo) * std::max<size_t>(1, wts.size()));
-  const uint64_t o_grps = carve(sizeof(GrpInfo) * NGRP), o_sels = carve(sizeof(SelInfo) * NSEL);
-  const uint64_t o_nt = carve(sizeof(NormTile) * NNT), o_fast = carve(4ull * std::max<size_t>(1, fast.size()));
+  const uint64_t o_sels = carve(sizeof(SelInfo) * NSEL), o_cbs = carve(sizeof(CbInfo) * NCB);
+  const uint64_t o_fast = carve(4ull * std::max<size_t>(1, fast.size()));
   const uint64_t o_units = carve(sizeof(UnitState) * U);
   const uint64_t o_slots = carve(8ull * std::max<uint64_t>(2, slot_elems) * R);
   const uint64_t o_ovf = carve(8ull * std::max<uint64_t>(1, ovf_entries) * R);
-  const uint64_t o_cnt = carve(8ull * NWT * R), o_gcnt = carve(8ull * NGRP * R);
+  const uint64_t o_d0 = carve(8ull * std::max<uint64_t>(1, d0_entries) * R);
+  const uint64_t o_d0k = carve(4ull * std::max<uint64_t>(1, d0_entries) * R);
+  const uint64_t o_wc = carve(4ull * NWC * R), o_cbc = carve(8ull * NCB * R);
   const uint64_t o_si = carve(4ull * K * R), o_sv = carve(4ull * K * R), o_sc = carve(4ull * K * R);
   const uint64_t o_blk = carve(4ull * QB * R), o_pre = carve(4ull * (QB + 1) * R);
   const uint64_t o_vi = carve(4ull * K * R), o_vc = carve(4ull * K * R);
@@ -1243,9 +1363,8 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   };
   upload(o_segs, segs.data(), sizeof(SegInfo) * L);
   upload(o_wts, wts.data(), sizeof(WtInfo) * wts.size());
-  upload(o_grps, grps.data(), sizeof(GrpInfo) * NGRP);
   upload(o_sels, sels.data(), sizeof(SelInfo) * NSEL);
-  upload(o_nt, ntiles.data(), sizeof(NormTile) * NNT);
+  upload(o_cbs, cbs.data(), sizeof(CbInfo) * NCB);
   upload(o_fast, fast.data(), 4 * fast.size());
   ok = ok && hipHostMalloc(reinterpret_cast<void**>(&ctx->h_status), 64, hipHostMallocDefault) == hipSuccess;
   ok = ok && hipDeviceSynchronize() == hipSuccess;
@@ -1254,15 +1373,15 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   DevCtx& c = ctx->dc;
   c.segs = reinterpret_cast<const SegInfo*>(base + o_segs);
   c.wts = reinterpret_cast<const WtInfo*>(base + o_wts);
-  c.grps = reinterpret_cast<const GrpInfo*>(base + o_grps);
   c.sels = reinterpret_cast<const SelInfo*>(base + o_sels);
-  c.ntiles = reinterpret_cast<const NormTile*>(base + o_nt);
+  c.cbs = reinterpret_cast<const CbInfo*>(base + o_cbs);
   c.fast_segs = reinterpret_cast<const uint32_t*>(base + o_fast);
   c.units = reinterpret_cast<UnitState*>(base + o_units);
   c.slots = reinterpret_cast<uint2*>(base + o_slots); c.slot_stride = std::max<uint64_t>(2, slot_elems);
   c.ovf = reinterpret_cast<uint2*>(base + o_ovf); c.ovf_stride = std::max<uint64_t>(1, ovf_entries);
-  c.wt_cnt = reinterpret_cast<uint2*>(base + o_cnt);
-  c.grp_cnt = reinterpret_cast<uint2*>(base + o_gcnt);
+  c.d0 = reinterpret_cast<uint2*>(base + o_d0); c.d0_key = reinterpret_cast<uint32_t*>(base + o_d0k);
+  c.d0_stride = std::max<uint64_t>(1, d0_entries);
+  c.wave_cnt = reinterpret_cast<uint32_t*>(base + o_wc); c.cb_cnt = reinterpret_cast<uint2*>(base + o_cbc);
   c.hist = reinterpret_cast<uint32_t*>(base + o_hist); c.ctr = reinterpret_cast<uint32_t*>(base + o_ctr);
   c.norm_acc = reinterpret_cast<uint64_t*>(base + o_acc);
   c.sel_idx = reinterpret_cast<uint32_t*>(base + o_si); c.sel_val = reinterpret_cast<uint32_t*>(base + o_sv);
@@ -1271,12 +1390,12 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.surv_idx = reinterpret_cast<uint32_t*>(base + o_vi); c.surv_code = reinterpret_cast<uint32_t*>(base + o_vc);
   c.status = reinterpret_cast<uint32_t*>(base + o_status);
   ctx->d_nnz_tmp = reinterpret_cast<uint32_t*>(base + o_tmp);
-  c.d = d; c.seed = cfg->seed; c.L = L; c.K = K; c.NWT = NWT; c.NGRP = NGRP; c.NSEL = NSEL; c.NNT = NNT; c.QB = QB;
+  c.d = d; c.seed = cfg->seed; c.L = L; c.K = K; c.NWT = NWT; c.NSEL = NSEL; c.NCB = NCB; c.NWC = NWC; c.QB = QB;
   c.nfast = static_cast<uint32_t>(fast.size()); c.s = s; c.w_idx = w_idx; c.w_lev = w_lev; c.w_val = w_val;
   c.sparsifier = cfg->sparsifier; c.quantizer = cfg->quantizer;
   c.cap_words = static_cast<uint32_t>(ctx->capacity / 4);
   ctx->one.start = 0; ctx->one.size = segs[0].size; ctx->one.slot_off = 0; ctx->one.ovf_off = 0;
-  ctx->one.lpc = segs[0].lpc ? segs[0].lpc : 8; ctx->one.ovf_cap = segs[0].ovf_cap;
+  ctx->one.lpc = segs[0].lpc; ctx->one.ovf_cap = segs[0].ovf_cap;
   k_init<<<dim3(static_cast<uint32_t>((U + 255) / 256)), 256, 0, ctx->stream>>>(c, static_cast<uint32_t>(U));
   if (hipStreamSynchronize(ctx->stream) != hipSuccess) {
     (void)hipFree(ctx->slab); (void)hipHostFree(ctx->h_status); delete ctx; return QSL_ERR_DEVICE;
@@ -1310,7 +1429,7 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   const DevCtx& c = ctx->dc;
   hipStream_t st = ctx->stream;
   if (SPARS == QSL_TOPK && ctx->n_sampled > 0) {
-    k_sample<<<dim3(SAMPLE_BLOCKS, c.nfast, R), BIG, 0, st>>>(c, m, delta);
+    k_sample<<<dim3(ctx->max_nsamp, c.nfast, R), BIG, 0, st>>>(c, m, delta);
     k_sample_scan<<<dim3(c.nfast, R), BIG, 0, st>>>(c);
   }
   const bool timed = ctx->timing != 0;
@@ -1328,9 +1447,8 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   k_select<0, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
   k_select<1, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
   k_select<2, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
-  k_tile_count<SPARS><<<dim3(c.NGRP, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
-  k_tile_write<SPARS><<<dim3(c.NGRP, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
-  k_norm<<<dim3(c.NNT, R), BLOCK, 0, st>>>(c);
+  k_tile_count<SPARS><<<dim3(c.NCB, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
+  k_tile_write<SPARS><<<dim3(c.NCB, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
   k_quantize<<<dim3(c.QB, R), BLOCK, 0, st>>>(c, m_out, worker0, round, sel_idx, sel_level);
   if (c.QB > MAX_QB_INLINE) k_surv_scan<<<dim3(R), 1024, 0, st>>>(c);
   k_surv_compact<<<dim3(c.QB, R), BLOCK, 0, st>>>(c);
