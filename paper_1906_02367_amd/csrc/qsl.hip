@@ -1321,7 +1321,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
       sg.nsel = static_cast<uint32_t>(std::min<uint64_t>(MAX_SELECT_BLOCKS, std::max<uint64_t>(16, (nrows + 127) / 128)));
       sg.ncb = (sg.d0_cap + DTILE - 1) / DTILE;
     } else {
-      sg.nsel = std::min(MAX_SELECT_BLOCKS, std::max(1u, (sg.nwt + 3) / 4));
+      sg.nsel = std::min(MAX_SELECT_BLOCKS, std::max(1u, (sg.nwt + 7) / 8));
       sg.ncb = (sg.nwt + GGROUP - 1) / GGROUP;
     }
     for (uint32_t j = 0; j < sg.nsel; ++j) { SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0; sels.push_back(si); }
