@@ -17,7 +17,7 @@ _SRC = os.path.join(_HERE, "qsl_oracle.cpp")
 _LIB = os.path.join(_HERE, "libqsl_oracle.so")
 
 TOPK, RANDK = 0, 1
-QSGD, SIGN_L1 = 0, 1
+QSGD, SIGN_L1, SIGN_L2, FP32, QSGD_SCALED = 0, 1, 2, 3, 4
 STREAM_SELECT, STREAM_QUANT = 0, 1
 
 

@@ -53,7 +53,8 @@ def compress(m, delta, d, seg_offset, seg_k, s, sparsifier, quantizer, seed, wor
     v = (m + delta).astype(f32)
     L = len(seg_k)
     w_idx = max(1, (d - 1).bit_length())
-    w_lev = (s - 1).bit_length()
+    qsgd = quantizer in (0, 4)                      # 4: the scaled operator of Lemma 2
+    w_lev = (s - 1).bit_length() if qsgd else 0
     sel, levels, negs, gvals, scales, counts = [], [], [], [], [], []
     for l in range(L):
         lo, hi, k = int(seg_offset[l]), int(seg_offset[l + 1]), int(seg_k[l])
@@ -63,9 +64,13 @@ def compress(m, delta, d, seg_offset, seg_k, s, sparsifier, quantizer, seed, wor
             ranked = sorted(range(lo, hi), key=lambda i: (-random_word(seed, worker, rnd, 0, i), i))
         S = sorted(ranked[:k])
         vs = [v[i] for i in S]
-        if quantizer == 0:
+        if qsgd:
             total = sum(Fraction(float(x)) ** 2 for x in vs)
             N = f32(math.sqrt(_round_fraction_to_double(total)))
+            N_sent = N
+            if quantizer == 4:
+                beta = min(k / (s * s), math.sqrt(k) / s)
+                N_sent = f32(N / f32(1.0 + beta))
             n_sent = 0
             for i, x in zip(S, vs):
                 lev = 0
@@ -79,14 +84,22 @@ def compress(m, delta, d, seg_offset, seg_k, s, sparsifier, quantizer, seed, wor
                 neg = bool(x < 0)
                 g = f32(0)
                 if lev:
-                    g = f32(f32(N * f32(lev)) / f32(s))
+                    g = f32(f32(N_sent * f32(lev)) / f32(s))
                     g = -g if neg else g
                     n_sent += 1
                 sel.append(i); levels.append(lev); negs.append(neg); gvals.append(g)
-            scales.append(N); counts.append(n_sent)
+            scales.append(N_sent); counts.append(n_sent)
+        elif quantizer == 3:                            # no quantiser
+            for i, x in zip(S, vs):
+                sel.append(i); levels.append(1); negs.append(bool(x < 0)); gvals.append(f32(x))
+            scales.append(f32(0)); counts.append(k)
         else:
-            total = sum(Fraction(float(abs(x))) for x in vs)
-            c = f32(_round_fraction_to_double(total) / float(k))
+            if quantizer == 1:
+                total = sum(Fraction(float(abs(x))) for x in vs)
+                c = f32(_round_fraction_to_double(total) / float(k))
+            else:                                       # ||v_S||_2 / k
+                total = sum(Fraction(float(x)) ** 2 for x in vs)
+                c = f32(math.sqrt(_round_fraction_to_double(total)) / float(k))
             for i, x in zip(S, vs):
                 neg = bool(x < 0)
                 sel.append(i); levels.append(1); negs.append(neg); gvals.append(-c if neg else c)
@@ -106,20 +119,23 @@ def compress(m, delta, d, seg_offset, seg_k, s, sparsifier, quantizer, seed, wor
     put(nnz, 32)
     for sc in scales:
         put(_bits(sc), 32)
-    if quantizer == 0 and L > 1:
+    if qsgd and L > 1:
         for c_ in counts:
             put(c_, 32)
     for i, lev in zip(sel, levels):
         if lev:
             put(i, w_idx)
     align32()
-    for lev, neg in zip(levels, negs):
+    for lev, neg, g in zip(levels, negs, gvals):
         if lev:
-            if quantizer == 0:
+            if quantizer == 3:
+                put(_bits(g), 32)
+                continue
+            if qsgd:
                 put(lev - 1, w_lev)
             put(int(neg), 1)
-    header = 32 + 32 * L + (32 * L if quantizer == 0 and L > 1 else 0)
-    payload_bits = header + nnz * (w_idx + (w_lev + 1 if quantizer == 0 else 1))
+    header = 32 + 32 * L + (32 * L if qsgd and L > 1 else 0)
+    payload_bits = header + nnz * (w_idx + (w_lev + 1 if qsgd else 32 if quantizer == 3 else 1))
     while len(bits) % 64:
         bits.append(0)
     msg = np.packbits(np.array(bits, dtype=np.uint8), bitorder="little")

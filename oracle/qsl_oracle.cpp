@@ -191,14 +191,17 @@ struct BitReader {
 };
 
 enum : uint32_t { SPARS_TOPK = 0, SPARS_RANDK = 1 };
-enum : uint32_t { QUANT_QSGD = 0, QUANT_SIGN_L1 = 1 };
+// QSGD (Definition 1, example 1); Sign scaled by ||v_S||_1 / k or ||v_S||_2 / k (Lemma 3 with m = 1, 2);
+// no quantisation at all (the TopK-SGD comparison scheme of Section 5); QSGD divided by 1 + beta_{k,s} (Lemma 2).
+enum : uint32_t { QUANT_QSGD = 0, QUANT_SIGN_L1 = 1, QUANT_SIGN_L2 = 2, QUANT_FP32 = 3, QUANT_QSGD_SCALED = 4 };
+inline bool is_qsgd(uint32_t q) { return q == QUANT_QSGD || q == QUANT_QSGD_SCALED; }
 
 struct Layout {
   uint64_t d; uint32_t L; const uint64_t* off; const uint32_t* k; uint32_t s; uint32_t quantizer;
   uint64_t K() const { uint64_t t = 0; for (uint32_t l = 0; l < L; ++l) t += k[l]; return t; }
-  bool has_counts() const { return quantizer == QUANT_QSGD && L > 1; }
+  bool has_counts() const { return is_qsgd(quantizer) && L > 1; }
   uint32_t w_idx() const { return index_width(d); }
-  uint32_t w_val() const { return quantizer == QUANT_QSGD ? level_width(s) + 1 : 1; }
+  uint32_t w_val() const { return is_qsgd(quantizer) ? level_width(s) + 1 : quantizer == QUANT_FP32 ? 32 : 1; }
   uint64_t header_bits() const { return 32 + 32ull * L + (has_counts() ? 32ull * L : 0); }
   uint64_t capacity_bytes() const {
     const uint64_t Kt = K();
@@ -213,8 +216,8 @@ struct Layout {
       if (off[l + 1] <= off[l]) return false;
       if (k[l] == 0 || k[l] > off[l + 1] - off[l]) return false;
     }
-    if (quantizer == QUANT_QSGD && (s == 0 || s > 32768)) return false;
-    return quantizer <= 1;
+    if (is_qsgd(quantizer) && (s == 0 || s > 32768)) return false;
+    return quantizer <= 4;
   }
   uint32_t segment_of(uint64_t i) const {
     uint32_t l = 0; while (off[l + 1] <= i) ++l; return l;
@@ -312,10 +315,18 @@ int qslo_compress(const float* m, const float* delta, float* m_out, uint64_t d, 
     std::vector<float> vs(kl);
     for (uint32_t j = 0; j < kl; ++j) vs[j] = v[Sl[j]];
 
-    if (quantizer == QUANT_QSGD) {
+    if (is_qsgd(quantizer)) {
       // Step 3: N = || v_S ||_2, the exact sum rounded to double, square root, rounded to float.
       const float N = static_cast<float>(std::sqrt(exact_sum_of_squares(vs.data(), kl)));
-      scale[l] = N;
+      // Lemma 2: the scaled operator sends Q_s(v_S) / (1 + beta_{k,s}), beta_{k,s} = min(k / s^2, sqrt(k) / s):
+      // the level codes are those of the unscaled operator, the transmitted norm is N / (1 + beta).
+      float N_sent = N;
+      if (quantizer == QUANT_QSGD_SCALED) {
+        const double beta = std::min(static_cast<double>(kl) / (static_cast<double>(s) * s),
+                                     std::sqrt(static_cast<double>(kl)) / s);
+        N_sent = N / static_cast<float>(1.0 + beta);
+      }
+      scale[l] = N_sent;
       // Step 4 (Definition 1, example 1): stochastic rounding of s|v_i|/N to one of
       // the two neighbouring integers, up with probability equal to the fraction.
       for (uint32_t j = 0; j < kl; ++j) {
@@ -334,14 +345,21 @@ int qslo_compress(const float* m, const float* delta, float* m_out, uint64_t d, 
         lev[base + j] = static_cast<uint16_t>(level);
         neg[base + j] = x < 0.0f;
         if (level) {
-          const float mag = qsgd_magnitude(N, level, s);
+          const float mag = qsgd_magnitude(N_sent, level, s);
           g[base + j] = neg[base + j] ? -mag : mag;
           ++nnz[l];
         }
       }
+    } else if (quantizer == QUANT_FP32) {
+      // no quantiser: g = Top_k(v) (or Rand_k(v)) itself
+      scale[l] = 0.0f;
+      for (uint32_t j = 0; j < kl; ++j) { neg[base + j] = vs[j] < 0.0f; lev[base + j] = 1; g[base + j] = vs[j]; }
+      nnz[l] = kl;
     } else {
-      // Step 3 (Lemma 3, m = 1): c = || v_S ||_1 / k.
-      const float c = static_cast<float>(exact_sum_of_abs(vs.data(), kl) / static_cast<double>(kl));
+      // Step 3 (Lemma 3): c = || v_S ||_m / k, m = 1 or 2.
+      const float c = quantizer == QUANT_SIGN_L1
+                          ? static_cast<float>(exact_sum_of_abs(vs.data(), kl) / static_cast<double>(kl))
+                          : static_cast<float>(std::sqrt(exact_sum_of_squares(vs.data(), kl)) / static_cast<double>(kl));
       scale[l] = c;
       // Step 4 (Definition 2): +c where v_i >= 0 (zero included), -c where v_i < 0.
       for (uint32_t j = 0; j < kl; ++j) {
@@ -364,12 +382,13 @@ int qslo_compress(const float* m, const float* delta, float* m_out, uint64_t d, 
   bw.put(total, 32);
   for (uint32_t l = 0; l < L; ++l) bw.put(f2u(scale[l]), 32);
   if (lay.has_counts()) for (uint32_t l = 0; l < L; ++l) bw.put(nnz[l], 32);
-  const uint32_t wi = lay.w_idx(), wl = level_width(s);
+  const uint32_t wi = lay.w_idx(), wl = is_qsgd(quantizer) ? level_width(s) : 0;
   for (uint64_t j = 0; j < K; ++j) if (lev[j]) bw.put(S[j], wi);
   bw.align32();
   for (uint64_t j = 0; j < K; ++j) {
     if (!lev[j]) continue;
-    if (quantizer == QUANT_QSGD) { bw.put(lev[j] - 1u, wl); bw.put(neg[j], 1); }
+    if (is_qsgd(quantizer)) { bw.put(lev[j] - 1u, wl); bw.put(neg[j], 1); }
+    else if (quantizer == QUANT_FP32) bw.put(f2u(g[j]), 32);
     else bw.put(neg[j], 1);
   }
   if (bw.overflow) return 2;
@@ -410,17 +429,19 @@ int64_t qslo_decode(const uint8_t* msg, uint64_t d, uint32_t L, const uint64_t* 
   std::vector<float> scale(L);
   for (uint32_t l = 0; l < L; ++l) scale[l] = u2f(static_cast<uint32_t>(br.get(32)));
   if (lay.has_counts()) for (uint32_t l = 0; l < L; ++l) br.get(32);
-  const uint32_t wi = lay.w_idx(), wl = level_width(s);
+  const uint32_t wi = lay.w_idx(), wl = is_qsgd(quantizer) ? level_width(s) : 0;
   for (uint64_t j = 0; j < total; ++j) idx_out[j] = static_cast<uint32_t>(br.get(wi));
   br.align32();
   for (uint64_t j = 0; j < total; ++j) {
     if (idx_out[j] >= d) return -1;
     const float sc = scale[lay.segment_of(idx_out[j])];
-    if (quantizer == QUANT_QSGD) {
+    if (is_qsgd(quantizer)) {
       const uint32_t level = static_cast<uint32_t>(br.get(wl)) + 1u;
       const bool negative = br.get(1);
       const float mag = qsgd_magnitude(sc, level, s);
       val_out[j] = negative ? -mag : mag;
+    } else if (quantizer == QUANT_FP32) {
+      val_out[j] = u2f(static_cast<uint32_t>(br.get(32)));
     } else {
       val_out[j] = br.get(1) ? -sc : sc;
     }

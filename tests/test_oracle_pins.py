@@ -246,6 +246,64 @@ def test_composed_operator_compression_inequality():
 
 
 # ------------------------------------------------------------------------------------------
+# the operator variants: scaled composition (Lemma 2), l2-scaled sign (Lemma 3, m = 2), no quantiser
+# ------------------------------------------------------------------------------------------
+def test_scaled_composition_same_codes_values_divided_and_lemma2_bound():
+    rng = np.random.default_rng(25)
+    d, k, s = 600, 50, 2                     # beta = min(k/s^2, sqrt(k)/s) = 3.54: outside Lemma 1, inside Lemma 2
+    x = rng.standard_normal(d).astype(f32)
+    beta = min(k / s**2, math.sqrt(k) / s)
+    off, kk = one_seg(d, k)
+    err = 0.0
+    n = 3000
+    for seed in range(n):
+        a = O.OracleOp(d, off, kk, s, O.TOPK, O.QSGD, seed).compress(np.zeros(d, f32), x, 1, 2)
+        b = O.OracleOp(d, off, kk, s, O.TOPK, O.QSGD_SCALED, seed).compress(np.zeros(d, f32), x, 1, 2)
+        assert np.array_equal(a["sel_idx"], b["sel_idx"]) and np.array_equal(a["sel_level"], b["sel_level"])
+        assert b["scales"][0] == f32(a["scales"][0] / f32(1.0 + beta))
+        sent = a["sel_level"] > 0
+        assert np.allclose(b["g_val"][sent] * (1.0 + beta), a["g_val"][sent], rtol=3e-7)
+        err += (b["m_out"].astype(np.float64) ** 2).sum()
+    # E||x - Q_s Top_k(x) / (1 + beta)||^2 <= [1 - k / (d (1 + beta))] ||x||^2
+    assert err / n <= (1 - k / (d * (1 + beta))) * (x.astype(np.float64) ** 2).sum() * 1.005
+
+
+def test_sign_l2_scaling_closed_form_and_compression():
+    rng = np.random.default_rng(27)
+    d, k = 3000, 64
+    v = (rng.standard_normal(d) * np.exp(rng.standard_normal(d))).astype(f32)
+    res = op(d, k, quantizer=O.SIGN_L2).compress(np.zeros(d, f32), v, 0, 0)
+    S = res["sel_idx"].astype(np.int64)
+    assert np.array_equal(S, brute_topk(v, k).astype(np.int64))
+    N2 = math.sqrt(math.fsum(float(x) ** 2 for x in v[S]))
+    c = f32(N2 / k)
+    assert res["scales"][0] == c
+    assert np.array_equal(bits_of(res["g_val"]), bits_of(np.where(v[S] < 0, -c, c).astype(f32)))
+    # Lemma 3 with m = 2: compression coefficient k^(2/m - 1) / d = 1/d
+    g = np.zeros(d); g[S] = res["g_val"]
+    assert ((g - v.astype(np.float64)) ** 2).sum() <= (1 - 1 / d) * (v.astype(np.float64) ** 2).sum()
+    assert res["bits"] == 64 + k * ((d - 1).bit_length() + 1)
+
+
+def test_no_quantiser_is_top_k_itself():
+    rng = np.random.default_rng(29)
+    d, k = 2500, 40
+    m = rng.standard_normal(d).astype(f32)
+    delta = rng.standard_normal(d).astype(f32)
+    v = (m + delta).astype(f32)
+    o = op(d, k, quantizer=O.FP32)
+    res = o.compress(m, delta, 3, 3)
+    S = brute_topk(v, k).astype(np.int64)
+    assert np.array_equal(res["sel_idx"].astype(np.int64), S)
+    assert np.array_equal(bits_of(res["g_val"]), bits_of(v[S]))
+    want = v.copy(); want[S] = 0
+    assert np.array_equal(res["m_out"], want)
+    assert res["bits"] == 64 + k * ((d - 1).bit_length() + 32)          # the 57 bits per coordinate of TopK-SGD at d ~ 2^25
+    di, dv = o.decode(res["msg"])
+    assert np.array_equal(di.astype(np.int64), S) and np.array_equal(bits_of(dv), bits_of(v[S]))
+
+
+# ------------------------------------------------------------------------------------------
 # error feedback (Algorithm 1, second worker line)
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("quantizer", [O.QSGD, O.SIGN_L1])
@@ -406,7 +464,8 @@ def test_randk_inclusion_frequency_and_energy():
 # the C++ oracle against the second, differently written statement of the operator
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("sparsifier", [O.TOPK, O.RANDK])
-@pytest.mark.parametrize("quantizer,s", [(O.QSGD, 16), (O.QSGD, 3), (O.SIGN_L1, 1)])
+@pytest.mark.parametrize("quantizer,s", [(O.QSGD, 16), (O.QSGD, 3), (O.SIGN_L1, 1), (O.SIGN_L2, 1), (O.FP32, 1),
+                                         (O.QSGD_SCALED, 4)])
 def test_oracle_matches_second_statement(sparsifier, quantizer, s):
     rng = np.random.default_rng(81 + s + sparsifier)
     for trial in range(4):
