@@ -28,11 +28,13 @@
  * Wire format of one message (little endian; fields are packed least-significant bit first;
  * "w_idx" = bits needed to write d - 1, at least 1; "w_lev" = bits needed to write s - 1):
  *     u32  nnz                         number of transmitted coordinates
- *     f32  scale[num_segments]         ||v_S||_2 (QSGD) or ||v_S||_1 / k (Sign), per segment
- *     u32  nnz_l[num_segments]         only for QSGD with num_segments > 1
+ *     f32  scale[num_segments]         per segment: ||v_S||_2 (QSGD), ||v_S||_2 / (1 + beta) (scaled QSGD),
+ *                                      ||v_S||_1 / k or ||v_S||_2 / k (Sign), 0 (no quantiser)
+ *     u32  nnz_l[num_segments]         only for QSGD (either form) with num_segments > 1
  *     nnz x w_idx bits                 coordinate indices, ascending     (starts on a 32-bit boundary)
  *     nnz x w_val bits                 QSGD: (level - 1) in w_lev bits, then the sign bit;
- *                                      Sign: the sign bit (1 = negative)  (starts on a 32-bit boundary)
+ *                                      Sign: the sign bit (1 = negative); no quantiser: the fp32 value
+ *                                      (starts on a 32-bit boundary)
  *     zero padding up to the capacity (a multiple of 8 bytes)
  * A QSGD coordinate whose level is 0 is not transmitted (Section 5.1.2 notes that the quantiser
  * "further induces sparsity").  The paper fixes no encoding; this one is the library's choice.
@@ -59,7 +61,11 @@ typedef enum {
 } qsl_status;
 
 enum { QSL_TOPK = 0, QSL_RANDK = 1 };    /* sparsifier, Section 2.2 */
-enum { QSL_QSGD = 0, QSL_SIGN_L1 = 1 };  /* quantiser, Definitions 1 and 2 */
+/* quantiser: QSGD (Definition 1, example 1); Sign scaled by ||Comp_k(x)||_1 / k (Definition 2, Lemma 3
+ * with m = 1) or by ||Comp_k(x)||_2 / k (Lemma 3 with m = 2); none, i.e. Comp_k(x) itself in fp32 (the
+ * TopK-SGD comparison scheme of Section 5); QSGD divided by 1 + beta_{k,s}, beta_{k,s} = min(k/s^2,
+ * sqrt(k)/s) (the scaled composition of Lemma 2: same level codes, transmitted norm N / (1 + beta)). */
+enum { QSL_QSGD = 0, QSL_SIGN_L1 = 1, QSL_SIGN_L2 = 2, QSL_FP32 = 3, QSL_QSGD_SCALED = 4 };
 
 /* Parameters of the operator Q Comp_k, in the paper's notation. */
 typedef struct {
@@ -67,9 +73,9 @@ typedef struct {
   uint32_t num_segments;      /* 1: one operator on the whole vector; 1 < L <= 16384: piecewise (Cor. 1)  */
   const uint64_t *seg_offset; /* host, num_segments + 1 entries, seg_offset[0] = 0, last = d, increasing */
   const uint32_t *seg_k;      /* host, k per segment, 1 <= k_l <= size of the segment                   */
-  uint32_t s;                 /* QSGD levels, 1 <= s <= 32768 (ignored by the sign quantiser)           */
+  uint32_t s;                 /* QSGD levels, 1 <= s <= 32768 (ignored by the other quantisers)         */
   uint32_t sparsifier;        /* QSL_TOPK or QSL_RANDK                                                  */
-  uint32_t quantizer;         /* QSL_QSGD or QSL_SIGN_L1                                                */
+  uint32_t quantizer;         /* one of the QSL_QSGD .. QSL_QSGD_SCALED values above                    */
   uint64_t seed;              /* seed of the counter-based randomness (Rand_k choice, QSGD rounding)    */
   uint32_t max_workers;       /* largest R passed to one call; scratch is sized for it                  */
   uint32_t flags;             /* 0, or QSL_FLAG_* below                                                 */

@@ -123,6 +123,11 @@ struct DevCtx {
 
 __device__ __forceinline__ uint32_t key_of_value(uint32_t vbits) { return (vbits & 0x7FFFFFFFu) << 1; }
 
+// quantiser families: QSGD and its scaled form (Lemma 2) share everything but the transmitted norm
+__host__ __device__ __forceinline__ bool is_qsgd(uint32_t q) { return q == QSL_QSGD || q == QSL_QSGD_SCALED; }
+// which exact sum the quantiser's scale needs: squares (l2 norm), magnitudes (l1 norm), none
+__host__ __device__ __forceinline__ bool wants_squares(uint32_t q) { return is_qsgd(q) || q == QSL_SIGN_L2; }
+
 template <int SPARS>
 __device__ __forceinline__ uint32_t entry_key(uint32_t idx, uint32_t bits, const RandKey& rk) {
   return SPARS == QSL_TOPK ? key_of_value(bits) : rand_word(rk, idx);
@@ -763,7 +768,7 @@ __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, const float* v, 
   Thresh th; th.tau = us.tau; th.need = us.need;
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const bool squares = c.quantizer == QSL_QSGD;
+  const bool squares = wants_squares(c.quantizer);
   uint64_t* mine = acc + threadIdx.x * (ACC_SLOTS + 1);
 #pragma unroll
   for (uint32_t i = 0; i < ACC_SLOTS; ++i) mine[i] = 0;
@@ -826,7 +831,8 @@ __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, const float* v, 
 }
 
 // digits -> one correctly rounded double -> the fp32 scale of the unit
-__device__ float finalize_scale(const uint64_t* acc, bool squares, uint32_t k) {
+__device__ float finalize_scale(const uint64_t* acc, uint32_t quantizer, uint32_t k, uint32_t s) {
+  const bool squares = wants_squares(quantizer);
   uint32_t dig[ACC_SLOTS + 2];
   uint64_t carry = 0;
   for (uint32_t i = 0; i < ACC_SLOTS; ++i) { const uint64_t t = acc[i] + carry; dig[i] = static_cast<uint32_t>(t); carry = t >> 32; }
@@ -857,7 +863,11 @@ __device__ float finalize_scale(const uint64_t* acc, bool squares, uint32_t k) {
     }
     S = ldexp(static_cast<double>(mant), e2 + (squares ? -298 : -149));
   }
-  return squares ? static_cast<float>(sqrt(S)) : static_cast<float>(S / static_cast<double>(k));
+  if (quantizer == QSL_SIGN_L1) return static_cast<float>(S / static_cast<double>(k));           // ||v_S||_1 / k
+  if (quantizer == QSL_SIGN_L2) return static_cast<float>(sqrt(S) / static_cast<double>(k));     // ||v_S||_2 / k
+  if (quantizer == QSL_FP32) return 0.0f;
+  (void)s;
+  return static_cast<float>(sqrt(S));                                                            // ||v_S||_2
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -883,7 +893,7 @@ __device__ __forceinline__ float qsgd_value(float N, uint32_t level, uint32_t s,
 __global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint32_t worker0, uint64_t round,
                                                     uint32_t* dbg_idx, uint16_t* dbg_level) {
   __shared__ uint32_t s_w[BLOCK / 64];
-  __shared__ float s_scale[BLOCK];
+  __shared__ float s_scale[BLOCK], s_sent[BLOCK];
   const uint32_t w = blockIdx.y;
   const uint32_t j = blockIdx.x * BLOCK + threadIdx.x;
   // the scales of the units this block's slots belong to (at most one unit per slot)
@@ -893,9 +903,17 @@ __global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint
   if (threadIdx.x <= seg_last - seg_first) {
     const uint32_t seg = seg_first + threadIdx.x;
     const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
-    const float sc = finalize_scale(c.norm_acc + u * ACC_SLOTS, c.quantizer == QSL_QSGD, c.segs[seg].k);
+    const uint32_t kl = c.segs[seg].k;
+    const float sc = finalize_scale(c.norm_acc + u * ACC_SLOTS, c.quantizer, kl, c.s);
     s_scale[threadIdx.x] = sc;
-    if (c.segs[seg].koff >= j_first) c.units[u].scale_bits = __float_as_uint(sc);   // the block holding the unit's first slot
+    // what the message carries: the scale itself, or N / (1 + beta_{k,s}) for the scaled composition (Lemma 2)
+    float sent = sc;
+    if (c.quantizer == QSL_QSGD_SCALED) {
+      const double beta = fmin(static_cast<double>(kl) / (static_cast<double>(c.s) * c.s), sqrt(static_cast<double>(kl)) / c.s);
+      sent = sc / static_cast<float>(1.0 + beta);
+    }
+    s_sent[threadIdx.x] = sent;
+    if (c.segs[seg].koff >= j_first) c.units[u].scale_bits = __float_as_uint(sent);   // the block holding the unit's first slot
   }
   __syncthreads();
   uint32_t sent = 0;
@@ -909,7 +927,7 @@ __global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint
     const bool neg = v < 0.0f;
     uint32_t level;
     float g;
-    if (c.quantizer == QSL_QSGD) {
+    if (is_qsgd(c.quantizer)) {
       level = 0;
       if (scale > 0.0f) {
         const float a = fabsf(v) / scale;
@@ -921,7 +939,10 @@ __global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint
         const float r01 = static_cast<float>(rand_word(rk, idx) >> 8) * 0x1p-24f;
         level = static_cast<uint32_t>(fl) + (r01 < frac ? 1u : 0u);
       }
-      g = qsgd_value(scale, level, c.s, neg);
+      g = qsgd_value(s_sent[seg - seg_first], level, c.s, neg);
+    } else if (c.quantizer == QSL_FP32) {
+      level = 1;
+      g = v;
     } else {
       level = 1;
       g = neg ? -scale : scale;
@@ -931,7 +952,7 @@ __global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint
     if (sent) {
       if (idx < c.d) m_out[static_cast<uint64_t>(w) * c.d + idx] = v - g;
       else atomicOr(c.status, 2u);                       // cannot happen: a selected slot was never written
-      if (c.quantizer == QSL_QSGD && c.L > 1) atomicAdd(&c.units[u].nnz, 1u);
+      if (is_qsgd(c.quantizer) && c.L > 1) atomicAdd(&c.units[u].nnz, 1u);
     }
     if (dbg_idx) dbg_idx[slot] = idx;
     if (dbg_level) dbg_level[slot] = static_cast<uint16_t>(level);
@@ -991,7 +1012,8 @@ __global__ __launch_bounds__(BLOCK) void k_surv_compact(DevCtx c) {
   if (sent) {
     const uint32_t level = code & 0x7FFFFFFFu, neg = code >> 31;
     c.surv_idx[static_cast<uint64_t>(w) * c.K + pos] = c.sel_idx[slot];
-    c.surv_code[static_cast<uint64_t>(w) * c.K + pos] = c.quantizer == QSL_QSGD ? ((level - 1u) | (neg << c.w_lev)) : neg;
+    c.surv_code[static_cast<uint64_t>(w) * c.K + pos] = is_qsgd(c.quantizer) ? ((level - 1u) | (neg << c.w_lev))
+                                                        : c.quantizer == QSL_FP32 ? c.sel_val[slot] : neg;
   }
 }
 
@@ -1025,7 +1047,7 @@ __global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t
                                             : block_sum_u32(c.blk_cnt + static_cast<uint64_t>(w) * c.QB, c.QB, s_part);
   const uint64_t q = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x;
   if (q >= c.cap_words) return;
-  const bool counts = c.quantizer == QSL_QSGD && c.L > 1;
+  const bool counts = is_qsgd(c.quantizer) && c.L > 1;
   const uint64_t hdr = 1 + static_cast<uint64_t>(c.L) + (counts ? c.L : 0);
   const uint64_t idx_words = (nnz * c.w_idx + 31) / 32, code_words = (nnz * c.w_val + 31) / 32;
   uint32_t word = 0;
@@ -1049,7 +1071,7 @@ __device__ __forceinline__ MsgView view_msg(const DevCtx& c, const uint8_t* msg,
   MsgView v;
   v.words = reinterpret_cast<const uint32_t*>(msg + static_cast<uint64_t>(row) * c.cap_words * 4);
   v.nnz = min(v.words[0], c.K);                         // a well-formed message never holds more than K entries
-  const bool counts = c.quantizer == QSL_QSGD && c.L > 1;
+  const bool counts = is_qsgd(c.quantizer) && c.L > 1;
   const uint64_t hdr = 1 + static_cast<uint64_t>(c.L) + (counts ? c.L : 0);
   v.idx_bit0 = hdr * 32;
   v.code_bit0 = (hdr + (static_cast<uint64_t>(v.nnz) * c.w_idx + 31) / 32) * 32;
@@ -1062,10 +1084,11 @@ __device__ __forceinline__ float msg_value(const DevCtx& c, const MsgView& v, ui
   const uint32_t code = get_bits(v.words, v.code_bit0 + static_cast<uint64_t>(j) * c.w_val, c.w_val);
   const uint32_t seg = c.L == 1 ? 0u : seg_of_coord(c, idx);
   const float scale = __uint_as_float(v.words[1 + seg]);
-  if (c.quantizer == QSL_QSGD) {
+  if (is_qsgd(c.quantizer)) {
     const uint32_t level = (code & ((1u << c.w_lev) - 1u)) + 1u;
     return qsgd_value(scale, level, c.s, (code >> c.w_lev) & 1u);
   }
+  if (c.quantizer == QSL_FP32) return __uint_as_float(code);
   return code ? -scale : scale;
 }
 // position of coordinate idx in the message, or -1
@@ -1216,8 +1239,8 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t d = cfg->d;
   const uint32_t L = cfg->num_segments;
   if (d == 0 || d >= (1ull << 32) || L == 0 || L > 16384) return QSL_ERR_INVALID_ARG;
-  if (cfg->sparsifier > 1 || cfg->quantizer > 1) return QSL_ERR_INVALID_ARG;
-  if (cfg->quantizer == QSL_QSGD && (cfg->s == 0 || cfg->s > 32768)) return QSL_ERR_INVALID_ARG;
+  if (cfg->sparsifier > 1 || cfg->quantizer > 4) return QSL_ERR_INVALID_ARG;
+  if (is_qsgd(cfg->quantizer) && (cfg->s == 0 || cfg->s > 32768)) return QSL_ERR_INVALID_ARG;
   if (cfg->max_workers == 0 || cfg->max_workers > 1024) return QSL_ERR_INVALID_ARG;
   if (cfg->seg_offset[0] != 0 || cfg->seg_offset[L] != d) return QSL_ERR_INVALID_ARG;
   uint64_t K64 = 0;
@@ -1243,11 +1266,11 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->slab = nullptr; ctx->h_status = nullptr;
 
   const uint32_t K = static_cast<uint32_t>(K64);
-  const uint32_t s = cfg->quantizer == QSL_QSGD ? cfg->s : 1;
+  const uint32_t s = is_qsgd(cfg->quantizer) ? cfg->s : 1;
   const uint32_t w_idx = std::max(1u, bit_width_u64(d - 1));
-  const uint32_t w_lev = cfg->quantizer == QSL_QSGD ? bit_width_u64(static_cast<uint64_t>(s) - 1) : 0;
-  const uint32_t w_val = w_lev + 1;
-  const bool counts = cfg->quantizer == QSL_QSGD && L > 1;
+  const uint32_t w_lev = is_qsgd(cfg->quantizer) ? bit_width_u64(static_cast<uint64_t>(s) - 1) : 0;
+  const uint32_t w_val = cfg->quantizer == QSL_FP32 ? 32 : w_lev + 1;
+  const bool counts = is_qsgd(cfg->quantizer) && L > 1;
   uint64_t bits = 32 + 32ull * L + (counts ? 32ull * L : 0);
   bits += align_up(static_cast<uint64_t>(K) * w_idx, 32) + align_up(static_cast<uint64_t>(K) * w_val, 32);
   ctx->capacity = static_cast<size_t>(align_up(bits, 64) / 8);
@@ -1513,7 +1536,7 @@ extern "C" qsl_status qsl_bits_sent(qsl_ctx* ctx, const uint8_t* msg, uint32_t R
   std::vector<uint32_t> nnz(R);
   QSL_HIP(hipMemcpyAsync(nnz.data(), ctx->d_nnz_tmp, 4ull * R, hipMemcpyDeviceToHost, ctx->stream));
   QSL_HIP(hipStreamSynchronize(ctx->stream));
-  const bool counts = c.quantizer == QSL_QSGD && c.L > 1;
+  const bool counts = is_qsgd(c.quantizer) && c.L > 1;
   const uint64_t hdr = 32 + 32ull * c.L + (counts ? 32ull * c.L : 0);
   for (uint32_t r = 0; r < R; ++r) bits_host[r] = hdr + static_cast<uint64_t>(nnz[r]) * (c.w_idx + c.w_val);
   return QSL_OK;

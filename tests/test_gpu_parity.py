@@ -35,10 +35,26 @@ def test_configs_reduced_size(P, cfg):
 
 
 @pytest.mark.parametrize("sparsifier", [W.TOPK, W.RANDK])
-@pytest.mark.parametrize("quantizer,s", [(W.QSGD, 15), (W.QSGD, 1), (W.QSGD, 32768), (W.SIGN_L1, 1)])
+@pytest.mark.parametrize("quantizer,s", [(W.QSGD, 15), (W.QSGD, 1), (W.QSGD, 32768), (W.SIGN_L1, 1), (W.SIGN_L2, 1),
+                                         (W.FP32, 1), (W.QSGD_SCALED, 4), (W.QSGD_SCALED, 15)])
 def test_operator_grid_small(P, sparsifier, quantizer, s):
     wl = custom(40_003, [0, 40_003], [777], s, sparsifier, quantizer, R=3)
     P.run_parity(wl, 2, worker0=5)
+
+
+@pytest.mark.parametrize("quantizer,s", [(W.SIGN_L2, 1), (W.FP32, 1), (W.QSGD_SCALED, 2)])
+def test_operator_variants_on_the_fast_path_and_layerwise(P, quantizer, s):
+    # the variants next to the hot path: l2-scaled sign (Lemma 3, m = 2), no quantiser (TopK-SGD), scaled QSGD (Lemma 2)
+    wl = custom(1_000_003, [0, 1_000_003], [1000], s, W.TOPK, quantizer, R=2)
+    run, op, m_host, _ = P.run_parity(wl, 2, expect_path=0)
+    out = torch.zeros(wl.d, dtype=torch.float32, device=run.q.device)
+    run.q.aggregate(run.msg, out, 0.5)
+    torch.cuda.synchronize()
+    want = op.aggregate(run.msg.cpu().numpy(), 0.5)
+    assert np.allclose(out.cpu().numpy(), want, rtol=1e-6, atol=1e-30)
+    off = [0, 64, 1_000, 40_000, 70_001]
+    wl = custom(70_001, off, [3, 10, 400, 30], s, W.RANDK, quantizer, R=2)
+    P.run_parity(wl, 2)
 
 
 def test_not_in_place(P):
