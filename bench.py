@@ -32,6 +32,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (2 = headline)")
+    ap.add_argument("--from-models", action="store_true",
+                    help="time qsl_compress_diff (Delta = x - xhat formed on the fly; the fresh buffers act as the "
+                         "local models) instead of qsl_compress; not the headline line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rounds", type=int, default=2)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -68,7 +71,10 @@ def main():
     torch.cuda.synchronize()
 
     def step(t):
-        q.compress(m, deltas[t % n_buf], m, 0, t, msg, msg_bits)
+        if args.from_models:
+            q.compress_diff(m, x, deltas[t % n_buf], m, 0, t, msg, msg_bits)
+        else:
+            q.compress(m, deltas[t % n_buf], m, 0, t, msg, msg_bits)
         q.aggregate(msg, x, -1.0 / R, accumulate=True)     # x <- x - (1/R) sum_r g^(r)
 
     if args.calibrate_copy:
@@ -95,12 +101,13 @@ def main():
     bits = msg_bits.cpu().numpy()
 
     avg_stream_s = stream_ms / 1e3 / max(1, launches)
-    achieved = ALGO_BYTES_PER_COORD * R * d / avg_stream_s / 1e9 if launches else None
+    algo_bytes = ALGO_BYTES_PER_COORD * R * d + (4 * d if args.from_models else 0)     # + one read of x
+    achieved = algo_bytes / avg_stream_s / 1e9 if launches else None
     roofline = {"bound": "hbm", "kernel": "k_stream", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
-                "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
+                "traffic": None if args.from_models else MEASURED_TRAFFIC_BYTES.get(args.config),
                 "avg_launch_us": avg_stream_s * 1e6, "launches": launches,
-                "algorithmic_bytes_per_launch": ALGO_BYTES_PER_COORD * R * d}
+                "algorithmic_bytes_per_launch": algo_bytes}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -114,8 +121,11 @@ def main():
         threads = max(1, min(R, cores, int(os.environ.get("OMP_NUM_THREADS", cores))))
         m_host = np.zeros((R, d), dtype=np.float32)
         cpu_t, cpu_coords = 0.0, 0
+        x_now = x.cpu().numpy()
         for t in range(args.cpu_rounds):
             d_host = deltas[t % n_buf].cpu().numpy()
+            if args.from_models:
+                d_host = np.subtract(x_now[None, :], d_host, dtype=np.float32)
             c0 = time.perf_counter()
             with ThreadPoolExecutor(max_workers=threads) as ex:
                 res = list(ex.map(lambda r: op.compress(m_host[r], d_host[r], r, t), range(R)))
@@ -136,7 +146,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "R": R, "d": d, "k": int(wl.K), "s": wl.s, "segments": wl.L,
                    "sparsifier": ["top_k", "rand_k"][wl.sparsifier], "quantizer": ["qsgd", "sign_l1"][wl.quantizer],
-                   "fresh_delta_buffers": n_buf,
+                   "fresh_delta_buffers": n_buf, "delta": "x - xhat on the fly" if args.from_models else "given",
                    "paths": {"fast": int((units[:, 0] == 0).sum()), "general": int((units[:, 0] == 1).sum()),
                              "fallback": int((units[:, 0] == 2).sum())},
                    "max_candidates": int(units[:, 1].max()), "mean_msg_bits": float(bits.mean())},

@@ -111,6 +111,17 @@ qsl_status qsl_compress(qsl_ctx *ctx, const float *m, const float *delta, float 
                         uint32_t R, uint64_t round, uint8_t *msg, uint64_t *msg_bits, uint32_t *sel_idx,
                         uint16_t *sel_level);
 
+/* The same step with the difference of Algorithm 1's synchronisation line formed on the fly:
+ * Delta = x_t - xhat_{t+1/2} is computed in registers (one fp32 subtraction per coordinate, then
+ * v = m + Delta as above), so the caller never materialises Delta.  Bit for bit the result of
+ * qsl_compress on delta[r, j] = x[j] - xhat_half[r, j].
+ *   x          device, const float [d]; the master's model, shared by the R workers
+ *   xhat_half  device, const float [R, d]; the local models after the local step
+ * Neither may overlap m_out.  All other arguments as for qsl_compress.  */
+qsl_status qsl_compress_diff(qsl_ctx *ctx, const float *m, const float *x, const float *xhat_half, float *m_out,
+                             uint32_t worker0, uint32_t R, uint64_t round, uint8_t *msg, uint64_t *msg_bits,
+                             uint32_t *sel_idx, uint16_t *sel_level);
+
 /* Algorithm 1, second worker line on its own: m <- (m + delta) - decode(msg), in place, for R
  * workers.  Gives bit-for-bit the memory that qsl_compress writes to m_out.
  *   m device float [R, d] (updated), delta device const float [R, d], msg device const [R, capacity] */

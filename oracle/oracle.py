@@ -131,6 +131,13 @@ class OracleOp:
         return dict(m_out=m_out, msg=msg, bits=int(bits[0]), sel_idx=sel_idx, sel_level=sel_level, sel_neg=sel_neg,
                     scales=scales, g_val=g_val)
 
+    def compress_diff(self, m, x, xhat_half, worker, rnd):
+        """The synchronisation line of Algorithm 1 as written: g = Q Comp_k(m + x_t - xhat_{t+1/2}), the
+        difference taken first, in fp32."""
+        x = np.ascontiguousarray(x, dtype=np.float32)
+        xhat_half = np.ascontiguousarray(xhat_half, dtype=np.float32)
+        return self.compress(m, np.subtract(x, xhat_half, dtype=np.float32), worker, rnd)
+
     def bits_sent(self, msg):
         msg = np.ascontiguousarray(msg, dtype=np.uint8)
         return int(lib().qslo_bits_sent(_p(msg, C.c_uint8), *self._lay))

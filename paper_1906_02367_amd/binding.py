@@ -45,6 +45,7 @@ def _load():
     lib.qsl_set_stream.argtypes = [vp, vp]; lib.qsl_set_stream.restype = C.c_int
     lib.qsl_msg_capacity_bytes.argtypes = [vp]; lib.qsl_msg_capacity_bytes.restype = C.c_size_t
     lib.qsl_compress.argtypes = [vp, vp, vp, vp, u32, u32, u64, vp, vp, vp, vp]; lib.qsl_compress.restype = C.c_int
+    lib.qsl_compress_diff.argtypes = [vp, vp, vp, vp, vp, u32, u32, u64, vp, vp, vp, vp]; lib.qsl_compress_diff.restype = C.c_int
     lib.qsl_error_update.argtypes = [vp, vp, vp, vp, u32]; lib.qsl_error_update.restype = C.c_int
     lib.qsl_aggregate.argtypes = [vp, vp, C.POINTER(u32), u32, C.c_float, C.c_int, vp]; lib.qsl_aggregate.restype = C.c_int
     lib.qsl_bits_sent.argtypes = [vp, vp, u32, C.POINTER(u64)]; lib.qsl_bits_sent.restype = C.c_int
@@ -58,7 +59,7 @@ def _load():
 _lib = _load()
 
 EXPORTED = ["qsl_create", "qsl_destroy", "qsl_set_stream", "qsl_msg_capacity_bytes", "qsl_compress",
-            "qsl_error_update", "qsl_aggregate", "qsl_bits_sent", "qsl_device_status", "qsl_debug_units",
+            "qsl_compress_diff", "qsl_error_update", "qsl_aggregate", "qsl_bits_sent", "qsl_device_status", "qsl_debug_units",
             "qsl_timing_enable", "qsl_timing_read", "qsl_status_string"]
 
 
@@ -125,6 +126,17 @@ class Qsl:
                                  _ptr(m_out, torch.float32), int(worker0), R, int(rnd), _ptr(msg, torch.uint8),
                                  _ptr(msg_bits, torch.int64, True), _ptr(sel_idx, torch.int32, True),
                                  _ptr(sel_level, torch.int16, True)), "qsl_compress")
+
+    def compress_diff(self, m, x, xhat_half, m_out, worker0, rnd, msg, msg_bits=None, sel_idx=None, sel_level=None):
+        R = m.shape[0]
+        assert m.shape == (R, self.d) and xhat_half.shape == m.shape and m_out.shape == m.shape and x.shape == (self.d,)
+        assert msg.shape == (R, self.capacity)
+        _check(_lib.qsl_set_stream(self._ctx, self._stream()), "qsl_set_stream")
+        _check(_lib.qsl_compress_diff(self._ctx, _ptr(m, torch.float32), _ptr(x, torch.float32),
+                                      _ptr(xhat_half, torch.float32), _ptr(m_out, torch.float32), int(worker0), R,
+                                      int(rnd), _ptr(msg, torch.uint8), _ptr(msg_bits, torch.int64, True),
+                                      _ptr(sel_idx, torch.int32, True), _ptr(sel_level, torch.int16, True)),
+               "qsl_compress_diff")
 
     def error_update(self, m, delta, msg):
         R = m.shape[0]

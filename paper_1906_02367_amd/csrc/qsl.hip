@@ -201,7 +201,8 @@ __global__ void k_init(DevCtx c, uint32_t U) {
 // the guess for Top_k: histogram of the rank keys of a strided sample of v = m + Delta
 // (runs of 64 consecutive coordinates, evenly spaced), then the key at a fixed rank of the sample
 // ------------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(BIG) void k_sample(DevCtx c, const float* m, const float* delta) {
+// With `xm` given, `delta` holds the local models and Delta = xm - delta is formed on the fly.
+__global__ __launch_bounds__(BIG) void k_sample(DevCtx c, const float* m, const float* delta, const float* xm) {
   __shared__ uint32_t lh[HBINS];
   const uint32_t seg = c.fast_segs[blockIdx.y], w = blockIdx.z;
   const SegInfo sg = c.segs[seg];
@@ -221,6 +222,7 @@ __global__ __launch_bounds__(BIG) void k_sample(DevCtx c, const float* m, const 
       ok[r] = run < sg.n_runs && pos < sg.size;
       a[r] = ok[r] ? m[row + pos] : 0.f;
       b[r] = ok[r] ? delta[row + pos] : 0.f;
+      if (xm != nullptr && ok[r]) b[r] = xm[sg.start + pos] - b[r];
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r)
@@ -253,14 +255,24 @@ struct StreamSeg { uint64_t start, size, slot_off, ovf_off; uint32_t lpc, ovf_ca
 
 typedef uint32_t u2v __attribute__((ext_vector_type(2)));
 
-template <int SPARS, bool SINGLE>
+// DIFF: `delta` holds the local models xhat_{t+1/2} and `xm` the master's model x_t (one row of d floats,
+// shared by the workers); Delta = x_t - xhat_{t+1/2} (Algorithm 1, sync step) is formed in registers.  The
+// grid is then one-dimensional and ordered so that the R blocks that read the same four chunks of x_t
+// follow each other on the same XCD (blocks go to the 8 XCDs round-robin), whose L2 serves R - 1 of them.
+template <int SPARS, bool SINGLE, bool DIFF>
 __global__ __launch_bounds__(BLOCK) void k_stream(DevCtx c, StreamSeg one, const float* m, const float* delta,
-                                                  float* m_out, uint32_t worker0, uint64_t round) {
+                                                  const float* xm, float* m_out, uint32_t worker0, uint64_t round,
+                                                  uint32_t R) {
   __shared__ uint2 s_stage[BLOCK / 64][32];
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const uint32_t wt = blockIdx.x * 4 + wave;
+  uint32_t blk = blockIdx.x, w = blockIdx.y;
+  if (DIFF) {
+    const uint32_t slot = blockIdx.x >> 3;
+    w = slot % R;
+    blk = (slot / R) * 8 + (blockIdx.x & 7u);
+  }
+  const uint32_t wt = blk * 4 + wave;
   if (wt >= c.NWT) return;
-  const uint32_t w = blockIdx.y;
   StreamSeg sg = one;
   uint32_t seg = 0, chunk = wt;
   if (!SINGLE) {
@@ -276,19 +288,22 @@ __global__ __launch_bounds__(BLOCK) void k_stream(DevCtx c, StreamSeg one, const
   const uint64_t row = static_cast<uint64_t>(w) * c.d + sg.start;
   const float* mp = m + row;
   const float* dp = delta + row;
+  const float* xp = DIFF ? xm + sg.start : nullptr;
   float* op = m_out + row;
   const uint64_t cb = static_cast<uint64_t>(chunk) * CHUNK;           // segment-local
   f4u v[4];
   if (sg.size - cb >= CHUNK) {
-    f4u a[4], b[4];
+    f4u a[4], b[4], x[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       const uint64_t e = cb + t * 256 + lane * 4;
       a[t] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(mp + e));
       b[t] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(dp + e));
+      if (DIFF) x[t] = *reinterpret_cast<const f4u*>(xp + e);        // cached: the other workers read it too
     }
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
+      if (DIFF) b[t] = x[t] - b[t];
       v[t] = a[t] + b[t];
       __builtin_nontemporal_store(v[t], reinterpret_cast<f4u*>(op + cb + t * 256 + lane * 4));
     }
@@ -299,7 +314,10 @@ __global__ __launch_bounds__(BLOCK) void k_stream(DevCtx c, StreamSeg one, const
       for (int j = 0; j < 4; ++j) {
         const uint64_t e = cb + t * 256 + lane * 4 + j;
         float x = 0.0f;                                               // past the end: never a candidate
-        if (e < sg.size) { x = mp[e] + dp[e]; op[e] = x; }
+        if (e < sg.size) {
+          const float dl = DIFF ? xp[e] - dp[e] : dp[e];
+          x = mp[e] + dl; op[e] = x;
+        }
         v[t][j] = x;
       }
     }
@@ -1446,13 +1464,14 @@ extern "C" qsl_status qsl_set_stream(qsl_ctx* ctx, void* hip_stream) {
 extern "C" size_t qsl_msg_capacity_bytes(const qsl_ctx* ctx) { return ctx ? ctx->capacity : 0; }
 
 template <int SPARS>
-static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* delta, float* m_out, uint32_t worker0,
+static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* delta, const float* xm, float* m_out,
+                                  uint32_t worker0,
                                   uint32_t R, uint64_t round, uint8_t* msg, uint64_t* msg_bits, uint32_t* sel_idx,
                                   uint16_t* sel_level) {
   const DevCtx& c = ctx->dc;
   hipStream_t st = ctx->stream;
   if (SPARS == QSL_TOPK && ctx->n_sampled > 0) {
-    k_sample<<<dim3(ctx->max_nsamp, c.nfast, R), BIG, 0, st>>>(c, m, delta);
+    k_sample<<<dim3(ctx->max_nsamp, c.nfast, R), BIG, 0, st>>>(c, m, delta, xm);
     k_sample_scan<<<dim3(c.nfast, R), BIG, 0, st>>>(c);
   }
   const bool timed = ctx->timing != 0;
@@ -1462,9 +1481,18 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
     }
     QSL_HIP(hipEventRecord(ctx->ev[ctx->ev_used], st));
   }
-  const dim3 sgrid((c.NWT + 3) / 4, R);
-  if (c.L == 1) k_stream<SPARS, true><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, m_out, worker0, round);
-  else k_stream<SPARS, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, m_out, worker0, round);
+  const uint32_t nblk = (c.NWT + 3) / 4;
+  if (xm == nullptr) {
+    const dim3 sgrid(nblk, R);
+    if (c.L == 1) k_stream<SPARS, true, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R);
+    else k_stream<SPARS, false, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R);
+  } else {
+    const uint64_t nb = static_cast<uint64_t>((nblk + 7) / 8) * 8 * R;
+    if (nb > 0x7FFFFFFFull) return QSL_ERR_UNSUPPORTED;
+    const dim3 sgrid(static_cast<uint32_t>(nb));
+    if (c.L == 1) k_stream<SPARS, true, true><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R);
+    else k_stream<SPARS, false, true><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R);
+  }
   if (timed) { QSL_HIP(hipEventRecord(ctx->ev[ctx->ev_used + 1], st)); ctx->ev_used += 2; }
 
   k_select<0, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
@@ -1480,19 +1508,32 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   return QSL_OK;
 }
 
-extern "C" qsl_status qsl_compress(qsl_ctx* ctx, const float* m, const float* delta, float* m_out, uint32_t worker0,
-                                   uint32_t R, uint64_t round, uint8_t* msg, uint64_t* msg_bits, uint32_t* sel_idx,
-                                   uint16_t* sel_level) {
+static qsl_status compress_checked(qsl_ctx* ctx, const float* m, const float* delta, const float* xm, float* m_out,
+                                   uint32_t worker0, uint32_t R, uint64_t round, uint8_t* msg, uint64_t* msg_bits,
+                                   uint32_t* sel_idx, uint16_t* sel_level) {
   if (!ctx || !m || !delta || !m_out || !msg || R == 0 || R > ctx->Rmax || (round >> 62)) return QSL_ERR_INVALID_ARG;
   if (static_cast<uint64_t>(worker0) + R > (1ull << 32)) return QSL_ERR_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(m) | reinterpret_cast<uintptr_t>(delta) | reinterpret_cast<uintptr_t>(m_out) |
-       reinterpret_cast<uintptr_t>(sel_idx)) & 3) return QSL_ERR_INVALID_ARG;
+       reinterpret_cast<uintptr_t>(xm) | reinterpret_cast<uintptr_t>(sel_idx)) & 3) return QSL_ERR_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(msg) | reinterpret_cast<uintptr_t>(msg_bits)) & 7) return QSL_ERR_INVALID_ARG;
   if (reinterpret_cast<uintptr_t>(sel_level) & 1) return QSL_ERR_INVALID_ARG;
   ctx->last_R = R;
   if (ctx->cfg.sparsifier == QSL_TOPK)
-    return launch_compress<QSL_TOPK>(ctx, m, delta, m_out, worker0, R, round, msg, msg_bits, sel_idx, sel_level);
-  return launch_compress<QSL_RANDK>(ctx, m, delta, m_out, worker0, R, round, msg, msg_bits, sel_idx, sel_level);
+    return launch_compress<QSL_TOPK>(ctx, m, delta, xm, m_out, worker0, R, round, msg, msg_bits, sel_idx, sel_level);
+  return launch_compress<QSL_RANDK>(ctx, m, delta, xm, m_out, worker0, R, round, msg, msg_bits, sel_idx, sel_level);
+}
+
+extern "C" qsl_status qsl_compress(qsl_ctx* ctx, const float* m, const float* delta, float* m_out, uint32_t worker0,
+                                   uint32_t R, uint64_t round, uint8_t* msg, uint64_t* msg_bits, uint32_t* sel_idx,
+                                   uint16_t* sel_level) {
+  return compress_checked(ctx, m, delta, nullptr, m_out, worker0, R, round, msg, msg_bits, sel_idx, sel_level);
+}
+
+extern "C" qsl_status qsl_compress_diff(qsl_ctx* ctx, const float* m, const float* x, const float* xhat_half,
+                                        float* m_out, uint32_t worker0, uint32_t R, uint64_t round, uint8_t* msg,
+                                        uint64_t* msg_bits, uint32_t* sel_idx, uint16_t* sel_level) {
+  if (!x) return QSL_ERR_INVALID_ARG;
+  return compress_checked(ctx, m, xhat_half, x, m_out, worker0, R, round, msg, msg_bits, sel_idx, sel_level);
 }
 
 extern "C" qsl_status qsl_error_update(qsl_ctx* ctx, float* m, const float* delta, const uint8_t* msg, uint32_t R) {

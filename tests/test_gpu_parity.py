@@ -253,3 +253,33 @@ def test_results_do_not_depend_on_launch_history(P):
     torch.cuda.synchronize()
     for m, msg in outs[1:]:
         assert torch.equal(m.view(torch.int32), outs[0][0].view(torch.int32)) and torch.equal(msg, outs[0][1])
+
+
+# ---------------------------------------------------------------------------------------------
+# Delta = x_t - xhat_{t+1/2} formed on the fly (the synchronisation line of Algorithm 1 as written)
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cfg,d,R", [(2, 1_000_003, 3), (3, 600_011, 2), (1, 65_536, 2), (4, 2_000_000, 5), (2, 70_001, 9)])
+def test_compress_diff_matches_oracle_and_plain_entry(P, cfg, d, R):
+    from paper_1906_02367_amd import binding as B
+    wl = W.config(cfg, d=d, R=R)
+    op = P.oracle_for(wl)
+    q = B.from_workload(wl)
+    rng = np.random.default_rng(cfg * 100 + R)
+    x = rng.standard_normal(wl.d).astype(f32)
+    m_host = (0.3 * W.delta_all(wl, 11)).astype(f32)
+    for t in range(2):
+        xhat = (x[None, :] - W.delta_all(wl, t)).astype(f32)            # so that x - xhat has the workload's shape
+        m_dev, x_dev, xh_dev = (torch.from_numpy(a).to(q.device) for a in (m_host, x, xhat))
+        msg, msg2 = q.new_msg(R).fill_(0xCD), q.new_msg(R)
+        m_out, m_out2 = torch.empty_like(m_dev), torch.empty_like(m_dev)
+        q.compress_diff(m_dev, x_dev, xh_dev, m_out, 3, t, msg)
+        q.compress(m_dev, x_dev.unsqueeze(0) - xh_dev, m_out2, 3, t, msg2)
+        torch.cuda.synchronize()
+        assert q.device_status() == B.OK
+        assert torch.equal(msg, msg2) and torch.equal(m_out.view(torch.int32), m_out2.view(torch.int32))
+        want = [op.compress_diff(m_host[r], x, xhat[r], 3 + r, t) for r in range(R)]
+        got_msg, got_m = msg.cpu().numpy(), m_out.cpu().numpy()
+        for r in range(R):
+            assert np.array_equal(got_msg[r], want[r]["msg"]), f"round {t} worker {r}: message differs"
+            assert np.array_equal(P.bits(got_m[r]), P.bits(want[r]["m_out"])), f"round {t} worker {r}: memory differs"
+        m_host = got_m

@@ -511,3 +511,39 @@ def test_memory_contracts_over_rounds_and_restart_is_exact():
     for t in range(30, T):
         m2 = o.compress(m2, deltas[t], 0, t)["m_out"]
     assert np.array_equal(bits_of(m), bits_of(m2))
+
+
+# ------------------------------------------------------------------------------------------
+# Algorithm 1 end to end with the oracle on a small quadratic: the memory identity of Section 3.4,
+# xhat_t - xtilde_t = (1/R) sum_r m_t^(r), ties together the sign conventions of Delta, of the memory
+# update and of the master's step (flipping any one of them breaks it)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("quantizer,sparsifier", [(O.SIGN_L1, O.TOPK), (O.QSGD, O.RANDK), (O.QSGD_SCALED, O.TOPK)])
+def test_memory_identity_of_the_virtual_sequence(quantizer, sparsifier):
+    rng = np.random.default_rng(17)
+    d, k, R, H, T = 300, 12, 3, 3, 60
+    o = op(d, k, s=4, sparsifier=sparsifier, quantizer=quantizer)
+    A = rng.standard_normal((R, 40, d)) / math.sqrt(d)
+    y = rng.standard_normal((R, 40))
+    x = np.zeros(d, f32)
+    xh = np.zeros((R, d), f32)
+    m = np.zeros((R, d), f32)
+    xt = np.zeros(d)                                           # virtual sequence, averaged over the workers
+    for t in range(T):
+        eta = 0.5 / (1 + 0.05 * t)
+        i = rng.integers(0, 40, size=R)
+        a = A[np.arange(R), i]
+        g = ((a * xh).sum(1) - y[np.arange(R), i])[:, None] * a          # gradient of 0.5 (a.x - y)^2 at xhat^(r)
+        xh_half = (xh - eta * g).astype(f32)
+        xt -= eta * g.mean(0)
+        if (t + 1) % H == 0:
+            outs = [o.compress_diff(m[r], x, xh_half[r], r, t) for r in range(R)]
+            m = np.stack([q["m_out"] for q in outs])
+            x = o.aggregate(np.stack([q["msg"] for q in outs]), -1.0 / R, out=x)
+            xh = np.repeat(x[None, :], R, axis=0)
+        else:
+            xh = xh_half
+        lhs = xh.astype(np.float64).mean(0) - xt
+        rhs = m.astype(np.float64).mean(0)
+        assert np.abs(lhs - rhs).max() <= 2e-6 * (1 + np.abs(rhs).max()), (t, np.abs(lhs - rhs).max())
+    assert np.abs(m).max() > 0
