@@ -82,7 +82,9 @@ typedef struct {
 } qsl_config;
 
 enum {
-  QSL_FLAG_NO_FAST_PATH = 1   /* always use the general multi-pass selection (testing, comparison)     */
+  QSL_FLAG_NO_FAST_PATH = 1,  /* never guess a threshold: exact multi-pass selection only (testing, comparison) */
+  QSL_FLAG_NO_SMALL_PATH = 2  /* segments of at most 65,536 coordinates also take the multi-pass kernels
+                                 instead of the one-block selection (testing, comparison)               */
 };
 
 /* Create a context for one operator on the current HIP device.  `hip_stream` is a hipStream_t
@@ -148,8 +150,8 @@ qsl_status qsl_device_status(qsl_ctx *ctx);
 
 /* Per-unit diagnostics of the last compress call (unit = worker-major (worker, segment)); synchronises.
  * out_host receives, per unit, 8 uint32: {path, candidates, threshold key, n_greater, n_equal_taken,
- * guess key, reserved, reserved}; path: 0 = single-pass fast path, 1 = general path by
- * configuration, 2 = general path after a failed guess.  */
+ * guess key, scale bits, transmitted}; path: 0 = single-pass fast path, 1 = multi-pass path by
+ * configuration, 2 = multi-pass path after a failed guess, 3 = one-block selection of a small segment.  */
 qsl_status qsl_debug_units(qsl_ctx *ctx, uint32_t *out_host, uint32_t max_units, uint32_t *n_units);
 
 /* Kernel timing for the benchmark: when enabled, compress calls bracket the streaming kernel with

@@ -17,6 +17,7 @@ from .build import LIB_PATH
 TOPK, RANDK = 0, 1
 QSGD, SIGN_L1, SIGN_L2, FP32, QSGD_SCALED = 0, 1, 2, 3, 4
 FLAG_NO_FAST_PATH = 1
+FLAG_NO_SMALL_PATH = 2
 
 OK, ERR_INVALID_ARG, ERR_BUFFER_TOO_SMALL, ERR_NONFINITE_INPUT, ERR_DEVICE, ERR_UNSUPPORTED = range(6)
 

@@ -1,15 +1,17 @@
 // qsl.hip -- kernels and C ABI of the compression hot path of Qsparse-local-SGD for gfx950.
 //
 // One synchronisation step of Algorithm 1 (arXiv:1906.02367) for a batch of R workers:
-//   k_sample     the guess (Top_k only): a quantile of a strided sample of |m + Delta|; for Rand_k
-//                the rank keys are uniform random words, so the guess is analytic
+//   k_sample     the guess (Top_k only): a quantile of a strided sample of |m + Delta| (of group maxima
+//                of the whole unit when no sample is reliable); for Rand_k the rank keys are uniform
+//                random words, so the guess is analytic
 //   k_stream     v = m + Delta (worker line 1), written over the error memory in ONE pass over HBM;
 //                each wave streams one chunk of 1024 coordinates and leaves the coordinates whose
 //                rank key reaches the unit's guess in the chunk's own slot line (written as one
 //                full 128-byte line: no read-modify-write in HBM, no atomic to wait for)
 //   k_select<l>  exact radix selection of the k-th largest key (Section 2.2: Top_k / Rand_k), 12+12+8
 //                bits, over the candidates -- or over the whole vector when the guess failed or the
-//                unit is too small/dense for guessing (the general path; always exact)
+//                unit is too dense for guessing (the general path; always exact)
+//   k_small      a unit of at most 16 chunks: selection, ordered compaction and norm by one block
 //   k_tile_count / k_tile_write    ordered compaction of the selected coordinates, ties to the lower index
 //                (k_tile_write also accumulates the exact ||v_S||_2^2 or ||v_S||_1: proof of Lemma 1; Lemma 3, m = 1)
 //   k_quantize   QSGD levels (Definition 1, example 1) or signs (Definition 2); error update
@@ -60,7 +62,8 @@ constexpr uint32_t CTR_OVF = NSUB;         // counter NSUB: cursor of the unit's
 constexpr uint32_t CTR_FAIL = NSUB + 1;    // counter NSUB + 1: set when the overflow pool ran out
 constexpr uint32_t CTR_LINES = NSUB + 2;
 
-enum : uint32_t { PATH_FAST = 0, PATH_GENERAL = 1, PATH_FALLBACK = 2 };
+enum : uint32_t { PATH_FAST = 0, PATH_GENERAL = 1, PATH_FALLBACK = 2, PATH_SMALL = 3 };
+constexpr uint32_t SMALL_CHUNKS = 16;      // a unit of at most 16 chunks (16,384 coordinates) is selected by one block
 
 struct SegInfo {
   uint64_t start, size;
@@ -73,14 +76,14 @@ struct SegInfo {
   uint32_t wc_base;      // first per-wave counter of this segment (per worker)
   uint32_t cb_base, ncb; // compaction blocks: index of the first one (per worker), how many
   uint32_t nsamp;        // blocks of this unit in the sampling kernel
-  uint32_t mode;         // PATH_FAST or PATH_GENERAL, decided on the host from (size, k)
+  uint32_t mode;         // PATH_FAST, PATH_GENERAL or PATH_SMALL, decided on the host from (size, k)
   uint32_t lpc;          // slot size: lpc * 16 bytes per chunk (4: 64 bytes, 8: one 128-byte line, 16: two lines)
   uint32_t ovf_cap;      // entries of the overflow pool
   uint32_t n_runs;       // sample: runs of 64 consecutive coordinates
   uint32_t r_s;          // sample rank that defines the guess
   uint32_t T_static;     // Rand_k: analytic guess
   uint32_t nsel;         // blocks of this unit in the selection kernels
-  uint32_t pad;
+  uint32_t samp_stride;  // sample: distance between the starts of two runs (64: the whole unit is read)
 };
 
 struct WtInfo { uint32_t seg, chunk, pad0, pad1; };                 // one chunk (multi-segment contexts only)
@@ -89,7 +92,7 @@ struct CbInfo { uint32_t seg, b, pad0, pad1; };                     // one compa
 
 // Every field is written by exactly one kernel of a call and read only by later kernels.
 struct UnitState {
-  uint32_t path;        // static: PATH_FAST or PATH_GENERAL
+  uint32_t path;        // static: PATH_FAST, PATH_GENERAL or PATH_SMALL
   uint32_t T;           // guess key (k_sample_scan; static for Rand_k and for the general path)
   uint32_t cand;        // candidates collected (k_select<0>)
   uint32_t fell_back;   // 1: the guess failed, the unit runs the general path (k_select<0>)
@@ -101,8 +104,9 @@ struct UnitState {
 };
 
 struct DevCtx {
-  const SegInfo* segs; const WtInfo* wts; const SelInfo* sels; const CbInfo* cbs;
+  const SegInfo* segs; const WtInfo* wts; const SelInfo* sels; const SelInfo* samps; const CbInfo* cbs;
   const uint32_t* fast_segs;
+  const uint32_t* small_segs;
   UnitState* units;
   uint2* slots; uint64_t slot_stride;   // per worker: one slot (lpc * 2 elements) per chunk of every fast segment
   uint2* ovf; uint64_t ovf_stride;      // per worker: overflow pools, for chunks with more candidates than a slot holds
@@ -143,19 +147,20 @@ __device__ __forceinline__ uint32_t eff_path(const UnitState& us) {
   return us.path == PATH_FAST && us.fell_back ? static_cast<uint32_t>(PATH_FALLBACK) : us.path;
 }
 
-// Find, scanning a 4096-bin histogram from its top, the bin in which the running count reaches
-// `target` (1-based).  NT threads (the whole block), thread t owns the 4096/NT bins below
-// 4096 - t * 4096/NT.  Returns the bin; *above = count in the bins above it.  If the histogram
+// Find, scanning the first NBINS bins of a histogram from the top, the bin in which the running count
+// reaches `target` (1-based).  NT threads (the whole block), thread t owns the NBINS/NT bins below
+// NBINS - t * NBINS/NT.  Returns the bin; *above = count in the bins above it.  If the histogram
 // holds fewer than `target` entries, returns bin 0 with *above = total - hist[0].  If `clear`,
 // zeroes the histogram afterwards.
-template <uint32_t NT>
+template <uint32_t NT, uint32_t NBINS = HBINS>
 __device__ uint32_t find_from_top(uint32_t* hist, uint32_t target, uint32_t* above, uint64_t* scratch,
                                   uint32_t* result, bool clear) {
-  constexpr uint32_t PER = HBINS / NT;
+  constexpr uint32_t PER = NBINS / NT;
+  static_assert(PER >= 1 && PER * NT == NBINS, "bins must divide evenly over the threads");
   const uint32_t t = threadIdx.x;
   uint32_t h[PER]; uint32_t sum = 0;
 #pragma unroll
-  for (uint32_t j = 0; j < PER; ++j) { h[j] = hist[HBINS - 1 - (PER * t + j)]; sum += h[j]; }
+  for (uint32_t j = 0; j < PER; ++j) { h[j] = hist[NBINS - 1 - (PER * t + j)]; sum += h[j]; }
   uint64_t total;
   const uint64_t before = block_exclusive_scan64(sum, scratch, &total);
   if (t == NT - 1) { result[0] = 0; result[1] = static_cast<uint32_t>(total) - h[PER - 1]; }
@@ -164,13 +169,13 @@ __device__ uint32_t find_from_top(uint32_t* hist, uint32_t target, uint32_t* abo
     uint32_t cum = static_cast<uint32_t>(before);
 #pragma unroll
     for (uint32_t j = 0; j < PER; ++j) {
-      if (cum + h[j] >= target) { result[0] = HBINS - 1 - (PER * t + j); result[1] = cum; break; }
+      if (cum + h[j] >= target) { result[0] = NBINS - 1 - (PER * t + j); result[1] = cum; break; }
       cum += h[j];
     }
   }
   if (clear) {
 #pragma unroll
-    for (uint32_t j = 0; j < PER; ++j) if (h[j]) hist[HBINS - 1 - (PER * t + j)] = 0;
+    for (uint32_t j = 0; j < PER; ++j) if (h[j]) hist[NBINS - 1 - (PER * t + j)] = 0;
   }
   __syncthreads();
   *above = result[1];
@@ -199,21 +204,57 @@ __global__ void k_init(DevCtx c, uint32_t U) {
 
 // ------------------------------------------------------------------------------------------------
 // the guess for Top_k: histogram of the rank keys of a strided sample of v = m + Delta
-// (runs of 64 consecutive coordinates, evenly spaced), then the key at a fixed rank of the sample
+// (runs of 64 consecutive coordinates, evenly spaced), then the key at a fixed rank of the sample.
+// A unit too small for a sample to be reliable is read whole: the guess is then the lower edge of
+// the histogram bin that holds the k-th largest of the maxima of groups of 16 coordinates, which
+// can never lie above the k-th largest key.
 // ------------------------------------------------------------------------------------------------
 // With `xm` given, `delta` holds the local models and Delta = xm - delta is formed on the fly.
 __global__ __launch_bounds__(BIG) void k_sample(DevCtx c, const float* m, const float* delta, const float* xm) {
   __shared__ uint32_t lh[HBINS];
-  const uint32_t seg = c.fast_segs[blockIdx.y], w = blockIdx.z;
+  const SelInfo si = c.samps[blockIdx.x];
+  const uint32_t seg = si.seg, w = blockIdx.y;
   const SegInfo sg = c.segs[seg];
-  if (blockIdx.x >= sg.nsamp) return;
   for (uint32_t i = threadIdx.x; i < HBINS; i += BIG) lh[i] = 0;
   __syncthreads();
   const uint64_t row = static_cast<uint64_t>(w) * c.d + sg.start;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   const uint32_t nwaves = sg.nsamp * (BIG / 64);
-  const uint64_t stride = sg.size / sg.n_runs;           // >= 64: the runs do not overlap
-  for (uint32_t run0 = blockIdx.x * (BIG / 64) + wave; run0 < sg.n_runs; run0 += 4 * nwaves) {
+  const uint64_t stride = sg.samp_stride;                // >= 64: the runs do not overlap
+  if (stride == 64) {                                     // the whole unit: a wave per chunk, 16 values per lane
+    for (uint64_t ch = si.j * (BIG / 64) + wave; ch < sg.nwt; ch += nwaves) {
+      f4u a[4], b[4], x[4];
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const uint64_t e = ch * CHUNK + t * 256 + lane * 4;
+        a[t] = b[t] = x[t] = f4u{0.f, 0.f, 0.f, 0.f};
+        if (e + 4 <= sg.size) {
+          a[t] = *reinterpret_cast<const f4u*>(m + row + e);
+          b[t] = *reinterpret_cast<const f4u*>(delta + row + e);
+          if (xm != nullptr) x[t] = *reinterpret_cast<const f4u*>(xm + sg.start + e);
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j)
+            if (e + j < sg.size) { a[t][j] = m[row + e + j]; b[t][j] = delta[row + e + j]; if (xm != nullptr) x[t][j] = xm[sg.start + e + j]; }
+        }
+      }
+      // Only the largest key of each lane's 16 coordinates is counted: the k-th largest of these
+      // group maxima cannot exceed the k-th largest key (k distinct coordinates are at least as large),
+      // so the bin it falls in still gives a valid guess, for a sixteenth of the LDS atomics.
+      uint32_t top = 0; bool any = false;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const uint64_t e = ch * CHUNK + t * 256 + lane * 4;
+        if (xm != nullptr) b[t] = x[t] - b[t];
+        const f4u vv = a[t] + b[t];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          if (e + j < sg.size) { top = max(top, key_of_value(__float_as_uint(vv[j]))); any = true; }
+      }
+      if (any) atomicAdd(&lh[top >> 20], 1u);
+    }
+  } else
+  for (uint32_t run0 = si.j * (BIG / 64) + wave; run0 < sg.n_runs; run0 += 4 * nwaves) {
     float a[4], b[4]; bool ok[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -518,9 +559,16 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, const float* v, uint32
     const uint64_t r_lo = gw * rpw, r_hi = r_lo + rpw < nrows ? r_lo + rpw : nrows;
     uint32_t seen = 0;                              // digit 0: candidates this wave met
     uint32_t off = 0;                               // digit 1: where this wave's candidates go in the dense list
-    if (LEVEL == 1) {
+    if (LEVEL == 1) {                               // at most MAX_SELECT_BLOCKS * 16 = 1024 waves: 16 loads in flight
+      uint32_t part[MAX_SELECT_BLOCKS * (BIG / 64) / WAVE];
+#pragma unroll
+      for (uint32_t i = 0; i < MAX_SELECT_BLOCKS * (BIG / 64) / WAVE; ++i) {
+        const uint32_t g = i * WAVE + lane;
+        part[i] = g < gw ? wcnt[g] : 0u;
+      }
       uint32_t x = 0;
-      for (uint32_t g = lane; g < gw; g += WAVE) x += wcnt[g];
+#pragma unroll
+      for (uint32_t i = 0; i < MAX_SELECT_BLOCKS * (BIG / 64) / WAVE; ++i) x += part[i];
       off = wave_sum(x);
     }
     for (uint64_t row0 = r_lo; row0 < r_hi; row0 += 4) {
@@ -567,10 +615,40 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, const float* v, uint32
     }
   } else {
     const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
-    for (uint64_t t = si.j; t < sg.nwt; t += sg.nsel) {
-      const uint64_t e = t * CHUNK + threadIdx.x;
-      uint32_t bin;
-      if (e < sg.size && level_bin<LEVEL>(coord_key<SPARS>(vp, e, sg.start, rk), prefix, &bin)) atomicAdd(&lh[bin], 1u);
+    const uint32_t nwaves = sg.nsel * (BIG / 64);
+    // a wave takes two chunks per step, 32 values per lane in flight
+    for (uint64_t ch = (si.j * (BIG / 64) + wave) * 2; ch < sg.nwt; ch += 2ull * nwaves) {
+      f4u x[2][4];
+      if (SPARS == QSL_TOPK) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const uint64_t e = (ch + h) * CHUNK + t * 256 + lane * 4;
+            x[h][t] = f4u{0.f, 0.f, 0.f, 0.f};
+            if (e + 4 <= sg.size) x[h][t] = *reinterpret_cast<const f4u*>(vp + e);
+            else {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) if (e + j < sg.size) x[h][t][j] = vp[e + j];
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const uint64_t e = (ch + h) * CHUNK + t * 256 + lane * 4;
+          Words4 rw = {{0u, 0u, 0u, 0u}};
+          if (SPARS == QSL_RANDK && e < sg.size) rw = rand_words4(rk, static_cast<uint32_t>(sg.start + e));
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(__float_as_uint(x[h][t][j])) : rw.w[j];
+            uint32_t bin;
+            if (e + j < sg.size && level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
+          }
+        }
+      }
     }
   }
   __syncthreads();
@@ -592,6 +670,7 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, const float* v, uint32
 // ------------------------------------------------------------------------------------------------
 constexpr uint32_t DTILE = 2048;           // dense-list entries per compaction block
 constexpr uint32_t GGROUP = 16;            // chunks per general-path group
+constexpr uint32_t ACC_ROWS = 32;          // accumulator rows of a compaction block (8 per wave)
 
 struct Thresh { uint32_t tau, need; };
 
@@ -625,7 +704,10 @@ __device__ __forceinline__ void load_chunk_masks(const float* vp, uint64_t cb, u
   *gmask = gm; *qmask = qm;
 }
 
-// digits of |v| (or v^2) into the thread's private accumulator row
+// digits of |v| (or v^2) into an accumulator row in LDS that a few lanes share (hence the atomics)
+__device__ __forceinline__ void lds_add(uint64_t* p, uint64_t x) {
+  atomicAdd(reinterpret_cast<unsigned long long*>(p), static_cast<unsigned long long>(x));
+}
 __device__ __forceinline__ void add_digits(uint64_t* mine, uint32_t bits, bool squares) {
   const uint32_t ab = bits & 0x7FFFFFFFu;
   const uint32_t ex = ab >> 23, frac = ab & 0x7FFFFFu;
@@ -638,12 +720,14 @@ __device__ __forceinline__ void add_digits(uint64_t* mine, uint32_t bits, bool s
     const uint32_t q = p >> 5, r = p & 31u;
     const uint64_t lo = sq << r;                            // low 64 bits of sq * 2^r  (r <= 30)
     const uint64_t hi = r ? (sq >> (64 - r)) : 0;
-    mine[q] += lo & 0xFFFFFFFFu; mine[q + 1] += lo >> 32; mine[q + 2] += hi;
+    lds_add(&mine[q], lo & 0xFFFFFFFFu); lds_add(&mine[q + 1], lo >> 32);
+    if (hi) lds_add(&mine[q + 2], hi);
   } else {
     const uint32_t p = e1 - 1u;                             // bit position above 2^-149
     const uint32_t q = p >> 5, r = p & 31u;
     const uint64_t sh = static_cast<uint64_t>(M) << r;      // < 2^55
-    mine[q] += sh & 0xFFFFFFFFu; mine[q + 1] += sh >> 32;
+    lds_add(&mine[q], sh & 0xFFFFFFFFu);
+    if (sh >> 32) lds_add(&mine[q + 1], sh >> 32);
   }
 }
 
@@ -721,7 +805,7 @@ __device__ void general_groups(const DevCtx& c, const SegInfo& sg, const float* 
 __device__ __forceinline__ Thresh last_digit(const DevCtx& c, uint64_t u, const UnitState& us, uint64_t* scratch,
                                              uint32_t* result) {
   uint32_t above;
-  const uint32_t bin = find_from_top<BLOCK>(c.hist + (u * 3 + 2) * HBINS, us.k_rem, &above, scratch, result, false);
+  const uint32_t bin = find_from_top<BLOCK, 256>(c.hist + (u * 3 + 2) * HBINS, us.k_rem, &above, scratch, result, false);
   Thresh th; th.tau = us.prefix | bin; th.need = us.k_rem - above;
   return th;
 }
@@ -730,6 +814,144 @@ __device__ __forceinline__ Thresh last_digit(const DevCtx& c, uint64_t u, const 
 __device__ __forceinline__ void fallback_range(const SegInfo& sg, uint32_t b, uint32_t* g_lo, uint32_t* g_hi) {
   const uint64_t ngg = (static_cast<uint64_t>(sg.nwt) + GGROUP - 1) / GGROUP;
   *g_lo = static_cast<uint32_t>(ngg * b / sg.ncb); *g_hi = static_cast<uint32_t>(ngg * (b + 1) / sg.ncb);
+}
+
+// ------------------------------------------------------------------------------------------------
+// small units (at most 16 chunks): the whole selection by one block of 256 threads.  Thread t keeps 16
+// consecutive coordinates of each of up to four tiles of 4096 in registers (Top_k: the bits of v;
+// Rand_k: the random words), the three digit
+// histograms live in LDS, and the block writes the selected coordinates in order together with the
+// digits of their norm -- what k_select<0..2>, k_tile_count and k_tile_write do for a larger unit,
+// without a launch in between.  (One CU retires ~64 lane-operations per cycle, so a block is kept
+// to 16,384 coordinates; and a kernel of many short-lived waves is bound by the rate at which waves
+// start, so the block is kept to four waves.)
+// ------------------------------------------------------------------------------------------------
+constexpr uint32_t SMALL_TILE = BLOCK * 16;       // 4096 coordinates: 16 consecutive ones per thread
+
+template <int LEVEL, int SPARS>
+__device__ __forceinline__ void small_hist(const uint32_t (&kv)[4][16], uint32_t M, uint32_t n, uint32_t prefix,
+                                           uint32_t* lh) {
+#pragma unroll
+  for (uint32_t i = 0; i < 4; ++i) {
+    if (i >= M) break;                                               // uniform over the block
+    const uint32_t e0 = (i * BLOCK + threadIdx.x) * 16;
+#pragma unroll
+    for (uint32_t j = 0; j < 16; ++j) {
+      const uint32_t key = SPARS == QSL_TOPK ? key_of_value(kv[i][j]) : kv[i][j];
+      uint32_t bin;
+      if (e0 + j < n && level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
+    }
+  }
+}
+
+template <int SPARS>
+__global__ __launch_bounds__(BLOCK) void k_small(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
+  __shared__ uint32_t lh[HBINS];
+  __shared__ uint64_t acc[ACC_ROWS * (ACC_SLOTS + 1)];
+  __shared__ uint64_t scratch[17];
+  __shared__ uint32_t result[2];
+  const uint32_t seg = c.small_segs[blockIdx.x], w = blockIdx.y;
+  const SegInfo sg = c.segs[seg];
+  const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
+  const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
+  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t n = static_cast<uint32_t>(sg.size);                 // <= SMALL_CHUNKS * CHUNK = 4 * SMALL_TILE
+  const uint32_t M = (n + SMALL_TILE - 1) / SMALL_TILE;              // 1 .. 4 tiles
+  uint32_t kv[4][16];
+#pragma unroll
+  for (uint32_t i = 0; i < 4; ++i) {
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {
+      const uint32_t e = (i * BLOCK + threadIdx.x) * 16 + q * 4;
+      if (SPARS == QSL_TOPK) {
+        f4u x = {0.f, 0.f, 0.f, 0.f};
+        if (e + 4 <= n) x = *reinterpret_cast<const f4u*>(vp + e);
+        else {
+#pragma unroll
+          for (uint32_t j = 0; j < 4; ++j) if (e + j < n) x[j] = vp[e + j];
+        }
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) kv[i][q * 4 + j] = __float_as_uint(x[j]);
+      } else {
+        Words4 rw = {{0u, 0u, 0u, 0u}};
+        if (e < n) rw = rand_words4(rk, static_cast<uint32_t>(sg.start) + e);
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) kv[i][q * 4 + j] = rw.w[j];
+      }
+    }
+  }
+  for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;
+
+  // the three digits of the k-th largest key
+  uint32_t above;
+  for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK) lh[i] = 0;
+  __syncthreads();
+  small_hist<0, SPARS>(kv, M, n, 0, lh);
+  __syncthreads();
+  uint32_t bin = find_from_top<BLOCK>(lh, sg.k, &above, scratch, result, true);
+  uint32_t prefix = bin << 20, k_rem = sg.k - above;
+  small_hist<1, SPARS>(kv, M, n, prefix, lh);
+  __syncthreads();
+  bin = find_from_top<BLOCK>(lh, k_rem, &above, scratch, result, true);
+  prefix |= bin << 8; k_rem -= above;
+  small_hist<2, SPARS>(kv, M, n, prefix, lh);
+  __syncthreads();
+  bin = find_from_top<BLOCK, 256>(lh, k_rem, &above, scratch, result, false);
+  const uint32_t tau = prefix | bin, need = k_rem - above;
+
+  // ordered compaction: key > tau, and the first `need` coordinates with key == tau
+  uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
+  uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
+  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
+  const bool squares = wants_squares(c.quantizer);
+  uint32_t run_gt = 0, run_eq = 0;
+#pragma unroll
+  for (uint32_t i = 0; i < 4; ++i) {
+    if (i >= M) break;                                               // uniform over the block
+    const uint32_t e0 = (i * BLOCK + threadIdx.x) * 16;
+    uint32_t gm = 0, qm = 0;
+#pragma unroll
+    for (uint32_t j = 0; j < 16; ++j) {
+      const uint32_t key = SPARS == QSL_TOPK ? key_of_value(kv[i][j]) : kv[i][j];
+      const bool inside = e0 + j < n;
+      gm |= (inside && key > tau ? 1u : 0u) << j;
+      qm |= (inside && key == tau ? 1u : 0u) << j;
+    }
+    uint64_t total;
+    const uint64_t ex = block_exclusive_scan64((static_cast<uint64_t>(__popc(qm)) << 32) | __popc(gm), scratch, &total);
+    const uint32_t gt0 = run_gt + static_cast<uint32_t>(ex), eq0 = run_eq + static_cast<uint32_t>(ex >> 32);
+    // which of this thread's ties are kept: the first need - eq0 of them
+    uint32_t keep = 0;
+    if (eq0 < need) {
+      keep = qm;
+      for (uint32_t extra = eq0 + __popc(qm); extra > need; --extra) keep &= ~(0x80000000u >> __clz(keep));   // drop the last
+    }
+    const uint32_t sel = gm | keep;
+#pragma unroll
+    for (uint32_t j = 0; j < 16; ++j) {
+      if ((sel >> j) & 1u) {
+        const uint32_t below = (1u << j) - 1u;
+        const uint32_t pos = gt0 + __popc(gm & below) + min(eq0 + __popc(qm & below), need);
+        const uint32_t bits = SPARS == QSL_TOPK ? kv[i][j] : __float_as_uint(vp[e0 + j]);
+        oi[pos] = static_cast<uint32_t>(sg.start) + e0 + j; ov[pos] = bits;
+        add_digits(mine, bits, squares);
+      }
+    }
+    run_gt += static_cast<uint32_t>(total); run_eq += static_cast<uint32_t>(total >> 32);
+  }
+  __syncthreads();
+  // the unit is this block's alone: its norm digits are stored, not added
+  for (uint32_t sl = wave; sl < ACC_SLOTS; sl += BLOCK / 64) {
+    uint64_t x = lane < ACC_ROWS ? acc[lane * (ACC_SLOTS + 1) + sl] : 0;
+    x = wave_sum64(x);
+    if (lane == 0) c.norm_acc[u * ACC_SLOTS + sl] = x;
+  }
+  if (threadIdx.x == 0) {
+    UnitState* us = &c.units[u];
+    us->cand = 0; us->fell_back = 0; us->prefix = tau & ~0xFFu; us->k_rem = k_rem;
+    us->tau = tau; us->need = need; us->n_gt = sg.k - need; us->nnz = 0;
+  }
 }
 
 template <int SPARS>
@@ -742,6 +964,10 @@ __global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, const float* v, 
   const uint64_t u = static_cast<uint64_t>(w) * c.L + cb.seg;
   const UnitState us = c.units[u];
   const uint32_t path = eff_path(us);
+  if (path == PATH_FAST && cb.b != 0 && cb.b * DTILE >= us.cand) {         // a tile past the end of the dense list
+    if (threadIdx.x == 0) c.cb_cnt[static_cast<uint64_t>(w) * c.NCB + sg.cb_base + cb.b] = make_uint2(0, 0);
+    return;
+  }
   const Thresh th = last_digit(c, u, us, scratch, result);
   if (threadIdx.x == 0 && cb.b == 0) { c.units[u].tau = th.tau; c.units[u].need = th.need; c.units[u].n_gt = sg.k - th.need; }
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
@@ -774,7 +1000,7 @@ __global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, const float* v, 
 
 template <int SPARS>
 __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
-  __shared__ uint64_t acc[BLOCK * (ACC_SLOTS + 1)];
+  __shared__ uint64_t acc[ACC_ROWS * (ACC_SLOTS + 1)];      // a row per 8 lanes of a wave: short atomic queues
   __shared__ uint32_t s_cnt[2 * GGROUP + 2];
   __shared__ uint64_t scratch[17], s_part[4];
   const CbInfo cb = c.cbs[blockIdx.x];
@@ -783,13 +1009,13 @@ __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, const float* v, 
   const uint64_t u = static_cast<uint64_t>(w) * c.L + cb.seg;
   const UnitState us = c.units[u];
   const uint32_t path = eff_path(us);
+  if (path == PATH_FAST && cb.b * DTILE >= us.cand) return;                 // a tile past the end of the dense list
   Thresh th; th.tau = us.tau; th.need = us.need;
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   const bool squares = wants_squares(c.quantizer);
-  uint64_t* mine = acc + threadIdx.x * (ACC_SLOTS + 1);
-#pragma unroll
-  for (uint32_t i = 0; i < ACC_SLOTS; ++i) mine[i] = 0;
+  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
+  for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;   // published by the barrier below
   // how many selected coordinates precede this block: the sum of the unit's earlier blocks' counts
   {
     const uint2* cc = c.cb_cnt + static_cast<uint64_t>(w) * c.NCB + sg.cb_base;
@@ -840,9 +1066,7 @@ __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, const float* v, 
   __syncthreads();
   uint64_t* ga = c.norm_acc + u * ACC_SLOTS;
   for (uint32_t s = wave; s < ACC_SLOTS; s += 4) {
-    uint64_t x = 0;
-#pragma unroll
-    for (uint32_t r = 0; r < BLOCK; r += WAVE) x += acc[(r + lane) * (ACC_SLOTS + 1) + s];
+    uint64_t x = lane < ACC_ROWS ? acc[lane * (ACC_SLOTS + 1) + s] : 0;
     x = wave_sum64(x);
     if (lane == 0 && x) atomicAdd(reinterpret_cast<unsigned long long*>(ga + s), static_cast<unsigned long long>(x));
   }
@@ -1223,8 +1447,9 @@ struct qsl_ctx {
   void* slab;                 // one allocation holding every scratch array
   uint32_t Rmax;
   uint32_t last_R;
+  uint32_t nsmall;            // segments selected by one block each (k_small)
   uint32_t n_sampled;         // segments whose guess comes from k_sample
-  uint32_t max_nsamp;         // most sampling blocks any of them uses
+  uint32_t nsamp_blocks;      // blocks of the sampling kernel (per worker)
   size_t capacity;
   uint32_t* h_status;         // pinned
   uint32_t* d_nnz_tmp;
@@ -1297,11 +1522,11 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   std::vector<SegInfo>& segs = ctx->segs;
   segs.resize(L);
   std::vector<WtInfo> wts;
-  std::vector<SelInfo> sels;
+  std::vector<SelInfo> sels, samps;
   std::vector<CbInfo> cbs;
-  std::vector<uint32_t> fast;
+  std::vector<uint32_t> fast, smalls;
   uint64_t slot_elems = 0, ovf_entries = 0, d0_entries = 0, nwt64 = 0, nwc = 0;
-  uint32_t koff = 0, max_nsamp = 1;
+  uint32_t koff = 0;
   ctx->n_sampled = 0;
   for (uint32_t l = 0; l < L; ++l) {
     SegInfo& sg = segs[l];
@@ -1313,29 +1538,46 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
     if (L > 1) {
       for (uint32_t t = 0; t < sg.nwt; ++t) { WtInfo wi; wi.seg = l; wi.chunk = t; wi.pad0 = wi.pad1 = 0; wts.push_back(wi); }
     }
-    sg.mode = PATH_GENERAL;
+    sg.mode = (sg.nwt <= SMALL_CHUNKS && !(cfg->flags & QSL_FLAG_NO_SMALL_PATH)) ? PATH_SMALL : PATH_GENERAL;
     sg.T_static = 0xFFFFFFFFu;
     sg.lpc = 8;
     const double n = static_cast<double>(sg.size), p = static_cast<double>(sg.k) / n;
-    double cand = 0;                                // expected number of candidates
-    if (!(cfg->flags & QSL_FLAG_NO_FAST_PATH) && sg.size >= (1u << 18)) {
+    double cand = 0, slack = 0;                     // expected number of candidates, room beyond 4x that
+    if (!(cfg->flags & QSL_FLAG_NO_FAST_PATH) && sg.nwt > SMALL_CHUNKS) {
       if (cfg->sparsifier == QSL_TOPK && static_cast<uint64_t>(sg.k) * 64 <= sg.size) {
         // candidates ~ alpha k; the sample must hold enough of them for the guess to sit below the
         // true threshold with ~6.5 sigma: (alpha - 1) sqrt(n_s p) >= 6.5 sqrt(alpha)
-        const double alphas[4] = {1.5, 2.0, 3.0, 4.0};
-        for (double alpha : alphas) {
-          const double n_s = 42.25 * alpha / ((alpha - 1) * (alpha - 1) * p);
-          if (n_s > n / 16) continue;
-          sg.n_runs = static_cast<uint32_t>(std::ceil(n_s / 64.0));
-          sg.r_s = static_cast<uint32_t>(std::ceil(alpha * (sg.n_runs * 64.0) * p));
-          sg.nsamp = std::min(MAX_SAMPLE_BLOCKS, std::max(16u, sg.n_runs / 128));
-          max_nsamp = std::max(max_nsamp, sg.nsamp);
-          cand = alpha * sg.k;
-          sg.d0_cap = static_cast<uint32_t>(std::min<double>(n, 4.0 * cand + 8192.0));
-          sg.mode = PATH_FAST;
-          ++ctx->n_sampled;
-          break;
+        // (a small unit has a small k, so a generous alpha costs few candidates and saves most of the sample)
+        const double alphas[10] = {1.5, 2.0, 3.0, 4.0, 6.0, 8.0, 12.0, 16.0, 24.0, 32.0};
+        for (double frac : {1.0 / 16, 1.0 / 4}) {
+          for (double alpha : alphas) {
+            const double n_s = 42.25 * alpha / ((alpha - 1) * (alpha - 1) * p);
+            if (n_s > n * frac) continue;
+            sg.n_runs = static_cast<uint32_t>(std::ceil(n_s / 64.0));
+            sg.samp_stride = static_cast<uint32_t>(sg.size / sg.n_runs);
+            sg.r_s = static_cast<uint32_t>(std::ceil(alpha * (sg.n_runs * 64.0) * p));
+            sg.nsamp = std::min(MAX_SAMPLE_BLOCKS, std::max(1u, (sg.n_runs + 255) / 256));   // 16 runs per wave
+            cand = alpha * sg.k;
+            slack = alpha <= 4.0 ? 8192.0 : 2048.0;
+            break;
+          }
+          if (cand != 0) break;
         }
+        if (cand == 0) {
+          // no sample of at most 1/4 of the unit is reliable: read all of it (k * 64 <= size, so there are
+          // at least 4 k groups of 16); the candidates are the k largest, the few more down to the k-th
+          // largest group maximum, and the rest of the histogram bin (1/8 of a binade) that falls in
+          sg.n_runs = static_cast<uint32_t>((sg.size + 63) / 64);
+          sg.samp_stride = 64;
+          sg.r_s = sg.k;
+          sg.nsamp = std::min(MAX_SAMPLE_BLOCKS, std::max(1u, (sg.nwt + 63) / 64));      // four chunks per wave
+          cand = 2.0 * sg.k;
+          slack = 2048.0;
+        }
+        sg.d0_cap = static_cast<uint32_t>(std::min<double>(n, 4.0 * cand + slack));
+        sg.mode = PATH_FAST;
+        ++ctx->n_sampled;
+        for (uint32_t j = 0; j < sg.nsamp; ++j) { SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0; samps.push_back(si); }
       } else if (cfg->sparsifier == QSL_RANDK && static_cast<uint64_t>(sg.k) * 16 <= sg.size) {
         // the keys are uniform 32-bit words: keep those above the (1 - q) quantile, q = p + 7 sigma
         const double q = p + 7.0 * std::sqrt(p * (1 - p) / n);
@@ -1358,19 +1600,35 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
       sg.ovf_cap = sg.d0_cap;
       sg.ovf_off = ovf_entries; ovf_entries += sg.ovf_cap;
       sg.d0_off = d0_entries; d0_entries += sg.d0_cap;
-      const uint64_t nrows = (static_cast<uint64_t>(sg.nwt) * sg.lpc + 63) / 64;
-      sg.nsel = static_cast<uint32_t>(std::min<uint64_t>(MAX_SELECT_BLOCKS, std::max<uint64_t>(16, (nrows + 127) / 128)));
       sg.ncb = (sg.d0_cap + DTILE - 1) / DTILE;
+    } else if (sg.mode == PATH_SMALL) {
+      smalls.push_back(l);
+      sg.nsel = 0; sg.ncb = 0;
     } else {
-      sg.nsel = std::min(MAX_SELECT_BLOCKS, std::max(1u, (sg.nwt + 7) / 8));
+      sg.nsel = std::min(MAX_SELECT_BLOCKS, std::max(1u, (sg.nwt + 31) / 32));   // two chunks per wave up to 2^21 coordinates
       sg.ncb = (sg.nwt + GGROUP - 1) / GGROUP;
     }
+  }
+  // blocks of a fast unit in the selection kernels: ~3 slot rows per wave, and no more than one block
+  // per compute unit in all (measured, 8 workers with 1560 rows each: 16 blocks per unit 12 us, 32 blocks
+  // 9 us, 48 blocks 12.5 us)
+  uint64_t fast_blocks = 0;
+  for (uint32_t l : fast) {
+    SegInfo& sg = segs[l];
+    const uint64_t nrows = (static_cast<uint64_t>(sg.nwt) * sg.lpc + 63) / 64;
+    sg.nsel = static_cast<uint32_t>(std::min<uint64_t>(MAX_SELECT_BLOCKS, std::max<uint64_t>(1, (nrows + 47) / 48)));
+    fast_blocks += static_cast<uint64_t>(sg.nsel) * ctx->Rmax;
+  }
+  if (fast_blocks > 256)
+    for (uint32_t l : fast) segs[l].nsel = static_cast<uint32_t>(std::max<uint64_t>(1, segs[l].nsel * 256ull / fast_blocks));
+  for (uint32_t l = 0; l < L; ++l) {
+    SegInfo& sg = segs[l];
     for (uint32_t j = 0; j < sg.nsel; ++j) { SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0; sels.push_back(si); }
     sg.wc_base = static_cast<uint32_t>(nwc); nwc += sg.nsel * (BIG / 64);
     sg.cb_base = static_cast<uint32_t>(cbs.size());
     for (uint32_t b = 0; b < sg.ncb; ++b) { CbInfo ci; ci.seg = l; ci.b = b; ci.pad0 = ci.pad1 = 0; cbs.push_back(ci); }
   }
-  ctx->max_nsamp = max_nsamp;
+  ctx->nsamp_blocks = static_cast<uint32_t>(samps.size());
   const uint32_t NWT = static_cast<uint32_t>(nwt64);
   const uint32_t NSEL = static_cast<uint32_t>(sels.size()), NCB = static_cast<uint32_t>(cbs.size());
   const uint32_t NWC = static_cast<uint32_t>(nwc);
@@ -1385,7 +1643,9 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t zero_bytes = bytes;
   const uint64_t o_segs = carve(sizeof(SegInfo) * L), o_wts = carve(sizeof(WtInfo) * std::max<size_t>(1, wts.size()));
   const uint64_t o_sels = carve(sizeof(SelInfo) * NSEL), o_cbs = carve(sizeof(CbInfo) * NCB);
+  const uint64_t o_samps = carve(sizeof(SelInfo) * samps.size());
   const uint64_t o_fast = carve(4ull * std::max<size_t>(1, fast.size()));
+  const uint64_t o_small = carve(4ull * std::max<size_t>(1, smalls.size()));
   const uint64_t o_units = carve(sizeof(UnitState) * U);
   const uint64_t o_slots = carve(8ull * std::max<uint64_t>(2, slot_elems) * R);
   const uint64_t o_ovf = carve(8ull * std::max<uint64_t>(1, ovf_entries) * R);
@@ -1405,8 +1665,10 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   upload(o_segs, segs.data(), sizeof(SegInfo) * L);
   upload(o_wts, wts.data(), sizeof(WtInfo) * wts.size());
   upload(o_sels, sels.data(), sizeof(SelInfo) * NSEL);
+  upload(o_samps, samps.data(), sizeof(SelInfo) * samps.size());
   upload(o_cbs, cbs.data(), sizeof(CbInfo) * NCB);
   upload(o_fast, fast.data(), 4 * fast.size());
+  upload(o_small, smalls.data(), 4 * smalls.size());
   ok = ok && hipHostMalloc(reinterpret_cast<void**>(&ctx->h_status), 64, hipHostMallocDefault) == hipSuccess;
   ok = ok && hipDeviceSynchronize() == hipSuccess;
   if (!ok) { (void)hipFree(ctx->slab); delete ctx; return QSL_ERR_DEVICE; }
@@ -1415,8 +1677,11 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.segs = reinterpret_cast<const SegInfo*>(base + o_segs);
   c.wts = reinterpret_cast<const WtInfo*>(base + o_wts);
   c.sels = reinterpret_cast<const SelInfo*>(base + o_sels);
+  c.samps = reinterpret_cast<const SelInfo*>(base + o_samps);
   c.cbs = reinterpret_cast<const CbInfo*>(base + o_cbs);
   c.fast_segs = reinterpret_cast<const uint32_t*>(base + o_fast);
+  c.small_segs = reinterpret_cast<const uint32_t*>(base + o_small);
+  ctx->nsmall = static_cast<uint32_t>(smalls.size());
   c.units = reinterpret_cast<UnitState*>(base + o_units);
   c.slots = reinterpret_cast<uint2*>(base + o_slots); c.slot_stride = std::max<uint64_t>(2, slot_elems);
   c.ovf = reinterpret_cast<uint2*>(base + o_ovf); c.ovf_stride = std::max<uint64_t>(1, ovf_entries);
@@ -1471,7 +1736,7 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   const DevCtx& c = ctx->dc;
   hipStream_t st = ctx->stream;
   if (SPARS == QSL_TOPK && ctx->n_sampled > 0) {
-    k_sample<<<dim3(ctx->max_nsamp, c.nfast, R), BIG, 0, st>>>(c, m, delta, xm);
+    k_sample<<<dim3(ctx->nsamp_blocks, R), BIG, 0, st>>>(c, m, delta, xm);
     k_sample_scan<<<dim3(c.nfast, R), BIG, 0, st>>>(c);
   }
   const bool timed = ctx->timing != 0;
@@ -1495,11 +1760,14 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   }
   if (timed) { QSL_HIP(hipEventRecord(ctx->ev[ctx->ev_used + 1], st)); ctx->ev_used += 2; }
 
-  k_select<0, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
-  k_select<1, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
-  k_select<2, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
-  k_tile_count<SPARS><<<dim3(c.NCB, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
-  k_tile_write<SPARS><<<dim3(c.NCB, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
+  if (ctx->nsmall) k_small<SPARS><<<dim3(ctx->nsmall, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
+  if (c.NSEL) {                                    // units that take a launch per digit and two for the compaction
+    k_select<0, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
+    k_select<1, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
+    k_select<2, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
+    k_tile_count<SPARS><<<dim3(c.NCB, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
+    k_tile_write<SPARS><<<dim3(c.NCB, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
+  }
   k_quantize<<<dim3(c.QB, R), BLOCK, 0, st>>>(c, m_out, worker0, round, sel_idx, sel_level);
   if (c.QB > MAX_QB_INLINE) k_surv_scan<<<dim3(R), 1024, 0, st>>>(c);
   k_surv_compact<<<dim3(c.QB, R), BLOCK, 0, st>>>(c);

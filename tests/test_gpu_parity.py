@@ -76,7 +76,9 @@ def test_fast_and_general_paths_agree_layerwise(P):
     # segments from 64 coordinates to ~1.9 M: a mix of fast and general units in one call
     wl = W.config(4, d=20_000_000, R=2)
     run, op, m_host, paths = P.run_parity(wl, 2)
-    assert (paths[0] == 0).any() and (paths[0] == 1).any()
+    assert (paths[0] == 0).any() and (paths[0] == 3).any()
+    run, op, m_host, paths = P.run_parity(wl, 1, flags=3)          # every unit through the multi-pass kernels
+    assert (paths[0] == 1).all()
 
 
 def test_failed_guess_falls_back(P):
@@ -132,14 +134,53 @@ def _adversarial(d, rng):
     yield "wide_range", (rng.standard_normal(d) * np.exp(8 * rng.standard_normal(d))).astype(f32)
 
 
+@pytest.mark.parametrize("flags,path", [(0, 3), (2, 1)])      # one-block selection / multi-pass kernels
 @pytest.mark.parametrize("quantizer,s", [(W.QSGD, 16), (W.SIGN_L1, 1)])
-@pytest.mark.parametrize("k", [1, 37, 20_011])
-def test_degenerate_inputs(P, quantizer, s, k):
-    d = 20_011
+@pytest.mark.parametrize("k", [1, 37, 12_011])
+def test_degenerate_inputs(P, quantizer, s, k, flags, path):
+    d = 12_011
     rng = np.random.default_rng(17)
     wl = custom(d, [0, d], [k], s, W.TOPK, quantizer, R=1)
     for name, v in _adversarial(d, rng):
-        P.run_parity(wl, 1, deltas=[v[None, :].copy()])
+        P.run_parity(wl, 1, deltas=[v[None, :].copy()], flags=flags, expect_path=path)
+
+
+@pytest.mark.parametrize("k", [1, 37, 600])
+def test_degenerate_inputs_whole_unit_guess(P, k):
+    # 17 .. 255 chunks: the guess comes from a histogram of the whole unit; inputs with few distinct
+    # magnitudes put everything into one bin, overflow the candidate list and must fall back
+    d = 40_009
+    rng = np.random.default_rng(23)
+    wl = custom(d, [0, d], [k], 16, W.TOPK, W.QSGD, R=1)
+    seen = set()
+    for name, v in _adversarial(d, rng):
+        run, op, m_host, paths = P.run_parity(wl, 1, deltas=[v[None, :].copy()])
+        seen.update(paths[0].tolist())
+    assert seen == {0, 2}, seen
+
+
+# sizes around the limit of the one-block selection (16,384 coordinates) and of its 16-per-thread layout
+@pytest.mark.parametrize("sparsifier", [W.TOPK, W.RANDK])
+@pytest.mark.parametrize("d,k", [(16_384, 100), (16_385, 16_385), (16_385, 3), (16_383, 16_383), (8_209, 4_000),
+                                 (32_769, 1), (65_537, 655), (17, 16), (1_025, 1_024), (262_143, 250)])
+def test_small_units_one_block_boundaries(P, sparsifier, d, k):
+    small = d <= 16_384
+    wl = custom(d, [0, d], [k], 7, sparsifier, W.QSGD, R=2)
+    P.run_parity(wl, 2, expect_path=3 if small else None)
+    wl = custom(d, [0, d], [k], 1, sparsifier, W.SIGN_L1, R=2)
+    P.run_parity(wl, 1, flags=3, expect_path=1)                   # the same through the multi-pass kernels
+    ties = np.round(np.random.default_rng(d).standard_normal((1, 2, d)) * 2).astype(f32)     # many equal magnitudes
+    P.run_parity(wl, 1, deltas=ties, expect_path=3 if small else None)
+
+
+def test_small_and_large_units_mixed(P):
+    # one call with one-block units, multi-pass units and guessed units side by side
+    off = [0, 100, 70_000, 70_001, 400_000, 410_000, 1_100_000]
+    k = [100, 70, 1, 30_000, 650, 600]
+    for sp, qz, s in [(W.TOPK, W.QSGD, 16), (W.RANDK, W.SIGN_L1, 1)]:
+        wl = custom(1_100_000, off, k, s, sp, qz, R=3)
+        run, op, m_host, paths = P.run_parity(wl, 2)
+        assert sorted(set(paths[0].tolist())) == [0, 1, 3], paths[0]
 
 
 def test_degenerate_inputs_on_fast_sizes(P):
