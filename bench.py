@@ -35,6 +35,8 @@ def main():
     ap.add_argument("--from-models", action="store_true",
                     help="time qsl_compress_diff (Delta = x - xhat formed on the fly; the fresh buffers act as the "
                          "local models) instead of qsl_compress; not the headline line")
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="do not bracket the streaming kernel with HIP events (diagnostic: the roofline entry is then empty)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rounds", type=int, default=2)
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -86,7 +88,7 @@ def main():
     for t in range(args.warmup):
         step(t)
     torch.cuda.synchronize()
-    q.timing_enable(True)
+    q.timing_enable(not args.no_kernel_timing)
     t0 = time.perf_counter()
     for t in range(args.warmup, total):
         step(t)

@@ -461,7 +461,7 @@ __device__ __forceinline__ SlotRow read_slot_row(const uint2* slots, uint32_t lp
   const uint32_t lane = lane_id();
   const uint32_t sub = lane & (lpc - 1);
   uint4 q = make_uint4(0, 0, 0, 0);
-  if (row < nrows && (row * 64 + lane) / lpc < nwt) q = reinterpret_cast<const uint4*>(slots)[row * 64 + lane];
+  if (row < nrows && ((row * 64 + lane) >> (__ffs(lpc) - 1)) < nwt) q = reinterpret_cast<const uint4*>(slots)[row * 64 + lane];   // lpc: 4, 8 or 16
   const uint32_t leader = lane & ~(lpc - 1);
   r.count = __shfl(q.x, leader, WAVE);
   r.ovf_at = __shfl(q.y, leader, WAVE);
@@ -507,20 +507,22 @@ __device__ __forceinline__ bool level_bin(uint32_t key, uint32_t prefix, uint32_
 //   fast unit, digit 2: reads the dense list;
 //   general path:       reads v.
 template <int LEVEL, int SPARS>
-__global__ __launch_bounds__(BIG) void k_select(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
+__global__ __launch_bounds__(BIG) void k_select(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round) {
   __shared__ uint32_t lh[HBINS];
   __shared__ uint64_t scratch[17];
   __shared__ uint32_t result[2], s_ctr[CTR_LINES];
-  const SelInfo si = c.sels[blockIdx.x];
+  // a single-segment context carries its plan in the kernel arguments: one dependent load less per block
+  SelInfo si; si.seg = 0; si.j = blockIdx.x;
+  if (c.L != 1) si = c.sels[blockIdx.x];
   const uint32_t w = blockIdx.y;
-  const SegInfo sg = c.segs[si.seg];
+  const SegInfo sg = c.L == 1 ? one : c.segs[si.seg];
   const uint64_t u = static_cast<uint64_t>(w) * c.L + si.seg;
   UnitState* usp = &c.units[u];
   const UnitState us = *usp;
   uint32_t* hist = c.hist + u * 3 * HBINS;
   for (uint32_t i = threadIdx.x; i < HBINS; i += BIG) lh[i] = 0;
   if (LEVEL == 0 && threadIdx.x < CTR_LINES)
-    s_ctr[threadIdx.x] = us.path == PATH_FAST ? c.ctr[(u * CTR_LINES + threadIdx.x) * PAD] : 0u;
+    s_ctr[threadIdx.x] = sg.mode == PATH_FAST ? c.ctr[(u * CTR_LINES + threadIdx.x) * PAD] : 0u;
   __syncthreads();
   uint32_t path, prefix = 0, k_rem = sg.k;
   if (LEVEL == 0) {
@@ -553,10 +555,10 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, const float* v, uint32
     uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
     uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
     uint32_t* wcnt = c.wave_cnt + static_cast<uint64_t>(w) * c.NWC + sg.wc_base;
-    const uint64_t nrows = (static_cast<uint64_t>(sg.nwt) * sg.lpc + 63) / 64;
+    const uint32_t nrows = static_cast<uint32_t>((static_cast<uint64_t>(sg.nwt) * sg.lpc + 63) >> 6);   // < 2^20
     const uint32_t nwaves = sg.nsel * (BIG / 64), gw = si.j * (BIG / 64) + wave;
-    const uint64_t rpw = (nrows + nwaves - 1) / nwaves;
-    const uint64_t r_lo = gw * rpw, r_hi = r_lo + rpw < nrows ? r_lo + rpw : nrows;
+    const uint32_t rpw = (nrows + nwaves - 1) / nwaves;
+    const uint64_t r_lo = static_cast<uint64_t>(gw) * rpw, r_hi = r_lo + rpw < nrows ? r_lo + rpw : nrows;
     uint32_t seen = 0;                              // digit 0: candidates this wave met
     uint32_t off = 0;                               // digit 1: where this wave's candidates go in the dense list
     if (LEVEL == 1) {                               // at most MAX_SELECT_BLOCKS * 16 = 1024 waves: 16 loads in flight
@@ -955,12 +957,13 @@ __global__ __launch_bounds__(BLOCK) void k_small(DevCtx c, const float* v, uint3
 }
 
 template <int SPARS>
-__global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
+__global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round) {
   __shared__ uint32_t s_cnt[2 * GGROUP + 2], s_red[8], result[2];
   __shared__ uint64_t scratch[17];
-  const CbInfo cb = c.cbs[blockIdx.x];
+  CbInfo cb; cb.seg = 0; cb.b = blockIdx.x;
+  if (c.L != 1) cb = c.cbs[blockIdx.x];
   const uint32_t w = blockIdx.y;
-  const SegInfo sg = c.segs[cb.seg];
+  const SegInfo sg = c.L == 1 ? one : c.segs[cb.seg];
   const uint64_t u = static_cast<uint64_t>(w) * c.L + cb.seg;
   const UnitState us = c.units[u];
   const uint32_t path = eff_path(us);
@@ -999,13 +1002,14 @@ __global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, const float* v, 
 }
 
 template <int SPARS>
-__global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
+__global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round) {
   __shared__ uint64_t acc[ACC_ROWS * (ACC_SLOTS + 1)];      // a row per 8 lanes of a wave: short atomic queues
   __shared__ uint32_t s_cnt[2 * GGROUP + 2];
   __shared__ uint64_t scratch[17], s_part[4];
-  const CbInfo cb = c.cbs[blockIdx.x];
+  CbInfo cb; cb.seg = 0; cb.b = blockIdx.x;
+  if (c.L != 1) cb = c.cbs[blockIdx.x];
   const uint32_t w = blockIdx.y;
-  const SegInfo sg = c.segs[cb.seg];
+  const SegInfo sg = c.L == 1 ? one : c.segs[cb.seg];
   const uint64_t u = static_cast<uint64_t>(w) * c.L + cb.seg;
   const UnitState us = c.units[u];
   const uint32_t path = eff_path(us);
@@ -1072,34 +1076,42 @@ __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, const float* v, 
   }
 }
 
-// digits -> one correctly rounded double -> the fp32 scale of the unit
-__device__ float finalize_scale(const uint64_t* acc, uint32_t quantizer, uint32_t k, uint32_t s) {
+// digits -> one correctly rounded double -> the fp32 scale of the unit.  Called by all 64 lanes of a
+// wave with the same arguments; lane i holds digit counter i, everything else is shuffles and ballots
+// (a per-thread digit array would live in scratch memory and cost microseconds).
+__device__ float finalize_scale(const uint64_t* acc, uint32_t quantizer, uint32_t k) {
   const bool squares = wants_squares(quantizer);
-  uint32_t dig[ACC_SLOTS + 2];
-  uint64_t carry = 0;
-  for (uint32_t i = 0; i < ACC_SLOTS; ++i) { const uint64_t t = acc[i] + carry; dig[i] = static_cast<uint32_t>(t); carry = t >> 32; }
-  dig[ACC_SLOTS] = static_cast<uint32_t>(carry);
-  dig[ACC_SLOTS + 1] = 0;
-  int tw = -1;
-  for (int i = ACC_SLOTS; i >= 0; --i) if (dig[i]) { tw = i; break; }
+  const uint32_t lane = lane_id();
+  const uint64_t a = lane < ACC_SLOTS ? acc[lane] : 0;
+  // 32-bit digits: low half of the own counter plus the high half of the one below, then ripple the carries
+  auto from_below = [&](uint32_t x) { const uint32_t y = __shfl_up(x, 1, WAVE); return lane ? y : 0u; };
+  uint64_t t = (a & 0xFFFFFFFFull) + from_below(static_cast<uint32_t>(a >> 32));
+  for (uint32_t it = 0; it < WAVE; ++it) {                            // ends after a few rounds; bounded anyway
+    const uint32_t carry = static_cast<uint32_t>(t >> 32);
+    if (__ballot(carry != 0) == 0) break;
+    t = (t & 0xFFFFFFFFull) + from_below(carry);
+  }
+  const uint32_t dig = static_cast<uint32_t>(t);                      // digit `lane` of the exact sum
+  const uint64_t nz = __ballot(dig != 0);
   double S = 0.0;
-  if (tw >= 0) {
-    const int top = tw * 32 + 31 - __clz(dig[tw]);
+  if (nz != 0) {
+    const int tw = 63 - __clzll(static_cast<long long>(nz));
+    const int top = tw * 32 + 31 - __clz(static_cast<int>(__shfl(dig, tw, WAVE)));
     const int low = top - 52;                       // position of the last kept bit
     uint64_t mant; int e2;
     if (low <= 0) {
-      mant = (static_cast<uint64_t>(dig[1]) << 32) | dig[0]; e2 = 0;      // the whole value, exact
+      mant = (static_cast<uint64_t>(__shfl(dig, 1, WAVE)) << 32) | __shfl(dig, 0, WAVE); e2 = 0;   // the whole value, exact
     } else {
-      const int wq = low >> 5, r = low & 31;        // wq + 1 <= tw <= ACC_SLOTS
-      const uint64_t lo64 = (static_cast<uint64_t>(dig[wq + 1]) << 32) | dig[wq];
-      const uint64_t hi32 = wq + 2 <= static_cast<int>(ACC_SLOTS) ? dig[wq + 2] : 0u;
+      const int wq = low >> 5, r = low & 31;
+      const uint64_t lo64 = (static_cast<uint64_t>(__shfl(dig, wq + 1, WAVE)) << 32) | __shfl(dig, wq, WAVE);
+      const uint64_t hi32 = __shfl(dig, wq + 2, WAVE);                // lanes above the top digit hold 0
       uint64_t win = lo64 >> r;
       if (r) win |= hi32 << (64 - r);
       mant = win & ((1ull << 53) - 1);
-      const int g = low - 1;
-      const uint32_t guard = (dig[g >> 5] >> (g & 31)) & 1u;
-      bool sticky = (dig[g >> 5] & ((1u << (g & 31)) - 1u)) != 0;
-      for (int i = 0; i < (g >> 5); ++i) sticky |= dig[i] != 0;
+      const int g = low - 1, gq = g >> 5, gb = g & 31;
+      const uint32_t dg = __shfl(dig, gq, WAVE);
+      const uint32_t guard = (dg >> gb) & 1u;
+      const bool sticky = (dg & ((1u << gb) - 1u)) != 0 || __ballot(dig != 0 && lane < static_cast<uint32_t>(gq)) != 0;
       if (guard && (sticky || (mant & 1u))) mant += 1;
       e2 = low;
     }
@@ -1108,7 +1120,6 @@ __device__ float finalize_scale(const uint64_t* acc, uint32_t quantizer, uint32_
   if (quantizer == QSL_SIGN_L1) return static_cast<float>(S / static_cast<double>(k));           // ||v_S||_1 / k
   if (quantizer == QSL_SIGN_L2) return static_cast<float>(sqrt(S) / static_cast<double>(k));     // ||v_S||_2 / k
   if (quantizer == QSL_FP32) return 0.0f;
-  (void)s;
   return static_cast<float>(sqrt(S));                                                            // ||v_S||_2
 }
 
@@ -1142,20 +1153,22 @@ __global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint
   const uint32_t j_first = blockIdx.x * BLOCK, j_last = min(j_first + BLOCK, c.K) - 1;
   const uint32_t seg_first = c.L == 1 ? 0u : seg_of_slot(c, j_first);
   const uint32_t seg_last = c.L == 1 ? 0u : seg_of_slot(c, j_last);
-  if (threadIdx.x <= seg_last - seg_first) {
-    const uint32_t seg = seg_first + threadIdx.x;
+  for (uint32_t i = threadIdx.x >> 6; i <= seg_last - seg_first; i += BLOCK / 64) {     // a wave per unit
+    const uint32_t seg = seg_first + i;
     const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
     const uint32_t kl = c.segs[seg].k;
-    const float sc = finalize_scale(c.norm_acc + u * ACC_SLOTS, c.quantizer, kl, c.s);
-    s_scale[threadIdx.x] = sc;
-    // what the message carries: the scale itself, or N / (1 + beta_{k,s}) for the scaled composition (Lemma 2)
-    float sent = sc;
-    if (c.quantizer == QSL_QSGD_SCALED) {
-      const double beta = fmin(static_cast<double>(kl) / (static_cast<double>(c.s) * c.s), sqrt(static_cast<double>(kl)) / c.s);
-      sent = sc / static_cast<float>(1.0 + beta);
+    const float sc = finalize_scale(c.norm_acc + u * ACC_SLOTS, c.quantizer, kl);
+    if (lane_id() == 0) {
+      s_scale[i] = sc;
+      // what the message carries: the scale itself, or N / (1 + beta_{k,s}) for the scaled composition (Lemma 2)
+      float sent = sc;
+      if (c.quantizer == QSL_QSGD_SCALED) {
+        const double beta = fmin(static_cast<double>(kl) / (static_cast<double>(c.s) * c.s), sqrt(static_cast<double>(kl)) / c.s);
+        sent = sc / static_cast<float>(1.0 + beta);
+      }
+      s_sent[i] = sent;
+      if (c.segs[seg].koff >= j_first) c.units[u].scale_bits = __float_as_uint(sent);   // the block holding the unit's first slot
     }
-    s_sent[threadIdx.x] = sent;
-    if (c.segs[seg].koff >= j_first) c.units[u].scale_bits = __float_as_uint(sent);   // the block holding the unit's first slot
   }
   __syncthreads();
   uint32_t sent = 0;
@@ -1762,11 +1775,11 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
 
   if (ctx->nsmall) k_small<SPARS><<<dim3(ctx->nsmall, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
   if (c.NSEL) {                                    // units that take a launch per digit and two for the compaction
-    k_select<0, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
-    k_select<1, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
-    k_select<2, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, m_out, worker0, round);
-    k_tile_count<SPARS><<<dim3(c.NCB, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
-    k_tile_write<SPARS><<<dim3(c.NCB, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
+    k_select<0, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round);
+    k_select<1, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round);
+    k_select<2, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round);
+    k_tile_count<SPARS><<<dim3(c.NCB, R), BLOCK, 0, st>>>(c, ctx->segs[0], m_out, worker0, round);
+    k_tile_write<SPARS><<<dim3(c.NCB, R), BLOCK, 0, st>>>(c, ctx->segs[0], m_out, worker0, round);
   }
   k_quantize<<<dim3(c.QB, R), BLOCK, 0, st>>>(c, m_out, worker0, round, sel_idx, sel_level);
   if (c.QB > MAX_QB_INLINE) k_surv_scan<<<dim3(R), 1024, 0, st>>>(c);
