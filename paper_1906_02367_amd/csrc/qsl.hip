@@ -1404,37 +1404,43 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(DevCtx c, const uint8_t* ms
   const uint32_t q = blockIdx.y;
   const uint32_t e = threadIdx.x >> 3, sub = threadIdx.x & 7u;
   const MsgView mine = view_msg(c, msg, rows.row[q]);
-  const uint32_t j = blockIdx.x * AGG_ENTRIES + e;
-  if (sub == 0) s_has[e] = 0;
-  __syncthreads();
-  uint32_t idx = 0xFFFFFFFFu;
-  if (j < mine.nnz) {
-    idx = msg_index(c, mine, j);
-    if (idx >= c.d) { if (sub == 0) atomicOr(c.status, 4u); idx = 0xFFFFFFFFu; }   // malformed message
-  }
-  if (idx != 0xFFFFFFFFu) {
-    unsigned long long has = 0;
-    for (uint32_t p = sub; p < R; p += 8) {
-      if (p == q) { s_val[e][p] = msg_value(c, mine, j, idx); has |= 1ull << p; continue; }
-      const MsgView other = view_msg(c, msg, rows.row[p]);
-      const int64_t pos = msg_find(c, other, idx);
-      if (pos >= 0) { s_val[e][p] = msg_value(c, other, static_cast<uint32_t>(pos), idx); has |= 1ull << p; }
+  // the grid is sized for a moderate message; a block walks the tiles of 32 entries that exist
+  for (uint32_t tile = blockIdx.x; tile * AGG_ENTRIES < mine.nnz; tile += gridDim.x) {
+    const uint32_t j = tile * AGG_ENTRIES + e;
+    if (sub == 0) s_has[e] = 0;
+    __syncthreads();
+    uint32_t idx = 0xFFFFFFFFu;
+    if (j < mine.nnz) {
+      idx = msg_index(c, mine, j);
+      if (idx >= c.d) { if (sub == 0) atomicOr(c.status, 4u); idx = 0xFFFFFFFFu; }   // malformed message
     }
-    if (has) atomicOr(&s_has[e], has);
+    if (idx != 0xFFFFFFFFu) {
+      unsigned long long has = 0;
+      for (uint32_t p = sub; p < R; p += 8) {
+        if (p == q) { s_val[e][p] = msg_value(c, mine, j, idx); has |= 1ull << p; continue; }
+        const MsgView other = view_msg(c, msg, rows.row[p]);
+        const int64_t pos = msg_find(c, other, idx);
+        if (pos >= 0) { s_val[e][p] = msg_value(c, other, static_cast<uint32_t>(pos), idx); has |= 1ull << p; }
+      }
+      if (has) atomicOr(&s_has[e], has);
+    }
+    __syncthreads();
+    if (sub == 0 && idx != 0xFFFFFFFFu) {
+      const unsigned long long has = s_has[e];
+      if (!(has & ((1ull << q) - 1ull))) {                // no earlier listed message owns this coordinate
+        float acc = 0.0f;
+        bool first = true;
+        for (uint32_t p = q; p < R; ++p) {
+          if (!((has >> p) & 1ull)) continue;
+          acc = first ? s_val[e][p] : acc + s_val[e][p];
+          first = false;
+        }
+        const float term = scale * acc;
+        out[idx] = accumulate ? out[idx] + term : term;
+      }
+    }
+    __syncthreads();                                       // s_val and s_has are reused by the next tile
   }
-  __syncthreads();
-  if (sub != 0 || idx == 0xFFFFFFFFu) return;
-  const unsigned long long has = s_has[e];
-  if (has & ((1ull << q) - 1ull)) return;               // an earlier listed message owns this coordinate
-  float acc = 0.0f;
-  bool first = true;
-  for (uint32_t p = q; p < R; ++p) {
-    if (!((has >> p) & 1ull)) continue;
-    acc = first ? s_val[e][p] : acc + s_val[e][p];
-    first = false;
-  }
-  const float term = scale * acc;
-  out[idx] = accumulate ? out[idx] + term : term;
 }
 
 __global__ void k_read_nnz(DevCtx c, const uint8_t* msg, uint32_t R, uint32_t* out) {
@@ -1461,6 +1467,7 @@ struct qsl_ctx {
   uint32_t Rmax;
   uint32_t last_R;
   uint32_t nsmall;            // segments selected by one block each (k_small)
+  uint32_t nnz_hint;          // entries a message is expected to hold at most (sizes the aggregation grid)
   uint32_t n_sampled;         // segments whose guess comes from k_sample
   uint32_t nsamp_blocks;      // blocks of the sampling kernel (per worker)
   size_t capacity;
@@ -1523,6 +1530,14 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
 
   const uint32_t K = static_cast<uint32_t>(K64);
   const uint32_t s = is_qsgd(cfg->quantizer) ? cfg->s : 1;
+  // QSGD drops the entries it rounds to level 0: a segment keeps sum_i min(1, s |v_i| / ||v||_2) <= s sqrt(k)
+  // of its k entries on average (Definition 1, example 1, with Cauchy-Schwarz); the other quantisers send all k
+  double hint = 0;
+  for (uint32_t l = 0; l < L; ++l) {
+    const double kl = cfg->seg_k[l];
+    hint += is_qsgd(cfg->quantizer) ? std::min(kl, 1.25 * s * std::sqrt(kl)) : kl;
+  }
+  ctx->nnz_hint = static_cast<uint32_t>(std::min<double>(hint, K));
   const uint32_t w_idx = std::max(1u, bit_width_u64(d - 1));
   const uint32_t w_lev = is_qsgd(cfg->quantizer) ? bit_width_u64(static_cast<uint64_t>(s) - 1) : 0;
   const uint32_t w_val = cfg->quantizer == QSL_FP32 ? 32 : w_lev + 1;
@@ -1844,7 +1859,9 @@ extern "C" qsl_status qsl_aggregate(qsl_ctx* ctx, const uint8_t* msg, const uint
     const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((c.d + BLOCK * 4 - 1) / (BLOCK * 4), 1u << 16));
     k_fill_zero<<<dim3(blocks), BLOCK, 0, ctx->stream>>>(out, c.d);
   }
-  k_aggregate<<<dim3((c.K + AGG_ENTRIES - 1) / AGG_ENTRIES, R), BLOCK, 0, ctx->stream>>>(c, msg, rows, R, scale,
+  const uint32_t tiles = (c.K + AGG_ENTRIES - 1) / AGG_ENTRIES;
+  const uint32_t agg_blocks = std::min(tiles, std::max(16u, (ctx->nnz_hint + AGG_ENTRIES - 1) / AGG_ENTRIES));
+  k_aggregate<<<dim3(agg_blocks, R), BLOCK, 0, ctx->stream>>>(c, msg, rows, R, scale,
                                                                                         accumulate, out);
   QSL_HIP(hipGetLastError());
   return QSL_OK;
