@@ -36,8 +36,8 @@
  *                                      Sign: the sign bit (1 = negative); no quantiser: the fp32 value
  *                                      (starts on a 32-bit boundary)
  *     zero padding up to the capacity (a multiple of 8 bytes)
- * A QSGD coordinate whose level is 0 is not transmitted (Section 5.1.2 notes that the quantiser
- * "further induces sparsity").  The paper fixes no encoding; this one is the library's choice.
+ * A QSGD coordinate whose level is 0 is not transmitted (Section 5.1.2 observes that the
+ * quantiser adds sparsity of its own).  The paper fixes no encoding; this one is the library's choice.
  */
 #ifndef QSL_H
 #define QSL_H

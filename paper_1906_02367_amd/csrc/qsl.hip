@@ -254,10 +254,10 @@ __global__ __launch_bounds__(BIG) void k_sample(DevCtx c, const float* m, const 
       if (any) atomicAdd(&lh[top >> 20], 1u);
     }
   } else
-  for (uint32_t run0 = si.j * (BIG / 64) + wave; run0 < sg.n_runs; run0 += 4 * nwaves) {
-    float a[4], b[4]; bool ok[4];
+  for (uint32_t run0 = si.j * (BIG / 64) + wave; run0 < sg.n_runs; run0 += 8 * nwaves) {     // 8 runs in flight
+    float a[8], b[8]; bool ok[8];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
+    for (int r = 0; r < 8; ++r) {
       const uint32_t run = run0 + r * nwaves;
       const uint64_t pos = static_cast<uint64_t>(run) * stride + lane;
       ok[r] = run < sg.n_runs && pos < sg.size;
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(BIG) void k_sample(DevCtx c, const float* m, const 
       if (xm != nullptr && ok[r]) b[r] = xm[sg.start + pos] - b[r];
     }
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
+    for (int r = 0; r < 8; ++r)
       if (ok[r]) atomicAdd(&lh[key_of_value(__float_as_uint(a[r] + b[r])) >> 20], 1u);
   }
   __syncthreads();
@@ -1584,7 +1584,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
             sg.n_runs = static_cast<uint32_t>(std::ceil(n_s / 64.0));
             sg.samp_stride = static_cast<uint32_t>(sg.size / sg.n_runs);
             sg.r_s = static_cast<uint32_t>(std::ceil(alpha * (sg.n_runs * 64.0) * p));
-            sg.nsamp = std::min(MAX_SAMPLE_BLOCKS, std::max(1u, (sg.n_runs + 255) / 256));   // 16 runs per wave
+            sg.nsamp = std::min(MAX_SAMPLE_BLOCKS, std::max(1u, (sg.n_runs + 127) / 128));   // 8 runs per wave, all in flight
             cand = alpha * sg.k;
             slack = alpha <= 4.0 ? 8192.0 : 2048.0;
             break;
