@@ -324,3 +324,34 @@ def test_compress_diff_matches_oracle_and_plain_entry(P, cfg, d, R):
             assert np.array_equal(got_msg[r], want[r]["msg"]), f"round {t} worker {r}: message differs"
             assert np.array_equal(P.bits(got_m[r]), P.bits(want[r]["m_out"])), f"round {t} worker {r}: memory differs"
         m_host = got_m
+
+
+# ---------------------------------------------------------------------------------------------
+# the counter of the random words at the far ends of its fields: round near 2^62, worker ids near
+# 2^32, a 64-bit seed with the high bits set (Rand_k uses stream 0, the QSGD rounding stream 1)
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("d,k", [(9_001, 90), (300_007, 3_000)])
+def test_random_word_counter_extremes(P, d, k):
+    from paper_1906_02367_amd import binding as B
+    seed = (1 << 64) - 59
+    wl = custom(d, [0, d], [k], 5, W.RANDK, W.QSGD, R=2, seed=seed)
+    op = P.oracle_for(wl)
+    q = B.from_workload(wl)
+    rng = np.random.default_rng(d)
+    m_host = rng.standard_normal((2, d)).astype(f32)
+    delta = rng.standard_normal((2, d)).astype(f32)
+    for rnd, worker0 in [((1 << 62) - 1, (1 << 32) - 2), ((1 << 32) + 7, 0), ((1 << 61) + (1 << 31), 1 << 31)]:
+        m_dev, d_dev = torch.from_numpy(m_host).to(q.device), torch.from_numpy(delta).to(q.device)
+        msg = q.new_msg(2)
+        q.compress(m_dev, d_dev, m_dev, worker0, rnd, msg)
+        torch.cuda.synchronize()
+        assert q.device_status() == B.OK
+        got_msg, got_m = msg.cpu().numpy(), m_dev.cpu().numpy()
+        for r in range(2):
+            o = op.compress(m_host[r], delta[r], worker0 + r, rnd)
+            assert np.array_equal(got_msg[r], o["msg"]), f"round {rnd} worker {worker0 + r}: message differs"
+            assert np.array_equal(P.bits(got_m[r]), P.bits(o["m_out"])), f"round {rnd} worker {worker0 + r}: memory differs"
+    with pytest.raises(B.QslError):
+        q.compress(m_dev, d_dev, m_dev, 0, 1 << 62, msg)                  # round out of range
+    with pytest.raises(B.QslError):
+        q.compress(m_dev, d_dev, m_dev, (1 << 32) - 1, 0, msg)            # worker0 + R > 2^32
