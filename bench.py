@@ -26,6 +26,22 @@ ALGO_BYTES_PER_COORD = 12       # read m, read Delta, write m': what the method 
 MEASURED_TRAFFIC_BYTES = {2: 2_515_700_000}
 
 
+def gpu_state():
+    """Clocks and power of GPU 0 as rocm-smi reports them (a child process, started before this process
+    touches the GPU); None if the tool is missing or says nothing useful."""
+    import shutil
+    import subprocess
+    exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    try:
+        out = subprocess.run([exe, "-d", "0", "--showclocks", "--showpower", "--json"], capture_output=True,
+                             text=True, timeout=20)
+        card = next(iter(json.loads(out.stdout).values()))
+        keep = {k: v for k, v in card.items() if any(t in k.lower() for t in ("sclk", "mclk", "fclk", "power"))}
+        return keep or None
+    except Exception:
+        return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -47,6 +63,7 @@ def main():
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
+    state = gpu_state()
     import numpy as np
     import torch
     from paper_1906_02367_amd import binding as B
@@ -98,6 +115,15 @@ def main():
     q.timing_enable(False)
     assert q.device_status() == B.OK
     elapsed = t1 - t0
+    # a second, separate pass: every round bracketed by events on the stream the library launches on
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for i, (e0, e1) in enumerate(ev):
+        e0.record()
+        step(total + i)
+        e1.record()
+    torch.cuda.synchronize()
+    per_round = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+    assert q.device_status() == B.OK
     coords_per_s = R * d * args.steps / elapsed
     units = q.debug_units()
     bits = msg_bits.cpu().numpy()
@@ -153,6 +179,9 @@ def main():
                              "fallback": int((units[:, 0] == 2).sum()), "one_block": int((units[:, 0] == 3).sum())},
                    "max_candidates": int(units[:, 1].max()), "mean_msg_bits": float(bits.mean())},
         "algorithmic_GBps_whole_step": ALGO_BYTES_PER_COORD * coords_per_s / 1e9,
+        "per_round_ms": {"median": per_round[len(per_round) // 2], "min": per_round[0], "max": per_round[-1],
+                         "note": "separate pass after the timed region, HIP events around each round"},
+        "gpu_state": state,
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
