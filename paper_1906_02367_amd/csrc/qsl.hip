@@ -1348,6 +1348,7 @@ __device__ __forceinline__ float msg_value(const DevCtx& c, const MsgView& v, ui
 }
 // position of coordinate idx in the message, or -1
 __device__ __forceinline__ int64_t msg_find(const DevCtx& c, const MsgView& v, uint32_t idx) {
+  if (v.nnz == c.d) return idx;                          // every coordinate is there (k = d): entry j is coordinate j
   uint32_t lo = 0, hi = v.nnz;
   while (lo < hi) {
     const uint32_t mid = lo + ((hi - lo) >> 1);

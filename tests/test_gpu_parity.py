@@ -205,6 +205,17 @@ def test_d_equals_one_and_k_equals_d(P):
     P.run_parity(wl, 2)
     wl = custom(5_000, [0, 5_000], [5_000], 16, W.TOPK, W.QSGD, R=1)      # QSGD on the whole vector
     P.run_parity(wl, 2)
+    # the sign of the whole vector (every message lists every coordinate), and the master line on such messages
+    wl = custom(20_003, [0, 20_003], [20_003], 1, W.TOPK, W.SIGN_L1, R=3)
+    run, op, m_host, _ = P.run_parity(wl, 2)
+    x0 = np.random.default_rng(8).standard_normal(wl.d).astype(f32)
+    out = torch.from_numpy(x0).to(run.q.device)
+    run.q.aggregate(run.msg, out, -1.0 / 3, worker_list=[2, 0], accumulate=True)
+    torch.cuda.synchronize()
+    msgs = run.msg.cpu().numpy()
+    want = op.aggregate(msgs, -1.0 / 3, worker_list=[2, 0], out=x0)
+    mag = sum(np.abs(op.decode(msgs[r])[1].astype(np.float64)) for r in (2, 0))
+    assert np.all(np.abs(out.cpu().numpy().astype(np.float64) - want) <= 1e-6 * (mag / 3 + np.abs(want)) + 1e-38)
 
 
 # ---------------------------------------------------------------------------------------------
