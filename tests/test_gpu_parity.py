@@ -366,3 +366,17 @@ def test_random_word_counter_extremes(P, d, k):
         q.compress(m_dev, d_dev, m_dev, 0, 1 << 62, msg)                  # round out of range
     with pytest.raises(B.QslError):
         q.compress(m_dev, d_dev, m_dev, (1 << 32) - 1, 0, msg)            # worker0 + R > 2^32
+
+
+# ---------------------------------------------------------------------------------------------
+# the paper's own per-tensor rule (Section 5.1.1): k_t = min(d_t, 1000) for every tensor -- whole small
+# tensors, dense selections in the mid-sized ones, sparse ones in the large
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("quantizer,s", [(W.SIGN_L1, 1), (W.QSGD, 15)])
+def test_per_tensor_rule_k_min_d_1000(P, quantizer, s):
+    base = W.config(4, d=6_000_000, R=2)
+    sizes = np.diff(base.seg_offset.astype(np.int64))
+    k = np.minimum(sizes, 1000).astype(np.uint32)
+    wl = W.Workload(4, "cfg4_k_min_d_1000", 2, base.d, base.seg_offset, k, s, W.TOPK, quantizer, 2, base.seed)
+    run, op, m_host, paths = P.run_parity(wl, 2)
+    assert set(paths[0].tolist()) == {0, 1, 3}, np.bincount(paths[0])
