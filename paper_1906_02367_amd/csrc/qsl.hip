@@ -300,8 +300,11 @@ typedef uint32_t u2v __attribute__((ext_vector_type(2)));
 // shared by the workers); Delta = x_t - xhat_{t+1/2} (Algorithm 1, sync step) is formed in registers.  The
 // grid is then one-dimensional and ordered so that the R blocks that read the same four chunks of x_t
 // follow each other on the same XCD (blocks go to the 8 XCDs round-robin), whose L2 serves R - 1 of them.
+// Occupancy is held to 3 waves per SIMD for a single-segment context (4 otherwise): measured on the
+// 8 x 25.6 M pass, 8 waves per SIMD 417 us, 5: 404, 4: 398, 3: 390, 2: 411 -- more requests in flight than
+// the memory system wants only make it slower; the segmented and the x_t-reading forms were best at 4.
 template <int SPARS, bool SINGLE, bool DIFF>
-__global__ __launch_bounds__(BLOCK) void k_stream(DevCtx c, StreamSeg one, const float* m, const float* delta,
+__global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE && !DIFF ? 3 : 4, SINGLE && !DIFF ? 3 : 4))) void k_stream(DevCtx c, StreamSeg one, const float* m, const float* delta,
                                                   const float* xm, float* m_out, uint32_t worker0, uint64_t round,
                                                   uint32_t R) {
   __shared__ uint2 s_stage[BLOCK / 64][32];
