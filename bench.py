@@ -23,23 +23,38 @@ ALGO_BYTES_PER_COORD = 12       # read m, read Delta, write m': what the method 
 # HBM bytes per k_stream launch measured with rocprofv3 (FETCH_SIZE and WRITE_SIZE, each scaled by what the
 # counter reads for a 1 GiB device copy): profiles/k_stream_cfg2_hbm_traffic.txt.  Only for the configuration
 # that was profiled.
-MEASURED_TRAFFIC_BYTES = {2: 2_515_700_000}
+MEASURED_TRAFFIC_BYTES = {2: 2_495_700_000}
 
 
 def gpu_state():
-    """Clocks and power of GPU 0 as rocm-smi reports them (a child process, started before this process
-    touches the GPU); None if the tool is missing or says nothing useful."""
-    import shutil
-    import subprocess
-    exe = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
-    try:
-        out = subprocess.run([exe, "-d", "0", "--showclocks", "--showpower", "--json"], capture_output=True,
-                             text=True, timeout=20)
-        card = next(iter(json.loads(out.stdout).values()))
-        keep = {k: v for k, v in card.items() if any(t in k.lower() for t in ("sclk", "mclk", "fclk", "power"))}
-        return keep or None
-    except Exception:
-        return None
+    """Clock levels and power of the first AMD GPU as the driver's sysfs files show them (plain file reads:
+    nothing is executed); None if they are not there."""
+    import glob
+
+    def read(path):
+        try:
+            with open(path) as f:
+                return f.read().strip()
+        except OSError:
+            return None
+
+    for dev in sorted(glob.glob("/sys/class/drm/card[0-9]*/device")):
+        if read(os.path.join(dev, "vendor")) != "0x1002":
+            continue
+        out = {}
+        for name in ("pp_dpm_sclk", "pp_dpm_mclk", "pp_dpm_fclk"):
+            txt = read(os.path.join(dev, name))
+            if txt:
+                cur = [ln.strip() for ln in txt.splitlines() if ln.strip().endswith("*")]
+                out[name] = cur[0] if cur else txt.splitlines()[-1].strip()
+        for hw in glob.glob(os.path.join(dev, "hwmon", "hwmon*")):
+            for name in ("power1_average", "power1_input", "power1_cap"):
+                txt = read(os.path.join(hw, name))
+                if txt and txt.isdigit():
+                    out[name + "_W"] = int(txt) / 1e6
+        if out:
+            return out
+    return None
 
 
 def main():
