@@ -1362,15 +1362,25 @@ __device__ __forceinline__ int64_t msg_find(const DevCtx& c, const MsgView& v, u
   return -1;
 }
 
-__global__ __launch_bounds__(BLOCK) void k_add_rows(float* m, const float* delta, uint64_t n) {
-  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * BLOCK * 4;
-  for (uint64_t i = (static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x) * 4; i < n; i += stride) {
-    if (i + 4 <= n) {
-      const f4u a = *reinterpret_cast<const f4u*>(m + i), b = *reinterpret_cast<const f4u*>(delta + i);
-      *reinterpret_cast<f4u*>(m + i) = a + b;
-    } else {
-      for (uint64_t j = i; j < n; ++j) m[j] = m[j] + delta[j];
+// m <- m + delta over the flat [R * d] arrays: the streaming recipe of k_stream (a wave per 1024 elements,
+// non-temporal dwordx4 accesses, 3 waves per SIMD)
+__global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_add_rows(float* m, const float* delta,
+                                                                                              uint64_t n) {
+  const uint64_t chunk = static_cast<uint64_t>(blockIdx.x) * (BLOCK / 64) + (threadIdx.x >> 6);
+  const uint64_t cb = chunk * CHUNK;
+  if (cb >= n) return;
+  const uint32_t lane = lane_id();
+  if (n - cb >= CHUNK) {
+    f4u a[4], b[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      a[t] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(m + cb + t * 256 + lane * 4));
+      b[t] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(delta + cb + t * 256 + lane * 4));
     }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) __builtin_nontemporal_store(a[t] + b[t], reinterpret_cast<f4u*>(m + cb + t * 256 + lane * 4));
+  } else {
+    for (uint64_t i = cb + lane; i < n; i += 64) m[i] = m[i] + delta[i];
   }
 }
 
@@ -1385,11 +1395,11 @@ __global__ __launch_bounds__(BLOCK) void k_subtract_msg(DevCtx c, float* m, cons
   *p = *p - msg_value(c, v, j, idx);
 }
 
-__global__ __launch_bounds__(BLOCK) void k_fill_zero(float* out, uint64_t n) {
+__global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(3, 3))) void k_fill_zero(float* out, uint64_t n) {
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * BLOCK * 4;
   const f4u z = {0.f, 0.f, 0.f, 0.f};
   for (uint64_t i = (static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x) * 4; i < n; i += stride) {
-    if (i + 4 <= n) *reinterpret_cast<f4u*>(out + i) = z;
+    if (i + 4 <= n) __builtin_nontemporal_store(z, reinterpret_cast<f4u*>(out + i));
     else for (uint64_t j = i; j < n; ++j) out[j] = 0.f;
   }
 }
@@ -1842,8 +1852,9 @@ extern "C" qsl_status qsl_error_update(qsl_ctx* ctx, float* m, const float* delt
   if (reinterpret_cast<uintptr_t>(msg) & 7) return QSL_ERR_INVALID_ARG;
   const DevCtx& c = ctx->dc;
   const uint64_t n = static_cast<uint64_t>(R) * c.d;
-  const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((n + BLOCK * 4 - 1) / (BLOCK * 4), 1u << 16));
-  k_add_rows<<<dim3(blocks), BLOCK, 0, ctx->stream>>>(m, delta, n);
+  const uint64_t blocks = (n + CHUNK * (BLOCK / 64) - 1) / (CHUNK * (BLOCK / 64));
+  if (blocks > 0x7FFFFFFFull) return QSL_ERR_UNSUPPORTED;
+  k_add_rows<<<dim3(static_cast<uint32_t>(blocks)), BLOCK, 0, ctx->stream>>>(m, delta, n);
   k_subtract_msg<<<dim3((c.K + BLOCK - 1) / BLOCK, R), BLOCK, 0, ctx->stream>>>(c, m, msg);
   QSL_HIP(hipGetLastError());
   return QSL_OK;
