@@ -69,7 +69,7 @@ def main():
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not bracket the streaming kernel with HIP events (diagnostic: the roofline entry is then empty)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-rounds", type=int, default=2)
+    ap.add_argument("--cpu-rounds", type=int, default=5)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (a kernel of known traffic, to scale rocprofv3 counters)")
     args = ap.parse_args()
