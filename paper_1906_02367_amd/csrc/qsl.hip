@@ -815,7 +815,7 @@ __device__ __forceinline__ Thresh last_digit(const DevCtx& c, uint64_t u, const 
   return th;
 }
 
-// range of general-path groups a compaction block of a fallen-back fast unit takes
+// range of general-path groups a compaction block takes (one group each while the unit has at most 256)
 __device__ __forceinline__ void fallback_range(const SegInfo& sg, uint32_t b, uint32_t* g_lo, uint32_t* g_hi) {
   const uint64_t ngg = (static_cast<uint64_t>(sg.nwt) + GGROUP - 1) / GGROUP;
   *g_lo = static_cast<uint32_t>(ngg * b / sg.ncb); *g_hi = static_cast<uint32_t>(ngg * (b + 1) / sg.ncb);
@@ -996,8 +996,8 @@ __global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, SegInfo one, con
     if (threadIdx.x == 0) *out = make_uint2(s_red[0] + s_red[1] + s_red[2] + s_red[3], s_red[4] + s_red[5] + s_red[6] + s_red[7]);
     return;
   }
-  uint32_t g_lo = cb.b, g_hi = cb.b + 1;
-  if (us.path == PATH_FAST) fallback_range(sg, cb.b, &g_lo, &g_hi);
+  uint32_t g_lo, g_hi;
+  fallback_range(sg, cb.b, &g_lo, &g_hi);
   uint32_t tg = 0, tq = 0;
   general_groups<SPARS, false>(c, sg, v + static_cast<uint64_t>(w) * c.d + sg.start, rk, th, g_lo, g_hi, 0, 0, nullptr,
                                nullptr, nullptr, false, s_cnt, &tg, &tq);
@@ -1064,8 +1064,8 @@ __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, SegInfo one, con
       my_gt += is_gt; my_eq += is_eq;
     }
   } else {
-    uint32_t g_lo = cb.b, g_hi = cb.b + 1;
-    if (us.path == PATH_FAST) fallback_range(sg, cb.b, &g_lo, &g_hi);
+    uint32_t g_lo, g_hi;
+    fallback_range(sg, cb.b, &g_lo, &g_hi);
     uint32_t tg, tq;
     general_groups<SPARS, true>(c, sg, v + static_cast<uint64_t>(w) * c.d + sg.start, rk, th, g_lo, g_hi, gt0, eq0, oi, ov,
                                 mine, squares, s_cnt, &tg, &tq);
@@ -1648,7 +1648,9 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
       sg.nsel = 0; sg.ncb = 0;
     } else {
       sg.nsel = std::min(MAX_SELECT_BLOCKS, std::max(1u, (sg.nwt + 31) / 32));   // two chunks per wave up to 2^21 coordinates
-      sg.ncb = (sg.nwt + GGROUP - 1) / GGROUP;
+      // at most 256 compaction blocks per unit, each a contiguous range of groups: every block ends with up to 20
+      // atomics on the unit's digit counters, and thousands of blocks on the same few lines serialise there
+      sg.ncb = std::min<uint32_t>(256, (sg.nwt + GGROUP - 1) / GGROUP);
     }
   }
   // blocks of a fast unit in the selection kernels: ~3 slot rows per wave, and no more than one block
