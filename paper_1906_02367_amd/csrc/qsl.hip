@@ -110,6 +110,7 @@ struct DevCtx {
   UnitState* units;
   uint2* slots; uint64_t slot_stride;   // per worker: one slot (lpc * 2 elements) per chunk of every fast segment
   uint2* ovf; uint64_t ovf_stride;      // per worker: overflow pools, for chunks with more candidates than a slot holds
+  uint32_t* slot_key; uint32_t* ovf_key; // Rand_k only: the rank key (random word) of every slot element / pool entry
   uint2* d0; uint32_t* d0_key; uint64_t d0_stride;   // per worker: dense, coordinate-ordered candidate lists (+ keys, Rand_k)
   uint32_t* wave_cnt;   // [R][NWC]: candidates met by each wave of k_select<0>
   uint2* cb_cnt;        // [R][NCB]: (#key > tau, #key == tau) of each compaction block
@@ -131,11 +132,6 @@ __device__ __forceinline__ uint32_t key_of_value(uint32_t vbits) { return (vbits
 __host__ __device__ __forceinline__ bool is_qsgd(uint32_t q) { return q == QSL_QSGD || q == QSL_QSGD_SCALED; }
 // which exact sum the quantiser's scale needs: squares (l2 norm), magnitudes (l1 norm), none
 __host__ __device__ __forceinline__ bool wants_squares(uint32_t q) { return is_qsgd(q) || q == QSL_SIGN_L2; }
-
-template <int SPARS>
-__device__ __forceinline__ uint32_t entry_key(uint32_t idx, uint32_t bits, const RandKey& rk) {
-  return SPARS == QSL_TOPK ? key_of_value(bits) : rand_word(rk, idx);
-}
 
 // rank key of a coordinate in the general path: from v (already written to m_out) or its random word
 template <int SPARS>
@@ -308,6 +304,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
                                                   const float* xm, float* m_out, uint32_t worker0, uint64_t round,
                                                   uint32_t R) {
   __shared__ uint2 s_stage[BLOCK / 64][32];
+  __shared__ uint32_t s_stage_key[SPARS == QSL_RANDK ? BLOCK / 64 : 1][32];
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   uint32_t blk = blockIdx.x, w = blockIdx.y;
   if (DIFF) {
@@ -369,10 +366,11 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   uint32_t pm = 0;                                                    // bit t*4+j: coordinate (t, j) is a candidate
   bool nonfinite = false;
+  Words4 rws[4];                                                      // Rand_k: the keys, kept for the slot's key line
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     Words4 rw;
-    if (SPARS == QSL_RANDK) rw = rand_words4(rk, static_cast<uint32_t>(sg.start + cb + t * 256 + lane * 4));
+    if (SPARS == QSL_RANDK) { rw = rand_words4(rk, static_cast<uint32_t>(sg.start + cb + t * 256 + lane * 4)); rws[t] = rw; }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const uint32_t bits = __float_as_uint(v[t][j]);
@@ -405,6 +403,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
     total = tot[0] + tot[1] + tot[2] + tot[3];
     uint32_t* ctr = c.ctr + u * (CTR_LINES * PAD);
     uint2* dst = stage + 1;                       // where entry 0 goes
+    uint32_t* dst_key = SPARS == QSL_RANDK ? s_stage_key[wave] + 1 : nullptr;
     bool write = true;
     if (total > cap) {                            // wave-uniform: the slot cannot hold this chunk
       if (lane == 0) {
@@ -414,6 +413,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
       ovf_at = __shfl(ovf_at, 0, WAVE);
       write = ovf_at != 0xFFFFFFFFu;
       dst = c.ovf + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off + ovf_at;
+      if (SPARS == QSL_RANDK) dst_key = c.ovf_key + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off + ovf_at;
     }
     if (lane == 0) atomicAdd(&ctr[(chunk & (NSUB - 1)) * PAD], total);          // nobody waits for this one
     if (write) {
@@ -424,8 +424,10 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
         uint32_t pos = base + before[t];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          if ((nib >> j) & 1u)
+          if ((nib >> j) & 1u) {
+            if (SPARS == QSL_RANDK) dst_key[pos] = rws[t].w[j];
             dst[pos++] = make_uint2(static_cast<uint32_t>(sg.start + cb + t * 256 + lane * 4 + j), __float_as_uint(v[t][j]));
+          }
         }
         base += tot[t];
       }
@@ -439,8 +441,9 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
   if (lane < sg.lpc * 2) {
     const uint2 e = stage[lane];
     const u2v ev = {e.x, e.y};
-    uint2* slot = c.slots + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off + static_cast<uint64_t>(chunk) * (sg.lpc * 2);
-    __builtin_nontemporal_store(ev, reinterpret_cast<u2v*>(slot + lane));
+    const uint64_t at = static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off + static_cast<uint64_t>(chunk) * (sg.lpc * 2);
+    __builtin_nontemporal_store(ev, reinterpret_cast<u2v*>(c.slots + at + lane));
+    if (SPARS == QSL_RANDK) __builtin_nontemporal_store(s_stage_key[wave][lane], c.slot_key + at + lane);   // the slot's key line
   }
 }
 
@@ -456,15 +459,21 @@ struct SlotRow {
   bool spill;            // n entries are read from the overflow pool
   bool has0, has1;       // this lane's first / second element is a candidate
   uint32_t idx0, bits0, idx1, bits1;
+  uint32_t key0, key1;   // Rand_k: their rank keys, from the slot's key line
 };
 
-__device__ __forceinline__ SlotRow read_slot_row(const uint2* slots, uint32_t lpc, uint32_t nwt, uint64_t row,
-                                                 uint64_t nrows) {
+__device__ __forceinline__ SlotRow read_slot_row(const uint2* slots, const uint32_t* slot_key, uint32_t lpc, uint32_t nwt,
+                                                 uint64_t row, uint64_t nrows) {
   SlotRow r;
   const uint32_t lane = lane_id();
   const uint32_t sub = lane & (lpc - 1);
   uint4 q = make_uint4(0, 0, 0, 0);
-  if (row < nrows && ((row * 64 + lane) >> (__ffs(lpc) - 1)) < nwt) q = reinterpret_cast<const uint4*>(slots)[row * 64 + lane];   // lpc: 4, 8 or 16
+  uint2 kq = make_uint2(0, 0);
+  if (row < nrows && ((row * 64 + lane) >> (__ffs(lpc) - 1)) < nwt) {                                                 // lpc: 4, 8 or 16
+    q = reinterpret_cast<const uint4*>(slots)[row * 64 + lane];
+    if (slot_key) kq = reinterpret_cast<const uint2*>(slot_key)[row * 64 + lane];
+  }
+  r.key0 = kq.x; r.key1 = kq.y;
   const uint32_t leader = lane & ~(lpc - 1);
   r.count = __shfl(q.x, leader, WAVE);
   r.ovf_at = __shfl(q.y, leader, WAVE);
@@ -555,6 +564,8 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, SegInfo one, const flo
   if (path == PATH_FAST && LEVEL < 2) {
     const uint2* slots = c.slots + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off;
     const uint2* ovf = c.ovf + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off;
+    const uint32_t* slot_key = SPARS == QSL_RANDK ? c.slot_key + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off : nullptr;
+    const uint32_t* ovf_key = SPARS == QSL_RANDK ? c.ovf_key + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off : nullptr;
     uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
     uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
     uint32_t* wcnt = c.wave_cnt + static_cast<uint64_t>(w) * c.NWC + sg.wc_base;
@@ -579,7 +590,7 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, SegInfo one, const flo
     for (uint64_t row0 = r_lo; row0 < r_hi; row0 += 4) {
       SlotRow rr[4];                               // four independent accesses in flight; rows past the end read as empty
 #pragma unroll
-      for (int b = 0; b < 4; ++b) rr[b] = read_slot_row(slots, sg.lpc, sg.nwt, row0 + b, r_hi);
+      for (int b = 0; b < 4; ++b) rr[b] = read_slot_row(slots, slot_key, sg.lpc, sg.nwt, row0 + b, r_hi);
 #pragma unroll
       for (int b = 0; b < 4; ++b) {
         const SlotRow& r = rr[b];
@@ -589,19 +600,19 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, SegInfo one, const flo
         if (!r.spill) {
           uint32_t bin;
           if (r.has0) {
-            const uint32_t key = entry_key<SPARS>(r.idx0, r.bits0, rk);
+            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(r.bits0) : r.key0;
             if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
             if (LEVEL == 1) { d0[pos] = make_uint2(r.idx0, r.bits0); if (SPARS == QSL_RANDK) d0k[pos] = key; ++pos; }
           }
           if (r.has1) {
-            const uint32_t key = entry_key<SPARS>(r.idx1, r.bits1, rk);
+            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(r.bits1) : r.key1;
             if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
             if (LEVEL == 1) { d0[pos] = make_uint2(r.idx1, r.bits1); if (SPARS == QSL_RANDK) d0k[pos] = key; }
           }
         } else {
           for (uint32_t e = 0; e < r.count; ++e) {
             const uint2 ent = ovf[r.ovf_at + e];
-            const uint32_t key = entry_key<SPARS>(ent.x, ent.y, rk);
+            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(ent.y) : ovf_key[r.ovf_at + e];
             uint32_t bin;
             if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
             if (LEVEL == 1) { d0[pos + e] = ent; if (SPARS == QSL_RANDK) d0k[pos + e] = key; }
@@ -1693,6 +1704,9 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t o_units = carve(sizeof(UnitState) * U);
   const uint64_t o_slots = carve(8ull * std::max<uint64_t>(2, slot_elems) * R);
   const uint64_t o_ovf = carve(8ull * std::max<uint64_t>(1, ovf_entries) * R);
+  const bool randk = cfg->sparsifier == QSL_RANDK;
+  const uint64_t o_skey = carve(randk ? 4ull * std::max<uint64_t>(2, slot_elems) * R : 4);
+  const uint64_t o_okey = carve(randk ? 4ull * std::max<uint64_t>(1, ovf_entries) * R : 4);
   const uint64_t o_d0 = carve(8ull * std::max<uint64_t>(1, d0_entries) * R);
   const uint64_t o_d0k = carve(4ull * std::max<uint64_t>(1, d0_entries) * R);
   const uint64_t o_wc = carve(4ull * NWC * R), o_cbc = carve(8ull * NCB * R);
@@ -1729,6 +1743,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.units = reinterpret_cast<UnitState*>(base + o_units);
   c.slots = reinterpret_cast<uint2*>(base + o_slots); c.slot_stride = std::max<uint64_t>(2, slot_elems);
   c.ovf = reinterpret_cast<uint2*>(base + o_ovf); c.ovf_stride = std::max<uint64_t>(1, ovf_entries);
+  c.slot_key = reinterpret_cast<uint32_t*>(base + o_skey); c.ovf_key = reinterpret_cast<uint32_t*>(base + o_okey);
   c.d0 = reinterpret_cast<uint2*>(base + o_d0); c.d0_key = reinterpret_cast<uint32_t*>(base + o_d0k);
   c.d0_stride = std::max<uint64_t>(1, d0_entries);
   c.wave_cnt = reinterpret_cast<uint32_t*>(base + o_wc); c.cb_cnt = reinterpret_cast<uint2*>(base + o_cbc);
