@@ -90,13 +90,16 @@ struct WtInfo { uint32_t seg, chunk, pad0, pad1; };                 // one chunk
 struct SelInfo { uint32_t seg, j, pad0, pad1; };                    // one block of a selection kernel
 struct CbInfo { uint32_t seg, b, pad0, pad1; };                     // one compaction block
 
-// Every field is written by exactly one kernel of a call and read only by later kernels.
+// Every field is written by exactly one kernel of a call and read only by later kernels (the blocks of
+// one launch start at different times: a field that a launch both reads and rewrites would show late
+// blocks the new value).
 struct UnitState {
   uint32_t path;        // static: PATH_FAST, PATH_GENERAL or PATH_SMALL
   uint32_t T;           // guess key (k_sample_scan; static for Rand_k and for the general path)
   uint32_t cand;        // candidates collected (k_select<0>)
   uint32_t fell_back;   // 1: the guess failed, the unit runs the general path (k_select<0>)
-  uint32_t prefix, k_rem;   // radix selection state (k_select<1>, k_select<2>)
+  uint32_t prefix1, k_rem1; // radix selection state after the first digit (found by k_select<1> from the first histogram) ...
+  uint32_t prefix2, k_rem2; // ... and after the second (k_select<2>); the third is found by k_tile_count
   uint32_t tau, need, n_gt; // threshold key, how many equal to it are kept, how many above (k_tile_count)
   uint32_t nnz;         // transmitted coordinates (zeroed by k_select<0>, counted by k_quantize)
   uint32_t scale_bits;  // fp32 scale (k_quantize)
@@ -194,7 +197,7 @@ __global__ void k_init(DevCtx c, uint32_t U) {
   const SegInfo& sg = c.segs[u % c.L];
   UnitState s;
   s.path = sg.mode; s.T = sg.mode == PATH_FAST ? sg.T_static : 0xFFFFFFFFu; s.cand = 0; s.fell_back = 0;
-  s.prefix = 0; s.k_rem = sg.k; s.tau = 0; s.need = 0; s.n_gt = 0; s.nnz = 0; s.scale_bits = 0; s.pad = 0;
+  s.prefix1 = 0; s.k_rem1 = sg.k; s.prefix2 = 0; s.k_rem2 = sg.k; s.tau = 0; s.need = 0; s.n_gt = 0; s.nnz = 0; s.scale_bits = 0; s.pad = 0;
   c.units[u] = s;
 }
 
@@ -554,10 +557,13 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, SegInfo one, const flo
       const uint32_t bin = find_from_top<BIG>(hist, sg.k, &above, scratch, result, false);
       prefix = bin << 20; k_rem = sg.k - above;
     } else {
-      const uint32_t bin = find_from_top<BIG>(hist + HBINS, us.k_rem, &above, scratch, result, false);
-      prefix = us.prefix | (bin << 8); k_rem = us.k_rem - above;
+      const uint32_t bin = find_from_top<BIG>(hist + HBINS, us.k_rem1, &above, scratch, result, false);
+      prefix = us.prefix1 | (bin << 8); k_rem = us.k_rem1 - above;
     }
-    if (threadIdx.x == 0 && si.j == 0) { usp->prefix = prefix; usp->k_rem = k_rem; }
+    if (threadIdx.x == 0 && si.j == 0) {
+      if (LEVEL == 1) { usp->prefix1 = prefix; usp->k_rem1 = k_rem; }
+      else { usp->prefix2 = prefix; usp->k_rem2 = k_rem; }
+    }
   }
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
@@ -821,8 +827,8 @@ __device__ void general_groups(const DevCtx& c, const SegInfo& sg, const float* 
 __device__ __forceinline__ Thresh last_digit(const DevCtx& c, uint64_t u, const UnitState& us, uint64_t* scratch,
                                              uint32_t* result) {
   uint32_t above;
-  const uint32_t bin = find_from_top<BLOCK, 256>(c.hist + (u * 3 + 2) * HBINS, us.k_rem, &above, scratch, result, false);
-  Thresh th; th.tau = us.prefix | bin; th.need = us.k_rem - above;
+  const uint32_t bin = find_from_top<BLOCK, 256>(c.hist + (u * 3 + 2) * HBINS, us.k_rem2, &above, scratch, result, false);
+  Thresh th; th.tau = us.prefix2 | bin; th.need = us.k_rem2 - above;
   return th;
 }
 
@@ -965,7 +971,7 @@ __global__ __launch_bounds__(BLOCK) void k_small(DevCtx c, const float* v, uint3
   }
   if (threadIdx.x == 0) {
     UnitState* us = &c.units[u];
-    us->cand = 0; us->fell_back = 0; us->prefix = tau & ~0xFFu; us->k_rem = k_rem;
+    us->cand = 0; us->fell_back = 0; us->prefix2 = tau & ~0xFFu; us->k_rem2 = k_rem;
     us->tau = tau; us->need = need; us->n_gt = sg.k - need; us->nnz = 0;
   }
 }

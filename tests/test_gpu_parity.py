@@ -380,3 +380,21 @@ def test_per_tensor_rule_k_min_d_1000(P, quantizer, s):
     wl = W.Workload(4, "cfg4_k_min_d_1000", 2, base.d, base.seg_offset, k, s, W.TOPK, quantizer, 2, base.seed)
     run, op, m_host, paths = P.run_parity(wl, 2)
     assert set(paths[0].tolist()) == {0, 1, 3}, np.bincount(paths[0])
+
+
+# ---------------------------------------------------------------------------------------------
+# dense selections in many mid-sized segments: more multi-pass selection blocks than the GPU holds at once,
+# so the blocks of one launch start at different times (a field of the unit state that one launch both read
+# and rewrote once showed late blocks the new value here)
+# ---------------------------------------------------------------------------------------------
+def test_dense_k_in_many_segments_more_blocks_than_fit(P):
+    rng = np.random.default_rng(5282)
+    d, L, R = 3_328_894, 17, 3
+    cuts = np.sort(rng.choice(np.arange(1, d), size=L - 1, replace=False))
+    off = np.concatenate([[0], cuts, [d]]).astype(np.uint64)
+    sizes = np.diff(off.astype(np.int64))
+    k = np.maximum(1, (sizes * rng.uniform(0.05, 1.0, size=L)).astype(np.int64)).astype(np.uint32)
+    wl = custom(d, off, k, 1, W.TOPK, W.SIGN_L1, R=R)
+    deltas = [(rng.standard_normal((R, d)) * np.exp(2 * rng.standard_normal(d))).astype(f32) for _ in range(3)]
+    run, op, m_host, paths = P.run_parity(wl, 3, deltas=deltas, worker0=55)
+    assert (paths[0] == 1).all()
