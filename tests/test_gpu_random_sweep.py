@@ -1,0 +1,111 @@
+"""Seeded random operator configurations against the oracle: sizes from one coordinate to a few million, one to
+thousands of segments, sparse to dense k (k = size included), every sparsifier / quantiser / flag combination,
+several kinds of input.  Every output of both rounds is compared bit for bit; the master line, the bit counts
+and the equivalence of the three ways to the same message (qsl_compress, qsl_compress_diff, qsl_compress followed
+by the stand-alone qsl_error_update) are checked on the last round."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from paper_1906_02367_amd import workloads as W  # noqa: E402
+
+f32 = np.float32
+
+
+@pytest.fixture(scope="module")
+def P():
+    import parity_util
+    return parity_util
+
+
+def random_case(seed, d_min, d_max, l_choices, r_max):
+    rng = np.random.default_rng(seed)
+    d = int(np.exp(rng.uniform(np.log(d_min), np.log(d_max))))
+    L = min(int(rng.choice(l_choices)), d)
+    cuts = np.sort(rng.choice(np.arange(1, d), size=L - 1, replace=False)) if L > 1 else np.array([], dtype=np.int64)
+    off = np.concatenate([[0], cuts, [d]]).astype(np.uint64)
+    sizes = np.diff(off.astype(np.int64))
+    mode = int(rng.integers(0, 4))
+    if mode == 0:
+        k = np.maximum(1, (sizes * rng.uniform(0.0005, 0.02)).astype(np.int64))        # sparse
+    elif mode == 1:
+        k = np.minimum(sizes, 1000)                                                    # the paper's per-tensor rule
+    elif mode == 2:
+        k = np.maximum(1, (sizes * rng.uniform(0.05, 1.0, size=L)).astype(np.int64))   # dense
+    else:
+        k = np.where(rng.random(L) < 0.3, sizes, np.maximum(1, sizes // int(rng.integers(2, 2000))))
+    k = np.minimum(k, sizes).astype(np.uint32)
+    sp, qz = int(rng.integers(0, 2)), int(rng.integers(0, 5))
+    s = int(rng.choice([1, 2, 3, 15, 16, 255, 1000, 32768]))
+    R = int(rng.integers(1, r_max + 1))
+    flags = int(rng.choice([0, 0, 0, 1, 2, 3]))
+    wl = W.Workload(2, f"random{seed}", R, d, off, k, s, sp, qz, 2, int(rng.integers(0, 2**63)))
+    kind = int(rng.integers(0, 4))
+    deltas = []
+    for _ in range(2):
+        x = rng.standard_normal((R, d)).astype(f32)
+        if kind == 1:
+            x *= np.exp(2 * rng.standard_normal(d)).astype(f32)         # heavy-tailed scales
+        elif kind == 2:
+            x = np.round(x * 2).astype(f32)                             # many equal magnitudes
+        elif kind == 3:
+            x[:, rng.random(d) < 0.7] = 0                               # mostly zeros
+        deltas.append(x)
+    return rng, wl, flags, deltas
+
+
+def check_case(P, seed, d_min, d_max, l_choices, r_max):
+    from paper_1906_02367_amd import binding as B
+    rng, wl, flags, deltas = random_case(seed, d_min, d_max, l_choices, r_max)
+    R, d = wl.R, wl.d
+    print(f"case {seed}: d={d} L={wl.L} K={wl.K} sparsifier={wl.sparsifier} quantizer={wl.quantizer} s={wl.s} R={R} "
+          f"flags={flags}", flush=True)
+    run, op, m_host, _ = P.run_parity(wl, 2, flags=flags, deltas=deltas, worker0=int(rng.integers(0, 100)),
+                                      in_place=bool(rng.integers(0, 2)))
+    q = run.q
+    lst = [int(x) for x in rng.permutation(R)[:max(1, R - 1)]]
+    x0 = rng.standard_normal(d).astype(f32)
+    out = torch.from_numpy(x0).to(q.device)
+    q.aggregate(run.msg, out, -1.0 / R, worker_list=lst, accumulate=True)
+    torch.cuda.synchronize()
+    msgs = run.msg.cpu().numpy()
+    want = op.aggregate(msgs, -1.0 / R, worker_list=lst, out=x0)
+    mag = np.zeros(d)
+    for r in lst:
+        i, v = op.decode(msgs[r])
+        mag[i] += np.abs(v.astype(np.float64))
+    err = np.abs(out.cpu().numpy().astype(np.float64) - want)
+    assert np.all(err <= 1e-6 * (mag / R + np.abs(want)) + 1e-38), f"master line off by {err.max()}"
+    assert q.bits_sent(run.msg) == [op.bits_sent(msgs[r]) for r in range(R)]
+    xx, md = torch.from_numpy(x0).to(q.device), torch.from_numpy(m_host).to(q.device)
+    xh = xx.unsqueeze(0) - torch.from_numpy(deltas[1]).to(q.device)
+    dl = xx.unsqueeze(0) - xh
+    ma, mb, msga, msgb = torch.empty_like(md), torch.empty_like(md), q.new_msg(R), q.new_msg(R)
+    q.compress_diff(md, xx, xh, ma, 7, 5, msga)
+    q.compress(md, dl, mb, 7, 5, msgb)
+    mc = md.clone()
+    q.error_update(mc, dl, msgb)
+    torch.cuda.synchronize()
+    assert torch.equal(msga, msgb) and torch.equal(ma.view(torch.int32), mb.view(torch.int32))
+    assert torch.equal(mc.view(torch.int32), mb.view(torch.int32))
+    assert q.device_status() == B.OK
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_random_small_and_mid_sizes(P, block):
+    for seed in range(20_000 + 40 * block, 20_000 + 40 * (block + 1)):
+        check_case(P, seed, 1, 600_000, [1, 1, 1, 2, 5, 17, 60], 8)
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_random_many_segments(P, block):
+    for seed in range(40_000 + 12 * block, 40_000 + 12 * (block + 1)):
+        check_case(P, seed, 20_000, 3_000_000, [40, 300, 2000, 9000], 3)
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_random_large_sizes(P, block):
+    for seed in range(5_270 + 10 * block, 5_270 + 10 * (block + 1)):      # 5282 once caught a race in k_select<2>
+        check_case(P, seed, 50_000, 8_000_000, [1, 1, 1, 2, 5, 17, 60], 3)
