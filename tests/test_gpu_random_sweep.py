@@ -42,7 +42,7 @@ def random_case(seed, d_min, d_max, l_choices, r_max):
     R = int(rng.integers(1, r_max + 1))
     flags = int(rng.choice([0, 0, 0, 1, 2, 3]))
     wl = W.Workload(2, f"random{seed}", R, d, off, k, s, sp, qz, 2, int(rng.integers(0, 2**63)))
-    kind = int(rng.integers(0, 4))
+    kind = int(rng.integers(0, 5))
     deltas = []
     for _ in range(2):
         x = rng.standard_normal((R, d)).astype(f32)
@@ -52,6 +52,8 @@ def random_case(seed, d_min, d_max, l_choices, r_max):
             x = np.round(x * 2).astype(f32)                             # many equal magnitudes
         elif kind == 3:
             x[:, rng.random(d) < 0.7] = 0                               # mostly zeros
+        elif kind == 4:                                                 # one magnitude and zeros: every guess overflows
+            x = np.sign(x) * (rng.random((R, d)) < 0.5).astype(f32) * f32(rng.choice([1.0, 3.5, 1e-30]))
         deltas.append(x)
     return rng, wl, flags, deltas
 
