@@ -398,3 +398,27 @@ def test_dense_k_in_many_segments_more_blocks_than_fit(P):
     deltas = [(rng.standard_normal((R, d)) * np.exp(2 * rng.standard_normal(d))).astype(f32) for _ in range(3)]
     run, op, m_host, paths = P.run_parity(wl, 3, deltas=deltas, worker0=55)
     assert (paths[0] == 1).sum() >= 30, np.bincount(paths[0])          # most of the 51 units take the multi-pass kernels
+
+
+def test_side_stream_gives_the_same_bytes(P):
+    # the library launches on whatever stream the caller hands it; two contexts on two streams at once
+    from paper_1906_02367_amd import binding as B
+    wl = W.config(2, d=1_000_003, R=2)
+    d0 = torch.from_numpy(W.delta_all(wl, 0)).to("cuda")
+    d1 = torch.from_numpy(W.delta_all(wl, 1)).to("cuda")
+    qa, qb = B.from_workload(wl), B.from_workload(wl)
+    ma, mb = torch.zeros(2, wl.d, device="cuda"), torch.zeros(2, wl.d, device="cuda")
+    msga, msgb = qa.new_msg(2), qb.new_msg(2)
+    xa, xb = torch.zeros(wl.d, device="cuda"), torch.zeros(wl.d, device="cuda")
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    for t, dl in enumerate((d0, d1)):
+        qa.compress(ma, dl, ma, 0, t, msga)
+        qa.aggregate(msga, xa, -0.5, accumulate=True)
+        with torch.cuda.stream(side):
+            qb.compress(mb, dl, mb, 0, t, msgb)
+            qb.aggregate(msgb, xb, -0.5, accumulate=True)
+    torch.cuda.synchronize()
+    assert torch.equal(msga, msgb) and torch.equal(ma.view(torch.int32), mb.view(torch.int32))
+    assert torch.equal(xa.view(torch.int32), xb.view(torch.int32))
+    assert qa.device_status() == B.OK and qb.device_status() == B.OK
