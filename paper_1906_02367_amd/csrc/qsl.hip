@@ -52,7 +52,7 @@ constexpr uint32_t CHUNK = 1024;           // coordinates one wave streams: 4 x 
 constexpr uint32_t BLOCK = 256;
 constexpr uint32_t HBINS = 4096;           // radix digits: 12 + 12 + 8 bits of the 32-bit rank key
 constexpr uint32_t ACC_SLOTS = 20;         // 32-bit digits of the exact accumulator
-constexpr uint32_t MAX_SAMPLE_BLOCKS = 128; // blocks (of 1024 threads) per unit of the sampling kernel: 16 .. 128
+constexpr uint32_t MAX_SAMPLE_BLOCKS = 128; // blocks (of 1024 threads) per unit of the sampling kernel: 1 .. 128
 constexpr uint32_t MAX_SELECT_BLOCKS = 64; // blocks (of 1024 threads) per unit of the selection kernels: 1 .. 64
 constexpr uint32_t BIG = 1024;             // threads of the sampling and selection kernels
 constexpr uint32_t MAX_QB_INLINE = 4096;   // above this many quantise blocks a separate prefix kernel runs
@@ -135,12 +135,6 @@ __device__ __forceinline__ uint32_t key_of_value(uint32_t vbits) { return (vbits
 __host__ __device__ __forceinline__ bool is_qsgd(uint32_t q) { return q == QSL_QSGD || q == QSL_QSGD_SCALED; }
 // which exact sum the quantiser's scale needs: squares (l2 norm), magnitudes (l1 norm), none
 __host__ __device__ __forceinline__ bool wants_squares(uint32_t q) { return is_qsgd(q) || q == QSL_SIGN_L2; }
-
-// rank key of a coordinate in the general path: from v (already written to m_out) or its random word
-template <int SPARS>
-__device__ __forceinline__ uint32_t coord_key(const float* vp, uint64_t e, uint64_t start, const RandKey& rk) {
-  return SPARS == QSL_TOPK ? key_of_value(__float_as_uint(vp[e])) : rand_word(rk, static_cast<uint32_t>(start + e));
-}
 
 __device__ __forceinline__ uint32_t eff_path(const UnitState& us) {
   return us.path == PATH_FAST && us.fell_back ? static_cast<uint32_t>(PATH_FALLBACK) : us.path;
@@ -681,11 +675,11 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, SegInfo one, const flo
 // ordered compaction of the selected coordinates, with the exact norm of what is selected.
 //
 // A "compaction block" covers either a tile of 2048 entries of a fast unit's dense candidate list
-// (each thread 8 consecutive entries), or a group of 16 chunks of v on the general path (each wave
-// 4 chunks, a lane 16 coordinates of a chunk).  k_tile_count leaves the number of selected
+// (each thread 8 consecutive entries), or, on the general path, a contiguous range of groups of 16
+// chunks of v (a group at a time: each wave 4 chunks, a lane 16 coordinates of a chunk; one group per
+// block while the unit has at most 256 groups).  k_tile_count leaves the number of selected
 // coordinates of every block; k_tile_write sums the earlier blocks' numbers to know where it writes.
-// A fast unit whose guess failed runs the general path with the blocks it has: each takes a
-// contiguous range of groups.
+// A fast unit whose guess failed runs the general path with the blocks it has.
 //
 // Exact norms: every |v| (or v^2) is an integer multiple of 2^-149 (2^-298); its 32-bit digits are
 // added into 64-bit counters; integer addition commutes, so any schedule gives the same sum.
@@ -757,7 +751,7 @@ __device__ __forceinline__ void add_digits(uint64_t* mine, uint32_t bits, bool s
 // WRITE = false: returns (in *tot_gt, *tot_eq, valid in thread 0) how many coordinates of these groups have key > tau / == tau.
 // WRITE = true: writes the selected ones, in coordinate order, starting at ranks (gt0, eq0).
 template <int SPARS, bool WRITE>
-__device__ void general_groups(const DevCtx& c, const SegInfo& sg, const float* vp, const RandKey& rk, Thresh th,
+__device__ void general_groups(const SegInfo& sg, const float* vp, const RandKey& rk, Thresh th,
                                uint32_t g_lo, uint32_t g_hi, uint32_t gt0, uint32_t eq0, uint32_t* oi, uint32_t* ov,
                                uint64_t* mine, bool squares, uint32_t* s_cnt /*[2][GGROUP + 1]*/,
                                uint32_t* tot_gt, uint32_t* tot_eq) {
@@ -1016,7 +1010,7 @@ __global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, SegInfo one, con
   uint32_t g_lo, g_hi;
   fallback_range(sg, cb.b, &g_lo, &g_hi);
   uint32_t tg = 0, tq = 0;
-  general_groups<SPARS, false>(c, sg, v + static_cast<uint64_t>(w) * c.d + sg.start, rk, th, g_lo, g_hi, 0, 0, nullptr,
+  general_groups<SPARS, false>(sg, v + static_cast<uint64_t>(w) * c.d + sg.start, rk, th, g_lo, g_hi, 0, 0, nullptr,
                                nullptr, nullptr, false, s_cnt, &tg, &tq);
   if (threadIdx.x == 0) *out = make_uint2(tg, tq);
 }
@@ -1084,7 +1078,7 @@ __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, SegInfo one, con
     uint32_t g_lo, g_hi;
     fallback_range(sg, cb.b, &g_lo, &g_hi);
     uint32_t tg, tq;
-    general_groups<SPARS, true>(c, sg, v + static_cast<uint64_t>(w) * c.d + sg.start, rk, th, g_lo, g_hi, gt0, eq0, oi, ov,
+    general_groups<SPARS, true>(sg, v + static_cast<uint64_t>(w) * c.d + sg.start, rk, th, g_lo, g_hi, gt0, eq0, oi, ov,
                                 mine, squares, s_cnt, &tg, &tq);
   }
   __syncthreads();
