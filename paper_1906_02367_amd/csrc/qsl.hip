@@ -110,6 +110,8 @@ struct DevCtx {
   const SegInfo* segs; const WtInfo* wts; const SelInfo* sels; const SelInfo* samps; const CbInfo* cbs;
   const uint32_t* fast_segs;
   const uint32_t* small_segs;
+  const uint32_t* seg_dir;  // [ceil(d / 1024) + 1]: segment of coordinate t * 1024 (the last entry: L - 1)
+  const uint32_t* slot_dir; // [ceil(K / 256) + 1]: segment of slot b * 256 of the selected arrays
   UnitState* units;
   uint2* slots; uint64_t slot_stride;   // per worker: one slot (lpc * 2 elements) per chunk of every fast segment
   uint2* ovf; uint64_t ovf_stride;      // per worker: overflow pools, for chunks with more candidates than a slot holds
@@ -1140,13 +1142,18 @@ __device__ float finalize_scale(const uint64_t* acc, uint32_t quantizer, uint32_
 // ------------------------------------------------------------------------------------------------
 // quantise, error update, message
 // ------------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t seg_of_slot(const DevCtx& c, uint32_t j) {   // segment owning slot j of [K]
-  uint32_t lo = 0, hi = c.L;
+// segment owning slot j of [K]: slot_dir[b] is the segment of slot b * 256 (same idea as seg_dir below)
+__device__ __forceinline__ uint32_t seg_of_slot(const DevCtx& c, uint32_t j) {
+  const uint32_t b = j >> 8;
+  uint32_t lo = c.slot_dir[b], hi = c.slot_dir[b + 1] + 1;
   while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (c.segs[mid].koff <= j) lo = mid; else hi = mid; }
   return lo;
 }
+// segment of coordinate i: seg_dir[t] is the segment of coordinate t * 1024, so the search is over the few
+// segments that touch one 1024-block instead of all L
 __device__ __forceinline__ uint32_t seg_of_coord(const DevCtx& c, uint32_t i) {
-  uint32_t lo = 0, hi = c.L;
+  const uint32_t t = i >> 10;
+  uint32_t lo = c.seg_dir[t], hi = c.seg_dir[t + 1] + 1;       // segs[lo].start <= i < segs[hi].start (or hi = L)
   while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (c.segs[mid].start <= i) lo = mid; else hi = mid; }
   return lo;
 }
@@ -1417,13 +1424,50 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(3, 3))) v
 
 struct RowList { uint32_t row[64]; };
 constexpr uint32_t AGG_ENTRIES = 32;     // message entries per block; 8 threads look one entry up in parallel
+constexpr uint32_t AGG_DIR_SHIFT = 10;   // a directory entry per 1024 coordinates
+constexpr uint32_t AGG_DIR_MIN = 4096;   // messages expected to be at least this long get a directory
+
+// Directory of a long message: dir[t] = number of entries whose coordinate lies below t * 1024, for
+// t = 0 .. ndir - 1 (ndir = ceil(d / 1024) + 1, so dir[ndir - 1] = nnz).  Entry j fills the slots between
+// its predecessor's 1024-block and its own; the last entry also fills the rest.  A lookup then needs
+// dir[t], dir[t + 1] and a binary search over the few entries of one 1024-block instead of log2(nnz)
+// dependent probes of the whole message.
+__global__ __launch_bounds__(BLOCK) void k_msg_directory(DevCtx c, const uint8_t* msg, RowList rows, uint32_t* dir,
+                                                         uint32_t ndir) {
+  const uint32_t q = blockIdx.y;
+  const MsgView v = view_msg(c, msg, rows.row[q]);
+  uint32_t* mine = dir + static_cast<uint64_t>(q) * ndir;
+  const uint32_t nth = gridDim.x * BLOCK, tid = blockIdx.x * BLOCK + threadIdx.x;
+  if (v.nnz == 0) { for (uint32_t t = tid; t < ndir; t += nth) mine[t] = 0; return; }
+  for (uint32_t j = tid; j < v.nnz; j += nth) {
+    const uint32_t cur = min(msg_index(c, v, j) >> AGG_DIR_SHIFT, ndir - 2);           // clamp: a malformed index
+    const uint32_t first = j ? min(msg_index(c, v, j - 1) >> AGG_DIR_SHIFT, ndir - 2) + 1 : 0u;
+    for (uint32_t t = first; t <= cur; ++t) mine[t] = j;                // empty when the predecessor shares the block
+    if (j == v.nnz - 1) for (uint32_t t = cur + 1; t < ndir; ++t) mine[t] = v.nnz;
+  }
+}
+
+// position of coordinate idx in a message with a directory, or -1
+__device__ __forceinline__ int64_t msg_find_dir(const DevCtx& c, const MsgView& v, const uint32_t* dir, uint32_t idx) {
+  if (v.nnz == c.d) return idx;                          // every coordinate is there (k = d): entry j is coordinate j
+  const uint32_t t = idx >> AGG_DIR_SHIFT;
+  uint32_t lo = dir[t], hi = min(dir[t + 1], v.nnz);
+  while (lo < hi) {
+    const uint32_t mid = lo + ((hi - lo) >> 1);
+    const uint32_t x = msg_index(c, v, mid);
+    if (x == idx) return mid;
+    if (x < idx) lo = mid + 1; else hi = mid;
+  }
+  return -1;
+}
 
 // Entry j of the q-th listed message is served by 8 threads, which look its coordinate up in the
 // other listed messages (binary search on the packed, ascending indices).  The coordinate is
 // written by the earliest listed message that holds it -- one writer per coordinate, no atomics --
 // and the values are added in list order, so the result does not depend on the schedule.
 __global__ __launch_bounds__(BLOCK) void k_aggregate(DevCtx c, const uint8_t* msg, RowList rows, uint32_t R,
-                                                     float scale, int accumulate, float* out) {
+                                                     float scale, int accumulate, float* out, const uint32_t* dir,
+                                                     uint32_t ndir) {
   __shared__ float s_val[AGG_ENTRIES][65];
   __shared__ unsigned long long s_has[AGG_ENTRIES];
   const uint32_t q = blockIdx.y;
@@ -1444,7 +1488,7 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(DevCtx c, const uint8_t* ms
       for (uint32_t p = sub; p < R; p += 8) {
         if (p == q) { s_val[e][p] = msg_value(c, mine, j, idx); has |= 1ull << p; continue; }
         const MsgView other = view_msg(c, msg, rows.row[p]);
-        const int64_t pos = msg_find(c, other, idx);
+        const int64_t pos = dir ? msg_find_dir(c, other, dir + static_cast<uint64_t>(p) * ndir, idx) : msg_find(c, other, idx);
         if (pos >= 0) { s_val[e][p] = msg_value(c, other, static_cast<uint32_t>(pos), idx); has |= 1ull << p; }
       }
       if (has) atomicOr(&s_has[e], has);
@@ -1493,6 +1537,8 @@ struct qsl_ctx {
   uint32_t last_R;
   uint32_t nsmall;            // segments selected by one block each (k_small)
   uint32_t nnz_hint;          // entries a message is expected to hold at most (sizes the aggregation grid)
+  uint32_t* agg_dir;          // [64][agg_ndir] directories of the listed messages (only if messages are expected to be long)
+  uint32_t agg_ndir;
   uint32_t n_sampled;         // segments whose guess comes from k_sample
   uint32_t nsamp_blocks;      // blocks of the sampling kernel (per worker)
   size_t capacity;
@@ -1701,6 +1747,20 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t o_samps = carve(sizeof(SelInfo) * samps.size());
   const uint64_t o_fast = carve(4ull * std::max<size_t>(1, fast.size()));
   const uint64_t o_small = carve(4ull * std::max<size_t>(1, smalls.size()));
+  std::vector<uint32_t> seg_dir(((d + 1023) >> 10) + 1);
+  for (size_t t = 0, l = 0; t < seg_dir.size(); ++t) {
+    const uint64_t coord = std::min<uint64_t>(static_cast<uint64_t>(t) << 10, d - 1);
+    while (l + 1 < L && ctx->off[l + 1] <= coord) ++l;
+    seg_dir[t] = static_cast<uint32_t>(l);
+  }
+  const uint64_t o_segdir = carve(4ull * seg_dir.size());
+  std::vector<uint32_t> slot_dir(((K + 255) >> 8) + 1);
+  for (size_t b = 0, l = 0; b < slot_dir.size(); ++b) {
+    const uint64_t slot = std::min<uint64_t>(static_cast<uint64_t>(b) << 8, K - 1);
+    while (l + 1 < L && segs[l + 1].koff <= slot) ++l;
+    slot_dir[b] = static_cast<uint32_t>(l);
+  }
+  const uint64_t o_slotdir = carve(4ull * slot_dir.size());
   const uint64_t o_units = carve(sizeof(UnitState) * U);
   const uint64_t o_slots = carve(8ull * std::max<uint64_t>(2, slot_elems) * R);
   const uint64_t o_ovf = carve(8ull * std::max<uint64_t>(1, ovf_entries) * R);
@@ -1714,6 +1774,9 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t o_blk = carve(4ull * QB * R), o_pre = carve(4ull * (QB + 1) * R);
   const uint64_t o_vi = carve(4ull * K * R), o_vc = carve(4ull * K * R);
   const uint64_t o_tmp = carve(4ull * 1024);
+  ctx->agg_ndir = static_cast<uint32_t>(((d + (1u << AGG_DIR_SHIFT) - 1) >> AGG_DIR_SHIFT) + 1);
+  const bool want_dir = ctx->nnz_hint >= AGG_DIR_MIN;
+  const uint64_t o_dir = carve(want_dir ? 4ull * 64 * ctx->agg_ndir : 4);
   if (hipMalloc(&ctx->slab, bytes) != hipSuccess) { delete ctx; return QSL_ERR_DEVICE; }
   char* base = static_cast<char*>(ctx->slab);
   bool ok = hipMemset(base, 0, zero_bytes) == hipSuccess;
@@ -1727,6 +1790,8 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   upload(o_cbs, cbs.data(), sizeof(CbInfo) * NCB);
   upload(o_fast, fast.data(), 4 * fast.size());
   upload(o_small, smalls.data(), 4 * smalls.size());
+  upload(o_segdir, seg_dir.data(), 4 * seg_dir.size());
+  upload(o_slotdir, slot_dir.data(), 4 * slot_dir.size());
   ok = ok && hipHostMalloc(reinterpret_cast<void**>(&ctx->h_status), 64, hipHostMallocDefault) == hipSuccess;
   ok = ok && hipDeviceSynchronize() == hipSuccess;
   if (!ok) { (void)hipFree(ctx->slab); delete ctx; return QSL_ERR_DEVICE; }
@@ -1739,6 +1804,8 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.cbs = reinterpret_cast<const CbInfo*>(base + o_cbs);
   c.fast_segs = reinterpret_cast<const uint32_t*>(base + o_fast);
   c.small_segs = reinterpret_cast<const uint32_t*>(base + o_small);
+  c.seg_dir = reinterpret_cast<const uint32_t*>(base + o_segdir);
+  c.slot_dir = reinterpret_cast<const uint32_t*>(base + o_slotdir);
   ctx->nsmall = static_cast<uint32_t>(smalls.size());
   c.units = reinterpret_cast<UnitState*>(base + o_units);
   c.slots = reinterpret_cast<uint2*>(base + o_slots); c.slot_stride = std::max<uint64_t>(2, slot_elems);
@@ -1755,6 +1822,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.surv_idx = reinterpret_cast<uint32_t*>(base + o_vi); c.surv_code = reinterpret_cast<uint32_t*>(base + o_vc);
   c.status = reinterpret_cast<uint32_t*>(base + o_status);
   ctx->d_nnz_tmp = reinterpret_cast<uint32_t*>(base + o_tmp);
+  ctx->agg_dir = want_dir ? reinterpret_cast<uint32_t*>(base + o_dir) : nullptr;
   c.d = d; c.seed = cfg->seed; c.L = L; c.K = K; c.NWT = NWT; c.NSEL = NSEL; c.NCB = NCB; c.NWC = NWC; c.QB = QB;
   c.nfast = static_cast<uint32_t>(fast.size()); c.s = s; c.w_idx = w_idx; c.w_lev = w_lev; c.w_val = w_val;
   c.sparsifier = cfg->sparsifier; c.quantizer = cfg->quantizer;
@@ -1893,8 +1961,9 @@ extern "C" qsl_status qsl_aggregate(qsl_ctx* ctx, const uint8_t* msg, const uint
   }
   const uint32_t tiles = (c.K + AGG_ENTRIES - 1) / AGG_ENTRIES;
   const uint32_t agg_blocks = std::min(tiles, std::max(16u, (ctx->nnz_hint + AGG_ENTRIES - 1) / AGG_ENTRIES));
-  k_aggregate<<<dim3(agg_blocks, R), BLOCK, 0, ctx->stream>>>(c, msg, rows, R, scale,
-                                                                                        accumulate, out);
+  uint32_t* dir = R > 1 ? ctx->agg_dir : nullptr;
+  if (dir) k_msg_directory<<<dim3(std::min(2048u, (c.K + BLOCK - 1) / BLOCK), R), BLOCK, 0, ctx->stream>>>(c, msg, rows, dir, ctx->agg_ndir);
+  k_aggregate<<<dim3(agg_blocks, R), BLOCK, 0, ctx->stream>>>(c, msg, rows, R, scale, accumulate, out, dir, ctx->agg_ndir);
   QSL_HIP(hipGetLastError());
   return QSL_OK;
 }
