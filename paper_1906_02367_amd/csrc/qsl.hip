@@ -110,6 +110,7 @@ struct DevCtx {
   const SegInfo* segs; const WtInfo* wts; const SelInfo* sels; const SelInfo* samps; const CbInfo* cbs;
   const uint32_t* fast_segs;
   const uint32_t* small_segs;
+  const uint32_t* big_segs; // the segments that are not selected by one block (they use histograms)
   const uint32_t* seg_dir;  // [ceil(d / 1024) + 1]: segment of coordinate t * 1024 (the last entry: L - 1)
   const uint32_t* slot_dir; // [ceil(K / 256) + 1]: segment of slot b * 256 of the selected arrays
   UnitState* units;
@@ -128,7 +129,7 @@ struct DevCtx {
   uint32_t* surv_idx; uint32_t* surv_code;                    // [R][K]
   uint32_t* status;
   uint64_t d, seed;
-  uint32_t L, K, NWT, NSEL, NCB, NWC, QB, nfast, s, w_idx, w_lev, w_val, sparsifier, quantizer, cap_words;
+  uint32_t L, K, NWT, NSEL, NCB, NWC, QB, nfast, nbig, s, w_idx, w_lev, w_val, sparsifier, quantizer, cap_words;
 };
 
 __device__ __forceinline__ uint32_t key_of_value(uint32_t vbits) { return (vbits & 0x7FFFFFFFu) << 1; }
@@ -1312,8 +1313,11 @@ __global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t
   // this is the last kernel of a call: it also returns the shared scratch of this worker to all-zero
   {
     const uint64_t tid = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x, nth = static_cast<uint64_t>(gridDim.x) * BLOCK;
+    // histograms: only the segments that have any (not the one-block ones), and of the third digit only its 256 bins
+    constexpr uint32_t ZW = 2 * HBINS + 256;
     uint32_t* h = c.hist + static_cast<uint64_t>(w) * c.L * 3 * HBINS;
-    for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * 3 * HBINS; i += nth) h[i] = 0;
+    for (uint64_t i = tid; i < static_cast<uint64_t>(c.nbig) * ZW; i += nth)
+      h[static_cast<uint64_t>(c.big_segs[i / ZW]) * 3 * HBINS + i % ZW] = 0;
     uint32_t* ct = c.ctr + static_cast<uint64_t>(w) * c.L * CTR_LINES * PAD;
     for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * CTR_LINES; i += nth) ct[i * PAD] = 0;
     uint64_t* na = c.norm_acc + static_cast<uint64_t>(w) * c.L * ACC_SLOTS;
@@ -1747,6 +1751,9 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t o_samps = carve(sizeof(SelInfo) * samps.size());
   const uint64_t o_fast = carve(4ull * std::max<size_t>(1, fast.size()));
   const uint64_t o_small = carve(4ull * std::max<size_t>(1, smalls.size()));
+  std::vector<uint32_t> bigs;
+  for (uint32_t l = 0; l < L; ++l) if (segs[l].mode != PATH_SMALL) bigs.push_back(l);
+  const uint64_t o_big = carve(4ull * std::max<size_t>(1, bigs.size()));
   std::vector<uint32_t> seg_dir(((d + 1023) >> 10) + 1);
   for (size_t t = 0, l = 0; t < seg_dir.size(); ++t) {
     const uint64_t coord = std::min<uint64_t>(static_cast<uint64_t>(t) << 10, d - 1);
@@ -1790,6 +1797,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   upload(o_cbs, cbs.data(), sizeof(CbInfo) * NCB);
   upload(o_fast, fast.data(), 4 * fast.size());
   upload(o_small, smalls.data(), 4 * smalls.size());
+  upload(o_big, bigs.data(), 4 * bigs.size());
   upload(o_segdir, seg_dir.data(), 4 * seg_dir.size());
   upload(o_slotdir, slot_dir.data(), 4 * slot_dir.size());
   ok = ok && hipHostMalloc(reinterpret_cast<void**>(&ctx->h_status), 64, hipHostMallocDefault) == hipSuccess;
@@ -1804,6 +1812,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.cbs = reinterpret_cast<const CbInfo*>(base + o_cbs);
   c.fast_segs = reinterpret_cast<const uint32_t*>(base + o_fast);
   c.small_segs = reinterpret_cast<const uint32_t*>(base + o_small);
+  c.big_segs = reinterpret_cast<const uint32_t*>(base + o_big); c.nbig = static_cast<uint32_t>(bigs.size());
   c.seg_dir = reinterpret_cast<const uint32_t*>(base + o_segdir);
   c.slot_dir = reinterpret_cast<const uint32_t*>(base + o_slotdir);
   ctx->nsmall = static_cast<uint32_t>(smalls.size());
