@@ -1298,11 +1298,18 @@ __global__ __launch_bounds__(BLOCK) void k_surv_compact(DevCtx c) {
 __device__ __forceinline__ uint32_t gather_word(const uint32_t* arr, uint64_t n, uint32_t width, uint64_t word) {
   if (width == 0) return 0;
   const uint64_t b0 = word * 32;
+  const uint64_t e_end = min(n, (b0 + 31) / width + 1);           // one past the last field that touches the word
   uint32_t out = 0;
-  for (uint64_t e = b0 / width; e < n && e * width < b0 + 32; ++e) {
-    const int64_t sh = static_cast<int64_t>(e * width) - static_cast<int64_t>(b0);
-    const uint32_t f = arr[e];
-    out |= sh >= 0 ? (f << sh) : (f >> (-sh));
+  for (uint64_t e0 = b0 / width; e0 < e_end; e0 += 8) {           // 8 loads in flight (a 1-bit field: 32 per word)
+    uint32_t f[8];
+#pragma unroll
+    for (uint32_t i = 0; i < 8; ++i) f[i] = e0 + i < e_end ? arr[e0 + i] : 0u;
+#pragma unroll
+    for (uint32_t i = 0; i < 8; ++i) {
+      if (e0 + i >= e_end) break;
+      const int64_t sh = static_cast<int64_t>((e0 + i) * width) - static_cast<int64_t>(b0);
+      out |= sh >= 0 ? (f[i] << sh) : (f[i] >> (-sh));
+    }
   }
   return out;
 }
@@ -1318,8 +1325,9 @@ __global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t
     uint32_t* h = c.hist + static_cast<uint64_t>(w) * c.L * 3 * HBINS;
     for (uint64_t i = tid; i < static_cast<uint64_t>(c.nbig) * ZW; i += nth)
       h[static_cast<uint64_t>(c.big_segs[i / ZW]) * 3 * HBINS + i % ZW] = 0;
-    uint32_t* ct = c.ctr + static_cast<uint64_t>(w) * c.L * CTR_LINES * PAD;
-    for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * CTR_LINES; i += nth) ct[i * PAD] = 0;
+    uint32_t* ct = c.ctr + static_cast<uint64_t>(w) * c.L * CTR_LINES * PAD;                 // counters: the guessing segments only
+    for (uint64_t i = tid; i < static_cast<uint64_t>(c.nfast) * CTR_LINES; i += nth)
+      ct[(static_cast<uint64_t>(c.fast_segs[i / CTR_LINES]) * CTR_LINES + i % CTR_LINES) * PAD] = 0;
     uint64_t* na = c.norm_acc + static_cast<uint64_t>(w) * c.L * ACC_SLOTS;
     for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * ACC_SLOTS; i += nth) na[i] = 0;
   }
