@@ -83,7 +83,7 @@ typedef struct {
 
 enum {
   QSL_FLAG_NO_FAST_PATH = 1,  /* never guess a threshold: exact multi-pass selection only (testing, comparison) */
-  QSL_FLAG_NO_SMALL_PATH = 2  /* segments of at most 65,536 coordinates also take the multi-pass kernels
+  QSL_FLAG_NO_SMALL_PATH = 2  /* segments of at most 4096 coordinates also take the multi-pass kernels  
                                  instead of the one-block selection (testing, comparison)               */
 };
 

@@ -11,7 +11,7 @@
 //   k_select<l>  exact radix selection of the k-th largest key (Section 2.2: Top_k / Rand_k), 12+12+8
 //                bits, over the candidates -- or over the whole vector when the guess failed or the
 //                unit is too dense for guessing (the general path; always exact)
-//   k_small      a unit of at most 16 chunks: selection, ordered compaction and norm by one block
+//   k_small      a unit of at most 4 chunks: selection, ordered compaction and norm by one block
 //   k_tile_count / k_tile_write    ordered compaction of the selected coordinates, ties to the lower index
 //                (k_tile_write also accumulates the exact ||v_S||_2^2 or ||v_S||_1: proof of Lemma 1; Lemma 3, m = 1)
 //   k_quantize   QSGD levels (Definition 1, example 1) or signs (Definition 2); error update
@@ -63,7 +63,7 @@ constexpr uint32_t CTR_FAIL = NSUB + 1;    // counter NSUB + 1: set when the ove
 constexpr uint32_t CTR_LINES = NSUB + 2;
 
 enum : uint32_t { PATH_FAST = 0, PATH_GENERAL = 1, PATH_FALLBACK = 2, PATH_SMALL = 3 };
-constexpr uint32_t SMALL_CHUNKS = 16;      // a unit of at most 16 chunks (16,384 coordinates) is selected by one block
+constexpr uint32_t SMALL_CHUNKS = 4;       // a unit of at most 4 chunks (4096 coordinates) is selected by one block
 
 struct SegInfo {
   uint64_t start, size;
@@ -836,30 +836,22 @@ __device__ __forceinline__ void fallback_range(const SegInfo& sg, uint32_t b, ui
 }
 
 // ------------------------------------------------------------------------------------------------
-// small units (at most 16 chunks): the whole selection by one block of 256 threads.  Thread t keeps 16
-// consecutive coordinates of each of up to four tiles of 4096 in registers (Top_k: the bits of v;
-// Rand_k: the random words), the three digit
-// histograms live in LDS, and the block writes the selected coordinates in order together with the
-// digits of their norm -- what k_select<0..2>, k_tile_count and k_tile_write do for a larger unit,
-// without a launch in between.  (One CU retires ~64 lane-operations per cycle, so a block is kept
-// to 16,384 coordinates; and a kernel of many short-lived waves is bound by the rate at which waves
-// start, so the block is kept to four waves.)
+// small units (at most 4 chunks = 4096 coordinates): the whole selection by one block of 256 threads.
+// Thread t keeps 16 consecutive coordinates in registers (Top_k: the bits of v; Rand_k: the random
+// words), the three digit histograms live in LDS, and the block writes the selected coordinates in order
+// together with the digits of their norm -- what k_select<0..2>, k_tile_count and k_tile_write do for a
+// larger unit, without a launch in between.  (One CU retires ~64 lane-operations per cycle: a block
+// needed 25 us for 16,384 coordinates and 50 us for 65,536, and the slowest block is the kernel's time,
+// so the limit is low; segments above it take the guessing path, whose kernels run anyway.)
 // ------------------------------------------------------------------------------------------------
-constexpr uint32_t SMALL_TILE = BLOCK * 16;       // 4096 coordinates: 16 consecutive ones per thread
-
 template <int LEVEL, int SPARS>
-__device__ __forceinline__ void small_hist(const uint32_t (&kv)[4][16], uint32_t M, uint32_t n, uint32_t prefix,
-                                           uint32_t* lh) {
+__device__ __forceinline__ void small_hist(const uint32_t (&kv)[16], uint32_t n, uint32_t prefix, uint32_t* lh) {
+  const uint32_t e0 = threadIdx.x * 16;
 #pragma unroll
-  for (uint32_t i = 0; i < 4; ++i) {
-    if (i >= M) break;                                               // uniform over the block
-    const uint32_t e0 = (i * BLOCK + threadIdx.x) * 16;
-#pragma unroll
-    for (uint32_t j = 0; j < 16; ++j) {
-      const uint32_t key = SPARS == QSL_TOPK ? key_of_value(kv[i][j]) : kv[i][j];
-      uint32_t bin;
-      if (e0 + j < n && level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
-    }
+  for (uint32_t j = 0; j < 16; ++j) {
+    const uint32_t key = SPARS == QSL_TOPK ? key_of_value(kv[j]) : kv[j];
+    uint32_t bin;
+    if (e0 + j < n && level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
   }
 }
 
@@ -875,29 +867,26 @@ __global__ __launch_bounds__(BLOCK) void k_small(DevCtx c, const float* v, uint3
   const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const uint32_t n = static_cast<uint32_t>(sg.size);                 // <= SMALL_CHUNKS * CHUNK = 4 * SMALL_TILE
-  const uint32_t M = (n + SMALL_TILE - 1) / SMALL_TILE;              // 1 .. 4 tiles
-  uint32_t kv[4][16];
+  const uint32_t n = static_cast<uint32_t>(sg.size);                 // <= SMALL_CHUNKS * CHUNK = 16 * BLOCK
+  const uint32_t e0 = threadIdx.x * 16;
+  uint32_t kv[16];
 #pragma unroll
-  for (uint32_t i = 0; i < 4; ++i) {
+  for (uint32_t q = 0; q < 4; ++q) {
+    const uint32_t e = e0 + q * 4;
+    if (SPARS == QSL_TOPK) {
+      f4u x = {0.f, 0.f, 0.f, 0.f};
+      if (e + 4 <= n) x = *reinterpret_cast<const f4u*>(vp + e);
+      else {
 #pragma unroll
-    for (uint32_t q = 0; q < 4; ++q) {
-      const uint32_t e = (i * BLOCK + threadIdx.x) * 16 + q * 4;
-      if (SPARS == QSL_TOPK) {
-        f4u x = {0.f, 0.f, 0.f, 0.f};
-        if (e + 4 <= n) x = *reinterpret_cast<const f4u*>(vp + e);
-        else {
-#pragma unroll
-          for (uint32_t j = 0; j < 4; ++j) if (e + j < n) x[j] = vp[e + j];
-        }
-#pragma unroll
-        for (uint32_t j = 0; j < 4; ++j) kv[i][q * 4 + j] = __float_as_uint(x[j]);
-      } else {
-        Words4 rw = {{0u, 0u, 0u, 0u}};
-        if (e < n) rw = rand_words4(rk, static_cast<uint32_t>(sg.start) + e);
-#pragma unroll
-        for (uint32_t j = 0; j < 4; ++j) kv[i][q * 4 + j] = rw.w[j];
+        for (uint32_t j = 0; j < 4; ++j) if (e + j < n) x[j] = vp[e + j];
       }
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) kv[q * 4 + j] = __float_as_uint(x[j]);
+    } else {
+      Words4 rw = {{0u, 0u, 0u, 0u}};
+      if (e < n) rw = rand_words4(rk, static_cast<uint32_t>(sg.start) + e);
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) kv[q * 4 + j] = rw.w[j];
     }
   }
   for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;
@@ -906,58 +895,51 @@ __global__ __launch_bounds__(BLOCK) void k_small(DevCtx c, const float* v, uint3
   uint32_t above;
   for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK) lh[i] = 0;
   __syncthreads();
-  small_hist<0, SPARS>(kv, M, n, 0, lh);
+  small_hist<0, SPARS>(kv, n, 0, lh);
   __syncthreads();
   uint32_t bin = find_from_top<BLOCK>(lh, sg.k, &above, scratch, result, true);
   uint32_t prefix = bin << 20, k_rem = sg.k - above;
-  small_hist<1, SPARS>(kv, M, n, prefix, lh);
+  small_hist<1, SPARS>(kv, n, prefix, lh);
   __syncthreads();
   bin = find_from_top<BLOCK>(lh, k_rem, &above, scratch, result, true);
   prefix |= bin << 8; k_rem -= above;
-  small_hist<2, SPARS>(kv, M, n, prefix, lh);
+  small_hist<2, SPARS>(kv, n, prefix, lh);
   __syncthreads();
   bin = find_from_top<BLOCK, 256>(lh, k_rem, &above, scratch, result, false);
   const uint32_t tau = prefix | bin, need = k_rem - above;
 
   // ordered compaction: key > tau, and the first `need` coordinates with key == tau
+  uint32_t gm = 0, qm = 0;
+#pragma unroll
+  for (uint32_t j = 0; j < 16; ++j) {
+    const uint32_t key = SPARS == QSL_TOPK ? key_of_value(kv[j]) : kv[j];
+    const bool inside = e0 + j < n;
+    gm |= (inside && key > tau ? 1u : 0u) << j;
+    qm |= (inside && key == tau ? 1u : 0u) << j;
+  }
+  uint64_t total;
+  const uint64_t ex = block_exclusive_scan64((static_cast<uint64_t>(__popc(qm)) << 32) | __popc(gm), scratch, &total);
+  const uint32_t gt0 = static_cast<uint32_t>(ex), eq0 = static_cast<uint32_t>(ex >> 32);
+  // which of this thread's ties are kept: the first need - eq0 of them
+  uint32_t keep = 0;
+  if (eq0 < need) {
+    keep = qm;
+    for (uint32_t extra = eq0 + __popc(qm); extra > need; --extra) keep &= ~(0x80000000u >> __clz(keep));   // drop the last
+  }
+  const uint32_t sel = gm | keep;
   uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
   uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
   uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
   const bool squares = wants_squares(c.quantizer);
-  uint32_t run_gt = 0, run_eq = 0;
 #pragma unroll
-  for (uint32_t i = 0; i < 4; ++i) {
-    if (i >= M) break;                                               // uniform over the block
-    const uint32_t e0 = (i * BLOCK + threadIdx.x) * 16;
-    uint32_t gm = 0, qm = 0;
-#pragma unroll
-    for (uint32_t j = 0; j < 16; ++j) {
-      const uint32_t key = SPARS == QSL_TOPK ? key_of_value(kv[i][j]) : kv[i][j];
-      const bool inside = e0 + j < n;
-      gm |= (inside && key > tau ? 1u : 0u) << j;
-      qm |= (inside && key == tau ? 1u : 0u) << j;
+  for (uint32_t j = 0; j < 16; ++j) {
+    if ((sel >> j) & 1u) {
+      const uint32_t below = (1u << j) - 1u;
+      const uint32_t pos = gt0 + __popc(gm & below) + min(eq0 + __popc(qm & below), need);
+      const uint32_t bits = SPARS == QSL_TOPK ? kv[j] : __float_as_uint(vp[e0 + j]);
+      oi[pos] = static_cast<uint32_t>(sg.start) + e0 + j; ov[pos] = bits;
+      add_digits(mine, bits, squares);
     }
-    uint64_t total;
-    const uint64_t ex = block_exclusive_scan64((static_cast<uint64_t>(__popc(qm)) << 32) | __popc(gm), scratch, &total);
-    const uint32_t gt0 = run_gt + static_cast<uint32_t>(ex), eq0 = run_eq + static_cast<uint32_t>(ex >> 32);
-    // which of this thread's ties are kept: the first need - eq0 of them
-    uint32_t keep = 0;
-    if (eq0 < need) {
-      keep = qm;
-      for (uint32_t extra = eq0 + __popc(qm); extra > need; --extra) keep &= ~(0x80000000u >> __clz(keep));   // drop the last
-    }
-    const uint32_t sel = gm | keep;
-#pragma unroll
-    for (uint32_t j = 0; j < 16; ++j) {
-      if ((sel >> j) & 1u) {
-        const uint32_t below = (1u << j) - 1u;
-        const uint32_t pos = gt0 + __popc(gm & below) + min(eq0 + __popc(qm & below), need);
-        const uint32_t bits = SPARS == QSL_TOPK ? kv[i][j] : __float_as_uint(vp[e0 + j]);
-        oi[pos] = static_cast<uint32_t>(sg.start) + e0 + j; ov[pos] = bits;
-        add_digits(mine, bits, squares);
-      }
-    }
-    run_gt += static_cast<uint32_t>(total); run_eq += static_cast<uint32_t>(total >> 32);
   }
   __syncthreads();
   // the unit is this block's alone: its norm digits are stored, not added

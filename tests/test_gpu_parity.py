@@ -136,20 +136,19 @@ def _adversarial(d, rng):
 
 @pytest.mark.parametrize("flags,path", [(0, 3), (2, 1)])      # one-block selection / multi-pass kernels
 @pytest.mark.parametrize("quantizer,s", [(W.QSGD, 16), (W.SIGN_L1, 1)])
-@pytest.mark.parametrize("k", [1, 37, 12_011])
+@pytest.mark.parametrize("k", [1, 37, 4_001])
 def test_degenerate_inputs(P, quantizer, s, k, flags, path):
-    d = 12_011
+    d = 4_001
     rng = np.random.default_rng(17)
     wl = custom(d, [0, d], [k], s, W.TOPK, quantizer, R=1)
     for name, v in _adversarial(d, rng):
         P.run_parity(wl, 1, deltas=[v[None, :].copy()], flags=flags, expect_path=path)
 
 
-@pytest.mark.parametrize("k", [1, 37, 600])
-def test_degenerate_inputs_whole_unit_guess(P, k):
-    # 17 .. 255 chunks: the guess comes from a histogram of the whole unit; inputs with few distinct
+@pytest.mark.parametrize("d,k", [(40_009, 1), (40_009, 37), (40_009, 600), (12_011, 1), (12_011, 37), (12_011, 180)])
+def test_degenerate_inputs_whole_unit_guess(P, k, d):
+    # 5 .. 255 chunks: the guess comes from a histogram of the whole unit; inputs with few distinct
     # magnitudes put everything into one bin, overflow the candidate list and must fall back
-    d = 40_009
     rng = np.random.default_rng(23)
     wl = custom(d, [0, d], [k], 16, W.TOPK, W.QSGD, R=1)
     seen = set()
@@ -159,12 +158,13 @@ def test_degenerate_inputs_whole_unit_guess(P, k):
     assert seen == {0, 2}, seen
 
 
-# sizes around the limit of the one-block selection (16,384 coordinates) and of its 16-per-thread layout
+# sizes around the limit of the one-block selection (4096 coordinates) and of its 16-per-thread layout
 @pytest.mark.parametrize("sparsifier", [W.TOPK, W.RANDK])
-@pytest.mark.parametrize("d,k", [(16_384, 100), (16_385, 16_385), (16_385, 3), (16_383, 16_383), (8_209, 4_000),
-                                 (32_769, 1), (65_537, 655), (17, 16), (1_025, 1_024), (262_143, 250)])
+@pytest.mark.parametrize("d,k", [(4_096, 100), (4_096, 4_096), (4_097, 4_097), (4_097, 3), (4_095, 4_095), (2_063, 1_000),
+                                 (16_385, 16_385), (8_209, 4_000), (32_769, 1), (65_537, 655), (17, 16), (15, 15),
+                                 (1_025, 1_024), (262_143, 250)])
 def test_small_units_one_block_boundaries(P, sparsifier, d, k):
-    small = d <= 16_384
+    small = d <= 4_096
     wl = custom(d, [0, d], [k], 7, sparsifier, W.QSGD, R=2)
     P.run_parity(wl, 2, expect_path=3 if small else None)
     wl = custom(d, [0, d], [k], 1, sparsifier, W.SIGN_L1, R=2)
