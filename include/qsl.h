@@ -142,6 +142,16 @@ qsl_status qsl_aggregate(qsl_ctx *ctx, const uint8_t *msg, const uint32_t *worke
  * from the message headers.  Synchronises the stream.  bits_host: host uint64 [R].  */
 qsl_status qsl_bits_sent(qsl_ctx *ctx, const uint8_t *msg, uint32_t R, uint64_t *bits_host);
 
+/* Accounting variant for Rand_k: the bits of one message if the indices are not transmitted.  Rand_k
+ * (Section 2.2) chooses its k-subset independently of the data, so a receiver that shares the seed and
+ * knows the worker and the round can regenerate it; the message then carries, per segment, the fp32
+ * scale, and per selected coordinate one fixed-width code: QSGD the level 0..s and a sign bit (level 0
+ * must now be written, the position is no longer free to drop), Sign one bit, no quantiser 32 bits.
+ * Needs no context and no GPU.  QSL_ERR_UNSUPPORTED for Top_k (its support depends on the data).
+ * The library does not emit this format; the count is for the communication axis of the paper's plots.
+ *   cfg host; bits host, receives the count */
+qsl_status qsl_bits_index_free(const qsl_config *cfg, uint64_t *bits);
+
 /* Synchronise the stream and return QSL_ERR_NONFINITE_INPUT if any compress call since the last
  * query met a NaN or Inf in m + delta (its outputs are then unspecified), QSL_ERR_DEVICE on a HIP
  * error or if a kernel met a malformed message (an index >= d; the entry is skipped), else QSL_OK.

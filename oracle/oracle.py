@@ -138,6 +138,24 @@ class OracleOp:
         xhat_half = np.ascontiguousarray(xhat_half, dtype=np.float32)
         return self.compress(m, np.subtract(x, xhat_half, dtype=np.float32), worker, rnd)
 
+    def bits_index_free(self):
+        """Accounting variant for Rand_k (Section 2.2: the k-subset does not depend on the data, so common
+        randomness lets the receiver rebuild it): a message without indices holds one fp32 scale per segment
+        and, for each of the K chosen coordinates, one code -- written out as a sum over the coordinates."""
+        if self.sparsifier != RANDK:
+            raise ValueError("only Rand_k can drop its indices")
+        bits = 0
+        for _segment in range(self.L):
+            bits += 32                                   # the scale
+        for _coordinate in range(self.K):
+            if self.quantizer == FP32:
+                bits += 32
+            elif self.quantizer in (SIGN_L1, SIGN_L2):
+                bits += 1
+            else:
+                bits += len(format(self.s, "b")) + 1     # a level in 0..s, then the sign
+        return bits
+
     def bits_sent(self, msg):
         msg = np.ascontiguousarray(msg, dtype=np.uint8)
         return int(lib().qslo_bits_sent(_p(msg, C.c_uint8), *self._lay))

@@ -54,13 +54,15 @@ def _load():
     lib.qsl_debug_units.argtypes = [vp, C.POINTER(u32), u32, C.POINTER(u32)]; lib.qsl_debug_units.restype = C.c_int
     lib.qsl_timing_enable.argtypes = [vp, C.c_int]; lib.qsl_timing_enable.restype = C.c_int
     lib.qsl_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u32)]; lib.qsl_timing_read.restype = C.c_int
+    lib.qsl_bits_index_free.argtypes = [C.POINTER(_Config), C.POINTER(u64)]; lib.qsl_bits_index_free.restype = C.c_int
     return lib
 
 
 _lib = _load()
 
 EXPORTED = ["qsl_create", "qsl_destroy", "qsl_set_stream", "qsl_msg_capacity_bytes", "qsl_compress",
-            "qsl_compress_diff", "qsl_error_update", "qsl_aggregate", "qsl_bits_sent", "qsl_device_status", "qsl_debug_units",
+            "qsl_compress_diff", "qsl_error_update", "qsl_aggregate", "qsl_bits_sent", "qsl_bits_index_free",
+            "qsl_device_status", "qsl_debug_units",
             "qsl_timing_enable", "qsl_timing_read", "qsl_status_string"]
 
 
@@ -79,6 +81,17 @@ def _ptr(t, dtype=None, allow_none=False):
     if dtype is not None and t.dtype != dtype:
         raise ValueError(f"expected dtype {dtype}, got {t.dtype}")
     return t.data_ptr()
+
+
+def bits_index_free(d, seg_offset, seg_k, s, sparsifier, quantizer):
+    """`qsl_bits_index_free`: bits of one Rand_k message without its indices (host only, no GPU needed)."""
+    off = np.ascontiguousarray(seg_offset, dtype=np.uint64)
+    k = np.ascontiguousarray(seg_k, dtype=np.uint32)
+    cfg = _Config(int(d), int(k.size), off.ctypes.data_as(C.POINTER(C.c_uint64)), k.ctypes.data_as(C.POINTER(C.c_uint32)),
+                  int(s), int(sparsifier), int(quantizer), 0, 1, 0)
+    bits = C.c_uint64(0)
+    _check(_lib.qsl_bits_index_free(C.byref(cfg), C.byref(bits)), "qsl_bits_index_free")
+    return int(bits.value)
 
 
 class Qsl:

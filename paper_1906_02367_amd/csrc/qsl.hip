@@ -1562,14 +1562,14 @@ extern "C" const char* qsl_status_string(qsl_status st) {
   return "unknown";
 }
 
-extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip_stream) {
-  if (!out || !cfg || !cfg->seg_offset || !cfg->seg_k) return QSL_ERR_INVALID_ARG;
+// argument checks of an operator description; *K_out = sum of the k_l
+static qsl_status check_config(const qsl_config* cfg, uint64_t* K_out) {
+  if (!cfg || !cfg->seg_offset || !cfg->seg_k) return QSL_ERR_INVALID_ARG;
   const uint64_t d = cfg->d;
   const uint32_t L = cfg->num_segments;
   if (d == 0 || d >= (1ull << 32) || L == 0 || L > 16384) return QSL_ERR_INVALID_ARG;
   if (cfg->sparsifier > 1 || cfg->quantizer > 4) return QSL_ERR_INVALID_ARG;
   if (is_qsgd(cfg->quantizer) && (cfg->s == 0 || cfg->s > 32768)) return QSL_ERR_INVALID_ARG;
-  if (cfg->max_workers == 0 || cfg->max_workers > 1024) return QSL_ERR_INVALID_ARG;
   if (cfg->seg_offset[0] != 0 || cfg->seg_offset[L] != d) return QSL_ERR_INVALID_ARG;
   uint64_t K64 = 0;
   for (uint32_t l = 0; l < L; ++l) {
@@ -1579,6 +1579,29 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
     K64 += cfg->seg_k[l];
   }
   if (K64 >= (1ull << 32)) return QSL_ERR_INVALID_ARG;
+  *K_out = K64;
+  return QSL_OK;
+}
+
+extern "C" qsl_status qsl_bits_index_free(const qsl_config* cfg, uint64_t* bits) {
+  uint64_t K = 0;
+  if (!bits) return QSL_ERR_INVALID_ARG;
+  const qsl_status st = check_config(cfg, &K);
+  if (st != QSL_OK) return st;
+  if (cfg->sparsifier != QSL_RANDK) return QSL_ERR_UNSUPPORTED;      // Top_k's support depends on the data
+  const uint64_t w = cfg->quantizer == QSL_FP32 ? 32 : is_qsgd(cfg->quantizer) ? bit_width_u64(cfg->s) + 1 : 1;
+  *bits = 32ull * cfg->num_segments + K * w;
+  return QSL_OK;
+}
+
+extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip_stream) {
+  uint64_t K64 = 0;
+  if (!out) return QSL_ERR_INVALID_ARG;
+  const qsl_status cfg_status = check_config(cfg, &K64);
+  if (cfg_status != QSL_OK) return cfg_status;
+  if (cfg->max_workers == 0 || cfg->max_workers > 1024) return QSL_ERR_INVALID_ARG;
+  const uint64_t d = cfg->d;
+  const uint32_t L = cfg->num_segments;
 
   qsl_ctx* ctx = new (std::nothrow) qsl_ctx();
   if (!ctx) return QSL_ERR_DEVICE;

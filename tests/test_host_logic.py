@@ -78,6 +78,30 @@ def test_invalid_configurations_are_rejected_before_any_gpu_work(lib, kwargs):
     assert not ctx.value
 
 
+@pytest.mark.parametrize("qz,s", [(0, 1), (0, 2), (0, 3), (0, 15), (0, 16), (0, 255), (0, 256), (1, 1), (2, 1), (3, 1), (4, 7)])
+def test_index_free_bit_count_of_rand_k(lib, qz, s):
+    """Host-only entry point against the oracle's count, and against a message the oracle builds: for the
+    quantisers that send all k coordinates, dropping the nnz word and the index field of the transmitted
+    format must leave exactly the index-free count."""
+    from oracle import oracle as O
+    lib.qsl_bits_index_free.argtypes = [C.POINTER(Config), C.POINTER(C.c_uint64)]
+    lib.qsl_bits_index_free.restype = C.c_int
+    d, off, k = 5_000, [0, 100, 1_124, 5_000], [7, 100, 1]
+    bits = C.c_uint64(0)
+    cfg = make_cfg(d, off, k, s=s, sp=1, qz=qz)
+    assert lib.qsl_bits_index_free(C.byref(cfg), C.byref(bits)) == 0
+    op = O.OracleOp(d, off, k, s, O.RANDK, qz, 1)
+    assert bits.value == op.bits_index_free()
+    if qz in (1, 2, 3):
+        v = np.random.default_rng(3).standard_normal(d).astype(np.float32)
+        out = op.compress(np.zeros(d, np.float32), v, 0, 0)
+        w_idx = 13                                                          # bits of d - 1 = 4999
+        assert op.bits_sent(out["msg"]) - 32 - sum(k) * w_idx == bits.value
+    cfg = make_cfg(d, off, k, s=s, sp=0, qz=qz)
+    assert lib.qsl_bits_index_free(C.byref(cfg), C.byref(bits)) == 5        # QSL_ERR_UNSUPPORTED for Top_k
+    assert lib.qsl_bits_index_free(None, C.byref(bits)) == 1
+
+
 def test_null_arguments_and_status_strings(lib):
     lib.qsl_status_string.argtypes = [C.c_int]
     lib.qsl_status_string.restype = C.c_char_p
