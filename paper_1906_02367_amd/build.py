@@ -8,7 +8,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(_HERE)
 LIB_PATH = os.path.join(_HERE, "libqsl.so")
 SOURCES = [os.path.join(_HERE, "csrc", "qsl.hip")]
-HEADERS = [os.path.join(_HERE, "csrc", "qsl_device.h"), os.path.join(ROOT, "include", "qsl.h")]
+HEADERS = [os.path.join(_HERE, "csrc", h) for h in ("qsl_device.h", "qsl_layout.h", "qsl_stream.h", "qsl_select.h",
+                                                    "qsl_encode.h", "qsl_decode.h")] + [os.path.join(ROOT, "include", "qsl.h")]
 
 HIPCC_FLAGS = [
     "-O3", "--offload-arch=gfx950", "-std=c++17",

@@ -1,0 +1,269 @@
+// qsl_encode.h -- From the selected coordinates to the packed message: the fp32 scale from the exact norm digits,
+// k_quantize (QSGD levels / signs, error update on the transmitted coordinates), k_surv_scan,
+// k_surv_compact, k_pack.
+// Part of the single translation unit qsl.hip (included there, in this order: layout, stream, select,
+// encode, decode); not a public header.
+#pragma once
+
+#include "qsl_device.h"
+#include "qsl_layout.h"
+
+namespace {
+
+// digits -> one correctly rounded double -> the fp32 scale of the unit.  Called by all 64 lanes of a
+// wave with the same arguments; lane i holds digit counter i, everything else is shuffles and ballots
+// (a per-thread digit array would live in scratch memory and cost microseconds).
+__device__ float finalize_scale(const uint64_t* acc, uint32_t quantizer, uint32_t k) {
+  const bool squares = wants_squares(quantizer);
+  const uint32_t lane = lane_id();
+  const uint64_t a = lane < ACC_SLOTS ? acc[lane] : 0;
+  // 32-bit digits: low half of the own counter plus the high half of the one below, then ripple the carries
+  auto from_below = [&](uint32_t x) { const uint32_t y = __shfl_up(x, 1, WAVE); return lane ? y : 0u; };
+  uint64_t t = (a & 0xFFFFFFFFull) + from_below(static_cast<uint32_t>(a >> 32));
+  for (uint32_t it = 0; it < WAVE; ++it) {                            // ends after a few rounds; bounded anyway
+    const uint32_t carry = static_cast<uint32_t>(t >> 32);
+    if (__ballot(carry != 0) == 0) break;
+    t = (t & 0xFFFFFFFFull) + from_below(carry);
+  }
+  const uint32_t dig = static_cast<uint32_t>(t);                      // digit `lane` of the exact sum
+  const uint64_t nz = __ballot(dig != 0);
+  double S = 0.0;
+  if (nz != 0) {
+    const int tw = 63 - __clzll(static_cast<long long>(nz));
+    const int top = tw * 32 + 31 - __clz(static_cast<int>(__shfl(dig, tw, WAVE)));
+    const int low = top - 52;                       // position of the last kept bit
+    uint64_t mant; int e2;
+    if (low <= 0) {
+      mant = (static_cast<uint64_t>(__shfl(dig, 1, WAVE)) << 32) | __shfl(dig, 0, WAVE); e2 = 0;   // the whole value, exact
+    } else {
+      const int wq = low >> 5, r = low & 31;
+      const uint64_t lo64 = (static_cast<uint64_t>(__shfl(dig, wq + 1, WAVE)) << 32) | __shfl(dig, wq, WAVE);
+      const uint64_t hi32 = __shfl(dig, wq + 2, WAVE);                // lanes above the top digit hold 0
+      uint64_t win = lo64 >> r;
+      if (r) win |= hi32 << (64 - r);
+      mant = win & ((1ull << 53) - 1);
+      const int g = low - 1, gq = g >> 5, gb = g & 31;
+      const uint32_t dg = __shfl(dig, gq, WAVE);
+      const uint32_t guard = (dg >> gb) & 1u;
+      const bool sticky = (dg & ((1u << gb) - 1u)) != 0 || __ballot(dig != 0 && lane < static_cast<uint32_t>(gq)) != 0;
+      if (guard && (sticky || (mant & 1u))) mant += 1;
+      e2 = low;
+    }
+    S = ldexp(static_cast<double>(mant), e2 + (squares ? -298 : -149));
+  }
+  if (quantizer == QSL_SIGN_L1) return static_cast<float>(S / static_cast<double>(k));           // ||v_S||_1 / k
+  if (quantizer == QSL_SIGN_L2) return static_cast<float>(sqrt(S) / static_cast<double>(k));     // ||v_S||_2 / k
+  if (quantizer == QSL_FP32) return 0.0f;
+  return static_cast<float>(sqrt(S));                                                            // ||v_S||_2
+}
+
+// ------------------------------------------------------------------------------------------------
+// quantise, error update, message
+// ------------------------------------------------------------------------------------------------
+// segment owning slot j of [K]: slot_dir[b] is the segment of slot b * 256 (same idea as seg_dir below)
+__device__ __forceinline__ uint32_t seg_of_slot(const DevCtx& c, uint32_t j) {
+  const uint32_t b = j >> 8;
+  uint32_t lo = c.slot_dir[b], hi = c.slot_dir[b + 1] + 1;
+  while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (c.segs[mid].koff <= j) lo = mid; else hi = mid; }
+  return lo;
+}
+// segment of coordinate i: seg_dir[t] is the segment of coordinate t * 1024, so the search is over the few
+// segments that touch one 1024-block instead of all L
+__device__ __forceinline__ uint32_t seg_of_coord(const DevCtx& c, uint32_t i) {
+  const uint32_t t = i >> 10;
+  uint32_t lo = c.seg_dir[t], hi = c.seg_dir[t + 1] + 1;       // segs[lo].start <= i < segs[hi].start (or hi = L)
+  while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (c.segs[mid].start <= i) lo = mid; else hi = mid; }
+  return lo;
+}
+
+__device__ __forceinline__ float qsgd_value(float N, uint32_t level, uint32_t s, bool neg) {
+  const float prod = N * static_cast<float>(level);
+  const float mag = prod / static_cast<float>(s);
+  return neg ? -mag : mag;
+}
+
+__global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint32_t worker0, uint64_t round,
+                                                    uint32_t* dbg_idx, uint16_t* dbg_level) {
+  __shared__ uint32_t s_w[BLOCK / 64];
+  __shared__ float s_scale[BLOCK], s_sent[BLOCK];
+  const uint32_t w = blockIdx.y;
+  const uint32_t j = blockIdx.x * BLOCK + threadIdx.x;
+  // the scales of the units this block's slots belong to (at most one unit per slot)
+  const uint32_t j_first = blockIdx.x * BLOCK, j_last = min(j_first + BLOCK, c.K) - 1;
+  const uint32_t seg_first = c.L == 1 ? 0u : seg_of_slot(c, j_first);
+  const uint32_t seg_last = c.L == 1 ? 0u : seg_of_slot(c, j_last);
+  for (uint32_t i = threadIdx.x >> 6; i <= seg_last - seg_first; i += BLOCK / 64) {     // a wave per unit
+    const uint32_t seg = seg_first + i;
+    const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
+    const uint32_t kl = c.segs[seg].k;
+    const float sc = finalize_scale(c.norm_acc + u * ACC_SLOTS, c.quantizer, kl);
+    if (lane_id() == 0) {
+      s_scale[i] = sc;
+      // what the message carries: the scale itself, or N / (1 + beta_{k,s}) for the scaled composition (Lemma 2)
+      float sent = sc;
+      if (c.quantizer == QSL_QSGD_SCALED) {
+        const double beta = fmin(static_cast<double>(kl) / (static_cast<double>(c.s) * c.s), sqrt(static_cast<double>(kl)) / c.s);
+        sent = sc / static_cast<float>(1.0 + beta);
+      }
+      s_sent[i] = sent;
+      if (c.segs[seg].koff >= j_first) c.units[u].scale_bits = __float_as_uint(sent);   // the block holding the unit's first slot
+    }
+  }
+  __syncthreads();
+  uint32_t sent = 0;
+  if (j < c.K) {
+    const uint32_t seg = c.L == 1 ? 0u : seg_of_slot(c, j);
+    const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
+    const uint64_t slot = static_cast<uint64_t>(w) * c.K + j;
+    const uint32_t idx = c.sel_idx[slot], bits = c.sel_val[slot];
+    const float scale = s_scale[seg - seg_first];
+    const float v = __uint_as_float(bits);
+    const bool neg = v < 0.0f;
+    uint32_t level;
+    float g;
+    if (is_qsgd(c.quantizer)) {
+      level = 0;
+      if (scale > 0.0f) {
+        const float a = fabsf(v) / scale;
+        float t = a * static_cast<float>(c.s);
+        if (t > static_cast<float>(c.s)) t = static_cast<float>(c.s);
+        const float fl = floorf(t);
+        const float frac = t - fl;
+        const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 1);
+        const float r01 = static_cast<float>(rand_word(rk, idx) >> 8) * 0x1p-24f;
+        level = static_cast<uint32_t>(fl) + (r01 < frac ? 1u : 0u);
+      }
+      g = qsgd_value(s_sent[seg - seg_first], level, c.s, neg);
+    } else if (c.quantizer == QSL_FP32) {
+      level = 1;
+      g = v;
+    } else {
+      level = 1;
+      g = neg ? -scale : scale;
+    }
+    sent = level != 0;
+    c.sel_code[slot] = level | (neg ? 0x80000000u : 0u);
+    if (sent) {
+      if (idx < c.d) m_out[static_cast<uint64_t>(w) * c.d + idx] = v - g;
+      else atomicOr(c.status, 2u);                       // cannot happen: a selected slot was never written
+      if (is_qsgd(c.quantizer) && c.L > 1) atomicAdd(&c.units[u].nnz, 1u);
+    }
+    if (dbg_idx) dbg_idx[slot] = idx;
+    if (dbg_level) dbg_level[slot] = static_cast<uint16_t>(level);
+  }
+  const uint32_t wc = __popcll(__ballot(sent));
+  if (lane_id() == 0) s_w[threadIdx.x >> 6] = wc;
+  __syncthreads();
+  uint32_t* cnt = c.blk_cnt + static_cast<uint64_t>(w) * c.QB;
+  if (threadIdx.x == 0) cnt[blockIdx.x] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+}
+
+// sum of cnt[0 .. n), by the whole block
+__device__ __forceinline__ uint32_t block_sum_u32(const uint32_t* cnt, uint32_t n, uint32_t* s_part) {
+  uint32_t x = 0;
+  for (uint32_t i = threadIdx.x; i < n; i += BLOCK) x += cnt[i];
+  x = wave_sum(x);
+  __syncthreads();
+  if (lane_id() == 0) s_part[threadIdx.x >> 6] = x;
+  __syncthreads();
+  return s_part[0] + s_part[1] + s_part[2] + s_part[3];
+}
+
+// only for very large K: exclusive prefix (and total) of the per-block survivor counts, one block per worker
+__global__ __launch_bounds__(1024) void k_surv_scan(DevCtx c) {
+  __shared__ uint64_t scratch[17];
+  const uint32_t* cnt = c.blk_cnt + static_cast<uint64_t>(blockIdx.x) * c.QB;
+  uint32_t* pre = c.blk_pre + static_cast<uint64_t>(blockIdx.x) * (c.QB + 1);
+  uint64_t carry = 0;
+  for (uint32_t base = 0; base < c.QB; base += 1024) {
+    const uint32_t i = base + threadIdx.x;
+    const uint64_t x = i < c.QB ? cnt[i] : 0;
+    uint64_t total;
+    const uint64_t ex = block_exclusive_scan64(x, scratch, &total) + carry;
+    if (i < c.QB) pre[i] = static_cast<uint32_t>(ex);
+    carry += total;
+  }
+  if (threadIdx.x == 0) pre[c.QB] = static_cast<uint32_t>(carry);
+}
+
+__global__ __launch_bounds__(BLOCK) void k_surv_compact(DevCtx c) {
+  __shared__ uint32_t s_w[BLOCK / 64], s_part[4];
+  const uint32_t w = blockIdx.y;
+  const uint32_t j = blockIdx.x * BLOCK + threadIdx.x;
+  // survivors before this block: the sum of the earlier blocks' counts
+  const uint32_t before = c.QB > MAX_QB_INLINE
+                              ? c.blk_pre[static_cast<uint64_t>(w) * (c.QB + 1) + blockIdx.x]
+                              : block_sum_u32(c.blk_cnt + static_cast<uint64_t>(w) * c.QB, blockIdx.x, s_part);
+  uint32_t code = 0;
+  const uint64_t slot = static_cast<uint64_t>(w) * c.K + j;
+  if (j < c.K) code = c.sel_code[slot];
+  const bool sent = (code & 0x7FFFFFFFu) != 0;
+  const uint64_t bal = __ballot(sent);
+  if (lane_id() == 0) s_w[threadIdx.x >> 6] = __popcll(bal);
+  __syncthreads();
+  uint32_t pos = before + popc_below(bal);
+  for (uint32_t i = 0; i < (threadIdx.x >> 6); ++i) pos += s_w[i];
+  if (sent) {
+    const uint32_t level = code & 0x7FFFFFFFu, neg = code >> 31;
+    c.surv_idx[static_cast<uint64_t>(w) * c.K + pos] = c.sel_idx[slot];
+    c.surv_code[static_cast<uint64_t>(w) * c.K + pos] = is_qsgd(c.quantizer) ? ((level - 1u) | (neg << c.w_lev))
+                                                        : c.quantizer == QSL_FP32 ? c.sel_val[slot] : neg;
+  }
+}
+
+// one thread per 32-bit word of the message: it gathers the fields that overlap its word
+__device__ __forceinline__ uint32_t gather_word(const uint32_t* arr, uint64_t n, uint32_t width, uint64_t word) {
+  if (width == 0) return 0;
+  const uint64_t b0 = word * 32;
+  const uint64_t e_end = min(n, (b0 + 31) / width + 1);           // one past the last field that touches the word
+  uint32_t out = 0;
+  for (uint64_t e0 = b0 / width; e0 < e_end; e0 += 8) {           // 8 loads in flight (a 1-bit field: 32 per word)
+    uint32_t f[8];
+#pragma unroll
+    for (uint32_t i = 0; i < 8; ++i) f[i] = e0 + i < e_end ? arr[e0 + i] : 0u;
+#pragma unroll
+    for (uint32_t i = 0; i < 8; ++i) {
+      if (e0 + i >= e_end) break;
+      const int64_t sh = static_cast<int64_t>((e0 + i) * width) - static_cast<int64_t>(b0);
+      out |= sh >= 0 ? (f[i] << sh) : (f[i] >> (-sh));
+    }
+  }
+  return out;
+}
+
+__global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t* msg_bits) {
+  __shared__ uint32_t s_part[4];
+  const uint32_t w = blockIdx.y;
+  // this is the last kernel of a call: it also returns the shared scratch of this worker to all-zero
+  {
+    const uint64_t tid = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x, nth = static_cast<uint64_t>(gridDim.x) * BLOCK;
+    // histograms: only the segments that have any (not the one-block ones), and of the third digit only its 256 bins
+    constexpr uint32_t ZW = 2 * HBINS + 256;
+    uint32_t* h = c.hist + static_cast<uint64_t>(w) * c.L * 3 * HBINS;
+    for (uint64_t i = tid; i < static_cast<uint64_t>(c.nbig) * ZW; i += nth)
+      h[static_cast<uint64_t>(c.big_segs[i / ZW]) * 3 * HBINS + i % ZW] = 0;
+    uint32_t* ct = c.ctr + static_cast<uint64_t>(w) * c.L * CTR_LINES * PAD;                 // counters: the guessing segments only
+    for (uint64_t i = tid; i < static_cast<uint64_t>(c.nfast) * CTR_LINES; i += nth)
+      ct[(static_cast<uint64_t>(c.fast_segs[i / CTR_LINES]) * CTR_LINES + i % CTR_LINES) * PAD] = 0;
+    uint64_t* na = c.norm_acc + static_cast<uint64_t>(w) * c.L * ACC_SLOTS;
+    for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * ACC_SLOTS; i += nth) na[i] = 0;
+  }
+  const uint64_t nnz = c.QB > MAX_QB_INLINE ? c.blk_pre[static_cast<uint64_t>(w) * (c.QB + 1) + c.QB]
+                                            : block_sum_u32(c.blk_cnt + static_cast<uint64_t>(w) * c.QB, c.QB, s_part);
+  const uint64_t q = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x;
+  if (q >= c.cap_words) return;
+  const bool counts = is_qsgd(c.quantizer) && c.L > 1;
+  const uint64_t hdr = 1 + static_cast<uint64_t>(c.L) + (counts ? c.L : 0);
+  const uint64_t idx_words = (nnz * c.w_idx + 31) / 32, code_words = (nnz * c.w_val + 31) / 32;
+  uint32_t word = 0;
+  if (q == 0) word = static_cast<uint32_t>(nnz);
+  else if (q < 1 + static_cast<uint64_t>(c.L)) word = c.units[static_cast<uint64_t>(w) * c.L + (q - 1)].scale_bits;
+  else if (q < hdr) word = c.units[static_cast<uint64_t>(w) * c.L + (q - 1 - c.L)].nnz;
+  else if (q < hdr + idx_words) word = gather_word(c.surv_idx + static_cast<uint64_t>(w) * c.K, nnz, c.w_idx, q - hdr);
+  else if (q < hdr + idx_words + code_words)
+    word = gather_word(c.surv_code + static_cast<uint64_t>(w) * c.K, nnz, c.w_val, q - hdr - idx_words);
+  reinterpret_cast<uint32_t*>(msg + static_cast<uint64_t>(w) * c.cap_words * 4)[q] = word;
+  if (q == 0 && msg_bits) msg_bits[w] = hdr * 32 + nnz * (c.w_idx + c.w_val);
+}
+
+}  // namespace

@@ -1,0 +1,641 @@
+// qsl_select.h -- Exact selection of the k largest rank keys of every unit (Section 2.2) and their ordered compaction:
+// k_select<0..2> (radix digits, over the candidates or over the whole vector), k_small (one block per small
+// unit), k_tile_count and k_tile_write (ordered output, exact norm digits).
+// Part of the single translation unit qsl.hip (included there, in this order: layout, stream, select,
+// encode, decode); not a public header.
+#pragma once
+
+#include "qsl_device.h"
+#include "qsl_layout.h"
+
+namespace {
+
+// ------------------------------------------------------------------------------------------------
+// walking the candidates of a fast unit.  A wave reads 64 x 16 bytes of the slot area at a time,
+// i.e. 64 / lpc whole slots; lane l holds elements 2 (l mod lpc) and 2 (l mod lpc) + 1 of its slot.
+// ------------------------------------------------------------------------------------------------
+struct SlotRow {
+  uint32_t count;        // candidates of this lane's chunk (0 if the chunk does not exist)
+  uint32_t ovf_at;       // where they are in the overflow pool, if count > cap
+  uint32_t n;            // candidates this lane is responsible for: 0..2 of its own elements, or all
+                         // `count` entries in the overflow pool if it holds the header of such a chunk
+  bool spill;            // n entries are read from the overflow pool
+  bool has0, has1;       // this lane's first / second element is a candidate
+  uint32_t idx0, bits0, idx1, bits1;
+  uint32_t key0, key1;   // Rand_k: their rank keys, from the slot's key line
+};
+
+__device__ __forceinline__ SlotRow read_slot_row(const uint2* slots, const uint32_t* slot_key, uint32_t lpc, uint32_t nwt,
+                                                 uint64_t row, uint64_t nrows) {
+  SlotRow r;
+  const uint32_t lane = lane_id();
+  const uint32_t sub = lane & (lpc - 1);
+  uint4 q = make_uint4(0, 0, 0, 0);
+  uint2 kq = make_uint2(0, 0);
+  if (row < nrows && ((row * 64 + lane) >> (__ffs(lpc) - 1)) < nwt) {                                                 // lpc: 4, 8 or 16
+    q = reinterpret_cast<const uint4*>(slots)[row * 64 + lane];
+    if (slot_key) kq = reinterpret_cast<const uint2*>(slot_key)[row * 64 + lane];
+  }
+  r.key0 = kq.x; r.key1 = kq.y;
+  const uint32_t leader = lane & ~(lpc - 1);
+  r.count = __shfl(q.x, leader, WAVE);
+  r.ovf_at = __shfl(q.y, leader, WAVE);
+  const uint32_t cap = lpc * 2 - 1;
+  const bool inl = r.count <= cap;
+  const uint32_t e0 = sub * 2;                    // element numbers of this lane; element e holds candidate e - 1
+  r.has0 = inl && e0 >= 1 && e0 <= r.count;
+  r.has1 = inl && e0 + 1 <= r.count;
+  r.spill = !inl && sub == 0;
+  r.n = r.spill ? r.count : (r.has0 ? 1u : 0u) + (r.has1 ? 1u : 0u);
+  r.idx0 = q.x; r.bits0 = q.y; r.idx1 = q.z; r.bits1 = q.w;
+  return r;
+}
+
+__device__ __forceinline__ uint32_t wave_exclusive_scan32(uint32_t x, uint32_t* total) {
+  uint32_t inc = x;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const uint32_t y = __shfl_up(inc, o, WAVE);
+    if (lane_id() >= static_cast<uint32_t>(o)) inc += y;
+  }
+  *total = __shfl(inc, 63, WAVE);
+  return inc - x;
+}
+
+// ------------------------------------------------------------------------------------------------
+// radix selection, one kernel per digit
+// ------------------------------------------------------------------------------------------------
+template <int LEVEL>
+__device__ __forceinline__ bool level_bin(uint32_t key, uint32_t prefix, uint32_t* bin) {
+  if (LEVEL == 0) { *bin = key >> 20; return true; }
+  if (LEVEL == 1) { *bin = (key >> 8) & 0xFFFu; return (key >> 20) == (prefix >> 20); }
+  *bin = key & 0xFFu; return (key >> 8) == (prefix >> 8);
+}
+
+// Digit LEVEL of the k-th largest key.  The blocks of a unit build the digit's histogram (LDS, then
+// a few global atomics per bin); which bin the previous digit fell in is recomputed by every block
+// from the previous kernel's histogram.
+//   fast unit, digit 0: reads the slot rows (every wave a contiguous range) and leaves the number of
+//                       candidates each wave met;
+//   fast unit, digit 1: reads them again and writes all candidates, in coordinate order, into the
+//                       unit's dense list (the offset of a wave = sum of the earlier waves' counts);
+//   fast unit, digit 2: reads the dense list;
+//   general path:       reads v.
+template <int LEVEL, int SPARS>
+__global__ __launch_bounds__(BIG) void k_select(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round) {
+  __shared__ uint32_t lh[HBINS];
+  __shared__ uint64_t scratch[17];
+  __shared__ uint32_t result[2], s_ctr[CTR_LINES];
+  // a single-segment context carries its plan in the kernel arguments: one dependent load less per block
+  SelInfo si; si.seg = 0; si.j = blockIdx.x;
+  if (c.L != 1) si = c.sels[blockIdx.x];
+  const uint32_t w = blockIdx.y;
+  const SegInfo sg = c.L == 1 ? one : c.segs[si.seg];
+  const uint64_t u = static_cast<uint64_t>(w) * c.L + si.seg;
+  UnitState* usp = &c.units[u];
+  const UnitState us = *usp;
+  uint32_t* hist = c.hist + u * 3 * HBINS;
+  for (uint32_t i = threadIdx.x; i < HBINS; i += BIG) lh[i] = 0;
+  if (LEVEL == 0 && threadIdx.x < CTR_LINES)
+    s_ctr[threadIdx.x] = sg.mode == PATH_FAST ? c.ctr[(u * CTR_LINES + threadIdx.x) * PAD] : 0u;
+  __syncthreads();
+  uint32_t path, prefix = 0, k_rem = sg.k;
+  if (LEVEL == 0) {
+    // a guess that produced too few candidates, or more than there is room for, is discarded here
+    path = us.path;
+    if (path == PATH_FAST) {
+      uint32_t cand = 0;
+      for (uint32_t i = 0; i < NSUB; ++i) cand += s_ctr[i];
+      if (s_ctr[CTR_FAIL] || cand < sg.k || cand > sg.d0_cap) path = PATH_FALLBACK;
+      if (threadIdx.x == 0 && si.j == 0) { usp->cand = cand; usp->fell_back = path == PATH_FALLBACK; }
+    } else if (threadIdx.x == 0 && si.j == 0) { usp->cand = 0; usp->fell_back = 0; }
+    if (threadIdx.x == 0 && si.j == 0) usp->nnz = 0;
+  } else {
+    path = eff_path(us);
+    uint32_t above;
+    if (LEVEL == 1) {
+      const uint32_t bin = find_from_top<BIG>(hist, sg.k, &above, scratch, result, false);
+      prefix = bin << 20; k_rem = sg.k - above;
+    } else {
+      const uint32_t bin = find_from_top<BIG>(hist + HBINS, us.k_rem1, &above, scratch, result, false);
+      prefix = us.prefix1 | (bin << 8); k_rem = us.k_rem1 - above;
+    }
+    if (threadIdx.x == 0 && si.j == 0) {
+      if (LEVEL == 1) { usp->prefix1 = prefix; usp->k_rem1 = k_rem; }
+      else { usp->prefix2 = prefix; usp->k_rem2 = k_rem; }
+    }
+  }
+  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  if (path == PATH_FAST && LEVEL < 2) {
+    const uint2* slots = c.slots + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off;
+    const uint2* ovf = c.ovf + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off;
+    const uint32_t* slot_key = SPARS == QSL_RANDK ? c.slot_key + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off : nullptr;
+    const uint32_t* ovf_key = SPARS == QSL_RANDK ? c.ovf_key + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off : nullptr;
+    uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    uint32_t* wcnt = c.wave_cnt + static_cast<uint64_t>(w) * c.NWC + sg.wc_base;
+    const uint32_t nrows = static_cast<uint32_t>((static_cast<uint64_t>(sg.nwt) * sg.lpc + 63) >> 6);   // < 2^20
+    const uint32_t nwaves = sg.nsel * (BIG / 64), gw = si.j * (BIG / 64) + wave;
+    const uint32_t rpw = (nrows + nwaves - 1) / nwaves;
+    const uint64_t r_lo = static_cast<uint64_t>(gw) * rpw, r_hi = r_lo + rpw < nrows ? r_lo + rpw : nrows;
+    uint32_t seen = 0;                              // digit 0: candidates this wave met
+    uint32_t off = 0;                               // digit 1: where this wave's candidates go in the dense list
+    if (LEVEL == 1) {                               // at most MAX_SELECT_BLOCKS * 16 = 1024 waves: 16 loads in flight
+      uint32_t part[MAX_SELECT_BLOCKS * (BIG / 64) / WAVE];
+#pragma unroll
+      for (uint32_t i = 0; i < MAX_SELECT_BLOCKS * (BIG / 64) / WAVE; ++i) {
+        const uint32_t g = i * WAVE + lane;
+        part[i] = g < gw ? wcnt[g] : 0u;
+      }
+      uint32_t x = 0;
+#pragma unroll
+      for (uint32_t i = 0; i < MAX_SELECT_BLOCKS * (BIG / 64) / WAVE; ++i) x += part[i];
+      off = wave_sum(x);
+    }
+    for (uint64_t row0 = r_lo; row0 < r_hi; row0 += 4) {
+      SlotRow rr[4];                               // four independent accesses in flight; rows past the end read as empty
+#pragma unroll
+      for (int b = 0; b < 4; ++b) rr[b] = read_slot_row(slots, slot_key, sg.lpc, sg.nwt, row0 + b, r_hi);
+#pragma unroll
+      for (int b = 0; b < 4; ++b) {
+        const SlotRow& r = rr[b];
+        uint32_t pos = 0, tot = 0;
+        if (LEVEL == 0) seen += r.n;
+        else { pos = off + wave_exclusive_scan32(r.n, &tot); off += tot; }
+        if (!r.spill) {
+          uint32_t bin;
+          if (r.has0) {
+            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(r.bits0) : r.key0;
+            if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
+            if (LEVEL == 1) { d0[pos] = make_uint2(r.idx0, r.bits0); if (SPARS == QSL_RANDK) d0k[pos] = key; ++pos; }
+          }
+          if (r.has1) {
+            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(r.bits1) : r.key1;
+            if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
+            if (LEVEL == 1) { d0[pos] = make_uint2(r.idx1, r.bits1); if (SPARS == QSL_RANDK) d0k[pos] = key; }
+          }
+        } else {
+          for (uint32_t e = 0; e < r.count; ++e) {
+            const uint2 ent = ovf[r.ovf_at + e];
+            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(ent.y) : ovf_key[r.ovf_at + e];
+            uint32_t bin;
+            if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
+            if (LEVEL == 1) { d0[pos + e] = ent; if (SPARS == QSL_RANDK) d0k[pos + e] = key; }
+          }
+        }
+      }
+    }
+    if (LEVEL == 0) { seen = wave_sum(seen); if (lane == 0) wcnt[gw] = seen; }
+  } else if (path == PATH_FAST) {
+    const uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    const uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    for (uint32_t e = si.j * BIG + threadIdx.x; e < us.cand; e += sg.nsel * BIG) {
+      const uint32_t key = SPARS == QSL_TOPK ? key_of_value(d0[e].y) : d0k[e];
+      uint32_t bin;
+      if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
+    }
+  } else {
+    const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
+    const uint32_t nwaves = sg.nsel * (BIG / 64);
+    // a wave takes two chunks per step, 32 values per lane in flight
+    for (uint64_t ch = (si.j * (BIG / 64) + wave) * 2; ch < sg.nwt; ch += 2ull * nwaves) {
+      f4u x[2][4];
+      if (SPARS == QSL_TOPK) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+#pragma unroll
+          for (int t = 0; t < 4; ++t) {
+            const uint64_t e = (ch + h) * CHUNK + t * 256 + lane * 4;
+            x[h][t] = f4u{0.f, 0.f, 0.f, 0.f};
+            if (e + 4 <= sg.size) x[h][t] = *reinterpret_cast<const f4u*>(vp + e);
+            else {
+#pragma unroll
+              for (int j = 0; j < 4; ++j) if (e + j < sg.size) x[h][t][j] = vp[e + j];
+            }
+          }
+        }
+      }
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const uint64_t e = (ch + h) * CHUNK + t * 256 + lane * 4;
+          Words4 rw = {{0u, 0u, 0u, 0u}};
+          if (SPARS == QSL_RANDK && e < sg.size) rw = rand_words4(rk, static_cast<uint32_t>(sg.start + e));
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(__float_as_uint(x[h][t][j])) : rw.w[j];
+            uint32_t bin;
+            if (e + j < sg.size && level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();
+  flush_hist(lh, hist + LEVEL * HBINS);
+}
+
+// ------------------------------------------------------------------------------------------------
+// ordered compaction of the selected coordinates, with the exact norm of what is selected.
+//
+// A "compaction block" covers either a tile of 2048 entries of a fast unit's dense candidate list
+// (each thread 8 consecutive entries), or, on the general path, a contiguous range of groups of 16
+// chunks of v (a group at a time: each wave 4 chunks, a lane 16 coordinates of a chunk; one group per
+// block while the unit has at most 256 groups).  k_tile_count leaves the number of selected
+// coordinates of every block; k_tile_write sums the earlier blocks' numbers to know where it writes.
+// A fast unit whose guess failed runs the general path with the blocks it has.
+//
+// Exact norms: every |v| (or v^2) is an integer multiple of 2^-149 (2^-298); its 32-bit digits are
+// added into 64-bit counters; integer addition commutes, so any schedule gives the same sum.
+// ------------------------------------------------------------------------------------------------
+constexpr uint32_t DTILE = 2048;           // dense-list entries per compaction block
+constexpr uint32_t GGROUP = 16;            // chunks per general-path group
+constexpr uint32_t ACC_ROWS = 32;          // accumulator rows of a compaction block (8 per wave)
+
+struct Thresh { uint32_t tau, need; };
+
+// one chunk of v in registers: 16 coordinates per lane, as two 16-bit masks (key > tau, key == tau)
+template <int SPARS>
+__device__ __forceinline__ void load_chunk_masks(const float* vp, uint64_t cb, uint64_t size, uint64_t start,
+                                                 const RandKey& rk, Thresh th, f4u* val, uint32_t* gmask,
+                                                 uint32_t* qmask) {
+  const uint32_t lane = lane_id();
+  uint32_t gm = 0, qm = 0;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+    const uint64_t e = cb + t * 256 + lane * 4;
+    f4u x = {0.f, 0.f, 0.f, 0.f};
+    if (e + 4 <= size) x = *reinterpret_cast<const f4u*>(vp + e);
+    else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) if (e + j < size) x[j] = vp[e + j];
+    }
+    val[t] = x;
+    Words4 rw;
+    if (SPARS == QSL_RANDK) rw = rand_words4(rk, static_cast<uint32_t>(start + e));
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint32_t key = SPARS == QSL_TOPK ? key_of_value(__float_as_uint(x[j])) : rw.w[j];
+      const bool inside = e + j < size;
+      gm |= (inside && key > th.tau ? 1u : 0u) << (t * 4 + j);
+      qm |= (inside && key == th.tau ? 1u : 0u) << (t * 4 + j);
+    }
+  }
+  *gmask = gm; *qmask = qm;
+}
+
+// digits of |v| (or v^2) into an accumulator row in LDS that a few lanes share (hence the atomics)
+__device__ __forceinline__ void lds_add(uint64_t* p, uint64_t x) {
+  atomicAdd(reinterpret_cast<unsigned long long*>(p), static_cast<unsigned long long>(x));
+}
+__device__ __forceinline__ void add_digits(uint64_t* mine, uint32_t bits, bool squares) {
+  const uint32_t ab = bits & 0x7FFFFFFFu;
+  const uint32_t ex = ab >> 23, frac = ab & 0x7FFFFFu;
+  const uint32_t M = ex ? (frac | 0x800000u) : frac;       // |v| = M * 2^(max(ex,1) - 150)
+  const uint32_t e1 = ex ? ex : 1u;
+  if (M == 0) return;
+  if (squares) {
+    const uint64_t sq = static_cast<uint64_t>(M) * M;       // < 2^48;  v^2 = sq * 2^(2 e1 - 300)
+    const uint32_t p = 2u * e1 - 2u;                        // bit position above 2^-298
+    const uint32_t q = p >> 5, r = p & 31u;
+    const uint64_t lo = sq << r;                            // low 64 bits of sq * 2^r  (r <= 30)
+    const uint64_t hi = r ? (sq >> (64 - r)) : 0;
+    lds_add(&mine[q], lo & 0xFFFFFFFFu); lds_add(&mine[q + 1], lo >> 32);
+    if (hi) lds_add(&mine[q + 2], hi);
+  } else {
+    const uint32_t p = e1 - 1u;                             // bit position above 2^-149
+    const uint32_t q = p >> 5, r = p & 31u;
+    const uint64_t sh = static_cast<uint64_t>(M) << r;      // < 2^55
+    lds_add(&mine[q], sh & 0xFFFFFFFFu);
+    if (sh >> 32) lds_add(&mine[q + 1], sh >> 32);
+  }
+}
+
+// the general-path groups [g_lo, g_hi) of one unit, by one 256-thread block.
+// WRITE = false: returns (in *tot_gt, *tot_eq, valid in thread 0) how many coordinates of these groups have key > tau / == tau.
+// WRITE = true: writes the selected ones, in coordinate order, starting at ranks (gt0, eq0).
+template <int SPARS, bool WRITE>
+__device__ void general_groups(const SegInfo& sg, const float* vp, const RandKey& rk, Thresh th,
+                               uint32_t g_lo, uint32_t g_hi, uint32_t gt0, uint32_t eq0, uint32_t* oi, uint32_t* ov,
+                               uint64_t* mine, bool squares, uint32_t* s_cnt /*[2][GGROUP + 1]*/,
+                               uint32_t* tot_gt, uint32_t* tot_eq) {
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  uint32_t run_gt = gt0, run_eq = eq0;             // ranks at the start of the current group (all threads agree)
+  for (uint32_t g = g_lo; g < g_hi; ++g) {
+    f4u val[4][4]; uint32_t gm[4], qm[4];
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {
+      const uint32_t lc = wave * 4 + q;            // chunk inside the group: a wave takes 4 consecutive ones
+      const uint64_t chunk = static_cast<uint64_t>(g) * GGROUP + lc;
+      gm[q] = 0; qm[q] = 0;
+      if (chunk < sg.nwt) load_chunk_masks<SPARS>(vp, chunk * CHUNK, sg.size, sg.start, rk, th, val[q], &gm[q], &qm[q]);
+      const uint32_t cg = wave_sum(__popc(gm[q])), cq = wave_sum(__popc(qm[q]));
+      if (lane == 0) { s_cnt[lc] = cg; s_cnt[GGROUP + 1 + lc] = cq; }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {                        // exclusive prefix over the 16 chunks, on top of the running ranks
+      uint32_t a = run_gt, b = run_eq;
+      for (uint32_t i = 0; i < GGROUP; ++i) {
+        const uint32_t x = s_cnt[i], y = s_cnt[GGROUP + 1 + i];
+        s_cnt[i] = a; s_cnt[GGROUP + 1 + i] = b; a += x; b += y;
+      }
+      s_cnt[GGROUP] = a; s_cnt[2 * GGROUP + 1] = b;
+    }
+    __syncthreads();
+    if (WRITE) {
+#pragma unroll
+      for (uint32_t q = 0; q < 4; ++q) {
+        if (__ballot((gm[q] | qm[q]) != 0) == 0) continue;          // wave-uniform
+        const uint32_t lc = wave * 4 + q;
+        const uint64_t cb = (static_cast<uint64_t>(g) * GGROUP + lc) * CHUNK;
+        uint32_t base_gt = s_cnt[lc], base_eq = s_cnt[GGROUP + 1 + lc];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+          const uint32_t gn = (gm[q] >> (t * 4)) & 0xFu, qn = (qm[q] >> (t * 4)) & 0xFu;
+          if (__ballot((gn | qn) != 0) == 0) continue;              // wave-uniform
+          uint32_t bg = 0, bq = 0, tg = 0, tq = 0;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const uint64_t b1 = __ballot((gn >> j) & 1u), b2 = __ballot((qn >> j) & 1u);
+            bg += popc_below(b1); tg += __popcll(b1); bq += popc_below(b2); tq += __popcll(b2);
+          }
+          uint32_t my_gt = base_gt + bg, my_eq = base_eq + bq;
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const bool is_gt = (gn >> j) & 1u, is_eq = (qn >> j) & 1u;
+            if (is_gt || (is_eq && my_eq < th.need)) {
+              const uint32_t pos = my_gt + min(my_eq, th.need);
+              const uint32_t bits = __float_as_uint(val[q][t][j]);
+              oi[pos] = static_cast<uint32_t>(sg.start + cb + t * 256 + lane * 4 + j); ov[pos] = bits;
+              add_digits(mine, bits, squares);
+            }
+            my_gt += is_gt; my_eq += is_eq;
+          }
+          base_gt += tg; base_eq += tq;
+        }
+      }
+    }
+    run_gt = s_cnt[GGROUP]; run_eq = s_cnt[2 * GGROUP + 1];
+    __syncthreads();                               // s_cnt is reused by the next group
+  }
+  *tot_gt = run_gt - gt0; *tot_eq = run_eq - eq0;
+}
+
+// the threshold key and the tie budget, from the histogram of the last digit
+__device__ __forceinline__ Thresh last_digit(const DevCtx& c, uint64_t u, const UnitState& us, uint64_t* scratch,
+                                             uint32_t* result) {
+  uint32_t above;
+  const uint32_t bin = find_from_top<BLOCK, 256>(c.hist + (u * 3 + 2) * HBINS, us.k_rem2, &above, scratch, result, false);
+  Thresh th; th.tau = us.prefix2 | bin; th.need = us.k_rem2 - above;
+  return th;
+}
+
+// range of general-path groups a compaction block takes (one group each while the unit has at most 256)
+__device__ __forceinline__ void fallback_range(const SegInfo& sg, uint32_t b, uint32_t* g_lo, uint32_t* g_hi) {
+  const uint64_t ngg = (static_cast<uint64_t>(sg.nwt) + GGROUP - 1) / GGROUP;
+  *g_lo = static_cast<uint32_t>(ngg * b / sg.ncb); *g_hi = static_cast<uint32_t>(ngg * (b + 1) / sg.ncb);
+}
+
+// ------------------------------------------------------------------------------------------------
+// small units (at most 4 chunks = 4096 coordinates): the whole selection by one block of 256 threads.
+// Thread t keeps 16 consecutive coordinates in registers (Top_k: the bits of v; Rand_k: the random
+// words), the three digit histograms live in LDS, and the block writes the selected coordinates in order
+// together with the digits of their norm -- what k_select<0..2>, k_tile_count and k_tile_write do for a
+// larger unit, without a launch in between.  (One CU retires ~64 lane-operations per cycle: a block
+// needed 25 us for 16,384 coordinates and 50 us for 65,536, and the slowest block is the kernel's time,
+// so the limit is low; segments above it take the guessing path, whose kernels run anyway.)
+// ------------------------------------------------------------------------------------------------
+template <int LEVEL, int SPARS>
+__device__ __forceinline__ void small_hist(const uint32_t (&kv)[16], uint32_t n, uint32_t prefix, uint32_t* lh) {
+  const uint32_t e0 = threadIdx.x * 16;
+#pragma unroll
+  for (uint32_t j = 0; j < 16; ++j) {
+    const uint32_t key = SPARS == QSL_TOPK ? key_of_value(kv[j]) : kv[j];
+    uint32_t bin;
+    if (e0 + j < n && level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
+  }
+}
+
+template <int SPARS>
+__global__ __launch_bounds__(BLOCK) void k_small(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
+  __shared__ uint32_t lh[HBINS];
+  __shared__ uint64_t acc[ACC_ROWS * (ACC_SLOTS + 1)];
+  __shared__ uint64_t scratch[17];
+  __shared__ uint32_t result[2];
+  const uint32_t seg = c.small_segs[blockIdx.x], w = blockIdx.y;
+  const SegInfo sg = c.segs[seg];
+  const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
+  const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
+  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t n = static_cast<uint32_t>(sg.size);                 // <= SMALL_CHUNKS * CHUNK = 16 * BLOCK
+  const uint32_t e0 = threadIdx.x * 16;
+  uint32_t kv[16];
+#pragma unroll
+  for (uint32_t q = 0; q < 4; ++q) {
+    const uint32_t e = e0 + q * 4;
+    if (SPARS == QSL_TOPK) {
+      f4u x = {0.f, 0.f, 0.f, 0.f};
+      if (e + 4 <= n) x = *reinterpret_cast<const f4u*>(vp + e);
+      else {
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) if (e + j < n) x[j] = vp[e + j];
+      }
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) kv[q * 4 + j] = __float_as_uint(x[j]);
+    } else {
+      Words4 rw = {{0u, 0u, 0u, 0u}};
+      if (e < n) rw = rand_words4(rk, static_cast<uint32_t>(sg.start) + e);
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) kv[q * 4 + j] = rw.w[j];
+    }
+  }
+  for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;
+
+  // the three digits of the k-th largest key
+  uint32_t above;
+  for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK) lh[i] = 0;
+  __syncthreads();
+  small_hist<0, SPARS>(kv, n, 0, lh);
+  __syncthreads();
+  uint32_t bin = find_from_top<BLOCK>(lh, sg.k, &above, scratch, result, true);
+  uint32_t prefix = bin << 20, k_rem = sg.k - above;
+  small_hist<1, SPARS>(kv, n, prefix, lh);
+  __syncthreads();
+  bin = find_from_top<BLOCK>(lh, k_rem, &above, scratch, result, true);
+  prefix |= bin << 8; k_rem -= above;
+  small_hist<2, SPARS>(kv, n, prefix, lh);
+  __syncthreads();
+  bin = find_from_top<BLOCK, 256>(lh, k_rem, &above, scratch, result, false);
+  const uint32_t tau = prefix | bin, need = k_rem - above;
+
+  // ordered compaction: key > tau, and the first `need` coordinates with key == tau
+  uint32_t gm = 0, qm = 0;
+#pragma unroll
+  for (uint32_t j = 0; j < 16; ++j) {
+    const uint32_t key = SPARS == QSL_TOPK ? key_of_value(kv[j]) : kv[j];
+    const bool inside = e0 + j < n;
+    gm |= (inside && key > tau ? 1u : 0u) << j;
+    qm |= (inside && key == tau ? 1u : 0u) << j;
+  }
+  uint64_t total;
+  const uint64_t ex = block_exclusive_scan64((static_cast<uint64_t>(__popc(qm)) << 32) | __popc(gm), scratch, &total);
+  const uint32_t gt0 = static_cast<uint32_t>(ex), eq0 = static_cast<uint32_t>(ex >> 32);
+  // which of this thread's ties are kept: the first need - eq0 of them
+  uint32_t keep = 0;
+  if (eq0 < need) {
+    keep = qm;
+    for (uint32_t extra = eq0 + __popc(qm); extra > need; --extra) keep &= ~(0x80000000u >> __clz(keep));   // drop the last
+  }
+  const uint32_t sel = gm | keep;
+  uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
+  uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
+  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
+  const bool squares = wants_squares(c.quantizer);
+#pragma unroll
+  for (uint32_t j = 0; j < 16; ++j) {
+    if ((sel >> j) & 1u) {
+      const uint32_t below = (1u << j) - 1u;
+      const uint32_t pos = gt0 + __popc(gm & below) + min(eq0 + __popc(qm & below), need);
+      const uint32_t bits = SPARS == QSL_TOPK ? kv[j] : __float_as_uint(vp[e0 + j]);
+      oi[pos] = static_cast<uint32_t>(sg.start) + e0 + j; ov[pos] = bits;
+      add_digits(mine, bits, squares);
+    }
+  }
+  __syncthreads();
+  // the unit is this block's alone: its norm digits are stored, not added
+  for (uint32_t sl = wave; sl < ACC_SLOTS; sl += BLOCK / 64) {
+    uint64_t x = lane < ACC_ROWS ? acc[lane * (ACC_SLOTS + 1) + sl] : 0;
+    x = wave_sum64(x);
+    if (lane == 0) c.norm_acc[u * ACC_SLOTS + sl] = x;
+  }
+  if (threadIdx.x == 0) {
+    UnitState* us = &c.units[u];
+    us->cand = 0; us->fell_back = 0; us->prefix2 = tau & ~0xFFu; us->k_rem2 = k_rem;
+    us->tau = tau; us->need = need; us->n_gt = sg.k - need; us->nnz = 0;
+  }
+}
+
+template <int SPARS>
+__global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round) {
+  __shared__ uint32_t s_cnt[2 * GGROUP + 2], s_red[8], result[2];
+  __shared__ uint64_t scratch[17];
+  CbInfo cb; cb.seg = 0; cb.b = blockIdx.x;
+  if (c.L != 1) cb = c.cbs[blockIdx.x];
+  const uint32_t w = blockIdx.y;
+  const SegInfo sg = c.L == 1 ? one : c.segs[cb.seg];
+  const uint64_t u = static_cast<uint64_t>(w) * c.L + cb.seg;
+  const UnitState us = c.units[u];
+  const uint32_t path = eff_path(us);
+  if (path == PATH_FAST && cb.b != 0 && cb.b * DTILE >= us.cand) {         // a tile past the end of the dense list
+    if (threadIdx.x == 0) c.cb_cnt[static_cast<uint64_t>(w) * c.NCB + sg.cb_base + cb.b] = make_uint2(0, 0);
+    return;
+  }
+  const Thresh th = last_digit(c, u, us, scratch, result);
+  if (threadIdx.x == 0 && cb.b == 0) { c.units[u].tau = th.tau; c.units[u].need = th.need; c.units[u].n_gt = sg.k - th.need; }
+  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
+  uint2* out = c.cb_cnt + static_cast<uint64_t>(w) * c.NCB + sg.cb_base + cb.b;
+  if (path == PATH_FAST) {
+    const uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    const uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    uint32_t gt = 0, eq = 0;
+    const uint32_t e0 = cb.b * DTILE + threadIdx.x * 8;
+#pragma unroll
+    for (uint32_t i = 0; i < 8; ++i) {
+      if (e0 + i < us.cand) {
+        const uint32_t key = SPARS == QSL_TOPK ? key_of_value(d0[e0 + i].y) : d0k[e0 + i];
+        gt += key > th.tau; eq += key == th.tau;
+      }
+    }
+    gt = wave_sum(gt); eq = wave_sum(eq);
+    if (lane_id() == 0) { s_red[threadIdx.x >> 6] = gt; s_red[4 + (threadIdx.x >> 6)] = eq; }
+    __syncthreads();
+    if (threadIdx.x == 0) *out = make_uint2(s_red[0] + s_red[1] + s_red[2] + s_red[3], s_red[4] + s_red[5] + s_red[6] + s_red[7]);
+    return;
+  }
+  uint32_t g_lo, g_hi;
+  fallback_range(sg, cb.b, &g_lo, &g_hi);
+  uint32_t tg = 0, tq = 0;
+  general_groups<SPARS, false>(sg, v + static_cast<uint64_t>(w) * c.d + sg.start, rk, th, g_lo, g_hi, 0, 0, nullptr,
+                               nullptr, nullptr, false, s_cnt, &tg, &tq);
+  if (threadIdx.x == 0) *out = make_uint2(tg, tq);
+}
+
+template <int SPARS>
+__global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round) {
+  __shared__ uint64_t acc[ACC_ROWS * (ACC_SLOTS + 1)];      // a row per 8 lanes of a wave: short atomic queues
+  __shared__ uint32_t s_cnt[2 * GGROUP + 2];
+  __shared__ uint64_t scratch[17], s_part[4];
+  CbInfo cb; cb.seg = 0; cb.b = blockIdx.x;
+  if (c.L != 1) cb = c.cbs[blockIdx.x];
+  const uint32_t w = blockIdx.y;
+  const SegInfo sg = c.L == 1 ? one : c.segs[cb.seg];
+  const uint64_t u = static_cast<uint64_t>(w) * c.L + cb.seg;
+  const UnitState us = c.units[u];
+  const uint32_t path = eff_path(us);
+  if (path == PATH_FAST && cb.b * DTILE >= us.cand) return;                 // a tile past the end of the dense list
+  Thresh th; th.tau = us.tau; th.need = us.need;
+  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const bool squares = wants_squares(c.quantizer);
+  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
+  for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;   // published by the barrier below
+  // how many selected coordinates precede this block: the sum of the unit's earlier blocks' counts
+  {
+    const uint2* cc = c.cb_cnt + static_cast<uint64_t>(w) * c.NCB + sg.cb_base;
+    uint64_t x = 0;
+    for (uint32_t i = threadIdx.x; i < cb.b; i += BLOCK) { const uint2 p = cc[i]; x += (static_cast<uint64_t>(p.y) << 32) | p.x; }
+    x = wave_sum64(x);
+    if (lane == 0) s_part[wave] = x;
+  }
+  __syncthreads();
+  const uint64_t before = s_part[0] + s_part[1] + s_part[2] + s_part[3];
+  const uint32_t gt0 = static_cast<uint32_t>(before), eq0 = static_cast<uint32_t>(before >> 32);
+  uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
+  uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
+  if (path == PATH_FAST) {
+    const uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    const uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+    const uint32_t e0 = cb.b * DTILE + threadIdx.x * 8;
+    uint2 ent[8]; uint32_t gm = 0, qm = 0;
+#pragma unroll
+    for (uint32_t i = 0; i < 8; ++i) {
+      ent[i] = make_uint2(0, 0);
+      if (e0 + i < us.cand) {
+        ent[i] = d0[e0 + i];
+        const uint32_t key = SPARS == QSL_TOPK ? key_of_value(ent[i].y) : d0k[e0 + i];
+        gm |= (key > th.tau ? 1u : 0u) << i; qm |= (key == th.tau ? 1u : 0u) << i;
+      }
+    }
+    uint64_t total;
+    const uint64_t ex = block_exclusive_scan64((static_cast<uint64_t>(__popc(qm)) << 32) | __popc(gm), scratch, &total);
+    uint32_t my_gt = gt0 + static_cast<uint32_t>(ex), my_eq = eq0 + static_cast<uint32_t>(ex >> 32);
+#pragma unroll
+    for (uint32_t i = 0; i < 8; ++i) {
+      const bool is_gt = (gm >> i) & 1u, is_eq = (qm >> i) & 1u;
+      if (is_gt || (is_eq && my_eq < th.need)) {
+        const uint32_t pos = my_gt + min(my_eq, th.need);
+        oi[pos] = ent[i].x; ov[pos] = ent[i].y;
+        add_digits(mine, ent[i].y, squares);
+      }
+      my_gt += is_gt; my_eq += is_eq;
+    }
+  } else {
+    uint32_t g_lo, g_hi;
+    fallback_range(sg, cb.b, &g_lo, &g_hi);
+    uint32_t tg, tq;
+    general_groups<SPARS, true>(sg, v + static_cast<uint64_t>(w) * c.d + sg.start, rk, th, g_lo, g_hi, gt0, eq0, oi, ov,
+                                mine, squares, s_cnt, &tg, &tq);
+  }
+  __syncthreads();
+  uint64_t* ga = c.norm_acc + u * ACC_SLOTS;
+  for (uint32_t s = wave; s < ACC_SLOTS; s += 4) {
+    uint64_t x = lane < ACC_ROWS ? acc[lane * (ACC_SLOTS + 1) + s] : 0;
+    x = wave_sum64(x);
+    if (lane == 0 && x) atomicAdd(reinterpret_cast<unsigned long long*>(ga + s), static_cast<unsigned long long>(x));
+  }
+}
+
+}  // namespace
