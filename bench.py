@@ -139,6 +139,18 @@ def main():
     torch.cuda.synchronize()
     per_round = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
     assert q.device_status() == B.OK
+    # for scale: the same traffic shape (two [R, d] reads, one [R, d] write) through PyTorch's own elementwise add
+    ref_out = torch.empty_like(m)
+    for _ in range(3):
+        torch.add(m, deltas[0], out=ref_out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        torch.add(m, deltas[0], out=ref_out)
+    e1.record()
+    torch.cuda.synchronize()
+    ref_us = e0.elapsed_time(e1) * 100.0
+    del ref_out
     coords_per_s = R * d * args.steps / elapsed
     units = q.debug_units()
     bits = msg_bits.cpu().numpy()
@@ -197,6 +209,8 @@ def main():
         "per_round_ms": {"median": per_round[len(per_round) // 2], "min": per_round[0], "max": per_round[-1],
                          "note": "separate pass after the timed region, HIP events around each round"},
         "gpu_state": state,
+        "stream_reference": {"what": "torch.add(m, delta, out=...) on the same [R, d] arrays: 2 reads + 1 write per coordinate",
+                             "us": ref_us, "GB/s": ALGO_BYTES_PER_COORD * R * d / ref_us / 1e3},
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
