@@ -63,6 +63,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (2 = headline)")
+    ap.add_argument("--workers", type=int, default=0,
+                    help="override the configuration's R (R = 1 is the deployment shape: one worker per GPU); "
+                         "not the headline line")
     ap.add_argument("--from-models", action="store_true",
                     help="time qsl_compress_diff (Delta = x - xhat formed on the fly; the fresh buffers act as the "
                          "local models) instead of qsl_compress; not the headline line")
@@ -89,7 +92,7 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    wl = W.config(args.config)
+    wl = W.config(args.config, R=args.workers) if args.workers else W.config(args.config)
     q = B.from_workload(wl, device=dev)
     R, d = wl.R, wl.d
     total = args.steps + args.warmup
