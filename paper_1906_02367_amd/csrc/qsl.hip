@@ -457,8 +457,10 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
     k_tile_write<SPARS><<<dim3(c.NCB, R), BLOCK, 0, st>>>(c, ctx->segs[0], m_out, worker0, round);
   }
   k_quantize<<<dim3(c.QB, R), BLOCK, 0, st>>>(c, m_out, worker0, round, sel_idx, sel_level);
-  if (c.QB > MAX_QB_INLINE) k_surv_scan<<<dim3(R), 1024, 0, st>>>(c);
-  k_surv_compact<<<dim3(c.QB, R), BLOCK, 0, st>>>(c);
+  if (is_qsgd(c.quantizer)) {                      // the other quantisers send every selected coordinate: k_quantize wrote the final arrays
+    if (c.QB > MAX_QB_INLINE) k_surv_scan<<<dim3(R), 1024, 0, st>>>(c);
+    k_surv_compact<<<dim3(c.QB, R), BLOCK, 0, st>>>(c);
+  }
   k_pack<<<dim3((c.cap_words + BLOCK - 1) / BLOCK, R), BLOCK, 0, st>>>(c, msg, msg_bits);
   QSL_HIP(hipGetLastError());
   return QSL_OK;

@@ -142,7 +142,11 @@ __global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint
       g = neg ? -scale : scale;
     }
     sent = level != 0;
-    c.sel_code[slot] = level | (neg ? 0x80000000u : 0u);
+    if (is_qsgd(c.quantizer)) c.sel_code[slot] = level | (neg ? 0x80000000u : 0u);
+    else {                                                 // every selected coordinate is sent: nothing to compact
+      c.surv_idx[slot] = idx;
+      c.surv_code[slot] = c.quantizer == QSL_FP32 ? bits : (neg ? 1u : 0u);
+    }
     if (sent) {
       if (idx < c.d) m_out[static_cast<uint64_t>(w) * c.d + idx] = v - g;
       else atomicOr(c.status, 2u);                       // cannot happen: a selected slot was never written
@@ -151,6 +155,7 @@ __global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint
     if (dbg_idx) dbg_idx[slot] = idx;
     if (dbg_level) dbg_level[slot] = static_cast<uint16_t>(level);
   }
+  if (!is_qsgd(c.quantizer)) return;                       // survivors are counted only where some may drop out
   const uint32_t wc = __popcll(__ballot(sent));
   if (lane_id() == 0) s_w[threadIdx.x >> 6] = wc;
   __syncthreads();
@@ -248,7 +253,8 @@ __global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t
     uint64_t* na = c.norm_acc + static_cast<uint64_t>(w) * c.L * ACC_SLOTS;
     for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * ACC_SLOTS; i += nth) na[i] = 0;
   }
-  const uint64_t nnz = c.QB > MAX_QB_INLINE ? c.blk_pre[static_cast<uint64_t>(w) * (c.QB + 1) + c.QB]
+  const uint64_t nnz = !is_qsgd(c.quantizer) ? c.K
+                       : c.QB > MAX_QB_INLINE ? c.blk_pre[static_cast<uint64_t>(w) * (c.QB + 1) + c.QB]
                                             : block_sum_u32(c.blk_cnt + static_cast<uint64_t>(w) * c.QB, c.QB, s_part);
   const uint64_t q = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x;
   if (q >= c.cap_words) return;
