@@ -206,7 +206,8 @@ def main():
                    "sparsifier": ["top_k", "rand_k"][wl.sparsifier], "quantizer": ["qsgd", "sign_l1"][wl.quantizer],
                    "fresh_delta_buffers": n_buf, "delta": "x - xhat on the fly" if args.from_models else "given",
                    "paths": {"fast": int((units[:, 0] == 0).sum()), "general": int((units[:, 0] == 1).sum()),
-                             "fallback": int((units[:, 0] == 2).sum()), "one_block": int((units[:, 0] == 3).sum())},
+                             "fallback": int((units[:, 0] == 2).sum()), "one_block": int((units[:, 0] == 3).sum()),
+                             "all_kept": int((units[:, 0] == 4).sum())},
                    "max_candidates": int(units[:, 1].max()), "mean_msg_bits": float(bits.mean())},
         "algorithmic_GBps_whole_step": ALGO_BYTES_PER_COORD * coords_per_s / 1e9,
         "per_round_ms": {"median": per_round[len(per_round) // 2], "min": per_round[0], "max": per_round[-1],

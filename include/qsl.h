@@ -82,7 +82,8 @@ typedef struct {
 } qsl_config;
 
 enum {
-  QSL_FLAG_NO_FAST_PATH = 1,  /* never guess a threshold: exact multi-pass selection only (testing, comparison) */
+  QSL_FLAG_NO_FAST_PATH = 1,  /* never guess a threshold and never skip the selection of a segment with k = size:
+                                 exact multi-pass selection only (testing, comparison)                  */
   QSL_FLAG_NO_SMALL_PATH = 2  /* segments of at most 4096 coordinates also take the multi-pass kernels  
                                  instead of the one-block selection (testing, comparison)               */
 };
@@ -161,7 +162,8 @@ qsl_status qsl_device_status(qsl_ctx *ctx);
 /* Per-unit diagnostics of the last compress call (unit = worker-major (worker, segment)); synchronises.
  * out_host receives, per unit, 8 uint32: {path, candidates, threshold key, n_greater, n_equal_taken,
  * guess key, scale bits, transmitted}; path: 0 = single-pass fast path, 1 = multi-pass path by
- * configuration, 2 = multi-pass path after a failed guess, 3 = one-block selection of a small segment.  */
+ * configuration, 2 = multi-pass path after a failed guess, 3 = one-block selection of a small segment,
+ * 4 = no selection (k equals the size of the segment: every coordinate is kept).  */
 qsl_status qsl_debug_units(qsl_ctx *ctx, uint32_t *out_host, uint32_t max_units, uint32_t *n_units);
 
 /* Kernel timing for the benchmark: when enabled, compress calls bracket the streaming kernel with

@@ -69,6 +69,7 @@ struct qsl_ctx {
   uint32_t Rmax;
   uint32_t last_R;
   uint32_t nsmall;            // segments selected by one block each (k_small)
+  uint32_t nfull_blocks;      // blocks of k_full (per worker): segments with k = size
   uint32_t nnz_hint;          // entries a message is expected to hold at most (sizes the aggregation grid)
   uint32_t* agg_dir;          // [64][agg_ndir] directories of the listed messages (only if messages are expected to be long)
   uint32_t agg_ndir;
@@ -177,7 +178,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   std::vector<SegInfo>& segs = ctx->segs;
   segs.resize(L);
   std::vector<WtInfo> wts;
-  std::vector<SelInfo> sels, samps;
+  std::vector<SelInfo> sels, samps, fulls;
   std::vector<CbInfo> cbs;
   std::vector<uint32_t> fast, smalls;
   uint64_t slot_elems = 0, ovf_entries = 0, d0_entries = 0, nwt64 = 0, nwc = 0;
@@ -194,11 +195,13 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
       for (uint32_t t = 0; t < sg.nwt; ++t) { WtInfo wi; wi.seg = l; wi.chunk = t; wi.pad0 = wi.pad1 = 0; wts.push_back(wi); }
     }
     sg.mode = (sg.nwt <= SMALL_CHUNKS && !(cfg->flags & QSL_FLAG_NO_SMALL_PATH)) ? PATH_SMALL : PATH_GENERAL;
+    // k = size: nothing to select (unless the caller asks for the multi-pass kernels only)
+    if (sg.mode != PATH_SMALL && sg.k == sg.size && !(cfg->flags & QSL_FLAG_NO_FAST_PATH)) sg.mode = PATH_FULL;
     sg.T_static = 0xFFFFFFFFu;
     sg.lpc = 8;
     const double n = static_cast<double>(sg.size), p = static_cast<double>(sg.k) / n;
     double cand = 0, slack = 0;                     // expected number of candidates, room beyond 4x that
-    if (!(cfg->flags & QSL_FLAG_NO_FAST_PATH) && sg.nwt > SMALL_CHUNKS) {
+    if (!(cfg->flags & QSL_FLAG_NO_FAST_PATH) && sg.nwt > SMALL_CHUNKS && sg.mode != PATH_FULL) {
       if (cfg->sparsifier == QSL_TOPK && static_cast<uint64_t>(sg.k) * 64 <= sg.size) {
         // candidates ~ alpha k; the sample must hold enough of them for the guess to sit below the
         // true threshold with ~6.5 sigma: (alpha - 1) sqrt(n_s p) >= 6.5 sqrt(alpha)
@@ -259,6 +262,11 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
     } else if (sg.mode == PATH_SMALL) {
       smalls.push_back(l);
       sg.nsel = 0; sg.ncb = 0;
+    } else if (sg.mode == PATH_FULL) {
+      const uint64_t ntiles = (sg.size + 4095) / 4096;
+      const uint32_t nb = static_cast<uint32_t>(std::min<uint64_t>(ntiles, MAX_FULL_BLOCKS));
+      for (uint32_t j = 0; j < nb; ++j) { SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0; fulls.push_back(si); }
+      sg.nsel = 0; sg.ncb = 0;
     } else {
       sg.nsel = std::min(MAX_SELECT_BLOCKS, std::max(1u, (sg.nwt + 31) / 32));   // two chunks per wave up to 2^21 coordinates
       // at most 256 compaction blocks per unit, each a contiguous range of groups: every block ends with up to 20
@@ -301,10 +309,11 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t o_segs = carve(sizeof(SegInfo) * L), o_wts = carve(sizeof(WtInfo) * std::max<size_t>(1, wts.size()));
   const uint64_t o_sels = carve(sizeof(SelInfo) * NSEL), o_cbs = carve(sizeof(CbInfo) * NCB);
   const uint64_t o_samps = carve(sizeof(SelInfo) * samps.size());
+  const uint64_t o_fulls = carve(sizeof(SelInfo) * std::max<size_t>(1, fulls.size()));
   const uint64_t o_fast = carve(4ull * std::max<size_t>(1, fast.size()));
   const uint64_t o_small = carve(4ull * std::max<size_t>(1, smalls.size()));
   std::vector<uint32_t> bigs;
-  for (uint32_t l = 0; l < L; ++l) if (segs[l].mode != PATH_SMALL) bigs.push_back(l);
+  for (uint32_t l = 0; l < L; ++l) if (segs[l].mode != PATH_SMALL && segs[l].mode != PATH_FULL) bigs.push_back(l);
   const uint64_t o_big = carve(4ull * std::max<size_t>(1, bigs.size()));
   std::vector<uint32_t> seg_dir(((d + 1023) >> 10) + 1);
   for (size_t t = 0, l = 0; t < seg_dir.size(); ++t) {
@@ -346,6 +355,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   upload(o_wts, wts.data(), sizeof(WtInfo) * wts.size());
   upload(o_sels, sels.data(), sizeof(SelInfo) * NSEL);
   upload(o_samps, samps.data(), sizeof(SelInfo) * samps.size());
+  upload(o_fulls, fulls.data(), sizeof(SelInfo) * fulls.size());
   upload(o_cbs, cbs.data(), sizeof(CbInfo) * NCB);
   upload(o_fast, fast.data(), 4 * fast.size());
   upload(o_small, smalls.data(), 4 * smalls.size());
@@ -368,6 +378,8 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.seg_dir = reinterpret_cast<const uint32_t*>(base + o_segdir);
   c.slot_dir = reinterpret_cast<const uint32_t*>(base + o_slotdir);
   ctx->nsmall = static_cast<uint32_t>(smalls.size());
+  c.fulls = reinterpret_cast<const SelInfo*>(base + o_fulls);
+  ctx->nfull_blocks = static_cast<uint32_t>(fulls.size());
   c.units = reinterpret_cast<UnitState*>(base + o_units);
   c.slots = reinterpret_cast<uint2*>(base + o_slots); c.slot_stride = std::max<uint64_t>(2, slot_elems);
   c.ovf = reinterpret_cast<uint2*>(base + o_ovf); c.ovf_stride = std::max<uint64_t>(1, ovf_entries);
@@ -449,6 +461,7 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   if (timed) { QSL_HIP(hipEventRecord(ctx->ev[ctx->ev_used + 1], st)); ctx->ev_used += 2; }
 
   if (ctx->nsmall) k_small<SPARS><<<dim3(ctx->nsmall, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
+  if (ctx->nfull_blocks) k_full<<<dim3(ctx->nfull_blocks, R), BLOCK, 0, st>>>(c, m_out);
   if (c.NSEL) {                                    // units that take a launch per digit and two for the compaction
     k_select<0, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round);
     k_select<1, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round);
@@ -518,6 +531,12 @@ extern "C" qsl_status qsl_aggregate(qsl_ctx* ctx, const uint8_t* msg, const uint
   for (uint32_t q = 0; q < R; ++q)
     for (uint32_t p = 0; p < q; ++p)
       if (rows.row[p] == rows.row[q]) return QSL_ERR_INVALID_ARG;       // a message may be listed once
+  if (c.K == c.d && !is_qsgd(c.quantizer)) {        // k = d and nothing dropped: every message lists every coordinate
+    const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((c.d + BLOCK - 1) / BLOCK, 1u << 16));
+    k_aggregate_dense<<<dim3(blocks), BLOCK, 0, ctx->stream>>>(c, msg, rows, R, scale, accumulate, out);
+    QSL_HIP(hipGetLastError());
+    return QSL_OK;
+  }
   if (!accumulate) {
     const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((c.d + BLOCK * 4 - 1) / (BLOCK * 4), 1u << 16));
     k_fill_zero<<<dim3(blocks), BLOCK, 0, ctx->stream>>>(out, c.d);

@@ -184,6 +184,32 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(DevCtx c, const uint8_t* ms
   }
 }
 
+// The master line when every message holds every coordinate (an operator with k = d whose quantiser drops
+// nothing, e.g. the sign of the whole vector): entry j of a message is coordinate j, so the sum is a plain
+// pass over the coordinates, in the same list order and with the same roundings as k_aggregate.  An
+// all-zero (empty) message adds nothing; any other entry count is reported as a malformed message.
+__global__ __launch_bounds__(BLOCK) void k_aggregate_dense(DevCtx c, const uint8_t* msg, RowList rows, uint32_t R,
+                                                           float scale, int accumulate, float* out) {
+  const uint64_t stride = static_cast<uint64_t>(gridDim.x) * BLOCK;
+  for (uint64_t j = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x; j < c.d; j += stride) {
+    float acc = 0.0f;
+    bool first = true;
+    for (uint32_t p = 0; p < R; ++p) {
+      const MsgView v = view_msg(c, msg, rows.row[p]);
+      if (v.nnz != c.d) {
+        if (v.nnz != 0 && j == 0) atomicOr(c.status, 4u);
+        continue;
+      }
+      const float val = msg_value(c, v, static_cast<uint32_t>(j), static_cast<uint32_t>(j));
+      acc = first ? val : acc + val;
+      first = false;
+    }
+    const float term = scale * acc;
+    if (!first) out[j] = accumulate ? out[j] + term : term;
+    else if (!accumulate) out[j] = 0.0f;
+  }
+}
+
 __global__ void k_read_nnz(DevCtx c, const uint8_t* msg, uint32_t R, uint32_t* out) {
   const uint32_t r = blockIdx.x * blockDim.x + threadIdx.x;
   if (r < R) out[r] = reinterpret_cast<const uint32_t*>(msg + static_cast<uint64_t>(r) * c.cap_words * 4)[0];

@@ -25,7 +25,8 @@ constexpr uint32_t CTR_OVF = NSUB;         // counter NSUB: cursor of the unit's
 constexpr uint32_t CTR_FAIL = NSUB + 1;    // counter NSUB + 1: set when the overflow pool ran out
 constexpr uint32_t CTR_LINES = NSUB + 2;
 
-enum : uint32_t { PATH_FAST = 0, PATH_GENERAL = 1, PATH_FALLBACK = 2, PATH_SMALL = 3 };
+enum : uint32_t { PATH_FAST = 0, PATH_GENERAL = 1, PATH_FALLBACK = 2, PATH_SMALL = 3, PATH_FULL = 4 };
+constexpr uint32_t MAX_FULL_BLOCKS = 512;  // blocks per unit of k_full (each ends with up to 20 atomics on the unit's digit counters)
 constexpr uint32_t SMALL_CHUNKS = 4;       // a unit of at most 4 chunks (4096 coordinates) is selected by one block
 
 struct SegInfo {
@@ -39,7 +40,7 @@ struct SegInfo {
   uint32_t wc_base;      // first per-wave counter of this segment (per worker)
   uint32_t cb_base, ncb; // compaction blocks: index of the first one (per worker), how many
   uint32_t nsamp;        // blocks of this unit in the sampling kernel
-  uint32_t mode;         // PATH_FAST, PATH_GENERAL or PATH_SMALL, decided on the host from (size, k)
+  uint32_t mode;         // PATH_FAST, PATH_GENERAL, PATH_SMALL or PATH_FULL, decided on the host from (size, k)
   uint32_t lpc;          // slot size: lpc * 16 bytes per chunk (4: 64 bytes, 8: one 128-byte line, 16: two lines)
   uint32_t ovf_cap;      // entries of the overflow pool
   uint32_t n_runs;       // sample: runs of 64 consecutive coordinates
@@ -57,7 +58,7 @@ struct CbInfo { uint32_t seg, b, pad0, pad1; };                     // one compa
 // one launch start at different times: a field that a launch both reads and rewrites would show late
 // blocks the new value).
 struct UnitState {
-  uint32_t path;        // static: PATH_FAST, PATH_GENERAL or PATH_SMALL
+  uint32_t path;        // static: PATH_FAST, PATH_GENERAL, PATH_SMALL or PATH_FULL
   uint32_t T;           // guess key (k_sample_scan; static for Rand_k and for the general path)
   uint32_t cand;        // candidates collected (k_select<0>)
   uint32_t fell_back;   // 1: the guess failed, the unit runs the general path (k_select<0>)
@@ -73,6 +74,7 @@ struct DevCtx {
   const SegInfo* segs; const WtInfo* wts; const SelInfo* sels; const SelInfo* samps; const CbInfo* cbs;
   const uint32_t* fast_segs;
   const uint32_t* small_segs;
+  const SelInfo* fulls;     // one entry per block of k_full: (segment with k = size, block number)
   const uint32_t* big_segs; // the segments that are not selected by one block (they use histograms)
   const uint32_t* seg_dir;  // [ceil(d / 1024) + 1]: segment of coordinate t * 1024 (the last entry: L - 1)
   const uint32_t* slot_dir; // [ceil(K / 256) + 1]: segment of slot b * 256 of the selected arrays

@@ -518,6 +518,74 @@ __global__ __launch_bounds__(BLOCK) void k_small(DevCtx c, const float* v, uint3
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// units with k = size: every coordinate is selected, so there is nothing to search (the error-feedback
+// schemes without sparsification that Section 5 compares with, as this operator).  The blocks of a unit
+// copy contiguous ranges of 4096-coordinate tiles of v into the selected arrays -- position = coordinate --
+// and add the digits of the norm.
+// ------------------------------------------------------------------------------------------------
+typedef uint32_t u4u __attribute__((ext_vector_type(4), aligned(4)));
+
+__global__ __launch_bounds__(BLOCK) void k_full(DevCtx c, const float* v) {
+  __shared__ uint64_t acc[ACC_ROWS * (ACC_SLOTS + 1)];
+  const SelInfo si = c.fulls[blockIdx.x];
+  const uint32_t w = blockIdx.y;
+  const SegInfo sg = c.segs[si.seg];
+  const uint64_t u = static_cast<uint64_t>(w) * c.L + si.seg;
+  const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
+  uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
+  uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const bool squares = wants_squares(c.quantizer);
+  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
+  for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;
+  __syncthreads();
+  const uint64_t ntiles = (sg.size + 4095) / 4096;
+  const uint32_t nb = static_cast<uint32_t>(ntiles < MAX_FULL_BLOCKS ? ntiles : MAX_FULL_BLOCKS);
+  const uint64_t t_lo = ntiles * si.j / nb, t_hi = ntiles * (si.j + 1) / nb;
+  for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
+    f4u x[4];
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {                       // a wave instruction covers 1 KiB of the row
+      const uint64_t e = tile * 4096 + q * 1024 + threadIdx.x * 4;
+      x[q] = f4u{0.f, 0.f, 0.f, 0.f};
+      if (e + 4 <= sg.size) x[q] = *reinterpret_cast<const f4u*>(vp + e);
+      else {
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) if (e + j < sg.size) x[q][j] = vp[e + j];
+      }
+    }
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {
+      const uint64_t e = tile * 4096 + q * 1024 + threadIdx.x * 4;
+      const uint32_t i0 = static_cast<uint32_t>(sg.start + e);
+      u4u bits, idx;
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) { bits[j] = __float_as_uint(x[q][j]); idx[j] = i0 + j; }
+      if (e + 4 <= sg.size) {
+        *reinterpret_cast<u4u*>(oi + e) = idx;
+        *reinterpret_cast<u4u*>(ov + e) = bits;
+      } else {
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) if (e + j < sg.size) { oi[e + j] = idx[j]; ov[e + j] = bits[j]; }
+      }
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) if (e + j < sg.size) add_digits(mine, bits[j], squares);
+    }
+  }
+  __syncthreads();
+  uint64_t* ga = c.norm_acc + u * ACC_SLOTS;
+  for (uint32_t s = wave; s < ACC_SLOTS; s += BLOCK / 64) {
+    uint64_t x = lane < ACC_ROWS ? acc[lane * (ACC_SLOTS + 1) + s] : 0;
+    x = wave_sum64(x);
+    if (lane == 0 && x) atomicAdd(reinterpret_cast<unsigned long long*>(ga + s), static_cast<unsigned long long>(x));
+  }
+  if (threadIdx.x == 0 && si.j == 0) {
+    UnitState* us = &c.units[u];
+    us->cand = 0; us->fell_back = 0; us->tau = 0; us->need = 0; us->n_gt = sg.k; us->nnz = 0;
+  }
+}
+
 template <int SPARS>
 __global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round) {
   __shared__ uint32_t s_cnt[2 * GGROUP + 2], s_red[8], result[2];

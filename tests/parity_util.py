@@ -102,7 +102,7 @@ def run_parity(wl, rounds, flags=0, in_place=True, host_deltas=True, worker0=0, 
         paths.append(units[:, 0].copy())
         if expect_path is not None:
             assert np.all(units[:, 0] == expect_path), f"round {t}: paths {np.unique(units[:, 0])}, want {expect_path}"
-        print(f"  {wl.name} round {t}: parity ok, paths {np.bincount(units[:, 0], minlength=4).tolist()}, "
+        print(f"  {wl.name} round {t}: parity ok, paths {np.bincount(units[:, 0], minlength=5).tolist()}, "
               f"candidates {units[:, 1].max()}, nnz {[int(o['sel_level'].astype(bool).sum()) for o in want][:4]}",
               flush=True)
     return run, op, m_host, paths

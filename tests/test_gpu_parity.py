@@ -141,6 +141,8 @@ def test_degenerate_inputs(P, quantizer, s, k, flags, path):
     d = 4_001
     rng = np.random.default_rng(17)
     wl = custom(d, [0, d], [k], s, W.TOPK, quantizer, R=1)
+    if k == d and flags == 2:
+        path = 4                                     # nothing to select: not a case for the multi-pass kernels
     for name, v in _adversarial(d, rng):
         P.run_parity(wl, 1, deltas=[v[None, :].copy()], flags=flags, expect_path=path)
 
@@ -216,6 +218,46 @@ def test_d_equals_one_and_k_equals_d(P):
     want = op.aggregate(msgs, -1.0 / 3, worker_list=[2, 0], out=x0)
     mag = sum(np.abs(op.decode(msgs[r])[1].astype(np.float64)) for r in (2, 0))
     assert np.all(np.abs(out.cpu().numpy().astype(np.float64) - want) <= 1e-6 * (mag / 3 + np.abs(want)) + 1e-38)
+
+
+# k = size of the segment (the error-feedback schemes without sparsification that Section 5 compares with, as
+# this operator): no selection at all; ragged sizes around the 4096-coordinate tiles and the 512-block limit
+@pytest.mark.parametrize("sparsifier", [W.TOPK, W.RANDK])
+@pytest.mark.parametrize("quantizer,s", [(W.QSGD, 15), (W.SIGN_L1, 1), (W.SIGN_L2, 1), (W.FP32, 1), (W.QSGD_SCALED, 3)])
+def test_every_coordinate_kept(P, sparsifier, quantizer, s):
+    for d in (4_097, 300_001, 2_200_003):                        # 2, 74 and 538 tiles (more than the blocks of a unit)
+        wl = custom(d, [0, d], [d], s, sparsifier, quantizer, R=2)
+        run, op, m_host, _ = P.run_parity(wl, 2, expect_path=4)
+        if d == 300_001:
+            # the master line on messages that list every coordinate; the third listed row is an empty (all-zero) message
+            msgs = torch.cat([run.msg, torch.zeros_like(run.msg[:1])])
+            msgs_host = msgs.cpu().numpy()
+            x0 = np.random.default_rng(d).standard_normal(d).astype(f32)
+            for lst, accumulate in (([1, 0], False), ([0, 2, 1], True)):
+                out = torch.from_numpy(x0).to(run.q.device)
+                run.q.aggregate(msgs, out, -0.5, worker_list=lst, accumulate=accumulate)
+                torch.cuda.synchronize()
+                want = op.aggregate(msgs_host, -0.5, worker_list=lst, out=x0.copy() if accumulate else None)
+                mag = np.zeros(d)
+                for r in lst:
+                    i, vv = op.decode(msgs_host[r])
+                    mag[i] += np.abs(vv.astype(np.float64))
+                got = out.cpu().numpy().astype(np.float64)
+                assert np.all(np.abs(got - want) <= 1e-6 * (mag * 0.5 + np.abs(want)) + 1e-38)
+            from paper_1906_02367_amd import binding as B
+            assert run.q.device_status() == B.OK
+    # segments that keep everything beside segments that select, in one call; degenerate values
+    off = [0, 5_000, 70_000, 70_001, 400_000, 410_001, 1_100_000]
+    k = [5_000, 65_000, 1, 30_000, 10_001, 600]
+    wl = custom(1_100_000, off, k, s, sparsifier, quantizer, R=3)
+    run, op, m_host, paths = P.run_parity(wl, 2)
+    assert paths[0].reshape(3, 6)[0].tolist() == [4, 4, 3, 1, 4, 0], paths[0]
+    rng = np.random.default_rng(31)
+    d = 50_000
+    wl = custom(d, [0, d], [d], s, sparsifier, quantizer, R=1)
+    for name, v in _adversarial(d, rng):
+        P.run_parity(wl, 1, deltas=[v[None, :].copy()], expect_path=4)
+    P.run_parity(wl, 1, flags=1, expect_path=1)                   # the same through the multi-pass kernels
 
 
 # ---------------------------------------------------------------------------------------------
