@@ -62,7 +62,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (2 = headline)")
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (2 = headline); 6 = the paper's own per-tensor rule on ResNet-50's tensor table")
     ap.add_argument("--workers", type=int, default=0,
                     help="override the configuration's R (R = 1 is the deployment shape: one worker per GPU); "
                          "not the headline line")

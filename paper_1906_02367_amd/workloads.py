@@ -26,7 +26,7 @@ RESNET50_D = 25_557_032
 
 @dataclasses.dataclass
 class Workload:
-    cfg: int                 # 1..5, which benchmark configuration this derives from
+    cfg: int                 # 1..5, which benchmark configuration's input distribution this uses
     name: str
     R: int                   # simulated workers
     d: int                   # coordinates per worker
@@ -74,8 +74,28 @@ def segment_table(d: int, n_seg: int = 160, lo: float = 64.0, hi: float = 2.4e6,
     return off, k
 
 
+def resnet50_tensor_sizes() -> list:
+    """Sizes of the 161 trainable tensors of ResNet-50 (He et al., 2016; bottleneck blocks 3-4-6-3, 1000
+    classes), in layer order: the segment table the paper's ResNet-50 runs compress tensor by tensor
+    (Section 5.1.1).  They add up to 25,557,032, and the paper's rule k_t = min(d_t, 1000) gives 99,400
+    on them -- the total k that Section 5.1.1 prints."""
+    sizes = [64 * 3 * 7 * 7, 64, 64]                                 # stem convolution, its batch-norm scale and shift
+    inplanes = 64
+    for planes, blocks in ((64, 3), (128, 4), (256, 6), (512, 3)):
+        for b in range(blocks):
+            sizes += [planes * inplanes, planes, planes,             # 1x1 convolution + batch norm
+                      planes * planes * 9, planes, planes,           # 3x3
+                      4 * planes * planes, 4 * planes, 4 * planes]   # 1x1, widening
+            if b == 0:                                               # projection shortcut of the stage's first block
+                sizes += [4 * planes * inplanes, 4 * planes, 4 * planes]
+            inplanes = 4 * planes
+    sizes += [2048 * 1000, 1000]                                     # classifier weight and bias
+    return sizes
+
+
 def config(cfg: int, d: int | None = None, R: int | None = None, rounds: int | None = None) -> Workload:
-    """Benchmark configuration `cfg` (1..5).  `d`, `R`, `rounds` shrink it for quick tests; k scales with d."""
+    """Benchmark configuration `cfg` (1..5; 6 = the paper's own per-tensor rule on ResNet-50's tensor table).
+    `d`, `R`, `rounds` shrink it for quick tests; k scales with d."""
     if cfg == 1:
         d0, R0, T0 = 65_536, 2, 10
         dd = d or d0
@@ -102,8 +122,18 @@ def config(cfg: int, d: int | None = None, R: int | None = None, rounds: int | N
         dd = d or d0
         off, k = _one_segment(dd, max(1, round(dd * 26_844 / d0)))
         wl = Workload(5, "cfg5_large_top0.01pct_qsgd256", R or R0, dd, off, k, 256, TOPK, QSGD, rounds or T0)
+    elif cfg == 6:
+        # the paper's own ResNet-50 setting (Section 5.1.1): every tensor compressed on its own with
+        # k_t = min(d_t, 1000), 8 workers, SignTop_k; inputs as for configuration 4 (one scale per tensor)
+        if d is not None:
+            raise ValueError("configuration 6 has ResNet-50's own tensor table; d cannot be changed")
+        sizes = np.array(resnet50_tensor_sizes(), dtype=np.int64)
+        off = np.zeros(sizes.size + 1, dtype=np.uint64)
+        off[1:] = np.cumsum(sizes).astype(np.uint64)
+        k = np.minimum(sizes, 1000).astype(np.uint32)
+        wl = Workload(4, "cfg6_resnet50_k_min_d_1000_sign", R or 8, RESNET50_D, off, k, 1, TOPK, SIGN_L1, rounds or 20)
     else:
-        raise ValueError("cfg must be 1..5")
+        raise ValueError("cfg must be 1..6")
     return wl
 
 
@@ -129,7 +159,7 @@ _sigma_cache: dict = {}
 
 def delta(wl: Workload, rnd: int, worker: int) -> np.ndarray:
     """Delta of one worker at one sync round, float32 [d]."""
-    key = (wl.cfg, wl.d)
+    key = (wl.cfg, wl.d, wl.L)
     if key not in _sigma_cache:
         _sigma_cache.clear()
         _sigma_cache[key] = _sigma(wl)

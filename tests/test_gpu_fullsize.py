@@ -14,7 +14,7 @@ def P():
     return parity_util
 
 
-@pytest.mark.parametrize("cfg,rounds", [(2, 20), (3, 20), (4, 20), (5, 5)])
+@pytest.mark.parametrize("cfg,rounds", [(2, 20), (3, 20), (4, 20), (5, 5), (6, 5)])
 def test_full_size_config(P, cfg, rounds):
     wl = W.config(cfg)
     print(f"\n[{wl.name}] R={wl.R} d={wl.d} K={wl.K} L={wl.L}", flush=True)

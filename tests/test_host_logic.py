@@ -128,6 +128,17 @@ def test_workload_tables():
     assert np.array_equal(a.seg_offset, b.seg_offset)
 
 
+def test_resnet50_tensor_table_gives_the_total_k_the_paper_prints():
+    """Section 5.1.1: k_t = min(d_t, 1000) for each tensor of ResNet-50 gives a total of k = 99,400."""
+    sizes = W.resnet50_tensor_sizes()
+    assert len(sizes) == 161 and sum(sizes) == 25_557_032
+    assert sum(min(n, 1000) for n in sizes) == 99_400
+    wl = W.config(6)
+    assert wl.L == 161 and wl.K == 99_400 and wl.d == 25_557_032 and wl.R == 8
+    assert np.array_equal(np.diff(wl.seg_offset.astype(np.int64)), np.array(sizes))
+    assert wl.sparsifier == W.TOPK and wl.quantizer == W.SIGN_L1
+
+
 def test_host_generators_are_deterministic_and_shaped():
     wl = W.config(2, d=10_000, R=3)
     a = W.delta_all(wl, 4)
