@@ -13,12 +13,13 @@
 //                bits, over the candidates -- or over the whole vector when the guess failed or the
 //                unit is too dense for guessing (the general path; always exact)
 //   k_small      a unit of at most 4 chunks: selection, ordered compaction and norm by one block
+//   k_full       a unit with k = size: nothing to select, the coordinates are copied in order
 //   k_tile_count / k_tile_write    ordered compaction of the selected coordinates, ties to the lower index
 //                (k_tile_write also accumulates the exact ||v_S||_2^2 or ||v_S||_1: proof of Lemma 1; Lemma 3, m = 1)
 //   k_quantize   QSGD levels (Definition 1, example 1) or signs (Definition 2); error update
 //                m <- v - g on the transmitted coordinates (Algorithm 1, worker line 2)
 //   k_surv_compact, k_pack    the packed message
-//   k_aggregate  master line of Algorithm 1, atomic-free
+//   k_aggregate  master line of Algorithm 1, atomic-free (k_aggregate_dense when every message lists every coordinate)
 //
 // A "unit" is one (worker, segment) pair: the operator is applied independently to each unit
 // (Corollary 1).  Rank key: Top_k: magnitude bits of v shifted left by one; Rand_k: the
