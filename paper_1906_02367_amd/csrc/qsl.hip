@@ -542,14 +542,16 @@ extern "C" qsl_status qsl_aggregate(qsl_ctx* ctx, const uint8_t* msg, const uint
     const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((c.d + BLOCK * 4 - 1) / (BLOCK * 4), 1u << 16));
     k_fill_zero<<<dim3(blocks), BLOCK, 0, ctx->stream>>>(out, c.d);
   }
-  const uint32_t tiles = (c.K + AGG_ENTRIES - 1) / AGG_ENTRIES;
-  // a block per expected tile, but no more than 8192 blocks in all: beyond that the launch of the waves costs more
-  // than walking a few tiles per block (8 long messages of 99,400 entries: 24,800 blocks 118 us, 8192 blocks 104 us)
-  const uint32_t agg_blocks = std::min(std::min(tiles, std::max(16u, (ctx->nnz_hint + AGG_ENTRIES - 1) / AGG_ENTRIES)),
-                                       std::max(16u, 8192u / R));
-  uint32_t* dir = R > 1 ? ctx->agg_dir : nullptr;
-  if (dir) k_msg_directory<<<dim3(std::min(2048u, (c.K + BLOCK - 1) / BLOCK), R), BLOCK, 0, ctx->stream>>>(c, msg, rows, dir, ctx->agg_ndir);
-  k_aggregate<<<dim3(agg_blocks, R), BLOCK, 0, ctx->stream>>>(c, msg, rows, R, scale, accumulate, out, dir, ctx->agg_ndir);
+  uint32_t* dir = R > 1 ? ctx->agg_dir : nullptr;   // allocated at qsl_create for operators whose messages are long
+  if (dir) {                                        // long messages: a thread per entry, searches narrowed by the directories
+    k_msg_directory<<<dim3(std::min(2048u, (c.K + BLOCK - 1) / BLOCK), R), BLOCK, 0, ctx->stream>>>(c, msg, rows, dir, ctx->agg_ndir);
+    const uint32_t eb = std::min((c.K + BLOCK - 1) / BLOCK, std::max(4u, (ctx->nnz_hint + BLOCK - 1) / BLOCK));
+    k_aggregate_entries<<<dim3(eb, R), BLOCK, 0, ctx->stream>>>(c, msg, rows, R, scale, accumulate, out, dir, ctx->agg_ndir);
+  } else {                                          // short messages: 8 threads per entry, a block per expected tile of 32
+    const uint32_t tiles = (c.K + AGG_ENTRIES - 1) / AGG_ENTRIES;
+    const uint32_t agg_blocks = std::min(tiles, std::max(16u, (ctx->nnz_hint + AGG_ENTRIES - 1) / AGG_ENTRIES));
+    k_aggregate<<<dim3(agg_blocks, R), BLOCK, 0, ctx->stream>>>(c, msg, rows, R, scale, accumulate, out);
+  }
   QSL_HIP(hipGetLastError());
   return QSL_OK;
 }
