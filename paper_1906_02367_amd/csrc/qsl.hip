@@ -207,11 +207,15 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
         // candidates ~ alpha k; the sample must hold enough of them for the guess to sit below the
         // true threshold with ~6.5 sigma: (alpha - 1) sqrt(n_s p) >= 6.5 sqrt(alpha)
         // (a small unit has a small k, so a generous alpha costs few candidates and saves most of the sample)
+        // The candidates of a chunk must fit its slot (at most 31, with 4 sigma to spare): a chunk with more sends all
+        // of them through the overflow pool, which the selection kernels read entry by entry -- a unit where most
+        // chunks do that (k = 1000 of 65,536 with alpha = 3: 47 per chunk) is far slower than on the multi-pass path.
+        auto fits = [&](double alpha) { const double pc = alpha * sg.k / sg.nwt; return pc + 4.0 * std::sqrt(pc) <= 31.0; };
         const double alphas[10] = {1.5, 2.0, 3.0, 4.0, 6.0, 8.0, 12.0, 16.0, 24.0, 32.0};
         for (double frac : {1.0 / 16, 1.0 / 4}) {
           for (double alpha : alphas) {
             const double n_s = 42.25 * alpha / ((alpha - 1) * (alpha - 1) * p);
-            if (n_s > n * frac) continue;
+            if (n_s > n * frac || !fits(alpha)) continue;
             sg.n_runs = static_cast<uint32_t>(std::ceil(n_s / 64.0));
             sg.samp_stride = static_cast<uint32_t>(sg.size / sg.n_runs);
             sg.r_s = static_cast<uint32_t>(std::ceil(alpha * (sg.n_runs * 64.0) * p));
@@ -222,7 +226,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
           }
           if (cand != 0) break;
         }
-        if (cand == 0) {
+        if (cand == 0 && fits(2.0)) {
           // no sample of at most 1/4 of the unit is reliable: read all of it (k * 64 <= size, so there are
           // at least 4 k groups of 16); the candidates are the k largest, the few more down to the k-th
           // largest group maximum, and the rest of the histogram bin (1/8 of a binade) that falls in
@@ -233,10 +237,12 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
           cand = 2.0 * sg.k;
           slack = 2048.0;
         }
-        sg.d0_cap = static_cast<uint32_t>(std::min<double>(n, 4.0 * cand + slack));
-        sg.mode = PATH_FAST;
-        ++ctx->n_sampled;
-        for (uint32_t j = 0; j < sg.nsamp; ++j) { SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0; samps.push_back(si); }
+        if (cand != 0) {                            // else: too dense for the slots, the unit takes the multi-pass kernels
+          sg.d0_cap = static_cast<uint32_t>(std::min<double>(n, 4.0 * cand + slack));
+          sg.mode = PATH_FAST;
+          ++ctx->n_sampled;
+          for (uint32_t j = 0; j < sg.nsamp; ++j) { SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0; samps.push_back(si); }
+        }
       } else if (cfg->sparsifier == QSL_RANDK && static_cast<uint64_t>(sg.k) * 16 <= sg.size) {
         // the keys are uniform 32-bit words: keep those above the (1 - q) quantile, q = p + 7 sigma
         const double q = p + 7.0 * std::sqrt(p * (1 - p) / n);

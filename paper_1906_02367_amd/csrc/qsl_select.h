@@ -321,6 +321,9 @@ __device__ void general_groups(const SegInfo& sg, const float* vp, const RandKey
                                uint32_t g_lo, uint32_t g_hi, uint32_t gt0, uint32_t eq0, uint32_t* oi, uint32_t* ov,
                                uint64_t* mine, bool squares, uint32_t* s_cnt /*[2][GGROUP + 1]*/,
                                uint32_t* tot_gt, uint32_t* tot_eq) {
+  constexpr uint32_t STAGE = 512;                  // list entries per wave (WRITE only)
+  __shared__ uint32_t stage_pos[WRITE ? (BLOCK / 64) * STAGE : 1];
+  __shared__ uint2 stage_iv[WRITE ? (BLOCK / 64) * STAGE : 1];
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   uint32_t run_gt = gt0, run_eq = eq0;             // ranks at the start of the current group (all threads agree)
   for (uint32_t g = g_lo; g < g_hi; ++g) {
@@ -345,6 +348,22 @@ __device__ void general_groups(const SegInfo& sg, const float* vp, const RandKey
     }
     __syncthreads();
     if (WRITE) {
+      // The selected coordinates are few per lane (a dense k is still a few per cent), so a loop that stores and
+      // adds digits where it finds one runs its body once per element position with one or two lanes active.
+      // The lanes park what they find in a list of the wave instead (rank, coordinate, value); the list is
+      // then worked off 64 entries at a time by all lanes.
+      uint32_t staged = 0;                                            // entries in the wave's list (wave-uniform)
+      auto flush = [&]() {
+        for (uint32_t o = 0; o < staged; o += 64) {
+          if (o + lane < staged) {
+            const uint32_t pos = stage_pos[wave * STAGE + o + lane];
+            const uint2 e = stage_iv[wave * STAGE + o + lane];
+            oi[pos] = e.x; ov[pos] = e.y;
+            add_digits(mine, e.y, squares);
+          }
+        }
+        staged = 0;
+      };
 #pragma unroll
       for (uint32_t q = 0; q < 4; ++q) {
         if (__ballot((gm[q] | qm[q]) != 0) == 0) continue;          // wave-uniform
@@ -362,20 +381,25 @@ __device__ void general_groups(const SegInfo& sg, const float* vp, const RandKey
             bg += popc_below(b1); tg += __popcll(b1); bq += popc_below(b2); tq += __popcll(b2);
           }
           uint32_t my_gt = base_gt + bg, my_eq = base_eq + bq;
+          if (staged + 256 > STAGE) flush();                         // room for the 4 x 64 elements of this step
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             const bool is_gt = (gn >> j) & 1u, is_eq = (qn >> j) & 1u;
-            if (is_gt || (is_eq && my_eq < th.need)) {
-              const uint32_t pos = my_gt + min(my_eq, th.need);
-              const uint32_t bits = __float_as_uint(val[q][t][j]);
-              oi[pos] = static_cast<uint32_t>(sg.start + cb + t * 256 + lane * 4 + j); ov[pos] = bits;
-              add_digits(mine, bits, squares);
+            const bool take = is_gt || (is_eq && my_eq < th.need);
+            const uint64_t tb = __ballot(take);
+            if (take) {
+              const uint32_t slot = wave * STAGE + staged + popc_below(tb);
+              stage_pos[slot] = my_gt + min(my_eq, th.need);
+              stage_iv[slot] = make_uint2(static_cast<uint32_t>(sg.start + cb + t * 256 + lane * 4 + j),
+                                          __float_as_uint(val[q][t][j]));
             }
+            staged += static_cast<uint32_t>(__popcll(tb));
             my_gt += is_gt; my_eq += is_eq;
           }
           base_gt += tg; base_eq += tq;
         }
       }
+      flush();
     }
     run_gt = s_cnt[GGROUP]; run_eq = s_cnt[2 * GGROUP + 1];
     __syncthreads();                               // s_cnt is reused by the next group
