@@ -175,13 +175,19 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, SegInfo one, const flo
             if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
             if (LEVEL == 1) { d0[pos] = make_uint2(r.idx1, r.bits1); if (SPARS == QSL_RANDK) d0k[pos] = key; }
           }
-        } else {
-          for (uint32_t e = 0; e < r.count; ++e) {
-            const uint2 ent = ovf[r.ovf_at + e];
-            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(ent.y) : ovf_key[r.ovf_at + e];
+        }
+        // chunks whose candidates went to the overflow pool: the whole wave reads each one's entries, 64 at a time
+        // (one lane walking them alone was the last wave to finish whenever a chunk had spilled)
+        for (uint64_t spilled = __ballot(r.spill); spilled; spilled &= spilled - 1) {
+          const int holder = __ffsll(static_cast<unsigned long long>(spilled)) - 1;
+          const uint32_t cnt = __shfl(r.count, holder, WAVE), at = __shfl(r.ovf_at, holder, WAVE);
+          const uint32_t first = __shfl(pos, holder, WAVE);
+          for (uint32_t e = lane; e < cnt; e += WAVE) {
+            const uint2 ent = ovf[at + e];
+            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(ent.y) : ovf_key[at + e];
             uint32_t bin;
             if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
-            if (LEVEL == 1) { d0[pos + e] = ent; if (SPARS == QSL_RANDK) d0k[pos + e] = key; }
+            if (LEVEL == 1) { d0[first + e] = ent; if (SPARS == QSL_RANDK) d0k[first + e] = key; }
           }
         }
       }
