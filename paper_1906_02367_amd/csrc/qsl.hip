@@ -300,6 +300,22 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
     sg.cb_base = static_cast<uint32_t>(cbs.size());
     for (uint32_t b = 0; b < sg.ncb; ++b) { CbInfo ci; ci.seg = l; ci.b = b; ci.pad0 = ci.pad1 = 0; cbs.push_back(ci); }
   }
+  // The launch lists in decreasing order of a block's work: the blocks of a kernel start over several microseconds
+  // (the waves of a few hundred 1024-thread blocks), and the kernel ends when the slowest block does, so the heavy
+  // blocks go first.  A multi-pass block weighs its chunks (every coordinate meets an LDS atomic), a guessing block
+  // its slot rows, a compaction block of the dense list one tile.
+  auto select_cost = [&](const SelInfo& si) {
+    const SegInfo& sg = segs[si.seg];
+    if (sg.mode == PATH_FAST) return 1.2 * static_cast<double>((static_cast<uint64_t>(sg.nwt) * sg.lpc + 63) / 64) / sg.nsel / 16.0;
+    return 0.8 * static_cast<double>(sg.nwt) / sg.nsel;
+  };
+  std::stable_sort(sels.begin(), sels.end(), [&](const SelInfo& a, const SelInfo& b) { return select_cost(a) > select_cost(b); });
+  auto compact_cost = [&](const CbInfo& ci) {
+    const SegInfo& sg = segs[ci.seg];
+    if (sg.mode == PATH_FAST) return 1.0;
+    return 16.0 * std::max(1.0, static_cast<double>((sg.nwt + GGROUP - 1) / GGROUP) / sg.ncb);
+  };
+  std::stable_sort(cbs.begin(), cbs.end(), [&](const CbInfo& a, const CbInfo& b) { return compact_cost(a) > compact_cost(b); });
   ctx->nsamp_blocks = static_cast<uint32_t>(samps.size());
   const uint32_t NWT = static_cast<uint32_t>(nwt64);
   const uint32_t NSEL = static_cast<uint32_t>(sels.size()), NCB = static_cast<uint32_t>(cbs.size());
@@ -469,12 +485,13 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
 
   if (ctx->nsmall) k_small<SPARS><<<dim3(ctx->nsmall, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
   if (ctx->nfull_blocks) k_full<<<dim3(ctx->nfull_blocks, R), BLOCK, 0, st>>>(c, m_out);
+  if (static_cast<uint64_t>(std::max(c.NSEL, c.NCB)) * R > 0x7FFFFFFFull) return QSL_ERR_UNSUPPORTED;   // one-dimensional grids
   if (c.NSEL) {                                    // units that take a launch per digit and two for the compaction
-    k_select<0, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round);
-    k_select<1, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round);
-    k_select<2, SPARS><<<dim3(c.NSEL, R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round);
-    k_tile_count<SPARS><<<dim3(c.NCB, R), BLOCK, 0, st>>>(c, ctx->segs[0], m_out, worker0, round);
-    k_tile_write<SPARS><<<dim3(c.NCB, R), BLOCK, 0, st>>>(c, ctx->segs[0], m_out, worker0, round);
+    k_select<0, SPARS><<<dim3(c.NSEL * R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
+    k_select<1, SPARS><<<dim3(c.NSEL * R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
+    k_select<2, SPARS><<<dim3(c.NSEL * R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
+    k_tile_count<SPARS><<<dim3(c.NCB * R), BLOCK, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
+    k_tile_write<SPARS><<<dim3(c.NCB * R), BLOCK, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
   }
   k_quantize<<<dim3(c.QB, R), BLOCK, 0, st>>>(c, m_out, worker0, round, sel_idx, sel_level);
   if (is_qsgd(c.quantizer)) {                      // the other quantisers send every selected coordinate: k_quantize wrote the final arrays

@@ -82,14 +82,17 @@ __device__ __forceinline__ bool level_bin(uint32_t key, uint32_t prefix, uint32_
 //   fast unit, digit 2: reads the dense list;
 //   general path:       reads v.
 template <int LEVEL, int SPARS>
-__global__ __launch_bounds__(BIG) void k_select(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round) {
+__global__ __launch_bounds__(BIG) void k_select(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round,
+                                                uint32_t R) {
   __shared__ uint32_t lh[HBINS];
   __shared__ uint64_t scratch[17];
   __shared__ uint32_t result[2], s_ctr[CTR_LINES];
   // a single-segment context carries its plan in the kernel arguments: one dependent load less per block
-  SelInfo si; si.seg = 0; si.j = blockIdx.x;
-  if (c.L != 1) si = c.sels[blockIdx.x];
-  const uint32_t w = blockIdx.y;
+  // one-dimensional grid, the workers innermost: the blocks of the plan's list start in list order (heaviest
+  // first) for all workers alike, instead of worker after worker
+  const uint32_t li = blockIdx.x / R, w = blockIdx.x % R;
+  SelInfo si; si.seg = 0; si.j = li;
+  if (c.L != 1) si = c.sels[li];
   const SegInfo sg = c.L == 1 ? one : c.segs[si.seg];
   const uint64_t u = static_cast<uint64_t>(w) * c.L + si.seg;
   UnitState* usp = &c.units[u];
@@ -617,12 +620,13 @@ __global__ __launch_bounds__(BLOCK) void k_full(DevCtx c, const float* v) {
 }
 
 template <int SPARS>
-__global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round) {
+__global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round,
+                                                      uint32_t R) {
   __shared__ uint32_t s_cnt[2 * GGROUP + 2], s_red[8], result[2];
   __shared__ uint64_t scratch[17];
-  CbInfo cb; cb.seg = 0; cb.b = blockIdx.x;
-  if (c.L != 1) cb = c.cbs[blockIdx.x];
-  const uint32_t w = blockIdx.y;
+  const uint32_t li = blockIdx.x / R, w = blockIdx.x % R;             // workers innermost, as in k_select
+  CbInfo cb; cb.seg = 0; cb.b = li;
+  if (c.L != 1) cb = c.cbs[li];
   const SegInfo sg = c.L == 1 ? one : c.segs[cb.seg];
   const uint64_t u = static_cast<uint64_t>(w) * c.L + cb.seg;
   const UnitState us = c.units[u];
@@ -662,13 +666,14 @@ __global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, SegInfo one, con
 }
 
 template <int SPARS>
-__global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round) {
+__global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round,
+                                                      uint32_t R) {
   __shared__ uint64_t acc[ACC_ROWS * (ACC_SLOTS + 1)];      // a row per 8 lanes of a wave: short atomic queues
   __shared__ uint32_t s_cnt[2 * GGROUP + 2];
   __shared__ uint64_t scratch[17], s_part[4];
-  CbInfo cb; cb.seg = 0; cb.b = blockIdx.x;
-  if (c.L != 1) cb = c.cbs[blockIdx.x];
-  const uint32_t w = blockIdx.y;
+  const uint32_t li = blockIdx.x / R, w = blockIdx.x % R;             // workers innermost, as in k_select
+  CbInfo cb; cb.seg = 0; cb.b = li;
+  if (c.L != 1) cb = c.cbs[li];
   const SegInfo sg = c.L == 1 ? one : c.segs[cb.seg];
   const uint64_t u = static_cast<uint64_t>(w) * c.L + cb.seg;
   const UnitState us = c.units[u];
