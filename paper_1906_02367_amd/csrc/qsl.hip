@@ -316,6 +316,13 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
     return 16.0 * std::max(1.0, static_cast<double>((sg.nwt + GGROUP - 1) / GGROUP) / sg.ncb);
   };
   std::stable_sort(cbs.begin(), cbs.end(), [&](const CbInfo& a, const CbInfo& b) { return compact_cost(a) > compact_cost(b); });
+  // a sample block's work: its share of the unit's runs (or chunks, when the whole unit is read); a small unit's: its size
+  auto sample_cost = [&](const SelInfo& si) {
+    const SegInfo& sg = segs[si.seg];
+    return (sg.samp_stride == 64 ? 16.0 * sg.nwt : static_cast<double>(sg.n_runs)) / sg.nsamp;
+  };
+  std::stable_sort(samps.begin(), samps.end(), [&](const SelInfo& a, const SelInfo& b) { return sample_cost(a) > sample_cost(b); });
+  std::stable_sort(smalls.begin(), smalls.end(), [&](uint32_t a, uint32_t b) { return segs[a].size > segs[b].size; });
   ctx->nsamp_blocks = static_cast<uint32_t>(samps.size());
   const uint32_t NWT = static_cast<uint32_t>(nwt64);
   const uint32_t NSEL = static_cast<uint32_t>(sels.size()), NCB = static_cast<uint32_t>(cbs.size());
@@ -458,8 +465,10 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
                                   uint16_t* sel_level) {
   const DevCtx& c = ctx->dc;
   hipStream_t st = ctx->stream;
+  if (static_cast<uint64_t>(std::max(std::max(c.NSEL, c.NCB), std::max(ctx->nsamp_blocks, ctx->nsmall))) * R > 0x7FFFFFFFull)
+    return QSL_ERR_UNSUPPORTED;                    // the list kernels use one-dimensional grids of (list entries x workers)
   if (SPARS == QSL_TOPK && ctx->n_sampled > 0) {
-    k_sample<<<dim3(ctx->nsamp_blocks, R), BIG, 0, st>>>(c, m, delta, xm);
+    k_sample<<<dim3(ctx->nsamp_blocks * R), BIG, 0, st>>>(c, m, delta, xm, R);
     k_sample_scan<<<dim3(c.nfast, R), BIG, 0, st>>>(c);
   }
   const bool timed = ctx->timing != 0;
@@ -483,9 +492,8 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   }
   if (timed) { QSL_HIP(hipEventRecord(ctx->ev[ctx->ev_used + 1], st)); ctx->ev_used += 2; }
 
-  if (ctx->nsmall) k_small<SPARS><<<dim3(ctx->nsmall, R), BLOCK, 0, st>>>(c, m_out, worker0, round);
+  if (ctx->nsmall) k_small<SPARS><<<dim3(ctx->nsmall * R), BLOCK, 0, st>>>(c, m_out, worker0, round, R);
   if (ctx->nfull_blocks) k_full<<<dim3(ctx->nfull_blocks, R), BLOCK, 0, st>>>(c, m_out);
-  if (static_cast<uint64_t>(std::max(c.NSEL, c.NCB)) * R > 0x7FFFFFFFull) return QSL_ERR_UNSUPPORTED;   // one-dimensional grids
   if (c.NSEL) {                                    // units that take a launch per digit and two for the compaction
     k_select<0, SPARS><<<dim3(c.NSEL * R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
     k_select<1, SPARS><<<dim3(c.NSEL * R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);

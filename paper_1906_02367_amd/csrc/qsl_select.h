@@ -452,12 +452,12 @@ __device__ __forceinline__ void small_hist(const uint32_t (&kv)[16], uint32_t n,
 }
 
 template <int SPARS>
-__global__ __launch_bounds__(BLOCK) void k_small(DevCtx c, const float* v, uint32_t worker0, uint64_t round) {
+__global__ __launch_bounds__(BLOCK) void k_small(DevCtx c, const float* v, uint32_t worker0, uint64_t round, uint32_t R) {
   __shared__ uint32_t lh[HBINS];
   __shared__ uint64_t acc[ACC_ROWS * (ACC_SLOTS + 1)];
   __shared__ uint64_t scratch[17];
   __shared__ uint32_t result[2];
-  const uint32_t seg = c.small_segs[blockIdx.x], w = blockIdx.y;
+  const uint32_t seg = c.small_segs[blockIdx.x / R], w = blockIdx.x % R;      // workers innermost, largest units first
   const SegInfo sg = c.segs[seg];
   const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
   const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;

@@ -30,10 +30,10 @@ __global__ void k_init(DevCtx c, uint32_t U) {
 // can never lie above the k-th largest key.
 // ------------------------------------------------------------------------------------------------
 // With `xm` given, `delta` holds the local models and Delta = xm - delta is formed on the fly.
-__global__ __launch_bounds__(BIG) void k_sample(DevCtx c, const float* m, const float* delta, const float* xm) {
+__global__ __launch_bounds__(BIG) void k_sample(DevCtx c, const float* m, const float* delta, const float* xm, uint32_t R) {
   __shared__ uint32_t lh[HBINS];
-  const SelInfo si = c.samps[blockIdx.x];
-  const uint32_t seg = si.seg, w = blockIdx.y;
+  const SelInfo si = c.samps[blockIdx.x / R];            // one-dimensional grid, workers innermost, largest samples first
+  const uint32_t seg = si.seg, w = blockIdx.x % R;
   const SegInfo sg = c.segs[seg];
   for (uint32_t i = threadIdx.x; i < HBINS; i += BIG) lh[i] = 0;
   __syncthreads();
