@@ -88,6 +88,13 @@ enum {
                                  instead of the one-block selection (testing, comparison)               */
 };
 
+/* Which way each segment of an operator will take through the selection -- the `path` that qsl_debug_units
+ * reports, before any failed guess: 0 = single-pass with a guessed threshold, 1 = multi-pass, 3 = one block,
+ * 4 = no selection (k = size).  The decision depends on (size, k, sparsifier, flags) only; qsl_create makes it
+ * with the same code.  Needs no context and no GPU.
+ *   cfg host; path_out host, uint32 [num_segments] */
+qsl_status qsl_plan_paths(const qsl_config *cfg, uint32_t *path_out);
+
 /* Create a context for one operator on the current HIP device.  `hip_stream` is a hipStream_t
  * (NULL = the default stream).  Allocates all scratch memory.  */
 qsl_status qsl_create(qsl_ctx **out, const qsl_config *cfg, void *hip_stream);

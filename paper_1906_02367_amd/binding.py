@@ -55,13 +55,14 @@ def _load():
     lib.qsl_timing_enable.argtypes = [vp, C.c_int]; lib.qsl_timing_enable.restype = C.c_int
     lib.qsl_timing_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(u32)]; lib.qsl_timing_read.restype = C.c_int
     lib.qsl_bits_index_free.argtypes = [C.POINTER(_Config), C.POINTER(u64)]; lib.qsl_bits_index_free.restype = C.c_int
+    lib.qsl_plan_paths.argtypes = [C.POINTER(_Config), C.POINTER(u32)]; lib.qsl_plan_paths.restype = C.c_int
     return lib
 
 
 _lib = _load()
 
 EXPORTED = ["qsl_create", "qsl_destroy", "qsl_set_stream", "qsl_msg_capacity_bytes", "qsl_compress",
-            "qsl_compress_diff", "qsl_error_update", "qsl_aggregate", "qsl_bits_sent", "qsl_bits_index_free",
+            "qsl_compress_diff", "qsl_error_update", "qsl_aggregate", "qsl_bits_sent", "qsl_bits_index_free", "qsl_plan_paths",
             "qsl_device_status", "qsl_debug_units",
             "qsl_timing_enable", "qsl_timing_read", "qsl_status_string"]
 
@@ -92,6 +93,17 @@ def bits_index_free(d, seg_offset, seg_k, s, sparsifier, quantizer):
     bits = C.c_uint64(0)
     _check(_lib.qsl_bits_index_free(C.byref(cfg), C.byref(bits)), "qsl_bits_index_free")
     return int(bits.value)
+
+
+def plan_paths(d, seg_offset, seg_k, s, sparsifier, quantizer, flags=0):
+    """`qsl_plan_paths`: the selection path of every segment (host only, no GPU needed)."""
+    off = np.ascontiguousarray(seg_offset, dtype=np.uint64)
+    k = np.ascontiguousarray(seg_k, dtype=np.uint32)
+    cfg = _Config(int(d), int(k.size), off.ctypes.data_as(C.POINTER(C.c_uint64)), k.ctypes.data_as(C.POINTER(C.c_uint32)),
+                  int(s), int(sparsifier), int(quantizer), 0, 1, int(flags))
+    out = np.zeros(k.size, dtype=np.uint32)
+    _check(_lib.qsl_plan_paths(C.byref(cfg), out.ctypes.data_as(C.POINTER(C.c_uint32))), "qsl_plan_paths")
+    return out
 
 
 class Qsl:

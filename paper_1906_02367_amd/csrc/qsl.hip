@@ -135,6 +135,87 @@ extern "C" qsl_status qsl_bits_index_free(const qsl_config* cfg, uint64_t* bits)
   return QSL_OK;
 }
 
+// Which way a segment goes through the selection, decided from (size, k, sparsifier, flags) alone; fills the fields of
+// the plan that follow from that decision (sample layout, static guess, room for candidates) and returns the expected
+// number of candidates of a guessing unit (0 otherwise).  sg.size, sg.k and sg.nwt are set by the caller.
+static double plan_segment(const qsl_config* cfg, SegInfo& sg) {
+  sg.mode = (sg.nwt <= SMALL_CHUNKS && !(cfg->flags & QSL_FLAG_NO_SMALL_PATH)) ? PATH_SMALL : PATH_GENERAL;
+  // k = size: nothing to select (unless the caller asks for the multi-pass kernels only)
+  if (sg.mode != PATH_SMALL && sg.k == sg.size && !(cfg->flags & QSL_FLAG_NO_FAST_PATH)) sg.mode = PATH_FULL;
+  sg.T_static = 0xFFFFFFFFu;
+  sg.lpc = 8;
+  const double n = static_cast<double>(sg.size), p = static_cast<double>(sg.k) / n;
+  double cand = 0, slack = 0;                     // expected number of candidates, room beyond 4x that
+  if (!(cfg->flags & QSL_FLAG_NO_FAST_PATH) && sg.nwt > SMALL_CHUNKS && sg.mode != PATH_FULL) {
+    if (cfg->sparsifier == QSL_TOPK && static_cast<uint64_t>(sg.k) * 64 <= sg.size) {
+      // candidates ~ alpha k; the sample must hold enough of them for the guess to sit below the
+      // true threshold with ~6.5 sigma: (alpha - 1) sqrt(n_s p) >= 6.5 sqrt(alpha)
+      // (a small unit has a small k, so a generous alpha costs few candidates and saves most of the sample)
+      // The candidates of a chunk must fit its slot (at most 31, with 4 sigma to spare): a chunk with more sends all
+      // of them through the overflow pool, which the selection kernels read entry by entry -- a unit where most
+      // chunks do that (k = 1000 of 65,536 with alpha = 3: 47 per chunk) is far slower than on the multi-pass path.
+      auto fits = [&](double alpha) { const double pc = alpha * sg.k / sg.nwt; return pc + 4.0 * std::sqrt(pc) <= 31.0; };
+      const double alphas[10] = {1.5, 2.0, 3.0, 4.0, 6.0, 8.0, 12.0, 16.0, 24.0, 32.0};
+      for (double frac : {1.0 / 16, 1.0 / 4}) {
+        for (double alpha : alphas) {
+          const double n_s = 42.25 * alpha / ((alpha - 1) * (alpha - 1) * p);
+          if (n_s > n * frac || !fits(alpha)) continue;
+          sg.n_runs = static_cast<uint32_t>(std::ceil(n_s / 64.0));
+          sg.samp_stride = static_cast<uint32_t>(sg.size / sg.n_runs);
+          sg.r_s = static_cast<uint32_t>(std::ceil(alpha * (sg.n_runs * 64.0) * p));
+          sg.nsamp = std::min(MAX_SAMPLE_BLOCKS, std::max(1u, (sg.n_runs + 127) / 128));   // 8 runs per wave, all in flight
+          cand = alpha * sg.k;
+          slack = alpha <= 4.0 ? 8192.0 : 2048.0;
+          break;
+        }
+        if (cand != 0) break;
+      }
+      if (cand == 0 && fits(2.0)) {
+        // no sample of at most 1/4 of the unit is reliable: read all of it (k * 64 <= size, so there are
+        // at least 4 k groups of 16); the candidates are the k largest, the few more down to the k-th
+        // largest group maximum, and the rest of the histogram bin (1/8 of a binade) that falls in
+        sg.n_runs = static_cast<uint32_t>((sg.size + 63) / 64);
+        sg.samp_stride = 64;
+        sg.r_s = sg.k;
+        sg.nsamp = std::min(MAX_SAMPLE_BLOCKS, std::max(1u, (sg.nwt + 63) / 64));      // four chunks per wave
+        cand = 2.0 * sg.k;
+        slack = 2048.0;
+      }
+      if (cand != 0) {                            // else: too dense for the slots, the unit takes the multi-pass kernels
+        sg.d0_cap = static_cast<uint32_t>(std::min<double>(n, 4.0 * cand + slack));
+        sg.mode = PATH_FAST;
+      }
+    } else if (cfg->sparsifier == QSL_RANDK && static_cast<uint64_t>(sg.k) * 16 <= sg.size) {
+      // the keys are uniform 32-bit words: keep those above the (1 - q) quantile, q = p + 7 sigma
+      const double q = p + 7.0 * std::sqrt(p * (1 - p) / n);
+      if (q * CHUNK <= 14.0) {                  // at most ~14 candidates per chunk: they fit a two-line slot
+        sg.T_static = static_cast<uint32_t>(std::floor(4294967296.0 * (1.0 - q)));
+        cand = q * n;
+        sg.d0_cap = static_cast<uint32_t>(std::min<double>(n, cand + 8.0 * std::sqrt(cand) + 1024.0));
+        sg.mode = PATH_FAST;
+      }
+    }
+  }
+  return cand;
+}
+
+extern "C" qsl_status qsl_plan_paths(const qsl_config* cfg, uint32_t* path_out) {
+  uint64_t K = 0;
+  if (!path_out) return QSL_ERR_INVALID_ARG;
+  const qsl_status st = check_config(cfg, &K);
+  if (st != QSL_OK) return st;
+  for (uint32_t l = 0; l < cfg->num_segments; ++l) {
+    SegInfo sg;
+    memset(&sg, 0, sizeof sg);
+    sg.size = cfg->seg_offset[l + 1] - cfg->seg_offset[l];
+    sg.k = cfg->seg_k[l];
+    sg.nwt = static_cast<uint32_t>((sg.size + CHUNK - 1) / CHUNK);
+    (void)plan_segment(cfg, sg);
+    path_out[l] = sg.mode;
+  }
+  return QSL_OK;
+}
+
 extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip_stream) {
   uint64_t K64 = 0;
   if (!out) return QSL_ERR_INVALID_ARG;
@@ -195,64 +276,10 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
     if (L > 1) {
       for (uint32_t t = 0; t < sg.nwt; ++t) { WtInfo wi; wi.seg = l; wi.chunk = t; wi.pad0 = wi.pad1 = 0; wts.push_back(wi); }
     }
-    sg.mode = (sg.nwt <= SMALL_CHUNKS && !(cfg->flags & QSL_FLAG_NO_SMALL_PATH)) ? PATH_SMALL : PATH_GENERAL;
-    // k = size: nothing to select (unless the caller asks for the multi-pass kernels only)
-    if (sg.mode != PATH_SMALL && sg.k == sg.size && !(cfg->flags & QSL_FLAG_NO_FAST_PATH)) sg.mode = PATH_FULL;
-    sg.T_static = 0xFFFFFFFFu;
-    sg.lpc = 8;
-    const double n = static_cast<double>(sg.size), p = static_cast<double>(sg.k) / n;
-    double cand = 0, slack = 0;                     // expected number of candidates, room beyond 4x that
-    if (!(cfg->flags & QSL_FLAG_NO_FAST_PATH) && sg.nwt > SMALL_CHUNKS && sg.mode != PATH_FULL) {
-      if (cfg->sparsifier == QSL_TOPK && static_cast<uint64_t>(sg.k) * 64 <= sg.size) {
-        // candidates ~ alpha k; the sample must hold enough of them for the guess to sit below the
-        // true threshold with ~6.5 sigma: (alpha - 1) sqrt(n_s p) >= 6.5 sqrt(alpha)
-        // (a small unit has a small k, so a generous alpha costs few candidates and saves most of the sample)
-        // The candidates of a chunk must fit its slot (at most 31, with 4 sigma to spare): a chunk with more sends all
-        // of them through the overflow pool, which the selection kernels read entry by entry -- a unit where most
-        // chunks do that (k = 1000 of 65,536 with alpha = 3: 47 per chunk) is far slower than on the multi-pass path.
-        auto fits = [&](double alpha) { const double pc = alpha * sg.k / sg.nwt; return pc + 4.0 * std::sqrt(pc) <= 31.0; };
-        const double alphas[10] = {1.5, 2.0, 3.0, 4.0, 6.0, 8.0, 12.0, 16.0, 24.0, 32.0};
-        for (double frac : {1.0 / 16, 1.0 / 4}) {
-          for (double alpha : alphas) {
-            const double n_s = 42.25 * alpha / ((alpha - 1) * (alpha - 1) * p);
-            if (n_s > n * frac || !fits(alpha)) continue;
-            sg.n_runs = static_cast<uint32_t>(std::ceil(n_s / 64.0));
-            sg.samp_stride = static_cast<uint32_t>(sg.size / sg.n_runs);
-            sg.r_s = static_cast<uint32_t>(std::ceil(alpha * (sg.n_runs * 64.0) * p));
-            sg.nsamp = std::min(MAX_SAMPLE_BLOCKS, std::max(1u, (sg.n_runs + 127) / 128));   // 8 runs per wave, all in flight
-            cand = alpha * sg.k;
-            slack = alpha <= 4.0 ? 8192.0 : 2048.0;
-            break;
-          }
-          if (cand != 0) break;
-        }
-        if (cand == 0 && fits(2.0)) {
-          // no sample of at most 1/4 of the unit is reliable: read all of it (k * 64 <= size, so there are
-          // at least 4 k groups of 16); the candidates are the k largest, the few more down to the k-th
-          // largest group maximum, and the rest of the histogram bin (1/8 of a binade) that falls in
-          sg.n_runs = static_cast<uint32_t>((sg.size + 63) / 64);
-          sg.samp_stride = 64;
-          sg.r_s = sg.k;
-          sg.nsamp = std::min(MAX_SAMPLE_BLOCKS, std::max(1u, (sg.nwt + 63) / 64));      // four chunks per wave
-          cand = 2.0 * sg.k;
-          slack = 2048.0;
-        }
-        if (cand != 0) {                            // else: too dense for the slots, the unit takes the multi-pass kernels
-          sg.d0_cap = static_cast<uint32_t>(std::min<double>(n, 4.0 * cand + slack));
-          sg.mode = PATH_FAST;
-          ++ctx->n_sampled;
-          for (uint32_t j = 0; j < sg.nsamp; ++j) { SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0; samps.push_back(si); }
-        }
-      } else if (cfg->sparsifier == QSL_RANDK && static_cast<uint64_t>(sg.k) * 16 <= sg.size) {
-        // the keys are uniform 32-bit words: keep those above the (1 - q) quantile, q = p + 7 sigma
-        const double q = p + 7.0 * std::sqrt(p * (1 - p) / n);
-        if (q * CHUNK <= 14.0) {                  // at most ~14 candidates per chunk: they fit a two-line slot
-          sg.T_static = static_cast<uint32_t>(std::floor(4294967296.0 * (1.0 - q)));
-          cand = q * n;
-          sg.d0_cap = static_cast<uint32_t>(std::min<double>(n, cand + 8.0 * std::sqrt(cand) + 1024.0));
-          sg.mode = PATH_FAST;
-        }
-      }
+    const double cand = plan_segment(cfg, sg);
+    if (sg.mode == PATH_FAST && cfg->sparsifier == QSL_TOPK) {        // a guessing Top_k unit samples
+      ++ctx->n_sampled;
+      for (uint32_t j = 0; j < sg.nsamp; ++j) { SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0; samps.push_back(si); }
     }
     if (sg.mode == PATH_FAST) {
       // the slot of a chunk (64, 128 or 256 bytes) holds the expected candidates with ~4 sigma to spare;

@@ -102,6 +102,48 @@ def test_index_free_bit_count_of_rand_k(lib, qz, s):
     assert lib.qsl_bits_index_free(None, C.byref(bits)) == 1
 
 
+def plan(lib, d, off, k, sp=0, qz=0, flags=0, s=16):
+    lib.qsl_plan_paths.argtypes = [C.POINTER(Config), C.POINTER(C.c_uint32)]
+    lib.qsl_plan_paths.restype = C.c_int
+    cfg = make_cfg(d, off, k, s=s, sp=sp, qz=qz)
+    cfg.flags = flags
+    out = (C.c_uint32 * len(k))()
+    assert lib.qsl_plan_paths(C.byref(cfg), out) == 0
+    return list(out)
+
+
+def test_plan_of_the_selection_paths(lib):
+    """The host's per-segment decision (made by the same code in qsl_create), without a GPU."""
+    FAST, MULTI, ONE_BLOCK, ALL_KEPT = 0, 1, 3, 4
+    # one segment: sparse -> guess; dense -> multi-pass; tiny -> one block; k = size -> nothing to select
+    assert plan(lib, 25_557_032, [0, 25_557_032], [25_557]) == [FAST]
+    assert plan(lib, 25_557_032, [0, 25_557_032], [2_555_703]) == [MULTI]
+    assert plan(lib, 4_096, [0, 4_096], [40]) == [ONE_BLOCK]
+    assert plan(lib, 4_097, [0, 4_097], [10]) == [FAST]
+    assert plan(lib, 4_097, [0, 4_097], [40]) == [MULTI]          # 16 candidates per chunk and their spread do not fit a slot
+    assert plan(lib, 4_096, [0, 4_096], [4_096]) == [ONE_BLOCK]
+    assert plan(lib, 300_000, [0, 300_000], [300_000]) == [ALL_KEPT]
+    # candidates must fit the chunk slots: 1000 of 65,536 is sparse enough to guess by k * 64 <= size, but not for the slots
+    assert plan(lib, 65_536, [0, 65_536], [1_000]) == [MULTI]
+    assert plan(lib, 262_144, [0, 262_144], [1_000]) == [FAST]
+    # Rand_k guesses analytically when at most ~14 candidates fall into a chunk
+    assert plan(lib, 25_557_032, [0, 25_557_032], [255_570], sp=1) == [FAST]
+    assert plan(lib, 25_557_032, [0, 25_557_032], [2_555_703], sp=1) == [MULTI]
+    # the testing flags
+    assert plan(lib, 25_557_032, [0, 25_557_032], [25_557], flags=1) == [MULTI]
+    assert plan(lib, 4_096, [0, 4_096], [40], flags=2) == [MULTI]
+    assert plan(lib, 4_096, [0, 4_096], [40], flags=3) == [MULTI]
+    assert plan(lib, 300_000, [0, 300_000], [300_000], flags=1) == [MULTI]
+    # the paper's ResNet-50 setting (Section 5.1.1): 108 small tensors, 20 too dense for guessing, 33 that guess
+    wl = W.config(6)
+    paths = plan(lib, wl.d, [int(x) for x in wl.seg_offset], [int(x) for x in wl.seg_k], qz=1, s=1)
+    assert (paths.count(ONE_BLOCK), paths.count(MULTI), paths.count(FAST), paths.count(ALL_KEPT)) == (108, 20, 33, 0)
+    # invalid descriptions are refused
+    cfg = make_cfg(100, [0, 100], [101])
+    out = (C.c_uint32 * 1)()
+    assert lib.qsl_plan_paths(C.byref(cfg), out) == 1 and lib.qsl_plan_paths(None, out) == 1
+
+
 def test_null_arguments_and_status_strings(lib):
     lib.qsl_status_string.argtypes = [C.c_int]
     lib.qsl_status_string.restype = C.c_char_p
