@@ -260,6 +260,18 @@ def test_every_coordinate_kept(P, sparsifier, quantizer, s):
     P.run_parity(wl, 1, flags=1, expect_path=1)                   # the same through the multi-pass kernels
 
 
+def test_plan_query_agrees_with_what_the_kernels_report(P):
+    # the host-only plan (qsl_plan_paths) and the path each unit reports after a call (no guess fails on these inputs)
+    from paper_1906_02367_amd import binding as B
+    off = [0, 100, 70_000, 70_001, 400_000, 410_001, 1_100_000]
+    k = [100, 70, 1, 30_000, 10_001, 600]
+    for sp, qz, s, flags in [(W.TOPK, W.QSGD, 16, 0), (W.RANDK, W.SIGN_L1, 1, 0), (W.TOPK, W.SIGN_L1, 1, 2), (W.TOPK, W.FP32, 1, 3)]:
+        wl = custom(1_100_000, off, k, s, sp, qz, R=2)
+        run, op, m_host, paths = P.run_parity(wl, 1, flags=flags)
+        plan = B.plan_paths(wl.d, wl.seg_offset, wl.seg_k, wl.s, wl.sparsifier, wl.quantizer, flags)
+        assert paths[0].reshape(2, len(k)).tolist() == [plan.tolist()] * 2, (paths[0], plan)
+
+
 # ---------------------------------------------------------------------------------------------
 # the other entry points
 # ---------------------------------------------------------------------------------------------
