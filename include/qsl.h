@@ -23,7 +23,10 @@
  *   - Argument errors are reported synchronously and have no side effect.  Errors that depend
  *     on the data (a NaN/Inf in m + Delta) set a status word on the device, returned by
  *     qsl_device_status().
- *   - A context is not thread-safe; calls on one context must not overlap.
+ *   - A context is not thread-safe; calls on one context must not overlap on the host.  On the GPU the
+ *     calls of one context share its scratch memory and are ordered by its stream; when the stream is
+ *     changed (qsl_set_stream) the library makes the new stream wait for the work already enqueued on
+ *     the old one, so calls on different streams still run one after the other.
  *
  * Wire format of one message (little endian; fields are packed least-significant bit first;
  * "w_idx" = bits needed to write d - 1, at least 1; "w_lev" = bits needed to write s - 1):
@@ -84,8 +87,11 @@ typedef struct {
 enum {
   QSL_FLAG_NO_FAST_PATH = 1,  /* never guess a threshold and never skip the selection of a segment with k = size:
                                  exact multi-pass selection only (testing, comparison)                  */
-  QSL_FLAG_NO_SMALL_PATH = 2  /* segments of at most 4096 coordinates also take the multi-pass kernels  
+  QSL_FLAG_NO_SMALL_PATH = 2, /* segments of at most 4096 coordinates also take the multi-pass kernels
                                  instead of the one-block selection (testing, comparison)               */
+  QSL_FLAG_OWN_V = 4          /* the context also allocates a float [max_workers, d] array of its own as the home
+                                 of v = m + delta, so that qsl_compress / qsl_compress_diff accept m_out = NULL
+                                 ("send g, leave the error memory alone")                               */
 };
 
 /* Which way each segment of an operator will take through the selection -- the `path` that qsl_debug_units
@@ -99,6 +105,8 @@ qsl_status qsl_plan_paths(const qsl_config *cfg, uint32_t *path_out);
  * (NULL = the default stream).  Allocates all scratch memory.  */
 qsl_status qsl_create(qsl_ctx **out, const qsl_config *cfg, void *hip_stream);
 qsl_status qsl_destroy(qsl_ctx *ctx);
+/* Later calls are enqueued on `hip_stream`.  If it differs from the current stream, the new stream first waits
+ * (hipStreamWaitEvent, no host synchronisation) for everything this context has enqueued on the old one.  */
 qsl_status qsl_set_stream(qsl_ctx *ctx, void *hip_stream);
 
 /* Size in bytes of one worker's message buffer (an upper bound over all inputs; multiple of 8). */
@@ -108,7 +116,9 @@ size_t qsl_msg_capacity_bytes(const qsl_ctx *ctx);
  * sync round `round` (< 2^62): forms v = m + delta, selects, quantises, packs the messages and
  * writes the new error memory.
  *   m, delta  device, const float [R, d]
- *   m_out     device, float [R, d]; receives m + delta - g; may be the same pointer as m; required
+ *   m_out     device, float [R, d]; receives m + delta - g; may be the same pointer as m.  NULL only for a
+ *             context created with QSL_FLAG_OWN_V: the messages are produced and m is left as it was
+ *             (the error update can follow later with qsl_error_update)
  *   msg       device, uint8 [R, capacity]; every byte is written (zero padded)
  *   msg_bits  device, uint64 [R] or NULL; payload bits of each message (padding excluded)
  *   sel_idx   device, uint32 [R, K] or NULL, K = sum_l k_l; the selected coordinates, ascending
@@ -146,8 +156,8 @@ qsl_status qsl_error_update(qsl_ctx *ctx, float *m, const float *delta, const ui
 qsl_status qsl_aggregate(qsl_ctx *ctx, const uint8_t *msg, const uint32_t *worker_list, uint32_t R, float scale,
                          int accumulate, float *out);
 
-/* Payload bits of each of R messages (the communication-budget axis of the paper's plots), read
- * from the message headers.  Synchronises the stream.  bits_host: host uint64 [R].  */
+/* Payload bits of each of R messages (the communication-budget axis of the plots of Section 5: test
+ * error and loss against the number of bits sent), read from the message headers.  Synchronises the stream.  bits_host: host uint64 [R].  */
 qsl_status qsl_bits_sent(qsl_ctx *ctx, const uint8_t *msg, uint32_t R, uint64_t *bits_host);
 
 /* Accounting variant for Rand_k: the bits of one message if the indices are not transmitted.  Rand_k

@@ -18,6 +18,7 @@ TOPK, RANDK = 0, 1
 QSGD, SIGN_L1, SIGN_L2, FP32, QSGD_SCALED = 0, 1, 2, 3, 4
 FLAG_NO_FAST_PATH = 1
 FLAG_NO_SMALL_PATH = 2
+FLAG_OWN_V = 4
 
 OK, ERR_INVALID_ARG, ERR_BUFFER_TOO_SMALL, ERR_NONFINITE_INPUT, ERR_DEVICE, ERR_UNSUPPORTED = range(6)
 
@@ -145,21 +146,22 @@ class Qsl:
     # -- the C entry points -------------------------------------------------------------------
     def compress(self, m, delta, m_out, worker0, rnd, msg, msg_bits=None, sel_idx=None, sel_level=None):
         R = m.shape[0]
-        assert m.shape == (R, self.d) and delta.shape == m.shape and m_out.shape == m.shape
+        assert m.shape == (R, self.d) and delta.shape == m.shape and (m_out is None or m_out.shape == m.shape)
         assert msg.shape == (R, self.capacity)
         _check(_lib.qsl_set_stream(self._ctx, self._stream()), "qsl_set_stream")
         _check(_lib.qsl_compress(self._ctx, _ptr(m, torch.float32), _ptr(delta, torch.float32),
-                                 _ptr(m_out, torch.float32), int(worker0), R, int(rnd), _ptr(msg, torch.uint8),
+                                 _ptr(m_out, torch.float32, True), int(worker0), R, int(rnd), _ptr(msg, torch.uint8),
                                  _ptr(msg_bits, torch.int64, True), _ptr(sel_idx, torch.int32, True),
                                  _ptr(sel_level, torch.int16, True)), "qsl_compress")
 
     def compress_diff(self, m, x, xhat_half, m_out, worker0, rnd, msg, msg_bits=None, sel_idx=None, sel_level=None):
         R = m.shape[0]
-        assert m.shape == (R, self.d) and xhat_half.shape == m.shape and m_out.shape == m.shape and x.shape == (self.d,)
+        assert m.shape == (R, self.d) and xhat_half.shape == m.shape and x.shape == (self.d,)
+        assert m_out is None or m_out.shape == m.shape
         assert msg.shape == (R, self.capacity)
         _check(_lib.qsl_set_stream(self._ctx, self._stream()), "qsl_set_stream")
         _check(_lib.qsl_compress_diff(self._ctx, _ptr(m, torch.float32), _ptr(x, torch.float32),
-                                      _ptr(xhat_half, torch.float32), _ptr(m_out, torch.float32), int(worker0), R,
+                                      _ptr(xhat_half, torch.float32), _ptr(m_out, torch.float32, True), int(worker0), R,
                                       int(rnd), _ptr(msg, torch.uint8), _ptr(msg_bits, torch.int64, True),
                                       _ptr(sel_idx, torch.int32, True), _ptr(sel_level, torch.int16, True)),
                "qsl_compress_diff")

@@ -79,6 +79,8 @@ struct qsl_ctx {
   size_t capacity;
   uint32_t* h_status;         // pinned
   uint32_t* d_nnz_tmp;
+  float* own_v;               // [Rmax, d] home of v for calls with m_out = NULL (QSL_FLAG_OWN_V), else null
+  hipEvent_t order_ev;        // orders the work of this context across a change of stream
   int timing;
   std::vector<hipEvent_t> ev;
   size_t ev_used;
@@ -222,6 +224,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const qsl_status cfg_status = check_config(cfg, &K64);
   if (cfg_status != QSL_OK) return cfg_status;
   if (cfg->max_workers == 0 || cfg->max_workers > 1024) return QSL_ERR_INVALID_ARG;
+  if (cfg->flags & ~static_cast<uint32_t>(QSL_FLAG_NO_FAST_PATH | QSL_FLAG_NO_SMALL_PATH | QSL_FLAG_OWN_V)) return QSL_ERR_INVALID_ARG;
   const uint64_t d = cfg->d;
   const uint32_t L = cfg->num_segments;
 
@@ -236,7 +239,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->Rmax = cfg->max_workers;
   ctx->last_R = 0;
   ctx->timing = 0; ctx->ev_used = 0;
-  ctx->slab = nullptr; ctx->h_status = nullptr;
+  ctx->slab = nullptr; ctx->h_status = nullptr; ctx->own_v = nullptr; ctx->order_ev = nullptr;
 
   const uint32_t K = static_cast<uint32_t>(K64);
   const uint32_t s = is_qsgd(cfg->quantizer) ? cfg->s : 1;
@@ -255,6 +258,8 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   uint64_t bits = 32 + 32ull * L + (counts ? 32ull * L : 0);
   bits += align_up(static_cast<uint64_t>(K) * w_idx, 32) + align_up(static_cast<uint64_t>(K) * w_val, 32);
   ctx->capacity = static_cast<size_t>(align_up(bits, 64) / 8);
+  // the kernels count the words of a message in 32 bits
+  if (ctx->capacity / 4 > 0xFFFFFFFFull) { delete ctx; return QSL_ERR_UNSUPPORTED; }
 
   // per-segment plan: single-pass guessing ("fast") where the unit is large and sparse enough
   std::vector<SegInfo>& segs = ctx->segs;
@@ -402,6 +407,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->agg_ndir = static_cast<uint32_t>(((d + (1u << AGG_DIR_SHIFT) - 1) >> AGG_DIR_SHIFT) + 1);
   const bool want_dir = ctx->nnz_hint >= AGG_DIR_MIN;
   const uint64_t o_dir = carve(want_dir ? 4ull * 64 * ctx->agg_ndir : 4);
+  const uint64_t o_ownv = carve((cfg->flags & QSL_FLAG_OWN_V) ? 4ull * R * d : 4);
   if (hipMalloc(&ctx->slab, bytes) != hipSuccess) { delete ctx; return QSL_ERR_DEVICE; }
   char* base = static_cast<char*>(ctx->slab);
   bool ok = hipMemset(base, 0, zero_bytes) == hipSuccess;
@@ -420,8 +426,15 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   upload(o_segdir, seg_dir.data(), 4 * seg_dir.size());
   upload(o_slotdir, slot_dir.data(), 4 * slot_dir.size());
   ok = ok && hipHostMalloc(reinterpret_cast<void**>(&ctx->h_status), 64, hipHostMallocDefault) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ctx->order_ev, hipEventDisableTiming) == hipSuccess;
   ok = ok && hipDeviceSynchronize() == hipSuccess;
-  if (!ok) { (void)hipFree(ctx->slab); delete ctx; return QSL_ERR_DEVICE; }
+  if (!ok) {
+    (void)hipFree(ctx->slab);
+    if (ctx->h_status) (void)hipHostFree(ctx->h_status);
+    if (ctx->order_ev) (void)hipEventDestroy(ctx->order_ev);
+    delete ctx;
+    return QSL_ERR_DEVICE;
+  }
 
   DevCtx& c = ctx->dc;
   c.segs = reinterpret_cast<const SegInfo*>(base + o_segs);
@@ -453,6 +466,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.status = reinterpret_cast<uint32_t*>(base + o_status);
   ctx->d_nnz_tmp = reinterpret_cast<uint32_t*>(base + o_tmp);
   ctx->agg_dir = want_dir ? reinterpret_cast<uint32_t*>(base + o_dir) : nullptr;
+  ctx->own_v = (cfg->flags & QSL_FLAG_OWN_V) ? reinterpret_cast<float*>(base + o_ownv) : nullptr;
   c.d = d; c.seed = cfg->seed; c.L = L; c.K = K; c.NWT = NWT; c.NSEL = NSEL; c.NCB = NCB; c.NWC = NWC; c.QB = QB;
   c.nfast = static_cast<uint32_t>(fast.size()); c.s = s; c.w_idx = w_idx; c.w_lev = w_lev; c.w_val = w_val;
   c.sparsifier = cfg->sparsifier; c.quantizer = cfg->quantizer;
@@ -461,7 +475,8 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->one.lpc = segs[0].lpc; ctx->one.ovf_cap = segs[0].ovf_cap;
   k_init<<<dim3(static_cast<uint32_t>((U + 255) / 256)), 256, 0, ctx->stream>>>(c, static_cast<uint32_t>(U));
   if (hipStreamSynchronize(ctx->stream) != hipSuccess) {
-    (void)hipFree(ctx->slab); (void)hipHostFree(ctx->h_status); delete ctx; return QSL_ERR_DEVICE;
+    (void)hipFree(ctx->slab); (void)hipHostFree(ctx->h_status); (void)hipEventDestroy(ctx->order_ev); delete ctx;
+    return QSL_ERR_DEVICE;
   }
   *out = ctx;
   return QSL_OK;
@@ -473,13 +488,21 @@ extern "C" qsl_status qsl_destroy(qsl_ctx* ctx) {
   for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
   if (ctx->slab) (void)hipFree(ctx->slab);
   if (ctx->h_status) (void)hipHostFree(ctx->h_status);
+  if (ctx->order_ev) (void)hipEventDestroy(ctx->order_ev);
   delete ctx;
   return QSL_OK;
 }
 
 extern "C" qsl_status qsl_set_stream(qsl_ctx* ctx, void* hip_stream) {
   if (!ctx) return QSL_ERR_INVALID_ARG;
-  ctx->stream = static_cast<hipStream_t>(hip_stream);
+  hipStream_t next = static_cast<hipStream_t>(hip_stream);
+  if (next != ctx->stream) {
+    // the calls of a context share its scratch: what is already enqueued on the old stream must finish before
+    // anything enqueued on the new one starts
+    QSL_HIP(hipEventRecord(ctx->order_ev, ctx->stream));
+    QSL_HIP(hipStreamWaitEvent(next, ctx->order_ev, 0));
+    ctx->stream = next;
+  }
   return QSL_OK;
 }
 
@@ -541,7 +564,9 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
 static qsl_status compress_checked(qsl_ctx* ctx, const float* m, const float* delta, const float* xm, float* m_out,
                                    uint32_t worker0, uint32_t R, uint64_t round, uint8_t* msg, uint64_t* msg_bits,
                                    uint32_t* sel_idx, uint16_t* sel_level) {
-  if (!ctx || !m || !delta || !m_out || !msg || R == 0 || R > ctx->Rmax || (round >> 62)) return QSL_ERR_INVALID_ARG;
+  if (!ctx || !m || !delta || !msg || R == 0 || R > ctx->Rmax || (round >> 62)) return QSL_ERR_INVALID_ARG;
+  if (!m_out) m_out = ctx->own_v;                  // "send g, leave m alone": v lives in the context's own array
+  if (!m_out) return QSL_ERR_INVALID_ARG;
   if (static_cast<uint64_t>(worker0) + R > (1ull << 32)) return QSL_ERR_INVALID_ARG;
   if ((reinterpret_cast<uintptr_t>(m) | reinterpret_cast<uintptr_t>(delta) | reinterpret_cast<uintptr_t>(m_out) |
        reinterpret_cast<uintptr_t>(xm) | reinterpret_cast<uintptr_t>(sel_idx)) & 3) return QSL_ERR_INVALID_ARG;

@@ -363,6 +363,10 @@ __device__ void general_groups(const SegInfo& sg, const float* vp, const RandKey
       // then worked off 64 entries at a time by all lanes.
       uint32_t staged = 0;                                            // entries in the wave's list (wave-uniform)
       auto flush = [&]() {
+        // the list is private to the wave, whose lanes run in lockstep: order the LDS traffic only
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         for (uint32_t o = 0; o < staged; o += 64) {
           if (o + lane < staged) {
             const uint32_t pos = stage_pos[wave * STAGE + o + lane];
@@ -371,6 +375,9 @@ __device__ void general_groups(const SegInfo& sg, const float* vp, const RandKey
             add_digits(mine, e.y, squares);
           }
         }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");      // ... and before the list is refilled
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         staged = 0;
       };
 #pragma unroll

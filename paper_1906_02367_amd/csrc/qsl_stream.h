@@ -190,9 +190,17 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
       }
     }
   }
+  bool nonfinite = false;
+#pragma unroll
+  for (int t = 0; t < 4; ++t) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) nonfinite |= (__float_as_uint(v[t][j]) & 0x7FFFFFFFu) >= 0x7F800000u;
+  }
+  if (__ballot(nonfinite) != 0 && lane == 0) atomicOr(c.status, 1u);
+  if (path != PATH_FAST) return;                  // uniform over the wave: only a guessing unit collects candidates
+
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   uint32_t pm = 0;                                                    // bit t*4+j: coordinate (t, j) is a candidate
-  bool nonfinite = false;
   Words4 rws[4];                                                      // Rand_k: the keys, kept for the slot's key line
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
@@ -200,15 +208,11 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
     if (SPARS == QSL_RANDK) { rw = rand_words4(rk, static_cast<uint32_t>(sg.start + cb + t * 256 + lane * 4)); rws[t] = rw; }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const uint32_t bits = __float_as_uint(v[t][j]);
-      nonfinite |= (bits & 0x7FFFFFFFu) >= 0x7F800000u;
-      const uint32_t key = SPARS == QSL_TOPK ? key_of_value(bits) : rw.w[j];
+      const uint32_t key = SPARS == QSL_TOPK ? key_of_value(__float_as_uint(v[t][j])) : rw.w[j];
       const bool inside = cb + t * 256 + lane * 4 + j < sg.size;
       pm |= (inside && key >= T ? 1u : 0u) << (t * 4 + j);
     }
   }
-  if (__ballot(nonfinite) != 0 && lane == 0) atomicOr(c.status, 1u);
-  if (path != PATH_FAST) return;                  // uniform over the wave
 
   const uint32_t cap = sg.lpc * 2 - 1;
   uint2* stage = s_stage[wave];

@@ -1,0 +1,116 @@
+"""GPU checks of how a context behaves around the operator itself: stopping and resuming a run from the saved
+error memory, a change of stream between two calls, and messages without touching the error memory."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from paper_1906_02367_amd import workloads as W  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def P():
+    import parity_util
+    return parity_util
+
+
+@pytest.mark.parametrize("cfg,d", [(2, 1_000_003), (3, 600_011), (4, 2_000_000)])
+def test_resume_from_saved_memory_equals_straight_run(P, cfg, d):
+    """The state of the hot path is the error memory and the round counter (the randomness is counter-based):
+    10 rounds, the memory copied out and into a fresh context, 10 more -- the same bytes as 20 rounds straight."""
+    from paper_1906_02367_amd import binding as B
+    wl = W.config(cfg, d=d, R=2)
+    dev = torch.device("cuda")
+    deltas = [torch.from_numpy(W.delta_all(wl, t)).to(dev) for t in range(20)]
+
+    def run(q, m, t0, t1, keep):
+        msg = q.new_msg(wl.R)
+        x = torch.zeros(wl.d, device=dev)
+        for t in range(t0, t1):
+            q.compress(m, deltas[t], m, 0, t, msg)
+            q.aggregate(msg, x, -1.0 / wl.R, accumulate=True)
+            keep.append((msg.clone(), x.clone()))
+        torch.cuda.synchronize()
+        assert q.device_status() == B.OK
+
+    straight, resumed = [], []
+    m_a = torch.zeros(wl.R, wl.d, device=dev)
+    run(B.from_workload(wl), m_a, 0, 20, straight)
+    q1 = B.from_workload(wl)
+    m_b = torch.zeros(wl.R, wl.d, device=dev)
+    run(q1, m_b, 0, 10, resumed)
+    saved = m_b.cpu().numpy().copy()                       # "checkpoint": the memory leaves the device ...
+    q1.close()
+    del q1, m_b
+    m_c = torch.from_numpy(saved).to(dev)                  # ... and comes back into a fresh context
+    run(B.from_workload(wl), m_c, 10, 20, resumed)
+    assert torch.equal(m_a.view(torch.int32), m_c.view(torch.int32))
+    for t in range(20):
+        assert torch.equal(straight[t][0], resumed[t][0]), f"round {t}: messages differ"
+    # the master's vector restarts from zero in the resumed half: compare the increments of the second half
+    for t in range(10, 20):
+        inc_a = straight[t][1] - straight[9][1] if t > 9 else None
+        assert torch.allclose(inc_a, resumed[t][1], rtol=1e-5, atol=1e-6), f"round {t}: aggregate differs"
+
+
+def test_calls_on_different_streams_are_ordered(P):
+    """compress on stream A, aggregate (and the next compress) on stream B, same context: the library makes the new
+    stream wait for the work on the old one, so the bytes equal those of a single-stream run."""
+    from paper_1906_02367_amd import binding as B
+    wl = W.config(2, d=4_000_037, R=4)
+    dev = torch.device("cuda")
+    deltas = [torch.from_numpy(W.delta_all(wl, t)).to(dev) for t in range(3)]
+    torch.cuda.synchronize()
+
+    def run(streams):
+        q = B.from_workload(wl)
+        m = torch.zeros(wl.R, wl.d, device=dev)
+        msg = q.new_msg(wl.R)
+        x = torch.zeros(wl.d, device=dev)
+        outs = []
+        torch.cuda.synchronize()
+        for t in range(3):
+            with torch.cuda.stream(streams[(2 * t) % len(streams)]):
+                q.compress(m, deltas[t], m, 0, t, msg)
+            with torch.cuda.stream(streams[(2 * t + 1) % len(streams)]):
+                q.aggregate(msg, x, -0.25, accumulate=True)
+                outs.append((msg.clone(), x.clone()))
+        torch.cuda.synchronize()
+        assert q.device_status() == B.OK
+        return m, outs
+
+    one = torch.cuda.current_stream()
+    m1, o1 = run([one])
+    m2, o2 = run([torch.cuda.Stream(), torch.cuda.Stream()])
+    assert torch.equal(m1.view(torch.int32), m2.view(torch.int32))
+    for (a, xa), (b, xb) in zip(o1, o2):
+        assert torch.equal(a, b) and torch.equal(xa.view(torch.int32), xb.view(torch.int32))
+
+
+@pytest.mark.parametrize("cfg,d", [(2, 1_000_003), (1, 65_536), (4, 2_000_000)])
+def test_messages_without_touching_the_memory(P, cfg, d):
+    """m_out = NULL on a context that owns a home for v: the same messages, m unchanged; the stand-alone error
+    update then gives the memory of the fused form."""
+    from paper_1906_02367_amd import binding as B
+    wl = W.config(cfg, d=d, R=2)
+    dev = torch.device("cuda")
+    q = B.from_workload(wl, flags=B.FLAG_OWN_V)
+    q_plain = B.from_workload(wl)
+    rng = np.random.default_rng(cfg)
+    m0 = (0.3 * rng.standard_normal((wl.R, wl.d))).astype(np.float32)
+    delta = torch.from_numpy(W.delta_all(wl, 0)).to(dev)
+    m = torch.from_numpy(m0).to(dev)
+    msg, msg2 = q.new_msg(wl.R), q_plain.new_msg(wl.R)
+    q.compress(m, delta, None, 0, 3, msg)
+    m_fused = torch.empty_like(m)
+    q_plain.compress(m, delta, m_fused, 0, 3, msg2)
+    torch.cuda.synchronize()
+    assert np.array_equal(m.cpu().numpy().view(np.uint32), m0.view(np.uint32))          # untouched
+    assert torch.equal(msg, msg2)
+    q.error_update(m, delta, msg)
+    torch.cuda.synchronize()
+    assert torch.equal(m.view(torch.int32), m_fused.view(torch.int32))
+    with pytest.raises(B.QslError):
+        q_plain.compress(m, delta, None, 0, 3, msg2)                                    # no home for v: refused
+    assert q.device_status() == B.OK

@@ -102,6 +102,77 @@ def test_index_free_bit_count_of_rand_k(lib, qz, s):
     assert lib.qsl_bits_index_free(None, C.byref(bits)) == 1
 
 
+@pytest.mark.parametrize("s", [1, 2, 3, 15, 16, 255, 256])
+def test_index_free_qsgd_stream_written_out_and_read_back(lib, s):
+    """The index-free count for QSGD, pinned without consulting either formula: the stream is written here, code by
+    code, from the oracle's levels and signs (every one of the K chosen coordinates, level 0 included, in the fewest
+    whole bits that can tell s + 1 levels apart, then one sign bit), read back with a reader of this test, and
+    dequantised as Definition 1's example does (norm * level / s); it must reproduce the values the oracle sent, and
+    its length must equal both counts.  A field one bit too narrow cannot hold level s; one bit too wide changes the length."""
+    from oracle import oracle as O
+    lib.qsl_bits_index_free.argtypes = [C.POINTER(Config), C.POINTER(C.c_uint64)]
+    lib.qsl_bits_index_free.restype = C.c_int
+    d, off, k = 5_000, [0, 100, 1_124, 5_000], [7, 100, 1]
+    op = O.OracleOp(d, off, k, s, O.RANDK, O.QSGD, 7)
+    rng = np.random.default_rng(s)
+    v = (rng.standard_normal(d) * np.exp(rng.standard_normal(d))).astype(np.float32)
+    out = op.compress(np.zeros(d, np.float32), v, 2, 5)
+    levels, negs = out["sel_level"].astype(int), out["sel_neg"].astype(int)
+    assert levels.max() <= s and (levels == s).any() or s > 3          # a segment with k = 1 always reaches level s
+    n_level_bits = 0
+    while (1 << n_level_bits) < s + 1:                                  # fewest bits for the s + 1 values 0..s
+        n_level_bits += 1
+    stream = []                                                         # one bit per list element, first bit first
+
+    def put(value, width):
+        assert 0 <= value < (1 << width), "the field cannot hold the value"
+        for b in range(width):
+            stream.append((value >> b) & 1)
+
+    for scale in out["scales"]:
+        put(int(np.float32(scale).view(np.uint32)), 32)
+    for lv, ng in zip(levels, negs):
+        put(int(lv), n_level_bits)
+        put(int(ng), 1)
+    # read it back
+    pos = 0
+
+    def get(width):
+        nonlocal pos
+        x = sum(bit << b for b, bit in enumerate(stream[pos:pos + width]))
+        pos += width
+        return x
+
+    scales = [np.uint32(get(32)).view(np.float32) for _ in k]
+    seg_of = np.repeat(np.arange(len(k)), k)
+    vals = []
+    for j in range(sum(k)):
+        lv, ng = get(n_level_bits), get(1)
+        mag = np.float32(np.float32(scales[seg_of[j]] * np.float32(lv)) / np.float32(s))
+        vals.append(np.float32(0.0) if lv == 0 else (-mag if ng else mag))     # level 0 stands for "nothing sent"
+    assert pos == len(stream)
+    assert np.array_equal(np.array(vals, dtype=np.float32).view(np.uint32), out["g_val"].view(np.uint32))
+    bits = C.c_uint64(0)
+    cfg = make_cfg(d, off, k, s=s, sp=1, qz=0)
+    assert lib.qsl_bits_index_free(C.byref(cfg), C.byref(bits)) == 0
+    assert len(stream) == bits.value == op.bits_index_free()
+
+
+def test_message_too_long_for_the_word_counters_is_refused(lib):
+    """More than 2^32 message words (K above ~2.1e9 with 32-bit indices and fp32 values): refused at qsl_create,
+    before any GPU work, instead of truncating the word count."""
+    lib.qsl_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(Config), C.c_void_p]
+    lib.qsl_create.restype = C.c_int
+    ctx = C.c_void_p()
+    d = 4_000_000_000
+    cfg = make_cfg(d, [0, d], [2_200_000_000], s=1, sp=0, qz=3)
+    assert lib.qsl_create(C.byref(ctx), C.byref(cfg), None) == 5          # QSL_ERR_UNSUPPORTED
+    assert not ctx.value
+    cfg = make_cfg(100, [0, 100], [5])
+    cfg.flags = 1 << 9                                                    # an unknown flag
+    assert lib.qsl_create(C.byref(ctx), C.byref(cfg), None) == 1
+
+
 def plan(lib, d, off, k, sp=0, qz=0, flags=0, s=16):
     lib.qsl_plan_paths.argtypes = [C.POINTER(Config), C.POINTER(C.c_uint32)]
     lib.qsl_plan_paths.restype = C.c_int
