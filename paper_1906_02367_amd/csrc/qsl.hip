@@ -605,38 +605,55 @@ extern "C" qsl_status qsl_error_update(qsl_ctx* ctx, float* m, const float* delt
   return QSL_OK;
 }
 
-extern "C" qsl_status qsl_aggregate(qsl_ctx* ctx, const uint8_t* msg, const uint32_t* worker_list, uint32_t R,
-                                    float scale, int accumulate, float* out) {
-  if (!ctx || !msg || !out || R == 0 || R > 64) return QSL_ERR_INVALID_ARG;
-  if ((reinterpret_cast<uintptr_t>(msg) & 7) || (reinterpret_cast<uintptr_t>(out) & 3)) return QSL_ERR_INVALID_ARG;
-  const DevCtx& c = ctx->dc;
-  RowList rows;
-  for (uint32_t q = 0; q < 64; ++q) rows.row[q] = q < R ? (worker_list ? worker_list[q] : q) : 0;
+// the listed rows, checked: a message may be listed once
+static qsl_status make_row_list(const uint32_t* worker_list, uint32_t R, RowList* rows) {
+  if (R == 0 || R > 64) return QSL_ERR_INVALID_ARG;
+  for (uint32_t q = 0; q < 64; ++q) rows->row[q] = q < R ? (worker_list ? worker_list[q] : q) : 0;
   for (uint32_t q = 0; q < R; ++q)
     for (uint32_t p = 0; p < q; ++p)
-      if (rows.row[p] == rows.row[q]) return QSL_ERR_INVALID_ARG;       // a message may be listed once
+      if (rows->row[p] == rows->row[q]) return QSL_ERR_INVALID_ARG;
+  return QSL_OK;
+}
+
+// The launches of the master line.  `dir` is room for R directories of `ndir` words, or null (then every message is
+// searched whole); `nnz_hint` sizes the grids.
+static qsl_status launch_aggregate(const DevCtx& c, hipStream_t st, uint32_t nnz_hint, uint32_t* dir, uint32_t ndir,
+                                   const uint8_t* msg, const RowList& rows, uint32_t R, float scale, int accumulate,
+                                   float* out) {
   if (c.K == c.d && !is_qsgd(c.quantizer)) {        // k = d and nothing dropped: every message lists every coordinate
     const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((c.d + BLOCK - 1) / BLOCK, 1u << 16));
-    k_aggregate_dense<<<dim3(blocks), BLOCK, 0, ctx->stream>>>(c, msg, rows, R, scale, accumulate, out);
+    k_aggregate_dense<<<dim3(blocks), BLOCK, 0, st>>>(c, msg, rows, R, scale, accumulate, out);
     QSL_HIP(hipGetLastError());
     return QSL_OK;
   }
   if (!accumulate) {
     const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((c.d + BLOCK * 4 - 1) / (BLOCK * 4), 1u << 16));
-    k_fill_zero<<<dim3(blocks), BLOCK, 0, ctx->stream>>>(out, c.d);
+    k_fill_zero<<<dim3(blocks), BLOCK, 0, st>>>(out, c.d);
   }
-  uint32_t* dir = R > 1 ? ctx->agg_dir : nullptr;   // allocated at qsl_create for operators whose messages are long
+  if (R == 1) dir = nullptr;
   if (dir) {                                        // long messages: a thread per entry, searches narrowed by the directories
-    k_msg_directory<<<dim3(std::min(2048u, (c.K + BLOCK - 1) / BLOCK), R), BLOCK, 0, ctx->stream>>>(c, msg, rows, dir, ctx->agg_ndir);
-    const uint32_t eb = std::min((c.K + BLOCK - 1) / BLOCK, std::max(4u, (ctx->nnz_hint + BLOCK - 1) / BLOCK));
-    k_aggregate_entries<<<dim3(eb, R), BLOCK, 0, ctx->stream>>>(c, msg, rows, R, scale, accumulate, out, dir, ctx->agg_ndir);
+    k_msg_directory<<<dim3(std::min(2048u, (c.K + BLOCK - 1) / BLOCK), R), BLOCK, 0, st>>>(c, msg, rows, dir, ndir);
+    const uint32_t eb = std::min((c.K + BLOCK - 1) / BLOCK, std::max(4u, (nnz_hint + BLOCK - 1) / BLOCK));
+    k_aggregate_entries<<<dim3(eb, R), BLOCK, 0, st>>>(c, msg, rows, R, scale, accumulate, out, dir, ndir);
   } else {                                          // short messages: 8 threads per entry, a block per expected tile of 32
     const uint32_t tiles = (c.K + AGG_ENTRIES - 1) / AGG_ENTRIES;
-    const uint32_t agg_blocks = std::min(tiles, std::max(16u, (ctx->nnz_hint + AGG_ENTRIES - 1) / AGG_ENTRIES));
-    k_aggregate<<<dim3(agg_blocks, R), BLOCK, 0, ctx->stream>>>(c, msg, rows, R, scale, accumulate, out);
+    const uint32_t agg_blocks = std::min(tiles, std::max(16u, (nnz_hint + AGG_ENTRIES - 1) / AGG_ENTRIES));
+    k_aggregate<<<dim3(agg_blocks, R), BLOCK, 0, st>>>(c, msg, rows, R, scale, accumulate, out);
   }
   QSL_HIP(hipGetLastError());
   return QSL_OK;
+}
+
+extern "C" qsl_status qsl_aggregate(qsl_ctx* ctx, const uint8_t* msg, const uint32_t* worker_list, uint32_t R,
+                                    float scale, int accumulate, float* out) {
+  if (!ctx || !msg || !out) return QSL_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(msg) & 7) || (reinterpret_cast<uintptr_t>(out) & 3)) return QSL_ERR_INVALID_ARG;
+  RowList rows;
+  const qsl_status st = make_row_list(worker_list, R, &rows);
+  if (st != QSL_OK) return st;
+  // the directories were allocated at qsl_create for operators whose messages are long
+  return launch_aggregate(ctx->dc, ctx->stream, ctx->nnz_hint, ctx->agg_dir, ctx->agg_ndir, msg, rows, R, scale,
+                          accumulate, out);
 }
 
 extern "C" qsl_status qsl_bits_sent(qsl_ctx* ctx, const uint8_t* msg, uint32_t R, uint64_t* bits_host) {
