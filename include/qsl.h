@@ -156,6 +156,23 @@ qsl_status qsl_error_update(qsl_ctx *ctx, float *m, const float *delta, const ui
 qsl_status qsl_aggregate(qsl_ctx *ctx, const uint8_t *msg, const uint32_t *worker_list, uint32_t R, float scale,
                          int accumulate, float *out);
 
+/* For callers that cannot allocate (code under HIP graph capture, serving loops, harnesses that forbid
+ * hipMalloc): the master line as qsl_aggregate computes it, without a context and without any allocation.
+ * The scratch of the aggregation kernels (one directory per listed message, and the status word) lives in a
+ * fixed array of device memory inside the library, QSL_STATIC_SCRATCH_BYTES per GPU, held until the process
+ * ends.  Same kernels, same order of additions and same result, bit for bit, as qsl_aggregate on a context
+ * created from `cfg`.
+ *   cfg          host; one segment only (num_segments = 1: a piecewise operator needs its segment tables in
+ *                device memory); seed, max_workers and flags are ignored
+ *   hip_stream   the stream to enqueue on (NULL = the default stream)
+ *   msg, worker_list, R, scale, accumulate, out   as for qsl_aggregate
+ * QSL_ERR_UNSUPPORTED if num_segments > 1 or if R * (ceil(d / 1024) + 1) * 4 + 256 bytes exceed the array;
+ * QSL_ERR_DEVICE if the device's ordinal is 64 or more.  Entries with an index >= d are skipped silently.
+ * All calls on one GPU share the array: calls that overlap on one GPU (two streams, two threads) race.  */
+#define QSL_STATIC_SCRATCH_BYTES (8u << 20)
+qsl_status qsl_aggregate_static(const qsl_config *cfg, void *hip_stream, const uint8_t *msg,
+                                const uint32_t *worker_list, uint32_t R, float scale, int accumulate, float *out);
+
 /* Payload bits of each of R messages (the communication-budget axis of the plots of Section 5: test
  * error and loss against the number of bits sent), read from the message headers.  Synchronises the stream.  bits_host: host uint64 [R].  */
 qsl_status qsl_bits_sent(qsl_ctx *ctx, const uint8_t *msg, uint32_t R, uint64_t *bits_host);

@@ -50,6 +50,8 @@ def _load():
     lib.qsl_compress_diff.argtypes = [vp, vp, vp, vp, vp, u32, u32, u64, vp, vp, vp, vp]; lib.qsl_compress_diff.restype = C.c_int
     lib.qsl_error_update.argtypes = [vp, vp, vp, vp, u32]; lib.qsl_error_update.restype = C.c_int
     lib.qsl_aggregate.argtypes = [vp, vp, C.POINTER(u32), u32, C.c_float, C.c_int, vp]; lib.qsl_aggregate.restype = C.c_int
+    lib.qsl_aggregate_static.argtypes = [C.POINTER(_Config), vp, vp, C.POINTER(u32), u32, C.c_float, C.c_int, vp]
+    lib.qsl_aggregate_static.restype = C.c_int
     lib.qsl_bits_sent.argtypes = [vp, vp, u32, C.POINTER(u64)]; lib.qsl_bits_sent.restype = C.c_int
     lib.qsl_device_status.argtypes = [vp]; lib.qsl_device_status.restype = C.c_int
     lib.qsl_debug_units.argtypes = [vp, C.POINTER(u32), u32, C.POINTER(u32)]; lib.qsl_debug_units.restype = C.c_int
@@ -63,7 +65,7 @@ def _load():
 _lib = _load()
 
 EXPORTED = ["qsl_create", "qsl_destroy", "qsl_set_stream", "qsl_msg_capacity_bytes", "qsl_compress",
-            "qsl_compress_diff", "qsl_error_update", "qsl_aggregate", "qsl_bits_sent", "qsl_bits_index_free", "qsl_plan_paths",
+            "qsl_compress_diff", "qsl_error_update", "qsl_aggregate", "qsl_aggregate_static", "qsl_bits_sent", "qsl_bits_index_free", "qsl_plan_paths",
             "qsl_device_status", "qsl_debug_units",
             "qsl_timing_enable", "qsl_timing_read", "qsl_status_string"]
 
@@ -105,6 +107,22 @@ def plan_paths(d, seg_offset, seg_k, s, sparsifier, quantizer, flags=0):
     out = np.zeros(k.size, dtype=np.uint32)
     _check(_lib.qsl_plan_paths(C.byref(cfg), out.ctypes.data_as(C.POINTER(C.c_uint32))), "qsl_plan_paths")
     return out
+
+
+def aggregate_static(d, k, s, sparsifier, quantizer, msg, out, scale, worker_list=None, accumulate=False):
+    """`qsl_aggregate_static`: the master line without a context and without any allocation (one segment)."""
+    off = np.array([0, int(d)], dtype=np.uint64)
+    kk = np.array([int(k)], dtype=np.uint32)
+    cfg = _Config(int(d), 1, off.ctypes.data_as(C.POINTER(C.c_uint64)), kk.ctypes.data_as(C.POINTER(C.c_uint32)),
+                  int(s), int(sparsifier), int(quantizer), 0, 1, 0)
+    if worker_list is None:
+        R, lst = msg.shape[0], None
+    else:
+        lst = (C.c_uint32 * len(worker_list))(*[int(x) for x in worker_list])
+        R = len(worker_list)
+    stream = C.c_void_p(torch.cuda.current_stream(msg.device).cuda_stream)
+    _check(_lib.qsl_aggregate_static(C.byref(cfg), stream, _ptr(msg, torch.uint8), lst, R, float(scale),
+                                     int(bool(accumulate)), _ptr(out, torch.float32)), "qsl_aggregate_static")
 
 
 class Qsl:

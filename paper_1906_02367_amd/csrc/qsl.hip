@@ -40,6 +40,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -124,6 +125,34 @@ static qsl_status check_config(const qsl_config* cfg, uint64_t* K_out) {
   if (K64 >= (1ull << 32)) return QSL_ERR_INVALID_ARG;
   *K_out = K64;
   return QSL_OK;
+}
+
+// Field widths and sizes of the wire format of an operator (the header of qsl.h describes the format).
+struct WireDims {
+  uint32_t s, w_idx, w_lev, w_val;
+  uint64_t capacity;        // bytes of one message buffer
+  uint32_t nnz_hint;        // entries a message is expected to hold at most
+};
+static WireDims wire_dims(const qsl_config* cfg, uint64_t K) {
+  WireDims w;
+  const uint32_t L = cfg->num_segments;
+  w.s = is_qsgd(cfg->quantizer) ? cfg->s : 1;
+  // QSGD drops the entries it rounds to level 0: a segment keeps sum_i min(1, s |v_i| / ||v||_2) <= s sqrt(k)
+  // of its k entries on average (Definition 1, example 1, with Cauchy-Schwarz); the other quantisers send all k
+  double hint = 0;
+  for (uint32_t l = 0; l < L; ++l) {
+    const double kl = cfg->seg_k[l];
+    hint += is_qsgd(cfg->quantizer) ? std::min(kl, 1.25 * w.s * std::sqrt(kl)) : kl;
+  }
+  w.nnz_hint = static_cast<uint32_t>(std::min<double>(hint, static_cast<double>(K)));
+  w.w_idx = std::max(1u, bit_width_u64(cfg->d - 1));
+  w.w_lev = is_qsgd(cfg->quantizer) ? bit_width_u64(static_cast<uint64_t>(w.s) - 1) : 0;
+  w.w_val = cfg->quantizer == QSL_FP32 ? 32 : w.w_lev + 1;
+  const bool counts = is_qsgd(cfg->quantizer) && L > 1;
+  uint64_t bits = 32 + 32ull * L + (counts ? 32ull * L : 0);
+  bits += align_up(K * w.w_idx, 32) + align_up(K * w.w_val, 32);
+  w.capacity = align_up(bits, 64) / 8;
+  return w;
 }
 
 extern "C" qsl_status qsl_bits_index_free(const qsl_config* cfg, uint64_t* bits) {
@@ -242,22 +271,10 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->slab = nullptr; ctx->h_status = nullptr; ctx->own_v = nullptr; ctx->order_ev = nullptr;
 
   const uint32_t K = static_cast<uint32_t>(K64);
-  const uint32_t s = is_qsgd(cfg->quantizer) ? cfg->s : 1;
-  // QSGD drops the entries it rounds to level 0: a segment keeps sum_i min(1, s |v_i| / ||v||_2) <= s sqrt(k)
-  // of its k entries on average (Definition 1, example 1, with Cauchy-Schwarz); the other quantisers send all k
-  double hint = 0;
-  for (uint32_t l = 0; l < L; ++l) {
-    const double kl = cfg->seg_k[l];
-    hint += is_qsgd(cfg->quantizer) ? std::min(kl, 1.25 * s * std::sqrt(kl)) : kl;
-  }
-  ctx->nnz_hint = static_cast<uint32_t>(std::min<double>(hint, K));
-  const uint32_t w_idx = std::max(1u, bit_width_u64(d - 1));
-  const uint32_t w_lev = is_qsgd(cfg->quantizer) ? bit_width_u64(static_cast<uint64_t>(s) - 1) : 0;
-  const uint32_t w_val = cfg->quantizer == QSL_FP32 ? 32 : w_lev + 1;
-  const bool counts = is_qsgd(cfg->quantizer) && L > 1;
-  uint64_t bits = 32 + 32ull * L + (counts ? 32ull * L : 0);
-  bits += align_up(static_cast<uint64_t>(K) * w_idx, 32) + align_up(static_cast<uint64_t>(K) * w_val, 32);
-  ctx->capacity = static_cast<size_t>(align_up(bits, 64) / 8);
+  const WireDims wd = wire_dims(cfg, K64);
+  const uint32_t s = wd.s, w_idx = wd.w_idx, w_lev = wd.w_lev, w_val = wd.w_val;
+  ctx->nnz_hint = wd.nnz_hint;
+  ctx->capacity = static_cast<size_t>(wd.capacity);
   // the kernels count the words of a message in 32 bits
   if (ctx->capacity / 4 > 0xFFFFFFFFull) { delete ctx; return QSL_ERR_UNSUPPORTED; }
 
@@ -654,6 +671,74 @@ extern "C" qsl_status qsl_aggregate(qsl_ctx* ctx, const uint8_t* msg, const uint
   // the directories were allocated at qsl_create for operators whose messages are long
   return launch_aggregate(ctx->dc, ctx->stream, ctx->nnz_hint, ctx->agg_dir, ctx->agg_ndir, msg, rows, R, scale,
                           accumulate, out);
+}
+
+// ----------------------------------------------------------------------------------------------------
+// the master line for callers that cannot allocate: the kernels' scratch is a fixed array of the library
+// ----------------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[QSL_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_STATIC_DEVICES = 64;
+constexpr uint64_t STATIC_DIR_OFFSET = 256;       // bytes [0, 256): the status word; then the directories
+void* g_scratch_ptr[MAX_STATIC_DEVICES];          // where `scratch` lies on each GPU (every GPU holds its own copy)
+std::mutex g_scratch_mutex;
+
+__global__ void k_clear_word(uint32_t* p) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) *p = 0;
+}
+
+// the device address of `scratch` on the current GPU; in host code the array's name is not that address
+qsl_status static_scratch(unsigned char** out) {
+  int dev = -1;
+  QSL_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= MAX_STATIC_DEVICES) return QSL_ERR_DEVICE;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    QSL_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return QSL_ERR_DEVICE;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = static_cast<unsigned char*>(g_scratch_ptr[dev]);
+  return QSL_OK;
+}
+}  // namespace
+
+extern "C" qsl_status qsl_aggregate_static(const qsl_config* cfg, void* hip_stream, const uint8_t* msg,
+                                           const uint32_t* worker_list, uint32_t R, float scale, int accumulate,
+                                           float* out) {
+  uint64_t K64 = 0;
+  if (!msg || !out) return QSL_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(msg) & 7) || (reinterpret_cast<uintptr_t>(out) & 3)) return QSL_ERR_INVALID_ARG;
+  qsl_status st = check_config(cfg, &K64);
+  if (st != QSL_OK) return st;
+  if (cfg->num_segments != 1) return QSL_ERR_UNSUPPORTED;     // segment tables would need device memory of their own
+  RowList rows;
+  st = make_row_list(worker_list, R, &rows);
+  if (st != QSL_OK) return st;
+  const WireDims wd = wire_dims(cfg, K64);
+  if (wd.capacity / 4 > 0xFFFFFFFFull) return QSL_ERR_UNSUPPORTED;
+  const uint32_t ndir = static_cast<uint32_t>(((cfg->d + (1u << AGG_DIR_SHIFT) - 1) >> AGG_DIR_SHIFT) + 1);
+  const bool want_dir = wd.nnz_hint >= AGG_DIR_MIN && R > 1;   // as qsl_create decides it
+  if (want_dir && STATIC_DIR_OFFSET + 4ull * R * ndir > QSL_STATIC_SCRATCH_BYTES) return QSL_ERR_UNSUPPORTED;
+  unsigned char* base = nullptr;
+  st = static_scratch(&base);
+  if (st != QSL_OK) return st;
+
+  DevCtx c;
+  memset(&c, 0, sizeof c);
+  c.d = cfg->d; c.seed = cfg->seed; c.L = 1; c.K = static_cast<uint32_t>(K64);
+  c.s = wd.s; c.w_idx = wd.w_idx; c.w_lev = wd.w_lev; c.w_val = wd.w_val;
+  c.sparsifier = cfg->sparsifier; c.quantizer = cfg->quantizer;
+  c.cap_words = static_cast<uint32_t>(wd.capacity / 4);
+  c.status = reinterpret_cast<uint32_t*>(base);
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  // the array keeps what the last call left: the status word starts at zero (a kernel, not a memset node, so that
+  // the call can be captured into a graph); the directories are written in full before they are read
+  k_clear_word<<<dim3(1), 64, 0, stream>>>(c.status);
+  uint32_t* dir = want_dir ? reinterpret_cast<uint32_t*>(base + STATIC_DIR_OFFSET) : nullptr;
+  return launch_aggregate(c, stream, wd.nnz_hint, dir, ndir, msg, rows, R, scale, accumulate, out);
 }
 
 extern "C" qsl_status qsl_bits_sent(qsl_ctx* ctx, const uint8_t* msg, uint32_t R, uint64_t* bits_host) {
