@@ -89,6 +89,8 @@ enum {
                                  exact multi-pass selection only (testing, comparison)                  */
   QSL_FLAG_NO_SMALL_PATH = 2, /* segments of at most 4096 coordinates also take the multi-pass kernels
                                  instead of the one-block selection (testing, comparison)               */
+  QSL_FLAG_NO_WARM_START = 8, /* every call guesses its thresholds from a fresh sample of m + delta, as the first call
+                                 does, instead of taking them from the previous call's candidates (testing, comparison) */
   QSL_FLAG_OWN_V = 4          /* the context also allocates a float [max_workers, d] array of its own as the home
                                  of v = m + delta, so that qsl_compress / qsl_compress_diff accept m_out = NULL
                                  ("send g, leave the error memory alone")                               */

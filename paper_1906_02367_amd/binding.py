@@ -19,6 +19,7 @@ QSGD, SIGN_L1, SIGN_L2, FP32, QSGD_SCALED = 0, 1, 2, 3, 4
 FLAG_NO_FAST_PATH = 1
 FLAG_NO_SMALL_PATH = 2
 FLAG_OWN_V = 4
+FLAG_NO_WARM_START = 8
 
 OK, ERR_INVALID_ARG, ERR_BUFFER_TOO_SMALL, ERR_NONFINITE_INPUT, ERR_DEVICE, ERR_UNSUPPORTED = range(6)
 

@@ -50,6 +50,7 @@
 #include "qsl_stream.h"
 #include "qsl_select.h"
 #include "qsl_encode.h"
+#include "qsl_lean.h"
 #include "qsl_decode.h"
 
 namespace {
@@ -76,6 +77,10 @@ struct qsl_ctx {
   uint32_t* agg_dir;          // [64][agg_ndir] directories of the listed messages (only if messages are expected to be long)
   uint32_t agg_ndir;
   uint32_t n_sampled;         // segments whose guess comes from k_sample
+  uint32_t nsel_general, ncb_general;   // blocks of the multi-pass kernels without / with (DevCtx::NSEL, NCB) the guessing units' share
+  uint32_t n_other;           // segments that k_quantize encodes (not the guessing ones)
+  uint32_t warm_R;            // workers whose guessing units carry a guess from an earlier call
+  uint32_t safe_left;         // calls still to be made with the multi-pass kernels standing by for failed guesses
   uint32_t nsamp_blocks;      // blocks of the sampling kernel (per worker)
   size_t capacity;
   uint32_t* h_status;         // pinned
@@ -213,7 +218,21 @@ static double plan_segment(const qsl_config* cfg, SegInfo& sg) {
         slack = 2048.0;
       }
       if (cand != 0) {                            // else: too dense for the slots, the unit takes the multi-pass kernels
-        sg.d0_cap = static_cast<uint32_t>(std::min<double>(n, 4.0 * cand + slack));
+        // Later calls take their guess from the previous call's candidates: the key at rank alpha_w k, far enough below
+        // rank k for the count above it to stay above k from one call to the next (6.5 sigma of its own noise, and at
+        // least a half more than k for drift).
+        double alpha_w = cand / sg.k;
+        for (double alpha : alphas)
+          if ((alpha - 1) * std::sqrt(static_cast<double>(sg.k)) >= 6.5 * std::sqrt(alpha) && fits(alpha)) { alpha_w = alpha; break; }
+        sg.r_warm = static_cast<uint32_t>(std::min<double>(n, std::ceil(alpha_w * sg.k)));
+        // where the threshold itself should show in the sample (half the expected count: rather too high than too low)
+        sg.r_tau = sg.samp_stride == 64 ? std::max(1u, sg.k / 4)
+                                        : std::max(1u, static_cast<uint32_t>(0.5 * sg.n_runs * 64.0 * p));
+        sg.r_tau = std::min(sg.r_tau, sg.r_s);
+        cand = std::max(cand, alpha_w * sg.k);
+        // room for sixteen times the expected candidates: a guess carried over from the last call may lie well below
+        // this call's threshold while the error memory is still building up
+        sg.d0_cap = static_cast<uint32_t>(std::min<double>(n, 16.0 * cand + slack));
         sg.mode = PATH_FAST;
       }
     } else if (cfg->sparsifier == QSL_RANDK && static_cast<uint64_t>(sg.k) * 16 <= sg.size) {
@@ -223,6 +242,7 @@ static double plan_segment(const qsl_config* cfg, SegInfo& sg) {
         sg.T_static = static_cast<uint32_t>(std::floor(4294967296.0 * (1.0 - q)));
         cand = q * n;
         sg.d0_cap = static_cast<uint32_t>(std::min<double>(n, cand + 8.0 * std::sqrt(cand) + 1024.0));
+        sg.r_warm = sg.k; sg.r_tau = 1;
         sg.mode = PATH_FAST;
       }
     }
@@ -253,7 +273,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const qsl_status cfg_status = check_config(cfg, &K64);
   if (cfg_status != QSL_OK) return cfg_status;
   if (cfg->max_workers == 0 || cfg->max_workers > 1024) return QSL_ERR_INVALID_ARG;
-  if (cfg->flags & ~static_cast<uint32_t>(QSL_FLAG_NO_FAST_PATH | QSL_FLAG_NO_SMALL_PATH | QSL_FLAG_OWN_V)) return QSL_ERR_INVALID_ARG;
+  if (cfg->flags & ~static_cast<uint32_t>(QSL_FLAG_NO_FAST_PATH | QSL_FLAG_NO_SMALL_PATH | QSL_FLAG_OWN_V | QSL_FLAG_NO_WARM_START)) return QSL_ERR_INVALID_ARG;
   const uint64_t d = cfg->d;
   const uint32_t L = cfg->num_segments;
 
@@ -266,7 +286,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->cfg.seg_k = ctx->k.data();
   ctx->stream = static_cast<hipStream_t>(hip_stream);
   ctx->Rmax = cfg->max_workers;
-  ctx->last_R = 0;
+  ctx->last_R = 0; ctx->warm_R = 0; ctx->safe_left = 0;
   ctx->timing = 0; ctx->ev_used = 0;
   ctx->slab = nullptr; ctx->h_status = nullptr; ctx->own_v = nullptr; ctx->order_ev = nullptr;
 
@@ -309,12 +329,13 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
       // take every candidate
       const double per_chunk = cand / sg.nwt, need = per_chunk + 4.0 * std::sqrt(per_chunk);
       sg.lpc = need <= 7.0 ? 4 : need <= 15.0 ? 8 : 16;
+      sg.fidx = static_cast<uint32_t>(fast.size());
       fast.push_back(l);
       sg.slot_off = slot_elems; slot_elems += static_cast<uint64_t>(sg.nwt) * sg.lpc * 2;
       sg.ovf_cap = sg.d0_cap;
       sg.ovf_off = ovf_entries; ovf_entries += sg.ovf_cap;
       sg.d0_off = d0_entries; d0_entries += sg.d0_cap;
-      sg.ncb = (sg.d0_cap + DTILE - 1) / DTILE;
+      sg.ncb = std::min<uint32_t>(256, (sg.nwt + GGROUP - 1) / GGROUP);    // for the call in which its guess fails
     } else if (sg.mode == PATH_SMALL) {
       smalls.push_back(l);
       sg.nsel = 0; sg.ncb = 0;
@@ -342,12 +363,23 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   }
   if (fast_blocks > 256)
     for (uint32_t l : fast) segs[l].nsel = static_cast<uint32_t>(std::max<uint64_t>(1, segs[l].nsel * 256ull / fast_blocks));
+  // The block lists of the multi-pass kernels: the units that always take them first, then the guessing units, whose
+  // share is launched only while the host expects failed guesses.  A guessing unit's blocks are also the blocks of
+  // k_lean_* (fsels).
+  std::vector<SelInfo> fsels, sels_f;
+  std::vector<CbInfo> cbs_f;
+  uint32_t cb_slots = 0;
   for (uint32_t l = 0; l < L; ++l) {
     SegInfo& sg = segs[l];
-    for (uint32_t j = 0; j < sg.nsel; ++j) { SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0; sels.push_back(si); }
+    const bool guessing = sg.mode == PATH_FAST;
+    for (uint32_t j = 0; j < sg.nsel; ++j) {
+      SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0;
+      (guessing ? sels_f : sels).push_back(si);
+      if (guessing) fsels.push_back(si);
+    }
     sg.wc_base = static_cast<uint32_t>(nwc); nwc += sg.nsel * (BIG / 64);
-    sg.cb_base = static_cast<uint32_t>(cbs.size());
-    for (uint32_t b = 0; b < sg.ncb; ++b) { CbInfo ci; ci.seg = l; ci.b = b; ci.pad0 = ci.pad1 = 0; cbs.push_back(ci); }
+    sg.cb_base = cb_slots; cb_slots += sg.ncb;
+    for (uint32_t b = 0; b < sg.ncb; ++b) { CbInfo ci; ci.seg = l; ci.b = b; ci.pad0 = ci.pad1 = 0; (guessing ? cbs_f : cbs).push_back(ci); }
   }
   // The launch lists in decreasing order of a block's work: the blocks of a kernel start over several microseconds
   // (the waves of a few hundred 1024-thread blocks), and the kernel ends when the slowest block does, so the heavy
@@ -358,13 +390,23 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
     if (sg.mode == PATH_FAST) return 1.2 * static_cast<double>((static_cast<uint64_t>(sg.nwt) * sg.lpc + 63) / 64) / sg.nsel / 16.0;
     return 0.8 * static_cast<double>(sg.nwt) / sg.nsel;
   };
-  std::stable_sort(sels.begin(), sels.end(), [&](const SelInfo& a, const SelInfo& b) { return select_cost(a) > select_cost(b); });
+  auto by_select_cost = [&](const SelInfo& a, const SelInfo& b) { return select_cost(a) > select_cost(b); };
+  std::stable_sort(sels.begin(), sels.end(), by_select_cost);
+  std::stable_sort(fsels.begin(), fsels.end(), by_select_cost);
+  auto general_cost = [&](uint32_t seg) { return static_cast<double>(segs[seg].nwt) / segs[seg].nsel; };
+  std::stable_sort(sels_f.begin(), sels_f.end(), [&](const SelInfo& a, const SelInfo& b) { return general_cost(a.seg) > general_cost(b.seg); });
   auto compact_cost = [&](const CbInfo& ci) {
     const SegInfo& sg = segs[ci.seg];
-    if (sg.mode == PATH_FAST) return 1.0;
-    return 16.0 * std::max(1.0, static_cast<double>((sg.nwt + GGROUP - 1) / GGROUP) / sg.ncb);
+    return std::max(1.0, static_cast<double>((sg.nwt + GGROUP - 1) / GGROUP) / sg.ncb);
   };
-  std::stable_sort(cbs.begin(), cbs.end(), [&](const CbInfo& a, const CbInfo& b) { return compact_cost(a) > compact_cost(b); });
+  auto by_compact_cost = [&](const CbInfo& a, const CbInfo& b) { return compact_cost(a) > compact_cost(b); };
+  std::stable_sort(cbs.begin(), cbs.end(), by_compact_cost);
+  std::stable_sort(cbs_f.begin(), cbs_f.end(), by_compact_cost);
+  ctx->nsel_general = static_cast<uint32_t>(sels.size());
+  ctx->ncb_general = static_cast<uint32_t>(cbs.size());
+  sels.insert(sels.end(), sels_f.begin(), sels_f.end());
+  cbs.insert(cbs.end(), cbs_f.begin(), cbs_f.end());
+  ctx->n_other = L - static_cast<uint32_t>(fast.size());
   // a sample block's work: its share of the unit's runs (or chunks, when the whole unit is read); a small unit's: its size
   auto sample_cost = [&](const SelInfo& si) {
     const SegInfo& sg = segs[si.seg];
@@ -375,6 +417,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->nsamp_blocks = static_cast<uint32_t>(samps.size());
   const uint32_t NWT = static_cast<uint32_t>(nwt64);
   const uint32_t NSEL = static_cast<uint32_t>(sels.size()), NCB = static_cast<uint32_t>(cbs.size());
+  const uint32_t NSELF = static_cast<uint32_t>(fsels.size());
   const uint32_t NWC = static_cast<uint32_t>(nwc);
   const uint32_t QB = (K + BLOCK - 1) / BLOCK;
   const uint64_t R = ctx->Rmax, U = R * L;
@@ -388,6 +431,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t o_segs = carve(sizeof(SegInfo) * L), o_wts = carve(sizeof(WtInfo) * std::max<size_t>(1, wts.size()));
   const uint64_t o_sels = carve(sizeof(SelInfo) * NSEL), o_cbs = carve(sizeof(CbInfo) * NCB);
   const uint64_t o_samps = carve(sizeof(SelInfo) * samps.size());
+  const uint64_t o_fsels = carve(sizeof(SelInfo) * std::max<size_t>(1, fsels.size()));
   const uint64_t o_fulls = carve(sizeof(SelInfo) * std::max<size_t>(1, fulls.size()));
   const uint64_t o_fast = carve(4ull * std::max<size_t>(1, fast.size()));
   const uint64_t o_small = carve(4ull * std::max<size_t>(1, smalls.size()));
@@ -416,7 +460,8 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t o_okey = carve(randk ? 4ull * std::max<uint64_t>(1, ovf_entries) * R : 4);
   const uint64_t o_d0 = carve(8ull * std::max<uint64_t>(1, d0_entries) * R);
   const uint64_t o_d0k = carve(4ull * std::max<uint64_t>(1, d0_entries) * R);
-  const uint64_t o_wc = carve(4ull * NWC * R), o_cbc = carve(8ull * NCB * R);
+  const uint64_t o_wc = carve(4ull * NWC * R), o_ws = carve(4ull * NWC * R), o_cbc = carve(8ull * NCB * R);
+  const uint64_t o_tlist = carve(16ull * LISTCAP * std::max<size_t>(1, fast.size()) * R);
   const uint64_t o_si = carve(4ull * K * R), o_sv = carve(4ull * K * R), o_sc = carve(4ull * K * R);
   const uint64_t o_blk = carve(4ull * QB * R), o_pre = carve(4ull * (QB + 1) * R);
   const uint64_t o_vi = carve(4ull * K * R), o_vc = carve(4ull * K * R);
@@ -435,6 +480,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   upload(o_wts, wts.data(), sizeof(WtInfo) * wts.size());
   upload(o_sels, sels.data(), sizeof(SelInfo) * NSEL);
   upload(o_samps, samps.data(), sizeof(SelInfo) * samps.size());
+  upload(o_fsels, fsels.data(), sizeof(SelInfo) * fsels.size());
   upload(o_fulls, fulls.data(), sizeof(SelInfo) * fulls.size());
   upload(o_cbs, cbs.data(), sizeof(CbInfo) * NCB);
   upload(o_fast, fast.data(), 4 * fast.size());
@@ -442,7 +488,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   upload(o_big, bigs.data(), 4 * bigs.size());
   upload(o_segdir, seg_dir.data(), 4 * seg_dir.size());
   upload(o_slotdir, slot_dir.data(), 4 * slot_dir.size());
-  ok = ok && hipHostMalloc(reinterpret_cast<void**>(&ctx->h_status), 64, hipHostMallocDefault) == hipSuccess;
+  ok = ok && hipHostMalloc(reinterpret_cast<void**>(&ctx->h_status), 64, hipHostMallocMapped) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&ctx->order_ev, hipEventDisableTiming) == hipSuccess;
   ok = ok && hipDeviceSynchronize() == hipSuccess;
   if (!ok) {
@@ -458,6 +504,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.wts = reinterpret_cast<const WtInfo*>(base + o_wts);
   c.sels = reinterpret_cast<const SelInfo*>(base + o_sels);
   c.samps = reinterpret_cast<const SelInfo*>(base + o_samps);
+  c.fsels = reinterpret_cast<const SelInfo*>(base + o_fsels);
   c.cbs = reinterpret_cast<const CbInfo*>(base + o_cbs);
   c.fast_segs = reinterpret_cast<const uint32_t*>(base + o_fast);
   c.small_segs = reinterpret_cast<const uint32_t*>(base + o_small);
@@ -473,7 +520,18 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.slot_key = reinterpret_cast<uint32_t*>(base + o_skey); c.ovf_key = reinterpret_cast<uint32_t*>(base + o_okey);
   c.d0 = reinterpret_cast<uint2*>(base + o_d0); c.d0_key = reinterpret_cast<uint32_t*>(base + o_d0k);
   c.d0_stride = std::max<uint64_t>(1, d0_entries);
-  c.wave_cnt = reinterpret_cast<uint32_t*>(base + o_wc); c.cb_cnt = reinterpret_cast<uint2*>(base + o_cbc);
+  c.wave_cnt = reinterpret_cast<uint32_t*>(base + o_wc); c.wave_sel = reinterpret_cast<uint32_t*>(base + o_ws);
+  c.cb_cnt = reinterpret_cast<uint2*>(base + o_cbc);
+  c.tlist = reinterpret_cast<uint4*>(base + o_tlist);
+  ctx->h_status[8] = 0;
+  {
+    void* dflag = nullptr;                          // the device's address of a word of the pinned host block
+    if (hipHostGetDevicePointer(&dflag, ctx->h_status + 8, 0) != hipSuccess || !dflag) {
+      (void)hipFree(ctx->slab); (void)hipHostFree(ctx->h_status); (void)hipEventDestroy(ctx->order_ev); delete ctx;
+      return QSL_ERR_DEVICE;
+    }
+    c.host_flag = static_cast<uint32_t*>(dflag);
+  }
   c.hist = reinterpret_cast<uint32_t*>(base + o_hist); c.ctr = reinterpret_cast<uint32_t*>(base + o_ctr);
   c.norm_acc = reinterpret_cast<uint64_t*>(base + o_acc);
   c.sel_idx = reinterpret_cast<uint32_t*>(base + o_si); c.sel_val = reinterpret_cast<uint32_t*>(base + o_sv);
@@ -485,7 +543,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->agg_dir = want_dir ? reinterpret_cast<uint32_t*>(base + o_dir) : nullptr;
   ctx->own_v = (cfg->flags & QSL_FLAG_OWN_V) ? reinterpret_cast<float*>(base + o_ownv) : nullptr;
   c.d = d; c.seed = cfg->seed; c.L = L; c.K = K; c.NWT = NWT; c.NSEL = NSEL; c.NCB = NCB; c.NWC = NWC; c.QB = QB;
-  c.nfast = static_cast<uint32_t>(fast.size()); c.s = s; c.w_idx = w_idx; c.w_lev = w_lev; c.w_val = w_val;
+  c.NSELF = NSELF; c.nfast = static_cast<uint32_t>(fast.size()); c.s = s; c.w_idx = w_idx; c.w_lev = w_lev; c.w_val = w_val;
   c.sparsifier = cfg->sparsifier; c.quantizer = cfg->quantizer;
   c.cap_words = static_cast<uint32_t>(ctx->capacity / 4);
   ctx->one.start = 0; ctx->one.size = segs[0].size; ctx->one.slot_off = 0; ctx->one.ovf_off = 0;
@@ -532,12 +590,20 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
                                   uint16_t* sel_level) {
   const DevCtx& c = ctx->dc;
   hipStream_t st = ctx->stream;
-  if (static_cast<uint64_t>(std::max(std::max(c.NSEL, c.NCB), std::max(ctx->nsamp_blocks, ctx->nsmall))) * R > 0x7FFFFFFFull)
+  if (static_cast<uint64_t>(std::max(std::max(c.NSEL, c.NCB), std::max(std::max(ctx->nsamp_blocks, ctx->nsmall), c.NSELF + c.nfast))) * R > 0x7FFFFFFFull)
     return QSL_ERR_UNSUPPORTED;                    // the list kernels use one-dimensional grids of (list entries x workers)
-  if (SPARS == QSL_TOPK && ctx->n_sampled > 0) {
+  // A kernel that had to resolve a failed guess with one block (slow for a large unit) leaves a word in pinned host
+  // memory; the next calls then keep the multi-pass kernels standing by for the units whose guess fails.  The word
+  // may be seen a few calls late: only speed depends on it, never the result.
+  if (ctx->h_status[8] != 0) { ctx->h_status[8] = 0; ctx->safe_left = 16; }
+  const bool safe = ctx->safe_left > 0;
+  if (safe) --ctx->safe_left;
+  const bool cold = ctx->warm_R < R || (ctx->cfg.flags & QSL_FLAG_NO_WARM_START) != 0;
+  if (SPARS == QSL_TOPK && ctx->n_sampled > 0 && cold) {
     k_sample<<<dim3(ctx->nsamp_blocks * R), BIG, 0, st>>>(c, m, delta, xm, R);
     k_sample_scan<<<dim3(c.nfast, R), BIG, 0, st>>>(c);
   }
+  ctx->warm_R = std::max(ctx->warm_R, R);
   const bool timed = ctx->timing != 0;
   if (timed) {
     if (ctx->ev_used + 2 > ctx->ev.size()) {
@@ -561,15 +627,25 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
 
   if (ctx->nsmall) k_small<SPARS><<<dim3(ctx->nsmall * R), BLOCK, 0, st>>>(c, m_out, worker0, round, R);
   if (ctx->nfull_blocks) k_full<<<dim3(ctx->nfull_blocks, R), BLOCK, 0, st>>>(c, m_out);
-  if (c.NSEL) {                                    // units that take a launch per digit and two for the compaction
-    k_select<0, SPARS><<<dim3(c.NSEL * R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
-    k_select<1, SPARS><<<dim3(c.NSEL * R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
-    k_select<2, SPARS><<<dim3(c.NSEL * R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
-    k_tile_count<SPARS><<<dim3(c.NCB * R), BLOCK, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
-    k_tile_write<SPARS><<<dim3(c.NCB * R), BLOCK, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
+  if (c.NSELF) {                                   // guessing units: candidates' histogram, threshold bin and dense list
+    k_lean_hist<SPARS><<<dim3(c.NSELF * R), BIG, 0, st>>>(c, ctx->segs[0], R);
+    k_lean_mark<SPARS><<<dim3(c.NSELF * R), BIG, 0, st>>>(c, ctx->segs[0], R);
   }
-  k_quantize<<<dim3(c.QB, R), BLOCK, 0, st>>>(c, m_out, worker0, round, sel_idx, sel_level);
-  if (is_qsgd(c.quantizer)) {                      // the other quantisers send every selected coordinate: k_quantize wrote the final arrays
+  // the multi-pass kernels: a launch per digit and two for the compaction, for the units planned that way -- and for
+  // the guessing units too while failed guesses are expected
+  const uint32_t nsel = safe ? c.NSEL : ctx->nsel_general, ncb = safe ? c.NCB : ctx->ncb_general;
+  if (nsel) {
+    k_select<0, SPARS><<<dim3(nsel * R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
+    k_select<1, SPARS><<<dim3(nsel * R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
+    k_select<2, SPARS><<<dim3(nsel * R), BIG, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
+    k_tile_count<SPARS><<<dim3(ncb * R), BLOCK, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
+    k_tile_write<SPARS><<<dim3(ncb * R), BLOCK, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
+  }
+  if (ctx->n_other || safe) k_quantize<<<dim3(c.QB, R), BLOCK, 0, st>>>(c, m_out, worker0, round, sel_idx, sel_level, safe ? 1 : 0);
+  if (c.NSELF)                                     // ... their exact threshold, ordered output and codes; one more block per unit for failures
+    k_lean_emit<SPARS><<<dim3((c.NSELF + c.nfast) * R), BIG, 0, st>>>(c, ctx->segs[0], R, c.NSELF * R, m_out, worker0, round,
+                                                                     sel_idx, sel_level, safe ? 1 : 0);
+  if (is_qsgd(c.quantizer)) {                      // the other quantisers send every selected coordinate: the final arrays are written already
     if (c.QB > MAX_QB_INLINE) k_surv_scan<<<dim3(R), 1024, 0, st>>>(c);
     k_surv_compact<<<dim3(c.QB, R), BLOCK, 0, st>>>(c);
   }
@@ -774,7 +850,7 @@ extern "C" qsl_status qsl_debug_units(qsl_ctx* ctx, uint32_t* out_host, uint32_t
   for (uint32_t u = 0; u < U; ++u) {
     uint32_t* o = out_host + 8ull * u;
     o[0] = us[u].path == PATH_FAST && us[u].fell_back ? static_cast<uint32_t>(PATH_FALLBACK) : us[u].path;
-    o[1] = us[u].cand; o[2] = us[u].tau; o[3] = us[u].n_gt; o[4] = us[u].need; o[5] = us[u].T;
+    o[1] = us[u].cand; o[2] = us[u].tau; o[3] = us[u].n_gt; o[4] = us[u].need; o[5] = us[u].path == PATH_FAST ? us[u].T_used : us[u].T;
     o[6] = us[u].scale_bits; o[7] = us[u].nnz;
   }
   *n_units = U;

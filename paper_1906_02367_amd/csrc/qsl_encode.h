@@ -82,10 +82,71 @@ __device__ __forceinline__ float qsgd_value(float N, uint32_t level, uint32_t s,
   return neg ? -mag : mag;
 }
 
+// The scale of a unit: what the codes are computed with (the norm, or the magnitude of a sign entry) and what the
+// message carries -- the same, or N / (1 + beta_{k,s}) for the scaled composition (Lemma 2).
+struct UnitScale { float scale, sent; };
+
+__device__ __forceinline__ UnitScale unit_scale(const DevCtx& c, float sc, uint32_t kl) {
+  UnitScale r; r.scale = sc; r.sent = sc;
+  if (c.quantizer == QSL_QSGD_SCALED) {
+    const double beta = fmin(static_cast<double>(kl) / (static_cast<double>(c.s) * c.s), sqrt(static_cast<double>(kl)) / c.s);
+    r.sent = sc / static_cast<float>(1.0 + beta);
+  }
+  return r;
+}
+
+// One selected coordinate (slot `slot` of the worker-major [R][K] arrays; coordinate idx, value bits): its code
+// (QSGD: Definition 1, example 1; Sign: Definition 2), the arrays the message is packed from, the error update
+// m <- v - g on a transmitted coordinate (Algorithm 1, second worker line), the optional debug outputs.
+// Returns whether the coordinate is transmitted.  rk1: the random stream of the QSGD rounding.
+__device__ __forceinline__ bool encode_entry(const DevCtx& c, uint32_t w, uint64_t slot, uint32_t idx, uint32_t bits,
+                                             UnitScale us, const RandKey& rk1, float* m_out, uint32_t* dbg_idx,
+                                             uint16_t* dbg_level) {
+  const float v = __uint_as_float(bits);
+  const bool neg = v < 0.0f;
+  uint32_t level;
+  float g;
+  if (is_qsgd(c.quantizer)) {
+    level = 0;
+    if (us.scale > 0.0f) {
+      const float a = fabsf(v) / us.scale;
+      float t = a * static_cast<float>(c.s);
+      if (t > static_cast<float>(c.s)) t = static_cast<float>(c.s);
+      const float fl = floorf(t);
+      const float frac = t - fl;
+      const float r01 = static_cast<float>(rand_word(rk1, idx) >> 8) * 0x1p-24f;
+      level = static_cast<uint32_t>(fl) + (r01 < frac ? 1u : 0u);
+    }
+    g = qsgd_value(us.sent, level, c.s, neg);
+  } else if (c.quantizer == QSL_FP32) {
+    level = 1;
+    g = v;
+  } else {
+    level = 1;
+    g = neg ? -us.scale : us.scale;
+  }
+  const bool sent = level != 0;
+  if (is_qsgd(c.quantizer)) { c.sel_idx[slot] = idx; c.sel_code[slot] = level | (neg ? 0x80000000u : 0u); }   // k_surv_compact reads both
+  else {                                                 // every selected coordinate is sent: nothing to compact
+    c.surv_idx[slot] = idx;
+    c.surv_code[slot] = c.quantizer == QSL_FP32 ? bits : (neg ? 1u : 0u);
+  }
+  if (sent) {
+    if (idx < c.d) m_out[static_cast<uint64_t>(w) * c.d + idx] = v - g;
+    else atomicOr(c.status, 2u);                       // cannot happen: a selected slot was never written
+  }
+  if (dbg_idx) dbg_idx[slot] = idx;
+  if (dbg_level) dbg_level[slot] = static_cast<uint16_t>(level);
+  return sent;
+}
+
+// The units that k_lean_emit has already encoded are skipped here: a guessing unit, unless its guess failed and
+// the multi-pass kernels of this call took it over (`safe`).
 __global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint32_t worker0, uint64_t round,
-                                                    uint32_t* dbg_idx, uint16_t* dbg_level) {
+                                                    uint32_t* dbg_idx, uint16_t* dbg_level, int safe) {
   __shared__ uint32_t s_w[BLOCK / 64];
-  __shared__ float s_scale[BLOCK], s_sent[BLOCK];
+  __shared__ float s_scale[BLOCK];
+  __shared__ uint32_t s_mine[BLOCK];
   const uint32_t w = blockIdx.y;
   const uint32_t j = blockIdx.x * BLOCK + threadIdx.x;
   // the scales of the units this block's slots belong to (at most one unit per slot)
@@ -95,72 +156,42 @@ __global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint
   for (uint32_t i = threadIdx.x >> 6; i <= seg_last - seg_first; i += BLOCK / 64) {     // a wave per unit
     const uint32_t seg = seg_first + i;
     const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
-    const uint32_t kl = c.segs[seg].k;
-    const float sc = finalize_scale(c.norm_acc + u * ACC_SLOTS, c.quantizer, kl);
+    const UnitState us = c.units[u];
+    const bool mine = !(us.path == PATH_FAST && !(safe && us.fell_back));
+    float sc = 0.0f;
+    if (mine) sc = finalize_scale(c.norm_acc + u * ACC_SLOTS, c.quantizer, c.segs[seg].k);
     if (lane_id() == 0) {
       s_scale[i] = sc;
-      // what the message carries: the scale itself, or N / (1 + beta_{k,s}) for the scaled composition (Lemma 2)
-      float sent = sc;
-      if (c.quantizer == QSL_QSGD_SCALED) {
-        const double beta = fmin(static_cast<double>(kl) / (static_cast<double>(c.s) * c.s), sqrt(static_cast<double>(kl)) / c.s);
-        sent = sc / static_cast<float>(1.0 + beta);
-      }
-      s_sent[i] = sent;
-      if (c.segs[seg].koff >= j_first) c.units[u].scale_bits = __float_as_uint(sent);   // the block holding the unit's first slot
+      s_mine[i] = mine;
+      // the block holding the unit's first slot records what the message carries
+      if (mine && c.segs[seg].koff >= j_first) c.units[u].scale_bits = __float_as_uint(unit_scale(c, sc, c.segs[seg].k).sent);
     }
   }
   __syncthreads();
-  uint32_t sent = 0;
+  bool sent = false;
   if (j < c.K) {
     const uint32_t seg = c.L == 1 ? 0u : seg_of_slot(c, j);
-    const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
-    const uint64_t slot = static_cast<uint64_t>(w) * c.K + j;
-    const uint32_t idx = c.sel_idx[slot], bits = c.sel_val[slot];
-    const float scale = s_scale[seg - seg_first];
-    const float v = __uint_as_float(bits);
-    const bool neg = v < 0.0f;
-    uint32_t level;
-    float g;
-    if (is_qsgd(c.quantizer)) {
-      level = 0;
-      if (scale > 0.0f) {
-        const float a = fabsf(v) / scale;
-        float t = a * static_cast<float>(c.s);
-        if (t > static_cast<float>(c.s)) t = static_cast<float>(c.s);
-        const float fl = floorf(t);
-        const float frac = t - fl;
-        const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 1);
-        const float r01 = static_cast<float>(rand_word(rk, idx) >> 8) * 0x1p-24f;
-        level = static_cast<uint32_t>(fl) + (r01 < frac ? 1u : 0u);
-      }
-      g = qsgd_value(s_sent[seg - seg_first], level, c.s, neg);
-    } else if (c.quantizer == QSL_FP32) {
-      level = 1;
-      g = v;
-    } else {
-      level = 1;
-      g = neg ? -scale : scale;
+    if (s_mine[seg - seg_first]) {
+      const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
+      const uint64_t slot = static_cast<uint64_t>(w) * c.K + j;
+      const RandKey rk1 = make_rand_key(c.seed, worker0 + w, round, 1);
+      sent = encode_entry(c, w, slot, c.sel_idx[slot], c.sel_val[slot], unit_scale(c, s_scale[seg - seg_first], c.segs[seg].k),
+                          rk1, m_out, dbg_idx, dbg_level);
+      if (sent && is_qsgd(c.quantizer) && c.L > 1) atomicAdd(&c.units[u].nnz, 1u);
     }
-    sent = level != 0;
-    if (is_qsgd(c.quantizer)) c.sel_code[slot] = level | (neg ? 0x80000000u : 0u);
-    else {                                                 // every selected coordinate is sent: nothing to compact
-      c.surv_idx[slot] = idx;
-      c.surv_code[slot] = c.quantizer == QSL_FP32 ? bits : (neg ? 1u : 0u);
-    }
-    if (sent) {
-      if (idx < c.d) m_out[static_cast<uint64_t>(w) * c.d + idx] = v - g;
-      else atomicOr(c.status, 2u);                       // cannot happen: a selected slot was never written
-      if (is_qsgd(c.quantizer) && c.L > 1) atomicAdd(&c.units[u].nnz, 1u);
-    }
-    if (dbg_idx) dbg_idx[slot] = idx;
-    if (dbg_level) dbg_level[slot] = static_cast<uint16_t>(level);
   }
   if (!is_qsgd(c.quantizer)) return;                       // survivors are counted only where some may drop out
   const uint32_t wc = __popcll(__ballot(sent));
   if (lane_id() == 0) s_w[threadIdx.x >> 6] = wc;
   __syncthreads();
   uint32_t* cnt = c.blk_cnt + static_cast<uint64_t>(w) * c.QB;
-  if (threadIdx.x == 0) cnt[blockIdx.x] = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+  // with guessing units in the plan a block of 256 slots may also hold entries that k_lean_emit encodes: the counts
+  // are then added (k_lean_hist has set them to zero); else this kernel is their only writer
+  if (threadIdx.x == 0) {
+    const uint32_t n = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+    if (c.nfast == 0) cnt[blockIdx.x] = n;
+    else if (n) atomicAdd(&cnt[blockIdx.x], n);
+  }
 }
 
 // sum of cnt[0 .. n), by the whole block
@@ -252,6 +283,12 @@ __global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t
       ct[(static_cast<uint64_t>(c.fast_segs[i / CTR_LINES]) * CTR_LINES + i % CTR_LINES) * PAD] = 0;
     uint64_t* na = c.norm_acc + static_cast<uint64_t>(w) * c.L * ACC_SLOTS;
     for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * ACC_SLOTS; i += nth) na[i] = 0;
+    // ... and the guess that this call's candidates suggest becomes the next call's
+    if (c.sparsifier == QSL_TOPK)
+      for (uint64_t i = tid; i < c.nfast; i += nth) {
+        UnitState* us = &c.units[static_cast<uint64_t>(w) * c.L + c.fast_segs[i]];
+        us->T_used = us->T; us->T = us->T_next; us->sh = us->sh_next;
+      }
   }
   const uint64_t nnz = !is_qsgd(c.quantizer) ? c.K
                        : c.QB > MAX_QB_INLINE ? c.blk_pre[static_cast<uint64_t>(w) * (c.QB + 1) + c.QB]

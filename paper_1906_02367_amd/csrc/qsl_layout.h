@@ -23,7 +23,9 @@ constexpr uint32_t NSUB = 64;              // candidate counters per unit: chunk
 constexpr uint32_t PAD = 64;               // words between two counters: atomics that share a cache line serialise
 constexpr uint32_t CTR_OVF = NSUB;         // counter NSUB: cursor of the unit's overflow pool
 constexpr uint32_t CTR_FAIL = NSUB + 1;    // counter NSUB + 1: set when the overflow pool ran out
-constexpr uint32_t CTR_LINES = NSUB + 2;
+constexpr uint32_t CTR_LIST = NSUB + 2;    // counter NSUB + 2: entries in the unit's list of threshold-bin candidates
+constexpr uint32_t CTR_LINES = NSUB + 3;
+constexpr uint32_t LISTCAP = 256;          // entries of that list; a threshold bin that holds more sends the unit to the block-wide selection
 
 enum : uint32_t { PATH_FAST = 0, PATH_GENERAL = 1, PATH_FALLBACK = 2, PATH_SMALL = 3, PATH_FULL = 4 };
 constexpr uint32_t MAX_FULL_BLOCKS = 512;  // blocks per unit of k_full (each ends with up to 20 atomics on the unit's digit counters)
@@ -48,6 +50,10 @@ struct SegInfo {
   uint32_t T_static;     // Rand_k: analytic guess
   uint32_t nsel;         // blocks of this unit in the selection kernels
   uint32_t samp_stride;  // sample: distance between the starts of two runs (64: the whole unit is read)
+  uint32_t r_warm;       // rank (among this call's candidates) whose bin edge becomes the next call's guess
+  uint32_t r_tau;        // sample rank that estimates the threshold itself (for the width of the histogram bins)
+  uint32_t fidx;         // number of this segment among the guessing ones
+  uint32_t pad0;
 };
 
 struct WtInfo { uint32_t seg, chunk, pad0, pad1; };                 // one chunk (multi-segment contexts only)
@@ -59,19 +65,25 @@ struct CbInfo { uint32_t seg, b, pad0, pad1; };                     // one compa
 // blocks the new value).
 struct UnitState {
   uint32_t path;        // static: PATH_FAST, PATH_GENERAL, PATH_SMALL or PATH_FULL
-  uint32_t T;           // guess key (k_sample_scan; static for Rand_k and for the general path)
-  uint32_t cand;        // candidates collected (k_select<0>)
-  uint32_t fell_back;   // 1: the guess failed, the unit runs the general path (k_select<0>)
+  uint32_t T;           // guess key of this call (k_sample_scan on a cold start; else rolled over from T_next by k_pack;
+                        // static for Rand_k and for the general path)
+  uint32_t sh;          // the candidates' histogram has bins of 2^sh keys above T (same sources as T)
+  uint32_t T_next, sh_next;   // guess and bin width for the next call, from this call's candidates (k_lean_mark)
+  uint32_t T_used;      // the guess the last call worked with (k_pack; diagnostics)
+  uint32_t cand;        // candidates collected (k_lean_hist)
+  uint32_t fell_back;   // 1: the guess failed -- too few candidates or no room for them (k_lean_hist)
+  uint32_t crowded;     // 1: the threshold's bin holds more than LISTCAP candidates (k_lean_mark)
+  uint32_t taubin, above;     // bin of the k-th largest candidate, candidates in the bins above it (k_lean_mark)
   uint32_t prefix1, k_rem1; // radix selection state after the first digit (found by k_select<1> from the first histogram) ...
   uint32_t prefix2, k_rem2; // ... and after the second (k_select<2>); the third is found by k_tile_count
   uint32_t tau, need, n_gt; // threshold key, how many equal to it are kept, how many above (k_tile_count)
   uint32_t nnz;         // transmitted coordinates (zeroed by k_select<0>, counted by k_quantize)
-  uint32_t scale_bits;  // fp32 scale (k_quantize)
-  uint32_t pad;
+  uint32_t scale_bits;  // fp32 scale (k_quantize, k_lean_emit)
 };
 
 struct DevCtx {
   const SegInfo* segs; const WtInfo* wts; const SelInfo* sels; const SelInfo* samps; const CbInfo* cbs;
+  const SelInfo* fsels;     // one entry per block of the guessing units' kernels (k_lean_*)
   const uint32_t* fast_segs;
   const uint32_t* small_segs;
   const SelInfo* fulls;     // one entry per block of k_full: (segment with k = size, block number)
@@ -83,7 +95,10 @@ struct DevCtx {
   uint2* ovf; uint64_t ovf_stride;      // per worker: overflow pools, for chunks with more candidates than a slot holds
   uint32_t* slot_key; uint32_t* ovf_key; // Rand_k only: the rank key (random word) of every slot element / pool entry
   uint2* d0; uint32_t* d0_key; uint64_t d0_stride;   // per worker: dense, coordinate-ordered candidate lists (+ keys, Rand_k)
-  uint32_t* wave_cnt;   // [R][NWC]: candidates met by each wave of k_select<0>
+  uint32_t* wave_cnt;   // [R][NWC]: candidates met by each wave of k_lean_hist
+  uint32_t* wave_sel;   // [R][NWC]: of these, how many lie in the bins above the threshold's (k_lean_mark)
+  uint4* tlist;         // [R][nfast][LISTCAP]: the candidates in the threshold's bin: (place in the dense list, value bits, key, -)
+  uint32_t* host_flag;  // pinned host memory: set when a failed guess had to be resolved by one block reading the whole unit
   uint2* cb_cnt;        // [R][NCB]: (#key > tau, #key == tau) of each compaction block
   uint32_t* hist;       // [U][3][HBINS], one histogram per radix digit; all zero between calls
   uint32_t* ctr;        // [U][CTR_LINES][PAD]; word 0 of each line is a counter; all zero between calls
@@ -94,10 +109,17 @@ struct DevCtx {
   uint32_t* surv_idx; uint32_t* surv_code;                    // [R][K]
   uint32_t* status;
   uint64_t d, seed;
-  uint32_t L, K, NWT, NSEL, NCB, NWC, QB, nfast, nbig, s, w_idx, w_lev, w_val, sparsifier, quantizer, cap_words;
+  uint32_t L, K, NWT, NSEL, NCB, NWC, QB, NSELF, nfast, nbig, s, w_idx, w_lev, w_val, sparsifier, quantizer, cap_words;
 };
 
 __device__ __forceinline__ uint32_t key_of_value(uint32_t vbits) { return (vbits & 0x7FFFFFFFu) << 1; }
+
+// Bin of a candidate's key in the histogram of a guessing unit: bins of 2^sh keys counted from the guess T
+// (every candidate has key >= T); whatever lies beyond the 4095 bins above T shares the last one.
+__device__ __forceinline__ uint32_t lean_bin(uint32_t key, uint32_t T, uint32_t sh) {
+  const uint32_t x = (key - T) >> sh;
+  return x < HBINS - 1 ? x : HBINS - 1;
+}
 
 // quantiser families: QSGD and its scaled form (Lemma 2) share everything but the transmitted norm
 __host__ __device__ __forceinline__ bool is_qsgd(uint32_t q) { return q == QSL_QSGD || q == QSL_QSGD_SCALED; }
@@ -150,6 +172,56 @@ __device__ uint32_t find_from_top(uint32_t* hist, uint32_t target, uint32_t* abo
   __syncthreads();
   *above = result[1];
   return result[0];
+}
+
+// The same scan for two ranks at once (t0 <= t1).  result[0], result[1]: bin and count above it for t0; result[2],
+// result[3]: for t1; result[4]: entries in the bin of t0; result[5]: entries in all.  A rank beyond the total gives
+// bin 0 with "above" = total - hist[0], as in find_from_top.
+template <uint32_t NT, uint32_t COPIES = 1>
+__device__ void find2_from_top(uint32_t* hist, uint32_t t0, uint32_t t1, uint64_t* scratch, uint32_t* result, bool clear) {
+  constexpr uint32_t PER = HBINS / NT;
+  static_assert(PER >= 1 && PER * NT == HBINS, "bins must divide evenly over the threads");
+  const uint32_t t = threadIdx.x;
+  uint32_t h[PER]; uint32_t sum = 0;
+#pragma unroll
+  for (uint32_t j = 0; j < PER; ++j) {
+    h[j] = 0;
+#pragma unroll
+    for (uint32_t cp = 0; cp < COPIES; ++cp) h[j] += hist[cp * HBINS + HBINS - 1 - (PER * t + j)];
+    sum += h[j];
+  }
+  uint64_t total;
+  const uint64_t before = block_exclusive_scan64(sum, scratch, &total);
+  if (t == NT - 1) {
+    const uint32_t rest = static_cast<uint32_t>(total) - h[PER - 1];
+    result[0] = 0; result[1] = rest; result[2] = 0; result[3] = rest; result[4] = h[PER - 1]; result[5] = static_cast<uint32_t>(total);
+  }
+  __syncthreads();
+#pragma unroll
+  for (uint32_t which = 0; which < 2; ++which) {
+    const uint32_t target = which ? t1 : t0;
+    if (before < target && before + sum >= target) {
+      uint32_t cum = static_cast<uint32_t>(before);
+#pragma unroll
+      for (uint32_t j = 0; j < PER; ++j) {
+        if (cum + h[j] >= target) {
+          result[2 * which] = HBINS - 1 - (PER * t + j); result[2 * which + 1] = cum;
+          if (which == 0) result[4] = h[j];
+          break;
+        }
+        cum += h[j];
+      }
+    }
+  }
+  if (clear) {
+#pragma unroll
+    for (uint32_t j = 0; j < PER; ++j)
+      if (h[j]) {
+#pragma unroll
+        for (uint32_t cp = 0; cp < COPIES; ++cp) hist[cp * HBINS + HBINS - 1 - (PER * t + j)] = 0;
+      }
+  }
+  __syncthreads();
 }
 
 __device__ __forceinline__ void flush_hist(const uint32_t* lh, uint32_t* gh) {

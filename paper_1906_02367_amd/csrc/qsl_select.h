@@ -72,21 +72,16 @@ __device__ __forceinline__ bool level_bin(uint32_t key, uint32_t prefix, uint32_
   *bin = key & 0xFFu; return (key >> 8) == (prefix >> 8);
 }
 
-// Digit LEVEL of the k-th largest key.  The blocks of a unit build the digit's histogram (LDS, then
-// a few global atomics per bin); which bin the previous digit fell in is recomputed by every block
-// from the previous kernel's histogram.
-//   fast unit, digit 0: reads the slot rows (every wave a contiguous range) and leaves the number of
-//                       candidates each wave met;
-//   fast unit, digit 1: reads them again and writes all candidates, in coordinate order, into the
-//                       unit's dense list (the offset of a wave = sum of the earlier waves' counts);
-//   fast unit, digit 2: reads the dense list;
-//   general path:       reads v.
+// Digit LEVEL of the k-th largest key of a unit on the multi-pass path: the blocks of the unit read v and build the
+// digit's histogram (LDS, then a few global atomics per bin); which bin the previous digit fell in is recomputed by
+// every block from the previous kernel's histogram.  A guessing unit is listed here too, for the call in which its
+// guess failed and the host asked for this chain (`safe` launches); otherwise its blocks return at once.
 template <int LEVEL, int SPARS>
 __global__ __launch_bounds__(BIG) void k_select(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round,
                                                 uint32_t R) {
   __shared__ uint32_t lh[HBINS];
   __shared__ uint64_t scratch[17];
-  __shared__ uint32_t result[2], s_ctr[CTR_LINES];
+  __shared__ uint32_t result[6];
   // a single-segment context carries its plan in the kernel arguments: one dependent load less per block
   // one-dimensional grid, the workers innermost: the blocks of the plan's list start in list order (heaviest
   // first) for all workers alike, instead of worker after worker
@@ -97,28 +92,27 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, SegInfo one, const flo
   const uint64_t u = static_cast<uint64_t>(w) * c.L + si.seg;
   UnitState* usp = &c.units[u];
   const UnitState us = *usp;
+  if (us.path == PATH_FAST && !us.fell_back) return;         // its guess held: k_lean_* select it
   uint32_t* hist = c.hist + u * 3 * HBINS;
   for (uint32_t i = threadIdx.x; i < HBINS; i += BIG) lh[i] = 0;
-  if (LEVEL == 0 && threadIdx.x < CTR_LINES)
-    s_ctr[threadIdx.x] = sg.mode == PATH_FAST ? c.ctr[(u * CTR_LINES + threadIdx.x) * PAD] : 0u;
   __syncthreads();
-  uint32_t path, prefix = 0, k_rem = sg.k;
+  uint32_t prefix = 0, k_rem = sg.k;
   if (LEVEL == 0) {
-    // a guess that produced too few candidates, or more than there is room for, is discarded here
-    path = us.path;
-    if (path == PATH_FAST) {
-      uint32_t cand = 0;
-      for (uint32_t i = 0; i < NSUB; ++i) cand += s_ctr[i];
-      if (s_ctr[CTR_FAIL] || cand < sg.k || cand > sg.d0_cap) path = PATH_FALLBACK;
-      if (threadIdx.x == 0 && si.j == 0) { usp->cand = cand; usp->fell_back = path == PATH_FALLBACK; }
-    } else if (threadIdx.x == 0 && si.j == 0) { usp->cand = 0; usp->fell_back = 0; }
-    if (threadIdx.x == 0 && si.j == 0) usp->nnz = 0;
+    if (us.path != PATH_FAST && threadIdx.x == 0 && si.j == 0) { usp->cand = 0; usp->fell_back = 0; usp->nnz = 0; }
   } else {
-    path = eff_path(us);
     uint32_t above;
     if (LEVEL == 1) {
-      const uint32_t bin = find_from_top<BIG>(hist, sg.k, &above, scratch, result, false);
+      // (for a guessing unit whose guess failed also rank r_warm >= k: its next guess comes from this histogram of
+      // the whole unit, as after a fresh sample)
+      find2_from_top<BIG>(hist, sg.k, us.path == PATH_FAST ? sg.r_warm : sg.k, scratch, result, false);
+      const uint32_t bin = result[0];
+      above = result[1];
       prefix = bin << 20; k_rem = sg.k - above;
+      if (SPARS == QSL_TOPK && us.path == PATH_FAST && threadIdx.x == 0 && si.j == 0) {
+        uint32_t sh = 11;
+        while (sh < 20 && (1u << (sh - 11)) < bin + 1 - result[2]) ++sh;
+        usp->T_next = result[2] << 20; usp->sh_next = sh;
+      }
     } else {
       const uint32_t bin = find_from_top<BIG>(hist + HBINS, us.k_rem1, &above, scratch, result, false);
       prefix = us.prefix1 | (bin << 8); k_rem = us.k_rem1 - above;
@@ -130,81 +124,7 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, SegInfo one, const flo
   }
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  if (path == PATH_FAST && LEVEL < 2) {
-    const uint2* slots = c.slots + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off;
-    const uint2* ovf = c.ovf + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off;
-    const uint32_t* slot_key = SPARS == QSL_RANDK ? c.slot_key + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off : nullptr;
-    const uint32_t* ovf_key = SPARS == QSL_RANDK ? c.ovf_key + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off : nullptr;
-    uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
-    uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
-    uint32_t* wcnt = c.wave_cnt + static_cast<uint64_t>(w) * c.NWC + sg.wc_base;
-    const uint32_t nrows = static_cast<uint32_t>((static_cast<uint64_t>(sg.nwt) * sg.lpc + 63) >> 6);   // < 2^20
-    const uint32_t nwaves = sg.nsel * (BIG / 64), gw = si.j * (BIG / 64) + wave;
-    const uint32_t rpw = (nrows + nwaves - 1) / nwaves;
-    const uint64_t r_lo = static_cast<uint64_t>(gw) * rpw, r_hi = r_lo + rpw < nrows ? r_lo + rpw : nrows;
-    uint32_t seen = 0;                              // digit 0: candidates this wave met
-    uint32_t off = 0;                               // digit 1: where this wave's candidates go in the dense list
-    if (LEVEL == 1) {                               // at most MAX_SELECT_BLOCKS * 16 = 1024 waves: 16 loads in flight
-      uint32_t part[MAX_SELECT_BLOCKS * (BIG / 64) / WAVE];
-#pragma unroll
-      for (uint32_t i = 0; i < MAX_SELECT_BLOCKS * (BIG / 64) / WAVE; ++i) {
-        const uint32_t g = i * WAVE + lane;
-        part[i] = g < gw ? wcnt[g] : 0u;
-      }
-      uint32_t x = 0;
-#pragma unroll
-      for (uint32_t i = 0; i < MAX_SELECT_BLOCKS * (BIG / 64) / WAVE; ++i) x += part[i];
-      off = wave_sum(x);
-    }
-    for (uint64_t row0 = r_lo; row0 < r_hi; row0 += 4) {
-      SlotRow rr[4];                               // four independent accesses in flight; rows past the end read as empty
-#pragma unroll
-      for (int b = 0; b < 4; ++b) rr[b] = read_slot_row(slots, slot_key, sg.lpc, sg.nwt, row0 + b, r_hi);
-#pragma unroll
-      for (int b = 0; b < 4; ++b) {
-        const SlotRow& r = rr[b];
-        uint32_t pos = 0, tot = 0;
-        if (LEVEL == 0) seen += r.n;
-        else { pos = off + wave_exclusive_scan32(r.n, &tot); off += tot; }
-        if (!r.spill) {
-          uint32_t bin;
-          if (r.has0) {
-            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(r.bits0) : r.key0;
-            if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
-            if (LEVEL == 1) { d0[pos] = make_uint2(r.idx0, r.bits0); if (SPARS == QSL_RANDK) d0k[pos] = key; ++pos; }
-          }
-          if (r.has1) {
-            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(r.bits1) : r.key1;
-            if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
-            if (LEVEL == 1) { d0[pos] = make_uint2(r.idx1, r.bits1); if (SPARS == QSL_RANDK) d0k[pos] = key; }
-          }
-        }
-        // chunks whose candidates went to the overflow pool: the whole wave reads each one's entries, 64 at a time
-        // (one lane walking them alone was the last wave to finish whenever a chunk had spilled)
-        for (uint64_t spilled = __ballot(r.spill); spilled; spilled &= spilled - 1) {
-          const int holder = __ffsll(static_cast<unsigned long long>(spilled)) - 1;
-          const uint32_t cnt = __shfl(r.count, holder, WAVE), at = __shfl(r.ovf_at, holder, WAVE);
-          const uint32_t first = __shfl(pos, holder, WAVE);
-          for (uint32_t e = lane; e < cnt; e += WAVE) {
-            const uint2 ent = ovf[at + e];
-            const uint32_t key = SPARS == QSL_TOPK ? key_of_value(ent.y) : ovf_key[at + e];
-            uint32_t bin;
-            if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
-            if (LEVEL == 1) { d0[first + e] = ent; if (SPARS == QSL_RANDK) d0k[first + e] = key; }
-          }
-        }
-      }
-    }
-    if (LEVEL == 0) { seen = wave_sum(seen); if (lane == 0) wcnt[gw] = seen; }
-  } else if (path == PATH_FAST) {
-    const uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
-    const uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
-    for (uint32_t e = si.j * BIG + threadIdx.x; e < us.cand; e += sg.nsel * BIG) {
-      const uint32_t key = SPARS == QSL_TOPK ? key_of_value(d0[e].y) : d0k[e];
-      uint32_t bin;
-      if (level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
-    }
-  } else {
+  {
     const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
     const uint32_t nwaves = sg.nsel * (BIG / 64);
     // a wave takes two chunks per step, 32 values per lane in flight
@@ -249,17 +169,15 @@ __global__ __launch_bounds__(BIG) void k_select(DevCtx c, SegInfo one, const flo
 // ------------------------------------------------------------------------------------------------
 // ordered compaction of the selected coordinates, with the exact norm of what is selected.
 //
-// A "compaction block" covers either a tile of 2048 entries of a fast unit's dense candidate list
-// (each thread 8 consecutive entries), or, on the general path, a contiguous range of groups of 16
-// chunks of v (a group at a time: each wave 4 chunks, a lane 16 coordinates of a chunk; one group per
-// block while the unit has at most 256 groups).  k_tile_count leaves the number of selected
-// coordinates of every block; k_tile_write sums the earlier blocks' numbers to know where it writes.
-// A fast unit whose guess failed runs the general path with the blocks it has.
+// A "compaction block" covers a contiguous range of groups of 16 chunks of v (a group at a time: each wave
+// 4 chunks, a lane 16 coordinates of a chunk; one group per block while the unit has at most 256 groups).
+// k_tile_count leaves the number of selected coordinates of every block; k_tile_write sums the earlier
+// blocks' numbers to know where it writes.  A guessing unit whose guess failed runs here with the blocks
+// the plan gives it for that case.
 //
 // Exact norms: every |v| (or v^2) is an integer multiple of 2^-149 (2^-298); its 32-bit digits are
 // added into 64-bit counters; integer addition commutes, so any schedule gives the same sum.
 // ------------------------------------------------------------------------------------------------
-constexpr uint32_t DTILE = 2048;           // dense-list entries per compaction block
 constexpr uint32_t GGROUP = 16;            // chunks per general-path group
 constexpr uint32_t ACC_ROWS = 32;          // accumulator rows of a compaction block (8 per wave)
 
@@ -629,7 +547,7 @@ __global__ __launch_bounds__(BLOCK) void k_full(DevCtx c, const float* v) {
 template <int SPARS>
 __global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, SegInfo one, const float* v, uint32_t worker0, uint64_t round,
                                                       uint32_t R) {
-  __shared__ uint32_t s_cnt[2 * GGROUP + 2], s_red[8], result[2];
+  __shared__ uint32_t s_cnt[2 * GGROUP + 2], result[2];
   __shared__ uint64_t scratch[17];
   const uint32_t li = blockIdx.x / R, w = blockIdx.x % R;             // workers innermost, as in k_select
   CbInfo cb; cb.seg = 0; cb.b = li;
@@ -637,33 +555,11 @@ __global__ __launch_bounds__(BLOCK) void k_tile_count(DevCtx c, SegInfo one, con
   const SegInfo sg = c.L == 1 ? one : c.segs[cb.seg];
   const uint64_t u = static_cast<uint64_t>(w) * c.L + cb.seg;
   const UnitState us = c.units[u];
-  const uint32_t path = eff_path(us);
-  if (path == PATH_FAST && cb.b != 0 && cb.b * DTILE >= us.cand) {         // a tile past the end of the dense list
-    if (threadIdx.x == 0) c.cb_cnt[static_cast<uint64_t>(w) * c.NCB + sg.cb_base + cb.b] = make_uint2(0, 0);
-    return;
-  }
+  if (us.path == PATH_FAST && !us.fell_back) return;         // its guess held: k_lean_* select it
   const Thresh th = last_digit(c, u, us, scratch, result);
   if (threadIdx.x == 0 && cb.b == 0) { c.units[u].tau = th.tau; c.units[u].need = th.need; c.units[u].n_gt = sg.k - th.need; }
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   uint2* out = c.cb_cnt + static_cast<uint64_t>(w) * c.NCB + sg.cb_base + cb.b;
-  if (path == PATH_FAST) {
-    const uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
-    const uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
-    uint32_t gt = 0, eq = 0;
-    const uint32_t e0 = cb.b * DTILE + threadIdx.x * 8;
-#pragma unroll
-    for (uint32_t i = 0; i < 8; ++i) {
-      if (e0 + i < us.cand) {
-        const uint32_t key = SPARS == QSL_TOPK ? key_of_value(d0[e0 + i].y) : d0k[e0 + i];
-        gt += key > th.tau; eq += key == th.tau;
-      }
-    }
-    gt = wave_sum(gt); eq = wave_sum(eq);
-    if (lane_id() == 0) { s_red[threadIdx.x >> 6] = gt; s_red[4 + (threadIdx.x >> 6)] = eq; }
-    __syncthreads();
-    if (threadIdx.x == 0) *out = make_uint2(s_red[0] + s_red[1] + s_red[2] + s_red[3], s_red[4] + s_red[5] + s_red[6] + s_red[7]);
-    return;
-  }
   uint32_t g_lo, g_hi;
   fallback_range(sg, cb.b, &g_lo, &g_hi);
   uint32_t tg = 0, tq = 0;
@@ -684,8 +580,7 @@ __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, SegInfo one, con
   const SegInfo sg = c.L == 1 ? one : c.segs[cb.seg];
   const uint64_t u = static_cast<uint64_t>(w) * c.L + cb.seg;
   const UnitState us = c.units[u];
-  const uint32_t path = eff_path(us);
-  if (path == PATH_FAST && cb.b * DTILE >= us.cand) return;                 // a tile past the end of the dense list
+  if (us.path == PATH_FAST && !us.fell_back) return;         // its guess held: k_lean_* select it
   Thresh th; th.tau = us.tau; th.need = us.need;
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
@@ -705,34 +600,7 @@ __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, SegInfo one, con
   const uint32_t gt0 = static_cast<uint32_t>(before), eq0 = static_cast<uint32_t>(before >> 32);
   uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
   uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
-  if (path == PATH_FAST) {
-    const uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
-    const uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
-    const uint32_t e0 = cb.b * DTILE + threadIdx.x * 8;
-    uint2 ent[8]; uint32_t gm = 0, qm = 0;
-#pragma unroll
-    for (uint32_t i = 0; i < 8; ++i) {
-      ent[i] = make_uint2(0, 0);
-      if (e0 + i < us.cand) {
-        ent[i] = d0[e0 + i];
-        const uint32_t key = SPARS == QSL_TOPK ? key_of_value(ent[i].y) : d0k[e0 + i];
-        gm |= (key > th.tau ? 1u : 0u) << i; qm |= (key == th.tau ? 1u : 0u) << i;
-      }
-    }
-    uint64_t total;
-    const uint64_t ex = block_exclusive_scan64((static_cast<uint64_t>(__popc(qm)) << 32) | __popc(gm), scratch, &total);
-    uint32_t my_gt = gt0 + static_cast<uint32_t>(ex), my_eq = eq0 + static_cast<uint32_t>(ex >> 32);
-#pragma unroll
-    for (uint32_t i = 0; i < 8; ++i) {
-      const bool is_gt = (gm >> i) & 1u, is_eq = (qm >> i) & 1u;
-      if (is_gt || (is_eq && my_eq < th.need)) {
-        const uint32_t pos = my_gt + min(my_eq, th.need);
-        oi[pos] = ent[i].x; ov[pos] = ent[i].y;
-        add_digits(mine, ent[i].y, squares);
-      }
-      my_gt += is_gt; my_eq += is_eq;
-    }
-  } else {
+  {
     uint32_t g_lo, g_hi;
     fallback_range(sg, cb.b, &g_lo, &g_hi);
     uint32_t tg, tq;

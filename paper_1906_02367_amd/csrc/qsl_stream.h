@@ -16,9 +16,13 @@ __global__ void k_init(DevCtx c, uint32_t U) {
   const uint32_t u = blockIdx.x * blockDim.x + threadIdx.x;
   if (u >= U) return;
   const SegInfo& sg = c.segs[u % c.L];
-  UnitState s;
-  s.path = sg.mode; s.T = sg.mode == PATH_FAST ? sg.T_static : 0xFFFFFFFFu; s.cand = 0; s.fell_back = 0;
-  s.prefix1 = 0; s.k_rem1 = sg.k; s.prefix2 = 0; s.k_rem2 = sg.k; s.tau = 0; s.need = 0; s.n_gt = 0; s.nnz = 0; s.scale_bits = 0; s.pad = 0;
+  UnitState s = {};
+  s.path = sg.mode; s.T = sg.mode == PATH_FAST ? sg.T_static : 0xFFFFFFFFu;
+  // Rand_k: the keys are uniform words, the guess and the bins are fixed: 4096 bins over [T, 2^32)
+  s.sh = 0;
+  while (s.sh < 20 && ((0xFFFFFFFFu - s.T) >> s.sh) >= HBINS) ++s.sh;
+  s.T_next = s.T; s.sh_next = s.sh; s.T_used = s.T;
+  s.k_rem1 = sg.k; s.k_rem2 = sg.k;
   c.units[u] = s;
 }
 
@@ -98,12 +102,20 @@ __global__ __launch_bounds__(BIG) void k_sample(DevCtx c, const float* m, const 
 
 __global__ __launch_bounds__(BIG) void k_sample_scan(DevCtx c) {
   __shared__ uint64_t scratch[17];
-  __shared__ uint32_t result[2];
+  __shared__ uint32_t result[6];
   const uint32_t seg = c.fast_segs[blockIdx.x], w = blockIdx.y;
   const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
-  uint32_t above;
-  const uint32_t bin = find_from_top<BIG, HBINS, 3>(c.hist + u * 3 * HBINS, c.segs[seg].r_s, &above, scratch, result, true);
-  if (threadIdx.x == 0) c.units[u].T = bin << 20;      // the guess: lower edge of the bin
+  const SegInfo& sg = c.segs[seg];
+  // two ranks of the sample: r_s, far enough down for the guess to lie below the true threshold, and r_tau <= r_s,
+  // about where the threshold itself lies -- the distance between the two sets the width of the candidates' bins
+  find2_from_top<BIG, 3>(c.hist + u * 3 * HBINS, sg.r_tau, sg.r_s, scratch, result, true);
+  if (threadIdx.x == 0) {
+    const uint32_t bin_tau = result[0], bin_s = result[2];
+    uint32_t sh = 11;                                   // 4096 bins over 8 x (estimated threshold - guess)
+    while (sh < 20 && (1u << (sh - 11)) < bin_tau + 1 - bin_s) ++sh;
+    c.units[u].T = bin_s << 20;                         // the guess: lower edge of the bin
+    c.units[u].sh = sh;
+  }
 }
 
 // ------------------------------------------------------------------------------------------------

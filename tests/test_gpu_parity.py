@@ -476,3 +476,62 @@ def test_side_stream_gives_the_same_bytes(P):
     assert torch.equal(msga, msgb) and torch.equal(ma.view(torch.int32), mb.view(torch.int32))
     assert torch.equal(xa.view(torch.int32), xb.view(torch.int32))
     assert qa.device_status() == B.OK and qb.device_status() == B.OK
+
+
+# ---------------------------------------------------------------------------------------------
+# the guess carried from call to call: what happens when the next call's values do not look like the last one's
+# ---------------------------------------------------------------------------------------------
+def test_guess_from_the_previous_call_survives_a_change_of_the_inputs(P):
+    """From the second call on a guessing unit takes its threshold guess from the previous call's candidates.  Inputs
+    that collapse (v a thousandth of what it was: too few candidates), then grow a millionfold (too many), then
+    settle: every round bit for bit the oracle's; the round of a jump runs through the failure path (reported as
+    path 2), the round after it is back on the short one."""
+    d, k, R = 1_000_003, 1000, 2
+    rng = np.random.default_rng(77)
+    for qz, s, flags in [(W.QSGD, 16, 0), (W.SIGN_L1, 1, 0), (W.QSGD, 16, 8)]:       # 8: a fresh sample every call
+        wl = custom(d, [0, d], [k], s, W.TOPK, qz, R)
+        op = P.oracle_for(wl)
+        deltas = [rng.standard_normal((R, d)).astype(f32) for _ in range(2)]
+        m = np.zeros((R, d), dtype=f32)
+        for t in range(2):                                   # the memory after two rounds, from the oracle
+            m = np.stack([o["m_out"] for o in P.oracle_round(op, m, deltas[t], t)])
+        deltas.append((-m + 1e-3 * rng.standard_normal((R, d))).astype(f32))          # v collapses
+        deltas += [(rng.standard_normal((R, d)) * sc).astype(f32) for sc in (1e-3, 1e3, 1e3, 1.0, 1.0)]
+        run, op, m_host, paths = P.run_parity(wl, len(deltas), deltas=deltas, flags=flags)
+        seen = [sorted(set(p.tolist())) for p in paths]
+        print("paths per round:", seen)
+        assert seen[0] == [0] and seen[1] == [0]
+        if flags == 0:
+            assert 2 in seen[2] and 2 in seen[4], seen            # the rounds of the two jumps take the failure path ...
+            assert seen[3] == [0] and seen[5] == [0] and seen[7] == [0], seen     # ... and the next ones do not
+        else:
+            assert all(sset == [0] for sset in seen), seen        # a fresh sample never fails on these inputs
+
+
+def test_ties_at_the_threshold_beyond_the_short_list(P):
+    """Thousands of equal magnitudes exactly at the threshold: the threshold's histogram bin holds more candidates
+    than the short list takes, so one block selects the unit from its dense candidate list (ties to the lower
+    coordinate)."""
+    d, k, R = 1_000_003, 4000, 2
+    rng = np.random.default_rng(78)
+    wl = custom(d, [0, d], [k], 16, W.TOPK, W.QSGD, R)
+    deltas = []
+    for t in range(3):
+        x = (rng.standard_normal((R, d)) * 0.01).astype(f32)
+        for r in range(R):
+            big = rng.choice(d, 6000, replace=False)
+            x[r, big[:3000]] = (10.0 + rng.random(3000)).astype(f32) * np.sign(rng.standard_normal(3000)).astype(f32)
+            x[r, big[3000:]] = f32(5.0) * np.sign(rng.standard_normal(3000)).astype(f32)     # 3000 ties; 1000 of them are kept
+        deltas.append(x)
+    run, op, m_host, paths = P.run_parity(wl, 3, deltas=deltas)
+    print("paths:", [p.tolist() for p in paths])
+
+
+def test_guess_carried_over_layerwise_and_rand_k(P):
+    # several rounds on the segmented and the Rand_k shapes: guesses of many units carried along
+    wl = W.config(4, d=6_000_000, R=3)
+    P.run_parity(wl, 5)
+    wl = W.config(3, d=2_000_003, R=2)
+    P.run_parity(wl, 4, expect_path=0)
+    wl = W.config(5, d=8_000_003, R=2)
+    P.run_parity(wl, 4, expect_path=0)
