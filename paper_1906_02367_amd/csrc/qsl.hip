@@ -47,9 +47,9 @@
 #include "qsl.h"
 #include "qsl_device.h"
 #include "qsl_layout.h"
-#include "qsl_stream.h"
 #include "qsl_select.h"
 #include "qsl_encode.h"
+#include "qsl_stream.h"
 #include "qsl_lean.h"
 #include "qsl_decode.h"
 
@@ -81,12 +81,16 @@ struct qsl_ctx {
   uint32_t n_other;           // segments that k_quantize encodes (not the guessing ones)
   uint32_t warm_R;            // workers whose guessing units carry a guess from an earlier call
   uint32_t safe_left;         // calls still to be made with the multi-pass kernels standing by for failed guesses
+  uint32_t* blk_cnt2[2];      // the two arrays of per-block counters of transmitted entries, used in turn
+  uint64_t calls;             // compress calls made
   uint32_t nsamp_blocks;      // blocks of the sampling kernel (per worker)
   size_t capacity;
   uint32_t* h_status;         // pinned
   uint32_t* d_nnz_tmp;
   float* own_v;               // [Rmax, d] home of v for calls with m_out = NULL (QSL_FLAG_OWN_V), else null
   hipEvent_t order_ev;        // orders the work of this context across a change of stream
+  hipStream_t side;           // the one-block units' kernel runs here, beside the guessing units' kernels
+  hipEvent_t fork_ev, join_ev;
   int timing;
   std::vector<hipEvent_t> ev;
   size_t ev_used;
@@ -175,8 +179,8 @@ extern "C" qsl_status qsl_bits_index_free(const qsl_config* cfg, uint64_t* bits)
 // the plan that follow from that decision (sample layout, static guess, room for candidates) and returns the expected
 // number of candidates of a guessing unit (0 otherwise).  sg.size, sg.k and sg.nwt are set by the caller.
 static double plan_segment(const qsl_config* cfg, SegInfo& sg) {
+  // at most 4096 coordinates: one block; k = size: nothing to select (unless the caller asks for the multi-pass kernels only)
   sg.mode = (sg.nwt <= SMALL_CHUNKS && !(cfg->flags & QSL_FLAG_NO_SMALL_PATH)) ? PATH_SMALL : PATH_GENERAL;
-  // k = size: nothing to select (unless the caller asks for the multi-pass kernels only)
   if (sg.mode != PATH_SMALL && sg.k == sg.size && !(cfg->flags & QSL_FLAG_NO_FAST_PATH)) sg.mode = PATH_FULL;
   sg.T_static = 0xFFFFFFFFu;
   sg.lpc = 8;
@@ -187,10 +191,10 @@ static double plan_segment(const qsl_config* cfg, SegInfo& sg) {
       // candidates ~ alpha k; the sample must hold enough of them for the guess to sit below the
       // true threshold with ~6.5 sigma: (alpha - 1) sqrt(n_s p) >= 6.5 sqrt(alpha)
       // (a small unit has a small k, so a generous alpha costs few candidates and saves most of the sample)
-      // The candidates of a chunk must fit its slot (at most 31, with 4 sigma to spare): a chunk with more sends all
+      // The candidates of a chunk must fit its slot (at most 63, with 4 sigma to spare): a chunk with more sends all
       // of them through the overflow pool, which the selection kernels read entry by entry -- a unit where most
       // chunks do that (k = 1000 of 65,536 with alpha = 3: 47 per chunk) is far slower than on the multi-pass path.
-      auto fits = [&](double alpha) { const double pc = alpha * sg.k / sg.nwt; return pc + 4.0 * std::sqrt(pc) <= 31.0; };
+      auto fits = [&](double alpha) { const double pc = alpha * sg.k / sg.nwt; return pc + 4.0 * std::sqrt(pc) <= 63.0; };
       const double alphas[10] = {1.5, 2.0, 3.0, 4.0, 6.0, 8.0, 12.0, 16.0, 24.0, 32.0};
       for (double frac : {1.0 / 16, 1.0 / 4}) {
         for (double alpha : alphas) {
@@ -238,7 +242,7 @@ static double plan_segment(const qsl_config* cfg, SegInfo& sg) {
     } else if (cfg->sparsifier == QSL_RANDK && static_cast<uint64_t>(sg.k) * 16 <= sg.size) {
       // the keys are uniform 32-bit words: keep those above the (1 - q) quantile, q = p + 7 sigma
       const double q = p + 7.0 * std::sqrt(p * (1 - p) / n);
-      if (q * CHUNK <= 14.0) {                  // at most ~14 candidates per chunk: they fit a two-line slot
+      if (q * CHUNK + 4.0 * std::sqrt(q * CHUNK) <= 63.0) {   // the candidates of a chunk fit its slot with 4 sigma to spare
         sg.T_static = static_cast<uint32_t>(std::floor(4294967296.0 * (1.0 - q)));
         cand = q * n;
         sg.d0_cap = static_cast<uint32_t>(std::min<double>(n, cand + 8.0 * std::sqrt(cand) + 1024.0));
@@ -247,6 +251,8 @@ static double plan_segment(const qsl_config* cfg, SegInfo& sg) {
       }
     }
   }
+  // too dense to guess, small enough for one block to hold in registers
+  if (sg.mode == PATH_GENERAL && sg.size <= BLOCK_MAX && !(cfg->flags & QSL_FLAG_NO_SMALL_PATH)) sg.mode = PATH_SMALL;
   return cand;
 }
 
@@ -265,6 +271,18 @@ extern "C" qsl_status qsl_plan_paths(const qsl_config* cfg, uint32_t* path_out) 
     path_out[l] = sg.mode;
   }
   return QSL_OK;
+}
+
+// releases everything a (possibly half-built) context holds
+static void free_ctx(qsl_ctx* ctx) {
+  if (ctx->side) { (void)hipStreamSynchronize(ctx->side); (void)hipStreamDestroy(ctx->side); }
+  for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+  if (ctx->order_ev) (void)hipEventDestroy(ctx->order_ev);
+  if (ctx->fork_ev) (void)hipEventDestroy(ctx->fork_ev);
+  if (ctx->join_ev) (void)hipEventDestroy(ctx->join_ev);
+  if (ctx->slab) (void)hipFree(ctx->slab);
+  if (ctx->h_status) (void)hipHostFree(ctx->h_status);
+  delete ctx;
 }
 
 extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip_stream) {
@@ -288,7 +306,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->Rmax = cfg->max_workers;
   ctx->last_R = 0; ctx->warm_R = 0; ctx->safe_left = 0;
   ctx->timing = 0; ctx->ev_used = 0;
-  ctx->slab = nullptr; ctx->h_status = nullptr; ctx->own_v = nullptr; ctx->order_ev = nullptr;
+  ctx->slab = nullptr; ctx->h_status = nullptr; ctx->own_v = nullptr; ctx->order_ev = nullptr; ctx->side = nullptr; ctx->fork_ev = nullptr; ctx->join_ev = nullptr;
 
   const uint32_t K = static_cast<uint32_t>(K64);
   const WireDims wd = wire_dims(cfg, K64);
@@ -306,7 +324,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   std::vector<CbInfo> cbs;
   std::vector<uint32_t> fast, smalls;
   uint64_t slot_elems = 0, ovf_entries = 0, d0_entries = 0, nwt64 = 0, nwc = 0;
-  uint32_t koff = 0;
+  uint32_t koff = 0, n_in_stream = 0;
   ctx->n_sampled = 0;
   for (uint32_t l = 0; l < L; ++l) {
     SegInfo& sg = segs[l];
@@ -315,20 +333,28 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
     sg.k = ctx->k[l]; sg.koff = koff; koff += sg.k;
     sg.nwt = static_cast<uint32_t>((sg.size + CHUNK - 1) / CHUNK);
     nwt64 += sg.nwt;
-    if (L > 1) {
-      for (uint32_t t = 0; t < sg.nwt; ++t) { WtInfo wi; wi.seg = l; wi.chunk = t; wi.pad0 = wi.pad1 = 0; wts.push_back(wi); }
-    }
     const double cand = plan_segment(cfg, sg);
+    if (L > 1) {
+      // The chunks in the order k_stream's waves take them, four to a block.  A unit of at most 4096 coordinates that one
+      // block is to select gets its block to itself: the list is filled up to a block boundary before and after it.
+      const bool own_block = sg.mode == PATH_SMALL && sg.nwt <= SMALL_CHUNKS;
+      auto fill_up = [&]() { while (wts.size() % 4) { WtInfo wi; wi.seg = l; wi.chunk = NO_CHUNK; wi.inblock = own_block; wi.pad1 = 0; wts.push_back(wi); } };
+      if (own_block) {                              // (the filler before it belongs to the previous units' block: no unit, no chunk)
+        while (wts.size() % 4) { WtInfo wi; wi.seg = l; wi.chunk = NO_CHUNK; wi.inblock = 0; wi.pad1 = 0; wts.push_back(wi); }
+      }
+      for (uint32_t t = 0; t < sg.nwt; ++t) { WtInfo wi; wi.seg = l; wi.chunk = t; wi.inblock = own_block; wi.pad1 = 0; wts.push_back(wi); }
+      if (own_block) { fill_up(); sg.mode = PATH_SMALL; sg.in_stream = 1; }
+    }
     if (sg.mode == PATH_FAST && cfg->sparsifier == QSL_TOPK) {        // a guessing Top_k unit samples
       ++ctx->n_sampled;
       for (uint32_t j = 0; j < sg.nsamp; ++j) { SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0; samps.push_back(si); }
     }
     if (sg.mode == PATH_FAST) {
-      // the slot of a chunk (64, 128 or 256 bytes) holds the expected candidates with ~4 sigma to spare;
+      // the slot of a chunk (64 to 512 bytes) holds the expected candidates with ~4 sigma to spare;
       // chunks that hold more (chance, or clustered large values) spill to an overflow pool that can
       // take every candidate
       const double per_chunk = cand / sg.nwt, need = per_chunk + 4.0 * std::sqrt(per_chunk);
-      sg.lpc = need <= 7.0 ? 4 : need <= 15.0 ? 8 : 16;
+      sg.lpc = need <= 7.0 ? 4 : need <= 15.0 ? 8 : need <= 31.0 ? 16 : 32;
       sg.fidx = static_cast<uint32_t>(fast.size());
       fast.push_back(l);
       sg.slot_off = slot_elems; slot_elems += static_cast<uint64_t>(sg.nwt) * sg.lpc * 2;
@@ -337,7 +363,8 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
       sg.d0_off = d0_entries; d0_entries += sg.d0_cap;
       sg.ncb = std::min<uint32_t>(256, (sg.nwt + GGROUP - 1) / GGROUP);    // for the call in which its guess fails
     } else if (sg.mode == PATH_SMALL) {
-      smalls.push_back(l);
+      if (!sg.in_stream) smalls.push_back(l);       // else a block of k_stream does it
+      else ++n_in_stream;
       sg.nsel = 0; sg.ncb = 0;
     } else if (sg.mode == PATH_FULL) {
       const uint64_t ntiles = (sg.size + 4095) / 4096;
@@ -406,7 +433,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->ncb_general = static_cast<uint32_t>(cbs.size());
   sels.insert(sels.end(), sels_f.begin(), sels_f.end());
   cbs.insert(cbs.end(), cbs_f.begin(), cbs_f.end());
-  ctx->n_other = L - static_cast<uint32_t>(fast.size());
+  ctx->n_other = L - static_cast<uint32_t>(fast.size()) - static_cast<uint32_t>(smalls.size()) - n_in_stream;   // what k_quantize encodes
   // a sample block's work: its share of the unit's runs (or chunks, when the whole unit is read); a small unit's: its size
   auto sample_cost = [&](const SelInfo& si) {
     const SegInfo& sg = segs[si.seg];
@@ -415,6 +442,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   std::stable_sort(samps.begin(), samps.end(), [&](const SelInfo& a, const SelInfo& b) { return sample_cost(a) > sample_cost(b); });
   std::stable_sort(smalls.begin(), smalls.end(), [&](uint32_t a, uint32_t b) { return segs[a].size > segs[b].size; });
   ctx->nsamp_blocks = static_cast<uint32_t>(samps.size());
+  if (L > 1) nwt64 = wts.size();                    // with the fillers around the small units
   const uint32_t NWT = static_cast<uint32_t>(nwt64);
   const uint32_t NSEL = static_cast<uint32_t>(sels.size()), NCB = static_cast<uint32_t>(cbs.size());
   const uint32_t NSELF = static_cast<uint32_t>(fsels.size());
@@ -427,6 +455,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   auto carve = [&](uint64_t n) { const uint64_t o = bytes; bytes = align_up(bytes + n, 256); return o; };
   const uint64_t o_hist = carve(4ull * 3 * HBINS * U), o_ctr = carve(4ull * CTR_LINES * PAD * U);
   const uint64_t o_acc = carve(8ull * ACC_SLOTS * U), o_status = carve(8);
+  const uint64_t o_blk = carve(4ull * QB * R * 2);    // the two arrays of per-block counters of transmitted entries
   const uint64_t zero_bytes = bytes;
   const uint64_t o_segs = carve(sizeof(SegInfo) * L), o_wts = carve(sizeof(WtInfo) * std::max<size_t>(1, wts.size()));
   const uint64_t o_sels = carve(sizeof(SelInfo) * NSEL), o_cbs = carve(sizeof(CbInfo) * NCB);
@@ -452,6 +481,9 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
     slot_dir[b] = static_cast<uint32_t>(l);
   }
   const uint64_t o_slotdir = carve(4ull * slot_dir.size());
+  std::vector<uint32_t> seg_start(L), seg_koff(L), seg_whole(L);
+  for (uint32_t l = 0; l < L; ++l) { seg_start[l] = static_cast<uint32_t>(segs[l].start); seg_koff[l] = segs[l].koff; seg_whole[l] = segs[l].k == segs[l].size; }
+  const uint64_t o_sstart = carve(4ull * L), o_skoff = carve(4ull * L), o_swhole = carve(4ull * L);
   const uint64_t o_units = carve(sizeof(UnitState) * U);
   const uint64_t o_slots = carve(8ull * std::max<uint64_t>(2, slot_elems) * R);
   const uint64_t o_ovf = carve(8ull * std::max<uint64_t>(1, ovf_entries) * R);
@@ -463,14 +495,14 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t o_wc = carve(4ull * NWC * R), o_ws = carve(4ull * NWC * R), o_cbc = carve(8ull * NCB * R);
   const uint64_t o_tlist = carve(16ull * LISTCAP * std::max<size_t>(1, fast.size()) * R);
   const uint64_t o_si = carve(4ull * K * R), o_sv = carve(4ull * K * R), o_sc = carve(4ull * K * R);
-  const uint64_t o_blk = carve(4ull * QB * R), o_pre = carve(4ull * (QB + 1) * R);
+  const uint64_t o_pre = carve(4ull * (QB + 1) * R);
   const uint64_t o_vi = carve(4ull * K * R), o_vc = carve(4ull * K * R);
   const uint64_t o_tmp = carve(4ull * 1024);
   ctx->agg_ndir = static_cast<uint32_t>(((d + (1u << AGG_DIR_SHIFT) - 1) >> AGG_DIR_SHIFT) + 1);
   const bool want_dir = ctx->nnz_hint >= AGG_DIR_MIN;
   const uint64_t o_dir = carve(want_dir ? 4ull * 64 * ctx->agg_ndir : 4);
   const uint64_t o_ownv = carve((cfg->flags & QSL_FLAG_OWN_V) ? 4ull * R * d : 4);
-  if (hipMalloc(&ctx->slab, bytes) != hipSuccess) { delete ctx; return QSL_ERR_DEVICE; }
+  if (hipMalloc(&ctx->slab, bytes) != hipSuccess) { ctx->slab = nullptr; free_ctx(ctx); return QSL_ERR_DEVICE; }
   char* base = static_cast<char*>(ctx->slab);
   bool ok = hipMemset(base, 0, zero_bytes) == hipSuccess;
   auto upload = [&](uint64_t o, const void* src, size_t n) {
@@ -488,16 +520,16 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   upload(o_big, bigs.data(), 4 * bigs.size());
   upload(o_segdir, seg_dir.data(), 4 * seg_dir.size());
   upload(o_slotdir, slot_dir.data(), 4 * slot_dir.size());
+  upload(o_sstart, seg_start.data(), 4ull * L);
+  upload(o_skoff, seg_koff.data(), 4ull * L);
+  upload(o_swhole, seg_whole.data(), 4ull * L);
   ok = ok && hipHostMalloc(reinterpret_cast<void**>(&ctx->h_status), 64, hipHostMallocMapped) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&ctx->order_ev, hipEventDisableTiming) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ctx->fork_ev, hipEventDisableTiming) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ctx->join_ev, hipEventDisableTiming) == hipSuccess;
+  ok = ok && hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess;      // default priority
   ok = ok && hipDeviceSynchronize() == hipSuccess;
-  if (!ok) {
-    (void)hipFree(ctx->slab);
-    if (ctx->h_status) (void)hipHostFree(ctx->h_status);
-    if (ctx->order_ev) (void)hipEventDestroy(ctx->order_ev);
-    delete ctx;
-    return QSL_ERR_DEVICE;
-  }
+  if (!ok) { free_ctx(ctx); return QSL_ERR_DEVICE; }
 
   DevCtx& c = ctx->dc;
   c.segs = reinterpret_cast<const SegInfo*>(base + o_segs);
@@ -511,7 +543,9 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.big_segs = reinterpret_cast<const uint32_t*>(base + o_big); c.nbig = static_cast<uint32_t>(bigs.size());
   c.seg_dir = reinterpret_cast<const uint32_t*>(base + o_segdir);
   c.slot_dir = reinterpret_cast<const uint32_t*>(base + o_slotdir);
-  ctx->nsmall = static_cast<uint32_t>(smalls.size());
+  c.seg_start = reinterpret_cast<const uint32_t*>(base + o_sstart); c.seg_koff = reinterpret_cast<const uint32_t*>(base + o_skoff);
+  c.seg_whole = reinterpret_cast<const uint32_t*>(base + o_swhole);
+  ctx->nsmall = static_cast<uint32_t>(smalls.size()); c.nblock = ctx->nsmall;
   c.fulls = reinterpret_cast<const SelInfo*>(base + o_fulls);
   ctx->nfull_blocks = static_cast<uint32_t>(fulls.size());
   c.units = reinterpret_cast<UnitState*>(base + o_units);
@@ -526,17 +560,17 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->h_status[8] = 0;
   {
     void* dflag = nullptr;                          // the device's address of a word of the pinned host block
-    if (hipHostGetDevicePointer(&dflag, ctx->h_status + 8, 0) != hipSuccess || !dflag) {
-      (void)hipFree(ctx->slab); (void)hipHostFree(ctx->h_status); (void)hipEventDestroy(ctx->order_ev); delete ctx;
-      return QSL_ERR_DEVICE;
-    }
+    if (hipHostGetDevicePointer(&dflag, ctx->h_status + 8, 0) != hipSuccess || !dflag) { free_ctx(ctx); return QSL_ERR_DEVICE; }
     c.host_flag = static_cast<uint32_t*>(dflag);
   }
   c.hist = reinterpret_cast<uint32_t*>(base + o_hist); c.ctr = reinterpret_cast<uint32_t*>(base + o_ctr);
   c.norm_acc = reinterpret_cast<uint64_t*>(base + o_acc);
   c.sel_idx = reinterpret_cast<uint32_t*>(base + o_si); c.sel_val = reinterpret_cast<uint32_t*>(base + o_sv);
   c.sel_code = reinterpret_cast<uint32_t*>(base + o_sc);
-  c.blk_cnt = reinterpret_cast<uint32_t*>(base + o_blk); c.blk_pre = reinterpret_cast<uint32_t*>(base + o_pre);
+  ctx->blk_cnt2[0] = reinterpret_cast<uint32_t*>(base + o_blk); ctx->blk_cnt2[1] = ctx->blk_cnt2[0] + QB * R;
+  ctx->calls = 0;
+  c.blk_cnt = ctx->blk_cnt2[0]; c.blk_cnt_next = ctx->blk_cnt2[1]; c.Rmax = ctx->Rmax;
+  c.blk_pre = reinterpret_cast<uint32_t*>(base + o_pre);
   c.surv_idx = reinterpret_cast<uint32_t*>(base + o_vi); c.surv_code = reinterpret_cast<uint32_t*>(base + o_vc);
   c.status = reinterpret_cast<uint32_t*>(base + o_status);
   ctx->d_nnz_tmp = reinterpret_cast<uint32_t*>(base + o_tmp);
@@ -549,10 +583,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->one.start = 0; ctx->one.size = segs[0].size; ctx->one.slot_off = 0; ctx->one.ovf_off = 0;
   ctx->one.lpc = segs[0].lpc; ctx->one.ovf_cap = segs[0].ovf_cap;
   k_init<<<dim3(static_cast<uint32_t>((U + 255) / 256)), 256, 0, ctx->stream>>>(c, static_cast<uint32_t>(U));
-  if (hipStreamSynchronize(ctx->stream) != hipSuccess) {
-    (void)hipFree(ctx->slab); (void)hipHostFree(ctx->h_status); (void)hipEventDestroy(ctx->order_ev); delete ctx;
-    return QSL_ERR_DEVICE;
-  }
+  if (hipStreamSynchronize(ctx->stream) != hipSuccess) { free_ctx(ctx); return QSL_ERR_DEVICE; }
   *out = ctx;
   return QSL_OK;
 }
@@ -560,11 +591,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
 extern "C" qsl_status qsl_destroy(qsl_ctx* ctx) {
   if (!ctx) return QSL_ERR_INVALID_ARG;
   (void)hipStreamSynchronize(ctx->stream);
-  for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
-  if (ctx->slab) (void)hipFree(ctx->slab);
-  if (ctx->h_status) (void)hipHostFree(ctx->h_status);
-  if (ctx->order_ev) (void)hipEventDestroy(ctx->order_ev);
-  delete ctx;
+  free_ctx(ctx);
   return QSL_OK;
 }
 
@@ -588,9 +615,11 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
                                   uint32_t worker0,
                                   uint32_t R, uint64_t round, uint8_t* msg, uint64_t* msg_bits, uint32_t* sel_idx,
                                   uint16_t* sel_level) {
-  const DevCtx& c = ctx->dc;
+  DevCtx& c = ctx->dc;
   hipStream_t st = ctx->stream;
-  if (static_cast<uint64_t>(std::max(std::max(c.NSEL, c.NCB), std::max(std::max(ctx->nsamp_blocks, ctx->nsmall), c.NSELF + c.nfast))) * R > 0x7FFFFFFFull)
+  c.blk_cnt = ctx->blk_cnt2[ctx->calls & 1]; c.blk_cnt_next = ctx->blk_cnt2[(ctx->calls & 1) ^ 1];
+  ++ctx->calls;
+  if (static_cast<uint64_t>(std::max(std::max(c.NSEL, c.NCB), std::max(std::max(ctx->nsamp_blocks, c.nblock), c.NSELF + c.nfast))) * R > 0x7FFFFFFFull)
     return QSL_ERR_UNSUPPORTED;                    // the list kernels use one-dimensional grids of (list entries x workers)
   // A kernel that had to resolve a failed guess with one block (slow for a large unit) leaves a word in pinned host
   // memory; the next calls then keep the multi-pass kernels standing by for the units whose guess fails.  The word
@@ -614,18 +643,31 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   const uint32_t nblk = (c.NWT + 3) / 4;
   if (xm == nullptr) {
     const dim3 sgrid(nblk, R);
-    if (c.L == 1) k_stream<SPARS, true, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R);
-    else k_stream<SPARS, false, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R);
+    if (c.L == 1) k_stream<SPARS, true, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, sel_idx, sel_level);
+    else k_stream<SPARS, false, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, sel_idx, sel_level);
   } else {
     const uint64_t nb = static_cast<uint64_t>((nblk + 7) / 8) * 8 * R;
     if (nb > 0x7FFFFFFFull) return QSL_ERR_UNSUPPORTED;
     const dim3 sgrid(static_cast<uint32_t>(nb));
-    if (c.L == 1) k_stream<SPARS, true, true><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R);
-    else k_stream<SPARS, false, true><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R);
+    if (c.L == 1) k_stream<SPARS, true, true><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, sel_idx, sel_level);
+    else k_stream<SPARS, false, true><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, sel_idx, sel_level);
   }
   if (timed) { QSL_HIP(hipEventRecord(ctx->ev[ctx->ev_used + 1], st)); ctx->ev_used += 2; }
 
-  if (ctx->nsmall) k_small<SPARS><<<dim3(ctx->nsmall * R), BLOCK, 0, st>>>(c, m_out, worker0, round, R);
+  // Units that a single block selects and encodes whole need nothing but v: their kernel runs on a stream of the
+  // context's own beside the kernels of the other units (one block works tens of microseconds on a unit of 40,960
+  // coordinates) and is joined before the messages are put together.
+  const bool forked = c.nblock != 0 && (c.NSELF != 0 || ctx->n_other != 0);
+  if (c.nblock) {
+    hipStream_t bs = st;
+    if (forked) {
+      QSL_HIP(hipEventRecord(ctx->fork_ev, st));
+      QSL_HIP(hipStreamWaitEvent(ctx->side, ctx->fork_ev, 0));
+      bs = ctx->side;
+    }
+    k_block_units<SPARS><<<dim3(c.nblock * R), BIG, 0, bs>>>(c, R, m_out, worker0, round, sel_idx, sel_level);
+    if (forked) QSL_HIP(hipEventRecord(ctx->join_ev, ctx->side));
+  }
   if (ctx->nfull_blocks) k_full<<<dim3(ctx->nfull_blocks, R), BLOCK, 0, st>>>(c, m_out);
   if (c.NSELF) {                                   // guessing units: candidates' histogram, threshold bin and dense list
     k_lean_hist<SPARS><<<dim3(c.NSELF * R), BIG, 0, st>>>(c, ctx->segs[0], R);
@@ -642,9 +684,11 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
     k_tile_write<SPARS><<<dim3(ncb * R), BLOCK, 0, st>>>(c, ctx->segs[0], m_out, worker0, round, R);
   }
   if (ctx->n_other || safe) k_quantize<<<dim3(c.QB, R), BLOCK, 0, st>>>(c, m_out, worker0, round, sel_idx, sel_level, safe ? 1 : 0);
-  if (c.NSELF)                                     // ... their exact threshold, ordered output and codes; one more block per unit for failures
+  // the guessing units' exact threshold, ordered output and codes; one more block per guessing unit for failures
+  if (c.NSELF)
     k_lean_emit<SPARS><<<dim3((c.NSELF + c.nfast) * R), BIG, 0, st>>>(c, ctx->segs[0], R, c.NSELF * R, m_out, worker0, round,
                                                                      sel_idx, sel_level, safe ? 1 : 0);
+  if (forked) QSL_HIP(hipStreamWaitEvent(st, ctx->join_ev, 0));
   if (is_qsgd(c.quantizer)) {                      // the other quantisers send every selected coordinate: the final arrays are written already
     if (c.QB > MAX_QB_INLINE) k_surv_scan<<<dim3(R), 1024, 0, st>>>(c);
     k_surv_compact<<<dim3(c.QB, R), BLOCK, 0, st>>>(c);

@@ -191,8 +191,11 @@ struct GroupSearch {
 // positions of coordinate idx in n (<= 8) of the other listed messages: the o-th other message, o = o0 .. o0 + n - 1,
 // is list entry o for o < q and o + 1 from there on.  The loads of a step are unconditional (a closed search
 // reads entry 0 again, which every message buffer has room for) so that all eight are in flight together.
+// `fixed_pos` >= 0: where the coordinate stands in every message that holds all K entries (a segment kept whole under a
+// quantiser that drops nothing: its entries are at the same places in every such message) -- no search then.
 __device__ __forceinline__ void group_find(const DevCtx& c, const uint8_t* msg, const RowList& rows, uint32_t o0, uint32_t n,
-                                           uint32_t q, uint32_t idx, const uint32_t* dir, uint32_t ndir, GroupSearch& s) {
+                                           uint32_t q, uint32_t idx, const uint32_t* dir, uint32_t ndir, int64_t fixed_pos,
+                                           GroupSearch& s) {
   const uint32_t t = idx >> AGG_DIR_SHIFT;
   uint32_t nnz[AGG_GROUP], dlo[AGG_GROUP], dhi[AGG_GROUP];
 #pragma unroll
@@ -214,6 +217,7 @@ __device__ __forceinline__ void group_find(const DevCtx& c, const uint8_t* msg, 
     s.pos[g] = -1; s.lo[g] = 0; s.hi[g] = 0;
     if (g < n) {
       if (s.v[g].nnz == c.d) s.pos[g] = idx;               // every coordinate is there (k = d): entry j is coordinate j
+      else if (fixed_pos >= 0 && s.v[g].nnz == c.K) s.pos[g] = fixed_pos;
       else { s.hi[g] = min(dhi[g], s.v[g].nnz); s.lo[g] = min(dlo[g], s.hi[g]); }
     }
   }
@@ -255,12 +259,20 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate_entries(DevCtx c, const uin
     const uint32_t idx = msg_index(c, mine, j);
     if (idx >= c.d) { atomicOr(c.status, 4u); continue; }          // malformed message
     const uint32_t seg = c.L == 1 ? 0u : seg_of_coord(c, idx);
+    // a segment that is kept whole (k = size, e.g. the small tensors under a per-tensor rule) by a quantiser that drops
+    // nothing stands at the same places in every full message
+    int64_t fixed_pos = -1;
+    if (c.L > 1 && !is_qsgd(c.quantizer) && mine.nnz == c.K && c.seg_whole[seg])
+      fixed_pos = static_cast<int64_t>(c.seg_koff[seg]) + (idx - c.seg_start[seg]);
+    // ... so if the first listed message is full it owns the coordinate: nothing to look up for the others' threads
+    if (fixed_pos >= 0 && q > 0 &&
+        reinterpret_cast<const uint32_t*>(msg + static_cast<uint64_t>(rows.row[0]) * c.cap_words * 4)[0] == c.K) continue;
     const uint32_t my_code = get_bits(mine.words, mine.code_bit0 + static_cast<uint64_t>(j) * c.w_val, c.w_val);
     float acc = value_of_code(c, my_code, __uint_as_float(mine.words[1 + seg]));
     bool owned = false;                                            // an earlier listed message holds the coordinate: its thread writes it
     for (uint32_t o0 = 0; o0 + 1 < R && !owned; o0 += AGG_GROUP) {
       const uint32_t n = min(AGG_GROUP, R - 1 - o0);
-      group_find(c, msg, rows, o0, n, q, idx, dir, ndir, s);
+      group_find(c, msg, rows, o0, n, q, idx, dir, ndir, fixed_pos, s);
       uint32_t w0[AGG_GROUP], w1[AGG_GROUP]; float sc[AGG_GROUP];
 #pragma unroll
       for (uint32_t g = 0; g < AGG_GROUP; ++g) {              // code fields and scales of the group, found or not: one batch

@@ -64,7 +64,7 @@ __device__ float finalize_scale(const uint64_t* acc, uint32_t quantizer, uint32_
 __device__ __forceinline__ uint32_t seg_of_slot(const DevCtx& c, uint32_t j) {
   const uint32_t b = j >> 8;
   uint32_t lo = c.slot_dir[b], hi = c.slot_dir[b + 1] + 1;
-  while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (c.segs[mid].koff <= j) lo = mid; else hi = mid; }
+  while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (c.seg_koff[mid] <= j) lo = mid; else hi = mid; }
   return lo;
 }
 // segment of coordinate i: seg_dir[t] is the segment of coordinate t * 1024, so the search is over the few
@@ -72,7 +72,7 @@ __device__ __forceinline__ uint32_t seg_of_slot(const DevCtx& c, uint32_t j) {
 __device__ __forceinline__ uint32_t seg_of_coord(const DevCtx& c, uint32_t i) {
   const uint32_t t = i >> 10;
   uint32_t lo = c.seg_dir[t], hi = c.seg_dir[t + 1] + 1;       // segs[lo].start <= i < segs[hi].start (or hi = L)
-  while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (c.segs[mid].start <= i) lo = mid; else hi = mid; }
+  while (hi - lo > 1) { const uint32_t mid = (lo + hi) >> 1; if (c.seg_start[mid] <= i) lo = mid; else hi = mid; }
   return lo;
 }
 
@@ -140,6 +140,57 @@ __device__ __forceinline__ bool encode_entry(const DevCtx& c, uint32_t w, uint64
   return sent;
 }
 
+// What follows the ordered pass of a selection done by one block of NT threads: the block's ROWS accumulator rows
+// added up, the fp32 scale, the codes and the error update of the unit's k selected coordinates (already in the
+// selected arrays), the unit's state.
+template <uint32_t NT, uint32_t ROWS>
+__device__ void block_encode_tail(const DevCtx& c, const SegInfo& sg, uint32_t w, uint64_t u, uint32_t tau, uint32_t need,
+                                  uint32_t worker0, uint64_t round, float* m_out, uint32_t* dbg_idx, uint16_t* dbg_level,
+                                  uint64_t* acc, float* s_scale, uint32_t* s_count) {
+  constexpr uint32_t NW = NT / 64, PW = (ACC_SLOTS + NW - 1) / NW;      // digit counters per wave
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
+  const uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
+  __syncthreads();                                   // the selected arrays and the accumulator rows are complete
+  uint64_t x[PW];
+#pragma unroll
+  for (uint32_t i = 0; i < PW; ++i) {
+    const uint32_t s = wave + i * NW;                // wave-uniform
+    x[i] = 0;
+    if (s < ACC_SLOTS) x[i] = wave_sum64(lane < ROWS ? acc[lane * (ACC_SLOTS + 1) + s] : 0);
+  }
+  __syncthreads();
+  if (lane == 0) {
+#pragma unroll
+    for (uint32_t i = 0; i < PW; ++i) if (wave + i * NW < ACC_SLOTS) acc[wave + i * NW] = x[i];
+  }
+  if (threadIdx.x == 0) *s_count = 0;
+  __syncthreads();
+  if (wave == 0) {
+    const float sc = finalize_scale(acc, c.quantizer, sg.k);
+    if (lane == 0) *s_scale = sc;
+  }
+  __syncthreads();
+  const UnitScale usc = unit_scale(c, *s_scale, sg.k);
+  const RandKey rk1 = make_rand_key(c.seed, worker0 + w, round, 1);
+  uint32_t nsent = 0;
+  for (uint32_t j = threadIdx.x; j < sg.k; j += NT) {
+    const uint64_t slot = static_cast<uint64_t>(w) * c.K + sg.koff + j;
+    const bool sent = encode_entry(c, w, slot, oi[j], ov[j], usc, rk1, m_out, dbg_idx, dbg_level);
+    if (sent && is_qsgd(c.quantizer)) { atomicAdd(&c.blk_cnt[static_cast<uint64_t>(w) * c.QB + ((sg.koff + j) >> 8)], 1u); ++nsent; }
+  }
+  if (is_qsgd(c.quantizer) && c.L > 1) {              // the unit's entry count for the message header
+    nsent = wave_sum(nsent);
+    if (lane == 0 && nsent) atomicAdd(s_count, nsent);
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    UnitState* usp = &c.units[u];
+    usp->tau = tau; usp->need = need; usp->n_gt = sg.k - need; usp->scale_bits = __float_as_uint(usc.sent);
+    if (is_qsgd(c.quantizer) && c.L > 1) usp->nnz = *s_count;
+  }
+}
+
 // The units that k_lean_emit has already encoded are skipped here: a guessing unit, unless its guess failed and
 // the multi-pass kernels of this call took it over (`safe`).
 __global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint32_t worker0, uint64_t round,
@@ -157,7 +208,7 @@ __global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint
     const uint32_t seg = seg_first + i;
     const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
     const UnitState us = c.units[u];
-    const bool mine = !(us.path == PATH_FAST && !(safe && us.fell_back));
+    const bool mine = us.path != PATH_SMALL && !(us.path == PATH_FAST && !(safe && us.fell_back));
     float sc = 0.0f;
     if (mine) sc = finalize_scale(c.norm_acc + u * ACC_SLOTS, c.quantizer, c.segs[seg].k);
     if (lane_id() == 0) {
@@ -185,12 +236,10 @@ __global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint
   if (lane_id() == 0) s_w[threadIdx.x >> 6] = wc;
   __syncthreads();
   uint32_t* cnt = c.blk_cnt + static_cast<uint64_t>(w) * c.QB;
-  // with guessing units in the plan a block of 256 slots may also hold entries that k_lean_emit encodes: the counts
-  // are then added (k_lean_hist has set them to zero); else this kernel is their only writer
+  // a block of 256 slots may also hold entries that another kernel encodes: the counts are added (they start at zero)
   if (threadIdx.x == 0) {
     const uint32_t n = s_w[0] + s_w[1] + s_w[2] + s_w[3];
-    if (c.nfast == 0) cnt[blockIdx.x] = n;
-    else if (n) atomicAdd(&cnt[blockIdx.x], n);
+    if (n) atomicAdd(&cnt[blockIdx.x], n);
   }
 }
 
@@ -283,6 +332,12 @@ __global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t
       ct[(static_cast<uint64_t>(c.fast_segs[i / CTR_LINES]) * CTR_LINES + i % CTR_LINES) * PAD] = 0;
     uint64_t* na = c.norm_acc + static_cast<uint64_t>(w) * c.L * ACC_SLOTS;
     for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * ACC_SLOTS; i += nth) na[i] = 0;
+    // the next call's counters of transmitted entries (the other of the two arrays; nobody uses it during this call)
+    {
+      const uint64_t gtid = (static_cast<uint64_t>(w) * gridDim.x + blockIdx.x) * BLOCK + threadIdx.x;
+      const uint64_t gnth = static_cast<uint64_t>(gridDim.y) * gridDim.x * BLOCK;
+      for (uint64_t i = gtid; i < static_cast<uint64_t>(c.Rmax) * c.QB; i += gnth) c.blk_cnt_next[i] = 0;
+    }
     // ... and the guess that this call's candidates suggest becomes the next call's
     if (c.sparsifier == QSL_TOPK)
       for (uint64_t i = tid; i < c.nfast; i += nth) {

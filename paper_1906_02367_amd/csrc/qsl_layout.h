@@ -29,7 +29,9 @@ constexpr uint32_t LISTCAP = 256;          // entries of that list; a threshold 
 
 enum : uint32_t { PATH_FAST = 0, PATH_GENERAL = 1, PATH_FALLBACK = 2, PATH_SMALL = 3, PATH_FULL = 4 };
 constexpr uint32_t MAX_FULL_BLOCKS = 512;  // blocks per unit of k_full (each ends with up to 20 atomics on the unit's digit counters)
-constexpr uint32_t SMALL_CHUNKS = 4;       // a unit of at most 4 chunks (4096 coordinates) is selected by one block
+constexpr uint32_t SMALL_CHUNKS = 4;       // a unit of at most 4 chunks (4096 coordinates) is always selected by one block
+constexpr uint32_t BLOCK_PER = 40;         // coordinates a thread of the one-block selection holds at most ...
+constexpr uint32_t BLOCK_MAX = BLOCK_PER * 1024;   // ... so a unit too dense to guess goes that way up to 40,960 coordinates
 
 struct SegInfo {
   uint64_t start, size;
@@ -43,7 +45,7 @@ struct SegInfo {
   uint32_t cb_base, ncb; // compaction blocks: index of the first one (per worker), how many
   uint32_t nsamp;        // blocks of this unit in the sampling kernel
   uint32_t mode;         // PATH_FAST, PATH_GENERAL, PATH_SMALL or PATH_FULL, decided on the host from (size, k)
-  uint32_t lpc;          // slot size: lpc * 16 bytes per chunk (4: 64 bytes, 8: one 128-byte line, 16: two lines)
+  uint32_t lpc;          // slot size: lpc * 16 bytes per chunk (4: 64 bytes, 8: one 128-byte line, 16: two lines, 32: four)
   uint32_t ovf_cap;      // entries of the overflow pool
   uint32_t n_runs;       // sample: runs of 64 consecutive coordinates
   uint32_t r_s;          // sample rank that defines the guess
@@ -53,10 +55,13 @@ struct SegInfo {
   uint32_t r_warm;       // rank (among this call's candidates) whose bin edge becomes the next call's guess
   uint32_t r_tau;        // sample rank that estimates the threshold itself (for the width of the histogram bins)
   uint32_t fidx;         // number of this segment among the guessing ones
-  uint32_t pad0;
+  uint32_t in_stream;    // 1: a block of k_stream selects and encodes the unit (at most 4096 coordinates, segmented context)
 };
 
-struct WtInfo { uint32_t seg, chunk, pad0, pad1; };                 // one chunk (multi-segment contexts only)
+// one chunk (multi-segment contexts only).  inblock = 1: the chunk's k_stream block belongs to one unit of at most 4096
+// coordinates, which that block also selects and encodes; chunk = NO_CHUNK then pads the unit to a whole block.
+struct WtInfo { uint32_t seg, chunk, inblock, pad1; };
+constexpr uint32_t NO_CHUNK = 0xFFFFFFFFu;
 struct SelInfo { uint32_t seg, j, pad0, pad1; };                    // one block of a selection kernel
 struct CbInfo { uint32_t seg, b, pad0, pad1; };                     // one compaction block
 
@@ -90,6 +95,8 @@ struct DevCtx {
   const uint32_t* big_segs; // the segments that are not selected by one block (they use histograms)
   const uint32_t* seg_dir;  // [ceil(d / 1024) + 1]: segment of coordinate t * 1024 (the last entry: L - 1)
   const uint32_t* slot_dir; // [ceil(K / 256) + 1]: segment of slot b * 256 of the selected arrays
+  const uint32_t* seg_start; const uint32_t* seg_koff;   // [L]: first coordinate / first slot of every segment, packed for the searches
+  const uint32_t* seg_whole;  // [L]: 1 where the segment is kept whole (k = size)
   UnitState* units;
   uint2* slots; uint64_t slot_stride;   // per worker: one slot (lpc * 2 elements) per chunk of every fast segment
   uint2* ovf; uint64_t ovf_stride;      // per worker: overflow pools, for chunks with more candidates than a slot holds
@@ -104,12 +111,13 @@ struct DevCtx {
   uint32_t* ctr;        // [U][CTR_LINES][PAD]; word 0 of each line is a counter; all zero between calls
   uint64_t* norm_acc;   // [U][ACC_SLOTS]; all zero between calls
   uint32_t* sel_idx; uint32_t* sel_val; uint32_t* sel_code;   // [R][K]; code = level | neg << 31
-  uint32_t* blk_cnt;    // [R][QB] survivors per quantise block
+  uint32_t* blk_cnt;    // [Rmax][QB] transmitted entries per block of 256 slots: added to by every kernel that encodes.  Two arrays
+  uint32_t* blk_cnt_next; // take turns from call to call: the last kernel of a call (k_pack) sets the next call's to zero.
   uint32_t* blk_pre;    // [R][QB + 1] their exclusive prefix and total (only when QB > MAX_QB_INLINE)
   uint32_t* surv_idx; uint32_t* surv_code;                    // [R][K]
   uint32_t* status;
   uint64_t d, seed;
-  uint32_t L, K, NWT, NSEL, NCB, NWC, QB, NSELF, nfast, nbig, s, w_idx, w_lev, w_val, sparsifier, quantizer, cap_words;
+  uint32_t L, K, NWT, NSEL, NCB, NWC, QB, NSELF, nfast, nblock, Rmax, nbig, s, w_idx, w_lev, w_val, sparsifier, quantizer, cap_words;
 };
 
 __device__ __forceinline__ uint32_t key_of_value(uint32_t vbits) { return (vbits & 0x7FFFFFFFu) << 1; }

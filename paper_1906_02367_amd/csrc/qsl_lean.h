@@ -88,10 +88,6 @@ __global__ __launch_bounds__(BIG) void k_lean_hist(DevCtx c, SegInfo one, uint32
   for (int b = 0; b < 4; ++b) rr[b] = read_slot_row(lu.slots, lu.slot_key, sg.lpc, sg.nwt, lu.r_lo + b, lu.r_hi);   // issued before anything waits
   for (uint32_t i = threadIdx.x; i < HBINS; i += BIG) lh[i] = 0;
   if (threadIdx.x < CTR_LINES) s_ctr[threadIdx.x] = c.ctr[(lu.u * CTR_LINES + threadIdx.x) * PAD];
-  // the survivor counters of the worker's slots (one per 256 slots; the kernels that encode add to them) start at
-  // zero: by the blocks of the first listed unit, one per worker
-  if (blockIdx.x < R && is_qsgd(c.quantizer))
-    for (uint32_t i = threadIdx.x; i < c.QB; i += BIG) c.blk_cnt[static_cast<uint64_t>(lu.w) * c.QB + i] = 0;
   __syncthreads();
   // a guess that produced too few candidates, or more than there is room for, is discarded here
   uint32_t cand = 0;
@@ -249,6 +245,108 @@ __global__ __launch_bounds__(BIG) void k_lean_mark(DevCtx c, SegInfo one, uint32
 }
 
 // ------------------------------------------------------------------------------------------------
+// A unit of at most 40,960 coordinates that is too dense for guessing, whole, by one block of 1024 threads: thread t
+// takes up to 40 consecutive coordinates, read again from v (which the cache holds) for each of the three radix
+// digits and for the ordered pass; one block-wide scan orders the output.  Selection, norm, codes and error update
+// without a launch in between.
+// ------------------------------------------------------------------------------------------------
+template <int SPARS>
+__device__ void block_unit(const DevCtx& c, const SegInfo& sg, uint32_t w, uint64_t u, const float* vp, uint32_t worker0,
+                           uint64_t round, float* m_out, uint32_t* dbg_idx, uint16_t* dbg_level, uint32_t* lh,
+                           uint64_t* acc, uint64_t* scratch, uint32_t* result, float* s_scale, uint32_t* s_count) {
+  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint32_t n = static_cast<uint32_t>(sg.size);                 // <= BLOCK_MAX
+  const uint32_t per = (((n + BIG - 1) / BIG) + 3u) & ~3u;           // coordinates per thread: a multiple of 4, <= BLOCK_PER
+  const uint32_t e0 = threadIdx.x * per;
+  // A pass over the thread's coordinates: the loads of five groups of four (dwordx4 each) are issued together, then
+  // f(e, bits, key) sees each coordinate inside the unit in order.  Two rounds of loads cover the 40 a thread can have.
+  auto pass = [&](auto&& f) {
+    constexpr uint32_t G = 5;
+    for (uint32_t q0 = 0; q0 < per; q0 += 4 * G) {
+      f4u x[G];
+#pragma unroll
+      for (uint32_t g = 0; g < G; ++g) {
+        const uint32_t e = e0 + q0 + g * 4;
+        x[g] = f4u{0.f, 0.f, 0.f, 0.f};
+        if (q0 + g * 4 < per) {
+          if (e + 4 <= n) x[g] = *reinterpret_cast<const f4u*>(vp + e);
+          else {
+#pragma unroll
+            for (uint32_t j = 0; j < 4; ++j) if (e + j < n) x[g][j] = vp[e + j];
+          }
+        }
+      }
+#pragma unroll
+      for (uint32_t g = 0; g < G; ++g) {
+        const uint32_t e = e0 + q0 + g * 4;
+        if (q0 + g * 4 >= per || e >= n) continue;
+        Words4 rw = {{0u, 0u, 0u, 0u}};
+        if (SPARS == QSL_RANDK) rw = rand_words4(rk, static_cast<uint32_t>(sg.start) + e);
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) {
+          const uint32_t bits = __float_as_uint(x[g][j]);
+          if (e + j < n) f(e + j, bits, SPARS == QSL_TOPK ? key_of_value(bits) : rw.w[j]);
+        }
+      }
+    }
+  };
+  for (uint32_t i = threadIdx.x; i < HBINS; i += BIG) lh[i] = 0;
+  for (uint32_t i = threadIdx.x; i < LEAN_ROWS * (ACC_SLOTS + 1); i += BIG) acc[i] = 0;
+  __syncthreads();
+  uint32_t above, bin;
+  // the three digits of the k-th largest key
+  pass([&](uint32_t, uint32_t, uint32_t key) { atomicAdd(&lh[key >> 20], 1u); });
+  __syncthreads();
+  bin = find_from_top<BIG>(lh, sg.k, &above, scratch, result, true);
+  uint32_t prefix = bin << 20, k_rem = sg.k - above;
+  pass([&](uint32_t, uint32_t, uint32_t key) { if ((key >> 20) == (prefix >> 20)) atomicAdd(&lh[(key >> 8) & 0xFFFu], 1u); });
+  __syncthreads();
+  bin = find_from_top<BIG>(lh, k_rem, &above, scratch, result, true);
+  prefix |= bin << 8; k_rem -= above;
+  pass([&](uint32_t, uint32_t, uint32_t key) { if ((key >> 8) == (prefix >> 8)) atomicAdd(&lh[key & 0xFFu], 1u); });
+  __syncthreads();
+  bin = find_from_top<BIG, 1024>(lh, k_rem, &above, scratch, result, true);      // bins 256 .. 1023 are empty
+  const uint32_t tau = prefix | bin, need = k_rem - above;
+  // ordered compaction: key > tau, and the first `need` coordinates with key == tau
+  uint32_t n_gt = 0, n_eq = 0;
+  pass([&](uint32_t, uint32_t, uint32_t key) { n_gt += key > tau; n_eq += key == tau; });
+  uint64_t total;
+  const uint64_t ex = block_exclusive_scan64((static_cast<uint64_t>(n_eq) << 32) | n_gt, scratch, &total);
+  uint32_t my_gt = static_cast<uint32_t>(ex), my_eq = static_cast<uint32_t>(ex >> 32);
+  uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
+  uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
+  uint64_t* mine = acc + ((wave & 7u) * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
+  const bool squares = wants_squares(c.quantizer);
+  if (n_gt != 0 || (n_eq != 0 && my_eq < need)) {
+    pass([&](uint32_t e, uint32_t bits, uint32_t key) {
+      const bool is_gt = key > tau, is_eq = key == tau;
+      if (is_gt || (is_eq && my_eq < need)) {
+        const uint32_t pos = my_gt + min(my_eq, need);
+        if (pos < sg.k) { oi[pos] = static_cast<uint32_t>(sg.start) + e; ov[pos] = bits; add_digits(mine, bits, squares); }
+      }
+      my_gt += is_gt; my_eq += is_eq;
+    });
+  }
+  if (threadIdx.x == 0) { c.units[u].cand = 0; c.units[u].fell_back = 0; }
+  block_encode_tail<BIG, LEAN_ROWS>(c, sg, w, u, tau, need, worker0, round, m_out, dbg_idx, dbg_level, acc, s_scale, s_count);
+}
+
+template <int SPARS>
+__global__ __launch_bounds__(BIG) void k_block_units(DevCtx c, uint32_t R, float* m_out, uint32_t worker0, uint64_t round,
+                                                     uint32_t* dbg_idx, uint16_t* dbg_level) {
+  __shared__ uint32_t lh[HBINS];
+  __shared__ uint64_t acc[LEAN_ROWS * (ACC_SLOTS + 1)];
+  __shared__ uint64_t scratch[17];
+  __shared__ uint32_t result[2], s_count;
+  __shared__ float s_scale;
+  const uint32_t seg = c.small_segs[blockIdx.x / R], w = blockIdx.x % R;       // workers innermost, largest units first
+  const SegInfo sg = c.segs[seg];
+  block_unit<SPARS>(c, sg, w, static_cast<uint64_t>(w) * c.L + seg, m_out + static_cast<uint64_t>(w) * c.d + sg.start,
+                    worker0, round, m_out, dbg_idx, dbg_level, lh, acc, scratch, result, &s_scale, &s_count);
+}
+
+// ------------------------------------------------------------------------------------------------
 // exact selection of one unit by one block of 1024 threads, by radix digits (12 + 12 + 8 bits) and an ordered pass,
 // followed by the norm and the encoding of the k selected coordinates: for a unit whose guess failed (FROM_V: the
 // keys come from v itself) or whose threshold bin was too crowded for the short list (from the dense list).  Slow
@@ -258,7 +356,7 @@ template <int SPARS, bool FROM_V>
 __device__ void block_select_encode(const DevCtx& c, const SegInfo& sg, uint32_t w, uint64_t u, const float* vp,
                                     const uint2* d0, const uint32_t* d0k, uint64_t n, uint32_t worker0, uint64_t round,
                                     float* m_out, uint32_t* dbg_idx, uint16_t* dbg_level, uint32_t* lh, uint64_t* acc,
-                                    uint64_t* scratch, uint32_t* result, float* s_scale) {
+                                    uint64_t* scratch, uint32_t* result, float* s_scale, uint32_t* s_count) {
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   auto load = [&](uint64_t i, uint32_t* idx, uint32_t* bits, uint32_t* key) {
@@ -333,34 +431,7 @@ __device__ void block_select_encode(const DevCtx& c, const SegInfo& sg, uint32_t
     }
     run_gt += static_cast<uint32_t>(total); run_eq += static_cast<uint32_t>(total >> 32);
   }
-  __syncthreads();
-  // the norm: the rows added up into row 0, then one wave turns the digits into the scale
-  {
-    static_assert(ACC_SLOTS <= 2 * (BIG / 64), "two digit counters per wave at most");
-    const uint64_t x0 = wave_sum64(acc[lane * (ACC_SLOTS + 1) + wave]);
-    const uint64_t x1 = wave + BIG / 64 < ACC_SLOTS ? wave_sum64(acc[lane * (ACC_SLOTS + 1) + wave + BIG / 64]) : 0;
-    __syncthreads();
-    if (lane == 0) { acc[wave] = x0; if (wave + BIG / 64 < ACC_SLOTS) acc[wave + BIG / 64] = x1; }
-  }
-  __syncthreads();
-  if (wave == 0) {
-    const float sc = finalize_scale(acc, c.quantizer, sg.k);
-    if (lane == 0) *s_scale = sc;
-  }
-  __syncthreads();
-  const UnitScale usc = unit_scale(c, *s_scale, sg.k);
-  const RandKey rk1 = make_rand_key(c.seed, worker0 + w, round, 1);
-  uint32_t nsent = 0;
-  for (uint32_t j = threadIdx.x; j < sg.k; j += BIG) {
-    const uint64_t slot = static_cast<uint64_t>(w) * c.K + sg.koff + j;
-    const bool sent = encode_entry(c, w, slot, oi[j], ov[j], usc, rk1, m_out, dbg_idx, dbg_level);
-    if (sent && is_qsgd(c.quantizer)) { atomicAdd(&c.blk_cnt[static_cast<uint64_t>(w) * c.QB + ((sg.koff + j) >> 8)], 1u); ++nsent; }
-  }
-  if (is_qsgd(c.quantizer) && c.L > 1 && nsent) atomicAdd(&c.units[u].nnz, nsent);
-  if (threadIdx.x == 0) {
-    UnitState* usp = &c.units[u];
-    usp->tau = tau; usp->need = need; usp->n_gt = sg.k - need; usp->scale_bits = __float_as_uint(usc.sent);
-  }
+  block_encode_tail<BIG, LEAN_ROWS>(c, sg, w, u, tau, need, worker0, round, m_out, dbg_idx, dbg_level, acc, s_scale, s_count);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -375,7 +446,7 @@ __global__ __launch_bounds__(BIG) void k_lean_emit(DevCtx c, SegInfo one, uint32
   __shared__ uint4 s_list[LISTCAP];
   __shared__ uint8_t s_sel[LISTCAP];
   __shared__ uint64_t scratch[17];
-  __shared__ uint32_t result[2], s_tau, s_need, s_nlist;
+  __shared__ uint32_t result[2], s_tau, s_need, s_count;
   __shared__ float s_scale;
   if (blockIdx.x >= n_regular) {
     // one block per guessing unit, idle unless the unit could not go the short way
@@ -388,11 +459,12 @@ __global__ __launch_bounds__(BIG) void k_lean_emit(DevCtx c, SegInfo one, uint32
       if (safe) return;                                           // the multi-pass kernels of this call took the unit
       if (threadIdx.x == 0) *c.host_flag = 1u;                    // the host will ask for them on its next calls
       block_select_encode<SPARS, true>(c, sg, w, u, m_out + static_cast<uint64_t>(w) * c.d + sg.start, nullptr, nullptr,
-                                       sg.size, worker0, round, m_out, dbg_idx, dbg_level, lh, acc, scratch, result, &s_scale);
+                                       sg.size, worker0, round, m_out, dbg_idx, dbg_level, lh, acc, scratch, result, &s_scale,
+                                       &s_count);
     } else if (us.crowded) {
       block_select_encode<SPARS, false>(c, sg, w, u, nullptr, c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off,
                                         c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off, us.cand, worker0,
-                                        round, m_out, dbg_idx, dbg_level, lh, acc, scratch, result, &s_scale);
+                                        round, m_out, dbg_idx, dbg_level, lh, acc, scratch, result, &s_scale, &s_count);
     }
     return;
   }

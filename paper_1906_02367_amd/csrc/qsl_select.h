@@ -1,6 +1,6 @@
 // qsl_select.h -- Exact selection of the k largest rank keys of every unit (Section 2.2) and their ordered compaction:
-// k_select<0..2> (radix digits, over the candidates or over the whole vector), k_small (one block per small
-// unit), k_tile_count and k_tile_write (ordered output, exact norm digits).
+// k_select<0..2> (radix digits over the whole vector), k_full (k = size), k_tile_count and k_tile_write (ordered
+// output, exact norm digits); the slot rows of the guessing units.
 // Part of the single translation unit qsl.hip (included there, in this order: layout, stream, select,
 // encode, decode); not a public header.
 #pragma once
@@ -354,126 +354,6 @@ __device__ __forceinline__ Thresh last_digit(const DevCtx& c, uint64_t u, const 
 __device__ __forceinline__ void fallback_range(const SegInfo& sg, uint32_t b, uint32_t* g_lo, uint32_t* g_hi) {
   const uint64_t ngg = (static_cast<uint64_t>(sg.nwt) + GGROUP - 1) / GGROUP;
   *g_lo = static_cast<uint32_t>(ngg * b / sg.ncb); *g_hi = static_cast<uint32_t>(ngg * (b + 1) / sg.ncb);
-}
-
-// ------------------------------------------------------------------------------------------------
-// small units (at most 4 chunks = 4096 coordinates): the whole selection by one block of 256 threads.
-// Thread t keeps 16 consecutive coordinates in registers (Top_k: the bits of v; Rand_k: the random
-// words), the three digit histograms live in LDS, and the block writes the selected coordinates in order
-// together with the digits of their norm -- what k_select<0..2>, k_tile_count and k_tile_write do for a
-// larger unit, without a launch in between.  (One CU retires ~64 lane-operations per cycle: a block
-// needed 25 us for 16,384 coordinates and 50 us for 65,536, and the slowest block is the kernel's time,
-// so the limit is low; segments above it take the guessing path, whose kernels run anyway.)
-// ------------------------------------------------------------------------------------------------
-template <int LEVEL, int SPARS>
-__device__ __forceinline__ void small_hist(const uint32_t (&kv)[16], uint32_t n, uint32_t prefix, uint32_t* lh) {
-  const uint32_t e0 = threadIdx.x * 16;
-#pragma unroll
-  for (uint32_t j = 0; j < 16; ++j) {
-    const uint32_t key = SPARS == QSL_TOPK ? key_of_value(kv[j]) : kv[j];
-    uint32_t bin;
-    if (e0 + j < n && level_bin<LEVEL>(key, prefix, &bin)) atomicAdd(&lh[bin], 1u);
-  }
-}
-
-template <int SPARS>
-__global__ __launch_bounds__(BLOCK) void k_small(DevCtx c, const float* v, uint32_t worker0, uint64_t round, uint32_t R) {
-  __shared__ uint32_t lh[HBINS];
-  __shared__ uint64_t acc[ACC_ROWS * (ACC_SLOTS + 1)];
-  __shared__ uint64_t scratch[17];
-  __shared__ uint32_t result[2];
-  const uint32_t seg = c.small_segs[blockIdx.x / R], w = blockIdx.x % R;      // workers innermost, largest units first
-  const SegInfo sg = c.segs[seg];
-  const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
-  const float* vp = v + static_cast<uint64_t>(w) * c.d + sg.start;
-  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
-  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const uint32_t n = static_cast<uint32_t>(sg.size);                 // <= SMALL_CHUNKS * CHUNK = 16 * BLOCK
-  const uint32_t e0 = threadIdx.x * 16;
-  uint32_t kv[16];
-#pragma unroll
-  for (uint32_t q = 0; q < 4; ++q) {
-    const uint32_t e = e0 + q * 4;
-    if (SPARS == QSL_TOPK) {
-      f4u x = {0.f, 0.f, 0.f, 0.f};
-      if (e + 4 <= n) x = *reinterpret_cast<const f4u*>(vp + e);
-      else {
-#pragma unroll
-        for (uint32_t j = 0; j < 4; ++j) if (e + j < n) x[j] = vp[e + j];
-      }
-#pragma unroll
-      for (uint32_t j = 0; j < 4; ++j) kv[q * 4 + j] = __float_as_uint(x[j]);
-    } else {
-      Words4 rw = {{0u, 0u, 0u, 0u}};
-      if (e < n) rw = rand_words4(rk, static_cast<uint32_t>(sg.start) + e);
-#pragma unroll
-      for (uint32_t j = 0; j < 4; ++j) kv[q * 4 + j] = rw.w[j];
-    }
-  }
-  for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;
-
-  // the three digits of the k-th largest key
-  uint32_t above;
-  for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK) lh[i] = 0;
-  __syncthreads();
-  small_hist<0, SPARS>(kv, n, 0, lh);
-  __syncthreads();
-  uint32_t bin = find_from_top<BLOCK>(lh, sg.k, &above, scratch, result, true);
-  uint32_t prefix = bin << 20, k_rem = sg.k - above;
-  small_hist<1, SPARS>(kv, n, prefix, lh);
-  __syncthreads();
-  bin = find_from_top<BLOCK>(lh, k_rem, &above, scratch, result, true);
-  prefix |= bin << 8; k_rem -= above;
-  small_hist<2, SPARS>(kv, n, prefix, lh);
-  __syncthreads();
-  bin = find_from_top<BLOCK, 256>(lh, k_rem, &above, scratch, result, false);
-  const uint32_t tau = prefix | bin, need = k_rem - above;
-
-  // ordered compaction: key > tau, and the first `need` coordinates with key == tau
-  uint32_t gm = 0, qm = 0;
-#pragma unroll
-  for (uint32_t j = 0; j < 16; ++j) {
-    const uint32_t key = SPARS == QSL_TOPK ? key_of_value(kv[j]) : kv[j];
-    const bool inside = e0 + j < n;
-    gm |= (inside && key > tau ? 1u : 0u) << j;
-    qm |= (inside && key == tau ? 1u : 0u) << j;
-  }
-  uint64_t total;
-  const uint64_t ex = block_exclusive_scan64((static_cast<uint64_t>(__popc(qm)) << 32) | __popc(gm), scratch, &total);
-  const uint32_t gt0 = static_cast<uint32_t>(ex), eq0 = static_cast<uint32_t>(ex >> 32);
-  // which of this thread's ties are kept: the first need - eq0 of them
-  uint32_t keep = 0;
-  if (eq0 < need) {
-    keep = qm;
-    for (uint32_t extra = eq0 + __popc(qm); extra > need; --extra) keep &= ~(0x80000000u >> __clz(keep));   // drop the last
-  }
-  const uint32_t sel = gm | keep;
-  uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
-  uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
-  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
-  const bool squares = wants_squares(c.quantizer);
-#pragma unroll
-  for (uint32_t j = 0; j < 16; ++j) {
-    if ((sel >> j) & 1u) {
-      const uint32_t below = (1u << j) - 1u;
-      const uint32_t pos = gt0 + __popc(gm & below) + min(eq0 + __popc(qm & below), need);
-      const uint32_t bits = SPARS == QSL_TOPK ? kv[j] : __float_as_uint(vp[e0 + j]);
-      oi[pos] = static_cast<uint32_t>(sg.start) + e0 + j; ov[pos] = bits;
-      add_digits(mine, bits, squares);
-    }
-  }
-  __syncthreads();
-  // the unit is this block's alone: its norm digits are stored, not added
-  for (uint32_t sl = wave; sl < ACC_SLOTS; sl += BLOCK / 64) {
-    uint64_t x = lane < ACC_ROWS ? acc[lane * (ACC_SLOTS + 1) + sl] : 0;
-    x = wave_sum64(x);
-    if (lane == 0) c.norm_acc[u * ACC_SLOTS + sl] = x;
-  }
-  if (threadIdx.x == 0) {
-    UnitState* us = &c.units[u];
-    us->cand = 0; us->fell_back = 0; us->prefix2 = tau & ~0xFFu; us->k_rem2 = k_rem;
-    us->tau = tau; us->need = need; us->n_gt = sg.k - need; us->nnz = 0;
-  }
 }
 
 // ------------------------------------------------------------------------------------------------

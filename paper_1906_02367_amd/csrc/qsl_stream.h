@@ -6,6 +6,8 @@
 
 #include "qsl_device.h"
 #include "qsl_layout.h"
+#include "qsl_select.h"
+#include "qsl_encode.h"
 
 namespace {
 
@@ -119,10 +121,110 @@ __global__ __launch_bounds__(BIG) void k_sample_scan(DevCtx c) {
 }
 
 // ------------------------------------------------------------------------------------------------
+// A unit of at most 4096 coordinates that has a k_stream block to itself (four waves, a chunk each): the block
+// has the unit's values in registers when it has streamed them, so it goes on to select, order, norm and encode the
+// unit itself -- radix digits of the k-th largest key in LDS, ranks by ballots and one exchange of the waves'
+// counts -- while the other blocks of the launch keep streaming.  Lane l of the wave with chunk c holds the
+// coordinates c * 1024 + t * 256 + l * 4 + j (t, j = 0..3) in v[t][j]; `cb` is the wave's first coordinate inside
+// the unit (>= the unit's size for a wave without a chunk).
+// ------------------------------------------------------------------------------------------------
+template <int LEVEL>
+__device__ __forceinline__ void stream_unit_hist(const uint32_t (&key)[16], uint32_t inside, uint32_t prefix, uint32_t* lh) {
+#pragma unroll
+  for (uint32_t i = 0; i < 16; ++i) {
+    uint32_t bin;
+    if (((inside >> i) & 1u) && level_bin<LEVEL>(key[i], prefix, &bin)) atomicAdd(&lh[bin], 1u);
+  }
+}
+
+template <int SPARS>
+__device__ void stream_block_unit(const DevCtx& c, const SegInfo& sg, uint64_t u, uint32_t w, uint64_t cb, const f4u (&v)[4],
+                                  uint32_t worker0, uint64_t round, float* m_out, uint32_t* dbg_idx, uint16_t* dbg_level,
+                                  uint32_t* lh, uint64_t* acc, uint64_t* scratch, uint32_t* result, uint32_t* s_wt,
+                                  float* s_scale, uint32_t* s_count) {
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
+  uint32_t key[16], inside = 0;
+#pragma unroll
+  for (uint32_t t = 0; t < 4; ++t) {
+    const uint64_t e = cb + t * 256 + lane * 4;
+    Words4 rw = {{0u, 0u, 0u, 0u}};
+    if (SPARS == QSL_RANDK && e < sg.size) rw = rand_words4(rk, static_cast<uint32_t>(sg.start + e));
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) {
+      key[t * 4 + j] = SPARS == QSL_TOPK ? key_of_value(__float_as_uint(v[t][j])) : rw.w[j];
+      inside |= (e + j < sg.size ? 1u : 0u) << (t * 4 + j);
+    }
+  }
+  for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK) lh[i] = 0;
+  for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;
+  __syncthreads();
+  // the three digits of the k-th largest key
+  uint32_t above;
+  stream_unit_hist<0>(key, inside, 0, lh);
+  __syncthreads();
+  uint32_t bin = find_from_top<BLOCK>(lh, sg.k, &above, scratch, result, true);
+  uint32_t prefix = bin << 20, k_rem = sg.k - above;
+  stream_unit_hist<1>(key, inside, prefix, lh);
+  __syncthreads();
+  bin = find_from_top<BLOCK>(lh, k_rem, &above, scratch, result, true);
+  prefix |= bin << 8; k_rem -= above;
+  stream_unit_hist<2>(key, inside, prefix, lh);
+  __syncthreads();
+  bin = find_from_top<BLOCK, 256>(lh, k_rem, &above, scratch, result, false);
+  const uint32_t tau = prefix | bin, need = k_rem - above;
+  // ranks in coordinate order: wave (= chunk), then t, then lane, then j.  Counts packed as (#equal << 16 | #greater).
+  uint32_t gm = 0, qm = 0;
+#pragma unroll
+  for (uint32_t i = 0; i < 16; ++i) {
+    gm |= (((inside >> i) & 1u) && key[i] > tau ? 1u : 0u) << i;
+    qm |= (((inside >> i) & 1u) && key[i] == tau ? 1u : 0u) << i;
+  }
+  uint32_t pre[4];
+#pragma unroll
+  for (uint32_t t = 0; t < 4; ++t) {
+    uint32_t tot;
+    pre[t] = wave_exclusive_scan32(__popc((gm >> (t * 4)) & 0xFu) | (__popc((qm >> (t * 4)) & 0xFu) << 16), &tot);
+    if (lane == 0) s_wt[wave * 4 + t] = tot;
+  }
+  __syncthreads();
+  uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
+  uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
+  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
+  const bool squares = wants_squares(c.quantizer);
+  uint32_t base = 0;                                // counts of everything before (wave, t = 0)
+  for (uint32_t i = 0; i < wave * 4; ++i) base += s_wt[i];
+#pragma unroll
+  for (uint32_t t = 0; t < 4; ++t) {
+    const uint32_t mine_t = base + pre[t];
+    uint32_t my_gt = mine_t & 0xFFFFu, my_eq = mine_t >> 16;
+    const uint32_t gn = (gm >> (t * 4)) & 0xFu, qn = (qm >> (t * 4)) & 0xFu;
+    if (gn | qn) {
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) {
+        const bool is_gt = (gn >> j) & 1u, is_eq = (qn >> j) & 1u;
+        if (is_gt || (is_eq && my_eq < need)) {
+          const uint32_t pos = my_gt + min(my_eq, need);
+          const uint32_t bits = __float_as_uint(v[t][j]);
+          if (pos < sg.k) {
+            oi[pos] = static_cast<uint32_t>(sg.start + cb + t * 256 + lane * 4 + j); ov[pos] = bits;
+            add_digits(mine, bits, squares);
+          }
+        }
+        my_gt += is_gt; my_eq += is_eq;
+      }
+    }
+    base += s_wt[wave * 4 + t];
+  }
+  if (threadIdx.x == 0) { c.units[u].cand = 0; c.units[u].fell_back = 0; }
+  block_encode_tail<BLOCK, ACC_ROWS>(c, sg, w, u, tau, need, worker0, round, m_out, dbg_idx, dbg_level, acc, s_scale, s_count);
+}
+
+// ------------------------------------------------------------------------------------------------
 // the streaming pass.  One wave per chunk of 1024 coordinates: 8 + 4 dwordx4 accesses with
 // streaming (non-temporal) cache hints, then the chunk's candidates go to the chunk's slot.
 //
-// Slot of a chunk: lpc * 2 elements of 8 bytes.  Element 0 is the header (count, overflow offset);
+// Slot of a chunk: lpc * 2 elements of 8 bytes (lpc = 4, 8, 16 or 32: 64 to 512 bytes).  Element 0 is the header (count, overflow offset);
 // elements 1 .. count hold (coordinate, value bits) in coordinate order.  A chunk with more
 // candidates than its slot holds puts all of them into the unit's overflow pool instead (one
 // returning atomic; rare unless the large values cluster) and records where.
@@ -141,9 +243,15 @@ typedef uint32_t u2v __attribute__((ext_vector_type(2)));
 template <int SPARS, bool SINGLE, bool DIFF>
 __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE && !DIFF ? 3 : 4, SINGLE && !DIFF ? 3 : 4))) void k_stream(DevCtx c, StreamSeg one, const float* m, const float* delta,
                                                   const float* xm, float* m_out, uint32_t worker0, uint64_t round,
-                                                  uint32_t R) {
-  __shared__ uint2 s_stage[BLOCK / 64][32];
-  __shared__ uint32_t s_stage_key[SPARS == QSL_RANDK ? BLOCK / 64 : 1][32];
+                                                  uint32_t R, uint32_t* dbg_idx, uint16_t* dbg_level) {
+  __shared__ uint2 s_stage[BLOCK / 64][64];
+  // only for the units that a block of this kernel selects and encodes itself (segmented contexts)
+  __shared__ uint32_t s_lh[SINGLE ? 1 : HBINS];
+  __shared__ uint64_t s_acc[SINGLE ? 1 : ACC_ROWS * (ACC_SLOTS + 1)];
+  __shared__ uint64_t s_scratch[17];
+  __shared__ uint32_t s_result[2], s_wt[16], s_count;
+  __shared__ float s_scale;
+  __shared__ uint32_t s_stage_key[SPARS == QSL_RANDK ? BLOCK / 64 : 1][64];
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   uint32_t blk = blockIdx.x, w = blockIdx.y;
   if (DIFF) {
@@ -155,10 +263,11 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
   if (wt >= c.NWT) return;
   StreamSeg sg = one;
   uint32_t seg = 0, chunk = wt;
+  bool inblock = false;
   if (!SINGLE) {
     const WtInfo wi = c.wts[wt];
     const SegInfo& s = c.segs[wi.seg];
-    seg = wi.seg; chunk = wi.chunk;
+    seg = wi.seg; chunk = wi.chunk; inblock = wi.inblock != 0;
     sg.start = s.start; sg.size = s.size; sg.slot_off = s.slot_off; sg.ovf_off = s.ovf_off;
     sg.lpc = s.lpc; sg.ovf_cap = s.ovf_cap;
   }
@@ -170,7 +279,8 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
   const float* dp = delta + row;
   const float* xp = DIFF ? xm + sg.start : nullptr;
   float* op = m_out + row;
-  const uint64_t cb = static_cast<uint64_t>(chunk) * CHUNK;           // segment-local
+  // segment-local; a wave that only fills up the block of a small unit has no chunk: nothing of it lies inside the unit
+  const uint64_t cb = !SINGLE && chunk == NO_CHUNK ? sg.size : static_cast<uint64_t>(chunk) * CHUNK;
   f4u v[4];
   if (sg.size - cb >= CHUNK) {
     f4u a[4], b[4], x[4];
@@ -209,6 +319,12 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
     for (int j = 0; j < 4; ++j) nonfinite |= (__float_as_uint(v[t][j]) & 0x7FFFFFFFu) >= 0x7F800000u;
   }
   if (__ballot(nonfinite) != 0 && lane == 0) atomicOr(c.status, 1u);
+  if (!SINGLE && inblock) {                       // uniform over the block: it selects and encodes its unit itself
+    const SegInfo unit = c.segs[seg];
+    stream_block_unit<SPARS>(c, unit, u, w, cb, v, worker0, round, m_out, dbg_idx, dbg_level, s_lh, s_acc, s_scratch,
+                             s_result, s_wt, &s_scale, &s_count);
+    return;
+  }
   if (path != PATH_FAST) return;                  // uniform over the wave: only a guessing unit collects candidates
 
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);

@@ -191,11 +191,15 @@ def test_plan_of_the_selection_paths(lib):
     assert plan(lib, 25_557_032, [0, 25_557_032], [2_555_703]) == [MULTI]
     assert plan(lib, 4_096, [0, 4_096], [40]) == [ONE_BLOCK]
     assert plan(lib, 4_097, [0, 4_097], [10]) == [FAST]
-    assert plan(lib, 4_097, [0, 4_097], [40]) == [MULTI]          # 16 candidates per chunk and their spread do not fit a slot
+    assert plan(lib, 4_097, [0, 4_097], [40]) == [FAST]
+    assert plan(lib, 4_097, [0, 4_097], [400]) == [ONE_BLOCK]     # too dense to guess, small enough for one block (up to 40,960)
+    assert plan(lib, 40_960, [0, 40_960], [4_000]) == [ONE_BLOCK]
+    assert plan(lib, 40_961, [0, 40_961], [4_000]) == [MULTI]
     assert plan(lib, 4_096, [0, 4_096], [4_096]) == [ONE_BLOCK]
     assert plan(lib, 300_000, [0, 300_000], [300_000]) == [ALL_KEPT]
-    # candidates must fit the chunk slots: 1000 of 65,536 is sparse enough to guess by k * 64 <= size, but not for the slots
-    assert plan(lib, 65_536, [0, 65_536], [1_000]) == [MULTI]
+    # the candidates of a chunk must fit its slot (at most 63): 1000 of 65,536 does, 3000 of 100,000 is too dense to guess at all
+    assert plan(lib, 65_536, [0, 65_536], [1_000]) == [FAST]
+    assert plan(lib, 100_000, [0, 100_000], [3_000]) == [MULTI]
     assert plan(lib, 262_144, [0, 262_144], [1_000]) == [FAST]
     # Rand_k guesses analytically when at most ~14 candidates fall into a chunk
     assert plan(lib, 25_557_032, [0, 25_557_032], [255_570], sp=1) == [FAST]
@@ -204,11 +208,13 @@ def test_plan_of_the_selection_paths(lib):
     assert plan(lib, 25_557_032, [0, 25_557_032], [25_557], flags=1) == [MULTI]
     assert plan(lib, 4_096, [0, 4_096], [40], flags=2) == [MULTI]
     assert plan(lib, 4_096, [0, 4_096], [40], flags=3) == [MULTI]
+    assert plan(lib, 30_000, [0, 30_000], [3_000], flags=2) == [MULTI]
     assert plan(lib, 300_000, [0, 300_000], [300_000], flags=1) == [MULTI]
-    # the paper's ResNet-50 setting (Section 5.1.1): 108 small tensors, 20 too dense for guessing, 33 that guess
+    # the paper's ResNet-50 setting (Section 5.1.1): 119 tensors for one block each (108 of at most 4096 coordinates, 11
+    # larger ones that are too dense for guessing), 42 that guess, none left for the multi-pass kernels
     wl = W.config(6)
     paths = plan(lib, wl.d, [int(x) for x in wl.seg_offset], [int(x) for x in wl.seg_k], qz=1, s=1)
-    assert (paths.count(ONE_BLOCK), paths.count(MULTI), paths.count(FAST), paths.count(ALL_KEPT)) == (108, 20, 33, 0)
+    assert (paths.count(ONE_BLOCK), paths.count(MULTI), paths.count(FAST), paths.count(ALL_KEPT)) == (119, 0, 42, 0)
     # invalid descriptions are refused
     cfg = make_cfg(100, [0, 100], [101])
     out = (C.c_uint32 * 1)()
