@@ -18,6 +18,7 @@ _LIB = os.path.join(_HERE, "libqsl_oracle.so")
 
 TOPK, RANDK = 0, 1
 QSGD, SIGN_L1, SIGN_L2, FP32, QSGD_SCALED = 0, 1, 2, 3, 4
+DENSE_FORMAT = 0x100          # added to the quantiser number: the index-free format of an operator that keeps every coordinate
 STREAM_SELECT, STREAM_QUANT = 0, 1
 
 
@@ -94,7 +95,7 @@ def exact_sum_of_abs(x):
 class OracleOp:
     """The operator Q Comp_k with its parameters fixed; one worker per call."""
 
-    def __init__(self, d, seg_offset, seg_k, s, sparsifier, quantizer, seed):
+    def __init__(self, d, seg_offset, seg_k, s, sparsifier, quantizer, seed, dense=False):
         self.d = int(d)
         self.off = np.ascontiguousarray(seg_offset, dtype=np.uint64)
         self.k = np.ascontiguousarray(seg_k, dtype=np.uint32)
@@ -102,9 +103,11 @@ class OracleOp:
         self.s = int(s)
         self.sparsifier = int(sparsifier)
         self.quantizer = int(quantizer)
+        self.dense = bool(dense)
+        self._qarg = self.quantizer | (DENSE_FORMAT if self.dense else 0)
         self.seed = int(seed)
         self.K = int(self.k.sum())
-        self._lay = (self.d, self.L, _p(self.off, C.c_uint64), _p(self.k, C.c_uint32), self.s, self.quantizer)
+        self._lay = (self.d, self.L, _p(self.off, C.c_uint64), _p(self.k, C.c_uint32), self.s, self._qarg)
         self.capacity = int(lib().qslo_msg_capacity_bytes(*self._lay))
         if self.capacity == 0:
             raise ValueError("invalid operator parameters")
@@ -123,7 +126,7 @@ class OracleOp:
         g_val = np.zeros(self.K, dtype=np.float32)
         rc = lib().qslo_compress(_p(m, C.c_float), _p(delta, C.c_float), _p(m_out, C.c_float), self.d, self.L,
                                  _p(self.off, C.c_uint64), _p(self.k, C.c_uint32), self.s, self.sparsifier,
-                                 self.quantizer, self.seed, int(worker), int(rnd), _p(msg, C.c_uint8), self.capacity,
+                                 self._qarg, self.seed, int(worker), int(rnd), _p(msg, C.c_uint8), self.capacity,
                                  _p(bits, C.c_uint64), _p(sel_idx, C.c_uint32), _p(sel_level, C.c_uint16),
                                  _p(sel_neg, C.c_uint8), _p(scales, C.c_float), _p(g_val, C.c_float))
         if rc != 0:

@@ -47,7 +47,7 @@ def _round_fraction_to_double(q: Fraction) -> float:
     return q.numerator / q.denominator
 
 
-def compress(m, delta, d, seg_offset, seg_k, s, sparsifier, quantizer, seed, worker, rnd):
+def compress(m, delta, d, seg_offset, seg_k, s, sparsifier, quantizer, seed, worker, rnd, dense=False):
     m = np.asarray(m, dtype=f32)
     delta = np.asarray(delta, dtype=f32)
     v = (m + delta).astype(f32)
@@ -116,26 +116,43 @@ def compress(m, delta, d, seg_offset, seg_k, s, sparsifier, quantizer, seed, wor
             bits.append(0)
 
     nnz = sum(counts)
-    put(nnz, 32)
-    for sc in scales:
-        put(_bits(sc), 32)
-    if qsgd and L > 1:
-        for c_ in counts:
-            put(c_, 32)
-    for i, lev in zip(sel, levels):
-        if lev:
-            put(i, w_idx)
-    align32()
-    for lev, neg, g in zip(levels, negs, gvals):
-        if lev:
+    if dense:
+        # the index-free format of an operator that keeps every coordinate: one code per coordinate, in order;
+        # a QSGD level is written as it is (0..s, in the bits needed to write s), then the sign bit
+        assert all(int(seg_k[l]) == int(seg_offset[l + 1]) - int(seg_offset[l]) for l in range(L))
+        put(d, 32)
+        for sc in scales:
+            put(_bits(sc), 32)
+        w_code = (s.bit_length() + 1) if qsgd else 32 if quantizer == 3 else 1
+        for lev, neg, g in zip(levels, negs, gvals):
             if quantizer == 3:
                 put(_bits(g), 32)
                 continue
             if qsgd:
-                put(lev - 1, w_lev)
+                put(lev, s.bit_length())
             put(int(neg), 1)
-    header = 32 + 32 * L + (32 * L if qsgd and L > 1 else 0)
-    payload_bits = header + nnz * (w_idx + (w_lev + 1 if qsgd else 32 if quantizer == 3 else 1))
+        payload_bits = 32 + 32 * L + d * w_code
+    else:
+        put(nnz, 32)
+        for sc in scales:
+            put(_bits(sc), 32)
+        if qsgd and L > 1:
+            for c_ in counts:
+                put(c_, 32)
+        for i, lev in zip(sel, levels):
+            if lev:
+                put(i, w_idx)
+        align32()
+        for lev, neg, g in zip(levels, negs, gvals):
+            if lev:
+                if quantizer == 3:
+                    put(_bits(g), 32)
+                    continue
+                if qsgd:
+                    put(lev - 1, w_lev)
+                put(int(neg), 1)
+        header = 32 + 32 * L + (32 * L if qsgd and L > 1 else 0)
+        payload_bits = header + nnz * (w_idx + (w_lev + 1 if qsgd else 32 if quantizer == 3 else 1))
     while len(bits) % 64:
         bits.append(0)
     msg = np.packbits(np.array(bits, dtype=np.uint8), bitorder="little")

@@ -195,13 +195,23 @@ enum : uint32_t { SPARS_TOPK = 0, SPARS_RANDK = 1 };
 // no quantisation at all (the TopK-SGD comparison scheme of Section 5); QSGD divided by 1 + beta_{k,s} (Lemma 2).
 enum : uint32_t { QUANT_QSGD = 0, QUANT_SIGN_L1 = 1, QUANT_SIGN_L2 = 2, QUANT_FP32 = 3, QUANT_QSGD_SCALED = 4 };
 inline bool is_qsgd(uint32_t q) { return q == QUANT_QSGD || q == QUANT_QSGD_SCALED; }
+// Added to the quantiser number by the callers of this file: the message has the index-free format of an operator
+// that keeps every coordinate (k = size in every segment: the error-feedback schemes without sparsification that
+// Section 5 compares with).  Every coordinate has a code, in coordinate order, so no index is written; a QSGD code
+// is the level 0..s itself, in the bits needed to write s, then the sign bit.
+const uint32_t QUANT_DENSE_FORMAT = 0x100;
 
 struct Layout {
-  uint64_t d; uint32_t L; const uint64_t* off; const uint32_t* k; uint32_t s; uint32_t quantizer;
+  uint64_t d; uint32_t L; const uint64_t* off; const uint32_t* k; uint32_t s; uint32_t quantizer; bool dense;
+  Layout(uint64_t d_, uint32_t L_, const uint64_t* off_, const uint32_t* k_, uint32_t s_, uint32_t quantizer_arg)
+      : d(d_), L(L_), off(off_), k(k_), s(s_), quantizer(quantizer_arg & 0xFFu), dense((quantizer_arg & QUANT_DENSE_FORMAT) != 0) {}
   uint64_t K() const { uint64_t t = 0; for (uint32_t l = 0; l < L; ++l) t += k[l]; return t; }
-  bool has_counts() const { return is_qsgd(quantizer) && L > 1; }
-  uint32_t w_idx() const { return index_width(d); }
-  uint32_t w_val() const { return is_qsgd(quantizer) ? level_width(s) + 1 : quantizer == QUANT_FP32 ? 32 : 1; }
+  bool has_counts() const { return is_qsgd(quantizer) && L > 1 && !dense; }
+  uint32_t w_idx() const { return dense ? 0 : index_width(d); }
+  uint32_t w_val() const {
+    if (is_qsgd(quantizer)) return (dense ? bit_width(s) : level_width(s)) + 1;
+    return quantizer == QUANT_FP32 ? 32 : 1;
+  }
   uint64_t header_bits() const { return 32 + 32ull * L + (has_counts() ? 32ull * L : 0); }
   uint64_t capacity_bytes() const {
     const uint64_t Kt = K();
@@ -217,6 +227,7 @@ struct Layout {
       if (k[l] == 0 || k[l] > off[l + 1] - off[l]) return false;
     }
     if (is_qsgd(quantizer) && (s == 0 || s > 32768)) return false;
+    if (dense) for (uint32_t l = 0; l < L; ++l) if (k[l] != off[l + 1] - off[l]) return false;
     return quantizer <= 4;
   }
   uint32_t segment_of(uint64_t i) const {
@@ -247,7 +258,7 @@ double qslo_exact_sum_of_abs(const float* x, uint64_t n) { return exact_sum_of_a
 
 uint64_t qslo_msg_capacity_bytes(uint64_t d, uint32_t L, const uint64_t* off, const uint32_t* k, uint32_t s,
                                  uint32_t quantizer) {
-  Layout lay{d, L, off, k, s, quantizer};
+  Layout lay(d, L, off, k, s, quantizer);
   return lay.valid() ? lay.capacity_bytes() : 0;
 }
 
@@ -270,7 +281,8 @@ int qslo_compress(const float* m, const float* delta, float* m_out, uint64_t d, 
                   const uint32_t* k, uint32_t s, uint32_t sparsifier, uint32_t quantizer, uint64_t seed,
                   uint32_t worker, uint64_t round, uint8_t* msg, uint64_t msg_capacity, uint64_t* msg_bits,
                   uint32_t* sel_idx, uint16_t* sel_level, uint8_t* sel_neg, float* scales, float* g_val) {
-  Layout lay{d, L, off, k, s, quantizer};
+  Layout lay(d, L, off, k, s, quantizer);
+  quantizer = lay.quantizer;                        // without the format flag
   if (!m || !delta || !msg || !lay.valid() || sparsifier > 1 || (round >> 62)) return 1;
   if (msg_capacity < lay.capacity_bytes()) return 2;
   const uint64_t K = lay.K();
@@ -379,20 +391,31 @@ int qslo_compress(const float* m, const float* delta, float* m_out, uint64_t d, 
   BitWriter bw(msg, msg_capacity);
   uint64_t total = 0;
   for (uint32_t l = 0; l < L; ++l) total += nnz[l];
-  bw.put(total, 32);
+  bw.put(lay.dense ? K : total, 32);
   for (uint32_t l = 0; l < L; ++l) bw.put(f2u(scale[l]), 32);
   if (lay.has_counts()) for (uint32_t l = 0; l < L; ++l) bw.put(nnz[l], 32);
-  const uint32_t wi = lay.w_idx(), wl = is_qsgd(quantizer) ? level_width(s) : 0;
-  for (uint64_t j = 0; j < K; ++j) if (lev[j]) bw.put(S[j], wi);
-  bw.align32();
-  for (uint64_t j = 0; j < K; ++j) {
-    if (!lev[j]) continue;
-    if (is_qsgd(quantizer)) { bw.put(lev[j] - 1u, wl); bw.put(neg[j], 1); }
-    else if (quantizer == QUANT_FP32) bw.put(f2u(g[j]), 32);
-    else bw.put(neg[j], 1);
+  if (lay.dense) {
+    // every coordinate, in order: no indices; a QSGD level is written as it is (0 included)
+    total = K;
+    const uint32_t wl = bit_width(s);
+    for (uint64_t j = 0; j < K; ++j) {
+      if (is_qsgd(quantizer)) { bw.put(lev[j], wl); bw.put(neg[j], 1); }
+      else if (quantizer == QUANT_FP32) bw.put(f2u(g[j]), 32);
+      else bw.put(neg[j], 1);
+    }
+  } else {
+    const uint32_t wi = lay.w_idx(), wl = is_qsgd(quantizer) ? level_width(s) : 0;
+    for (uint64_t j = 0; j < K; ++j) if (lev[j]) bw.put(S[j], wi);
+    bw.align32();
+    for (uint64_t j = 0; j < K; ++j) {
+      if (!lev[j]) continue;
+      if (is_qsgd(quantizer)) { bw.put(lev[j] - 1u, wl); bw.put(neg[j], 1); }
+      else if (quantizer == QUANT_FP32) bw.put(f2u(g[j]), 32);
+      else bw.put(neg[j], 1);
+    }
   }
   if (bw.overflow) return 2;
-  if (msg_bits) *msg_bits = lay.header_bits() + total * (wi + lay.w_val());
+  if (msg_bits) *msg_bits = lay.header_bits() + total * (lay.w_idx() + lay.w_val());
 
   // Step 6 (Algorithm 1, worker line 2): m <- v - g.  Off the transmitted set this is v itself.
   if (m_out) {
@@ -411,7 +434,7 @@ int qslo_compress(const float* m, const float* delta, float* m_out, uint64_t d, 
 // Payload bit count read back from a message.
 uint64_t qslo_bits_sent(const uint8_t* msg, uint64_t d, uint32_t L, const uint64_t* off, const uint32_t* k,
                         uint32_t s, uint32_t quantizer) {
-  Layout lay{d, L, off, k, s, quantizer};
+  Layout lay(d, L, off, k, s, quantizer);
   BitReader br(msg);
   const uint64_t total = br.get(32);
   return lay.header_bits() + total * (lay.w_idx() + lay.w_val());
@@ -421,25 +444,27 @@ uint64_t qslo_bits_sent(const uint8_t* msg, uint64_t d, uint32_t L, const uint64
 // `max_out` is too small or the message is inconsistent.
 int64_t qslo_decode(const uint8_t* msg, uint64_t d, uint32_t L, const uint64_t* off, const uint32_t* k, uint32_t s,
                     uint32_t quantizer, uint32_t* idx_out, float* val_out, uint64_t max_out) {
-  Layout lay{d, L, off, k, s, quantizer};
+  Layout lay(d, L, off, k, s, quantizer);
+  quantizer = lay.quantizer;
   if (!lay.valid()) return -1;
   BitReader br(msg);
   const uint64_t total = br.get(32);
   if (total > max_out || total > lay.K()) return -1;
+  if (lay.dense && total != 0 && total != d) return -1;
   std::vector<float> scale(L);
   for (uint32_t l = 0; l < L; ++l) scale[l] = u2f(static_cast<uint32_t>(br.get(32)));
   if (lay.has_counts()) for (uint32_t l = 0; l < L; ++l) br.get(32);
-  const uint32_t wi = lay.w_idx(), wl = is_qsgd(quantizer) ? level_width(s) : 0;
-  for (uint64_t j = 0; j < total; ++j) idx_out[j] = static_cast<uint32_t>(br.get(wi));
+  const uint32_t wi = lay.w_idx(), wl = is_qsgd(quantizer) ? (lay.dense ? bit_width(s) : level_width(s)) : 0;
+  for (uint64_t j = 0; j < total; ++j) idx_out[j] = lay.dense ? static_cast<uint32_t>(j) : static_cast<uint32_t>(br.get(wi));
   br.align32();
   for (uint64_t j = 0; j < total; ++j) {
     if (idx_out[j] >= d) return -1;
     const float sc = scale[lay.segment_of(idx_out[j])];
     if (is_qsgd(quantizer)) {
-      const uint32_t level = static_cast<uint32_t>(br.get(wl)) + 1u;
+      const uint32_t level = static_cast<uint32_t>(br.get(wl)) + (lay.dense ? 0u : 1u);
       const bool negative = br.get(1);
       const float mag = qsgd_magnitude(sc, level, s);
-      val_out[j] = negative ? -mag : mag;
+      val_out[j] = level == 0 ? 0.0f : negative ? -mag : mag;
     } else if (quantizer == QUANT_FP32) {
       val_out[j] = u2f(static_cast<uint32_t>(br.get(32)));
     } else {
@@ -452,7 +477,7 @@ int64_t qslo_decode(const uint8_t* msg, uint64_t d, uint32_t L, const uint64_t* 
 // Stand-alone error update (Algorithm 1, worker line 2) from a message: m <- (m + delta) - decode(msg).
 int qslo_error_update(float* m, const float* delta, const uint8_t* msg, uint64_t d, uint32_t L, const uint64_t* off,
                       const uint32_t* k, uint32_t s, uint32_t quantizer) {
-  Layout lay{d, L, off, k, s, quantizer};
+  Layout lay(d, L, off, k, s, quantizer);
   if (!lay.valid()) return 1;
   const uint64_t K = lay.K();
   std::vector<uint32_t> idx(K); std::vector<float> val(K);
@@ -468,7 +493,7 @@ int qslo_error_update(float* m, const float* delta, const uint8_t* msg, uint64_t
 int qslo_aggregate(const uint8_t* msgs, uint64_t msg_stride, const uint32_t* list, uint32_t R, float scale,
                    int accumulate, float* out, uint64_t d, uint32_t L, const uint64_t* off, const uint32_t* k,
                    uint32_t s, uint32_t quantizer) {
-  Layout lay{d, L, off, k, s, quantizer};
+  Layout lay(d, L, off, k, s, quantizer);
   if (!lay.valid()) return 1;
   const uint64_t K = lay.K();
   std::vector<double> acc(d, 0.0);

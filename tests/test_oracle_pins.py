@@ -547,3 +547,95 @@ def test_memory_identity_of_the_virtual_sequence(quantizer, sparsifier):
         rhs = m.astype(np.float64).mean(0)
         assert np.abs(lhs - rhs).max() <= 2e-6 * (1 + np.abs(rhs).max()), (t, np.abs(lhs - rhs).max())
     assert np.abs(m).max() > 0
+
+
+# ------------------------------------------------------------------------------------------
+# the index-free format of an operator that keeps every coordinate (k = size in every segment: the error-feedback
+# schemes without sparsification that Section 5 compares with): an independent reader written here, the closed form
+# of the bit count, the same operator output as the format with indices, and the second statement
+# ------------------------------------------------------------------------------------------
+def read_dense_message(msg, d, L, s, quantizer):
+    bits = np.unpackbits(np.asarray(msg, dtype=np.uint8), bitorder="little")
+    pos = 0
+
+    def get(w):
+        nonlocal pos
+        val = 0
+        for b in range(w):
+            val |= int(bits[pos + b]) << b
+        pos += w
+        return val
+
+    n = get(32)
+    scales = [np.array([get(32)], dtype=np.uint32).view(f32)[0] for _ in range(L)]
+    qsgd = quantizer in (O.QSGD, O.QSGD_SCALED)
+    n_level_bits = 0
+    while (1 << n_level_bits) < s + 1:                                  # fewest bits that tell the levels 0..s apart
+        n_level_bits += 1
+    lev, neg, raw = [], [], []
+    for _ in range(n):
+        if quantizer == O.FP32:
+            raw.append(get(32))
+            continue
+        lev.append(get(n_level_bits) if qsgd else 1)
+        neg.append(get(1))
+    used = pos
+    assert not bits[used:].any()                                        # zero padding
+    return n, scales, lev, neg, raw, used
+
+
+@pytest.mark.parametrize("sparsifier", [O.TOPK, O.RANDK])
+@pytest.mark.parametrize("quantizer,s", [(O.QSGD, 1), (O.QSGD, 2), (O.QSGD, 15), (O.QSGD, 16), (O.QSGD, 255), (O.SIGN_L1, 1),
+                                         (O.SIGN_L2, 1), (O.FP32, 1), (O.QSGD_SCALED, 3)])
+def test_index_free_format_carries_the_same_operator_output(sparsifier, quantizer, s):
+    rng = np.random.default_rng(300 + s + quantizer)
+    d = 777
+    off = np.array([0, 100, 164, 700, 777], dtype=np.uint64)
+    k = np.diff(off.astype(np.int64)).astype(np.uint32)                 # every coordinate kept
+    with_idx = O.OracleOp(d, off, k, s, sparsifier, quantizer, 5)
+    dense = O.OracleOp(d, off, k, s, sparsifier, quantizer, 5, dense=True)
+    m = rng.standard_normal(d).astype(f32)
+    delta = (rng.standard_normal(d) * np.exp(rng.standard_normal(d))).astype(f32)
+    delta[::50] = -m[::50]                                              # some exact zeros in v
+    a, b = with_idx.compress(m, delta, 2, 9), dense.compress(m, delta, 2, 9)
+    # the operator itself does not depend on the format
+    for name in ("sel_idx", "sel_level", "sel_neg"):
+        assert np.array_equal(a[name], b[name]), name
+    for name in ("scales", "g_val", "m_out"):
+        assert np.array_equal(bits_of(a[name]), bits_of(b[name])), name
+    assert np.array_equal(b["sel_idx"], np.arange(d))
+    # closed form of the bit count: one length word, one scale per segment, one code per coordinate
+    qsgd = quantizer in (O.QSGD, O.QSGD_SCALED)
+    w_code = 32 if quantizer == O.FP32 else 1 + (int(np.ceil(np.log2(s + 1))) if qsgd else 0)
+    assert b["bits"] == 32 + 32 * 4 + d * w_code == dense.bits_sent(b["msg"])
+    assert b["bits"] < a["bits"] or (qsgd and (a["sel_level"] == 0).sum() > d // 4)       # no indices: shorter
+    # the reader of this test rebuilds g from the bytes
+    n, scales, lev, neg, raw, used = read_dense_message(b["msg"], d, 4, s, quantizer)
+    assert n == d and used == b["bits"]
+    assert [x.tobytes() for x in scales] == [x.tobytes() for x in b["scales"]]
+    seg_of = np.searchsorted(off, np.arange(d), side="right") - 1
+    if quantizer == O.FP32:
+        assert np.array_equal(np.array(raw, dtype=np.uint32), bits_of(b["g_val"]))
+    else:
+        assert lev == list(b["sel_level"]) and neg == list(b["sel_neg"])
+        for j in range(d):
+            sc = scales[seg_of[j]]
+            mag = f32(f32(sc * f32(lev[j])) / f32(s)) if qsgd else sc
+            want = f32(0) if lev[j] == 0 else (-mag if neg[j] else mag)
+            assert bits_of(np.array([want]))[0] == bits_of(b["g_val"][j:j + 1])[0], j
+    # decoding, the stand-alone error update and the master line give what the format with indices gives
+    ia, va = with_idx.decode(a["msg"])
+    ib, vb = dense.decode(b["msg"])
+    full = np.zeros(d, f32); full[ia] = va
+    assert np.array_equal(ib, np.arange(d)) and np.array_equal(full, vb)
+    assert np.array_equal(bits_of(dense.error_update(m, delta, b["msg"])), bits_of(b["m_out"]))
+    x0 = rng.standard_normal(d).astype(f32)
+    msgs_a, msgs_b = np.stack([a["msg"], a["msg"]]), np.stack([b["msg"], b["msg"]])
+    assert np.array_equal(with_idx.aggregate(msgs_a, -0.5, out=x0), dense.aggregate(msgs_b, -0.5, out=x0))
+    # the second statement, bit for bit
+    c = OS.compress(m, delta, d, off, k, s, sparsifier, quantizer, 5, 2, 9, dense=True)
+    assert c["bits"] == b["bits"]
+    assert np.array_equal(b["msg"][: c["msg"].size], c["msg"]) and not b["msg"][c["msg"].size:].any()
+    # a segment that does not keep everything cannot use the format
+    with pytest.raises(ValueError):
+        O.OracleOp(d, off, np.array([100, 64, 535, 77], dtype=np.uint32), s, sparsifier, quantizer, 5, dense=True)
