@@ -62,7 +62,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (2 = headline); 6 = the paper's own per-tensor rule on ResNet-50's tensor table")
+    ap.add_argument("--config", type=int, default=2, help="benchmark configuration 1..5 (2 = headline); 6 = the paper's own per-tensor rule on ResNet-50's tensor table; "
+                         "7, 8 = every coordinate kept with index-free messages (EF-signSGD, EF-QSGD as this operator)")
     ap.add_argument("--workers", type=int, default=0,
                     help="override the configuration's R (R = 1 is the deployment shape: one worker per GPU); "
                          "not the headline line")
@@ -171,7 +172,7 @@ def main():
     if not args.no_cpu_baseline:
         from concurrent.futures import ThreadPoolExecutor
         from oracle import oracle as O
-        op = O.OracleOp(wl.d, wl.seg_offset, wl.seg_k, wl.s, wl.sparsifier, wl.quantizer, wl.seed)
+        op = O.OracleOp(wl.d, wl.seg_offset, wl.seg_k, wl.s, wl.sparsifier, wl.quantizer, wl.seed, dense=wl.dense)
         try:
             cores = len(os.sched_getaffinity(0))
         except AttributeError:

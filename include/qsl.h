@@ -39,6 +39,13 @@
  *                                      Sign: the sign bit (1 = negative); no quantiser: the fp32 value
  *                                      (starts on a 32-bit boundary)
  *     zero padding up to the capacity (a multiple of 8 bytes)
+ * Index-free format (QSL_FLAG_DENSE_FORMAT; every coordinate is kept, so entry j is coordinate j):
+ *     u32  d
+ *     f32  scale[num_segments]
+ *     d x w_code bits                  QSGD: the level 0..s in the bits needed to write s, then the sign bit;
+ *                                      Sign: the sign bit; no quantiser: the fp32 value
+ *     zero padding up to the capacity
+ *   payload bits = 32 + 32 num_segments + d w_code.
  * A QSGD coordinate whose level is 0 is not transmitted (Section 5.1.2 observes that the
  * quantiser adds sparsity of its own).  The paper fixes no encoding; this one is the library's choice.
  */
@@ -91,6 +98,10 @@ enum {
                                  instead of the one-block selection (testing, comparison)               */
   QSL_FLAG_NO_WARM_START = 8, /* every call guesses its thresholds from a fresh sample of m + delta, as the first call
                                  does, instead of taking them from the previous call's candidates (testing, comparison) */
+  QSL_FLAG_DENSE_FORMAT = 16, /* only for an operator that keeps every coordinate (k = size in every segment: the
+                                 error-feedback schemes without sparsification that Section 5 compares with): the
+                                 messages have the index-free format described above, and qsl_compress runs as two
+                                 streaming passes                                                        */
   QSL_FLAG_OWN_V = 4          /* the context also allocates a float [max_workers, d] array of its own as the home
                                  of v = m + delta, so that qsl_compress / qsl_compress_diff accept m_out = NULL
                                  ("send g, leave the error memory alone")                               */

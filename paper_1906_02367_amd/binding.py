@@ -20,6 +20,7 @@ FLAG_NO_FAST_PATH = 1
 FLAG_NO_SMALL_PATH = 2
 FLAG_OWN_V = 4
 FLAG_NO_WARM_START = 8
+FLAG_DENSE_FORMAT = 16
 
 OK, ERR_INVALID_ARG, ERR_BUFFER_TOO_SMALL, ERR_NONFINITE_INPUT, ERR_DEVICE, ERR_UNSUPPORTED = range(6)
 
@@ -232,5 +233,7 @@ class Qsl:
 
 
 def from_workload(wl, max_workers=None, flags=0, device=None) -> Qsl:
+    if getattr(wl, "dense", False):
+        flags |= FLAG_DENSE_FORMAT
     return Qsl(wl.d, wl.seg_offset, wl.seg_k, wl.s, wl.sparsifier, wl.quantizer, wl.seed,
                max_workers or wl.R, flags=flags, device=device)

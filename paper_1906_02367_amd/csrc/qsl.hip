@@ -51,6 +51,7 @@
 #include "qsl_encode.h"
 #include "qsl_stream.h"
 #include "qsl_lean.h"
+#include "qsl_dense.h"
 #include "qsl_decode.h"
 
 namespace {
@@ -132,6 +133,7 @@ static qsl_status check_config(const qsl_config* cfg, uint64_t* K_out) {
     K64 += cfg->seg_k[l];
   }
   if (K64 >= (1ull << 32)) return QSL_ERR_INVALID_ARG;
+  if ((cfg->flags & QSL_FLAG_DENSE_FORMAT) && K64 != d) return QSL_ERR_INVALID_ARG;      // every segment must keep everything
   *K_out = K64;
   return QSL_OK;
 }
@@ -154,10 +156,13 @@ static WireDims wire_dims(const qsl_config* cfg, uint64_t K) {
     hint += is_qsgd(cfg->quantizer) ? std::min(kl, 1.25 * w.s * std::sqrt(kl)) : kl;
   }
   w.nnz_hint = static_cast<uint32_t>(std::min<double>(hint, static_cast<double>(K)));
-  w.w_idx = std::max(1u, bit_width_u64(cfg->d - 1));
-  w.w_lev = is_qsgd(cfg->quantizer) ? bit_width_u64(static_cast<uint64_t>(w.s) - 1) : 0;
+  const bool dense = (cfg->flags & QSL_FLAG_DENSE_FORMAT) != 0;
+  w.w_idx = dense ? 0 : std::max(1u, bit_width_u64(cfg->d - 1));
+  // with indices a level 1..s is written as level - 1; without, 0..s as it is
+  w.w_lev = is_qsgd(cfg->quantizer) ? bit_width_u64(static_cast<uint64_t>(w.s) - (dense ? 0 : 1)) : 0;
   w.w_val = cfg->quantizer == QSL_FP32 ? 32 : w.w_lev + 1;
-  const bool counts = is_qsgd(cfg->quantizer) && L > 1;
+  if (dense) w.nnz_hint = static_cast<uint32_t>(K);
+  const bool counts = is_qsgd(cfg->quantizer) && L > 1 && !dense;
   uint64_t bits = 32 + 32ull * L + (counts ? 32ull * L : 0);
   bits += align_up(K * w.w_idx, 32) + align_up(K * w.w_val, 32);
   w.capacity = align_up(bits, 64) / 8;
@@ -251,6 +256,7 @@ static double plan_segment(const qsl_config* cfg, SegInfo& sg) {
       }
     }
   }
+  if (cfg->flags & QSL_FLAG_DENSE_FORMAT) { sg.mode = PATH_FULL; return 0; }   // nothing to select anywhere: two streaming passes
   // too dense to guess, small enough for one block to hold in registers
   if (sg.mode == PATH_GENERAL && sg.size <= BLOCK_MAX && !(cfg->flags & QSL_FLAG_NO_SMALL_PATH)) sg.mode = PATH_SMALL;
   return cand;
@@ -291,7 +297,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const qsl_status cfg_status = check_config(cfg, &K64);
   if (cfg_status != QSL_OK) return cfg_status;
   if (cfg->max_workers == 0 || cfg->max_workers > 1024) return QSL_ERR_INVALID_ARG;
-  if (cfg->flags & ~static_cast<uint32_t>(QSL_FLAG_NO_FAST_PATH | QSL_FLAG_NO_SMALL_PATH | QSL_FLAG_OWN_V | QSL_FLAG_NO_WARM_START)) return QSL_ERR_INVALID_ARG;
+  if (cfg->flags & ~static_cast<uint32_t>(QSL_FLAG_NO_FAST_PATH | QSL_FLAG_NO_SMALL_PATH | QSL_FLAG_OWN_V | QSL_FLAG_NO_WARM_START | QSL_FLAG_DENSE_FORMAT)) return QSL_ERR_INVALID_ARG;
   const uint64_t d = cfg->d;
   const uint32_t L = cfg->num_segments;
 
@@ -494,9 +500,11 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t o_d0k = carve(4ull * std::max<uint64_t>(1, d0_entries) * R);
   const uint64_t o_wc = carve(4ull * NWC * R), o_ws = carve(4ull * NWC * R), o_cbc = carve(8ull * NCB * R);
   const uint64_t o_tlist = carve(16ull * LISTCAP * std::max<size_t>(1, fast.size()) * R);
-  const uint64_t o_si = carve(4ull * K * R), o_sv = carve(4ull * K * R), o_sc = carve(4ull * K * R);
+  const bool dense = (cfg->flags & QSL_FLAG_DENSE_FORMAT) != 0;
+  const uint64_t KA = dense ? 1 : K;                 // the index-free format needs no per-entry arrays
+  const uint64_t o_si = carve(4ull * KA * R), o_sv = carve(4ull * KA * R), o_sc = carve(4ull * KA * R);
   const uint64_t o_pre = carve(4ull * (QB + 1) * R);
-  const uint64_t o_vi = carve(4ull * K * R), o_vc = carve(4ull * K * R);
+  const uint64_t o_vi = carve(4ull * KA * R), o_vc = carve(4ull * KA * R);
   const uint64_t o_tmp = carve(4ull * 1024);
   ctx->agg_ndir = static_cast<uint32_t>(((d + (1u << AGG_DIR_SHIFT) - 1) >> AGG_DIR_SHIFT) + 1);
   const bool want_dir = ctx->nnz_hint >= AGG_DIR_MIN;
@@ -578,7 +586,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->own_v = (cfg->flags & QSL_FLAG_OWN_V) ? reinterpret_cast<float*>(base + o_ownv) : nullptr;
   c.d = d; c.seed = cfg->seed; c.L = L; c.K = K; c.NWT = NWT; c.NSEL = NSEL; c.NCB = NCB; c.NWC = NWC; c.QB = QB;
   c.NSELF = NSELF; c.nfast = static_cast<uint32_t>(fast.size()); c.s = s; c.w_idx = w_idx; c.w_lev = w_lev; c.w_val = w_val;
-  c.sparsifier = cfg->sparsifier; c.quantizer = cfg->quantizer;
+  c.sparsifier = cfg->sparsifier; c.quantizer = cfg->quantizer; c.dense = dense;
   c.cap_words = static_cast<uint32_t>(ctx->capacity / 4);
   ctx->one.start = 0; ctx->one.size = segs[0].size; ctx->one.slot_off = 0; ctx->one.ovf_off = 0;
   ctx->one.lpc = segs[0].lpc; ctx->one.ovf_cap = segs[0].ovf_cap;
@@ -609,6 +617,32 @@ extern "C" qsl_status qsl_set_stream(qsl_ctx* ctx, void* hip_stream) {
 }
 
 extern "C" size_t qsl_msg_capacity_bytes(const qsl_ctx* ctx) { return ctx ? ctx->capacity : 0; }
+
+// An operator that keeps every coordinate, index-free messages: two streaming passes (qsl_dense.h).
+static qsl_status launch_dense(qsl_ctx* ctx, const float* m, const float* delta, const float* xm, float* m_out,
+                               uint32_t worker0, uint32_t R, uint64_t round, uint8_t* msg, uint64_t* msg_bits,
+                               uint32_t* sel_idx, uint16_t* sel_level) {
+  const DevCtx& c = ctx->dc;
+  hipStream_t st = ctx->stream;
+  const uint64_t ntiles = (c.d + DTILE - 1) / DTILE;
+  const dim3 grid(static_cast<uint32_t>(std::min<uint64_t>(ntiles, MAX_DENSE_BLOCKS)), R);
+  const bool timed = ctx->timing != 0;
+  if (timed) {
+    if (ctx->ev_used + 2 > ctx->ev.size()) {
+      for (int i = 0; i < 2; ++i) { hipEvent_t e; QSL_HIP(hipEventCreate(&e)); ctx->ev.push_back(e); }
+    }
+    QSL_HIP(hipEventRecord(ctx->ev[ctx->ev_used], st));
+  }
+  if (xm == nullptr) k_dense_norm<false><<<grid, BLOCK, 0, st>>>(c, m, delta, xm, m_out);
+  else k_dense_norm<true><<<grid, BLOCK, 0, st>>>(c, m, delta, xm, m_out);
+  if (timed) { QSL_HIP(hipEventRecord(ctx->ev[ctx->ev_used + 1], st)); ctx->ev_used += 2; }
+  const uint32_t U = R * c.L;
+  k_dense_scales<<<dim3((U + BLOCK / 64 - 1) / (BLOCK / 64)), BLOCK, 0, st>>>(c, U);
+  const dim3 egrid(static_cast<uint32_t>(std::min<uint64_t>(ntiles, MAX_ENCODE_BLOCKS)), R);
+  k_dense_encode<<<egrid, BLOCK, 0, st>>>(c, m_out, worker0, round, msg, msg_bits, sel_idx, sel_level);
+  QSL_HIP(hipGetLastError());
+  return QSL_OK;
+}
 
 template <int SPARS>
 static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* delta, const float* xm, float* m_out,
@@ -710,6 +744,7 @@ static qsl_status compress_checked(qsl_ctx* ctx, const float* m, const float* de
   if ((reinterpret_cast<uintptr_t>(msg) | reinterpret_cast<uintptr_t>(msg_bits)) & 7) return QSL_ERR_INVALID_ARG;
   if (reinterpret_cast<uintptr_t>(sel_level) & 1) return QSL_ERR_INVALID_ARG;
   ctx->last_R = R;
+  if (ctx->dc.dense) return launch_dense(ctx, m, delta, xm, m_out, worker0, R, round, msg, msg_bits, sel_idx, sel_level);
   if (ctx->cfg.sparsifier == QSL_TOPK)
     return launch_compress<QSL_TOPK>(ctx, m, delta, xm, m_out, worker0, R, round, msg, msg_bits, sel_idx, sel_level);
   return launch_compress<QSL_RANDK>(ctx, m, delta, xm, m_out, worker0, R, round, msg, msg_bits, sel_idx, sel_level);
@@ -757,8 +792,8 @@ static qsl_status make_row_list(const uint32_t* worker_list, uint32_t R, RowList
 static qsl_status launch_aggregate(const DevCtx& c, hipStream_t st, uint32_t nnz_hint, uint32_t* dir, uint32_t ndir,
                                    const uint8_t* msg, const RowList& rows, uint32_t R, float scale, int accumulate,
                                    float* out) {
-  if (c.K == c.d && !is_qsgd(c.quantizer)) {        // k = d and nothing dropped: every message lists every coordinate
-    const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((c.d + BLOCK - 1) / BLOCK, 1u << 16));
+  if (c.K == c.d && (c.dense || !is_qsgd(c.quantizer))) {   // k = d and nothing dropped: every message lists every coordinate
+    const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((c.d / 4 + BLOCK) / BLOCK, 1u << 16));
     k_aggregate_dense<<<dim3(blocks), BLOCK, 0, st>>>(c, msg, rows, R, scale, accumulate, out);
     QSL_HIP(hipGetLastError());
     return QSL_OK;
@@ -869,7 +904,7 @@ extern "C" qsl_status qsl_bits_sent(qsl_ctx* ctx, const uint8_t* msg, uint32_t R
   std::vector<uint32_t> nnz(R);
   QSL_HIP(hipMemcpyAsync(nnz.data(), ctx->d_nnz_tmp, 4ull * R, hipMemcpyDeviceToHost, ctx->stream));
   QSL_HIP(hipStreamSynchronize(ctx->stream));
-  const bool counts = is_qsgd(c.quantizer) && c.L > 1;
+  const bool counts = is_qsgd(c.quantizer) && c.L > 1 && !c.dense;
   const uint64_t hdr = 32 + 32ull * c.L + (counts ? 32ull * c.L : 0);
   for (uint32_t r = 0; r < R; ++r) bits_host[r] = hdr + static_cast<uint64_t>(nnz[r]) * (c.w_idx + c.w_val);
   return QSL_OK;

@@ -19,19 +19,22 @@ __device__ __forceinline__ MsgView view_msg(const DevCtx& c, const uint8_t* msg,
   MsgView v;
   v.words = reinterpret_cast<const uint32_t*>(msg + static_cast<uint64_t>(row) * c.cap_words * 4);
   v.nnz = min(v.words[0], c.K);                         // a well-formed message never holds more than K entries
-  const bool counts = is_qsgd(c.quantizer) && c.L > 1;
+  const bool counts = is_qsgd(c.quantizer) && c.L > 1 && !c.dense;
   const uint64_t hdr = 1 + static_cast<uint64_t>(c.L) + (counts ? c.L : 0);
   v.idx_bit0 = hdr * 32;
   v.code_bit0 = (hdr + (static_cast<uint64_t>(v.nnz) * c.w_idx + 31) / 32) * 32;
   return v;
 }
 __device__ __forceinline__ uint32_t msg_index(const DevCtx& c, const MsgView& v, uint32_t j) {
+  if (c.dense) return j;                                 // the index-free format: entry j is coordinate j
   return get_bits(v.words, v.idx_bit0 + static_cast<uint64_t>(j) * c.w_idx, c.w_idx);
 }
 // the value a code field stands for, given the scale its segment transmitted
 __device__ __forceinline__ float value_of_code(const DevCtx& c, uint32_t code, float scale) {
   if (is_qsgd(c.quantizer)) {
-    const uint32_t level = (code & ((1u << c.w_lev) - 1u)) + 1u;
+    // with indices only the levels 1..s are transmitted, as level - 1; the index-free format writes 0..s as they are
+    const uint32_t level = (code & ((1u << c.w_lev) - 1u)) + (c.dense ? 0u : 1u);
+    if (level == 0) return 0.0f;
     return qsgd_value(scale, level, c.s, (code >> c.w_lev) & 1u);
   }
   if (c.quantizer == QSL_FP32) return __uint_as_float(code);
@@ -306,22 +309,55 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate_entries(DevCtx c, const uin
 __global__ __launch_bounds__(BLOCK) void k_aggregate_dense(DevCtx c, const uint8_t* msg, RowList rows, uint32_t R,
                                                            float scale, int accumulate, float* out) {
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * BLOCK;
-  for (uint64_t j = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x; j < c.d; j += stride) {
-    float acc = 0.0f;
+  const uint64_t n4 = (c.d + 3) / 4;                       // a thread takes four consecutive coordinates at a time
+  const bool counts = is_qsgd(c.quantizer) && c.L > 1 && !c.dense;
+  const uint64_t hdr = 1 + static_cast<uint64_t>(c.L) + (counts ? c.L : 0);
+  const uint64_t code_bit0 = (hdr + (c.d * c.w_idx + 31) / 32) * 32;      // of a message that holds all d entries
+  for (uint64_t g = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x; g < n4; g += stride) {
+    const uint64_t j0 = g * 4;
+    const uint32_t nj = static_cast<uint32_t>(min<uint64_t>(4, c.d - j0));
+    uint32_t seg[4] = {0u, 0u, 0u, 0u};
+    if (c.L > 1) {
+      seg[0] = seg_of_coord(c, static_cast<uint32_t>(j0));
+      seg[3] = seg_of_coord(c, static_cast<uint32_t>(j0 + nj - 1));
+      seg[1] = seg[2] = seg[0];
+      if (seg[3] != seg[0]) {
+        seg[1] = nj > 1 ? seg_of_coord(c, static_cast<uint32_t>(j0 + 1)) : seg[0];
+        seg[2] = nj > 2 ? seg_of_coord(c, static_cast<uint32_t>(j0 + 2)) : seg[0];
+      }
+    }
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
     bool first = true;
     for (uint32_t p = 0; p < R; ++p) {
-      const MsgView v = view_msg(c, msg, rows.row[p]);
-      if (v.nnz != c.d) {
-        if (v.nnz != 0 && j == 0) atomicOr(c.status, 4u);
+      const uint32_t* words = reinterpret_cast<const uint32_t*>(msg + static_cast<uint64_t>(rows.row[p]) * c.cap_words * 4);
+      const uint32_t nnz = words[0];
+      if (nnz != c.d) {
+        if (nnz != 0 && g == 0) atomicOr(c.status, 4u);
         continue;
       }
-      const float val = msg_value(c, v, static_cast<uint32_t>(j), static_cast<uint32_t>(j));
-      acc = first ? val : acc + val;
+#pragma unroll
+      for (uint32_t jj = 0; jj < 4; ++jj) {
+        if (jj < nj) {
+          const uint32_t code = get_bits(words, code_bit0 + (j0 + jj) * c.w_val, c.w_val);
+          const float val = value_of_code(c, code, __uint_as_float(words[1 + seg[jj]]));
+          acc[jj] = first ? val : acc[jj] + val;
+        }
+      }
       first = false;
     }
-    const float term = scale * acc;
-    if (!first) out[j] = accumulate ? out[j] + term : term;
-    else if (!accumulate) out[j] = 0.0f;
+    f4u o = {0.f, 0.f, 0.f, 0.f};
+    if (accumulate) {
+      if (nj == 4) o = *reinterpret_cast<const f4u*>(out + j0);
+      else for (uint32_t jj = 0; jj < nj; ++jj) o[jj] = out[j0 + jj];
+    }
+    if (first && accumulate) continue;                     // no message had anything to add
+#pragma unroll
+    for (uint32_t jj = 0; jj < 4; ++jj) {
+      const float term = scale * acc[jj];
+      o[jj] = first ? 0.0f : accumulate ? o[jj] + term : term;
+    }
+    if (nj == 4) *reinterpret_cast<f4u*>(out + j0) = o;
+    else for (uint32_t jj = 0; jj < nj; ++jj) out[j0 + jj] = o[jj];
   }
 }
 

@@ -1,0 +1,273 @@
+// qsl_dense.h -- An operator that keeps every coordinate (k = size in every segment: the error-feedback schemes
+// without sparsification that Section 5 compares with, as this operator) with the index-free message format: two
+// streaming passes and nothing per entry in between.
+//   k_dense_norm    v = m + Delta (Algorithm 1, first worker line) written over the error memory, 12 bytes per
+//                   coordinate, with the exact digits of every segment's norm added up on the way
+//   k_dense_scales  one wave per unit: digits -> fp32 scale (||v||_2 for QSGD, ||v||_1 / k or ||v||_2 / k for Sign)
+//   k_dense_encode  reads v, writes m' = v - g (second worker line) and the packed codes, 8 bytes per coordinate:
+//                   a block owns 4096 consecutive coordinates and with them whole 32-bit words of the code stream
+// Part of the single translation unit qsl.hip (included after qsl_encode.h); not a public header.
+#pragma once
+
+#include "qsl_device.h"
+#include "qsl_layout.h"
+#include "qsl_select.h"
+#include "qsl_encode.h"
+
+namespace {
+
+constexpr uint32_t DTILE = 4096;             // coordinates per tile: 256 threads x 4 x dwordx4
+constexpr uint32_t MAX_DENSE_BLOCKS = 1024;  // blocks per worker of the first pass (each a contiguous range of tiles; each ends with atomics on a unit's counters)
+constexpr uint32_t MAX_ENCODE_BLOCKS = 8192; // ... and of the second, which has no such ending
+
+// digits of |v| (or v^2) straight into a unit's counters in memory (for the few tiles that span several segments)
+__device__ __forceinline__ void add_digits_global(uint64_t* acc, uint32_t bits, bool squares) {
+  const uint32_t ab = bits & 0x7FFFFFFFu;
+  const uint32_t ex = ab >> 23, frac = ab & 0x7FFFFFu;
+  const uint32_t M = ex ? (frac | 0x800000u) : frac;
+  const uint32_t e1 = ex ? ex : 1u;
+  if (M == 0) return;
+  auto add = [&](uint32_t q, uint64_t x) { if (x) atomicAdd(reinterpret_cast<unsigned long long*>(acc + q), static_cast<unsigned long long>(x)); };
+  if (squares) {
+    const uint64_t sq = static_cast<uint64_t>(M) * M;
+    const uint32_t p = 2u * e1 - 2u, q = p >> 5, r = p & 31u;
+    const uint64_t lo = sq << r, hi = r ? (sq >> (64 - r)) : 0;
+    add(q, lo & 0xFFFFFFFFu); add(q + 1, lo >> 32); add(q + 2, hi);
+  } else {
+    const uint32_t p = e1 - 1u, q = p >> 5, r = p & 31u;
+    const uint64_t sh = static_cast<uint64_t>(M) << r;
+    add(q, sh & 0xFFFFFFFFu); add(q + 1, sh >> 32);
+  }
+}
+
+// the tiles [t_lo, t_hi) of block b out of nb
+__device__ __forceinline__ void dense_range(uint64_t d, uint32_t b, uint32_t nb, uint64_t* t_lo, uint64_t* t_hi) {
+  const uint64_t ntiles = (d + DTILE - 1) / DTILE;
+  *t_lo = ntiles * b / nb; *t_hi = ntiles * (b + 1) / nb;
+}
+
+// With `xm` given, `delta` holds the local models and Delta = xm - delta is formed on the fly (as in k_stream).
+template <bool DIFF>
+__global__ __launch_bounds__(BLOCK) void k_dense_norm(DevCtx c, const float* m, const float* delta, const float* xm,
+                                                      float* m_out) {
+  __shared__ uint64_t acc[ACC_ROWS * (ACC_SLOTS + 1)];
+  const uint32_t w = blockIdx.y, wave = threadIdx.x >> 6, lane = lane_id();
+  const bool squares = wants_squares(c.quantizer), need_norm = c.quantizer != QSL_FP32;
+  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
+  for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;
+  __syncthreads();
+  const uint64_t row = static_cast<uint64_t>(w) * c.d;
+  uint64_t t_lo, t_hi;
+  dense_range(c.d, blockIdx.x, gridDim.x, &t_lo, &t_hi);
+  uint32_t cur = 0xFFFFFFFFu;                       // the segment whose digits the block's rows hold
+  bool nonfinite = false;
+  // the rows into the segment's counters, then zero again (uniform over the block)
+  auto flush = [&]() {
+    __syncthreads();
+    if (cur != 0xFFFFFFFFu) {
+      uint64_t* ga = c.norm_acc + (static_cast<uint64_t>(w) * c.L + cur) * ACC_SLOTS;
+      for (uint32_t s = wave; s < ACC_SLOTS; s += BLOCK / 64) {
+        uint64_t x = lane < ACC_ROWS ? acc[lane * (ACC_SLOTS + 1) + s] : 0;
+        x = wave_sum64(x);
+        if (lane == 0 && x) atomicAdd(reinterpret_cast<unsigned long long*>(ga + s), static_cast<unsigned long long>(x));
+      }
+      __syncthreads();
+      for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;
+      __syncthreads();
+    }
+  };
+  for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
+    const uint64_t base = tile * DTILE;
+    f4u v[4];
+    // one group of four at a time: with all loads of a tile issued first the pass was slower (186 us against 150 us
+    // for 2 x 25.6 M coordinates), and so it was with more, smaller blocks (their atomics on the unit's counters)
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {
+      const uint64_t e = base + q * 1024 + threadIdx.x * 4;
+      v[q] = f4u{0.f, 0.f, 0.f, 0.f};
+      if (e + 4 <= c.d) {
+        const f4u a = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(m + row + e));
+        f4u b = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(delta + row + e));
+        if (DIFF) b = *reinterpret_cast<const f4u*>(xm + e) - b;
+        v[q] = a + b;
+        __builtin_nontemporal_store(v[q], reinterpret_cast<f4u*>(m_out + row + e));
+      } else {
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j)
+          if (e + j < c.d) {
+            const float dl = DIFF ? xm[e + j] - delta[row + e + j] : delta[row + e + j];
+            v[q][j] = m[row + e + j] + dl;
+            m_out[row + e + j] = v[q][j];
+          }
+      }
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) nonfinite |= (__float_as_uint(v[q][j]) & 0x7FFFFFFFu) >= 0x7F800000u;
+    }
+    if (!need_norm) continue;
+    const uint64_t last = min(base + DTILE, c.d) - 1;
+    const uint32_t seg_first = c.L == 1 ? 0u : seg_of_coord(c, static_cast<uint32_t>(base));
+    const uint32_t seg_last = c.L == 1 ? 0u : seg_of_coord(c, static_cast<uint32_t>(last));
+    if (seg_first == seg_last) {
+      if (seg_first != cur) { flush(); cur = seg_first; }
+#pragma unroll
+      for (uint32_t q = 0; q < 4; ++q) {
+        const uint64_t e = base + q * 1024 + threadIdx.x * 4;
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) if (e + j < c.d) add_digits(mine, __float_as_uint(v[q][j]), squares);
+      }
+    } else {                                          // several segments in one tile: each coordinate to its own unit's counters
+      flush(); cur = 0xFFFFFFFFu;
+#pragma unroll
+      for (uint32_t q = 0; q < 4; ++q) {
+        const uint64_t e = base + q * 1024 + threadIdx.x * 4;
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j)
+          if (e + j < c.d) {
+            const uint32_t seg = seg_of_coord(c, static_cast<uint32_t>(e + j));
+            add_digits_global(c.norm_acc + (static_cast<uint64_t>(w) * c.L + seg) * ACC_SLOTS, __float_as_uint(v[q][j]), squares);
+          }
+      }
+    }
+  }
+  flush();
+  if (__ballot(nonfinite) != 0 && lane == 0) atomicOr(c.status, 1u);
+}
+
+// one wave per unit: the scale the codes are computed with and the scale the message carries; the digit counters
+// are returned to zero for the next call
+__global__ __launch_bounds__(BLOCK) void k_dense_scales(DevCtx c, uint32_t U) {
+  const uint32_t u = blockIdx.x * (BLOCK / 64) + (threadIdx.x >> 6);
+  if (u >= U) return;
+  const uint32_t seg = u % c.L, lane = lane_id();
+  const uint32_t kl = c.segs[seg].k;
+  const float sc = finalize_scale(c.norm_acc + static_cast<uint64_t>(u) * ACC_SLOTS, c.quantizer, kl);
+  if (lane < ACC_SLOTS) c.norm_acc[static_cast<uint64_t>(u) * ACC_SLOTS + lane] = 0;
+  if (lane == 0) {
+    const UnitScale us = unit_scale(c, sc, kl);
+    c.units[u].scale_code = __float_as_uint(us.scale);
+    c.units[u].scale_bits = __float_as_uint(us.sent);
+    c.units[u].cand = 0; c.units[u].fell_back = 0; c.units[u].tau = 0; c.units[u].need = 0; c.units[u].n_gt = kl; c.units[u].nnz = kl;
+  }
+}
+
+__global__ __launch_bounds__(BLOCK) void k_dense_encode(DevCtx c, float* m_out, uint32_t worker0, uint64_t round, uint8_t* msg,
+                                                        uint64_t* msg_bits, uint32_t* dbg_idx, uint16_t* dbg_level) {
+  __shared__ uint32_t s_bits[(DTILE / 32) * 32];        // the tile's part of the code stream: 128 words per bit of code width
+  const uint32_t w = blockIdx.y;
+  const uint32_t wv = c.w_val;
+  uint32_t* words = reinterpret_cast<uint32_t*>(msg + static_cast<uint64_t>(w) * c.cap_words * 4);
+  const uint64_t hdr = 1 + static_cast<uint64_t>(c.L);
+  const uint64_t code_words = (c.d * wv + 31) / 32;
+  if (blockIdx.x == 0) {                               // header: the length word, the scales; the payload bit count
+    for (uint64_t i = threadIdx.x; i < hdr; i += BLOCK)
+      words[i] = i == 0 ? static_cast<uint32_t>(c.d) : c.units[static_cast<uint64_t>(w) * c.L + (i - 1)].scale_bits;
+    if (threadIdx.x == 0 && msg_bits) msg_bits[w] = hdr * 32 + c.d * wv;
+  }
+  if (blockIdx.x == gridDim.x - 1)                     // zero padding up to the capacity
+    for (uint64_t i = hdr + code_words + threadIdx.x; i < c.cap_words; i += BLOCK) words[i] = 0;
+  const uint64_t row = static_cast<uint64_t>(w) * c.d;
+  const RandKey rk1 = make_rand_key(c.seed, worker0 + w, round, 1);
+  uint64_t t_lo, t_hi;
+  dense_range(c.d, blockIdx.x, gridDim.x, &t_lo, &t_hi);
+  uint32_t cur = 0xFFFFFFFFu;
+  float cur_scale = 0.f, cur_sent = 0.f;
+  for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
+    const uint64_t base = tile * DTILE;
+    const uint64_t last = min(base + DTILE, c.d) - 1;
+    const uint32_t seg_first = c.L == 1 ? 0u : seg_of_coord(c, static_cast<uint32_t>(base));
+    const uint32_t seg_last = c.L == 1 ? 0u : seg_of_coord(c, static_cast<uint32_t>(last));
+    const bool one_seg = seg_first == seg_last;
+    if (one_seg && seg_first != cur) {
+      cur = seg_first;
+      const UnitState& us = c.units[static_cast<uint64_t>(w) * c.L + cur];
+      cur_scale = __uint_as_float(us.scale_code); cur_sent = __uint_as_float(us.scale_bits);
+    }
+    for (uint32_t i = threadIdx.x; i < (DTILE / 32) * wv; i += BLOCK) s_bits[i] = 0;
+    __syncthreads();
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {
+      const uint32_t le = q * 1024 + threadIdx.x * 4;           // inside the tile
+      const uint64_t e = base + le;
+      if (e >= c.d) continue;
+      f4u x = {0.f, 0.f, 0.f, 0.f};
+      const bool whole = e + 4 <= c.d;
+      if (whole) x = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(m_out + row + e));
+      else {
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) if (e + j < c.d) x[j] = m_out[row + e + j];
+      }
+      Words4 rw = {{0u, 0u, 0u, 0u}};
+      if (is_qsgd(c.quantizer)) rw = rand_words4(rk1, static_cast<uint32_t>(e));     // e is a multiple of 4: one block
+      f4u res = x;
+      uint32_t code[4];
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) {
+        float scale = cur_scale, sent_scale = cur_sent;
+        if (!one_seg && e + j < c.d) {
+          const UnitState& us = c.units[static_cast<uint64_t>(w) * c.L + seg_of_coord(c, static_cast<uint32_t>(e + j))];
+          scale = __uint_as_float(us.scale_code); sent_scale = __uint_as_float(us.scale_bits);
+        }
+        const float v = x[j];
+        const bool neg = v < 0.0f;
+        uint32_t level = 1;
+        float g;
+        if (is_qsgd(c.quantizer)) {                      // Definition 1, example 1: the same single IEEE operations as encode_entry
+          level = 0;
+          if (scale > 0.0f) {
+            const float a = fabsf(v) / scale;
+            float t = a * static_cast<float>(c.s);
+            if (t > static_cast<float>(c.s)) t = static_cast<float>(c.s);
+            const float fl = floorf(t);
+            const float frac = t - fl;
+            const float r01 = static_cast<float>(rw.w[j] >> 8) * 0x1p-24f;
+            level = static_cast<uint32_t>(fl) + (r01 < frac ? 1u : 0u);
+          }
+          g = qsgd_value(sent_scale, level, c.s, neg);
+          code[j] = level | (static_cast<uint32_t>(neg) << c.w_lev);
+        } else if (c.quantizer == QSL_FP32) {
+          g = v; code[j] = __float_as_uint(v);
+        } else {                                         // Definition 2
+          g = neg ? -scale : scale; code[j] = neg;
+        }
+        if (level != 0) res[j] = v - g;                  // Algorithm 1, second worker line
+        if (e + j < c.d) {
+          if (dbg_idx) dbg_idx[static_cast<uint64_t>(w) * c.K + e + j] = static_cast<uint32_t>(e + j);
+          if (dbg_level) dbg_level[static_cast<uint64_t>(w) * c.K + e + j] = static_cast<uint16_t>(level);
+        } else code[j] = 0;
+      }
+      if (whole) __builtin_nontemporal_store(res, reinterpret_cast<f4u*>(m_out + row + e));
+      else {
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) if (e + j < c.d) m_out[row + e + j] = res[j];
+      }
+      // the four codes into the tile's bit buffer
+      if (wv == 32) {
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) s_bits[le + j] = code[j];
+      } else if (wv <= 16) {
+        const uint64_t val = static_cast<uint64_t>(code[0]) | (static_cast<uint64_t>(code[1]) << wv) |
+                             (static_cast<uint64_t>(code[2]) << (2 * wv)) | (static_cast<uint64_t>(code[3]) << (3 * wv));
+        const uint32_t o = le * wv, word = o >> 5, sh = o & 31u;
+        const uint64_t lo = val << sh;
+        if (static_cast<uint32_t>(lo)) atomicOr(&s_bits[word], static_cast<uint32_t>(lo));
+        if (lo >> 32) atomicOr(&s_bits[word + 1], static_cast<uint32_t>(lo >> 32));
+        if (sh && (val >> (64 - sh))) atomicOr(&s_bits[word + 2], static_cast<uint32_t>(val >> (64 - sh)));
+      } else {
+#pragma unroll
+        for (uint32_t j = 0; j < 4; ++j) {
+          const uint32_t o = (le + j) * wv, word = o >> 5, sh = o & 31u;
+          const uint64_t lo = static_cast<uint64_t>(code[j]) << sh;
+          if (static_cast<uint32_t>(lo)) atomicOr(&s_bits[word], static_cast<uint32_t>(lo));
+          if (lo >> 32) atomicOr(&s_bits[word + 1], static_cast<uint32_t>(lo >> 32));
+        }
+      }
+    }
+    __syncthreads();
+    const uint64_t w0 = tile * (DTILE / 32) * wv;        // the tile's first word of the code stream
+    for (uint32_t i = threadIdx.x; i < (DTILE / 32) * wv; i += BLOCK)
+      if (w0 + i < code_words) words[hdr + w0 + i] = s_bits[i];
+    __syncthreads();
+  }
+}
+
+}  // namespace

@@ -83,7 +83,8 @@ struct UnitState {
   uint32_t prefix2, k_rem2; // ... and after the second (k_select<2>); the third is found by k_tile_count
   uint32_t tau, need, n_gt; // threshold key, how many equal to it are kept, how many above (k_tile_count)
   uint32_t nnz;         // transmitted coordinates (zeroed by k_select<0>, counted by k_quantize)
-  uint32_t scale_bits;  // fp32 scale (k_quantize, k_lean_emit)
+  uint32_t scale_bits;  // fp32 scale that the message carries (k_quantize, k_lean_emit, ...)
+  uint32_t scale_code;  // index-free format only: the scale the codes are computed with (k_dense_scales)
 };
 
 struct DevCtx {
@@ -117,6 +118,7 @@ struct DevCtx {
   uint32_t* surv_idx; uint32_t* surv_code;                    // [R][K]
   uint32_t* status;
   uint64_t d, seed;
+  uint32_t dense;       // 1: every coordinate is kept and the messages have the index-free format
   uint32_t L, K, NWT, NSEL, NCB, NWC, QB, NSELF, nfast, nblock, Rmax, nbig, s, w_idx, w_lev, w_val, sparsifier, quantizer, cap_words;
 };
 

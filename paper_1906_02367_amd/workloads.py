@@ -37,6 +37,7 @@ class Workload:
     quantizer: int
     rounds: int
     seed: int = BASE_SEED    # seed handed to the operator (Rand_k / QSGD randomness)
+    dense: bool = False      # every coordinate kept and index-free messages (the comparison schemes without sparsification)
 
     @property
     def L(self) -> int:
@@ -132,8 +133,16 @@ def config(cfg: int, d: int | None = None, R: int | None = None, rounds: int | N
         off[1:] = np.cumsum(sizes).astype(np.uint64)
         k = np.minimum(sizes, 1000).astype(np.uint32)
         wl = Workload(4, "cfg6_resnet50_k_min_d_1000_sign", R or 8, RESNET50_D, off, k, 1, TOPK, SIGN_L1, rounds or 20)
+    elif cfg in (7, 8):
+        # the comparison schemes of Section 5 without sparsification, as this operator: every coordinate kept (k = d),
+        # error feedback, index-free messages; 7: the sign of the whole vector scaled by its l1 norm / d (EF-signSGD),
+        # 8: 4-bit QSGD, s = 15 (EF-QSGD).  Inputs as for configuration 2.
+        dd = d or RESNET50_D
+        off, k = _one_segment(dd, dd)
+        wl = Workload(2, "cfg7_ef_sign_dense" if cfg == 7 else "cfg8_ef_qsgd15_dense", R or 2, dd, off, k, 1 if cfg == 7 else 15,
+                      TOPK, SIGN_L1 if cfg == 7 else QSGD, rounds or 10, dense=True)
     else:
-        raise ValueError("cfg must be 1..6")
+        raise ValueError("cfg must be 1..8")
     return wl
 
 
