@@ -179,7 +179,8 @@ qsl_status qsl_aggregate(qsl_ctx *ctx, const uint8_t *msg, const uint32_t *worke
  *                device memory); seed, max_workers and flags are ignored
  *   hip_stream   the stream to enqueue on (NULL = the default stream)
  *   msg, worker_list, R, scale, accumulate, out   as for qsl_aggregate
- * QSL_ERR_UNSUPPORTED if num_segments > 1 or if R * (ceil(d / 1024) + 1) * 4 + 256 bytes exceed the array;
+ * QSL_ERR_UNSUPPORTED if num_segments > 1 or if rows * (ceil(d / 1024) + 1) * 4 + 256 bytes exceed the array, where
+ * rows = 65 when the kernels for many messages are used (R >= 56, or R >= 24 with long messages), else R;
  * QSL_ERR_DEVICE if the device's ordinal is 64 or more.  Entries with an index >= d are skipped silently.
  * All calls on one GPU share the array: calls that overlap on one GPU (two streams, two threads) race.  */
 #define QSL_STATIC_SCRATCH_BYTES (8u << 20)

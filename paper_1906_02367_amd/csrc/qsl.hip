@@ -507,8 +507,8 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t o_vi = carve(4ull * KA * R), o_vc = carve(4ull * KA * R);
   const uint64_t o_tmp = carve(4ull * 1024);
   ctx->agg_ndir = static_cast<uint32_t>(((d + (1u << AGG_DIR_SHIFT) - 1) >> AGG_DIR_SHIFT) + 1);
-  const bool want_dir = ctx->nnz_hint >= AGG_DIR_MIN;
-  const uint64_t o_dir = carve(want_dir ? 4ull * 64 * ctx->agg_ndir : 4);
+  const bool want_dir = true;                       // (6.4 MB for 25.6 M coordinates)
+  const uint64_t o_dir = carve(4ull * 65 * ctx->agg_ndir);       // 64 directories and the list of crowded ranges
   const uint64_t o_ownv = carve((cfg->flags & QSL_FLAG_OWN_V) ? 4ull * R * d : 4);
   if (hipMalloc(&ctx->slab, bytes) != hipSuccess) { ctx->slab = nullptr; free_ctx(ctx); return QSL_ERR_DEVICE; }
   char* base = static_cast<char*>(ctx->slab);
@@ -802,9 +802,19 @@ static qsl_status launch_aggregate(const DevCtx& c, hipStream_t st, uint32_t nnz
     const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((c.d + BLOCK * 4 - 1) / (BLOCK * 4), 1u << 16));
     k_fill_zero<<<dim3(blocks), BLOCK, 0, st>>>(out, c.d);
   }
-  if (R == 1) dir = nullptr;
+  const bool by_ranges = R >= AGG_RANGES_MIN_R || (R >= AGG_RANGES_MIN_R_LONG && nnz_hint >= AGG_DIR_MIN);
+  if (dir && by_ranges) {                           // many messages: a wave per 1024 coordinates, work linear in the entries
+    uint32_t* dense_list = dir + 64ull * ndir;      // behind the 64 directories: a counter and up to ndir - 1 ranges
+    k_msg_directory<<<dim3(std::min(2048u, (c.K + BLOCK - 1) / BLOCK), R), BLOCK, 0, st>>>(c, msg, rows, dir, ndir, dense_list);
+    k_aggregate_ranges<<<dim3(ndir - 1), 64, 0, st>>>(c, msg, rows, R, scale, accumulate, out, dir, ndir, dense_list);
+    k_aggregate_dense_ranges<<<dim3(std::min(AGG_DENSE_BLOCKS, ndir - 1)), 1024, 0, st>>>(c, msg, rows, R, scale, accumulate, out, dir,
+                                                                                        ndir, dense_list);
+    QSL_HIP(hipGetLastError());
+    return QSL_OK;
+  }
+  if (R == 1 || nnz_hint < AGG_DIR_MIN) dir = nullptr;   // short messages are searched whole
   if (dir) {                                        // long messages: a thread per entry, searches narrowed by the directories
-    k_msg_directory<<<dim3(std::min(2048u, (c.K + BLOCK - 1) / BLOCK), R), BLOCK, 0, st>>>(c, msg, rows, dir, ndir);
+    k_msg_directory<<<dim3(std::min(2048u, (c.K + BLOCK - 1) / BLOCK), R), BLOCK, 0, st>>>(c, msg, rows, dir, ndir, nullptr);
     const uint32_t eb = std::min((c.K + BLOCK - 1) / BLOCK, std::max(4u, (nnz_hint + BLOCK - 1) / BLOCK));
     k_aggregate_entries<<<dim3(eb, R), BLOCK, 0, st>>>(c, msg, rows, R, scale, accumulate, out, dir, ndir);
   } else {                                          // short messages: 8 threads per entry, a block per expected tile of 32
@@ -875,8 +885,11 @@ extern "C" qsl_status qsl_aggregate_static(const qsl_config* cfg, void* hip_stre
   const WireDims wd = wire_dims(cfg, K64);
   if (wd.capacity / 4 > 0xFFFFFFFFull) return QSL_ERR_UNSUPPORTED;
   const uint32_t ndir = static_cast<uint32_t>(((cfg->d + (1u << AGG_DIR_SHIFT) - 1) >> AGG_DIR_SHIFT) + 1);
-  const bool want_dir = wd.nnz_hint >= AGG_DIR_MIN && R > 1;   // as qsl_create decides it
-  if (want_dir && STATIC_DIR_OFFSET + 4ull * R * ndir > QSL_STATIC_SCRATCH_BYTES) return QSL_ERR_UNSUPPORTED;
+  const bool by_ranges = R >= AGG_RANGES_MIN_R || (R >= AGG_RANGES_MIN_R_LONG && wd.nnz_hint >= AGG_DIR_MIN);
+  const bool want_dir = R > 1 && (wd.nnz_hint >= AGG_DIR_MIN || by_ranges);   // as launch_aggregate uses them
+  // (the kernels for many messages keep a list of up to ndir ranges behind 64 directories)
+  const uint64_t dir_rows = by_ranges ? 65 : R;
+  if (want_dir && STATIC_DIR_OFFSET + 4ull * dir_rows * ndir > QSL_STATIC_SCRATCH_BYTES) return QSL_ERR_UNSUPPORTED;
   unsigned char* base = nullptr;
   st = static_scratch(&base);
   if (st != QSL_OK) return st;

@@ -103,7 +103,11 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(3, 3))) v
 struct RowList { uint32_t row[64]; };
 constexpr uint32_t AGG_ENTRIES = 32;     // message entries per block; 8 threads look one entry up in parallel
 constexpr uint32_t AGG_DIR_SHIFT = 10;   // a directory entry per 1024 coordinates
-constexpr uint32_t AGG_DIR_MIN = 4096;   // messages expected to be at least this long get a directory
+constexpr uint32_t AGG_DIR_MIN = 4096;   // messages expected to be at least this long are searched through their directories
+// k_aggregate_ranges takes over from 24 listed messages on when they are long, from 56 on in any case (measured, 8 workers'
+// messages repeated: 99,400 entries each: 15 / 32 / 64 messages 138 / 442 / 1480 us by look-ups, 170 / 277 / 473 us by
+// ranges; ~1,600 entries each: 14 / 31 / 105 us against 44 / 64 / 93 us)
+constexpr uint32_t AGG_RANGES_MIN_R_LONG = 24, AGG_RANGES_MIN_R = 56;
 
 // Directory of a long message: dir[t] = number of entries whose coordinate lies below t * 1024, for
 // t = 0 .. ndir - 1 (ndir = ceil(d / 1024) + 1, so dir[ndir - 1] = nnz).  Entry j fills the slots between
@@ -111,10 +115,11 @@ constexpr uint32_t AGG_DIR_MIN = 4096;   // messages expected to be at least thi
 // dir[t], dir[t + 1] and a binary search over the few entries of one 1024-block instead of log2(nnz)
 // dependent probes of the whole message.
 __global__ __launch_bounds__(BLOCK) void k_msg_directory(DevCtx c, const uint8_t* msg, RowList rows, uint32_t* dir,
-                                                         uint32_t ndir) {
+                                                         uint32_t ndir, uint32_t* dense_list) {
   const uint32_t q = blockIdx.y;
   const MsgView v = view_msg(c, msg, rows.row[q]);
   uint32_t* mine = dir + static_cast<uint64_t>(q) * ndir;
+  if (dense_list && q == 0 && blockIdx.x == 0 && threadIdx.x == 0) dense_list[0] = 0;    // the list k_aggregate_ranges fills
   const uint32_t nth = gridDim.x * BLOCK, tid = blockIdx.x * BLOCK + threadIdx.x;
   if (v.nnz == 0) { for (uint32_t t = tid; t < ndir; t += nth) mine[t] = 0; return; }
   for (uint32_t j = tid; j < v.nnz; j += nth) {
@@ -299,6 +304,166 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate_entries(DevCtx c, const uin
     if (owned) continue;
     const float term = scale * acc;
     out[idx] = accumulate ? out[idx] + term : term;
+  }
+}
+
+// Many messages: work linear in the number of entries.  A wave owns 1024 consecutive coordinates (one cell of the
+// directories): lane p knows where listed message p's entries of that range begin and end; the entries of as many
+// messages as the staging list holds are decoded side by side into LDS, then added into an LDS image of the range
+// message after message, in list order -- the entries of one message have distinct coordinates, so the additions of
+// one message do not meet, and the order of the fp32 additions is that of k_aggregate.  No look-ups in other
+// messages: the cost of the kernels above grows with the square of the number of messages (8, 15, 32, 64 messages
+// of 99,400 entries: 55, 138, 442, 1480 us), this one's with their number.  A range that holds more than 4096
+// entries in all (segments kept whole: every message has every coordinate) would keep one wave busy for long, so
+// the waves only list such ranges and a second launch gives each of them a block of 1024 threads.
+constexpr uint32_t AGG_RANGE = 1u << AGG_DIR_SHIFT;      // coordinates per range
+constexpr uint32_t AGG_DENSE_MIN = 4096;                 // entries in a range from which a whole block takes it
+constexpr uint32_t AGG_DENSE_BLOCKS = 512;
+
+template <uint32_t NT>
+__device__ __forceinline__ void range_barrier() {
+  if (NT == WAVE) {                                      // one wave, lanes in lockstep: order the LDS traffic only
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  } else __syncthreads();
+}
+
+// One range by NT threads (NT = 64: a wave; else a block).  STAGE: entries the staging list holds (>= 1024, so that one
+// message's share of a range fits).  Returns false, having done nothing, if LIST and the range holds AGG_DENSE_MIN
+// entries or more (uniform over the threads).
+template <uint32_t NT, uint32_t STAGE, bool LIST>
+__device__ bool aggregate_range(const DevCtx& c, const uint8_t* msg, const RowList& rows, uint32_t R, float scale, int accumulate,
+                                float* out, const uint32_t* dir, uint32_t ndir, uint32_t t, float* s_acc, uint8_t* s_has,
+                                uint32_t* s_loc, float* s_val) {
+  const uint32_t lane = lane_id(), tid = threadIdx.x;
+  const uint64_t base = static_cast<uint64_t>(t) << AGG_DIR_SHIFT;
+  // lane p (of every wave): listed message p -- its row, its length, its entries [lo, hi) that fall into this range
+  uint32_t my_row = 0, my_nnz = 0, lo = 0, hi = 0;
+  if (lane < R) {
+    my_row = rows.row[lane];
+    my_nnz = min(reinterpret_cast<const uint32_t*>(msg + static_cast<uint64_t>(my_row) * c.cap_words * 4)[0], c.K);
+    lo = min(dir[static_cast<uint64_t>(lane) * ndir + t], my_nnz);
+    hi = min(dir[static_cast<uint64_t>(lane) * ndir + t + 1], my_nnz);
+    if (hi < lo) hi = lo;
+    if (hi - lo > AGG_RANGE) hi = lo + AGG_RANGE;        // a well-formed message has at most one entry per coordinate
+  }
+  const uint32_t cnt = hi - lo;
+  if (__ballot(cnt != 0) == 0) return true;              // nothing to add here
+  if (LIST && wave_sum(cnt) >= AGG_DENSE_MIN) return false;
+  for (uint32_t i = tid; i < AGG_RANGE; i += NT) s_has[i] = 0;
+  const bool counts = is_qsgd(c.quantizer) && c.L > 1;
+  const uint64_t hdr = 1 + static_cast<uint64_t>(c.L) + (counts ? c.L : 0);
+  const uint32_t idx_mask = c.w_idx == 32 ? 0xFFFFFFFFu : (1u << c.w_idx) - 1u;
+  // the segments of the range's first and last coordinate: mostly the same one
+  const uint32_t seg_lo = c.L == 1 ? 0u : seg_of_coord(c, static_cast<uint32_t>(base));
+  const uint32_t seg_hi = c.L == 1 ? 0u : seg_of_coord(c, static_cast<uint32_t>(min<uint64_t>(base + AGG_RANGE, c.d) - 1));
+  uint32_t p0 = 0;
+  while (p0 < R) {                                       // uniform over the threads
+    // the batch p0 .. p1 - 1: as many messages as the staging list holds (at least one)
+    uint32_t tot;
+    const uint32_t before = wave_exclusive_scan32(lane >= p0 && lane < R ? cnt : 0u, &tot);
+    const uint64_t over = __ballot(lane > p0 && lane < R && before + cnt > STAGE);
+    const uint32_t p1 = over ? static_cast<uint32_t>(__ffsll(static_cast<unsigned long long>(over)) - 1) : R;
+    const uint32_t n_staged = p1 < R ? __shfl(before, p1, WAVE) : tot;
+    const uint64_t in_batch = __ballot(cnt != 0 && lane >= p0 && lane < p1);
+    // decode the batch side by side, 4 x NT staged entries per step with their loads in flight together: staged entry
+    // f belongs to the last message x of the batch with before_x <= f
+    constexpr uint32_t UN = 4;
+    for (uint32_t f0 = 0; f0 < n_staged; f0 += UN * NT) {
+      uint32_t q_row[UN], q_nnz[UN], q_lo[UN], q_before[UN];
+#pragma unroll
+      for (uint32_t u = 0; u < UN; ++u) { q_row[u] = 0; q_nnz[u] = 0; q_lo[u] = 0; q_before[u] = 0; }
+      for (uint64_t left = in_batch; left; left &= left - 1) {      // the batch's messages that have entries here, in order
+        const int x = __ffsll(static_cast<unsigned long long>(left)) - 1;     // (uniform: every lane takes part in the shuffles)
+        const uint32_t bx = __shfl(before, x, WAVE);
+        const uint32_t rx = __shfl(my_row, x, WAVE), nx = __shfl(my_nnz, x, WAVE), lx = __shfl(lo, x, WAVE);
+#pragma unroll
+        for (uint32_t u = 0; u < UN; ++u)
+          if (f0 + u * NT + tid >= bx) { q_row[u] = rx; q_nnz[u] = nx; q_lo[u] = lx; q_before[u] = bx; }
+      }
+      uint32_t idx[UN], code[UN];
+      const uint32_t* words[UN];
+#pragma unroll
+      for (uint32_t u = 0; u < UN; ++u) {
+        const uint32_t f = f0 + u * NT + tid;
+        words[u] = reinterpret_cast<const uint32_t*>(msg + static_cast<uint64_t>(q_row[u]) * c.cap_words * 4);
+        idx[u] = 0xFFFFFFFFu; code[u] = 0;
+        if (f < n_staged) {
+          const uint32_t j = q_lo[u] + (f - q_before[u]);
+          idx[u] = get_bits(words[u], hdr * 32 + static_cast<uint64_t>(j) * c.w_idx, c.w_idx) & idx_mask;
+          const uint64_t code_bit0 = (hdr + (static_cast<uint64_t>(q_nnz[u]) * c.w_idx + 31) / 32) * 32;
+          code[u] = get_bits(words[u], code_bit0 + static_cast<uint64_t>(j) * c.w_val, c.w_val);
+        }
+      }
+#pragma unroll
+      for (uint32_t u = 0; u < UN; ++u) {
+        const uint32_t f = f0 + u * NT + tid;
+        if (f < n_staged) {
+          uint32_t loc = 0xFFFFFFFFu;
+          float val = 0.0f;
+          if (idx[u] >= base && idx[u] < base + AGG_RANGE && idx[u] < c.d) {
+            const uint32_t seg = c.L == 1 ? 0u : seg_lo == seg_hi ? seg_lo : seg_of_coord(c, idx[u]);
+            val = value_of_code(c, code[u], __uint_as_float(words[u][1 + seg]));
+            loc = static_cast<uint32_t>(idx[u] - base);
+          } else atomicOr(c.status, 4u);                   // malformed message: the entry is skipped
+          s_loc[f] = loc; s_val[f] = val;
+        }
+      }
+    }
+    range_barrier<NT>();
+    // add them message after message
+    for (uint64_t left = in_batch; left; left &= left - 1) {
+      const int x = __ffsll(static_cast<unsigned long long>(left)) - 1;
+      const uint32_t bx = __shfl(before, x, WAVE), cx = __shfl(cnt, x, WAVE);
+      for (uint32_t i = tid; i < cx; i += NT) {
+        const uint32_t loc = s_loc[bx + i];
+        if (loc != 0xFFFFFFFFu) {
+          const float v = s_val[bx + i];
+          s_acc[loc] = s_has[loc] ? s_acc[loc] + v : v;
+          s_has[loc] = 1;
+        }
+      }
+      range_barrier<NT>();
+    }
+    p0 = p1;
+  }
+  for (uint32_t i = tid; i < AGG_RANGE; i += NT) {
+    if (s_has[i]) {
+      const float term = scale * s_acc[i];
+      out[base + i] = accumulate ? out[base + i] + term : term;
+    }
+  }
+  return true;
+}
+
+// a wave per range; the ranges with too many entries for one wave go to `dense_list` (dense_list[0] counts them)
+__global__ __launch_bounds__(64) void k_aggregate_ranges(DevCtx c, const uint8_t* msg, RowList rows, uint32_t R, float scale,
+                                                         int accumulate, float* out, const uint32_t* dir, uint32_t ndir,
+                                                         uint32_t* dense_list) {
+  __shared__ float s_acc[AGG_RANGE];
+  __shared__ uint8_t s_has[AGG_RANGE];
+  __shared__ uint32_t s_loc[1024];
+  __shared__ float s_val[1024];
+  if (!aggregate_range<64, 1024, true>(c, msg, rows, R, scale, accumulate, out, dir, ndir, blockIdx.x, s_acc, s_has, s_loc, s_val) &&
+      threadIdx.x == 0)
+    dense_list[1 + atomicAdd(&dense_list[0], 1u)] = blockIdx.x;
+}
+
+// a block of 1024 threads per listed range
+__global__ __launch_bounds__(1024) void k_aggregate_dense_ranges(DevCtx c, const uint8_t* msg, RowList rows, uint32_t R,
+                                                                 float scale, int accumulate, float* out, const uint32_t* dir,
+                                                                 uint32_t ndir, const uint32_t* dense_list) {
+  __shared__ float s_acc[AGG_RANGE];
+  __shared__ uint8_t s_has[AGG_RANGE];
+  __shared__ uint32_t s_loc[8192];
+  __shared__ float s_val[8192];
+  const uint32_t n = min(dense_list[0], ndir - 1);
+  for (uint32_t li = blockIdx.x; li < n; li += gridDim.x) {
+    const uint32_t t = dense_list[1 + li];
+    if (t < ndir - 1)
+      aggregate_range<1024, 8192, false>(c, msg, rows, R, scale, accumulate, out, dir, ndir, t, s_acc, s_has, s_loc, s_val);
+    __syncthreads();                                     // the LDS arrays are reused for the block's next range
   }
 }
 

@@ -65,7 +65,7 @@ def test_static_aggregate_refuses_what_does_not_fit():
     cfg = B._Config(16, 2, off2, k2, 1, 0, 1, 0, 1, 0)                    # two segments
     stream = C.c_void_p(torch.cuda.current_stream(dev).cuda_stream)
     assert lib.qsl_aggregate_static(C.byref(cfg), stream, msg.data_ptr(), None, 2, 1.0, 0, out.data_ptr()) == B.ERR_UNSUPPORTED
-    d = (1 << 32) - 1                                                        # 64 directories of 4 M words: beyond the array
+    d = (1 << 32) - 1                                                        # 65 directories of 4 M words: beyond the array
     off1 = (C.c_uint64 * 2)(0, d)
     k1 = (C.c_uint32 * 1)(100_000)
     cfg = B._Config(d, 1, off1, k1, 1, 0, 1, 0, 1, 0)
