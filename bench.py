@@ -20,10 +20,36 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0           # MI355X HBM3E, published peak
 ALGO_BYTES_PER_COORD = 12       # read m, read Delta, write m': what the method itself must move
-# HBM bytes per k_stream launch measured with rocprofv3 (FETCH_SIZE and WRITE_SIZE, each scaled by what the
-# counter reads for a 1 GiB device copy): profiles/k_stream_cfg2_hbm_traffic.txt.  Only for the configuration
-# that was profiled.
-MEASURED_TRAFFIC_BYTES = {2: 2_495_900_000}
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def kernel_source_digest():
+    """sha256 over the kernel sources: a counter summary under profiles/ names the digest it was taken with."""
+    import hashlib
+    h = hashlib.sha256()
+    src = os.path.join(ROOT, "paper_1906_02367_amd", "csrc")
+    for name in sorted(os.listdir(src)):
+        with open(os.path.join(src, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` from the rocprofv3 counter summary profiles/<kernel>_<workload>_hbm_traffic.txt
+    (FETCH_SIZE and WRITE_SIZE runs, scaled by a device copy of known size), if that summary was taken with the kernel
+    sources as they are now; else None and the reason."""
+    import re
+    path = os.path.join(PROFILES, f"{kernel}_{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None, "no counter summary for this kernel and workload under profiles/"
+    text = open(path).read()
+    dig = re.search(r"kernel_source_sha256:\s*([0-9a-f]+)", text)
+    tot = re.search(r"traffic_bytes_per_launch:\s*([0-9]+)", text)
+    if not dig or not tot:
+        return None, f"{os.path.basename(path)} has no digest or total"
+    if dig.group(1) != kernel_source_digest():
+        return None, f"{os.path.basename(path)} was taken with other kernel sources ({dig.group(1)})"
+    return int(tot.group(1)), f"profiles/{os.path.basename(path)}"
 
 
 def gpu_state():
@@ -70,6 +96,9 @@ def main():
     ap.add_argument("--from-models", action="store_true",
                     help="time qsl_compress_diff (Delta = x - xhat formed on the fly; the fresh buffers act as the "
                          "local models) instead of qsl_compress; not the headline line")
+    ap.add_argument("--standalone-update", action="store_true",
+                    help="the error memory is written by the stand-alone qsl_error_update (compress writes a copy that is "
+                         "thrown away): times that entry point inside the round; not the headline line")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not bracket the streaming kernel with HIP events (diagnostic: the roofline entry is then empty)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -108,11 +137,19 @@ def main():
     x = torch.zeros(d, dtype=torch.float32, device=dev)       # the master's parameter vector
     torch.cuda.synchronize()
 
-    def step(t):
+    m_copy = torch.empty_like(m) if args.standalone_update else None
+
+    def compress(t):
         if args.from_models:
             q.compress_diff(m, x, deltas[t % n_buf], m, 0, t, msg, msg_bits)
+        elif args.standalone_update:
+            q.compress(m, deltas[t % n_buf], m_copy, 0, t, msg, msg_bits)
+            q.error_update(m, deltas[t % n_buf], msg)
         else:
             q.compress(m, deltas[t % n_buf], m, 0, t, msg, msg_bits)
+
+    def step(t):
+        compress(t)
         q.aggregate(msg, x, -1.0 / R, accumulate=True)     # x <- x - (1/R) sum_r g^(r)
 
     if args.calibrate_copy:
@@ -135,14 +172,18 @@ def main():
     assert q.device_status() == B.OK
     elapsed = t1 - t0
     # a second, separate pass: every round bracketed by events on the stream the library launches on
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    for i, (e0, e1) in enumerate(ev):
+    ev = [tuple(torch.cuda.Event(enable_timing=True) for _ in range(3)) for _ in range(args.steps)]
+    for i, (e0, ec, e1) in enumerate(ev):
         e0.record()
-        step(total + i)
+        compress(total + i)
+        ec.record()
+        q.aggregate(msg, x, -1.0 / R, accumulate=True)
         e1.record()
     torch.cuda.synchronize()
-    per_round = sorted(e0.elapsed_time(e1) for e0, e1 in ev)
+    per_round = sorted(e0.elapsed_time(e1) for e0, ec, e1 in ev)
+    per_compress = sorted(e0.elapsed_time(ec) for e0, ec, e1 in ev)
     assert q.device_status() == B.OK
+    state_after = gpu_state()
     # for scale: the same traffic shape (two [R, d] reads, one [R, d] write) through PyTorch's own elementwise add
     ref_out = torch.empty_like(m)
     for _ in range(3):
@@ -162,11 +203,20 @@ def main():
     avg_stream_s = stream_ms / 1e3 / max(1, launches)
     algo_bytes = ALGO_BYTES_PER_COORD * R * d + (4 * d if args.from_models else 0)     # + one read of x
     achieved = algo_bytes / avg_stream_s / 1e9 if launches else None
-    roofline = {"bound": "hbm", "kernel": "k_stream", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+    kernel = "k_dense_norm" if wl.dense else "k_stream"
+    plain = not (args.from_models or args.workers or args.standalone_update)
+    traffic, traffic_source = measured_traffic(kernel, wl.name) if plain else (None, "only the plain entry point is profiled")
+    roofline = {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
-                "traffic": None if args.from_models else MEASURED_TRAFFIC_BYTES.get(args.config),
+                "traffic": traffic, "traffic_source": traffic_source,
                 "avg_launch_us": avg_stream_s * 1e6, "launches": launches,
                 "algorithmic_bytes_per_launch": algo_bytes}
+    # the whole compress call (every kernel from the sample to the packed message) on the same accounting; an operator
+    # that keeps every coordinate reads v once more and writes m' in its second pass: 20 bytes per coordinate
+    step_bytes = (20 if wl.dense else ALGO_BYTES_PER_COORD) * R * d
+    compress_ms = per_compress[len(per_compress) // 2]
+    compress_call = {"median_ms": compress_ms, "min_ms": per_compress[0], "algorithmic_bytes": step_bytes,
+                     "GB/s": step_bytes / compress_ms / 1e6, "frac": step_bytes / compress_ms / 1e6 / HBM_PEAK_GBS}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -204,16 +254,20 @@ def main():
         "ms_per_step": elapsed / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "R": R, "d": d, "k": int(wl.K), "s": wl.s, "segments": wl.L,
-                   "sparsifier": ["top_k", "rand_k"][wl.sparsifier], "quantizer": ["qsgd", "sign_l1"][wl.quantizer],
+                   "sparsifier": ["top_k", "rand_k"][wl.sparsifier],
+                   "quantizer": ["qsgd", "sign_l1", "sign_l2", "fp32", "qsgd_scaled"][wl.quantizer],
+                   "format": "index-free" if wl.dense else "indices + codes",
+                   "error_update": "stand-alone qsl_error_update" if args.standalone_update else "fused",
                    "fresh_delta_buffers": n_buf, "delta": "x - xhat on the fly" if args.from_models else "given",
                    "paths": {"fast": int((units[:, 0] == 0).sum()), "general": int((units[:, 0] == 1).sum()),
                              "fallback": int((units[:, 0] == 2).sum()), "one_block": int((units[:, 0] == 3).sum()),
                              "all_kept": int((units[:, 0] == 4).sum())},
                    "max_candidates": int(units[:, 1].max()), "mean_msg_bits": float(bits.mean())},
-        "algorithmic_GBps_whole_step": ALGO_BYTES_PER_COORD * coords_per_s / 1e9,
+        "algorithmic_GBps_whole_step": step_bytes / (R * d) * coords_per_s / 1e9,
+        "compress_call": compress_call,
         "per_round_ms": {"median": per_round[len(per_round) // 2], "min": per_round[0], "max": per_round[-1],
                          "note": "separate pass after the timed region, HIP events around each round"},
-        "gpu_state": state,
+        "gpu_state": {"before": state, "after": state_after, "kernel_source_sha256": kernel_source_digest()},
         "stream_reference": {"what": "torch.add(m, delta, out=...) on the same [R, d] arrays: 2 reads + 1 write per coordinate",
                              "us": ref_us, "GB/s": ALGO_BYTES_PER_COORD * R * d / ref_us / 1e3},
         "roofline": roofline,
