@@ -110,3 +110,27 @@ def test_messages_without_touching_the_memory(P, cfg, d):
     with pytest.raises(B.QslError):
         q_plain.compress(m, delta, None, 0, 3, msg2)                                    # no home for v: refused
     assert q.device_status() == B.OK
+
+
+@pytest.mark.parametrize("cfg,d", [(2, 1_000_003), (3, 600_011), (4, 2_000_000), (6, None)])
+def test_same_bytes_whatever_the_launch_shape(P, cfg, d):
+    """The operator is applied to each worker's vector on its own (Algorithm 1, worker lines), so how many workers
+    one call carries may not show in the result: 6 workers in one call, the same 6 in a context made for 9, and one
+    worker per call in a context made for one (other grids, other kernel instances) -- the same bytes, 3 rounds."""
+    from paper_1906_02367_amd import binding as B
+    wl = W.config(cfg, d=d, R=6)
+    dev = torch.device("cuda")
+    deltas = [torch.from_numpy(W.delta_all(wl, t)).to(dev) for t in range(3)]
+    q6, q9 = B.from_workload(wl), B.from_workload(wl, max_workers=9)
+    q1 = [B.from_workload(wl, max_workers=1) for _ in range(wl.R)]      # a context per worker: each carries its own guess
+    m6, m9, m1 = (torch.zeros(wl.R, wl.d, device=dev) for _ in range(3))
+    for t in range(3):
+        msg6, msg9, msg1 = q6.new_msg(wl.R), q9.new_msg(wl.R), q6.new_msg(wl.R)
+        q6.compress(m6, deltas[t], m6, 0, t, msg6)
+        q9.compress(m9, deltas[t], m9, 0, t, msg9)
+        for r in range(wl.R):
+            q1[r].compress(m1[r:r + 1], deltas[t][r:r + 1], m1[r:r + 1], r, t, msg1[r:r + 1])
+        torch.cuda.synchronize()
+        assert torch.equal(msg6, msg9) and torch.equal(msg6, msg1), f"round {t}: messages differ"
+        assert torch.equal(m6.view(torch.int32), m9.view(torch.int32)), f"round {t}: memory differs (9-worker context)"
+        assert torch.equal(m6.view(torch.int32), m1.view(torch.int32)), f"round {t}: memory differs (one worker per call)"

@@ -285,6 +285,46 @@ def test_sign_l2_scaling_closed_form_and_compression():
     assert res["bits"] == 64 + k * ((d - 1).bit_length() + 1)
 
 
+@pytest.mark.parametrize("sparsifier", [O.TOPK, O.RANDK])
+def test_norm_scaling_with_m_above_2_is_dominated_by_the_two_built_scalings(sparsifier):
+    """Lemma 3 allows any norm index m for the scale c_m = ||v_S||_m / k.  With the selected set S fixed, the error
+    ||c sign(v_S) - v||^2 = ||v||^2 - 2 c ||v_S||_1 + k c^2 is a parabola in c whose minimum sits at c_1 = ||v_S||_1 / k
+    (the m = 1 scale); norms do not grow with m, so c_1 >= c_2 >= c_3 >= ... and the error can only grow with m: m = 1
+    and m = 2 (both built) are at least as good as every larger m on every input, as the coefficient
+    gamma_m = k^(2/m - 1) / d, decreasing in m, says in the worst case.  Checked on the oracle's own selection and scales."""
+    rng = np.random.default_rng(31)
+    for d, k in [(3000, 64), (500, 500), (4096, 1), (2000, 333)]:
+        v = (rng.standard_normal(d) * np.exp(1.5 * rng.standard_normal(d))).astype(f32)
+        off, kk = one_seg(d, k)
+        r1 = O.OracleOp(d, off, kk, 1, sparsifier, O.SIGN_L1, 9).compress(np.zeros(d, f32), v, 0, 0)
+        r2 = O.OracleOp(d, off, kk, 1, sparsifier, O.SIGN_L2, 9).compress(np.zeros(d, f32), v, 0, 0)
+        S = r1["sel_idx"].astype(np.int64)
+        assert np.array_equal(S, r2["sel_idx"].astype(np.int64))
+        a = np.abs(v[S].astype(np.float64))
+        x2 = (v.astype(np.float64) ** 2).sum()
+        n1 = a.sum()
+
+        def err(c):
+            return x2 - 2.0 * c * n1 + k * c * c
+
+        c = {m: (a ** m).sum() ** (1.0 / m) / k for m in (1, 2, 3, 4, 8)}
+        c["inf"] = a.max() / k
+        # the two built scales are the m = 1 and m = 2 members of the family
+        assert abs(float(r1["scales"][0]) - c[1]) <= 1e-6 * c[1] and abs(float(r2["scales"][0]) - c[2]) <= 1e-6 * c[2]
+        order = [1, 2, 3, 4, 8, "inf"]
+        for lo, hi in zip(order, order[1:]):
+            assert c[lo] >= c[hi] * (1 - 1e-12)
+            assert err(c[lo]) <= err(c[hi]) + 1e-9 * x2, (d, k, lo, hi)
+        # the closed form against the error of the oracle's own output (the identity behind the argument)
+        for res, m in ((r1, 1), (r2, 2)):
+            g = np.zeros(d); g[S] = res["g_val"]
+            assert abs(((g - v.astype(np.float64)) ** 2).sum() - err(c[m])) <= 1e-5 * x2
+        # Lemma 3's coefficient for m >= 2 holds for Top_k on every input (for Rand_k only in expectation)
+        if sparsifier == O.TOPK:
+            for m in (2, 3, 4, 8):
+                assert err(c[m]) <= (1 - k ** (2.0 / m - 1) / d) * x2 * (1 + 1e-12)
+
+
 def test_no_quantiser_is_top_k_itself():
     rng = np.random.default_rng(29)
     d, k = 2500, 40
