@@ -325,7 +325,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   // per-segment plan: single-pass guessing ("fast") where the unit is large and sparse enough
   std::vector<SegInfo>& segs = ctx->segs;
   segs.resize(L);
-  std::vector<WtInfo> wts;
+  std::vector<WtInfo> wts, wts_own;
   std::vector<SelInfo> sels, samps, fulls;
   std::vector<CbInfo> cbs;
   std::vector<uint32_t> fast, smalls;
@@ -342,14 +342,15 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
     const double cand = plan_segment(cfg, sg);
     if (L > 1) {
       // The chunks in the order k_stream's waves take them, four to a block.  A unit of at most 4096 coordinates that one
-      // block is to select gets its block to itself: the list is filled up to a block boundary before and after it.
+      // block is to select gets its block to itself (filled up with waves that have no chunk), and these blocks come
+      // first in the grid: they run longest, so they start before the streaming blocks rather than after them.
       const bool own_block = sg.mode == PATH_SMALL && sg.nwt <= SMALL_CHUNKS;
-      auto fill_up = [&]() { while (wts.size() % 4) { WtInfo wi; wi.seg = l; wi.chunk = NO_CHUNK; wi.inblock = own_block; wi.pad1 = 0; wts.push_back(wi); } };
-      if (own_block) {                              // (the filler before it belongs to the previous units' block: no unit, no chunk)
-        while (wts.size() % 4) { WtInfo wi; wi.seg = l; wi.chunk = NO_CHUNK; wi.inblock = 0; wi.pad1 = 0; wts.push_back(wi); }
+      std::vector<WtInfo>& list = own_block ? wts_own : wts;
+      for (uint32_t t = 0; t < sg.nwt; ++t) { WtInfo wi; wi.seg = l; wi.chunk = t; wi.inblock = own_block; wi.pad1 = 0; list.push_back(wi); }
+      if (own_block) {
+        while (wts_own.size() % 4) { WtInfo wi; wi.seg = l; wi.chunk = NO_CHUNK; wi.inblock = 1; wi.pad1 = 0; wts_own.push_back(wi); }
+        sg.mode = PATH_SMALL; sg.in_stream = 1;
       }
-      for (uint32_t t = 0; t < sg.nwt; ++t) { WtInfo wi; wi.seg = l; wi.chunk = t; wi.inblock = own_block; wi.pad1 = 0; wts.push_back(wi); }
-      if (own_block) { fill_up(); sg.mode = PATH_SMALL; sg.in_stream = 1; }
     }
     if (sg.mode == PATH_FAST && cfg->sparsifier == QSL_TOPK) {        // a guessing Top_k unit samples
       ++ctx->n_sampled;
@@ -448,7 +449,10 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   std::stable_sort(samps.begin(), samps.end(), [&](const SelInfo& a, const SelInfo& b) { return sample_cost(a) > sample_cost(b); });
   std::stable_sort(smalls.begin(), smalls.end(), [&](uint32_t a, uint32_t b) { return segs[a].size > segs[b].size; });
   ctx->nsamp_blocks = static_cast<uint32_t>(samps.size());
-  if (L > 1) nwt64 = wts.size();                    // with the fillers around the small units
+  if (L > 1) {                                      // the small units' own blocks first, with their fillers
+    wts.insert(wts.begin(), wts_own.begin(), wts_own.end());
+    nwt64 = wts.size();
+  }
   const uint32_t NWT = static_cast<uint32_t>(nwt64);
   const uint32_t NSEL = static_cast<uint32_t>(sels.size()), NCB = static_cast<uint32_t>(cbs.size());
   const uint32_t NSELF = static_cast<uint32_t>(fsels.size());

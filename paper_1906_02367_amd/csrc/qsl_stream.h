@@ -159,26 +159,32 @@ __device__ void stream_block_unit(const DevCtx& c, const SegInfo& sg, uint64_t u
   for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK) lh[i] = 0;
   for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;
   __syncthreads();
-  // the three digits of the k-th largest key
-  uint32_t above;
-  stream_unit_hist<0>(key, inside, 0, lh);
-  __syncthreads();
-  uint32_t bin = find_from_top<BLOCK>(lh, sg.k, &above, scratch, result, true);
-  uint32_t prefix = bin << 20, k_rem = sg.k - above;
-  stream_unit_hist<1>(key, inside, prefix, lh);
-  __syncthreads();
-  bin = find_from_top<BLOCK>(lh, k_rem, &above, scratch, result, true);
-  prefix |= bin << 8; k_rem -= above;
-  stream_unit_hist<2>(key, inside, prefix, lh);
-  __syncthreads();
-  bin = find_from_top<BLOCK, 256>(lh, k_rem, &above, scratch, result, false);
-  const uint32_t tau = prefix | bin, need = k_rem - above;
+  // the three digits of the k-th largest key -- unless the unit keeps every coordinate (a tensor of at most k
+  // coordinates under a rule like k_t = min(d_t, 1000), Section 5.1.1): then there is nothing to find
+  const bool all = sg.k == sg.size;                 // uniform over the block
+  uint32_t tau = 0, need = 0;
+  if (!all) {
+    uint32_t above;
+    stream_unit_hist<0>(key, inside, 0, lh);
+    __syncthreads();
+    uint32_t bin = find_from_top<BLOCK>(lh, sg.k, &above, scratch, result, true);
+    uint32_t prefix = bin << 20, k_rem = sg.k - above;
+    stream_unit_hist<1>(key, inside, prefix, lh);
+    __syncthreads();
+    bin = find_from_top<BLOCK>(lh, k_rem, &above, scratch, result, true);
+    prefix |= bin << 8; k_rem -= above;
+    stream_unit_hist<2>(key, inside, prefix, lh);
+    __syncthreads();
+    bin = find_from_top<BLOCK, 256>(lh, k_rem, &above, scratch, result, false);
+    tau = prefix | bin; need = k_rem - above;
+  }
   // ranks in coordinate order: wave (= chunk), then t, then lane, then j.  Counts packed as (#equal << 16 | #greater).
   uint32_t gm = 0, qm = 0;
 #pragma unroll
   for (uint32_t i = 0; i < 16; ++i) {
-    gm |= (((inside >> i) & 1u) && key[i] > tau ? 1u : 0u) << i;
-    qm |= (((inside >> i) & 1u) && key[i] == tau ? 1u : 0u) << i;
+    const bool in = (inside >> i) & 1u;
+    gm |= (in && (all || key[i] > tau) ? 1u : 0u) << i;
+    qm |= (in && !all && key[i] == tau ? 1u : 0u) << i;
   }
   uint32_t pre[4];
 #pragma unroll
