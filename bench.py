@@ -99,6 +99,10 @@ def main():
     ap.add_argument("--standalone-update", action="store_true",
                     help="the error memory is written by the stand-alone qsl_error_update (compress writes a copy that is "
                          "thrown away): times that entry point inside the round; not the headline line")
+    ap.add_argument("--aggregate-messages", default="",
+                    help="comma-separated message counts (at most 64): after the timed rounds, also time qsl_aggregate alone "
+                         "on that many messages of this workload (master line of Algorithm 1 with many workers); an extra "
+                         "object in the JSON line, not part of `value`")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="do not bracket the streaming kernel with HIP events (diagnostic: the roofline entry is then empty)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -218,6 +222,36 @@ def main():
     compress_call = {"median_ms": compress_ms, "min_ms": per_compress[0], "algorithmic_bytes": step_bytes,
                      "GB/s": step_bytes / compress_ms / 1e6, "frac": step_bytes / compress_ms / 1e6 / HBM_PEAK_GBS}
 
+    aggregate_scaling = None
+    if args.aggregate_messages:
+        counts = sorted({int(c) for c in args.aggregate_messages.split(",")})
+        n_max = counts[-1]
+        qa = B.from_workload(wl, max_workers=n_max, device=dev)
+        many = qa.new_msg(n_max)
+        ma = torch.empty_like(m)
+        for b in range((n_max + R - 1) // R):              # workers b R .. b R + R - 1: their own inputs and random words
+            n = min(R, n_max - b * R)
+            ma.zero_()
+            qa.compress(ma[:n], deltas[b % n_buf][:n], ma[:n], b * R, 0, many[b * R:b * R + n])
+        torch.cuda.synchronize()
+        entries = [int(v) for v in many[:, :4].contiguous().view(torch.int32)[:, 0].cpu()]
+        xa = torch.zeros(d, dtype=torch.float32, device=dev)
+        aggregate_scaling = []
+        for n in counts:
+            for _ in range(3):
+                qa.aggregate(many[:n], xa, -1.0 / n, accumulate=True)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                qa.aggregate(many[:n], xa, -1.0 / n, accumulate=True)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1000.0 / 20
+            tot = sum(entries[:n]) if not wl.dense else n * d
+            aggregate_scaling.append({"messages": n, "entries": tot, "us": us, "ns_per_entry": us * 1000.0 / max(1, tot)})
+        assert qa.device_status() == B.OK
+        del qa, many, ma, xa
+
     cpu = None
     if not args.no_cpu_baseline:
         from concurrent.futures import ThreadPoolExecutor
@@ -273,6 +307,8 @@ def main():
         "roofline": roofline,
         "cpu_baseline": cpu,
     }
+    if aggregate_scaling is not None:
+        line["aggregate_scaling"] = aggregate_scaling
     print(json.dumps(line))
 
 
