@@ -1,25 +1,35 @@
 // qsl.hip -- host side and C ABI of the compression hot path of Qsparse-local-SGD for gfx950; the kernels
-// are in the headers included below (qsl_stream.h, qsl_select.h, qsl_encode.h, qsl_decode.h).
+// are in the headers included below (qsl_stream.h, qsl_lean.h, qsl_select.h, qsl_encode.h, qsl_dense.h, qsl_decode.h).
 //
 // One synchronisation step of Algorithm 1 (arXiv:1906.02367) for a batch of R workers:
-//   k_sample     the guess (Top_k only): a quantile of a strided sample of |m + Delta| (of group maxima
-//                of the whole unit when no sample is reliable); for Rand_k the rank keys are uniform
-//                random words, so the guess is analytic
 //   k_stream     v = m + Delta (worker line 1), written over the error memory in ONE pass over HBM;
 //                each wave streams one chunk of 1024 coordinates and leaves the coordinates whose
-//                rank key reaches the unit's guess in the chunk's own slot line (written as one
-//                full 128-byte line: no read-modify-write in HBM, no atomic to wait for)
-//   k_select<l>  exact radix selection of the k-th largest key (Section 2.2: Top_k / Rand_k), 12+12+8
-//                bits, over the candidates -- or over the whole vector when the guess failed or the
-//                unit is too dense for guessing (the general path; always exact)
-//   k_small      a unit of at most 4 chunks: selection, ordered compaction and norm by one block
+//                rank key reaches the unit's guess in the chunk's own slot (written as one full
+//                slot-sized store: no read-modify-write in HBM, no atomic to wait for).  In a segmented
+//                context a unit of at most 4096 coordinates has a block of this kernel to itself, which
+//                also selects and encodes it.
+//   the guess    Top_k: carried from the previous call of the context (k_lean_mark derives it from the
+//                candidates it sees); on the first call a quantile of a strided sample of |m + Delta|
+//                (k_sample, k_sample_scan).  Rand_k: the rank keys are uniform random words, so it is analytic.
+//   k_lean_hist, k_lean_mark, k_lean_emit
+//                the guessing units: exact selection of the k largest keys among the candidates (Section 2.2:
+//                Top_k / Rand_k, ties to the lower coordinate), the exact ||v_S||_2^2 or ||v_S||_1 (proof of
+//                Lemma 1; Lemma 3, m = 1), QSGD levels (Definition 1, example 1) or signs (Definition 2), and
+//                the error update m <- v - g on the transmitted coordinates (Algorithm 1, worker line 2)
+//   k_block_units  a unit too dense for guessing, of at most 40,960 coordinates: all of the above by one block,
+//                on a second stream beside the guessing units' kernels
 //   k_full       a unit with k = size: nothing to select, the coordinates are copied in order
-//   k_tile_count / k_tile_write    ordered compaction of the selected coordinates, ties to the lower index
-//                (k_tile_write also accumulates the exact ||v_S||_2^2 or ||v_S||_1: proof of Lemma 1; Lemma 3, m = 1)
-//   k_quantize   QSGD levels (Definition 1, example 1) or signs (Definition 2); error update
-//                m <- v - g on the transmitted coordinates (Algorithm 1, worker line 2)
+//   k_select<l>, k_tile_count, k_tile_write, k_quantize
+//                exact radix selection (12 + 12 + 8 bits) over the whole vector, ordered compaction and
+//                encoding: dense k on a large unit, and the units whose guess failed while the host expects
+//                failures (always exact; only the speed depends on the guess)
 //   k_surv_compact, k_pack    the packed message
-//   k_aggregate  master line of Algorithm 1, atomic-free (k_aggregate_dense when every message lists every coordinate)
+//   k_dense_norm, k_dense_scales, k_dense_encode    an operator that keeps every coordinate, with messages that
+//                carry no indices: two streaming passes
+//   k_aggregate, k_aggregate_entries, k_aggregate_ranges, k_aggregate_dense
+//                master line of Algorithm 1, atomic-free, messages added in list order: by look-ups in the other
+//                messages (few messages), by coordinate ranges (many), or coordinate by coordinate (every
+//                message lists every coordinate)
 //
 // A "unit" is one (worker, segment) pair: the operator is applied independently to each unit
 // (Corollary 1).  Rank key: Top_k: magnitude bits of v shifted left by one; Rand_k: the
