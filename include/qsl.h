@@ -139,7 +139,11 @@ size_t qsl_msg_capacity_bytes(const qsl_ctx *ctx);
  *             (0 = not transmitted); 1 for every entry under the sign quantiser
  * The random word of coordinate i is Philox4x32-10 with counter (i / 4, worker, round mod 2^32,
  * (round >> 32) | stream << 30), key (seed mod 2^32, seed >> 32), output word i mod 4; stream 0
- * ranks coordinates for Rand_k, stream 1 drives the QSGD rounding.  */
+ * ranks coordinates for Rand_k, stream 1 drives the QSGD rounding.
+ * Speed only, never the result: for Top_k the context keeps, per row r of the batch and per segment, a guess of
+ * the selection threshold taken from its previous call (the first call, or QSL_FLAG_NO_WARM_START, samples the
+ * input instead).  The guess serves best when row r carries the same worker from call to call; a context
+ * whose rows change hands between unrelated inputs selects just as exactly, but may do so by slower kernels.  */
 qsl_status qsl_compress(qsl_ctx *ctx, const float *m, const float *delta, float *m_out, uint32_t worker0,
                         uint32_t R, uint64_t round, uint8_t *msg, uint64_t *msg_bits, uint32_t *sel_idx,
                         uint16_t *sel_level);

@@ -120,7 +120,8 @@ def run_async(problem, op: Operator, H=4, T=400, b=8, xi=None, seed=0, on_sync=N
     """Algorithm 2: per-worker synchronisation times, subset aggregation scaled by 1/R.
     `on_sync(t, S, m_before, delta, msg, m_after, x_before, x_after)` as in `run_sync`, with the reporting set S."""
     dev, R = problem.device, problem.R
-    q = op.make(R, dev)
+    q = op.make(R, dev)                                  # the master's context (aggregation, bit counts)
+    qw = [op.make(1, dev) for _ in range(R)]             # one per worker: each keeps its own worker's threshold guess
     xi = xi if xi is not None else 0.5 * D * H / op.k
     rng = np.random.default_rng(seed)
     next_sync = rng.integers(1, H + 1, size=R)           # worker r synchronises when t + 1 == next_sync[r]
@@ -138,7 +139,7 @@ def run_async(problem, op: Operator, H=4, T=400, b=8, xi=None, seed=0, on_sync=N
             delta = xr - xh                              # x^(r) - xhat^(r)_{t+1/2}; only the rows in S are used
             m_before, x_before = (m.clone(), x.clone()) if on_sync else (None, None)
             for r in S:                                  # the reporting workers compress, each with its own id
-                q.compress(m[r:r + 1], delta[r:r + 1], m[r:r + 1], r, t, msg[r:r + 1])
+                qw[r].compress(m[r:r + 1], delta[r:r + 1], m[r:r + 1], r, t, msg[r:r + 1])
             q.aggregate(msg, x, -1.0 / R, worker_list=S, accumulate=True)
             total_bits += sum(q.bits_sent(msg)[r] for r in S)
             if on_sync:

@@ -398,15 +398,26 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   // blocks of a fast unit in the selection kernels: ~3 slot rows per wave, and no more than one block
   // per compute unit in all (measured, 8 workers with 1560 rows each: 16 blocks per unit 12 us, 32 blocks
   // 9 us, 48 blocks 12.5 us)
-  uint64_t fast_blocks = 0;
-  for (uint32_t l : fast) {
-    SegInfo& sg = segs[l];
-    const uint64_t nrows = (static_cast<uint64_t>(sg.nwt) * sg.lpc + 63) / 64;
-    sg.nsel = static_cast<uint32_t>(std::min<uint64_t>(MAX_SELECT_BLOCKS, std::max<uint64_t>(1, (nrows + 47) / 48)));
-    fast_blocks += static_cast<uint64_t>(sg.nsel) * ctx->Rmax;
+  // Every unit gets one block; the blocks that are left of the budget go, one at a time, to the unit whose blocks
+  // have the most rows to read (the slowest block is the kernel's time).
+  {
+    auto rows_of = [&](uint32_t l) { return (static_cast<uint64_t>(segs[l].nwt) * segs[l].lpc + 63) / 64; };
+    auto want_of = [&](uint32_t l) { return static_cast<uint32_t>(std::min<uint64_t>(MAX_SELECT_BLOCKS, std::max<uint64_t>(1, (rows_of(l) + 47) / 48))); };
+    uint64_t used = 0;
+    for (uint32_t l : fast) { segs[l].nsel = 1; used += ctx->Rmax; }
+    auto load = [&](uint32_t l) { return static_cast<double>(rows_of(l)) / segs[l].nsel; };
+    auto lighter = [&](uint32_t a, uint32_t b) { return load(a) < load(b); };
+    std::vector<uint32_t> heap;
+    for (uint32_t l : fast) if (want_of(l) > 1) heap.push_back(l);
+    std::make_heap(heap.begin(), heap.end(), lighter);
+    const uint64_t budget = 256;                     // measured: 384, 512 and 768 are no faster on segmented contexts and slower on one segment
+    while (!heap.empty() && used + ctx->Rmax <= budget) {
+      std::pop_heap(heap.begin(), heap.end(), lighter);
+      const uint32_t l = heap.back();
+      ++segs[l].nsel; used += ctx->Rmax;
+      if (segs[l].nsel < want_of(l)) std::push_heap(heap.begin(), heap.end(), lighter); else heap.pop_back();
+    }
   }
-  if (fast_blocks > 256)
-    for (uint32_t l : fast) segs[l].nsel = static_cast<uint32_t>(std::max<uint64_t>(1, segs[l].nsel * 256ull / fast_blocks));
   // The block lists of the multi-pass kernels: the units that always take them first, then the guessing units, whose
   // share is launched only while the host expects failed guesses.  A guessing unit's blocks are also the blocks of
   // k_lean_* (fsels).
@@ -665,10 +676,12 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
                                   uint16_t* sel_level) {
   DevCtx& c = ctx->dc;
   hipStream_t st = ctx->stream;
-  c.blk_cnt = ctx->blk_cnt2[ctx->calls & 1]; c.blk_cnt_next = ctx->blk_cnt2[(ctx->calls & 1) ^ 1];
-  ++ctx->calls;
   if (static_cast<uint64_t>(std::max(std::max(c.NSEL, c.NCB), std::max(std::max(ctx->nsamp_blocks, c.nblock), c.NSELF + c.nfast))) * R > 0x7FFFFFFFull)
     return QSL_ERR_UNSUPPORTED;                    // the list kernels use one-dimensional grids of (list entries x workers)
+  if (xm != nullptr && static_cast<uint64_t>(((c.NWT + 3) / 4 + 7) / 8) * 8 * R > 0x7FFFFFFFull)
+    return QSL_ERR_UNSUPPORTED;                    // ... and so does the streaming kernel when it reads x_t
+  c.blk_cnt = ctx->blk_cnt2[ctx->calls & 1]; c.blk_cnt_next = ctx->blk_cnt2[(ctx->calls & 1) ^ 1];
+  ++ctx->calls;
   // A kernel that had to resolve a failed guess with one block (slow for a large unit) leaves a word in pinned host
   // memory; the next calls then keep the multi-pass kernels standing by for the units whose guess fails.  The word
   // may be seen a few calls late: only speed depends on it, never the result.
@@ -694,9 +707,7 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
     if (c.L == 1) k_stream<SPARS, true, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, sel_idx, sel_level);
     else k_stream<SPARS, false, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, sel_idx, sel_level);
   } else {
-    const uint64_t nb = static_cast<uint64_t>((nblk + 7) / 8) * 8 * R;
-    if (nb > 0x7FFFFFFFull) return QSL_ERR_UNSUPPORTED;
-    const dim3 sgrid(static_cast<uint32_t>(nb));
+    const dim3 sgrid(static_cast<uint32_t>(static_cast<uint64_t>((nblk + 7) / 8) * 8 * R));     // checked above
     if (c.L == 1) k_stream<SPARS, true, true><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, sel_idx, sel_level);
     else k_stream<SPARS, false, true><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, sel_idx, sel_level);
   }
