@@ -88,6 +88,7 @@ struct qsl_ctx {
   uint32_t* agg_dir;          // [64][agg_ndir] directories of the listed messages (only if messages are expected to be long)
   uint32_t agg_ndir;
   uint32_t n_sampled;         // segments whose guess comes from k_sample
+  uint32_t nbig_general;                // how many entries of DevCtx::big_segs are units of the multi-pass kernels (they come first)
   uint32_t nsel_general, ncb_general;   // blocks of the multi-pass kernels without / with (DevCtx::NSEL, NCB) the guessing units' share
   uint32_t n_other;           // segments that k_quantize encodes (not the guessing ones)
   uint32_t warm_R;            // workers whose guessing units carry a guess from an earlier call
@@ -496,7 +497,11 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t o_fast = carve(4ull * std::max<size_t>(1, fast.size()));
   const uint64_t o_small = carve(4ull * std::max<size_t>(1, smalls.size()));
   std::vector<uint32_t> bigs;
-  for (uint32_t l = 0; l < L; ++l) if (segs[l].mode != PATH_SMALL && segs[l].mode != PATH_FULL) bigs.push_back(l);
+  // the units that use the three histograms in memory: those of the multi-pass kernels first, then the guessing ones
+  // (whose only histogram k_lean_emit clears itself, unless the multi-pass kernels stood by for them in that call)
+  for (uint32_t l = 0; l < L; ++l) if (segs[l].mode == PATH_GENERAL) bigs.push_back(l);
+  ctx->nbig_general = static_cast<uint32_t>(bigs.size());
+  for (uint32_t l = 0; l < L; ++l) if (segs[l].mode == PATH_FAST) bigs.push_back(l);
   const uint64_t o_big = carve(4ull * std::max<size_t>(1, bigs.size()));
   std::vector<uint32_t> seg_dir(((d + 1023) >> 10) + 1);
   for (size_t t = 0, l = 0; t < seg_dir.size(); ++t) {
@@ -752,7 +757,7 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
     if (c.QB > MAX_QB_INLINE) k_surv_scan<<<dim3(R), 1024, 0, st>>>(c);
     k_surv_compact<<<dim3(c.QB, R), BLOCK, 0, st>>>(c);
   }
-  k_pack<<<dim3((c.cap_words + BLOCK - 1) / BLOCK, R), BLOCK, 0, st>>>(c, msg, msg_bits);
+  k_pack<<<dim3((c.cap_words + BLOCK - 1) / BLOCK, R), BLOCK, 0, st>>>(c, msg, msg_bits, safe ? c.nbig : ctx->nbig_general);
   QSL_HIP(hipGetLastError());
   return QSL_OK;
 }

@@ -316,16 +316,17 @@ __device__ __forceinline__ uint32_t gather_word(const uint32_t* arr, uint64_t n,
   return out;
 }
 
-__global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t* msg_bits) {
+__global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t* msg_bits, uint32_t nzero) {
   __shared__ uint32_t s_part[4];
   const uint32_t w = blockIdx.y;
   // this is the last kernel of a call: it also returns the shared scratch of this worker to all-zero
   {
     const uint64_t tid = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x, nth = static_cast<uint64_t>(gridDim.x) * BLOCK;
-    // histograms: only the segments that have any (not the one-block ones), and of the third digit only its 256 bins
+    // histograms: only the first `nzero` of the segments that have any (the units of the multi-pass kernels; the
+    // guessing units too when those kernels stood by for them in this call), and of the third digit only its 256 bins
     constexpr uint32_t ZW = 2 * HBINS + 256;
     uint32_t* h = c.hist + static_cast<uint64_t>(w) * c.L * 3 * HBINS;
-    for (uint64_t i = tid; i < static_cast<uint64_t>(c.nbig) * ZW; i += nth)
+    for (uint64_t i = tid; i < static_cast<uint64_t>(nzero) * ZW; i += nth)
       h[static_cast<uint64_t>(c.big_segs[i / ZW]) * 3 * HBINS + i % ZW] = 0;
     uint32_t* ct = c.ctr + static_cast<uint64_t>(w) * c.L * CTR_LINES * PAD;                 // counters: the guessing segments only
     for (uint64_t i = tid; i < static_cast<uint64_t>(c.nfast) * CTR_LINES; i += nth)

@@ -471,6 +471,8 @@ __global__ __launch_bounds__(BIG) void k_lean_emit(DevCtx c, SegInfo one, uint32
   LeanUnit lu;
   lean_unit<SPARS>(c, one, R, lu);
   const SegInfo& sg = lu.sg;
+  // the candidates' histogram has served (k_lean_mark was its last reader): this block's share of it back to zero
+  for (uint32_t i = lu.j * BIG + threadIdx.x; i < HBINS; i += sg.nsel * BIG) c.hist[lu.u * 3 * HBINS + i] = 0;
   UnitState* usp = &c.units[lu.u];
   const UnitState us = *usp;
   if (us.fell_back || us.crowded) return;
