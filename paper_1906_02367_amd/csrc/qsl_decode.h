@@ -500,11 +500,19 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate_dense(DevCtx c, const uint8
         if (nnz != 0 && g == 0) atomicOr(c.status, 4u);
         continue;
       }
+      // the codes of the thread's coordinates are consecutive in the stream: up to 8 bits each come in one read
+      // (77 -> 62 us for two messages of 25.6 M one-bit codes; issuing the reads of several messages together, or a
+      // wave per 1024 coordinates as in the streaming pass, were both slower again: 72-77 us)
+      const bool packed = c.w_val <= 8;                      // uniform
+      const uint32_t four = packed ? get_bits(words, code_bit0 + j0 * c.w_val, nj * c.w_val) : 0u;
+      const float scale0 = __uint_as_float(words[1 + seg[0]]);
 #pragma unroll
       for (uint32_t jj = 0; jj < 4; ++jj) {
         if (jj < nj) {
-          const uint32_t code = get_bits(words, code_bit0 + (j0 + jj) * c.w_val, c.w_val);
-          const float val = value_of_code(c, code, __uint_as_float(words[1 + seg[jj]]));
+          const uint32_t code = packed ? (four >> (jj * c.w_val)) & ((1u << c.w_val) - 1u)
+                                       : get_bits(words, code_bit0 + (j0 + jj) * c.w_val, c.w_val);
+          const float sc = seg[jj] == seg[0] ? scale0 : __uint_as_float(words[1 + seg[jj]]);
+          const float val = value_of_code(c, code, sc);
           acc[jj] = first ? val : acc[jj] + val;
         }
       }
