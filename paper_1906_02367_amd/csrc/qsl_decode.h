@@ -1,7 +1,8 @@
 // qsl_decode.h -- Reading messages: the stand-alone error update (k_add_rows, k_subtract_msg) and the master's
-// aggregation (k_fill_zero, k_msg_directory, k_aggregate), k_read_nnz.
-// Part of the single translation unit qsl.hip (included there, in this order: layout, stream, select,
-// encode, decode); not a public header.
+// aggregation (k_fill_zero, k_msg_directory, k_aggregate, k_aggregate_entries, k_aggregate_ranges,
+// k_aggregate_dense_ranges, k_aggregate_dense), k_read_nnz.
+// Part of the single translation unit qsl.hip (included there, in this order: device, layout, select,
+// encode, stream, lean, dense, decode); not a public header.
 #pragma once
 
 #include "qsl_device.h"

@@ -1,8 +1,9 @@
 // qsl_encode.h -- From the selected coordinates to the packed message: the fp32 scale from the exact norm digits,
-// k_quantize (QSGD levels / signs, error update on the transmitted coordinates), k_surv_scan,
+// encode_entry (QSGD level / sign of one selected coordinate, error update if it is transmitted) and block_encode_tail,
+// which every selection path calls; k_quantize (the same for the units of the multi-pass kernels), k_surv_scan,
 // k_surv_compact, k_pack.
-// Part of the single translation unit qsl.hip (included there, in this order: layout, stream, select,
-// encode, decode); not a public header.
+// Part of the single translation unit qsl.hip (included there, in this order: device, layout, select,
+// encode, stream, lean, dense, decode); not a public header.
 #pragma once
 
 #include "qsl_device.h"

@@ -1,7 +1,7 @@
 // qsl_layout.h -- Shared by all kernels of the library: tuning constants, the per-segment plan and per-unit state as they
 // lie in device memory, and the histogram helpers of the radix selection.
-// Part of the single translation unit qsl.hip (included there, in this order: layout, stream, select,
-// encode, decode); not a public header.
+// Part of the single translation unit qsl.hip (included there, in this order: device, layout, select,
+// encode, stream, lean, dense, decode); not a public header.
 #pragma once
 
 #include "qsl_device.h"

@@ -1,8 +1,8 @@
 // qsl_select.h -- Exact selection of the k largest rank keys of every unit (Section 2.2) and their ordered compaction:
 // k_select<0..2> (radix digits over the whole vector), k_full (k = size), k_tile_count and k_tile_write (ordered
 // output, exact norm digits); the slot rows of the guessing units.
-// Part of the single translation unit qsl.hip (included there, in this order: layout, stream, select,
-// encode, decode); not a public header.
+// Part of the single translation unit qsl.hip (included there, in this order: device, layout, select,
+// encode, stream, lean, dense, decode); not a public header.
 #pragma once
 
 #include "qsl_device.h"

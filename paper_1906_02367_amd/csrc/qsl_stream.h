@@ -1,7 +1,7 @@
 // qsl_stream.h -- The kernels in front of the selection: unit-state initialisation, the sampled guess for Top_k
 // (k_sample, k_sample_scan) and the one pass over HBM (k_stream: v = m + Delta, candidates to slots).
-// Part of the single translation unit qsl.hip (included there, in this order: layout, stream, select,
-// encode, decode); not a public header.
+// Part of the single translation unit qsl.hip (included there, in this order: device, layout, select,
+// encode, stream, lean, dense, decode); not a public header.
 #pragma once
 
 #include "qsl_device.h"

@@ -14,11 +14,11 @@ def P():
     return parity_util
 
 
-@pytest.mark.parametrize("cfg,rounds", [(2, 20), (3, 20), (4, 20), (5, 5), (6, 5)])
+@pytest.mark.parametrize("cfg,rounds", [(2, 20), (3, 20), (4, 20), (5, 5), (6, 5), (7, 3), (8, 3)])
 def test_full_size_config(P, cfg, rounds):
     wl = W.config(cfg)
     print(f"\n[{wl.name}] R={wl.R} d={wl.d} K={wl.K} L={wl.L}", flush=True)
-    run, op, m_host, paths = P.run_parity(wl, rounds, host_deltas=False)
+    run, op, m_host, paths = P.run_parity(wl, rounds, host_deltas=False, dense=wl.dense)
     if cfg in (2, 3, 5):
         assert all((p == 0).all() for p in paths), "the benchmark sizes must run on the single-pass path"
     # master line on the last round's messages
