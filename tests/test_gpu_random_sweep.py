@@ -111,3 +111,84 @@ def test_random_many_segments(P, block):
 def test_random_large_sizes(P, block):
     for seed in range(5_270 + 10 * block, 5_270 + 10 * (block + 1)):      # 5282 once caught a race in k_select<2>
         check_case(P, seed, 50_000, 8_000_000, [1, 1, 1, 2, 5, 17, 60], 3)
+
+
+def sequence_case(P, seed):
+    """Several rounds on one context with inputs that change character from round to round (scale jumps of orders of
+    magnitude, heavy tails, ties, zeros): the guess carried from call to call is wrong in every way it can be, so the
+    failure handling (one-block rescue, the multi-pass kernels standing by, the next guess from whole-unit
+    histograms) runs alongside the ordinary path.  Every round bit for bit against the oracle."""
+    from paper_1906_02367_amd import binding as B
+    rng = np.random.default_rng(seed)
+    d = int(np.exp(rng.uniform(np.log(70_000), np.log(2_500_000))))
+    L = min(int(rng.choice([1, 1, 3, 40])), d)
+    cuts = np.sort(rng.choice(np.arange(1, d), size=L - 1, replace=False)) if L > 1 else np.array([], dtype=np.int64)
+    off = np.concatenate([[0], cuts, [d]]).astype(np.uint64)
+    sizes = np.diff(off.astype(np.int64))
+    k = np.minimum(sizes, np.maximum(1, (sizes * rng.uniform(0.0005, 0.01)).astype(np.int64))).astype(np.uint32)
+    qz, s = int(rng.integers(0, 5)), int(rng.choice([1, 3, 16, 255]))
+    R = int(rng.integers(1, 4))
+    flags = int(rng.choice([0, 0, 0, 8]))                                  # 8: a fresh sample on every call
+    wl = W.Workload(2, f"sequence{seed}", R, d, off, k, s, 0, qz, 5, int(rng.integers(0, 2**63)))
+    deltas = []
+    for _ in range(5):
+        x = rng.standard_normal((R, d)).astype(f32)
+        kind = int(rng.integers(0, 4))
+        if kind == 1:
+            x *= np.exp(2 * rng.standard_normal(d)).astype(f32)
+        elif kind == 2:
+            x = np.round(x * 2).astype(f32)
+        elif kind == 3:
+            x[:, rng.random(d) < 0.9] = 0
+        x *= f32(10.0 ** rng.uniform(-4, 4))
+        deltas.append(x)
+    print(f"sequence {seed}: d={d} L={L} K={wl.K} quantizer={qz} s={s} R={R} flags={flags}", flush=True)
+    run, op, m_host, paths = P.run_parity(wl, 5, flags=flags, deltas=deltas)
+    assert run.q.device_status() == B.OK
+    return paths
+
+
+@pytest.mark.parametrize("block", range(3))
+def test_random_sequences_with_jumps(P, block):
+    for seed in range(61_000 + 8 * block, 61_000 + 8 * (block + 1)):
+        sequence_case(P, seed)
+
+
+@pytest.mark.parametrize("block", range(2))
+def test_random_index_free(P, block):
+    """Every coordinate kept, messages without indices: random sizes, segment tables, quantisers and inputs."""
+    for seed in range(62_000 + 10 * block, 62_000 + 10 * (block + 1)):
+        rng = np.random.default_rng(seed)
+        d = int(np.exp(rng.uniform(np.log(1), np.log(1_500_000))))
+        L = min(int(rng.choice([1, 1, 2, 7, 60, 700])), d)
+        cuts = np.sort(rng.choice(np.arange(1, d), size=L - 1, replace=False)) if L > 1 else np.array([], dtype=np.int64)
+        off = np.concatenate([[0], cuts, [d]]).astype(np.uint64)
+        k = np.diff(off.astype(np.int64)).astype(np.uint32)
+        qz, s = int(rng.integers(0, 5)), int(rng.choice([1, 2, 3, 15, 16, 255, 1000]))
+        R = int(rng.integers(1, 5))
+        wl = W.Workload(2, f"indexfree{seed}", R, d, off, k, s, int(rng.integers(0, 2)), qz, 2, int(rng.integers(0, 2**63)))
+        deltas = []
+        for _ in range(2):
+            x = rng.standard_normal((R, d)).astype(f32)
+            kind = int(rng.integers(0, 3))
+            if kind == 1:
+                x *= np.exp(2 * rng.standard_normal(d)).astype(f32)
+            elif kind == 2:
+                x[:, rng.random(d) < 0.7] = 0
+            deltas.append(x)
+        print(f"index-free {seed}: d={d} L={L} quantizer={qz} s={s} R={R}", flush=True)
+        run, op, m_host, _ = P.run_parity(wl, 2, deltas=deltas, dense=True, in_place=bool(rng.integers(0, 2)))
+        q = run.q
+        x0 = rng.standard_normal(d).astype(f32)
+        out = torch.from_numpy(x0).to(q.device)
+        q.aggregate(run.msg, out, -1.0 / R, accumulate=True)
+        torch.cuda.synchronize()
+        msgs = run.msg.cpu().numpy()
+        want = op.aggregate(msgs, -1.0 / R, out=x0)
+        mag = np.zeros(d)
+        for r in range(R):
+            i, v = op.decode(msgs[r])
+            mag[i] += np.abs(v.astype(np.float64))
+        err = np.abs(out.cpu().numpy().astype(np.float64) - want)
+        assert np.all(err <= 1e-6 * (mag / R + np.abs(want)) + 1e-38), f"master line off by {err.max()}"
+        assert q.bits_sent(run.msg) == [op.bits_sent(msgs[r]) for r in range(R)]
