@@ -17,7 +17,7 @@ _SRC = os.path.join(_HERE, "qsl_oracle.cpp")
 _LIB = os.path.join(_HERE, "libqsl_oracle.so")
 
 TOPK, RANDK = 0, 1
-QSGD, SIGN_L1, SIGN_L2, FP32, QSGD_SCALED = 0, 1, 2, 3, 4
+QSGD, SIGN_L1, SIGN_L2, FP32, QSGD_SCALED, SIGN_L3, SIGN_L4 = 0, 1, 2, 3, 4, 5, 6
 DENSE_FORMAT = 0x100          # added to the quantiser number: the index-free format of an operator that keeps every coordinate
 STREAM_SELECT, STREAM_QUANT = 0, 1
 
@@ -153,7 +153,7 @@ class OracleOp:
         for _coordinate in range(self.K):
             if self.quantizer == FP32:
                 bits += 32
-            elif self.quantizer in (SIGN_L1, SIGN_L2):
+            elif self.quantizer in (SIGN_L1, SIGN_L2, SIGN_L3, SIGN_L4):
                 bits += 1
             else:
                 bits += len(format(self.s, "b")) + 1     # a level in 0..s, then the sign

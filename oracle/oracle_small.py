@@ -47,6 +47,23 @@ def _round_fraction_to_double(q: Fraction) -> float:
     return q.numerator / q.denominator
 
 
+def cube_root_fixed(x: float) -> float:
+    """The cube root as the method takes it for m = 3: a start value from the binary exponent, then eight Newton
+    steps y <- (2 y + x / y^2) / 3, every operation one IEEE double operation (Python floats are)."""
+    if not x > 0.0:
+        return 0.0
+    mant, e = math.frexp(x)                       # x = mant * 2^e, 0.5 <= mant < 1: binary exponent E = e - 1
+    E = e - 1
+    q, r = divmod(E, 3)                           # floor division: r in {0, 1, 2}
+    y = math.ldexp(1.0, q) * (1.0, 1.2599210498948732, 1.5874010519681994)[r]
+    for _ in range(8):
+        t = y * y
+        u = x / t
+        w = 2.0 * y
+        y = (w + u) / 3.0
+    return y
+
+
 def compress(m, delta, d, seg_offset, seg_k, s, sparsifier, quantizer, seed, worker, rnd, dense=False):
     m = np.asarray(m, dtype=f32)
     delta = np.asarray(delta, dtype=f32)
@@ -97,9 +114,15 @@ def compress(m, delta, d, seg_offset, seg_k, s, sparsifier, quantizer, seed, wor
             if quantizer == 1:
                 total = sum(Fraction(float(abs(x))) for x in vs)
                 c = f32(_round_fraction_to_double(total) / float(k))
-            else:                                       # ||v_S||_2 / k
+            elif quantizer == 2:                        # ||v_S||_2 / k
                 total = sum(Fraction(float(x)) ** 2 for x in vs)
                 c = f32(math.sqrt(_round_fraction_to_double(total)) / float(k))
+            elif quantizer == 5:                        # ||v_S||_3 / k (Lemma 3, m = 3)
+                total = sum(Fraction(float(abs(x))) ** 3 for x in vs)
+                c = f32(cube_root_fixed(_round_fraction_to_double(total)) / float(k))
+            else:                                       # ||v_S||_4 / k (Lemma 3, m = 4)
+                total = sum(Fraction(float(x)) ** 4 for x in vs)
+                c = f32(math.sqrt(math.sqrt(_round_fraction_to_double(total))) / float(k))
             for i, x in zip(S, vs):
                 neg = bool(x < 0)
                 sel.append(i); levels.append(1); negs.append(neg); gvals.append(-c if neg else c)

@@ -84,11 +84,12 @@ uint32_t random_word(uint64_t seed, uint32_t worker, uint64_t round, uint32_t st
 }
 
 // ---------------------------------------------------------------------------
-// Exact sums.  A wide fixed-point integer (640 bits) holds sum_i M_i * 2^{p_i}
-// exactly; it is then rounded once, to nearest-even, to a double.
+// Exact sums.  A wide fixed-point integer (1408 bits: enough for 2^32 fourth powers of
+// fp32 values) holds sum_i M_i * 2^{p_i} exactly; it is then rounded once, to nearest-even,
+// to a double.
 // ---------------------------------------------------------------------------
 struct WideInt {
-  static const int LIMBS = 10;
+  static const int LIMBS = 22;
   uint64_t limb[LIMBS];
   WideInt() { std::memset(limb, 0, sizeof limb); }
   // add mant * 2^shift  (mant < 2^48, so the shifted value spans at most two limbs)
@@ -100,6 +101,21 @@ struct WideInt {
     uint64_t carry = 0;
     uint64_t t = limb[j] + lo; carry = t < lo; limb[j] = t; ++j;
     t = limb[j] + hi; uint64_t c2 = t < hi; t += carry; c2 |= (t < carry); limb[j] = t; carry = c2; ++j;
+    while (carry && j < static_cast<unsigned>(LIMBS)) { limb[j] += 1; carry = (limb[j] == 0); ++j; }
+  }
+  // add (hi * 2^64 + lo) * 2^shift: the value spans at most three limbs
+  void add_shifted128(uint64_t lo, uint64_t hi, unsigned shift) {
+    const unsigned w = shift / 64, b = shift % 64;
+    const uint64_t part[3] = {lo << b, b ? ((lo >> (64 - b)) | (hi << b)) : hi, b ? (hi >> (64 - b)) : 0};
+    uint64_t carry = 0;
+    unsigned j = w;
+    for (int i = 0; i < 3 && j < static_cast<unsigned>(LIMBS); ++i, ++j) {
+      const uint64_t t = limb[j] + part[i];
+      const uint64_t c1 = t < part[i];
+      const uint64_t t2 = t + carry;
+      const uint64_t c2 = t2 < carry;
+      limb[j] = t2; carry = c1 | c2;
+    }
     while (carry && j < static_cast<unsigned>(LIMBS)) { limb[j] += 1; carry = (limb[j] == 0); ++j; }
   }
   int top_bit() const {  // index of the highest set bit, -1 if zero
@@ -157,6 +173,41 @@ double exact_sum_of_abs(const float* x, uint64_t n) {
   return acc.to_double(-149);
 }
 
+// RN64( sum_i |x_i|^p ), p = 3 or 4, with the sum taken exactly (|x|^p = M^p * 2^{p E}, M^p < 2^96)
+double exact_sum_of_power(const float* x, uint64_t n, unsigned p) {
+  WideInt acc;
+  for (uint64_t i = 0; i < n; ++i) {
+    uint32_t M; int E; split_abs(x[i], &M, &E);
+    if (!M) continue;
+    unsigned __int128 P = M;
+    for (unsigned j = 1; j < p; ++j) P *= M;
+    acc.add_shifted128(static_cast<uint64_t>(P), static_cast<uint64_t>(P >> 64), p * static_cast<unsigned>(E + 149));
+  }
+  return acc.to_double(-149 * static_cast<int>(p));
+}
+
+// Cube root of a positive normal double by a fixed sequence of IEEE operations, so that every implementation that
+// performs them one by one gets the same bits: start from 2^floor(E/3) times 1, 2^(1/3) or 2^(2/3) (E the binary
+// exponent; at most 26 % below the root), then eight Newton steps y <- (2 y + x / y^2) / 3, each of which squares
+// the relative error.  Lemma 3 fixes the norm, not how its root is rounded: this is the reading taken.
+double cube_root_fixed(double x) {
+  if (!(x > 0.0)) return 0.0;
+  uint64_t b; std::memcpy(&b, &x, 8);
+  const int E = static_cast<int>(b >> 52) - 1023;
+  int q = E / 3, r = E % 3;
+  if (r < 0) { r += 3; q -= 1; }
+  const uint64_t yb = static_cast<uint64_t>(q + 1023) << 52;
+  double y; std::memcpy(&y, &yb, 8);
+  y = y * (r == 0 ? 1.0 : r == 1 ? 1.2599210498948732 : 1.5874010519681994);
+  for (int it = 0; it < 8; ++it) {
+    const double t = y * y;
+    const double u = x / t;
+    const double w = 2.0 * y;
+    y = (w + u) / 3.0;
+  }
+  return y;
+}
+
 // ---------------------------------------------------------------------------
 // Wire format helpers
 // ---------------------------------------------------------------------------
@@ -193,7 +244,8 @@ struct BitReader {
 enum : uint32_t { SPARS_TOPK = 0, SPARS_RANDK = 1 };
 // QSGD (Definition 1, example 1); Sign scaled by ||v_S||_1 / k or ||v_S||_2 / k (Lemma 3 with m = 1, 2);
 // no quantisation at all (the TopK-SGD comparison scheme of Section 5); QSGD divided by 1 + beta_{k,s} (Lemma 2).
-enum : uint32_t { QUANT_QSGD = 0, QUANT_SIGN_L1 = 1, QUANT_SIGN_L2 = 2, QUANT_FP32 = 3, QUANT_QSGD_SCALED = 4 };
+enum : uint32_t { QUANT_QSGD = 0, QUANT_SIGN_L1 = 1, QUANT_SIGN_L2 = 2, QUANT_FP32 = 3, QUANT_QSGD_SCALED = 4,
+                  QUANT_SIGN_L3 = 5, QUANT_SIGN_L4 = 6 };
 inline bool is_qsgd(uint32_t q) { return q == QUANT_QSGD || q == QUANT_QSGD_SCALED; }
 // Added to the quantiser number by the callers of this file: the message has the index-free format of an operator
 // that keeps every coordinate (k = size in every segment: the error-feedback schemes without sparsification that
@@ -228,7 +280,7 @@ struct Layout {
     }
     if (is_qsgd(quantizer) && (s == 0 || s > 32768)) return false;
     if (dense) for (uint32_t l = 0; l < L; ++l) if (k[l] != off[l + 1] - off[l]) return false;
-    return quantizer <= 4;
+    return quantizer <= QUANT_SIGN_L4;
   }
   uint32_t segment_of(uint64_t i) const {
     uint32_t l = 0; while (off[l + 1] <= i) ++l; return l;
@@ -368,10 +420,14 @@ int qslo_compress(const float* m, const float* delta, float* m_out, uint64_t d, 
       for (uint32_t j = 0; j < kl; ++j) { neg[base + j] = vs[j] < 0.0f; lev[base + j] = 1; g[base + j] = vs[j]; }
       nnz[l] = kl;
     } else {
-      // Step 3 (Lemma 3): c = || v_S ||_m / k, m = 1 or 2.
-      const float c = quantizer == QUANT_SIGN_L1
-                          ? static_cast<float>(exact_sum_of_abs(vs.data(), kl) / static_cast<double>(kl))
-                          : static_cast<float>(std::sqrt(exact_sum_of_squares(vs.data(), kl)) / static_cast<double>(kl));
+      // Step 3 (Lemma 3): c = || v_S ||_m / k, m = 1 .. 4: the exact sum of the m-th powers rounded to double,
+      // its m-th root in double, the division by k in double, one rounding to float.
+      double norm;
+      if (quantizer == QUANT_SIGN_L1) norm = exact_sum_of_abs(vs.data(), kl);
+      else if (quantizer == QUANT_SIGN_L2) norm = std::sqrt(exact_sum_of_squares(vs.data(), kl));
+      else if (quantizer == QUANT_SIGN_L3) norm = cube_root_fixed(exact_sum_of_power(vs.data(), kl, 3));
+      else norm = std::sqrt(std::sqrt(exact_sum_of_power(vs.data(), kl, 4)));
+      const float c = static_cast<float>(norm / static_cast<double>(kl));
       scale[l] = c;
       // Step 4 (Definition 2): +c where v_i >= 0 (zero included), -c where v_i < 0.
       for (uint32_t j = 0; j < kl; ++j) {

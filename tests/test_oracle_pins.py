@@ -287,7 +287,8 @@ def test_sign_l2_scaling_closed_form_and_compression():
 
 @pytest.mark.parametrize("sparsifier", [O.TOPK, O.RANDK])
 def test_norm_scaling_with_m_above_2_is_dominated_by_the_two_built_scalings(sparsifier):
-    """Lemma 3 allows any norm index m for the scale c_m = ||v_S||_m / k.  With the selected set S fixed, the error
+    """Why m = 1, 2 are the scalings to use (m = 3, 4 are built as well, larger m are not).
+    Lemma 3 allows any norm index m for the scale c_m = ||v_S||_m / k.  With the selected set S fixed, the error
     ||c sign(v_S) - v||^2 = ||v||^2 - 2 c ||v_S||_1 + k c^2 is a parabola in c whose minimum sits at c_1 = ||v_S||_1 / k
     (the m = 1 scale); norms do not grow with m, so c_1 >= c_2 >= c_3 >= ... and the error can only grow with m: m = 1
     and m = 2 (both built) are at least as good as every larger m on every input, as the coefficient
@@ -309,8 +310,11 @@ def test_norm_scaling_with_m_above_2_is_dominated_by_the_two_built_scalings(spar
 
         c = {m: (a ** m).sum() ** (1.0 / m) / k for m in (1, 2, 3, 4, 8)}
         c["inf"] = a.max() / k
-        # the two built scales are the m = 1 and m = 2 members of the family
+        # the built scales are the m = 1 .. 4 members of the family
         assert abs(float(r1["scales"][0]) - c[1]) <= 1e-6 * c[1] and abs(float(r2["scales"][0]) - c[2]) <= 1e-6 * c[2]
+        for qz, m in ((O.SIGN_L3, 3), (O.SIGN_L4, 4)):
+            rm = O.OracleOp(d, off, kk, 1, sparsifier, qz, 9).compress(np.zeros(d, f32), v, 0, 0)
+            assert np.array_equal(S, rm["sel_idx"].astype(np.int64)) and abs(float(rm["scales"][0]) - c[m]) <= 1e-6 * c[m]
         order = [1, 2, 3, 4, 8, "inf"]
         for lo, hi in zip(order, order[1:]):
             assert c[lo] >= c[hi] * (1 - 1e-12)
@@ -323,6 +327,87 @@ def test_norm_scaling_with_m_above_2_is_dominated_by_the_two_built_scalings(spar
         if sparsifier == O.TOPK:
             for m in (2, 3, 4, 8):
                 assert err(c[m]) <= (1 - k ** (2.0 / m - 1) / d) * x2 * (1 + 1e-12)
+
+
+def _iroot(n: int, m: int) -> int:
+    """floor of the m-th root of a non-negative integer (Newton on integers)"""
+    if n < 2:
+        return n
+    x = 1 << -(-n.bit_length() // m)
+    while True:
+        y = ((m - 1) * x + n // x ** (m - 1)) // m
+        if y >= x:
+            return x
+        x = y
+
+
+def _exact_norm_bounds(values, m, extra_bits=96):
+    """(lo, hi) rationals with lo <= ||values||_m <= hi, hi - lo = 2^-extra_bits / q, from exact integer arithmetic"""
+    from fractions import Fraction
+    total = sum(Fraction(float(abs(x))) ** m for x in values)
+    p, q = total.numerator, total.denominator
+    r = _iroot(p * q ** (m - 1) << (m * extra_bits), m)          # floor(2^B q^(1/m)... ) : root(p/q) = root(p q^(m-1)) / q
+    return Fraction(r, q << extra_bits), Fraction(r + 1, q << extra_bits)
+
+
+def test_cube_root_by_fixed_operations_is_the_cube_root():
+    """The m = 3 scale takes its root by a start value and eight Newton steps in double: over the whole range the sum
+    of cubes can take (2^-447 .. 2^416) the result is within two units in the last place of the true cube root."""
+    from fractions import Fraction
+    from oracle.oracle_small import cube_root_fixed
+    rng = np.random.default_rng(33)
+    xs = [math.ldexp(float(rng.uniform(1, 2)), int(e)) for e in rng.integers(-447, 417, size=400)]
+    xs += [math.ldexp(1.0, e) for e in (-447, -446, -445, -3, -2, -1, 0, 1, 2, 3, 414, 415, 416)] + [27.0, 1e-300 * 1e200, 8.0]
+    for x in xs:
+        y = cube_root_fixed(x)
+        fx = Fraction(x)
+        lo, hi = Fraction(math.nextafter(math.nextafter(y, 0.0), 0.0)), Fraction(math.nextafter(math.nextafter(y, math.inf), math.inf))
+        assert lo ** 3 <= fx <= hi ** 3, x
+    assert cube_root_fixed(27.0) == 3.0 and cube_root_fixed(8.0) == 2.0 and cube_root_fixed(0.0) == 0.0
+
+
+@pytest.mark.parametrize("quantizer,m", [(O.SIGN_L3, 3), (O.SIGN_L4, 4)])
+@pytest.mark.parametrize("sparsifier", [O.TOPK, O.RANDK])
+def test_sign_scaled_by_the_m_norm_against_exact_integer_roots(quantizer, m, sparsifier):
+    """Lemma 3 with m = 3, 4: c = ||v_S||_m / k.  The scale the oracle sends is the fp32 nearest to the exact value
+    (computed here with integer m-th roots of exact rational power sums), on inputs that span the fp32 range; the
+    output is +-c on the selected set, the compression error obeys the identity of the lemma's proof and its
+    coefficient gamma_m = k^(2/m - 1) / d (Top_k)."""
+    from fractions import Fraction
+    rng = np.random.default_rng(35 + m)
+    cases = [(3000, 64, 1.5, 0), (500, 500, 1.0, 0), (64, 1, 2.0, 0), (2000, 333, 0.5, 0), (900, 40, 3.0, -100), (900, 40, 3.0, 80)]
+    for d, k, spread, shift in cases:
+        v = (rng.standard_normal(d) * np.exp(spread * rng.standard_normal(d))).astype(np.float64) * 2.0 ** shift
+        v = v.astype(f32)
+        assert np.all(np.isfinite(v))
+        off, kk = one_seg(d, k)
+        res = O.OracleOp(d, off, kk, 1, sparsifier, quantizer, 11).compress(np.zeros(d, f32), v, 2, 3)
+        S = res["sel_idx"].astype(np.int64)
+        if sparsifier == O.TOPK:
+            assert np.array_equal(S, brute_topk(v, k).astype(np.int64))
+        c = res["scales"][0]
+        lo, hi = _exact_norm_bounds(v[S], m)
+        lo, hi = lo / k, hi / k
+        fc = Fraction(float(c))
+        ulp = Fraction(float(np.spacing(f32(c)))) if c > 0 else Fraction(2.0 ** -149)
+        # nearest fp32 (a sum this far from a rounding tie leaves no room for the double arithmetic in between to matter)
+        assert fc - hi <= ulp * Fraction(500001, 1000000) and lo - fc <= ulp * Fraction(500001, 1000000), (d, k, float(c))
+        assert np.array_equal(bits_of(res["g_val"]), bits_of(np.where(v[S] < 0, -c, c).astype(f32)))
+        assert res["bits"] == 64 + k * ((d - 1).bit_length() + 1)
+        if shift == 0:
+            x2 = (v.astype(np.float64) ** 2).sum()
+            g = np.zeros(d); g[S] = res["g_val"]
+            err = ((g - v.astype(np.float64)) ** 2).sum()
+            n1 = np.abs(v[S].astype(np.float64)).sum()
+            cf = float(c)
+            assert abs(err - (x2 - 2.0 * cf * n1 + k * cf * cf)) <= 1e-5 * x2
+            if sparsifier == O.TOPK:
+                assert err <= (1 - k ** (2.0 / m - 1) / d) * x2 * (1 + 1e-9)
+    # all-zero kept values: the scale is zero and k entries of +0 are sent, as for m = 1, 2
+    d, k = 50, 7
+    off, kk = one_seg(d, k)
+    res = O.OracleOp(d, off, kk, 1, O.TOPK, quantizer, 1).compress(np.zeros(d, f32), np.zeros(d, f32), 0, 0)
+    assert res["scales"][0] == 0 and np.all(res["g_val"] == 0) and len(res["sel_idx"]) == k
 
 
 def test_no_quantiser_is_top_k_itself():
@@ -505,7 +590,7 @@ def test_randk_inclusion_frequency_and_energy():
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("sparsifier", [O.TOPK, O.RANDK])
 @pytest.mark.parametrize("quantizer,s", [(O.QSGD, 16), (O.QSGD, 3), (O.SIGN_L1, 1), (O.SIGN_L2, 1), (O.FP32, 1),
-                                         (O.QSGD_SCALED, 4)])
+                                         (O.QSGD_SCALED, 4), (O.SIGN_L3, 1), (O.SIGN_L4, 1)])
 def test_oracle_matches_second_statement(sparsifier, quantizer, s):
     rng = np.random.default_rng(81 + s + sparsifier)
     for trial in range(4):
@@ -626,7 +711,7 @@ def read_dense_message(msg, d, L, s, quantizer):
 
 @pytest.mark.parametrize("sparsifier", [O.TOPK, O.RANDK])
 @pytest.mark.parametrize("quantizer,s", [(O.QSGD, 1), (O.QSGD, 2), (O.QSGD, 15), (O.QSGD, 16), (O.QSGD, 255), (O.SIGN_L1, 1),
-                                         (O.SIGN_L2, 1), (O.FP32, 1), (O.QSGD_SCALED, 3)])
+                                         (O.SIGN_L2, 1), (O.FP32, 1), (O.QSGD_SCALED, 3), (O.SIGN_L3, 1), (O.SIGN_L4, 1)])
 def test_index_free_format_carries_the_same_operator_output(sparsifier, quantizer, s):
     rng = np.random.default_rng(300 + s + quantizer)
     d = 777
