@@ -289,7 +289,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": wl.name, "R": R, "d": d, "k": int(wl.K), "s": wl.s, "segments": wl.L,
                    "sparsifier": ["top_k", "rand_k"][wl.sparsifier],
-                   "quantizer": ["qsgd", "sign_l1", "sign_l2", "fp32", "qsgd_scaled"][wl.quantizer],
+                   "quantizer": ["qsgd", "sign_l1", "sign_l2", "fp32", "qsgd_scaled", "sign_l3", "sign_l4"][wl.quantizer],
                    "format": "index-free" if wl.dense else "indices + codes",
                    "error_update": "stand-alone qsl_error_update" if args.standalone_update else "fused",
                    "fresh_delta_buffers": n_buf, "delta": "x - xhat on the fly" if args.from_models else "given",

@@ -72,10 +72,13 @@ typedef enum {
 
 enum { QSL_TOPK = 0, QSL_RANDK = 1 };    /* sparsifier, Section 2.2 */
 /* quantiser: QSGD (Definition 1, example 1); Sign scaled by ||Comp_k(x)||_1 / k (Definition 2, Lemma 3
- * with m = 1) or by ||Comp_k(x)||_2 / k (Lemma 3 with m = 2); none, i.e. Comp_k(x) itself in fp32 (the
+ * with m = 1), by ||Comp_k(x)||_2 / k (m = 2), or by ||Comp_k(x)||_m / k with m = 3, 4 (QSL_SIGN_L3, QSL_SIGN_L4: the
+ * exact sum of the m-th powers rounded to double, its root in double -- two square roots for m = 4, for m = 3 a start
+ * value from the binary exponent and eight Newton steps, every step one IEEE operation -- divided by k in double and
+ * rounded to float); none, i.e. Comp_k(x) itself in fp32 (the
  * TopK-SGD comparison scheme of Section 5); QSGD divided by 1 + beta_{k,s}, beta_{k,s} = min(k/s^2,
  * sqrt(k)/s) (the scaled composition of Lemma 2: same level codes, transmitted norm N / (1 + beta)). */
-enum { QSL_QSGD = 0, QSL_SIGN_L1 = 1, QSL_SIGN_L2 = 2, QSL_FP32 = 3, QSL_QSGD_SCALED = 4 };
+enum { QSL_QSGD = 0, QSL_SIGN_L1 = 1, QSL_SIGN_L2 = 2, QSL_FP32 = 3, QSL_QSGD_SCALED = 4, QSL_SIGN_L3 = 5, QSL_SIGN_L4 = 6 };
 
 /* Parameters of the operator Q Comp_k, in the paper's notation. */
 typedef struct {

@@ -15,7 +15,7 @@ import torch
 from .build import LIB_PATH
 
 TOPK, RANDK = 0, 1
-QSGD, SIGN_L1, SIGN_L2, FP32, QSGD_SCALED = 0, 1, 2, 3, 4
+QSGD, SIGN_L1, SIGN_L2, FP32, QSGD_SCALED, SIGN_L3, SIGN_L4 = 0, 1, 2, 3, 4, 5, 6
 FLAG_NO_FAST_PATH = 1
 FLAG_NO_SMALL_PATH = 2
 FLAG_OWN_V = 4

@@ -133,7 +133,7 @@ static qsl_status check_config(const qsl_config* cfg, uint64_t* K_out) {
   const uint64_t d = cfg->d;
   const uint32_t L = cfg->num_segments;
   if (d == 0 || d >= (1ull << 32) || L == 0 || L > 16384) return QSL_ERR_INVALID_ARG;
-  if (cfg->sparsifier > 1 || cfg->quantizer > 4) return QSL_ERR_INVALID_ARG;
+  if (cfg->sparsifier > 1 || cfg->quantizer > QSL_SIGN_L4) return QSL_ERR_INVALID_ARG;
   if (is_qsgd(cfg->quantizer) && (cfg->s == 0 || cfg->s > 32768)) return QSL_ERR_INVALID_ARG;
   if (cfg->seg_offset[0] != 0 || cfg->seg_offset[L] != d) return QSL_ERR_INVALID_ARG;
   uint64_t K64 = 0;

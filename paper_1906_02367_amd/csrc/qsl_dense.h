@@ -21,23 +21,19 @@ constexpr uint32_t MAX_DENSE_BLOCKS = 1024;  // blocks per worker of the first p
 constexpr uint32_t MAX_ENCODE_BLOCKS = 8192; // ... and of the second, which has no such ending
 
 // digits of |v| (or v^2) straight into a unit's counters in memory (for the few tiles that span several segments)
-__device__ __forceinline__ void add_digits_global(uint64_t* acc, uint32_t bits, bool squares) {
+__device__ __forceinline__ void add_digits_global(uint64_t* acc, uint32_t bits, uint32_t power) {
   const uint32_t ab = bits & 0x7FFFFFFFu;
   const uint32_t ex = ab >> 23, frac = ab & 0x7FFFFFu;
   const uint32_t M = ex ? (frac | 0x800000u) : frac;
   const uint32_t e1 = ex ? ex : 1u;
   if (M == 0) return;
   auto add = [&](uint32_t q, uint64_t x) { if (x) atomicAdd(reinterpret_cast<unsigned long long*>(acc + q), static_cast<unsigned long long>(x)); };
-  if (squares) {
-    const uint64_t sq = static_cast<uint64_t>(M) * M;
-    const uint32_t p = 2u * e1 - 2u, q = p >> 5, r = p & 31u;
-    const uint64_t lo = sq << r, hi = r ? (sq >> (64 - r)) : 0;
-    add(q, lo & 0xFFFFFFFFu); add(q + 1, lo >> 32); add(q + 2, hi);
-  } else {
-    const uint32_t p = e1 - 1u, q = p >> 5, r = p & 31u;
-    const uint64_t sh = static_cast<uint64_t>(M) << r;
-    add(q, sh & 0xFFFFFFFFu); add(q + 1, sh >> 32);
-  }
+  uint64_t lo, hi;                                         // M^power < 2^96
+  power_of_mantissa(M, power, &lo, &hi);
+  const uint32_t p = power * (e1 - 1u), q = p >> 5, r = p & 31u;
+  const uint64_t a0 = lo << r;
+  const uint64_t a1 = (hi << r) | (r ? lo >> (64 - r) : 0);
+  add(q, a0 & 0xFFFFFFFFu); add(q + 1, a0 >> 32); add(q + 2, a1 & 0xFFFFFFFFu); add(q + 3, a1 >> 32);
 }
 
 // the tiles [t_lo, t_hi) of block b out of nb
@@ -52,9 +48,10 @@ __global__ __launch_bounds__(BLOCK) void k_dense_norm(DevCtx c, const float* m, 
                                                       float* m_out) {
   __shared__ uint64_t acc[ACC_ROWS * (ACC_SLOTS + 1)];
   const uint32_t w = blockIdx.y, wave = threadIdx.x >> 6, lane = lane_id();
-  const bool squares = wants_squares(c.quantizer), need_norm = c.quantizer != QSL_FP32;
-  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
-  for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;
+  const uint32_t power = norm_power(c.quantizer);
+  const bool need_norm = c.quantizer != QSL_FP32;
+  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * acc_stride(c.quantizer);
+  for (uint32_t i = threadIdx.x; i < ACC_ROWS * acc_stride(c.quantizer); i += BLOCK) acc[i] = 0;
   __syncthreads();
   const uint64_t row = static_cast<uint64_t>(w) * c.d;
   uint64_t t_lo, t_hi;
@@ -66,13 +63,13 @@ __global__ __launch_bounds__(BLOCK) void k_dense_norm(DevCtx c, const float* m, 
     __syncthreads();
     if (cur != 0xFFFFFFFFu) {
       uint64_t* ga = c.norm_acc + (static_cast<uint64_t>(w) * c.L + cur) * ACC_SLOTS;
-      for (uint32_t s = wave; s < ACC_SLOTS; s += BLOCK / 64) {
-        uint64_t x = lane < ACC_ROWS ? acc[lane * (ACC_SLOTS + 1) + s] : 0;
+      for (uint32_t s = wave; s < acc_slots(c.quantizer); s += BLOCK / 64) {
+        uint64_t x = lane < ACC_ROWS ? acc[lane * acc_stride(c.quantizer) + s] : 0;
         x = wave_sum64(x);
         if (lane == 0 && x) atomicAdd(reinterpret_cast<unsigned long long*>(ga + s), static_cast<unsigned long long>(x));
       }
       __syncthreads();
-      for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;
+      for (uint32_t i = threadIdx.x; i < ACC_ROWS * acc_stride(c.quantizer); i += BLOCK) acc[i] = 0;
       __syncthreads();
     }
   };
@@ -113,7 +110,7 @@ __global__ __launch_bounds__(BLOCK) void k_dense_norm(DevCtx c, const float* m, 
       for (uint32_t q = 0; q < 4; ++q) {
         const uint64_t e = base + q * 1024 + threadIdx.x * 4;
 #pragma unroll
-        for (uint32_t j = 0; j < 4; ++j) if (e + j < c.d) add_digits(mine, __float_as_uint(v[q][j]), squares);
+        for (uint32_t j = 0; j < 4; ++j) if (e + j < c.d) add_digits(mine, __float_as_uint(v[q][j]), power);
       }
     } else {                                          // several segments in one tile: each coordinate to its own unit's counters
       flush(); cur = 0xFFFFFFFFu;
@@ -124,7 +121,7 @@ __global__ __launch_bounds__(BLOCK) void k_dense_norm(DevCtx c, const float* m, 
         for (uint32_t j = 0; j < 4; ++j)
           if (e + j < c.d) {
             const uint32_t seg = seg_of_coord(c, static_cast<uint32_t>(e + j));
-            add_digits_global(c.norm_acc + (static_cast<uint64_t>(w) * c.L + seg) * ACC_SLOTS, __float_as_uint(v[q][j]), squares);
+            add_digits_global(c.norm_acc + (static_cast<uint64_t>(w) * c.L + seg) * ACC_SLOTS, __float_as_uint(v[q][j]), power);
           }
       }
     }

@@ -14,10 +14,29 @@ namespace {
 // digits -> one correctly rounded double -> the fp32 scale of the unit.  Called by all 64 lanes of a
 // wave with the same arguments; lane i holds digit counter i, everything else is shuffles and ballots
 // (a per-thread digit array would live in scratch memory and cost microseconds).
+// The cube root by a fixed sequence of IEEE double operations (Lemma 3 with m = 3 fixes the norm, not how its root is
+// rounded): 2^floor(E / 3) times 1, 2^(1/3) or 2^(2/3) for the binary exponent E of x, then eight Newton steps
+// y <- (2 y + x / y^2) / 3.  x is zero or a positive normal number.
+__device__ __forceinline__ double cube_root_fixed(double x) {
+  if (!(x > 0.0)) return 0.0;
+  const int E = static_cast<int>(static_cast<unsigned long long>(__double_as_longlong(x)) >> 52) - 1023;
+  int q = E / 3, r = E % 3;
+  if (r < 0) { r += 3; q -= 1; }
+  double y = __longlong_as_double(static_cast<long long>(q + 1023) << 52);
+  y = y * (r == 0 ? 1.0 : r == 1 ? 1.2599210498948732 : 1.5874010519681994);
+  for (int it = 0; it < 8; ++it) {
+    const double t = y * y;
+    const double u = x / t;
+    const double w = 2.0 * y;
+    y = (w + u) / 3.0;
+  }
+  return y;
+}
+
 __device__ float finalize_scale(const uint64_t* acc, uint32_t quantizer, uint32_t k) {
-  const bool squares = wants_squares(quantizer);
+  const int power = static_cast<int>(norm_power(quantizer));
   const uint32_t lane = lane_id();
-  const uint64_t a = lane < ACC_SLOTS ? acc[lane] : 0;
+  const uint64_t a = lane < acc_slots(quantizer) ? acc[lane] : 0;
   // 32-bit digits: low half of the own counter plus the high half of the one below, then ripple the carries
   auto from_below = [&](uint32_t x) { const uint32_t y = __shfl_up(x, 1, WAVE); return lane ? y : 0u; };
   uint64_t t = (a & 0xFFFFFFFFull) + from_below(static_cast<uint32_t>(a >> 32));
@@ -50,10 +69,12 @@ __device__ float finalize_scale(const uint64_t* acc, uint32_t quantizer, uint32_
       if (guard && (sticky || (mant & 1u))) mant += 1;
       e2 = low;
     }
-    S = ldexp(static_cast<double>(mant), e2 + (squares ? -298 : -149));
+    S = ldexp(static_cast<double>(mant), e2 - 149 * power);
   }
   if (quantizer == QSL_SIGN_L1) return static_cast<float>(S / static_cast<double>(k));           // ||v_S||_1 / k
   if (quantizer == QSL_SIGN_L2) return static_cast<float>(sqrt(S) / static_cast<double>(k));     // ||v_S||_2 / k
+  if (quantizer == QSL_SIGN_L3) return static_cast<float>(cube_root_fixed(S) / static_cast<double>(k));     // ||v_S||_3 / k
+  if (quantizer == QSL_SIGN_L4) return static_cast<float>(sqrt(sqrt(S)) / static_cast<double>(k));          // ||v_S||_4 / k
   if (quantizer == QSL_FP32) return 0.0f;
   return static_cast<float>(sqrt(S));                                                            // ||v_S||_2
 }
@@ -158,12 +179,12 @@ __device__ void block_encode_tail(const DevCtx& c, const SegInfo& sg, uint32_t w
   for (uint32_t i = 0; i < PW; ++i) {
     const uint32_t s = wave + i * NW;                // wave-uniform
     x[i] = 0;
-    if (s < ACC_SLOTS) x[i] = wave_sum64(lane < ROWS ? acc[lane * (ACC_SLOTS + 1) + s] : 0);
+    if (s < acc_slots(c.quantizer)) x[i] = wave_sum64(lane < ROWS ? acc[lane * acc_stride(c.quantizer) + s] : 0);
   }
   __syncthreads();
   if (lane == 0) {
 #pragma unroll
-    for (uint32_t i = 0; i < PW; ++i) if (wave + i * NW < ACC_SLOTS) acc[wave + i * NW] = x[i];
+    for (uint32_t i = 0; i < PW; ++i) if (wave + i * NW < acc_slots(c.quantizer)) acc[wave + i * NW] = x[i];
   }
   if (threadIdx.x == 0) *s_count = 0;
   __syncthreads();
@@ -333,7 +354,8 @@ __global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t
     for (uint64_t i = tid; i < static_cast<uint64_t>(c.nfast) * CTR_LINES; i += nth)
       ct[(static_cast<uint64_t>(c.fast_segs[i / CTR_LINES]) * CTR_LINES + i % CTR_LINES) * PAD] = 0;
     uint64_t* na = c.norm_acc + static_cast<uint64_t>(w) * c.L * ACC_SLOTS;
-    for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * ACC_SLOTS; i += nth) na[i] = 0;
+    const uint32_t ns = acc_slots(c.quantizer);
+    for (uint64_t i = tid; i < static_cast<uint64_t>(c.L) * ns; i += nth) na[(i / ns) * ACC_SLOTS + i % ns] = 0;
     // the next call's counters of transmitted entries (the other of the two arrays; nobody uses it during this call)
     {
       const uint64_t gtid = (static_cast<uint64_t>(w) * gridDim.x + blockIdx.x) * BLOCK + threadIdx.x;

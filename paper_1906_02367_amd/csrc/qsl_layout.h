@@ -14,7 +14,7 @@ namespace {
 constexpr uint32_t CHUNK = 1024;           // coordinates one wave streams: 4 x (64 lanes x 4)
 constexpr uint32_t BLOCK = 256;
 constexpr uint32_t HBINS = 4096;           // radix digits: 12 + 12 + 8 bits of the 32-bit rank key
-constexpr uint32_t ACC_SLOTS = 20;         // 32-bit digits of the exact accumulator
+constexpr uint32_t ACC_SLOTS = 40;         // 32-bit digits of the exact accumulator: fourth powers of fp32 values span 4 * 254 + 96 bits, plus 32 for their number
 constexpr uint32_t MAX_SAMPLE_BLOCKS = 128; // blocks (of 1024 threads) per unit of the sampling kernel: 1 .. 128
 constexpr uint32_t MAX_SELECT_BLOCKS = 64; // blocks (of 1024 threads) per unit of the selection kernels: 1 .. 64
 constexpr uint32_t BIG = 1024;             // threads of the sampling and selection kernels
@@ -135,6 +135,14 @@ __device__ __forceinline__ uint32_t lean_bin(uint32_t key, uint32_t T, uint32_t 
 __host__ __device__ __forceinline__ bool is_qsgd(uint32_t q) { return q == QSL_QSGD || q == QSL_QSGD_SCALED; }
 // which exact sum the quantiser's scale needs: squares (l2 norm), magnitudes (l1 norm), none
 __host__ __device__ __forceinline__ bool wants_squares(uint32_t q) { return is_qsgd(q) || q == QSL_SIGN_L2; }
+// ... as the power p of sum |v|^p: 2 (QSGD, sign scaled by the l2 norm), 1, 3 or 4 (Lemma 3 with m = 1, 3, 4)
+__host__ __device__ __forceinline__ uint32_t norm_power(uint32_t q) {
+  return q == QSL_SIGN_L3 ? 3u : q == QSL_SIGN_L4 ? 4u : wants_squares(q) ? 2u : 1u;
+}
+// How many of the ACC_SLOTS digits the quantiser's sum can reach (squares of fp32 values: 2 * 254 + 48 bits, plus 32
+// for their number), and the distance between two accumulator rows in LDS: the kernels clear and add up only these.
+__host__ __device__ __forceinline__ uint32_t acc_slots(uint32_t q) { return norm_power(q) <= 2u ? 20u : ACC_SLOTS; }
+__host__ __device__ __forceinline__ uint32_t acc_stride(uint32_t q) { return acc_slots(q) + 1u; }
 
 __device__ __forceinline__ uint32_t eff_path(const UnitState& us) {
   return us.path == PATH_FAST && us.fell_back ? static_cast<uint32_t>(PATH_FALLBACK) : us.path;

@@ -156,7 +156,7 @@ __global__ __launch_bounds__(BIG) void k_lean_mark(DevCtx c, SegInfo one, uint32
 #pragma unroll
   for (int b = 0; b < 4; ++b) rr[b] = read_slot_row(lu.slots, lu.slot_key, sg.lpc, sg.nwt, lu.r_lo + b, lu.r_hi);
   uint32_t off = waves_before(lu.wcnt, lu.gw);      // where this wave's candidates go in the dense list
-  for (uint32_t i = threadIdx.x; i < LEAN_ROWS * (ACC_SLOTS + 1); i += BIG) acc[i] = 0;     // published by the scan's barriers
+  for (uint32_t i = threadIdx.x; i < LEAN_ROWS * acc_stride(c.quantizer); i += BIG) acc[i] = 0;     // published by the scan's barriers
   // rank k: the threshold's bin; rank r_warm >= k: where the next call's guess goes
   find2_from_top<BIG>(c.hist + lu.u * 3 * HBINS, sg.k, sg.r_warm, scratch, result, false);
   const uint32_t taubin = result[0], above = result[1], in_bin = result[4];
@@ -179,8 +179,8 @@ __global__ __launch_bounds__(BIG) void k_lean_mark(DevCtx c, SegInfo one, uint32
     }
   }
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const bool squares = wants_squares(c.quantizer);
-  uint64_t* mine = acc + ((wave & 7u) * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
+  const uint32_t power = norm_power(c.quantizer);
+  uint64_t* mine = acc + ((wave & 7u) * 8 + (lane & 7u)) * acc_stride(c.quantizer);
   uint32_t* cursor = c.ctr + (lu.u * CTR_LINES + CTR_LIST) * PAD;
   uint4* list = c.tlist + (static_cast<uint64_t>(lu.w) * c.nfast + sg.fidx) * LISTCAP;
   uint32_t n_above = 0;
@@ -192,7 +192,7 @@ __global__ __launch_bounds__(BIG) void k_lean_mark(DevCtx c, SegInfo one, uint32
       lu.d0[p] = make_uint2(idx, bits);
       if (SPARS == QSL_RANDK) lu.d0k[p] = key;
       const uint32_t b = lean_bin(key, T, sh);
-      if (b > taubin) { ++n_above; add_digits(mine, bits, squares); }
+      if (b > taubin) { ++n_above; add_digits(mine, bits, power); }
       else inside = b == taubin && !crowded;
     }
     const uint64_t ib = __ballot(inside);
@@ -238,8 +238,8 @@ __global__ __launch_bounds__(BIG) void k_lean_mark(DevCtx c, SegInfo one, uint32
   if (lane == 0) lu.wsel[lu.gw] = n_above;
   __syncthreads();
   uint64_t* ga = c.norm_acc + lu.u * ACC_SLOTS;
-  for (uint32_t s = wave; s < ACC_SLOTS; s += BIG / 64) {
-    const uint64_t x = wave_sum64(acc[lane * (ACC_SLOTS + 1) + s]);       // LEAN_ROWS = 64 rows: one per lane
+  for (uint32_t s = wave; s < acc_slots(c.quantizer); s += BIG / 64) {
+    const uint64_t x = wave_sum64(acc[lane * acc_stride(c.quantizer) + s]);       // LEAN_ROWS = 64 rows: one per lane
     if (lane == 0 && x) atomicAdd(reinterpret_cast<unsigned long long*>(ga + s), static_cast<unsigned long long>(x));
   }
 }
@@ -292,7 +292,7 @@ __device__ void block_unit(const DevCtx& c, const SegInfo& sg, uint32_t w, uint6
     }
   };
   for (uint32_t i = threadIdx.x; i < HBINS; i += BIG) lh[i] = 0;
-  for (uint32_t i = threadIdx.x; i < LEAN_ROWS * (ACC_SLOTS + 1); i += BIG) acc[i] = 0;
+  for (uint32_t i = threadIdx.x; i < LEAN_ROWS * acc_stride(c.quantizer); i += BIG) acc[i] = 0;
   __syncthreads();
   uint32_t above, bin;
   // the three digits of the k-th largest key
@@ -316,14 +316,14 @@ __device__ void block_unit(const DevCtx& c, const SegInfo& sg, uint32_t w, uint6
   uint32_t my_gt = static_cast<uint32_t>(ex), my_eq = static_cast<uint32_t>(ex >> 32);
   uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
   uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
-  uint64_t* mine = acc + ((wave & 7u) * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
-  const bool squares = wants_squares(c.quantizer);
+  uint64_t* mine = acc + ((wave & 7u) * 8 + (lane & 7u)) * acc_stride(c.quantizer);
+  const uint32_t power = norm_power(c.quantizer);
   if (n_gt != 0 || (n_eq != 0 && my_eq < need)) {
     pass([&](uint32_t e, uint32_t bits, uint32_t key) {
       const bool is_gt = key > tau, is_eq = key == tau;
       if (is_gt || (is_eq && my_eq < need)) {
         const uint32_t pos = my_gt + min(my_eq, need);
-        if (pos < sg.k) { oi[pos] = static_cast<uint32_t>(sg.start) + e; ov[pos] = bits; add_digits(mine, bits, squares); }
+        if (pos < sg.k) { oi[pos] = static_cast<uint32_t>(sg.start) + e; ov[pos] = bits; add_digits(mine, bits, power); }
       }
       my_gt += is_gt; my_eq += is_eq;
     });
@@ -371,7 +371,7 @@ __device__ void block_select_encode(const DevCtx& c, const SegInfo& sg, uint32_t
     }
   };
   for (uint32_t i = threadIdx.x; i < HBINS; i += BIG) lh[i] = 0;
-  for (uint32_t i = threadIdx.x; i < LEAN_ROWS * (ACC_SLOTS + 1); i += BIG) acc[i] = 0;
+  for (uint32_t i = threadIdx.x; i < LEAN_ROWS * acc_stride(c.quantizer); i += BIG) acc[i] = 0;
   __syncthreads();
   uint32_t prefix = 0, k_rem = sg.k, above, idx, bits, key;
   for (uint64_t i = threadIdx.x; i < n; i += BIG) { load(i, &idx, &bits, &key); atomicAdd(&lh[key >> 20], 1u); }
@@ -403,8 +403,8 @@ __device__ void block_select_encode(const DevCtx& c, const SegInfo& sg, uint32_t
   // ordered pass: key > tau, and the first `need` with key == tau; a thread takes 4 consecutive entries of a tile
   uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
   uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
-  const bool squares = wants_squares(c.quantizer);
-  uint64_t* mine = acc + ((wave & 7u) * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
+  const uint32_t power = norm_power(c.quantizer);
+  uint64_t* mine = acc + ((wave & 7u) * 8 + (lane & 7u)) * acc_stride(c.quantizer);
   uint32_t run_gt = 0, run_eq = 0;
   for (uint64_t base = 0; base < n; base += 4ull * BIG) {
     uint32_t ix[4], bt[4], gm = 0, qm = 0;
@@ -425,7 +425,7 @@ __device__ void block_select_encode(const DevCtx& c, const SegInfo& sg, uint32_t
       const bool is_gt = (gm >> q) & 1u, is_eq = (qm >> q) & 1u;
       if (is_gt || (is_eq && my_eq < need)) {
         const uint32_t pos = my_gt + min(my_eq, need);
-        if (pos < sg.k) { oi[pos] = ix[q]; ov[pos] = bt[q]; add_digits(mine, bt[q], squares); }
+        if (pos < sg.k) { oi[pos] = ix[q]; ov[pos] = bt[q]; add_digits(mine, bt[q], power); }
       }
       my_gt += is_gt; my_eq += is_eq;
     }
@@ -479,7 +479,7 @@ __global__ __launch_bounds__(BIG) void k_lean_emit(DevCtx c, SegInfo one, uint32
   const uint32_t T = us.T, sh = us.sh, taubin = us.taubin;
   const uint32_t k_rem = sg.k - us.above;                         // how many of the threshold bin's candidates are selected (>= 1)
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const bool squares = wants_squares(c.quantizer);
+  const uint32_t power = norm_power(c.quantizer);
   // The loads that depend on nothing are issued together: the list's length and entries (a thread per entry of the
   // whole array; what lies beyond the length is stale and ignored), the digits of the norm, the counts of the waves.
   static_assert(LISTCAP <= BIG, "a thread per list entry");
@@ -487,7 +487,7 @@ __global__ __launch_bounds__(BIG) void k_lean_emit(DevCtx c, SegInfo one, uint32
   const uint32_t n_list = min(c.ctr[(lu.u * CTR_LINES + CTR_LIST) * PAD], LISTCAP);
   uint4 me = make_uint4(0, 0, 0, 0);
   if (threadIdx.x < LISTCAP) me = glist[threadIdx.x];
-  const uint64_t my_digit = threadIdx.x < ACC_SLOTS ? c.norm_acc[lu.u * ACC_SLOTS + threadIdx.x] : 0;
+  const uint64_t my_digit = threadIdx.x < acc_slots(c.quantizer) ? c.norm_acc[lu.u * ACC_SLOTS + threadIdx.x] : 0;
   const uint32_t cnt = lu.wcnt[lu.gw];
   const uint32_t d_off = waves_before(lu.wcnt, lu.gw);
   uint32_t s_off = waves_before(lu.wsel, lu.gw);
@@ -510,12 +510,12 @@ __global__ __launch_bounds__(BIG) void k_lean_emit(DevCtx c, SegInfo one, uint32
     sel = rank < k_rem;
     s_sel[threadIdx.x] = sel;
     if (rank == k_rem - 1) s_tau = me.z;                          // the k-th largest key of the unit
-    if (sel) add_digits(acc, me.y, squares);                      // the rest of the norm (LDS atomics on one row)
+    if (sel) add_digits(acc, me.y, power);                      // the rest of the norm (LDS atomics on one row)
   }
   __syncthreads();
   if (sel && me.z == s_tau) atomicAdd(&s_need, 1u);
   // the scale: the digits k_lean_mark added up, plus the selected entries of the list
-  if (threadIdx.x < ACC_SLOTS) acc[threadIdx.x] += my_digit;
+  if (threadIdx.x < acc_slots(c.quantizer)) acc[threadIdx.x] += my_digit;
   __syncthreads();
   if (wave == 0) {
     const float sc = finalize_scale(acc, c.quantizer, sg.k);

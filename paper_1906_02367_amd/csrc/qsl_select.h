@@ -217,13 +217,23 @@ __device__ __forceinline__ void load_chunk_masks(const float* vp, uint64_t cb, u
 __device__ __forceinline__ void lds_add(uint64_t* p, uint64_t x) {
   atomicAdd(reinterpret_cast<unsigned long long*>(p), static_cast<unsigned long long>(x));
 }
-__device__ __forceinline__ void add_digits(uint64_t* mine, uint32_t bits, bool squares) {
+// M^power (power = 1 .. 4, M < 2^24) as hi * 2^64 + lo
+__device__ __forceinline__ void power_of_mantissa(uint32_t M, uint32_t power, uint64_t* lo, uint64_t* hi) {
+  const uint64_t sq = static_cast<uint64_t>(M) * M;         // < 2^48
+  *hi = 0;
+  if (power == 1) *lo = M;
+  else if (power == 2) *lo = sq;
+  else if (power == 3) { *lo = sq * M; *hi = __umul64hi(sq, M); }
+  else { *lo = sq * sq; *hi = __umul64hi(sq, sq); }
+}
+// |v|^power = M^power * 2^(power (e1 - 150)): its 32-bit digits above 2^(-149 power) into the row
+__device__ __forceinline__ void add_digits(uint64_t* mine, uint32_t bits, uint32_t power) {
   const uint32_t ab = bits & 0x7FFFFFFFu;
   const uint32_t ex = ab >> 23, frac = ab & 0x7FFFFFu;
   const uint32_t M = ex ? (frac | 0x800000u) : frac;       // |v| = M * 2^(max(ex,1) - 150)
   const uint32_t e1 = ex ? ex : 1u;
   if (M == 0) return;
-  if (squares) {
+  if (power == 2) {
     const uint64_t sq = static_cast<uint64_t>(M) * M;       // < 2^48;  v^2 = sq * 2^(2 e1 - 300)
     const uint32_t p = 2u * e1 - 2u;                        // bit position above 2^-298
     const uint32_t q = p >> 5, r = p & 31u;
@@ -231,12 +241,20 @@ __device__ __forceinline__ void add_digits(uint64_t* mine, uint32_t bits, bool s
     const uint64_t hi = r ? (sq >> (64 - r)) : 0;
     lds_add(&mine[q], lo & 0xFFFFFFFFu); lds_add(&mine[q + 1], lo >> 32);
     if (hi) lds_add(&mine[q + 2], hi);
-  } else {
+  } else if (power == 1) {
     const uint32_t p = e1 - 1u;                             // bit position above 2^-149
     const uint32_t q = p >> 5, r = p & 31u;
     const uint64_t sh = static_cast<uint64_t>(M) << r;      // < 2^55
     lds_add(&mine[q], sh & 0xFFFFFFFFu);
     if (sh >> 32) lds_add(&mine[q + 1], sh >> 32);
+  } else {                                                  // cubes and fourth powers: up to 96 bits, four digits
+    uint64_t lo, hi;
+    power_of_mantissa(M, power, &lo, &hi);
+    const uint32_t p = power * (e1 - 1u), q = p >> 5, r = p & 31u;
+    const uint64_t a0 = lo << r;
+    const uint64_t a1 = (hi << r) | (r ? lo >> (64 - r) : 0);
+    lds_add(&mine[q], a0 & 0xFFFFFFFFu); lds_add(&mine[q + 1], a0 >> 32);
+    if (a1) { lds_add(&mine[q + 2], a1 & 0xFFFFFFFFu); if (a1 >> 32) lds_add(&mine[q + 3], a1 >> 32); }
   }
 }
 
@@ -246,7 +264,7 @@ __device__ __forceinline__ void add_digits(uint64_t* mine, uint32_t bits, bool s
 template <int SPARS, bool WRITE>
 __device__ void general_groups(const SegInfo& sg, const float* vp, const RandKey& rk, Thresh th,
                                uint32_t g_lo, uint32_t g_hi, uint32_t gt0, uint32_t eq0, uint32_t* oi, uint32_t* ov,
-                               uint64_t* mine, bool squares, uint32_t* s_cnt /*[2][GGROUP + 1]*/,
+                               uint64_t* mine, uint32_t power, uint32_t* s_cnt /*[2][GGROUP + 1]*/,
                                uint32_t* tot_gt, uint32_t* tot_eq) {
   constexpr uint32_t STAGE = 512;                  // list entries per wave (WRITE only)
   __shared__ uint32_t stage_pos[WRITE ? (BLOCK / 64) * STAGE : 1];
@@ -290,7 +308,7 @@ __device__ void general_groups(const SegInfo& sg, const float* vp, const RandKey
             const uint32_t pos = stage_pos[wave * STAGE + o + lane];
             const uint2 e = stage_iv[wave * STAGE + o + lane];
             oi[pos] = e.x; ov[pos] = e.y;
-            add_digits(mine, e.y, squares);
+            add_digits(mine, e.y, power);
           }
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");      // ... and before the list is refilled
@@ -374,9 +392,9 @@ __global__ __launch_bounds__(BLOCK) void k_full(DevCtx c, const float* v) {
   uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
   uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const bool squares = wants_squares(c.quantizer);
-  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
-  for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;
+  const uint32_t power = norm_power(c.quantizer);
+  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * acc_stride(c.quantizer);
+  for (uint32_t i = threadIdx.x; i < ACC_ROWS * acc_stride(c.quantizer); i += BLOCK) acc[i] = 0;
   __syncthreads();
   const uint64_t ntiles = (sg.size + 4095) / 4096;
   const uint32_t nb = static_cast<uint32_t>(ntiles < MAX_FULL_BLOCKS ? ntiles : MAX_FULL_BLOCKS);
@@ -408,13 +426,13 @@ __global__ __launch_bounds__(BLOCK) void k_full(DevCtx c, const float* v) {
         for (uint32_t j = 0; j < 4; ++j) if (e + j < sg.size) { oi[e + j] = idx[j]; ov[e + j] = bits[j]; }
       }
 #pragma unroll
-      for (uint32_t j = 0; j < 4; ++j) if (e + j < sg.size) add_digits(mine, bits[j], squares);
+      for (uint32_t j = 0; j < 4; ++j) if (e + j < sg.size) add_digits(mine, bits[j], power);
     }
   }
   __syncthreads();
   uint64_t* ga = c.norm_acc + u * ACC_SLOTS;
-  for (uint32_t s = wave; s < ACC_SLOTS; s += BLOCK / 64) {
-    uint64_t x = lane < ACC_ROWS ? acc[lane * (ACC_SLOTS + 1) + s] : 0;
+  for (uint32_t s = wave; s < acc_slots(c.quantizer); s += BLOCK / 64) {
+    uint64_t x = lane < ACC_ROWS ? acc[lane * acc_stride(c.quantizer) + s] : 0;
     x = wave_sum64(x);
     if (lane == 0 && x) atomicAdd(reinterpret_cast<unsigned long long*>(ga + s), static_cast<unsigned long long>(x));
   }
@@ -464,9 +482,9 @@ __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, SegInfo one, con
   Thresh th; th.tau = us.tau; th.need = us.need;
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
-  const bool squares = wants_squares(c.quantizer);
-  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
-  for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;   // published by the barrier below
+  const uint32_t power = norm_power(c.quantizer);
+  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * acc_stride(c.quantizer);
+  for (uint32_t i = threadIdx.x; i < ACC_ROWS * acc_stride(c.quantizer); i += BLOCK) acc[i] = 0;   // published by the barrier below
   // how many selected coordinates precede this block: the sum of the unit's earlier blocks' counts
   {
     const uint2* cc = c.cb_cnt + static_cast<uint64_t>(w) * c.NCB + sg.cb_base;
@@ -485,12 +503,12 @@ __global__ __launch_bounds__(BLOCK) void k_tile_write(DevCtx c, SegInfo one, con
     fallback_range(sg, cb.b, &g_lo, &g_hi);
     uint32_t tg, tq;
     general_groups<SPARS, true>(sg, v + static_cast<uint64_t>(w) * c.d + sg.start, rk, th, g_lo, g_hi, gt0, eq0, oi, ov,
-                                mine, squares, s_cnt, &tg, &tq);
+                                mine, power, s_cnt, &tg, &tq);
   }
   __syncthreads();
   uint64_t* ga = c.norm_acc + u * ACC_SLOTS;
-  for (uint32_t s = wave; s < ACC_SLOTS; s += 4) {
-    uint64_t x = lane < ACC_ROWS ? acc[lane * (ACC_SLOTS + 1) + s] : 0;
+  for (uint32_t s = wave; s < acc_slots(c.quantizer); s += 4) {
+    uint64_t x = lane < ACC_ROWS ? acc[lane * acc_stride(c.quantizer) + s] : 0;
     x = wave_sum64(x);
     if (lane == 0 && x) atomicAdd(reinterpret_cast<unsigned long long*>(ga + s), static_cast<unsigned long long>(x));
   }

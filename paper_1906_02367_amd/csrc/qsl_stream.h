@@ -157,7 +157,7 @@ __device__ void stream_block_unit(const DevCtx& c, const SegInfo& sg, uint64_t u
     }
   }
   for (uint32_t i = threadIdx.x; i < HBINS; i += BLOCK) lh[i] = 0;
-  for (uint32_t i = threadIdx.x; i < ACC_ROWS * (ACC_SLOTS + 1); i += BLOCK) acc[i] = 0;
+  for (uint32_t i = threadIdx.x; i < ACC_ROWS * acc_stride(c.quantizer); i += BLOCK) acc[i] = 0;
   __syncthreads();
   // the three digits of the k-th largest key -- unless the unit keeps every coordinate (a tensor of at most k
   // coordinates under a rule like k_t = min(d_t, 1000), Section 5.1.1): then there is nothing to find
@@ -196,8 +196,8 @@ __device__ void stream_block_unit(const DevCtx& c, const SegInfo& sg, uint64_t u
   __syncthreads();
   uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
   uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
-  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * (ACC_SLOTS + 1);
-  const bool squares = wants_squares(c.quantizer);
+  uint64_t* mine = acc + (wave * 8 + (lane & 7u)) * acc_stride(c.quantizer);
+  const uint32_t power = norm_power(c.quantizer);
   uint32_t base = 0;                                // counts of everything before (wave, t = 0)
   for (uint32_t i = 0; i < wave * 4; ++i) base += s_wt[i];
 #pragma unroll
@@ -214,7 +214,7 @@ __device__ void stream_block_unit(const DevCtx& c, const SegInfo& sg, uint64_t u
           const uint32_t bits = __float_as_uint(v[t][j]);
           if (pos < sg.k) {
             oi[pos] = static_cast<uint32_t>(sg.start + cb + t * 256 + lane * 4 + j); ov[pos] = bits;
-            add_digits(mine, bits, squares);
+            add_digits(mine, bits, power);
           }
         }
         my_gt += is_gt; my_eq += is_eq;

@@ -20,7 +20,7 @@ import numpy as np
 
 BASE_SEED = 190602367
 TOPK, RANDK = 0, 1
-QSGD, SIGN_L1, SIGN_L2, FP32, QSGD_SCALED = 0, 1, 2, 3, 4
+QSGD, SIGN_L1, SIGN_L2, FP32, QSGD_SCALED, SIGN_L3, SIGN_L4 = 0, 1, 2, 3, 4, 5, 6
 RESNET50_D = 25_557_032
 
 

@@ -36,15 +36,16 @@ def test_configs_reduced_size(P, cfg):
 
 @pytest.mark.parametrize("sparsifier", [W.TOPK, W.RANDK])
 @pytest.mark.parametrize("quantizer,s", [(W.QSGD, 15), (W.QSGD, 1), (W.QSGD, 32768), (W.SIGN_L1, 1), (W.SIGN_L2, 1),
-                                         (W.FP32, 1), (W.QSGD_SCALED, 4), (W.QSGD_SCALED, 15)])
+                                         (W.FP32, 1), (W.QSGD_SCALED, 4), (W.QSGD_SCALED, 15), (W.SIGN_L3, 1), (W.SIGN_L4, 1)])
 def test_operator_grid_small(P, sparsifier, quantizer, s):
     wl = custom(40_003, [0, 40_003], [777], s, sparsifier, quantizer, R=3)
     P.run_parity(wl, 2, worker0=5)
 
 
-@pytest.mark.parametrize("quantizer,s", [(W.SIGN_L2, 1), (W.FP32, 1), (W.QSGD_SCALED, 2)])
+@pytest.mark.parametrize("quantizer,s", [(W.SIGN_L2, 1), (W.FP32, 1), (W.QSGD_SCALED, 2), (W.SIGN_L3, 1), (W.SIGN_L4, 1)])
 def test_operator_variants_on_the_fast_path_and_layerwise(P, quantizer, s):
-    # the variants next to the hot path: l2-scaled sign (Lemma 3, m = 2), no quantiser (TopK-SGD), scaled QSGD (Lemma 2)
+    # the variants next to the hot path: sign scaled by the l2, l3, l4 norm (Lemma 3, m = 2, 3, 4), no quantiser
+    # (TopK-SGD), scaled QSGD (Lemma 2)
     wl = custom(1_000_003, [0, 1_000_003], [1000], s, W.TOPK, quantizer, R=2)
     run, op, m_host, _ = P.run_parity(wl, 2, expect_path=0)
     out = torch.zeros(wl.d, dtype=torch.float32, device=run.q.device)
@@ -223,7 +224,8 @@ def test_d_equals_one_and_k_equals_d(P):
 # k = size of the segment (the error-feedback schemes without sparsification that Section 5 compares with, as
 # this operator): no selection at all; ragged sizes around the 4096-coordinate tiles and the 512-block limit
 @pytest.mark.parametrize("sparsifier", [W.TOPK, W.RANDK])
-@pytest.mark.parametrize("quantizer,s", [(W.QSGD, 15), (W.SIGN_L1, 1), (W.SIGN_L2, 1), (W.FP32, 1), (W.QSGD_SCALED, 3)])
+@pytest.mark.parametrize("quantizer,s", [(W.QSGD, 15), (W.SIGN_L1, 1), (W.SIGN_L2, 1), (W.FP32, 1), (W.QSGD_SCALED, 3),
+                                         (W.SIGN_L3, 1), (W.SIGN_L4, 1)])
 def test_every_coordinate_kept(P, sparsifier, quantizer, s):
     for d in (4_097, 300_001, 2_200_003):                        # 2, 74 and 538 tiles (more than the blocks of a unit)
         wl = custom(d, [0, d], [d], s, sparsifier, quantizer, R=2)
@@ -426,7 +428,7 @@ def test_random_word_counter_extremes(P, d, k):
 # the paper's own per-tensor rule (Section 5.1.1): k_t = min(d_t, 1000) for every tensor -- whole small
 # tensors, dense selections in the mid-sized ones, sparse ones in the large
 # ---------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("quantizer,s", [(W.SIGN_L1, 1), (W.QSGD, 15)])
+@pytest.mark.parametrize("quantizer,s", [(W.SIGN_L1, 1), (W.QSGD, 15), (W.SIGN_L3, 1), (W.SIGN_L4, 1)])
 def test_per_tensor_rule_k_min_d_1000(P, quantizer, s):
     base = W.config(4, d=6_000_000, R=2)
     sizes = np.diff(base.seg_offset.astype(np.int64))
@@ -543,7 +545,7 @@ def test_guess_carried_over_layerwise_and_rand_k(P):
 # ---------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("sparsifier", [W.TOPK, W.RANDK])
 @pytest.mark.parametrize("quantizer,s", [(W.QSGD, 15), (W.QSGD, 1), (W.QSGD, 256), (W.QSGD, 32768), (W.SIGN_L1, 1),
-                                         (W.SIGN_L2, 1), (W.FP32, 1), (W.QSGD_SCALED, 3)])
+                                         (W.SIGN_L2, 1), (W.FP32, 1), (W.QSGD_SCALED, 3), (W.SIGN_L3, 1), (W.SIGN_L4, 1)])
 def test_index_free_format(P, sparsifier, quantizer, s):
     from paper_1906_02367_amd import binding as B
     rng = np.random.default_rng(900 + s + quantizer)

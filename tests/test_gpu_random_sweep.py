@@ -37,7 +37,7 @@ def random_case(seed, d_min, d_max, l_choices, r_max):
     else:
         k = np.where(rng.random(L) < 0.3, sizes, np.maximum(1, sizes // int(rng.integers(2, 2000))))
     k = np.minimum(k, sizes).astype(np.uint32)
-    sp, qz = int(rng.integers(0, 2)), int(rng.integers(0, 5))
+    sp, qz = int(rng.integers(0, 2)), int(rng.integers(0, 5))      # (the two later quantisers have sweeps of their own below: the seeds here keep their cases)
     s = int(rng.choice([1, 2, 3, 15, 16, 255, 1000, 32768]))
     R = int(rng.integers(1, r_max + 1))
     flags = int(rng.choice([0, 0, 0, 1, 2, 3]))
@@ -126,7 +126,7 @@ def sequence_case(P, seed):
     off = np.concatenate([[0], cuts, [d]]).astype(np.uint64)
     sizes = np.diff(off.astype(np.int64))
     k = np.minimum(sizes, np.maximum(1, (sizes * rng.uniform(0.0005, 0.01)).astype(np.int64))).astype(np.uint32)
-    qz, s = int(rng.integers(0, 5)), int(rng.choice([1, 3, 16, 255]))
+    qz, s = int(rng.integers(0, 7)), int(rng.choice([1, 3, 16, 255]))
     R = int(rng.integers(1, 4))
     flags = int(rng.choice([0, 0, 0, 8]))                                  # 8: a fresh sample on every call
     wl = W.Workload(2, f"sequence{seed}", R, d, off, k, s, 0, qz, 5, int(rng.integers(0, 2**63)))
@@ -164,7 +164,7 @@ def test_random_index_free(P, block):
         cuts = np.sort(rng.choice(np.arange(1, d), size=L - 1, replace=False)) if L > 1 else np.array([], dtype=np.int64)
         off = np.concatenate([[0], cuts, [d]]).astype(np.uint64)
         k = np.diff(off.astype(np.int64)).astype(np.uint32)
-        qz, s = int(rng.integers(0, 5)), int(rng.choice([1, 2, 3, 15, 16, 255, 1000]))
+        qz, s = int(rng.integers(0, 7)), int(rng.choice([1, 2, 3, 15, 16, 255, 1000]))
         R = int(rng.integers(1, 5))
         wl = W.Workload(2, f"indexfree{seed}", R, d, off, k, s, int(rng.integers(0, 2)), qz, 2, int(rng.integers(0, 2**63)))
         deltas = []
@@ -192,3 +192,17 @@ def test_random_index_free(P, block):
         err = np.abs(out.cpu().numpy().astype(np.float64) - want)
         assert np.all(err <= 1e-6 * (mag / R + np.abs(want)) + 1e-38), f"master line off by {err.max()}"
         assert q.bits_sent(run.msg) == [op.bits_sent(msgs[r]) for r in range(R)]
+
+
+@pytest.mark.parametrize("block", range(2))
+def test_random_sign_scaled_by_higher_norms(P, block):
+    """Lemma 3 with m = 3, 4 over random sizes, segment tables, both sparsifiers, every path and flag: the sums of
+    cubes and fourth powers are exact on both sides, so the scale inside the message is bit-exact too."""
+    for seed in range(63_000 + 15 * block, 63_000 + 15 * (block + 1)):
+        rng, wl, flags, deltas = random_case(seed, 1, 900_000, [1, 1, 2, 5, 17, 60, 400], 4)
+        wl = W.Workload(2, f"higher{seed}", wl.R, wl.d, wl.seg_offset, wl.seg_k, 1, wl.sparsifier, int(rng.choice([W.SIGN_L3, W.SIGN_L4])),
+                        2, wl.seed)
+        if seed % 3 == 0:                                            # values near both ends of the fp32 range
+            deltas = [x * f32(2.0 ** int(rng.integers(-110, 90))) for x in deltas]
+        print(f"case {seed}: d={wl.d} L={wl.L} K={wl.K} sparsifier={wl.sparsifier} quantizer={wl.quantizer} R={wl.R} flags={flags}", flush=True)
+        P.run_parity(wl, 2, flags=flags, deltas=deltas, in_place=bool(rng.integers(0, 2)))
