@@ -371,7 +371,10 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
       // the slot of a chunk (64 to 512 bytes) holds the expected candidates with ~4 sigma to spare;
       // chunks that hold more (chance, or clustered large values) spill to an overflow pool that can
       // take every candidate
-      const double per_chunk = cand / sg.nwt, need = per_chunk + 4.0 * std::sqrt(per_chunk);
+      // (sized for the calls that take their guess from the call before, i.e. all but the first: r_warm candidates;
+      // the sampled guess of a first call may bring up to twice as many, and more of its chunks spill)
+      const double steady = cfg->sparsifier == QSL_TOPK ? static_cast<double>(sg.r_warm) : cand;
+      const double per_chunk = steady / sg.nwt, need = per_chunk + 4.0 * std::sqrt(per_chunk);
       sg.lpc = need <= 7.0 ? 4 : need <= 15.0 ? 8 : need <= 31.0 ? 16 : 32;
       sg.fidx = static_cast<uint32_t>(fast.size());
       fast.push_back(l);
