@@ -188,8 +188,9 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(DevCtx c, const uint8_t* ms
 // earliest listed message that holds a coordinate writes it, the values are added in list order -- but a wave
 // serves 64 entries instead of 8, and kernels of this kind are bound by the number of waves they start
 // (8 messages of 99,400 entries: 104 us with 8 threads per entry, 55 us this way; short messages are the
-// other way round: 8 x 543 entries 8 us against 16 us).
-constexpr uint32_t AGG_GROUP = 8;
+// other way round: 8 x 543 entries 8 us against 16 us).  Four searches at a time: with eight the kernel needs 83
+// registers (5 waves per SIMD) and takes 56.6 us on those messages, with four 51 registers and 53 us, with two 58 us.
+constexpr uint32_t AGG_GROUP = 4;
 
 struct GroupSearch {
   MsgView v[AGG_GROUP];
