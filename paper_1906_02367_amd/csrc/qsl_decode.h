@@ -182,9 +182,9 @@ __global__ __launch_bounds__(BLOCK) void k_aggregate(DevCtx c, const uint8_t* ms
 }
 
 // Long messages (with directories).  One thread per entry: the thread that holds entry j of the q-th listed
-// message looks its coordinate up in the other listed messages itself, eight messages at a time with the eight
+// message looks its coordinate up in the other listed messages itself, AGG_GROUP messages at a time with the
 // binary searches advancing in step (their probes are independent loads, so a step costs one memory round trip,
-// not eight); a directory narrows every search to the entries of one 1024-block.  The rule is the same -- the
+// not one per message); a directory narrows every search to the entries of one 1024-block.  The rule is the same -- the
 // earliest listed message that holds a coordinate writes it, the values are added in list order -- but a wave
 // serves 64 entries instead of 8, and kernels of this kind are bound by the number of waves they start
 // (8 messages of 99,400 entries: 104 us with 8 threads per entry, 55 us this way; short messages are the
@@ -200,7 +200,7 @@ struct GroupSearch {
 
 // positions of coordinate idx in n (<= 8) of the other listed messages: the o-th other message, o = o0 .. o0 + n - 1,
 // is list entry o for o < q and o + 1 from there on.  The loads of a step are unconditional (a closed search
-// reads entry 0 again, which every message buffer has room for) so that all eight are in flight together.
+// reads entry 0 again, which every message buffer has room for) so that all of a group are in flight together.
 // `fixed_pos` >= 0: where the coordinate stands in every message that holds all K entries (a segment kept whole under a
 // quantiser that drops nothing: its entries are at the same places in every such message) -- no search then.
 __device__ __forceinline__ void group_find(const DevCtx& c, const uint8_t* msg, const RowList& rows, uint32_t o0, uint32_t n,
