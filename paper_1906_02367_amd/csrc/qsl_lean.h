@@ -83,9 +83,9 @@ __global__ __launch_bounds__(BIG) void k_lean_hist(DevCtx c, SegInfo one, uint32
   const SegInfo& sg = lu.sg;
   UnitState* usp = &c.units[lu.u];
   const uint32_t T = usp->T, sh = usp->sh;
-  SlotRow rr[4];                                 // four independent accesses in flight; rows past the end read as empty
+  RawRow rr[ROWS_IN_FLIGHT];                     // independent accesses in flight; rows past the end read as empty
 #pragma unroll
-  for (int b = 0; b < 4; ++b) rr[b] = read_slot_row(lu.slots, lu.slot_key, sg.lpc, sg.nwt, lu.r_lo + b, lu.r_hi);   // issued before anything waits
+  for (int b = 0; b < ROWS_IN_FLIGHT; ++b) rr[b] = load_slot_row(lu.slots, lu.slot_key, sg.lpc, sg.nwt, lu.r_lo + b, lu.r_hi);   // issued before anything waits
   for (uint32_t i = threadIdx.x; i < HBINS; i += BIG) lh[i] = 0;
   if (threadIdx.x < CTR_LINES) s_ctr[threadIdx.x] = c.ctr[(lu.u * CTR_LINES + threadIdx.x) * PAD];
   __syncthreads();
@@ -106,14 +106,15 @@ __global__ __launch_bounds__(BIG) void k_lean_hist(DevCtx c, SegInfo one, uint32
   if (failed) return;
   const uint32_t lane = lane_id();
   uint32_t seen = 0;
-  for (uint64_t row0 = lu.r_lo; row0 < lu.r_hi; row0 += 4) {
+  for (uint64_t row0 = lu.r_lo; row0 < lu.r_hi; row0 += ROWS_IN_FLIGHT) {
     if (row0 != lu.r_lo) {
 #pragma unroll
-      for (int b = 0; b < 4; ++b) rr[b] = read_slot_row(lu.slots, lu.slot_key, sg.lpc, sg.nwt, row0 + b, lu.r_hi);
+      for (int b = 0; b < ROWS_IN_FLIGHT; ++b) rr[b] = load_slot_row(lu.slots, lu.slot_key, sg.lpc, sg.nwt, row0 + b, lu.r_hi);
     }
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const SlotRow& r = rr[b];
+    for (int b = 0; b < ROWS_IN_FLIGHT; ++b) {
+      if (row0 + b >= lu.r_hi) break;                              // uniform over the wave
+      const SlotRow r = parse_slot_row(rr[b], sg.lpc);
       seen += r.n;
       if (!r.spill) {
         if (r.has0) atomicAdd(&lh[lean_bin(SPARS == QSL_TOPK ? key_of_value(r.bits0) : r.key0, T, sh)], 1u);
@@ -152,9 +153,9 @@ __global__ __launch_bounds__(BIG) void k_lean_mark(DevCtx c, SegInfo one, uint32
   if (us.fell_back) return;
   const uint32_t T = us.T, sh = us.sh;
   // the loads that depend on nothing are issued first: this wave's first slot rows, the earlier waves' counts
-  SlotRow rr[4];
+  RawRow rr[ROWS_IN_FLIGHT];
 #pragma unroll
-  for (int b = 0; b < 4; ++b) rr[b] = read_slot_row(lu.slots, lu.slot_key, sg.lpc, sg.nwt, lu.r_lo + b, lu.r_hi);
+  for (int b = 0; b < ROWS_IN_FLIGHT; ++b) rr[b] = load_slot_row(lu.slots, lu.slot_key, sg.lpc, sg.nwt, lu.r_lo + b, lu.r_hi);
   uint32_t off = waves_before(lu.wcnt, lu.gw);      // where this wave's candidates go in the dense list
   for (uint32_t i = threadIdx.x; i < LEAN_ROWS * acc_stride(c.quantizer); i += BIG) acc[i] = 0;     // published by the scan's barriers
   // rank k: the threshold's bin; rank r_warm >= k: where the next call's guess goes
@@ -205,14 +206,15 @@ __global__ __launch_bounds__(BIG) void k_lean_mark(DevCtx c, SegInfo one, uint32
       if (inside && q < LISTCAP) list[q] = make_uint4(p, bits, key, idx);
     }
   };
-  for (uint64_t row0 = lu.r_lo; row0 < lu.r_hi; row0 += 4) {
+  for (uint64_t row0 = lu.r_lo; row0 < lu.r_hi; row0 += ROWS_IN_FLIGHT) {
     if (row0 != lu.r_lo) {
 #pragma unroll
-      for (int b = 0; b < 4; ++b) rr[b] = read_slot_row(lu.slots, lu.slot_key, sg.lpc, sg.nwt, row0 + b, lu.r_hi);
+      for (int b = 0; b < ROWS_IN_FLIGHT; ++b) rr[b] = load_slot_row(lu.slots, lu.slot_key, sg.lpc, sg.nwt, row0 + b, lu.r_hi);
     }
 #pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const SlotRow& r = rr[b];
+    for (int b = 0; b < ROWS_IN_FLIGHT; ++b) {
+      if (row0 + b >= lu.r_hi) break;                              // uniform over the wave
+      const SlotRow r = parse_slot_row(rr[b], sg.lpc);
       uint32_t tot;
       const uint32_t pos = off + wave_exclusive_scan32(r.n, &tot);
       off += tot;

@@ -25,18 +25,30 @@ struct SlotRow {
   uint32_t key0, key1;   // Rand_k: their rank keys, from the slot's key line
 };
 
-__device__ __forceinline__ SlotRow read_slot_row(const uint2* slots, const uint32_t* slot_key, uint32_t lpc, uint32_t nwt,
-                                                 uint64_t row, uint64_t nrows) {
+// The 16 bytes of a slot row that this lane reads (and, for Rand_k, the 8 bytes of its key line), as loaded: kept
+// in this form while several rows are in flight, parsed when the row's turn comes (a parsed row takes twice the
+// registers).  Rows past the end, and lanes past the unit's last chunk, read as empty.
+struct RawRow { uint4 q; uint2 kq; };
+
+__device__ __forceinline__ RawRow load_slot_row(const uint2* slots, const uint32_t* slot_key, uint32_t lpc, uint32_t nwt,
+                                                uint64_t row, uint64_t nrows) {
+  RawRow r;
+  const uint32_t lane = lane_id();
+  r.q = make_uint4(0, 0, 0, 0);
+  r.kq = make_uint2(0, 0);
+  if (row < nrows && ((row * 64 + lane) >> (__ffs(lpc) - 1)) < nwt) {                                                 // lpc: 4, 8, 16 or 32
+    r.q = reinterpret_cast<const uint4*>(slots)[row * 64 + lane];
+    if (slot_key) r.kq = reinterpret_cast<const uint2*>(slot_key)[row * 64 + lane];
+  }
+  return r;
+}
+
+__device__ __forceinline__ SlotRow parse_slot_row(const RawRow& raw, uint32_t lpc) {
   SlotRow r;
   const uint32_t lane = lane_id();
   const uint32_t sub = lane & (lpc - 1);
-  uint4 q = make_uint4(0, 0, 0, 0);
-  uint2 kq = make_uint2(0, 0);
-  if (row < nrows && ((row * 64 + lane) >> (__ffs(lpc) - 1)) < nwt) {                                                 // lpc: 4, 8 or 16
-    q = reinterpret_cast<const uint4*>(slots)[row * 64 + lane];
-    if (slot_key) kq = reinterpret_cast<const uint2*>(slot_key)[row * 64 + lane];
-  }
-  r.key0 = kq.x; r.key1 = kq.y;
+  const uint4 q = raw.q;
+  r.key0 = raw.kq.x; r.key1 = raw.kq.y;
   const uint32_t leader = lane & ~(lpc - 1);
   r.count = __shfl(q.x, leader, WAVE);
   r.ovf_at = __shfl(q.y, leader, WAVE);
@@ -50,6 +62,8 @@ __device__ __forceinline__ SlotRow read_slot_row(const uint2* slots, const uint3
   r.idx0 = q.x; r.bits0 = q.y; r.idx1 = q.z; r.bits1 = q.w;
   return r;
 }
+
+constexpr int ROWS_IN_FLIGHT = 8;                 // slot rows a wave of the guessing units' kernels loads at a time
 
 __device__ __forceinline__ uint32_t wave_exclusive_scan32(uint32_t x, uint32_t* total) {
   uint32_t inc = x;
