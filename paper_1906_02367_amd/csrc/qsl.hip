@@ -426,6 +426,12 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   // share is launched only while the host expects failed guesses.  A guessing unit's blocks are also the blocks of
   // k_lean_* (fsels).
   std::vector<SelInfo> fsels, sels_f;
+  // A guessing unit with a single block takes k_lean_one (one launch instead of three) -- unless the context also has
+  // units for k_block_units: those run beside the guessing units' kernels on the second stream, and k_lean_one's
+  // blocks (123 registers, 42 KB of LDS: one per compute unit) leave them no room to (measured on the 161-tensor
+  // table: 541 us per round with it against 536 us with the three kernels, whose blocks share a compute unit).
+  bool one_kernel = true;
+  for (uint32_t l = 0; l < L; ++l) if (segs[l].mode == PATH_SMALL && !segs[l].in_stream) one_kernel = false;
   std::vector<CbInfo> cbs_f;
   uint32_t cb_slots = 0;
   for (uint32_t l = 0; l < L; ++l) {
@@ -434,7 +440,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
     for (uint32_t j = 0; j < sg.nsel; ++j) {
       SelInfo si; si.seg = l; si.j = j; si.pad0 = si.pad1 = 0;
       (guessing ? sels_f : sels).push_back(si);
-      if (guessing) fsels.push_back(si);
+      if (guessing && (sg.nsel > 1 || !one_kernel)) fsels.push_back(si);      // (else the unit goes to k_lean_one)
     }
     sg.wc_base = static_cast<uint32_t>(nwc); nwc += sg.nsel * (BIG / 64);
     sg.cb_base = cb_slots; cb_slots += sg.ncb;
@@ -452,6 +458,10 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   auto by_select_cost = [&](const SelInfo& a, const SelInfo& b) { return select_cost(a) > select_cost(b); };
   std::stable_sort(sels.begin(), sels.end(), by_select_cost);
   std::stable_sort(fsels.begin(), fsels.end(), by_select_cost);
+  std::vector<uint32_t> ones;                       // guessing segments whose units have a single block, heaviest first
+  for (uint32_t l : fast) if (segs[l].nsel == 1 && one_kernel) ones.push_back(l);
+  std::stable_sort(ones.begin(), ones.end(), [&](uint32_t a, uint32_t b) {
+    return static_cast<uint64_t>(segs[a].nwt) * segs[a].lpc > static_cast<uint64_t>(segs[b].nwt) * segs[b].lpc; });
   auto general_cost = [&](uint32_t seg) { return static_cast<double>(segs[seg].nwt) / segs[seg].nsel; };
   std::stable_sort(sels_f.begin(), sels_f.end(), [&](const SelInfo& a, const SelInfo& b) { return general_cost(a.seg) > general_cost(b.seg); });
   auto compact_cost = [&](const CbInfo& ci) {
@@ -496,6 +506,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t o_sels = carve(sizeof(SelInfo) * NSEL), o_cbs = carve(sizeof(CbInfo) * NCB);
   const uint64_t o_samps = carve(sizeof(SelInfo) * samps.size());
   const uint64_t o_fsels = carve(sizeof(SelInfo) * std::max<size_t>(1, fsels.size()));
+  const uint64_t o_ones = carve(4ull * std::max<size_t>(1, ones.size()));
   const uint64_t o_fulls = carve(sizeof(SelInfo) * std::max<size_t>(1, fulls.size()));
   const uint64_t o_fast = carve(4ull * std::max<size_t>(1, fast.size()));
   const uint64_t o_small = carve(4ull * std::max<size_t>(1, smalls.size()));
@@ -554,6 +565,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   upload(o_sels, sels.data(), sizeof(SelInfo) * NSEL);
   upload(o_samps, samps.data(), sizeof(SelInfo) * samps.size());
   upload(o_fsels, fsels.data(), sizeof(SelInfo) * fsels.size());
+  upload(o_ones, ones.data(), 4ull * ones.size());
   upload(o_fulls, fulls.data(), sizeof(SelInfo) * fulls.size());
   upload(o_cbs, cbs.data(), sizeof(CbInfo) * NCB);
   upload(o_fast, fast.data(), 4 * fast.size());
@@ -582,6 +594,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.sels = reinterpret_cast<const SelInfo*>(base + o_sels);
   c.samps = reinterpret_cast<const SelInfo*>(base + o_samps);
   c.fsels = reinterpret_cast<const SelInfo*>(base + o_fsels);
+  c.one_segs = reinterpret_cast<const uint32_t*>(base + o_ones); c.none = static_cast<uint32_t>(ones.size());
   c.cbs = reinterpret_cast<const CbInfo*>(base + o_cbs);
   c.fast_segs = reinterpret_cast<const uint32_t*>(base + o_fast);
   c.small_segs = reinterpret_cast<const uint32_t*>(base + o_small);
@@ -688,7 +701,7 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
                                   uint16_t* sel_level) {
   DevCtx& c = ctx->dc;
   hipStream_t st = ctx->stream;
-  if (static_cast<uint64_t>(std::max(std::max(c.NSEL, c.NCB), std::max(std::max(ctx->nsamp_blocks, c.nblock), c.NSELF + c.nfast))) * R > 0x7FFFFFFFull)
+  if (static_cast<uint64_t>(std::max(std::max(c.NSEL, c.NCB), std::max(std::max(ctx->nsamp_blocks, c.nblock), c.NSELF + c.nfast + c.none))) * R > 0x7FFFFFFFull)
     return QSL_ERR_UNSUPPORTED;                    // the list kernels use one-dimensional grids of (list entries x workers)
   if (xm != nullptr && static_cast<uint64_t>(((c.NWT + 3) / 4 + 7) / 8) * 8 * R > 0x7FFFFFFFull)
     return QSL_ERR_UNSUPPORTED;                    // ... and so does the streaming kernel when it reads x_t
@@ -728,7 +741,7 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   // Units that a single block selects and encodes whole need nothing but v: their kernel runs on a stream of the
   // context's own beside the kernels of the other units (one block works tens of microseconds on a unit of 40,960
   // coordinates) and is joined before the messages are put together.
-  const bool forked = c.nblock != 0 && (c.NSELF != 0 || ctx->n_other != 0);
+  const bool forked = c.nblock != 0 && (c.NSELF != 0 || c.none != 0 || ctx->n_other != 0);
   if (c.nblock) {
     hipStream_t bs = st;
     if (forked) {
@@ -740,6 +753,8 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
     if (forked) QSL_HIP(hipEventRecord(ctx->join_ev, ctx->side));
   }
   if (ctx->nfull_blocks) k_full<<<dim3(ctx->nfull_blocks, R), BLOCK, 0, st>>>(c, m_out);
+  // guessing units of a single block: the whole way from the slots to the encoded entries in one launch
+  if (c.none) k_lean_one<SPARS><<<dim3(c.none * R), BIG, 0, st>>>(c, ctx->segs[0], R, m_out, worker0, round, sel_idx, sel_level, safe ? 1 : 0);
   if (c.NSELF) {                                   // guessing units: candidates' histogram, threshold bin and dense list
     k_lean_hist<SPARS><<<dim3(c.NSELF * R), BIG, 0, st>>>(c, ctx->segs[0], R);
     k_lean_mark<SPARS><<<dim3(c.NSELF * R), BIG, 0, st>>>(c, ctx->segs[0], R);

@@ -103,6 +103,7 @@ struct DevCtx {
   uint2* ovf; uint64_t ovf_stride;      // per worker: overflow pools, for chunks with more candidates than a slot holds
   uint32_t* slot_key; uint32_t* ovf_key; // Rand_k only: the rank key (random word) of every slot element / pool entry
   uint2* d0; uint32_t* d0_key; uint64_t d0_stride;   // per worker: dense, coordinate-ordered candidate lists (+ keys, Rand_k)
+  const uint32_t* one_segs; // the guessing segments whose units have a single block: k_lean_one takes them (heaviest first)
   uint32_t* wave_cnt;   // [R][NWC]: candidates met by each wave of k_lean_hist
   uint32_t* wave_sel;   // [R][NWC]: of these, how many lie in the bins above the threshold's (k_lean_mark)
   uint4* tlist;         // [R][nfast][LISTCAP]: the candidates in the threshold's bin: (place in the dense list, value bits, key, -)
@@ -120,6 +121,7 @@ struct DevCtx {
   uint64_t d, seed;
   uint32_t dense;       // 1: every coordinate is kept and the messages have the index-free format
   uint32_t L, K, NWT, NSEL, NCB, NWC, QB, NSELF, nfast, nblock, Rmax, nbig, s, w_idx, w_lev, w_val, sparsifier, quantizer, cap_words;
+  uint32_t none;        // entries of one_segs
 };
 
 __device__ __forceinline__ uint32_t key_of_value(uint32_t vbits) { return (vbits & 0x7FFFFFFFu) << 1; }

@@ -456,6 +456,7 @@ __global__ __launch_bounds__(BIG) void k_lean_emit(DevCtx c, SegInfo one, uint32
     const uint32_t seg = c.L == 1 ? 0u : c.fast_segs[bi / R], w = bi % R;
     const SegInfo sg = c.L == 1 ? one : c.segs[seg];
     const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
+    if (c.none != 0 && sg.nsel == 1) return;                      // k_lean_one looks after its units itself
     const UnitState us = c.units[u];
     if (us.fell_back) {
       if (safe) return;                                           // the multi-pass kernels of this call took the unit
@@ -580,6 +581,292 @@ __global__ __launch_bounds__(BIG) void k_lean_emit(DevCtx c, SegInfo one, uint32
     s_off += static_cast<uint32_t>(__popcll(tb));
   }
   if (is_qsgd(c.quantizer) && c.L > 1 && lane == 0 && nsent) atomicAdd(&usp->nnz, nsent);
+}
+
+// ------------------------------------------------------------------------------------------------
+// A guessing unit that the plan gives a single block in the three kernels above needs none of their launch
+// boundaries: what they hand each other through memory (histogram, per-wave counts, norm digits, short list) one
+// block can keep in LDS, with barriers where they had kernel ends.  Same steps, same results; the dense list is still
+// written (the rescue of a crowded threshold bin reads it, and so does the ordered output).
+// ------------------------------------------------------------------------------------------------
+template <int SPARS>
+__global__ __launch_bounds__(BIG) void k_lean_one(DevCtx c, SegInfo one, uint32_t R, float* m_out, uint32_t worker0,
+                                                  uint64_t round, uint32_t* dbg_idx, uint16_t* dbg_level, int safe) {
+  __shared__ uint32_t lh[HBINS];
+  __shared__ uint64_t acc[LEAN_ROWS * (ACC_SLOTS + 1)];
+  __shared__ uint4 s_list[LISTCAP];
+  __shared__ uint8_t s_sel[LISTCAP];
+  __shared__ uint64_t scratch[17];
+  __shared__ uint32_t result[6], s_ctr[CTR_LINES], s_wcnt[BIG / 64], s_wsel[BIG / 64], s_nlist, s_tau, s_need, s_count;
+  __shared__ float s_scale;
+  constexpr uint32_t NW = BIG / 64;
+  const uint32_t w = blockIdx.x % R;                 // workers innermost, heaviest units first
+  const uint32_t seg = c.L == 1 ? 0u : c.one_segs[blockIdx.x / R];
+  const SegInfo sg = c.L == 1 ? one : c.segs[seg];
+  const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
+  UnitState* usp = &c.units[u];
+  const UnitState us = *usp;
+  const uint32_t T = us.T, sh = us.sh;
+  const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
+  const uint2* slots = c.slots + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off;
+  const uint2* ovf = c.ovf + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off;
+  const uint32_t* slot_key = SPARS == QSL_RANDK ? c.slot_key + static_cast<uint64_t>(w) * c.slot_stride + sg.slot_off : nullptr;
+  const uint32_t* ovf_key = SPARS == QSL_RANDK ? c.ovf_key + static_cast<uint64_t>(w) * c.ovf_stride + sg.ovf_off : nullptr;
+  uint2* d0 = c.d0 + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+  uint32_t* d0k = c.d0_key + static_cast<uint64_t>(w) * c.d0_stride + sg.d0_off;
+  const uint32_t nrows = static_cast<uint32_t>((static_cast<uint64_t>(sg.nwt) * sg.lpc + 63) >> 6);
+  const uint32_t rpw = (nrows + NW - 1) / NW;        // every wave a contiguous range of slot rows
+  const uint64_t r_lo = static_cast<uint64_t>(wave) * rpw;
+  const uint64_t r_hi = r_lo + rpw < nrows ? r_lo + rpw : nrows;
+  const uint32_t power = norm_power(c.quantizer);
+  const uint32_t st = acc_stride(c.quantizer);
+  constexpr int RIF = SPARS == QSL_RANDK ? 4 : ROWS_IN_FLIGHT;   // rows in flight (a Rand_k row carries its keys: more registers)
+
+  // ---- the candidates' histogram and the number each wave holds (what k_lean_hist does)
+  RawRow rr[RIF];
+#pragma unroll
+  for (int b = 0; b < RIF; ++b) rr[b] = load_slot_row(slots, slot_key, sg.lpc, sg.nwt, r_lo + b, r_hi);
+  for (uint32_t i = threadIdx.x; i < HBINS; i += BIG) lh[i] = 0;
+  for (uint32_t i = threadIdx.x; i < LEAN_ROWS * st; i += BIG) acc[i] = 0;
+  if (threadIdx.x < CTR_LINES) s_ctr[threadIdx.x] = c.ctr[(u * CTR_LINES + threadIdx.x) * PAD];
+  if (threadIdx.x == 0) { s_nlist = 0; s_need = 0; s_tau = 0; s_count = 0; }
+  __syncthreads();
+  uint32_t cand = 0;
+  for (uint32_t i = 0; i < NSUB; ++i) cand += s_ctr[i];
+  const bool failed = s_ctr[CTR_FAIL] != 0 || cand < sg.k || cand > sg.d0_cap;
+  if (threadIdx.x == 0) {
+    usp->cand = cand; usp->fell_back = failed; usp->nnz = 0; usp->crowded = 0;
+    if (failed && SPARS == QSL_TOPK) {                // as in k_lean_hist: towards where the candidates are
+      const uint32_t step = cand < sg.k / 2 ? 1u << 24 : 1u << 22;
+      usp->T_next = cand < sg.k ? (T > step ? T - step : 0u) : (T < 0xFFFFFFFFu - step ? T + step : T);
+      usp->sh_next = sh;
+    }
+  }
+  if (failed) {
+    if (safe) return;                                 // the multi-pass kernels of this call take the unit
+    if (threadIdx.x == 0) *c.host_flag = 1u;
+    __syncthreads();
+    block_select_encode<SPARS, true>(c, sg, w, u, m_out + static_cast<uint64_t>(w) * c.d + sg.start, nullptr, nullptr, sg.size,
+                                     worker0, round, m_out, dbg_idx, dbg_level, lh, acc, scratch, result, &s_scale, &s_count);
+    return;
+  }
+  uint32_t seen = 0;
+  for (uint64_t row0 = r_lo; row0 < r_hi; row0 += RIF) {
+    if (row0 != r_lo) {
+#pragma unroll
+      for (int b = 0; b < RIF; ++b) rr[b] = load_slot_row(slots, slot_key, sg.lpc, sg.nwt, row0 + b, r_hi);
+    }
+#pragma unroll
+    for (int b = 0; b < RIF; ++b) {
+      if (row0 + b >= r_hi) break;
+      const SlotRow r = parse_slot_row(rr[b], sg.lpc);
+      seen += r.n;
+      if (!r.spill) {
+        if (r.has0) atomicAdd(&lh[lean_bin(SPARS == QSL_TOPK ? key_of_value(r.bits0) : r.key0, T, sh)], 1u);
+        if (r.has1) atomicAdd(&lh[lean_bin(SPARS == QSL_TOPK ? key_of_value(r.bits1) : r.key1, T, sh)], 1u);
+      }
+      for (uint64_t spilled = __ballot(r.spill); spilled; spilled &= spilled - 1) {
+        const int holder = __ffsll(static_cast<unsigned long long>(spilled)) - 1;
+        const uint32_t cnt = __shfl(r.count, holder, WAVE), at = __shfl(r.ovf_at, holder, WAVE);
+        for (uint32_t e = lane; e < cnt; e += WAVE) {
+          const uint32_t key = SPARS == QSL_TOPK ? key_of_value(ovf[at + e].y) : ovf_key[at + e];
+          atomicAdd(&lh[lean_bin(key, T, sh)], 1u);
+        }
+      }
+    }
+  }
+  seen = wave_sum(seen);
+  if (lane == 0) s_wcnt[wave] = seen;
+  // the first rows again, for the second walk (they come from the cache now)
+#pragma unroll
+  for (int b = 0; b < RIF; ++b) rr[b] = load_slot_row(slots, slot_key, sg.lpc, sg.nwt, r_lo + b, r_hi);
+  __syncthreads();
+
+  // ---- threshold bin, dense list, what is certainly selected, the short list (what k_lean_mark does)
+  find2_from_top<BIG>(lh, sg.k, sg.r_warm, scratch, result, false);
+  const uint32_t taubin = result[0], above = result[1], in_bin = result[4];
+  const bool crowded = in_bin > LISTCAP;
+  if (threadIdx.x == 0) {
+    usp->taubin = taubin; usp->above = above; usp->crowded = crowded;
+    if (SPARS == QSL_TOPK) {                          // the next call's guess and bin width, as in k_lean_mark
+      const uint32_t tau_lo = T + (taubin << sh);
+      uint32_t T_next;
+      if (result[5] >= sg.r_warm) T_next = T + (result[2] << sh);
+      else { const uint32_t down = max(tau_lo - T, 1u << sh); T_next = T > down ? T - down : 0u; }
+      const uint32_t span = max(tau_lo - T_next, 1u) >> 10;
+      uint32_t sh_next = 0;
+      while (sh_next < 20 && (1u << sh_next) < span) ++sh_next;
+      if (taubin == HBINS - 1) sh_next = min(20u, max(sh_next, sh + 4));
+      usp->T_next = T_next; usp->sh_next = sh_next;
+    }
+  }
+  uint32_t off = 0;
+  for (uint32_t g = 0; g < wave; ++g) off += s_wcnt[g];
+  const uint32_t d_off = off, cnt_w = s_wcnt[wave];
+  uint64_t* mine = acc + ((wave & 7u) * 8 + (lane & 7u)) * st;
+  uint32_t n_above = 0;
+  auto visit = [&](bool has, uint32_t p, uint32_t idx, uint32_t bits, uint32_t key) {
+    bool inside = false;
+    if (has) {
+      d0[p] = make_uint2(idx, bits);
+      if (SPARS == QSL_RANDK) d0k[p] = key;
+      const uint32_t b = lean_bin(key, T, sh);
+      if (b > taubin) { ++n_above; add_digits(mine, bits, power); }
+      else inside = b == taubin && !crowded;
+    }
+    const uint64_t ib = __ballot(inside);
+    if (ib != 0) {                                   // wave-uniform
+      const int first = __ffsll(static_cast<unsigned long long>(ib)) - 1;
+      uint32_t base = 0;
+      if (static_cast<int>(lane) == first) base = atomicAdd(&s_nlist, static_cast<uint32_t>(__popcll(ib)));
+      base = __shfl(base, first, WAVE);
+      const uint32_t q = base + popc_below(ib);
+      if (inside && q < LISTCAP) s_list[q] = make_uint4(p, bits, key, idx);
+    }
+  };
+  for (uint64_t row0 = r_lo; row0 < r_hi; row0 += RIF) {
+    if (row0 != r_lo) {
+#pragma unroll
+      for (int b = 0; b < RIF; ++b) rr[b] = load_slot_row(slots, slot_key, sg.lpc, sg.nwt, row0 + b, r_hi);
+    }
+#pragma unroll
+    for (int b = 0; b < RIF; ++b) {
+      if (row0 + b >= r_hi) break;
+      const SlotRow r = parse_slot_row(rr[b], sg.lpc);
+      uint32_t tot;
+      const uint32_t pos = off + wave_exclusive_scan32(r.n, &tot);
+      off += tot;
+      const bool h0 = !r.spill && r.has0, h1 = !r.spill && r.has1;
+      if (__ballot(h0 || h1) != 0) {
+        visit(h0, pos, r.idx0, r.bits0, SPARS == QSL_TOPK ? key_of_value(r.bits0) : r.key0);
+        visit(h1, pos + (h0 ? 1u : 0u), r.idx1, r.bits1, SPARS == QSL_TOPK ? key_of_value(r.bits1) : r.key1);
+      }
+      for (uint64_t spilled = __ballot(r.spill); spilled; spilled &= spilled - 1) {
+        const int holder = __ffsll(static_cast<unsigned long long>(spilled)) - 1;
+        const uint32_t cnt = __shfl(r.count, holder, WAVE), at = __shfl(r.ovf_at, holder, WAVE);
+        const uint32_t first = __shfl(pos, holder, WAVE);
+        for (uint32_t e0 = 0; e0 < cnt; e0 += WAVE) {
+          const uint32_t e = e0 + lane;
+          uint2 ent = make_uint2(0, 0); uint32_t key = 0;
+          if (e < cnt) { ent = ovf[at + e]; key = SPARS == QSL_TOPK ? key_of_value(ent.y) : ovf_key[at + e]; }
+          visit(e < cnt, first + e, ent.x, ent.y, key);
+        }
+      }
+    }
+  }
+  n_above = wave_sum(n_above);
+  if (lane == 0) s_wsel[wave] = n_above;
+  __threadfence_block();                             // the dense list is read back below, by other waves too
+  __syncthreads();
+  if (crowded) {                                     // more ties in the threshold's bin than the short list holds
+    block_select_encode<SPARS, false>(c, sg, w, u, nullptr, d0, d0k, cand, worker0, round, m_out, dbg_idx, dbg_level, lh, acc,
+                                      scratch, result, &s_scale, &s_count);
+    return;
+  }
+
+  // ---- exact threshold from the short list, the scale, ordered output and codes (what k_lean_emit does)
+  // this wave's first candidates, issued before the reductions
+  uint2 ent_first = make_uint2(0, 0);
+  uint32_t key_first = 0;
+  if (lane < cnt_w) { ent_first = d0[d_off + lane]; if (SPARS == QSL_RANDK) key_first = d0k[d_off + lane]; }
+  {                                                  // the accumulator rows added up into row 0 (as block_encode_tail does)
+    constexpr uint32_t PW = (ACC_SLOTS + NW - 1) / NW;
+    const uint32_t ns = acc_slots(c.quantizer);
+    uint64_t x[PW];
+#pragma unroll
+    for (uint32_t i = 0; i < PW; ++i) {
+      const uint32_t sl = wave + i * NW;
+      x[i] = 0;
+      if (sl < ns) x[i] = wave_sum64(acc[lane * st + sl]);       // LEAN_ROWS = 64 rows: one per lane
+    }
+    __syncthreads();
+    if (lane == 0) {
+#pragma unroll
+      for (uint32_t i = 0; i < PW; ++i) if (wave + i * NW < ns) acc[wave + i * NW] = x[i];
+    }
+  }
+  const uint32_t n_list = min(s_nlist, LISTCAP);
+  const uint32_t k_rem = sg.k - above;
+  uint4 me = make_uint4(0, 0, 0, 0);
+  if (threadIdx.x < n_list) me = s_list[threadIdx.x];
+  __syncthreads();
+  bool sel = false;
+  if (threadIdx.x < n_list) {
+    uint32_t rank = 0;
+    for (uint32_t j = 0; j < n_list; ++j) {
+      const uint4 o = s_list[j];
+      rank += (o.z > me.z || (o.z == me.z && o.x < me.x)) ? 1u : 0u;
+    }
+    sel = rank < k_rem;
+    s_sel[threadIdx.x] = sel;
+    if (rank == k_rem - 1) s_tau = me.z;
+    if (sel) add_digits(acc, me.y, power);
+  }
+  __syncthreads();
+  if (sel && me.z == s_tau) atomicAdd(&s_need, 1u);
+  if (wave == 0) {
+    const float sc = finalize_scale(acc, c.quantizer, sg.k);
+    if (lane == 0) s_scale = sc;
+  }
+  __syncthreads();
+  const UnitScale usc = unit_scale(c, s_scale, sg.k);
+  uint32_t s_off = 0;
+  for (uint32_t g = 0; g < wave; ++g) s_off += s_wsel[g];
+  {
+    uint32_t x = 0;
+    for (uint32_t j = lane; j < n_list; j += WAVE) x += (s_sel[j] && s_list[j].x < d_off) ? 1u : 0u;
+    s_off += wave_sum(x);
+  }
+  const RandKey rk1 = make_rand_key(c.seed, worker0 + w, round, 1);
+  uint32_t nsent = 0;
+  for (uint32_t e0 = 0; e0 < cnt_w; e0 += WAVE) {
+    const uint32_t e = e0 + lane;
+    uint2 ent = make_uint2(0, 0);
+    uint32_t bin = 0;
+    if (e < cnt_w) {
+      uint32_t key = key_first;
+      if (e0 == 0) ent = ent_first;
+      else { ent = d0[d_off + e]; if (SPARS == QSL_RANDK) key = d0k[d_off + e]; }
+      bin = lean_bin(SPARS == QSL_TOPK ? key_of_value(ent.y) : key, T, sh);
+    }
+    bool take = e < cnt_w && bin > taubin;
+    const bool maybe = e < cnt_w && bin == taubin;
+    if (__ballot(maybe) != 0) {
+      for (uint32_t j = 0; j < n_list; ++j) {
+        const uint32_t p = s_list[j].x;
+        if (maybe && p == d_off + e && s_sel[j]) take = true;
+      }
+    }
+    const uint64_t tb = __ballot(take);
+    const uint32_t pos = s_off + popc_below(tb);
+    bool sent = false;
+    if (take && pos < sg.k) {
+      const uint64_t slot = static_cast<uint64_t>(w) * c.K + sg.koff + pos;
+      sent = encode_entry(c, w, slot, ent.x, ent.y, usc, rk1, m_out, dbg_idx, dbg_level);
+    }
+    if (is_qsgd(c.quantizer)) {
+      const uint64_t sb = __ballot(sent);
+      if (sb != 0) {
+        const uint32_t b_first = (sg.koff + s_off) >> 8;
+        const bool in_first = ((sg.koff + pos) >> 8) == b_first;
+        const uint32_t n0 = static_cast<uint32_t>(__popcll(__ballot(sent && in_first)));
+        const uint32_t n1 = static_cast<uint32_t>(__popcll(sb)) - n0;
+        if (lane == 0) {
+          uint32_t* bc = c.blk_cnt + static_cast<uint64_t>(w) * c.QB;
+          if (n0) atomicAdd(&bc[b_first], n0);
+          if (n1) atomicAdd(&bc[b_first + 1], n1);
+          nsent += n0 + n1;
+        }
+      }
+    }
+    s_off += static_cast<uint32_t>(__popcll(tb));
+  }
+  if (is_qsgd(c.quantizer) && c.L > 1 && lane == 0 && nsent) atomicAdd(&s_count, nsent);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    usp->tau = s_tau; usp->need = s_need; usp->n_gt = sg.k - s_need; usp->scale_bits = __float_as_uint(usc.sent);
+    if (is_qsgd(c.quantizer) && c.L > 1) usp->nnz = s_count;
+  }
 }
 
 }  // namespace
