@@ -16,6 +16,7 @@
 //                Top_k / Rand_k, ties to the lower coordinate), the exact ||v_S||_2^2 or ||v_S||_1 (proof of
 //                Lemma 1; Lemma 3, m = 1), QSGD levels (Definition 1, example 1) or signs (Definition 2), and
 //                the error update m <- v - g on the transmitted coordinates (Algorithm 1, worker line 2)
+//   k_lean_one   the same three steps in one launch for a guessing unit that needs only one block
 //   k_block_units  a unit too dense for guessing, of at most 40,960 coordinates: all of the above by one block,
 //                on a second stream beside the guessing units' kernels
 //   k_full       a unit with k = size: nothing to select, the coordinates are copied in order

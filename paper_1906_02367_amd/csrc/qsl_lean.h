@@ -10,6 +10,7 @@
 //                 worker line).  Extra blocks, one per guessing unit, take the units whose guess failed or whose
 //                 threshold bin is too crowded for the list: one block selects exactly, by radix digits, from the
 //                 dense list or from v itself.
+//   k_lean_one    the three steps above in one launch, for a unit that has a single block in them
 // The result never depends on the guess or on the bins: they only decide how much work the exact selection is.
 // Part of the single translation unit qsl.hip (included after qsl_encode.h); not a public header.
 #pragma once
