@@ -540,14 +540,11 @@ __global__ __launch_bounds__(BIG) void k_lean_emit(DevCtx c, SegInfo one, uint32
   uint32_t nsent = 0;
   for (uint32_t e0 = 0; e0 < cnt; e0 += WAVE) {
     const uint32_t e = e0 + lane;
-    uint2 ent = make_uint2(0, 0);
+    const uint2 ent = ent_first;                                  // loaded one step ahead
+    const uint32_t key = key_first;
+    if (e + WAVE < cnt) { ent_first = lu.d0[d_off + e + WAVE]; if (SPARS == QSL_RANDK) key_first = lu.d0k[d_off + e + WAVE]; }
     uint32_t bin = 0;
-    if (e < cnt) {
-      uint32_t key = key_first;
-      if (e0 == 0) ent = ent_first;
-      else { ent = lu.d0[d_off + e]; if (SPARS == QSL_RANDK) key = lu.d0k[d_off + e]; }
-      bin = lean_bin(SPARS == QSL_TOPK ? key_of_value(ent.y) : key, T, sh);
-    }
+    if (e < cnt) bin = lean_bin(SPARS == QSL_TOPK ? key_of_value(ent.y) : key, T, sh);
     bool take = e < cnt && bin > taubin;
     const bool maybe = e < cnt && bin == taubin;
     if (__ballot(maybe) != 0) {                                   // rare: look the entry up in the short list
@@ -822,14 +819,11 @@ __global__ __launch_bounds__(BIG) void k_lean_one(DevCtx c, SegInfo one, uint32_
   uint32_t nsent = 0;
   for (uint32_t e0 = 0; e0 < cnt_w; e0 += WAVE) {
     const uint32_t e = e0 + lane;
-    uint2 ent = make_uint2(0, 0);
+    const uint2 ent = ent_first;                                  // loaded one step ahead
+    const uint32_t key = key_first;
+    if (e + WAVE < cnt_w) { ent_first = d0[d_off + e + WAVE]; if (SPARS == QSL_RANDK) key_first = d0k[d_off + e + WAVE]; }
     uint32_t bin = 0;
-    if (e < cnt_w) {
-      uint32_t key = key_first;
-      if (e0 == 0) ent = ent_first;
-      else { ent = d0[d_off + e]; if (SPARS == QSL_RANDK) key = d0k[d_off + e]; }
-      bin = lean_bin(SPARS == QSL_TOPK ? key_of_value(ent.y) : key, T, sh);
-    }
+    if (e < cnt_w) bin = lean_bin(SPARS == QSL_TOPK ? key_of_value(ent.y) : key, T, sh);
     bool take = e < cnt_w && bin > taubin;
     const bool maybe = e < cnt_w && bin == taubin;
     if (__ballot(maybe) != 0) {
