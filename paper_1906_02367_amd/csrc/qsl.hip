@@ -427,12 +427,8 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   // share is launched only while the host expects failed guesses.  A guessing unit's blocks are also the blocks of
   // k_lean_* (fsels).
   std::vector<SelInfo> fsels, sels_f;
-  // A guessing unit with a single block takes k_lean_one (one launch instead of three) -- unless the context also has
-  // units for k_block_units: those run beside the guessing units' kernels on the second stream, and k_lean_one's
-  // blocks (123 registers, 42 KB of LDS: one per compute unit) leave them no room to (measured on the 161-tensor
-  // table: 541 us per round with it against 536 us with the three kernels, whose blocks share a compute unit).
-  bool one_kernel = true;
-  for (uint32_t l = 0; l < L; ++l) if (segs[l].mode == PATH_SMALL && !segs[l].in_stream) one_kernel = false;
+  // A guessing unit with a single block takes k_lean_one: one launch instead of three.
+  const bool one_kernel = true;
   std::vector<CbInfo> cbs_f;
   uint32_t cb_slots = 0;
   for (uint32_t l = 0; l < L; ++l) {
@@ -742,8 +738,20 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   // Units that a single block selects and encodes whole need nothing but v: their kernel runs on a stream of the
   // context's own beside the kernels of the other units (one block works tens of microseconds on a unit of 40,960
   // coordinates) and is joined before the messages are put together.
-  const bool forked = c.nblock != 0 && (c.NSELF != 0 || c.none != 0 || ctx->n_other != 0);
-  if (c.nblock) {
+  // With k_lean_one in the call the roles are swapped: the block units start on the caller's stream at once and
+  // k_lean_one follows on the second stream behind the event -- its blocks take a compute unit each (123 registers),
+  // so whichever kernel is dispatched first keeps the other waiting, and the block units are the longer (measured on
+  // the 161-tensor table: k_lean_one first 541-548 us per round, the three kernels 536 us).  Not while failed guesses
+  // are expected: the multi-pass kernels on the caller's stream read what k_lean_one finds out about its units.
+  const bool swapped = c.nblock != 0 && c.none != 0 && !safe;
+  const bool forked = c.nblock != 0 && !swapped && (c.NSELF != 0 || c.none != 0 || ctx->n_other != 0);
+  if (swapped) {
+    QSL_HIP(hipEventRecord(ctx->fork_ev, st));
+    QSL_HIP(hipStreamWaitEvent(ctx->side, ctx->fork_ev, 0));
+    k_block_units<SPARS><<<dim3(c.nblock * R), BIG, 0, st>>>(c, R, m_out, worker0, round, sel_idx, sel_level);
+    k_lean_one<SPARS><<<dim3(c.none * R), BIG, 0, ctx->side>>>(c, ctx->segs[0], R, m_out, worker0, round, sel_idx, sel_level, 0);
+    QSL_HIP(hipEventRecord(ctx->join_ev, ctx->side));
+  } else if (c.nblock) {
     hipStream_t bs = st;
     if (forked) {
       QSL_HIP(hipEventRecord(ctx->fork_ev, st));
@@ -755,7 +763,7 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   }
   if (ctx->nfull_blocks) k_full<<<dim3(ctx->nfull_blocks, R), BLOCK, 0, st>>>(c, m_out);
   // guessing units of a single block: the whole way from the slots to the encoded entries in one launch
-  if (c.none) k_lean_one<SPARS><<<dim3(c.none * R), BIG, 0, st>>>(c, ctx->segs[0], R, m_out, worker0, round, sel_idx, sel_level, safe ? 1 : 0);
+  if (c.none && !swapped) k_lean_one<SPARS><<<dim3(c.none * R), BIG, 0, st>>>(c, ctx->segs[0], R, m_out, worker0, round, sel_idx, sel_level, safe ? 1 : 0);
   if (c.NSELF) {                                   // guessing units: candidates' histogram, threshold bin and dense list
     k_lean_hist<SPARS><<<dim3(c.NSELF * R), BIG, 0, st>>>(c, ctx->segs[0], R);
     k_lean_mark<SPARS><<<dim3(c.NSELF * R), BIG, 0, st>>>(c, ctx->segs[0], R);
@@ -775,7 +783,7 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   if (c.NSELF)
     k_lean_emit<SPARS><<<dim3((c.NSELF + c.nfast) * R), BIG, 0, st>>>(c, ctx->segs[0], R, c.NSELF * R, m_out, worker0, round,
                                                                      sel_idx, sel_level, safe ? 1 : 0);
-  if (forked) QSL_HIP(hipStreamWaitEvent(st, ctx->join_ev, 0));
+  if (forked || swapped) QSL_HIP(hipStreamWaitEvent(st, ctx->join_ev, 0));
   if (is_qsgd(c.quantizer)) {                      // the other quantisers send every selected coordinate: the final arrays are written already
     if (c.QB > MAX_QB_INLINE) k_surv_scan<<<dim3(R), 1024, 0, st>>>(c);
     k_surv_compact<<<dim3(c.QB, R), BLOCK, 0, st>>>(c);
