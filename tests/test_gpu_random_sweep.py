@@ -206,3 +206,31 @@ def test_random_sign_scaled_by_higher_norms(P, block):
             deltas = [x * f32(2.0 ** int(rng.integers(-110, 90))) for x in deltas]
         print(f"case {seed}: d={wl.d} L={wl.L} K={wl.K} sparsifier={wl.sparsifier} quantizer={wl.quantizer} R={wl.R} flags={flags}", flush=True)
         P.run_parity(wl, 2, flags=flags, deltas=deltas, in_place=bool(rng.integers(0, 2)))
+
+
+@pytest.mark.parametrize("seed", [64_001, 64_002, 64_003])
+def test_sequences_with_jumps_under_the_per_tensor_rule(P, seed):
+    """k_t = min(d_t, 1000) (Section 5.1.1) on a table that has every kind of unit at once -- kept whole, selected inside
+    the streaming kernel, by one block beside the guessing units' kernel, guessing -- over rounds whose inputs jump by
+    orders of magnitude: guesses fail, the multi-pass kernels stand by for some calls and are dropped again, and the
+    two streams change roles with that.  Every round bit for bit against the oracle."""
+    from paper_1906_02367_amd import binding as B
+    rng = np.random.default_rng(seed)
+    sizes = np.array([300, 2048, 5000, 9408, 16384, 36864, 70000, 147456, 300000, 589824, 1000, 40960, 65536, 131072] * 2)
+    rng.shuffle(sizes)
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.uint64)
+    d = int(off[-1])
+    k = np.minimum(sizes, 1000).astype(np.uint32)
+    qz, s = int(rng.choice([W.SIGN_L1, W.QSGD, W.SIGN_L4])), int(rng.choice([3, 16]))
+    R = 3
+    wl = W.Workload(2, f"rule{seed}", R, d, off, k, s, W.TOPK, qz, 7, int(rng.integers(0, 2**63)))
+    deltas = []
+    for t in range(7):
+        x = rng.standard_normal((R, d)).astype(f32) * np.exp(rng.standard_normal(d)).astype(f32)
+        x *= f32(10.0 ** (rng.uniform(-4, 4) if t in (2, 3, 5) else 0.0))
+        deltas.append(x)
+    run, op, m_host, paths = P.run_parity(wl, 7, deltas=deltas)
+    assert run.q.device_status() == B.OK
+    seen = np.unique(np.concatenate(paths))
+    assert 0 in seen or 2 in seen, seen                         # guessing units ...
+    assert 3 in seen, seen                                      # ... and units selected by one block were there
