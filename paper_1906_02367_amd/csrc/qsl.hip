@@ -358,9 +358,18 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
       // first in the grid: they run longest, so they start before the streaming blocks rather than after them.
       const bool own_block = sg.mode == PATH_SMALL && sg.nwt <= SMALL_CHUNKS;
       std::vector<WtInfo>& list = own_block ? wts_own : wts;
-      for (uint32_t t = 0; t < sg.nwt; ++t) { WtInfo wi; wi.seg = l; wi.chunk = t; wi.inblock = own_block; wi.pad1 = 0; list.push_back(wi); }
+      for (uint32_t t = 0; t < sg.nwt; ++t) {
+        WtInfo wi; wi.seg = l; wi.chunk = t; wi.inblock = own_block;
+        wi.first = static_cast<uint32_t>(sg.start + static_cast<uint64_t>(t) * CHUNK);
+        wi.valid = static_cast<uint16_t>(std::min<uint64_t>(CHUNK, sg.size - static_cast<uint64_t>(t) * CHUNK));
+        list.push_back(wi);
+      }
       if (own_block) {
-        while (wts_own.size() % 4) { WtInfo wi; wi.seg = l; wi.chunk = NO_CHUNK; wi.inblock = 1; wi.pad1 = 0; wts_own.push_back(wi); }
+        while (wts_own.size() % 4) {
+          WtInfo wi; wi.seg = l; wi.chunk = NO_CHUNK; wi.inblock = 1;
+          wi.first = static_cast<uint32_t>(sg.start + sg.size); wi.valid = 0;
+          wts_own.push_back(wi);
+        }
         sg.mode = PATH_SMALL; sg.in_stream = 1;
       }
     }

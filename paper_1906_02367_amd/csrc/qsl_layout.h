@@ -60,7 +60,9 @@ struct SegInfo {
 
 // one chunk (multi-segment contexts only).  inblock = 1: the chunk's k_stream block belongs to one unit of at most 4096
 // coordinates, which that block also selects and encodes; chunk = NO_CHUNK then pads the unit to a whole block.
-struct WtInfo { uint32_t seg, chunk, inblock, pad1; };
+// first = the chunk's first coordinate within the row and valid = how many of its 1024 lie inside the unit, so that the
+// wave's streaming loads wait for this one record only and not for the segment's as well.
+struct WtInfo { uint32_t seg, chunk, first; uint16_t valid, inblock; };
 constexpr uint32_t NO_CHUNK = 0xFFFFFFFFu;
 struct SelInfo { uint32_t seg, j, pad0, pad1; };                    // one block of a selection kernel
 struct CbInfo { uint32_t seg, b, pad0, pad1; };                     // one compaction block

@@ -270,29 +270,29 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
   StreamSeg sg = one;
   uint32_t seg = 0, chunk = wt;
   bool inblock = false;
+  uint64_t first = static_cast<uint64_t>(wt) * CHUNK;                 // of the chunk, within the row
+  uint32_t valid = static_cast<uint32_t>(min(static_cast<uint64_t>(CHUNK), one.size - first));
   if (!SINGLE) {
     const WtInfo wi = c.wts[wt];
     const SegInfo& s = c.segs[wi.seg];
-    seg = wi.seg; chunk = wi.chunk; inblock = wi.inblock != 0;
+    seg = wi.seg; chunk = wi.chunk; inblock = wi.inblock != 0; first = wi.first; valid = wi.valid;
     sg.start = s.start; sg.size = s.size; sg.slot_off = s.slot_off; sg.ovf_off = s.ovf_off;
     sg.lpc = s.lpc; sg.ovf_cap = s.ovf_cap;
   }
   const uint64_t u = static_cast<uint64_t>(w) * c.L + seg;
   const uint32_t T = c.units[u].T;
   const uint32_t path = c.units[u].path;
-  const uint64_t row = static_cast<uint64_t>(w) * c.d + sg.start;
+  const uint64_t row = static_cast<uint64_t>(w) * c.d + first;
   const float* mp = m + row;
   const float* dp = delta + row;
-  const float* xp = DIFF ? xm + sg.start : nullptr;
+  const float* xp = DIFF ? xm + first : nullptr;
   float* op = m_out + row;
-  // segment-local; a wave that only fills up the block of a small unit has no chunk: nothing of it lies inside the unit
-  const uint64_t cb = !SINGLE && chunk == NO_CHUNK ? sg.size : static_cast<uint64_t>(chunk) * CHUNK;
   f4u v[4];
-  if (sg.size - cb >= CHUNK) {
+  if (valid == CHUNK) {
     f4u a[4], b[4], x[4];
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
-      const uint64_t e = cb + t * 256 + lane * 4;
+      const uint32_t e = t * 256 + lane * 4;
       a[t] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(mp + e));
       b[t] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(dp + e));
       if (DIFF) x[t] = *reinterpret_cast<const f4u*>(xp + e);        // cached: the other workers read it too
@@ -301,16 +301,16 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
     for (int t = 0; t < 4; ++t) {
       if (DIFF) b[t] = x[t] - b[t];
       v[t] = a[t] + b[t];
-      __builtin_nontemporal_store(v[t], reinterpret_cast<f4u*>(op + cb + t * 256 + lane * 4));
+      __builtin_nontemporal_store(v[t], reinterpret_cast<f4u*>(op + t * 256 + lane * 4));
     }
   } else {
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
-        const uint64_t e = cb + t * 256 + lane * 4 + j;
+        const uint32_t e = t * 256 + lane * 4 + j;
         float x = 0.0f;                                               // past the end: never a candidate
-        if (e < sg.size) {
+        if (e < valid) {
           const float dl = DIFF ? xp[e] - dp[e] : dp[e];
           x = mp[e] + dl; op[e] = x;
         }
@@ -318,6 +318,8 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
       }
     }
   }
+  // segment-local; a wave that only fills up the block of a small unit has no chunk: nothing of it lies inside the unit
+  const uint64_t cb = first - sg.start;
   bool nonfinite = false;
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
@@ -339,11 +341,11 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
 #pragma unroll
   for (int t = 0; t < 4; ++t) {
     Words4 rw;
-    if (SPARS == QSL_RANDK) { rw = rand_words4(rk, static_cast<uint32_t>(sg.start + cb + t * 256 + lane * 4)); rws[t] = rw; }
+    if (SPARS == QSL_RANDK) { rw = rand_words4(rk, static_cast<uint32_t>(first + t * 256 + lane * 4)); rws[t] = rw; }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const uint32_t key = SPARS == QSL_TOPK ? key_of_value(__float_as_uint(v[t][j])) : rw.w[j];
-      const bool inside = cb + t * 256 + lane * 4 + j < sg.size;
+      const bool inside = static_cast<uint32_t>(t * 256 + lane * 4 + j) < valid;
       pm |= (inside && key >= T ? 1u : 0u) << (t * 4 + j);
     }
   }
@@ -391,7 +393,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
         for (int j = 0; j < 4; ++j) {
           if ((nib >> j) & 1u) {
             if (SPARS == QSL_RANDK) dst_key[pos] = rws[t].w[j];
-            dst[pos++] = make_uint2(static_cast<uint32_t>(sg.start + cb + t * 256 + lane * 4 + j), __float_as_uint(v[t][j]));
+            dst[pos++] = make_uint2(static_cast<uint32_t>(first + t * 256 + lane * 4 + j), __float_as_uint(v[t][j]));
           }
         }
         base += tot[t];

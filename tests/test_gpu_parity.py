@@ -641,3 +641,79 @@ def test_aggregate_many_messages(P, case):
             mag[i] += np.abs(v.astype(np.float64))
         assert np.all(np.abs(got.astype(np.float64) - ref) <= 1e-6 * (mag / 64 + np.abs(ref)) + 1e-38)
     assert q.device_status() == B.OK
+
+
+# ---------------------------------------------------------------------------------------------
+# the master line on long messages whose coordinates are shared by all, by about half or by hardly any of the listed
+# messages, call after call on one context, with lists that change
+# ---------------------------------------------------------------------------------------------
+def _aggregate_by_definition(decoded, lst, scale, x0, accumulate, d):
+    acc = np.zeros(d, f32)
+    has = np.zeros(d, bool)
+    for r in lst:
+        i, v = decoded[r]
+        acc[i] = np.where(has[i], acc[i] + v, v).astype(f32)
+        has[i] = True
+    term = (f32(scale) * acc).astype(f32)
+    want = x0.copy() if accumulate else np.zeros(d, f32)
+    want[has] = (want[has] + term[has]).astype(f32) if accumulate else term[has]
+    return want
+
+
+@pytest.mark.parametrize("case", ["sign_layerwise", "qsgd_layerwise", "sign_one_segment"])
+def test_aggregate_long_messages_shared_coordinates(P, case):
+    from paper_1906_02367_amd import binding as B
+    rng = np.random.default_rng(77 + len(case))
+    if case == "sign_layerwise":           # segments kept whole (at the same places in every message) beside sparse ones
+        off = [0, 700, 1_724, 300_000, 301_000, 1_000_003]
+        wl = custom(1_000_003, off, [700, 1_024, 9_000, 1_000, 3_000], 1, W.TOPK, W.SIGN_L1, R=8)
+    elif case == "qsgd_layerwise":         # entries drop out: no two messages alike, whole segments included
+        off = [0, 700, 1_724, 300_000, 301_000, 1_000_003]
+        wl = custom(1_000_003, off, [700, 1_024, 9_000, 1_000, 3_000], 4, W.TOPK, W.QSGD, R=8)
+    else:
+        wl = custom(2_000_003, [0, 2_000_003], [20_000], 1, W.TOPK, W.SIGN_L1, R=8)
+    q = B.from_workload(wl)
+    op = P.oracle_for(wl)
+    msg = q.new_msg(8)
+    # what the workers share decides how many coordinates several messages hold: all, about half, hardly any
+    common = (rng.standard_normal(wl.d) * np.exp(rng.standard_normal(wl.d))).astype(f32)
+    for share in (1.0, 0.5, 0.0):
+        own = (rng.standard_normal((8, wl.d)) * np.exp(rng.standard_normal(wl.d))).astype(f32)
+        delta = torch.from_numpy((f32(share) * common[None, :] + f32(1.0 - share) * own).astype(f32)).to(q.device)
+        m = torch.zeros(8, wl.d, device=q.device)
+        q.compress(m, delta, m, 0, int(share * 10), msg)
+        torch.cuda.synchronize()
+        msgs = msg.cpu().numpy()
+        decoded = [op.decode(msgs[r]) for r in range(8)]
+        if share == 0.5:
+            both = len(np.intersect1d(decoded[0][0], decoded[1][0]))
+            assert 0 < both < len(decoded[0][0])
+        x0 = rng.standard_normal(wl.d).astype(f32)
+        for lst, accumulate in [(list(range(8)), True), ([5, 2], False), ([7, 0, 3, 6, 1], True), ([4], True),
+                                (list(range(7, -1, -1)), False), ([1, 2, 3], True)]:
+            out = torch.from_numpy(x0).to(q.device)
+            q.aggregate(msg, out, -0.125, worker_list=lst, accumulate=accumulate)
+            torch.cuda.synchronize()
+            want = _aggregate_by_definition(decoded, lst, -0.125, x0, accumulate, wl.d)
+            assert np.array_equal(out.cpu().numpy().view(np.uint32), want.view(np.uint32)), (case, share, lst)
+    # a message cut short (here: empty) among full ones: its coordinates are not at the places the others have them
+    cut = msg.clone()
+    cut[3].zero_()
+    torch.cuda.synchronize()
+    msgs = cut.cpu().numpy()
+    decoded = [op.decode(msgs[r]) if r != 3 else (np.zeros(0, np.int64), np.zeros(0, f32)) for r in range(8)]
+    for lst in ([3, 0, 1], [0, 1, 3, 2], list(range(8))):
+        out = torch.from_numpy(x0).to(q.device)
+        q.aggregate(cut, out, 0.5, worker_list=lst, accumulate=True)
+        torch.cuda.synchronize()
+        want = _aggregate_by_definition(decoded, lst, 0.5, x0, True, wl.d)
+        assert np.array_equal(out.cpu().numpy().view(np.uint32), want.view(np.uint32)), (case, "cut", lst)
+    # ... and full lists again afterwards
+    msgs = msg.cpu().numpy()
+    decoded = [op.decode(msgs[r]) for r in range(8)]
+    out = torch.from_numpy(x0).to(q.device)
+    q.aggregate(msg, out, 1.0, accumulate=False)
+    torch.cuda.synchronize()
+    want = _aggregate_by_definition(decoded, list(range(8)), 1.0, x0, False, wl.d)
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), want.view(np.uint32))
+    assert q.device_status() == B.OK
