@@ -25,7 +25,7 @@
 //                encoding: dense k on a large unit, and the units whose guess failed while the host expects
 //                failures (always exact; only the speed depends on the guess)
 //   k_surv_compact, k_pack    the packed message
-//   k_dense_norm, k_dense_scales, k_dense_encode    an operator that keeps every coordinate, with messages that
+//   k_dense_norm, k_dense_sum, k_dense_scales, k_dense_encode    an operator that keeps every coordinate, with messages that
 //                carry no indices: two streaming passes
 //   k_aggregate, k_aggregate_entries, k_aggregate_ranges, k_aggregate_dense
 //                master line of Algorithm 1, atomic-free, messages added in list order: by look-ups in the other
@@ -560,6 +560,8 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const bool want_dir = true;                       // (6.4 MB for 25.6 M coordinates)
   const uint64_t o_dir = carve(4ull * 65 * ctx->agg_ndir);       // 64 directories and the list of crowded ranges
   const uint64_t o_ownv = carve((cfg->flags & QSL_FLAG_OWN_V) ? 4ull * R * d : 4);
+  const uint64_t dense_nb = dense ? std::min<uint64_t>((d + DTILE - 1) / DTILE, MAX_DENSE_BLOCKS) : 0;
+  const uint64_t o_dpart = carve(8ull * R * ACC_SLOTS * dense_nb + 8), o_dtag = carve(4ull * R * dense_nb + 4);
   if (hipMalloc(&ctx->slab, bytes) != hipSuccess) { ctx->slab = nullptr; free_ctx(ctx); return QSL_ERR_DEVICE; }
   char* base = static_cast<char*>(ctx->slab);
   bool ok = hipMemset(base, 0, zero_bytes) == hipSuccess;
@@ -637,6 +639,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   c.blk_pre = reinterpret_cast<uint32_t*>(base + o_pre);
   c.surv_idx = reinterpret_cast<uint32_t*>(base + o_vi); c.surv_code = reinterpret_cast<uint32_t*>(base + o_vc);
   c.status = reinterpret_cast<uint32_t*>(base + o_status);
+  c.dense_part = reinterpret_cast<uint64_t*>(base + o_dpart); c.dense_tag = reinterpret_cast<uint32_t*>(base + o_dtag);
   ctx->d_nnz_tmp = reinterpret_cast<uint32_t*>(base + o_tmp);
   ctx->agg_dir = want_dir ? reinterpret_cast<uint32_t*>(base + o_dir) : nullptr;
   ctx->own_v = (cfg->flags & QSL_FLAG_OWN_V) ? reinterpret_cast<float*>(base + o_ownv) : nullptr;
@@ -692,6 +695,7 @@ static qsl_status launch_dense(qsl_ctx* ctx, const float* m, const float* delta,
   if (xm == nullptr) k_dense_norm<false><<<grid, BLOCK, 0, st>>>(c, m, delta, xm, m_out);
   else k_dense_norm<true><<<grid, BLOCK, 0, st>>>(c, m, delta, xm, m_out);
   if (timed) { QSL_HIP(hipEventRecord(ctx->ev[ctx->ev_used + 1], st)); ctx->ev_used += 2; }
+  if (c.quantizer != QSL_FP32) k_dense_sum<<<dim3((grid.x + SUM_ROWS - 1) / SUM_ROWS, R), SUM_BLOCK, 0, st>>>(c, grid.x);
   const uint32_t U = R * c.L;
   k_dense_scales<<<dim3((U + BLOCK / 64 - 1) / (BLOCK / 64)), BLOCK, 0, st>>>(c, U);
   const dim3 egrid(static_cast<uint32_t>(std::min<uint64_t>(ntiles, MAX_ENCODE_BLOCKS)), R);

@@ -3,6 +3,7 @@
 // streaming passes and nothing per entry in between.
 //   k_dense_norm    v = m + Delta (Algorithm 1, first worker line) written over the error memory, 12 bytes per
 //                   coordinate, with the exact digits of every segment's norm added up on the way
+//   k_dense_sum     the digit sums that the blocks of k_dense_norm stored, into their units' counters
 //   k_dense_scales  one wave per unit: digits -> fp32 scale (||v||_2 for QSGD, ||v||_1 / k or ||v||_2 / k for Sign)
 //   k_dense_encode  reads v, writes m' = v - g (second worker line) and the packed codes, 8 bytes per coordinate:
 //                   a block owns 4096 consecutive coordinates and with them whole 32-bit words of the code stream
@@ -17,7 +18,13 @@
 namespace {
 
 constexpr uint32_t DTILE = 4096;             // coordinates per tile: 256 threads x 4 x dwordx4
-constexpr uint32_t MAX_DENSE_BLOCKS = 1024;  // blocks per worker of the first pass (each a contiguous range of tiles; each ends with atomics on a unit's counters)
+// Blocks per worker of the first pass, each a contiguous range of tiles.  The pass wants many: without the digits
+// (fp32 values, 2 x 25.6 M coordinates) 1024 blocks per worker take 127 us, 2048 121 us, 4096 112 us, 16384 100 us.  With
+// that many, adding every block's digits to its unit's counters by atomics costs more than it saves (292 us: additions
+// to one address queue up), so a block stores the sums of its first unit as a row of its own and k_dense_sum adds the
+// rows up; only what a block meets beyond its first unit (few blocks, if any) goes to the counters directly.
+constexpr uint32_t MAX_DENSE_BLOCKS = 16384;
+constexpr uint32_t NO_UNIT = 0xFFFFFFFFu;
 constexpr uint32_t MAX_ENCODE_BLOCKS = 8192; // ... and of the second, which has no such ending
 
 // digits of |v| (or v^2) straight into a unit's counters in memory (for the few tiles that span several segments)
@@ -56,18 +63,26 @@ __global__ __launch_bounds__(BLOCK) void k_dense_norm(DevCtx c, const float* m, 
   const uint64_t row = static_cast<uint64_t>(w) * c.d;
   uint64_t t_lo, t_hi;
   dense_range(c.d, blockIdx.x, gridDim.x, &t_lo, &t_hi);
-  uint32_t cur = 0xFFFFFFFFu;                       // the segment whose digits the block's rows hold
+  uint32_t cur = NO_UNIT;                           // the segment whose digits the block's rows hold
   bool nonfinite = false;
-  // the rows into the segment's counters, then zero again (uniform over the block)
+  bool own_row = true;                              // nothing stored yet: the next sums go to the block's own row
+  const uint64_t nb = gridDim.x;
+  // the rows added up: into the block's own row the first time, into the segment's counters after that; then zero again
+  // (uniform over the block)
   auto flush = [&]() {
     __syncthreads();
-    if (cur != 0xFFFFFFFFu) {
+    if (cur != NO_UNIT) {
       uint64_t* ga = c.norm_acc + (static_cast<uint64_t>(w) * c.L + cur) * ACC_SLOTS;
       for (uint32_t s = wave; s < acc_slots(c.quantizer); s += BLOCK / 64) {
         uint64_t x = lane < ACC_ROWS ? acc[lane * acc_stride(c.quantizer) + s] : 0;
         x = wave_sum64(x);
-        if (lane == 0 && x) atomicAdd(reinterpret_cast<unsigned long long*>(ga + s), static_cast<unsigned long long>(x));
+        if (lane == 0) {
+          if (own_row) c.dense_part[(static_cast<uint64_t>(w) * ACC_SLOTS + s) * nb + blockIdx.x] = x;
+          else if (x) atomicAdd(reinterpret_cast<unsigned long long*>(ga + s), static_cast<unsigned long long>(x));
+        }
       }
+      if (own_row && threadIdx.x == 0) c.dense_tag[static_cast<uint64_t>(w) * nb + blockIdx.x] = cur;
+      own_row = false;
       __syncthreads();
       for (uint32_t i = threadIdx.x; i < ACC_ROWS * acc_stride(c.quantizer); i += BLOCK) acc[i] = 0;
       __syncthreads();
@@ -76,19 +91,29 @@ __global__ __launch_bounds__(BLOCK) void k_dense_norm(DevCtx c, const float* m, 
   for (uint64_t tile = t_lo; tile < t_hi; ++tile) {
     const uint64_t base = tile * DTILE;
     f4u v[4];
-    // one group of four at a time: with all loads of a tile issued first the pass was slower (186 us against 150 us
-    // for 2 x 25.6 M coordinates), and so it was with more, smaller blocks (their atomics on the unit's counters)
+    // the tile's loads first, then its stores (146 us against 159 us one group of four at a time, 2 x 25.6 M coordinates in
+    // 1024 blocks per worker; the next tile's loads issued before this tile's digits are added: no change)
+    if (base + DTILE <= c.d) {
+      f4u a[4], b[4], x[4];
 #pragma unroll
-    for (uint32_t q = 0; q < 4; ++q) {
-      const uint64_t e = base + q * 1024 + threadIdx.x * 4;
-      v[q] = f4u{0.f, 0.f, 0.f, 0.f};
-      if (e + 4 <= c.d) {
-        const f4u a = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(m + row + e));
-        f4u b = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(delta + row + e));
-        if (DIFF) b = *reinterpret_cast<const f4u*>(xm + e) - b;
-        v[q] = a + b;
+      for (uint32_t q = 0; q < 4; ++q) {
+        const uint64_t e = base + q * 1024 + threadIdx.x * 4;
+        a[q] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(m + row + e));
+        b[q] = __builtin_nontemporal_load(reinterpret_cast<const f4u*>(delta + row + e));
+        if (DIFF) x[q] = *reinterpret_cast<const f4u*>(xm + e);
+      }
+#pragma unroll
+      for (uint32_t q = 0; q < 4; ++q) {
+        const uint64_t e = base + q * 1024 + threadIdx.x * 4;
+        if (DIFF) b[q] = x[q] - b[q];
+        v[q] = a[q] + b[q];
         __builtin_nontemporal_store(v[q], reinterpret_cast<f4u*>(m_out + row + e));
-      } else {
+      }
+    } else {                                        // the row's last, ragged tile
+#pragma unroll
+      for (uint32_t q = 0; q < 4; ++q) {
+        const uint64_t e = base + q * 1024 + threadIdx.x * 4;
+        v[q] = f4u{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (uint32_t j = 0; j < 4; ++j)
           if (e + j < c.d) {
@@ -97,6 +122,9 @@ __global__ __launch_bounds__(BLOCK) void k_dense_norm(DevCtx c, const float* m, 
             m_out[row + e + j] = v[q][j];
           }
       }
+    }
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {
 #pragma unroll
       for (uint32_t j = 0; j < 4; ++j) nonfinite |= (__float_as_uint(v[q][j]) & 0x7FFFFFFFu) >= 0x7F800000u;
     }
@@ -113,7 +141,7 @@ __global__ __launch_bounds__(BLOCK) void k_dense_norm(DevCtx c, const float* m, 
         for (uint32_t j = 0; j < 4; ++j) if (e + j < c.d) add_digits(mine, __float_as_uint(v[q][j]), power);
       }
     } else {                                          // several segments in one tile: each coordinate to its own unit's counters
-      flush(); cur = 0xFFFFFFFFu;
+      flush(); cur = NO_UNIT;
 #pragma unroll
       for (uint32_t q = 0; q < 4; ++q) {
         const uint64_t e = base + q * 1024 + threadIdx.x * 4;
@@ -127,7 +155,55 @@ __global__ __launch_bounds__(BLOCK) void k_dense_norm(DevCtx c, const float* m, 
     }
   }
   flush();
+  if (own_row && threadIdx.x == 0) c.dense_tag[static_cast<uint64_t>(w) * nb + blockIdx.x] = NO_UNIT;   // no row from this block
   if (__ballot(nonfinite) != 0 && lane == 0) atomicOr(c.status, 1u);
+}
+
+// The rows of k_dense_norm's blocks into the counters of their units.  A block takes 512 rows, each of its waves one digit
+// (or two, or three): a lane adds up its eight rows' sums of that digit, the wave its lanes', and one lane adds the result
+// to the unit's counter -- if the 512 rows belong to one unit, as they nearly always do; else every row goes to its own
+// unit's counters.  (A thread per row and a wave-wide sum per digit: 14 us for 2 x 6240 rows; this way 4.5 us.)
+constexpr uint32_t SUM_BLOCK = 1024, SUM_ROWS = 512;
+__global__ __launch_bounds__(SUM_BLOCK) void k_dense_sum(DevCtx c, uint32_t nb) {
+  constexpr uint32_t G = SUM_ROWS / 64;
+  const uint32_t w = blockIdx.y, lane = lane_id(), wave = threadIdx.x >> 6;
+  const uint32_t r0 = blockIdx.x * SUM_ROWS;
+  uint32_t tags[G];
+#pragma unroll
+  for (uint32_t g = 0; g < G; ++g) {
+    const uint32_t b = r0 + g * 64 + lane;
+    tags[g] = b < nb ? c.dense_tag[static_cast<uint64_t>(w) * nb + b] : NO_UNIT;
+  }
+  uint32_t tag0 = NO_UNIT;                           // the unit of the first row that has one (every wave finds the same)
+#pragma unroll
+  for (uint32_t g = 0; g < G; ++g) {
+    const uint64_t bal = __ballot(tags[g] != NO_UNIT);
+    if (tag0 == NO_UNIT && bal != 0) tag0 = __shfl(tags[g], __ffsll(static_cast<long long>(bal)) - 1, WAVE);
+  }
+  if (tag0 == NO_UNIT) return;
+  bool mixed = false;
+#pragma unroll
+  for (uint32_t g = 0; g < G; ++g) mixed = mixed || __ballot(tags[g] != NO_UNIT && tags[g] != tag0) != 0;
+  for (uint32_t s = wave; s < acc_slots(c.quantizer); s += SUM_BLOCK / 64) {
+    uint64_t x[G];
+#pragma unroll
+    for (uint32_t g = 0; g < G; ++g)
+      x[g] = tags[g] != NO_UNIT ? c.dense_part[(static_cast<uint64_t>(w) * ACC_SLOTS + s) * nb + r0 + g * 64 + lane] : 0;
+    if (!mixed) {
+      uint64_t sum = 0;
+#pragma unroll
+      for (uint32_t g = 0; g < G; ++g) sum += x[g];
+      sum = wave_sum64(sum);
+      if (lane == 0 && sum)
+        atomicAdd(reinterpret_cast<unsigned long long*>(c.norm_acc + (static_cast<uint64_t>(w) * c.L + tag0) * ACC_SLOTS + s),
+                  static_cast<unsigned long long>(sum));
+    } else {
+#pragma unroll
+      for (uint32_t g = 0; g < G; ++g)
+        if (x[g]) atomicAdd(reinterpret_cast<unsigned long long*>(c.norm_acc + (static_cast<uint64_t>(w) * c.L + tags[g]) * ACC_SLOTS + s),
+                            static_cast<unsigned long long>(x[g]));
+    }
+  }
 }
 
 // one wave per unit: the scale the codes are computed with and the scale the message carries; the digit counters

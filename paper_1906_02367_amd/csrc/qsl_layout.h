@@ -119,6 +119,8 @@ struct DevCtx {
   uint32_t* blk_cnt_next; // take turns from call to call: the last kernel of a call (k_pack) sets the next call's to zero.
   uint32_t* blk_pre;    // [R][QB + 1] their exclusive prefix and total (only when QB > MAX_QB_INLINE)
   uint32_t* surv_idx; uint32_t* surv_code;                    // [R][K]
+  uint64_t* dense_part; // index-free format: [R][ACC_SLOTS][blocks of k_dense_norm] digit sums of every block's first unit ...
+  uint32_t* dense_tag;  // ... [R][blocks]: which unit that is, or NO_UNIT
   uint32_t* status;
   uint64_t d, seed;
   uint32_t dense;       // 1: every coordinate is kept and the messages have the index-free format
