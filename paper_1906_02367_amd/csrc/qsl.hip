@@ -867,7 +867,7 @@ static qsl_status launch_aggregate(const DevCtx& c, hipStream_t st, uint32_t nnz
                                    const uint8_t* msg, const RowList& rows, uint32_t R, float scale, int accumulate,
                                    float* out) {
   if (c.K == c.d && (c.dense || !is_qsgd(c.quantizer))) {   // k = d and nothing dropped: every message lists every coordinate
-    const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((c.d / 4 + BLOCK) / BLOCK, 1u << 16));
+    const uint32_t blocks = static_cast<uint32_t>(std::min<uint64_t>((c.d / 8 + BLOCK) / BLOCK, 1u << 16));   // two groups of four per thread
     k_aggregate_dense<<<dim3(blocks), BLOCK, 0, st>>>(c, msg, rows, R, scale, accumulate, out);
     QSL_HIP(hipGetLastError());
     return QSL_OK;

@@ -473,66 +473,81 @@ __global__ __launch_bounds__(1024) void k_aggregate_dense_ranges(DevCtx c, const
 // nothing, e.g. the sign of the whole vector): entry j of a message is coordinate j, so the sum is a plain
 // pass over the coordinates, in the same list order and with the same roundings as k_aggregate.  An
 // all-zero (empty) message adds nothing; any other entry count is reported as a malformed message.
-__global__ __launch_bounds__(BLOCK) void k_aggregate_dense(DevCtx c, const uint8_t* msg, RowList rows, uint32_t R,
-                                                           float scale, int accumulate, float* out) {
+// four consecutive coordinates from j0 on (nj of them exist); `o`: what `out` holds there (if accumulate)
+__device__ __forceinline__ void aggregate_dense_quad(const DevCtx& c, const uint8_t* __restrict__ msg, const RowList& rows, uint32_t R,
+                                                     float scale, int accumulate, float* __restrict__ out, uint64_t code_bit0,
+                                                     uint64_t j0, uint32_t nj, f4u o) {
+  uint32_t seg[4] = {0u, 0u, 0u, 0u};
+  if (c.L > 1) {
+    seg[0] = seg_of_coord(c, static_cast<uint32_t>(j0));
+    seg[3] = seg_of_coord(c, static_cast<uint32_t>(j0 + nj - 1));
+    seg[1] = seg[2] = seg[0];
+    if (seg[3] != seg[0]) {
+      seg[1] = nj > 1 ? seg_of_coord(c, static_cast<uint32_t>(j0 + 1)) : seg[0];
+      seg[2] = nj > 2 ? seg_of_coord(c, static_cast<uint32_t>(j0 + 2)) : seg[0];
+    }
+  }
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  bool first = true;
+  for (uint32_t p = 0; p < R; ++p) {
+    const uint32_t* words = reinterpret_cast<const uint32_t*>(msg + static_cast<uint64_t>(rows.row[p]) * c.cap_words * 4);
+    const uint32_t nnz = words[0];
+    if (nnz != c.d) {
+      if (nnz != 0 && j0 == 0) atomicOr(c.status, 4u);
+      continue;
+    }
+    // the codes of the four coordinates are consecutive in the stream: up to 8 bits each come in one read
+    // (77 -> 62 us for two messages of 25.6 M one-bit codes; issuing the reads of several messages together, or a
+    // wave per 1024 coordinates as in the streaming pass, were both slower again: 72-77 us)
+    const bool packed = c.w_val <= 8;                      // uniform
+    const uint32_t four = packed ? get_bits(words, code_bit0 + j0 * c.w_val, nj * c.w_val) : 0u;
+    const float scale0 = __uint_as_float(words[1 + seg[0]]);
+#pragma unroll
+    for (uint32_t jj = 0; jj < 4; ++jj) {
+      if (jj < nj) {
+        const uint32_t code = packed ? (four >> (jj * c.w_val)) & ((1u << c.w_val) - 1u)
+                                     : get_bits(words, code_bit0 + (j0 + jj) * c.w_val, c.w_val);
+        const float sc = seg[jj] == seg[0] ? scale0 : __uint_as_float(words[1 + seg[jj]]);
+        const float val = value_of_code(c, code, sc);
+        acc[jj] = first ? val : acc[jj] + val;
+      }
+    }
+    first = false;
+  }
+  if (first && accumulate) return;                       // no message had anything to add
+#pragma unroll
+  for (uint32_t jj = 0; jj < 4; ++jj) {
+    const float term = scale * acc[jj];
+    o[jj] = first ? 0.0f : accumulate ? o[jj] + term : term;
+  }
+  if (nj == 4) *reinterpret_cast<f4u*>(out + j0) = o;
+  else for (uint32_t jj = 0; jj < nj; ++jj) out[j0 + jj] = o[jj];
+}
+
+// A thread takes two groups of four consecutive coordinates at a time, a grid's width apart; what `out` holds of both is
+// read first (one group: 62 us for two messages of 25.6 M one-bit codes; its read of `out` before those of the messages
+// instead of after them: 59 us; two groups: 57 us; with streaming hints on `out`, which the next round's call finds
+// partly in the last-level cache otherwise: 61 us).
+__global__ __launch_bounds__(BLOCK) void k_aggregate_dense(DevCtx c, const uint8_t* __restrict__ msg, RowList rows, uint32_t R,
+                                                           float scale, int accumulate, float* __restrict__ out) {
   const uint64_t stride = static_cast<uint64_t>(gridDim.x) * BLOCK;
-  const uint64_t n4 = (c.d + 3) / 4;                       // a thread takes four consecutive coordinates at a time
+  const uint64_t n4 = (c.d + 3) / 4;
   const bool counts = is_qsgd(c.quantizer) && c.L > 1 && !c.dense;
   const uint64_t hdr = 1 + static_cast<uint64_t>(c.L) + (counts ? c.L : 0);
   const uint64_t code_bit0 = (hdr + (c.d * c.w_idx + 31) / 32) * 32;      // of a message that holds all d entries
-  for (uint64_t g = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x; g < n4; g += stride) {
-    const uint64_t j0 = g * 4;
-    const uint32_t nj = static_cast<uint32_t>(min<uint64_t>(4, c.d - j0));
-    uint32_t seg[4] = {0u, 0u, 0u, 0u};
-    if (c.L > 1) {
-      seg[0] = seg_of_coord(c, static_cast<uint32_t>(j0));
-      seg[3] = seg_of_coord(c, static_cast<uint32_t>(j0 + nj - 1));
-      seg[1] = seg[2] = seg[0];
-      if (seg[3] != seg[0]) {
-        seg[1] = nj > 1 ? seg_of_coord(c, static_cast<uint32_t>(j0 + 1)) : seg[0];
-        seg[2] = nj > 2 ? seg_of_coord(c, static_cast<uint32_t>(j0 + 2)) : seg[0];
-      }
-    }
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
-    bool first = true;
-    for (uint32_t p = 0; p < R; ++p) {
-      const uint32_t* words = reinterpret_cast<const uint32_t*>(msg + static_cast<uint64_t>(rows.row[p]) * c.cap_words * 4);
-      const uint32_t nnz = words[0];
-      if (nnz != c.d) {
-        if (nnz != 0 && g == 0) atomicOr(c.status, 4u);
-        continue;
-      }
-      // the codes of the thread's coordinates are consecutive in the stream: up to 8 bits each come in one read
-      // (77 -> 62 us for two messages of 25.6 M one-bit codes; issuing the reads of several messages together, or a
-      // wave per 1024 coordinates as in the streaming pass, were both slower again: 72-77 us)
-      const bool packed = c.w_val <= 8;                      // uniform
-      const uint32_t four = packed ? get_bits(words, code_bit0 + j0 * c.w_val, nj * c.w_val) : 0u;
-      const float scale0 = __uint_as_float(words[1 + seg[0]]);
-#pragma unroll
-      for (uint32_t jj = 0; jj < 4; ++jj) {
-        if (jj < nj) {
-          const uint32_t code = packed ? (four >> (jj * c.w_val)) & ((1u << c.w_val) - 1u)
-                                       : get_bits(words, code_bit0 + (j0 + jj) * c.w_val, c.w_val);
-          const float sc = seg[jj] == seg[0] ? scale0 : __uint_as_float(words[1 + seg[jj]]);
-          const float val = value_of_code(c, code, sc);
-          acc[jj] = first ? val : acc[jj] + val;
-        }
-      }
-      first = false;
-    }
-    f4u o = {0.f, 0.f, 0.f, 0.f};
+  for (uint64_t g = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x; g < n4; g += 2 * stride) {
+    const uint64_t ja = g * 4, jb = (g + stride) * 4;
+    const uint32_t na = static_cast<uint32_t>(min<uint64_t>(4, c.d - ja));
+    const uint32_t nb = g + stride < n4 ? static_cast<uint32_t>(min<uint64_t>(4, c.d - jb)) : 0u;
+    f4u oa = {0.f, 0.f, 0.f, 0.f}, ob = {0.f, 0.f, 0.f, 0.f};
     if (accumulate) {
-      if (nj == 4) o = *reinterpret_cast<const f4u*>(out + j0);
-      else for (uint32_t jj = 0; jj < nj; ++jj) o[jj] = out[j0 + jj];
+      if (na == 4) oa = *reinterpret_cast<const f4u*>(out + ja);
+      else for (uint32_t jj = 0; jj < na; ++jj) oa[jj] = out[ja + jj];
+      if (nb == 4) ob = *reinterpret_cast<const f4u*>(out + jb);
+      else for (uint32_t jj = 0; jj < nb; ++jj) ob[jj] = out[jb + jj];
     }
-    if (first && accumulate) continue;                     // no message had anything to add
-#pragma unroll
-    for (uint32_t jj = 0; jj < 4; ++jj) {
-      const float term = scale * acc[jj];
-      o[jj] = first ? 0.0f : accumulate ? o[jj] + term : term;
-    }
-    if (nj == 4) *reinterpret_cast<f4u*>(out + j0) = o;
-    else for (uint32_t jj = 0; jj < nj; ++jj) out[j0 + jj] = o[jj];
+    aggregate_dense_quad(c, msg, rows, R, scale, accumulate, out, code_bit0, ja, na, oa);
+    if (nb) aggregate_dense_quad(c, msg, rows, R, scale, accumulate, out, code_bit0, jb, nb, ob);
   }
 }
 
