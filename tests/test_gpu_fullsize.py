@@ -36,3 +36,17 @@ def test_full_size_config(P, cfg, rounds):
     got = out.cpu().numpy().astype(np.float64)
     assert np.all(np.abs(got - want) <= 1e-6 * dense_abs / wl.R + 1e-38)
     assert q.bits_sent(run.msg) == [op.bits_sent(msgs[r]) for r in range(wl.R)]
+
+
+@pytest.mark.parametrize("quantizer,s", [(W.QSGD, 15), (W.SIGN_L2, 1)])
+def test_index_free_rows_longer_than_the_first_pass_has_blocks(P, quantizer, s):
+    """Rows of more than 16384 tiles of 4096 coordinates: a block of the first pass then takes several tiles, and what it
+    meets beyond its first unit goes to that unit's counters directly -- three units whose ends lie inside tiles."""
+    d = 70_000_003
+    off = np.array([0, 33_000_001, 33_002_000, d], dtype=np.uint64)
+    k = np.diff(off.astype(np.int64)).astype(np.uint32)
+    wl = W.Workload(2, "long_rows_index_free", 1, d, off, k, s, W.TOPK, quantizer, 1, 4321)
+    print(f"\n[{wl.name}] R={wl.R} d={wl.d} L={wl.L}", flush=True)
+    run, op, m_host, paths = P.run_parity(wl, 2, host_deltas=False, dense=True, expect_path=4)
+    msgs = run.msg.cpu().numpy()
+    assert run.q.bits_sent(run.msg) == [op.bits_sent(msgs[0])]
