@@ -24,7 +24,7 @@
 //                exact radix selection (12 + 12 + 8 bits) over the whole vector, ordered compaction and
 //                encoding: dense k on a large unit, and the units whose guess failed while the host expects
 //                failures (always exact; only the speed depends on the guess)
-//   k_surv_compact, k_pack    the packed message
+//   k_pack, k_pack_sent       the packed message (k_pack_sent: QSGD, whose entries of level 0 drop out)
 //   k_dense_norm, k_dense_sum, k_dense_scales, k_dense_encode    an operator that keeps every coordinate, with messages that
 //                carry no indices: two streaming passes
 //   k_aggregate, k_aggregate_entries, k_aggregate_ranges, k_aggregate_dense
@@ -554,7 +554,8 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   const uint64_t KA = dense ? 1 : K;                 // the index-free format needs no per-entry arrays
   const uint64_t o_si = carve(4ull * KA * R), o_sv = carve(4ull * KA * R), o_sc = carve(4ull * KA * R);
   const uint64_t o_pre = carve(4ull * (QB + 1) * R);
-  const uint64_t o_vi = carve(4ull * KA * R), o_vc = carve(4ull * KA * R);
+  const uint64_t KV = is_qsgd(cfg->quantizer) ? 1 : KA;     // the final arrays of the quantisers that send every selected coordinate
+  const uint64_t o_vi = carve(4ull * KV * R), o_vc = carve(4ull * KV * R);
   const uint64_t o_tmp = carve(4ull * 1024);
   ctx->agg_ndir = static_cast<uint32_t>(((d + (1u << AGG_DIR_SHIFT) - 1) >> AGG_DIR_SHIFT) + 1);
   const bool want_dir = true;                       // (6.4 MB for 25.6 M coordinates)
@@ -737,14 +738,16 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
     QSL_HIP(hipEventRecord(ctx->ev[ctx->ev_used], st));
   }
   const uint32_t nblk = (c.NWT + 3) / 4;
+  // QSGD: k_pack_sent adds the fields of the transmitted entries to messages that the streaming pass has cleared
+  uint32_t* msg_zero = is_qsgd(c.quantizer) ? reinterpret_cast<uint32_t*>(msg) : nullptr;
   if (xm == nullptr) {
     const dim3 sgrid(nblk, R);
-    if (c.L == 1) k_stream<SPARS, true, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, sel_idx, sel_level);
-    else k_stream<SPARS, false, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, sel_idx, sel_level);
+    if (c.L == 1) k_stream<SPARS, true, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, msg_zero, sel_idx, sel_level);
+    else k_stream<SPARS, false, false><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, msg_zero, sel_idx, sel_level);
   } else {
     const dim3 sgrid(static_cast<uint32_t>(static_cast<uint64_t>((nblk + 7) / 8) * 8 * R));     // checked above
-    if (c.L == 1) k_stream<SPARS, true, true><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, sel_idx, sel_level);
-    else k_stream<SPARS, false, true><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, sel_idx, sel_level);
+    if (c.L == 1) k_stream<SPARS, true, true><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, msg_zero, sel_idx, sel_level);
+    else k_stream<SPARS, false, true><<<sgrid, BLOCK, 0, st>>>(c, ctx->one, m, delta, xm, m_out, worker0, round, R, msg_zero, sel_idx, sel_level);
   }
   if (timed) { QSL_HIP(hipEventRecord(ctx->ev[ctx->ev_used + 1], st)); ctx->ev_used += 2; }
 
@@ -797,11 +800,13 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
     k_lean_emit<SPARS><<<dim3((c.NSELF + c.nfast) * R), BIG, 0, st>>>(c, ctx->segs[0], R, c.NSELF * R, m_out, worker0, round,
                                                                      sel_idx, sel_level, safe ? 1 : 0);
   if (forked || swapped) QSL_HIP(hipStreamWaitEvent(st, ctx->join_ev, 0));
-  if (is_qsgd(c.quantizer)) {                      // the other quantisers send every selected coordinate: the final arrays are written already
+  const uint32_t nzero = safe ? c.nbig : ctx->nbig_general;
+  if (is_qsgd(c.quantizer)) {                      // entries may drop out: the message from the selected arrays, a block per 256 slots
     if (c.QB > MAX_QB_INLINE) k_surv_scan<<<dim3(R), 1024, 0, st>>>(c);
-    k_surv_compact<<<dim3(c.QB, R), BLOCK, 0, st>>>(c);
+    k_pack_sent<<<dim3(c.QB, R), BLOCK, 0, st>>>(c, msg, msg_bits, nzero);
+  } else {                                         // every selected coordinate is sent: the final arrays are written already
+    k_pack<<<dim3((c.cap_words + BLOCK - 1) / BLOCK, R), BLOCK, 0, st>>>(c, msg, msg_bits, nzero);
   }
-  k_pack<<<dim3((c.cap_words + BLOCK - 1) / BLOCK, R), BLOCK, 0, st>>>(c, msg, msg_bits, safe ? c.nbig : ctx->nbig_general);
   QSL_HIP(hipGetLastError());
   return QSL_OK;
 }

@@ -1,7 +1,7 @@
 // qsl_encode.h -- From the selected coordinates to the packed message: the fp32 scale from the exact norm digits,
 // encode_entry (QSGD level / sign of one selected coordinate, error update if it is transmitted) and block_encode_tail,
 // which every selection path calls; k_quantize (the same for the units of the multi-pass kernels), k_surv_scan,
-// k_surv_compact, k_pack.
+// k_pack (every selected coordinate is sent) and k_pack_sent (QSGD: the entries of level 0 drop out).
 // Part of the single translation unit qsl.hip (included there, in this order: device, layout, select,
 // encode, stream, lean, dense, decode); not a public header.
 #pragma once
@@ -148,7 +148,7 @@ __device__ __forceinline__ bool encode_entry(const DevCtx& c, uint32_t w, uint64
     g = neg ? -us.scale : us.scale;
   }
   const bool sent = level != 0;
-  if (is_qsgd(c.quantizer)) { c.sel_idx[slot] = idx; c.sel_code[slot] = level | (neg ? 0x80000000u : 0u); }   // k_surv_compact reads both
+  if (is_qsgd(c.quantizer)) { c.sel_idx[slot] = idx; c.sel_code[slot] = level | (neg ? 0x80000000u : 0u); }   // k_pack_sent reads both
   else {                                                 // every selected coordinate is sent: nothing to compact
     c.surv_idx[slot] = idx;
     c.surv_code[slot] = c.quantizer == QSL_FP32 ? bits : (neg ? 1u : 0u);
@@ -265,17 +265,6 @@ __global__ __launch_bounds__(BLOCK) void k_quantize(DevCtx c, float* m_out, uint
   }
 }
 
-// sum of cnt[0 .. n), by the whole block
-__device__ __forceinline__ uint32_t block_sum_u32(const uint32_t* cnt, uint32_t n, uint32_t* s_part) {
-  uint32_t x = 0;
-  for (uint32_t i = threadIdx.x; i < n; i += BLOCK) x += cnt[i];
-  x = wave_sum(x);
-  __syncthreads();
-  if (lane_id() == 0) s_part[threadIdx.x >> 6] = x;
-  __syncthreads();
-  return s_part[0] + s_part[1] + s_part[2] + s_part[3];
-}
-
 // only for very large K: exclusive prefix (and total) of the per-block survivor counts, one block per worker
 __global__ __launch_bounds__(1024) void k_surv_scan(DevCtx c) {
   __shared__ uint64_t scratch[17];
@@ -291,31 +280,6 @@ __global__ __launch_bounds__(1024) void k_surv_scan(DevCtx c) {
     carry += total;
   }
   if (threadIdx.x == 0) pre[c.QB] = static_cast<uint32_t>(carry);
-}
-
-__global__ __launch_bounds__(BLOCK) void k_surv_compact(DevCtx c) {
-  __shared__ uint32_t s_w[BLOCK / 64], s_part[4];
-  const uint32_t w = blockIdx.y;
-  const uint32_t j = blockIdx.x * BLOCK + threadIdx.x;
-  // survivors before this block: the sum of the earlier blocks' counts
-  const uint32_t before = c.QB > MAX_QB_INLINE
-                              ? c.blk_pre[static_cast<uint64_t>(w) * (c.QB + 1) + blockIdx.x]
-                              : block_sum_u32(c.blk_cnt + static_cast<uint64_t>(w) * c.QB, blockIdx.x, s_part);
-  uint32_t code = 0;
-  const uint64_t slot = static_cast<uint64_t>(w) * c.K + j;
-  if (j < c.K) code = c.sel_code[slot];
-  const bool sent = (code & 0x7FFFFFFFu) != 0;
-  const uint64_t bal = __ballot(sent);
-  if (lane_id() == 0) s_w[threadIdx.x >> 6] = __popcll(bal);
-  __syncthreads();
-  uint32_t pos = before + popc_below(bal);
-  for (uint32_t i = 0; i < (threadIdx.x >> 6); ++i) pos += s_w[i];
-  if (sent) {
-    const uint32_t level = code & 0x7FFFFFFFu, neg = code >> 31;
-    c.surv_idx[static_cast<uint64_t>(w) * c.K + pos] = c.sel_idx[slot];
-    c.surv_code[static_cast<uint64_t>(w) * c.K + pos] = is_qsgd(c.quantizer) ? ((level - 1u) | (neg << c.w_lev))
-                                                        : c.quantizer == QSL_FP32 ? c.sel_val[slot] : neg;
-  }
 }
 
 // one thread per 32-bit word of the message: it gathers the fields that overlap its word
@@ -338,10 +302,8 @@ __device__ __forceinline__ uint32_t gather_word(const uint32_t* arr, uint64_t n,
   return out;
 }
 
-__global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t* msg_bits, uint32_t nzero) {
-  __shared__ uint32_t s_part[4];
-  const uint32_t w = blockIdx.y;
-  // this is the last kernel of a call: it also returns the shared scratch of this worker to all-zero
+// The last kernel of a call also returns the shared scratch of its worker to all-zero; the blocks of worker w share the work.
+__device__ __forceinline__ void end_of_call(const DevCtx& c, uint32_t w, uint32_t nzero) {
   {
     const uint64_t tid = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x, nth = static_cast<uint64_t>(gridDim.x) * BLOCK;
     // histograms: only the first `nzero` of the segments that have any (the units of the multi-pass kernels; the
@@ -369,23 +331,95 @@ __global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t
         us->T_used = us->T; us->T = us->T_next; us->sh = us->sh_next;
       }
   }
-  const uint64_t nnz = !is_qsgd(c.quantizer) ? c.K
-                       : c.QB > MAX_QB_INLINE ? c.blk_pre[static_cast<uint64_t>(w) * (c.QB + 1) + c.QB]
-                                            : block_sum_u32(c.blk_cnt + static_cast<uint64_t>(w) * c.QB, c.QB, s_part);
+}
+
+__global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t* msg_bits, uint32_t nzero) {
+  const uint32_t w = blockIdx.y;
+  end_of_call(c, w, nzero);
+  const uint64_t nnz = c.K;                          // a quantiser that sends every selected coordinate (QSGD: k_pack_sent)
   const uint64_t q = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x;
   if (q >= c.cap_words) return;
-  const bool counts = is_qsgd(c.quantizer) && c.L > 1;
-  const uint64_t hdr = 1 + static_cast<uint64_t>(c.L) + (counts ? c.L : 0);
+  const uint64_t hdr = 1 + static_cast<uint64_t>(c.L);
   const uint64_t idx_words = (nnz * c.w_idx + 31) / 32, code_words = (nnz * c.w_val + 31) / 32;
   uint32_t word = 0;
   if (q == 0) word = static_cast<uint32_t>(nnz);
   else if (q < 1 + static_cast<uint64_t>(c.L)) word = c.units[static_cast<uint64_t>(w) * c.L + (q - 1)].scale_bits;
-  else if (q < hdr) word = c.units[static_cast<uint64_t>(w) * c.L + (q - 1 - c.L)].nnz;
   else if (q < hdr + idx_words) word = gather_word(c.surv_idx + static_cast<uint64_t>(w) * c.K, nnz, c.w_idx, q - hdr);
   else if (q < hdr + idx_words + code_words)
     word = gather_word(c.surv_code + static_cast<uint64_t>(w) * c.K, nnz, c.w_val, q - hdr - idx_words);
   reinterpret_cast<uint32_t*>(msg + static_cast<uint64_t>(w) * c.cap_words * 4)[q] = word;
   if (q == 0 && msg_bits) msg_bits[w] = hdr * 32 + nnz * (c.w_idx + c.w_val);
+}
+
+// QSGD drops the entries it rounds to level 0.  k_pack_sent puts the message together from the selected arrays as they
+// are, with no compacted copy in between: block b takes the 256 slots b * 256 .. b * 256 + 255, lines up its transmitted
+// entries in LDS, and writes their index and code fields where they belong -- behind those of the blocks before it (it
+// adds up their counts itself).  The words that lie wholly inside the block's share of a section are stored; the two at
+// its ends, which it may share with its neighbours, are added with atomicOr to words that k_stream has cleared
+// (as it has the padding behind the last field).
+__device__ __forceinline__ void put_fields(uint32_t* words, uint64_t bit0, const uint32_t* s_val, uint32_t n, uint32_t width) {
+  if (n == 0 || width == 0) return;
+  const uint64_t bit_end = bit0 + static_cast<uint64_t>(n) * width;              // the block's fields: bits [bit0, bit_end)
+  const uint64_t q_lo = bit0 >> 5, q_hi = (bit_end - 1) >> 5;
+  for (uint64_t q = q_lo + threadIdx.x; q <= q_hi; q += BLOCK) {
+    const uint64_t b_lo = max(q * 32, bit0), b_hi = min(q * 32 + 32, bit_end);   // the part of word q that is the block's
+    uint32_t out = 0;
+    for (uint64_t e = (b_lo - bit0) / width; e * width + bit0 < b_hi; ++e) {     // fields that overlap the word
+      const int64_t sh = static_cast<int64_t>(bit0 + e * width) - static_cast<int64_t>(q * 32);
+      const uint32_t f = s_val[e];
+      out |= sh >= 0 ? (f << sh) : (f >> (-sh));
+    }
+    if (b_lo == q * 32 && b_hi == q * 32 + 32) words[q] = out;
+    else if (out) atomicOr(&words[q], out);
+  }
+}
+
+__global__ __launch_bounds__(BLOCK) void k_pack_sent(DevCtx c, uint8_t* msg, uint64_t* msg_bits, uint32_t nzero) {
+  __shared__ uint32_t s_idx[BLOCK], s_code[BLOCK], s_w[BLOCK / 64], s_part[4];
+  const uint32_t w = blockIdx.y, b = blockIdx.x, lane = lane_id(), wave = threadIdx.x >> 6;
+  end_of_call(c, w, nzero);
+  // transmitted entries before this block, and in all
+  uint32_t before, nnz;
+  if (c.QB > MAX_QB_INLINE) {
+    before = c.blk_pre[static_cast<uint64_t>(w) * (c.QB + 1) + b]; nnz = c.blk_pre[static_cast<uint64_t>(w) * (c.QB + 1) + c.QB];
+  } else {
+    const uint32_t* cnt = c.blk_cnt + static_cast<uint64_t>(w) * c.QB;
+    uint32_t x = 0, y = 0;
+    for (uint32_t i = threadIdx.x; i < c.QB; i += BLOCK) { const uint32_t v = cnt[i]; y += v; if (i < b) x += v; }
+    x = wave_sum(x); y = wave_sum(y);
+    if (lane == 0) { s_w[wave] = x; s_part[wave] = y; }
+    __syncthreads();
+    before = s_w[0] + s_w[1] + s_w[2] + s_w[3]; nnz = s_part[0] + s_part[1] + s_part[2] + s_part[3];
+    __syncthreads();
+  }
+  // the block's transmitted entries, in slot order, side by side in LDS
+  const uint32_t j = b * BLOCK + threadIdx.x;
+  const uint64_t slot = static_cast<uint64_t>(w) * c.K + j;
+  const uint32_t code = j < c.K ? c.sel_code[slot] : 0u;
+  const bool sent = (code & 0x7FFFFFFFu) != 0;
+  const uint64_t bal = __ballot(sent);
+  if (lane == 0) s_w[wave] = static_cast<uint32_t>(__popcll(bal));
+  __syncthreads();
+  uint32_t pos = popc_below(bal);
+  for (uint32_t i = 0; i < wave; ++i) pos += s_w[i];
+  const uint32_t n = s_w[0] + s_w[1] + s_w[2] + s_w[3];
+  if (sent) {
+    s_idx[pos] = c.sel_idx[slot];
+    s_code[pos] = ((code & 0x7FFFFFFFu) - 1u) | ((code >> 31) << c.w_lev);      // a level 1..s is written as level - 1
+  }
+  __syncthreads();
+  uint32_t* words = reinterpret_cast<uint32_t*>(msg + static_cast<uint64_t>(w) * c.cap_words * 4);
+  const bool counts = c.L > 1;
+  const uint64_t hdr = 1 + static_cast<uint64_t>(c.L) + (counts ? c.L : 0);
+  const uint64_t idx_words = (static_cast<uint64_t>(nnz) * c.w_idx + 31) / 32;
+  put_fields(words, hdr * 32 + static_cast<uint64_t>(before) * c.w_idx, s_idx, n, c.w_idx);
+  put_fields(words, (hdr + idx_words) * 32 + static_cast<uint64_t>(before) * c.w_val, s_code, n, c.w_val);
+  if (b == 0) {                                        // the header: entry count, scales, entry counts of the segments
+    for (uint64_t q = threadIdx.x; q < hdr; q += BLOCK)
+      words[q] = q == 0 ? nnz : q < 1 + static_cast<uint64_t>(c.L) ? c.units[static_cast<uint64_t>(w) * c.L + (q - 1)].scale_bits
+                                                                   : c.units[static_cast<uint64_t>(w) * c.L + (q - 1 - c.L)].nnz;
+    if (threadIdx.x == 0 && msg_bits) msg_bits[w] = hdr * 32 + static_cast<uint64_t>(nnz) * (c.w_idx + c.w_val);
+  }
 }
 
 }  // namespace

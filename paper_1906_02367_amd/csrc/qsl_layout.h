@@ -118,7 +118,7 @@ struct DevCtx {
   uint32_t* blk_cnt;    // [Rmax][QB] transmitted entries per block of 256 slots: added to by every kernel that encodes.  Two arrays
   uint32_t* blk_cnt_next; // take turns from call to call: the last kernel of a call (k_pack) sets the next call's to zero.
   uint32_t* blk_pre;    // [R][QB + 1] their exclusive prefix and total (only when QB > MAX_QB_INLINE)
-  uint32_t* surv_idx; uint32_t* surv_code;                    // [R][K]
+  uint32_t* surv_idx; uint32_t* surv_code;                    // [R][K]: what k_pack reads (not QSGD, which k_pack_sent packs from sel_*)
   uint64_t* dense_part; // index-free format: [R][ACC_SLOTS][blocks of k_dense_norm] digit sums of every block's first unit ...
   uint32_t* dense_tag;  // ... [R][blocks]: which unit that is, or NO_UNIT
   uint32_t* status;

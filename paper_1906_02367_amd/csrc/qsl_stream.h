@@ -249,7 +249,7 @@ typedef uint32_t u2v __attribute__((ext_vector_type(2)));
 template <int SPARS, bool SINGLE, bool DIFF>
 __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE && !DIFF ? 3 : 4, SINGLE && !DIFF ? 3 : 4))) void k_stream(DevCtx c, StreamSeg one, const float* m, const float* delta,
                                                   const float* xm, float* m_out, uint32_t worker0, uint64_t round,
-                                                  uint32_t R, uint32_t* dbg_idx, uint16_t* dbg_level) {
+                                                  uint32_t R, uint32_t* msg_zero, uint32_t* dbg_idx, uint16_t* dbg_level) {
   __shared__ uint2 s_stage[BLOCK / 64][64];
   // only for the units that a block of this kernel selects and encodes itself (segmented contexts)
   __shared__ uint32_t s_lh[SINGLE ? 1 : HBINS];
@@ -267,6 +267,7 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
   }
   const uint32_t wt = blk * 4 + wave;
   if (wt >= c.NWT) return;
+
   StreamSeg sg = one;
   uint32_t seg = 0, chunk = wt;
   bool inblock = false;
@@ -327,6 +328,12 @@ __global__ __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SINGLE &&
     for (int j = 0; j < 4; ++j) nonfinite |= (__float_as_uint(v[t][j]) & 0x7FFFFFFFu) >= 0x7F800000u;
   }
   if (__ballot(nonfinite) != 0 && lane == 0) atomicOr(c.status, 1u);
+  // `msg_zero` (the messages, if k_pack_sent is to put them together: it adds its fields to words that are zero): wave
+  // wt clears the words wt * 64 .. wt * 64 + 63 of its worker's message (and on, a grid's width apart, if the message
+  // is longer than that).  Here, behind the streaming accesses: ahead of them it cost the pass 1 %.
+  if (msg_zero != nullptr && wt < (c.cap_words + 63u) / 64u)
+    for (uint64_t q = static_cast<uint64_t>(wt) * 64 + lane; q < c.cap_words; q += static_cast<uint64_t>(c.NWT) * 64)
+      msg_zero[static_cast<uint64_t>(w) * c.cap_words + q] = 0;
   if (!SINGLE && inblock) {                       // uniform over the block: it selects and encodes its unit itself
     const SegInfo unit = c.segs[seg];
     stream_block_unit<SPARS>(c, unit, u, w, cb, v, worker0, round, m_out, dbg_idx, dbg_level, s_lh, s_acc, s_scratch,
