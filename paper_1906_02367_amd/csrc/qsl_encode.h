@@ -337,18 +337,19 @@ __global__ __launch_bounds__(BLOCK) void k_pack(DevCtx c, uint8_t* msg, uint64_t
   const uint32_t w = blockIdx.y;
   end_of_call(c, w, nzero);
   const uint64_t nnz = c.K;                          // a quantiser that sends every selected coordinate (QSGD: k_pack_sent)
-  const uint64_t q = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x;
-  if (q >= c.cap_words) return;
   const uint64_t hdr = 1 + static_cast<uint64_t>(c.L);
   const uint64_t idx_words = (nnz * c.w_idx + 31) / 32, code_words = (nnz * c.w_val + 31) / 32;
-  uint32_t word = 0;
-  if (q == 0) word = static_cast<uint32_t>(nnz);
-  else if (q < 1 + static_cast<uint64_t>(c.L)) word = c.units[static_cast<uint64_t>(w) * c.L + (q - 1)].scale_bits;
-  else if (q < hdr + idx_words) word = gather_word(c.surv_idx + static_cast<uint64_t>(w) * c.K, nnz, c.w_idx, q - hdr);
-  else if (q < hdr + idx_words + code_words)
-    word = gather_word(c.surv_code + static_cast<uint64_t>(w) * c.K, nnz, c.w_val, q - hdr - idx_words);
-  reinterpret_cast<uint32_t*>(msg + static_cast<uint64_t>(w) * c.cap_words * 4)[q] = word;
-  if (q == 0 && msg_bits) msg_bits[w] = hdr * 32 + nnz * (c.w_idx + c.w_val);
+  // one word per thread, or several a grid's width apart (the host sizes the grid)
+  for (uint64_t q = static_cast<uint64_t>(blockIdx.x) * BLOCK + threadIdx.x; q < c.cap_words; q += static_cast<uint64_t>(gridDim.x) * BLOCK) {
+    uint32_t word = 0;
+    if (q == 0) word = static_cast<uint32_t>(nnz);
+    else if (q < 1 + static_cast<uint64_t>(c.L)) word = c.units[static_cast<uint64_t>(w) * c.L + (q - 1)].scale_bits;
+    else if (q < hdr + idx_words) word = gather_word(c.surv_idx + static_cast<uint64_t>(w) * c.K, nnz, c.w_idx, q - hdr);
+    else if (q < hdr + idx_words + code_words)
+      word = gather_word(c.surv_code + static_cast<uint64_t>(w) * c.K, nnz, c.w_val, q - hdr - idx_words);
+    reinterpret_cast<uint32_t*>(msg + static_cast<uint64_t>(w) * c.cap_words * 4)[q] = word;
+    if (q == 0 && msg_bits) msg_bits[w] = hdr * 32 + nnz * (c.w_idx + c.w_val);
+  }
 }
 
 // QSGD drops the entries it rounds to level 0.  k_pack_sent puts the message together from the selected arrays as they
