@@ -759,7 +759,9 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   // so whichever kernel is dispatched first keeps the other waiting, and the block units are the longer (measured on
   // the 161-tensor table: k_lean_one first 541-548 us per round, the three kernels 536 us).  Not while failed guesses
   // are expected: the multi-pass kernels on the caller's stream read what k_lean_one finds out about its units.
-  const bool swapped = c.nblock != 0 && c.none != 0 && !safe;
+  // ... nor when some guessing units have several blocks: their three kernels would wait on the caller's stream behind
+  // the block units (161 tensors, one worker: 160 us per round that way, against 133 us with the block units on the second stream).
+  const bool swapped = c.nblock != 0 && c.none != 0 && c.NSELF == 0 && !safe;
   const bool forked = c.nblock != 0 && !swapped && (c.NSELF != 0 || c.none != 0 || ctx->n_other != 0);
   if (swapped) {
     QSL_HIP(hipEventRecord(ctx->fork_ev, st));

@@ -248,9 +248,9 @@ __global__ __launch_bounds__(BIG) void k_lean_mark(DevCtx c, SegInfo one, uint32
 }
 
 // ------------------------------------------------------------------------------------------------
-// A unit of at most 40,960 coordinates that is too dense for guessing, whole, by one block of 1024 threads: thread t
-// takes up to 40 consecutive coordinates, read again from v (which the cache holds) for each of the three radix
-// digits and for the ordered pass; one block-wide scan orders the output.  Selection, norm, codes and error update
+// A unit of at most 40,960 coordinates that is too dense for guessing, whole, by one block of 1024 threads: a wave
+// takes up to 2560 consecutive coordinates, read again from v (which the cache holds) for each of the three radix
+// digits and for the ordered pass; one block-wide scan and ballots inside the waves order the output.  Selection, norm, codes and error update
 // without a launch in between.
 // ------------------------------------------------------------------------------------------------
 template <int SPARS>
@@ -260,19 +260,24 @@ __device__ void block_unit(const DevCtx& c, const SegInfo& sg, uint32_t w, uint6
   const RandKey rk = make_rand_key(c.seed, worker0 + w, round, 0);
   const uint32_t wave = threadIdx.x >> 6, lane = lane_id();
   const uint32_t n = static_cast<uint32_t>(sg.size);                 // <= BLOCK_MAX
-  const uint32_t per = (((n + BIG - 1) / BIG) + 3u) & ~3u;           // coordinates per thread: a multiple of 4, <= BLOCK_PER
-  const uint32_t e0 = threadIdx.x * per;
-  // A pass over the thread's coordinates: the loads of five groups of four (dwordx4 each) are issued together, then
-  // f(e, bits, key) sees each coordinate inside the unit in order.  Two rounds of loads cover the 40 a thread can have.
+  // Wave wv takes the coordinates [wv * gw * 256, (wv + 1) * gw * 256) of the unit, in gw <= 10 groups of 256: lane l holds
+  // the four coordinates (g * 64 + l) * 4 .. + 3 of group g, so that a load of the wave is 1 KB in a row.  (A thread with
+  // 36 consecutive coordinates of its own made every load touch 64 cache lines, and the first pass over a unit of 36,864
+  // coordinates, which comes from memory, took 14 of the block's 43 us.)
+  // A pass: the loads of five groups are issued together, then f(e, bits[4], keys[4], nv) sees the lane's four
+  // coordinates of each group (the first nv of them lie inside the unit), group after group; every lane of the wave
+  // makes the same calls.
+  const uint32_t gw = (n + (BIG / 64) * 256 - 1) / ((BIG / 64) * 256);
+  const uint32_t wbase = wave * gw * 256;
   auto pass = [&](auto&& f) {
-    constexpr uint32_t G = 5;
-    for (uint32_t q0 = 0; q0 < per; q0 += 4 * G) {
+    constexpr uint32_t G = 5;                        // (ten at once: the compiler spills, 600 bytes per lane)
+    for (uint32_t g0 = 0; g0 < gw; g0 += G) {
       f4u x[G];
 #pragma unroll
       for (uint32_t g = 0; g < G; ++g) {
-        const uint32_t e = e0 + q0 + g * 4;
+        const uint32_t e = wbase + (g0 + g) * 256 + lane * 4;
         x[g] = f4u{0.f, 0.f, 0.f, 0.f};
-        if (q0 + g * 4 < per) {
+        if (g0 + g < gw) {
           if (e + 4 <= n) x[g] = *reinterpret_cast<const f4u*>(vp + e);
           else {
 #pragma unroll
@@ -282,15 +287,18 @@ __device__ void block_unit(const DevCtx& c, const SegInfo& sg, uint32_t w, uint6
       }
 #pragma unroll
       for (uint32_t g = 0; g < G; ++g) {
-        const uint32_t e = e0 + q0 + g * 4;
-        if (q0 + g * 4 >= per || e >= n) continue;
+        if (g0 + g >= gw) continue;                                  // uniform over the wave
+        const uint32_t e = wbase + (g0 + g) * 256 + lane * 4;
+        const uint32_t nv = e < n ? min(4u, n - e) : 0u;
         Words4 rw = {{0u, 0u, 0u, 0u}};
-        if (SPARS == QSL_RANDK) rw = rand_words4(rk, static_cast<uint32_t>(sg.start) + e);
+        if (SPARS == QSL_RANDK && nv) rw = rand_words4(rk, static_cast<uint32_t>(sg.start) + e);
+        uint32_t bits[4], keys[4];
 #pragma unroll
         for (uint32_t j = 0; j < 4; ++j) {
-          const uint32_t bits = __float_as_uint(x[g][j]);
-          if (e + j < n) f(e + j, bits, SPARS == QSL_TOPK ? key_of_value(bits) : rw.w[j]);
+          bits[j] = __float_as_uint(x[g][j]);
+          keys[j] = SPARS == QSL_TOPK ? key_of_value(bits[j]) : rw.w[j];
         }
+        f(e, bits, keys, nv);
       }
     }
   };
@@ -299,36 +307,63 @@ __device__ void block_unit(const DevCtx& c, const SegInfo& sg, uint32_t w, uint6
   __syncthreads();
   uint32_t above, bin;
   // the three digits of the k-th largest key
-  pass([&](uint32_t, uint32_t, uint32_t key) { atomicAdd(&lh[key >> 20], 1u); });
+  pass([&](uint32_t, const uint32_t*, const uint32_t* keys, uint32_t nv) {
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) if (j < nv) atomicAdd(&lh[keys[j] >> 20], 1u);
+  });
   __syncthreads();
   bin = find_from_top<BIG>(lh, sg.k, &above, scratch, result, true);
   uint32_t prefix = bin << 20, k_rem = sg.k - above;
-  pass([&](uint32_t, uint32_t, uint32_t key) { if ((key >> 20) == (prefix >> 20)) atomicAdd(&lh[(key >> 8) & 0xFFFu], 1u); });
+  pass([&](uint32_t, const uint32_t*, const uint32_t* keys, uint32_t nv) {
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) if (j < nv && (keys[j] >> 20) == (prefix >> 20)) atomicAdd(&lh[(keys[j] >> 8) & 0xFFFu], 1u);
+  });
   __syncthreads();
   bin = find_from_top<BIG>(lh, k_rem, &above, scratch, result, true);
   prefix |= bin << 8; k_rem -= above;
-  pass([&](uint32_t, uint32_t, uint32_t key) { if ((key >> 8) == (prefix >> 8)) atomicAdd(&lh[key & 0xFFu], 1u); });
+  pass([&](uint32_t, const uint32_t*, const uint32_t* keys, uint32_t nv) {
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) if (j < nv && (keys[j] >> 8) == (prefix >> 8)) atomicAdd(&lh[keys[j] & 0xFFu], 1u);
+  });
   __syncthreads();
   bin = find_from_top<BIG, 1024>(lh, k_rem, &above, scratch, result, true);      // bins 256 .. 1023 are empty
   const uint32_t tau = prefix | bin, need = k_rem - above;
   // ordered compaction: key > tau, and the first `need` coordinates with key == tau
   uint32_t n_gt = 0, n_eq = 0;
-  pass([&](uint32_t, uint32_t, uint32_t key) { n_gt += key > tau; n_eq += key == tau; });
+  pass([&](uint32_t, const uint32_t*, const uint32_t* keys, uint32_t nv) {
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j) if (j < nv) { n_gt += keys[j] > tau; n_eq += keys[j] == tau; }
+  });
   uint64_t total;
   const uint64_t ex = block_exclusive_scan64((static_cast<uint64_t>(n_eq) << 32) | n_gt, scratch, &total);
-  uint32_t my_gt = static_cast<uint32_t>(ex), my_eq = static_cast<uint32_t>(ex >> 32);
+  // the wave's coordinates follow those of the waves before it: what these hold is what lane 0's prefix says
+  const uint64_t ex0 = __shfl(ex, 0, WAVE);
+  uint32_t run_gt = static_cast<uint32_t>(ex0), run_eq = static_cast<uint32_t>(ex0 >> 32);
   uint32_t* oi = c.sel_idx + static_cast<uint64_t>(w) * c.K + sg.koff;
   uint32_t* ov = c.sel_val + static_cast<uint64_t>(w) * c.K + sg.koff;
   uint64_t* mine = acc + ((wave & 7u) * 8 + (lane & 7u)) * acc_stride(c.quantizer);
   const uint32_t power = norm_power(c.quantizer);
-  if (n_gt != 0 || (n_eq != 0 && my_eq < need)) {
-    pass([&](uint32_t e, uint32_t bits, uint32_t key) {
-      const bool is_gt = key > tau, is_eq = key == tau;
-      if (is_gt || (is_eq && my_eq < need)) {
-        const uint32_t pos = my_gt + min(my_eq, need);
-        if (pos < sg.k) { oi[pos] = static_cast<uint32_t>(sg.start) + e; ov[pos] = bits; add_digits(mine, bits, power); }
+  if (__ballot(n_gt != 0 || n_eq != 0) != 0) {
+    pass([&](uint32_t e, const uint32_t* bits, const uint32_t* keys, uint32_t nv) {
+      // inside a group the coordinates run lane after lane: what the lower lanes hold comes first
+      uint32_t bg = 0, bq = 0, tg = 0, tq = 0;
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) {
+        const uint64_t b1 = __ballot(j < nv && keys[j] > tau), b2 = __ballot(j < nv && keys[j] == tau);
+        bg += popc_below(b1); tg += static_cast<uint32_t>(__popcll(b1));
+        bq += popc_below(b2); tq += static_cast<uint32_t>(__popcll(b2));
       }
-      my_gt += is_gt; my_eq += is_eq;
+      uint32_t my_gt = run_gt + bg, my_eq = run_eq + bq;
+#pragma unroll
+      for (uint32_t j = 0; j < 4; ++j) {
+        const bool is_gt = j < nv && keys[j] > tau, is_eq = j < nv && keys[j] == tau;
+        if (is_gt || (is_eq && my_eq < need)) {
+          const uint32_t pos = my_gt + min(my_eq, need);
+          if (pos < sg.k) { oi[pos] = static_cast<uint32_t>(sg.start) + e + j; ov[pos] = bits[j]; add_digits(mine, bits[j], power); }
+        }
+        my_gt += is_gt; my_eq += is_eq;
+      }
+      run_gt += tg; run_eq += tq;
     });
   }
   if (threadIdx.x == 0) { c.units[u].cand = 0; c.units[u].fell_back = 0; }
