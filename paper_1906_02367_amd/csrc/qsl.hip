@@ -103,6 +103,8 @@ struct qsl_ctx {
   float* own_v;               // [Rmax, d] home of v for calls with m_out = NULL (QSL_FLAG_OWN_V), else null
   hipEvent_t order_ev;        // orders the work of this context across a change of stream
   hipStream_t side;           // the one-block units' kernel runs here, beside the guessing units' kernels
+  hipStream_t side2;          // ... and k_lean_one here, when the guessing units with several blocks have kernels of their own
+  hipEvent_t join2_ev;
   hipEvent_t fork_ev, join_ev;
   int timing;
   std::vector<hipEvent_t> ev;
@@ -294,6 +296,8 @@ extern "C" qsl_status qsl_plan_paths(const qsl_config* cfg, uint32_t* path_out) 
 // releases everything a (possibly half-built) context holds
 static void free_ctx(qsl_ctx* ctx) {
   if (ctx->side) { (void)hipStreamSynchronize(ctx->side); (void)hipStreamDestroy(ctx->side); }
+  if (ctx->side2) { (void)hipStreamSynchronize(ctx->side2); (void)hipStreamDestroy(ctx->side2); }
+  if (ctx->join2_ev) (void)hipEventDestroy(ctx->join2_ev);
   for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
   if (ctx->order_ev) (void)hipEventDestroy(ctx->order_ev);
   if (ctx->fork_ev) (void)hipEventDestroy(ctx->fork_ev);
@@ -324,7 +328,7 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ctx->Rmax = cfg->max_workers;
   ctx->last_R = 0; ctx->warm_R = 0; ctx->safe_left = 0;
   ctx->timing = 0; ctx->ev_used = 0;
-  ctx->slab = nullptr; ctx->h_status = nullptr; ctx->own_v = nullptr; ctx->order_ev = nullptr; ctx->side = nullptr; ctx->fork_ev = nullptr; ctx->join_ev = nullptr;
+  ctx->slab = nullptr; ctx->h_status = nullptr; ctx->own_v = nullptr; ctx->order_ev = nullptr; ctx->side = nullptr; ctx->side2 = nullptr; ctx->join2_ev = nullptr; ctx->fork_ev = nullptr; ctx->join_ev = nullptr;
 
   const uint32_t K = static_cast<uint32_t>(K64);
   const WireDims wd = wire_dims(cfg, K64);
@@ -593,7 +597,9 @@ extern "C" qsl_status qsl_create(qsl_ctx** out, const qsl_config* cfg, void* hip
   ok = ok && hipEventCreateWithFlags(&ctx->order_ev, evf) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&ctx->fork_ev, evf) == hipSuccess;
   ok = ok && hipEventCreateWithFlags(&ctx->join_ev, evf) == hipSuccess;
+  ok = ok && hipEventCreateWithFlags(&ctx->join2_ev, evf) == hipSuccess;
   ok = ok && hipStreamCreateWithFlags(&ctx->side, hipStreamNonBlocking) == hipSuccess;      // default priority
+  ok = ok && hipStreamCreateWithFlags(&ctx->side2, hipStreamNonBlocking) == hipSuccess;
   ok = ok && hipDeviceSynchronize() == hipSuccess;
   if (!ok) { free_ctx(ctx); return QSL_ERR_DEVICE; }
 
@@ -763,6 +769,11 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
   // the block units (161 tensors, one worker: 160 us per round that way, against 133 us with the block units on the second stream).
   const bool swapped = c.nblock != 0 && c.none != 0 && c.NSELF == 0 && !safe;
   const bool forked = c.nblock != 0 && !swapped && (c.NSELF != 0 || c.none != 0 || ctx->n_other != 0);
+  // Guessing units of both kinds in one call (a single block: k_lean_one; several: the three kernels) and no block units:
+  // k_lean_one goes to a stream of its own, beside the three kernels (160 tensors, one worker: 115 -> 106 us per round,
+  // two workers 171 -> 162 us).  Beside k_block_units as well, three kernels at once, it loses (161 tensors, one worker:
+  // 127 -> 134 us; four workers 293 -> 302 us).
+  const bool one_aside = c.none != 0 && c.NSELF != 0 && c.nblock == 0 && !safe;
   if (swapped) {
     QSL_HIP(hipEventRecord(ctx->fork_ev, st));
     QSL_HIP(hipStreamWaitEvent(ctx->side, ctx->fork_ev, 0));
@@ -779,9 +790,15 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
     k_block_units<SPARS><<<dim3(c.nblock * R), BIG, 0, bs>>>(c, R, m_out, worker0, round, sel_idx, sel_level);
     if (forked) QSL_HIP(hipEventRecord(ctx->join_ev, ctx->side));
   }
+  if (one_aside) {
+    if (!forked) QSL_HIP(hipEventRecord(ctx->fork_ev, st));
+    QSL_HIP(hipStreamWaitEvent(ctx->side2, ctx->fork_ev, 0));
+    k_lean_one<SPARS><<<dim3(c.none * R), BIG, 0, ctx->side2>>>(c, ctx->segs[0], R, m_out, worker0, round, sel_idx, sel_level, 0);
+    QSL_HIP(hipEventRecord(ctx->join2_ev, ctx->side2));
+  }
   if (ctx->nfull_blocks) k_full<<<dim3(ctx->nfull_blocks, R), BLOCK, 0, st>>>(c, m_out);
   // guessing units of a single block: the whole way from the slots to the encoded entries in one launch
-  if (c.none && !swapped) k_lean_one<SPARS><<<dim3(c.none * R), BIG, 0, st>>>(c, ctx->segs[0], R, m_out, worker0, round, sel_idx, sel_level, safe ? 1 : 0);
+  if (c.none && !swapped && !one_aside) k_lean_one<SPARS><<<dim3(c.none * R), BIG, 0, st>>>(c, ctx->segs[0], R, m_out, worker0, round, sel_idx, sel_level, safe ? 1 : 0);
   if (c.NSELF) {                                   // guessing units: candidates' histogram, threshold bin and dense list
     k_lean_hist<SPARS><<<dim3(c.NSELF * R), BIG, 0, st>>>(c, ctx->segs[0], R);
     k_lean_mark<SPARS><<<dim3(c.NSELF * R), BIG, 0, st>>>(c, ctx->segs[0], R);
@@ -802,6 +819,7 @@ static qsl_status launch_compress(qsl_ctx* ctx, const float* m, const float* del
     k_lean_emit<SPARS><<<dim3((c.NSELF + c.nfast) * R), BIG, 0, st>>>(c, ctx->segs[0], R, c.NSELF * R, m_out, worker0, round,
                                                                      sel_idx, sel_level, safe ? 1 : 0);
   if (forked || swapped) QSL_HIP(hipStreamWaitEvent(st, ctx->join_ev, 0));
+  if (one_aside) QSL_HIP(hipStreamWaitEvent(st, ctx->join2_ev, 0));
   const uint32_t nzero = safe ? c.nbig : ctx->nbig_general;
   if (is_qsgd(c.quantizer)) {                      // entries may drop out: the message from the selected arrays, a block per 256 slots
     if (c.QB > MAX_QB_INLINE) k_surv_scan<<<dim3(R), 1024, 0, st>>>(c);
