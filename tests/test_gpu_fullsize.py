@@ -50,3 +50,15 @@ def test_index_free_rows_longer_than_the_first_pass_has_blocks(P, quantizer, s):
     run, op, m_host, paths = P.run_parity(wl, 2, host_deltas=False, dense=True, expect_path=4)
     msgs = run.msg.cpu().numpy()
     assert run.q.bits_sent(run.msg) == [op.bits_sent(msgs[0])]
+
+
+@pytest.mark.parametrize("cfg,R", [(4, 1), (6, 2), (6, 1)])
+def test_per_tensor_configurations_with_few_workers(P, cfg, R):
+    """With few workers the block budget gives the large tensors several blocks: the guessing units then take both
+    k_lean_one and the three kernels, side by side on streams of the context's own (and beside k_block_units)."""
+    wl = W.config(cfg, R=R)
+    print(f"\n[{wl.name}] R={wl.R} d={wl.d} K={wl.K} L={wl.L}", flush=True)
+    run, op, m_host, paths = P.run_parity(wl, 4, host_deltas=False)
+    assert all((p != 2).all() for p in paths)                       # no guess failed
+    msgs = run.msg.cpu().numpy()
+    assert run.q.bits_sent(run.msg) == [op.bits_sent(msgs[r]) for r in range(wl.R)]
